@@ -1,0 +1,160 @@
+/*
+ * ba.h -- C boundary of the MI355X (gfx950) Block-attention prefill library.
+ *
+ * Block-attention (arXiv 2409.15355) splits a prompt into blocks: every block but
+ * the last is encoded on its own (Section 2.1), its cached keys are rotated to the
+ * block's place in the new prompt (Section 2.3, Eq. 1-3), and only the last block --
+ * the user query -- attends to everything before it (Section 2.5).  The three entry
+ * points below are those three steps.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * - Tensors are DEVICE memory described by `ba_tensor`: element pointer, token and head
+ *   strides in ELEMENTS, innermost head_dim contiguous.  The default packed layout is
+ *   [tokens][heads][head_dim] (stride_head = head_dim, stride_tok = heads * head_dim).
+ *   Base pointers and both strides must be 16-byte aligned.
+ * - Small metadata arrays (block offsets, per-block descriptors, cu_* arrays, q_to_kv,
+ *   inv_freq) are HOST memory.  They are read and validated before the call returns
+ *   and may be freed immediately afterwards.
+ * - The caller owns all device memory, including the workspace; the library allocates
+ *   nothing on the device and keeps no device state between calls.
+ * - `stream` is a hipStream_t (NULL = the default stream).  All device work is
+ *   enqueued on it; calls return without synchronising.
+ * - Every call returns BA_OK or a negative status; nothing aborts or throws.
+ *   `ba_last_error()` gives a thread-local description of the last failure.
+ * - Outputs are fully overwritten for every row the call covers.
+ * - Supported: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads; query head h
+ *   uses KV head h / (n_q_heads / n_kv_heads) (a q_to_kv map is accepted only if it
+ *   says exactly that).
+ */
+#ifndef BA_H_
+#define BA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BA_OK 0
+#define BA_ERR_INVALID_ARG (-1) /* null pointer, non-monotone offsets, bad head counts ... */
+#define BA_ERR_UNSUPPORTED (-2) /* head_dim, dtype or head map outside what is built      */
+#define BA_ERR_ALIGNMENT (-3)   /* pointer or stride not 16-byte aligned                   */
+#define BA_ERR_WORKSPACE (-4)   /* workspace missing or too small                          */
+#define BA_ERR_DEVICE (-5)      /* a HIP call failed; see ba_last_error()                  */
+
+#define BA_DTYPE_BF16 0
+#define BA_DTYPE_F32 1 /* ba_reencode_positions only */
+
+#define BA_ROPE_INTERLEAVED 0 /* Eq. 1: dimension pairs (2j, 2j+1)                  */
+#define BA_ROPE_HALF 1        /* pairs (j, j + head_dim/2), as Llama checkpoints store */
+
+#define BA_ROPE_NONE 0  /* q and k arrive already rotated                               */
+#define BA_ROPE_APPLY 1 /* rotate inside: local positions in ba_encode_blocks (first token
+                           of a block at 0, Section 2.3), absolute positions in
+                           ba_final_block_attention                                    */
+
+#define BA_REENC_SHIFT 0    /* cache holds keys rotated at old_pos0 + u (u = index in block) */
+#define BA_REENC_ABSOLUTE 1 /* cache holds every token of the block at old_pos0             */
+
+typedef struct ba_tensor {
+  void *ptr;           /* device pointer to element (token 0, head 0, dim 0) */
+  int64_t stride_tok;  /* elements between consecutive tokens               */
+  int64_t stride_head; /* elements between consecutive heads                */
+  int32_t dtype;       /* BA_DTYPE_*                                        */
+} ba_tensor;
+
+typedef struct ba_heads {
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  const int32_t *q_to_kv; /* host, nullable -> h / (n_q_heads / n_kv_heads)             */
+  float softmax_scale;    /* <= 0 -> 1 / sqrt(head_dim)                                 */
+  double rope_base;       /* theta_j = rope_base^(-2j/head_dim) (Eq. 1's theta_j)       */
+  const double *inv_freq; /* host, nullable: head_dim/2 overrides of theta_j            */
+  int32_t rope_layout;    /* BA_ROPE_INTERLEAVED or BA_ROPE_HALF                        */
+} ba_heads;
+
+/* Library version (major * 10000 + minor * 100 + patch). */
+int32_t ba_version(void);
+/* Static name of a status code. */
+const char *ba_status_string(int32_t status);
+/* Thread-local text describing the last non-OK status returned on this thread. */
+const char *ba_last_error(void);
+
+/*
+ * Step 1 -- independent per-block causal attention (Section 1, step 1; Section 2.1).
+ *
+ * Token t of block b attends to tokens [c[b], t] of its own block only:
+ *   o[t, h] = softmax_s(scale * <q^[t,h], k^[s,kv(h)]>) v[s, kv(h)],  s in [c[b], t].
+ * q [T, n_q_heads, D], k, v [T, n_kv_heads, D], o [T, n_q_heads, D], all bf16.
+ * block_offsets: host, n_blocks+1 ints, c[0] = 0 <= c[1] <= ... <= c[n_blocks] = T.
+ * Blocks are independent, so a batch of prompts is simply a longer block list.
+ * rope_mode BA_ROPE_APPLY rotates q and k at LOCAL positions (t - c[b]); then the
+ * rotated keys -- the cacheable K of Section 2.3 -- are written to k_local_out
+ * [T, n_kv_heads, D] if it is non-null, else kept in the workspace.  With
+ * BA_ROPE_NONE k is used as given and k_local_out must be null.
+ * Zero-length blocks are legal no-ops.  ws/ws_bytes: device workspace of at least
+ * ba_encode_blocks_workspace_bytes() bytes (may be null when that is 0).
+ */
+int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
+                         const ba_tensor *v, const ba_tensor *o_out,
+                         const ba_tensor *k_local_out, int32_t n_blocks,
+                         const int32_t *block_offsets, int32_t rope_mode, void *ws,
+                         size_t ws_bytes, void *stream);
+size_t ba_encode_blocks_workspace_bytes(const ba_heads *heads, int32_t n_blocks,
+                                        const int32_t *block_offsets, int32_t rope_mode,
+                                        int32_t have_k_local_out);
+
+/*
+ * Step 2 -- position re-encoding of cached keys (Section 2.3, Eq. 2 then Eq. 3).
+ *
+ * For block b and in-block index u, every layer and KV head:
+ *   k' = R(p_new) R(p_old)^T k,  p_new = new_pos0[b] + u,
+ *   p_old = old_pos0[b] + u (BA_REENC_SHIFT: a uniform rotation by new_pos0 - old_pos0)
+ *        or old_pos0[b]     (BA_REENC_ABSOLUTE: e.g. a cache of un-rotated keys).
+ * k_src / k_dst: [n_layers][tokens][n_kv_heads][D] with layer strides in elements; block
+ * b is read from token src_tok_off[b] and written to token dst_tok_off[b] (a gather
+ * into the prompt's K buffer).  k_dst may be exactly k_src (same pointer, strides and
+ * offsets: in place); any other overlap is an error.  dtype bf16 (fp32 rotate, one
+ * round-to-nearest-even on store) or fp32.  old_pos0 null -> 0; new_pos0 null ->
+ * dst_tok_off.  A zero shift copies bit for bit.  Only heads->n_kv_heads, head_dim,
+ * rope_base / inv_freq and rope_layout are read from `heads`.
+ */
+int32_t ba_reencode_positions(const ba_heads *heads, const ba_tensor *k_src,
+                              const ba_tensor *k_dst, int32_t n_layers,
+                              int64_t layer_stride_src, int64_t layer_stride_dst,
+                              int32_t n_blocks, const int32_t *src_tok_off,
+                              const int32_t *dst_tok_off, const int32_t *len,
+                              const int32_t *old_pos0, const int32_t *new_pos0, int32_t mode,
+                              void *stream);
+
+/*
+ * Step 3 -- final-block attention (Section 1, step 3; Section 2.5).
+ *
+ * Prompt n owns rows [cu_q[n], cu_q[n+1]) of q_f / k_f / v_f / o_out (its final block,
+ * at least one token; cu_q[0] = 0) and rows [cu_ctx[n], cu_ctx[n+1]) of k_ctx / v_ctx (the
+ * concatenated, already re-encoded KV of its earlier blocks; may be empty, then this is
+ * plain causal attention).  Final-block token i attends to all context keys and to
+ * final-block keys <= i.  Token i sits at absolute position q_pos0[n] + i (q_pos0 null ->
+ * the prompt's context length).  With BA_ROPE_APPLY q_f and k_f are rotated at those
+ * positions inside; k_ctx is always used as given.  k_f_rot_out (nullable, shaped like
+ * k_f) receives the rotated final-block keys for later decoding.
+ * All tensors bf16.  ws: at least ba_final_block_attention_workspace_bytes() bytes.
+ */
+int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f,
+                                 const ba_tensor *k_ctx, const ba_tensor *v_ctx,
+                                 const ba_tensor *k_f, const ba_tensor *v_f,
+                                 const ba_tensor *o_out, const ba_tensor *k_f_rot_out,
+                                 int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_ctx,
+                                 const int32_t *q_pos0, int32_t rope_mode, void *ws,
+                                 size_t ws_bytes, void *stream);
+size_t ba_final_block_attention_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
+                                                const int32_t *cu_q, const int32_t *cu_ctx,
+                                                int32_t rope_mode, int32_t have_k_f_rot_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BA_H_ */

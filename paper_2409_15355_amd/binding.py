@@ -1,0 +1,195 @@
+"""Thin ctypes face of the HIP library: argument marshalling only.
+
+Function names and argument order follow ``include/ba.h``.  Tensors are torch CUDA
+tensors (PyTorch is used for device memory and streams, nothing else); metadata are
+host sequences of ints.  Every step of the hot path runs inside ``libba_hip.so``; if
+the library is missing, loading fails loudly -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libba_hip.so")
+
+BA_OK = 0
+DTYPE_BF16, DTYPE_F32 = 0, 1
+ROPE_INTERLEAVED, ROPE_HALF = 0, 1
+ROPE_NONE, ROPE_APPLY = 0, 1
+REENC_SHIFT, REENC_ABSOLUTE = 0, 1
+
+EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_encode_blocks",
+           "ba_encode_blocks_workspace_bytes", "ba_reencode_positions",
+           "ba_final_block_attention", "ba_final_block_attention_workspace_bytes"]
+
+
+class BaTensor(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("stride_tok", ctypes.c_int64),
+                ("stride_head", ctypes.c_int64), ("dtype", ctypes.c_int32)]
+
+
+class BaHeads(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("q_to_kv", ctypes.POINTER(ctypes.c_int32)),
+                ("softmax_scale", ctypes.c_float), ("rope_base", ctypes.c_double),
+                ("inv_freq", ctypes.POINTER(ctypes.c_double)), ("rope_layout", ctypes.c_int32)]
+
+
+class BaError(RuntimeError):
+    def __init__(self, status: int, name: str, detail: str):
+        super().__init__(f"{name} ({status}): {detail}")
+        self.status = status
+
+
+_lib = None
+_I32P = ctypes.POINTER(ctypes.c_int32)
+_TP = ctypes.POINTER(BaTensor)
+_HP = ctypes.POINTER(BaHeads)
+
+
+def load():
+    """dlopen libba_hip.so (built by ``paper_2409_15355_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2409_15355_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    lib.ba_version.restype = ctypes.c_int32
+    lib.ba_status_string.restype = ctypes.c_char_p
+    lib.ba_status_string.argtypes = [ctypes.c_int32]
+    lib.ba_last_error.restype = ctypes.c_char_p
+    lib.ba_encode_blocks.restype = ctypes.c_int32
+    lib.ba_encode_blocks.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, ctypes.c_int32, _I32P, ctypes.c_int32,
+                                     ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.ba_encode_blocks_workspace_bytes.restype = ctypes.c_size_t
+    lib.ba_encode_blocks_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, ctypes.c_int32, ctypes.c_int32]
+    lib.ba_reencode_positions.restype = ctypes.c_int32
+    lib.ba_reencode_positions.argtypes = [_HP, _TP, _TP, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_int32, _I32P, _I32P, _I32P, _I32P, _I32P, ctypes.c_int32,
+                                          ctypes.c_void_p]
+    lib.ba_final_block_attention.restype = ctypes.c_int32
+    lib.ba_final_block_attention.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, _TP, _TP, ctypes.c_int32, _I32P,
+                                             _I32P, _I32P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t,
+                                             ctypes.c_void_p]
+    lib.ba_final_block_attention_workspace_bytes.restype = ctypes.c_size_t
+    lib.ba_final_block_attention_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, ctypes.c_int32,
+                                                             ctypes.c_int32]
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != BA_OK:
+        lib = load()
+        raise BaError(status, lib.ba_status_string(status).decode(), lib.ba_last_error().decode())
+
+
+class Heads:
+    """Host-side head description (ba_heads) that keeps its arrays alive."""
+
+    def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, rope_base: float = 10000.0,
+                 rope_layout: int = ROPE_INTERLEAVED, softmax_scale: float = 0.0,
+                 q_to_kv: Optional[Sequence[int]] = None, inv_freq: Optional[Sequence[float]] = None):
+        self._q_to_kv = None if q_to_kv is None else np.ascontiguousarray(q_to_kv, dtype=np.int32)
+        self._inv_freq = None if inv_freq is None else np.ascontiguousarray(inv_freq, dtype=np.float64)
+        self.c = BaHeads(n_q_heads, n_kv_heads, head_dim,
+                         None if self._q_to_kv is None else self._q_to_kv.ctypes.data_as(_I32P),
+                         float(softmax_scale), float(rope_base),
+                         None if self._inv_freq is None else self._inv_freq.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                         rope_layout)
+        self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
+
+
+def _tensor(t, dtype_code: Optional[int] = None) -> Optional[BaTensor]:
+    """[tokens, heads, D] torch tensor (any token / head strides, D contiguous)."""
+    if t is None:
+        return None
+    import torch
+    if t.dim() != 3 or t.stride(2) != 1:
+        raise ValueError("expected a [tokens, heads, head_dim] tensor with contiguous head_dim")
+    if dtype_code is None:
+        dtype_code = DTYPE_F32 if t.dtype == torch.float32 else DTYPE_BF16
+        if t.dtype not in (torch.float32, torch.bfloat16):
+            raise ValueError(f"dtype {t.dtype} not supported")
+    return BaTensor(t.data_ptr(), t.stride(0), t.stride(1), dtype_code)
+
+
+def _ref(x):
+    return None if x is None else ctypes.byref(x)
+
+
+def _ints(a) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ip(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_I32P)
+
+
+def _stream_handle(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+def ba_version() -> int:
+    return int(load().ba_version())
+
+
+def ba_encode_blocks_workspace_bytes(heads: Heads, block_offsets, rope_mode: int = ROPE_APPLY,
+                                     have_k_local_out: bool = False) -> int:
+    offs = _ints(block_offsets)
+    return int(load().ba_encode_blocks_workspace_bytes(ctypes.byref(heads.c), len(offs) - 1, _ip(offs),
+                                                       rope_mode, int(have_k_local_out)))
+
+
+def ba_encode_blocks(heads: Heads, q, k, v, o_out, k_local_out, block_offsets, rope_mode: int = ROPE_APPLY,
+                     ws=None, stream=None) -> None:
+    offs = _ints(block_offsets)
+    wp, wb = _ws(ws)
+    tq, tk, tv, to, tkl = _tensor(q), _tensor(k), _tensor(v), _tensor(o_out), _tensor(k_local_out)
+    _check(load().ba_encode_blocks(ctypes.byref(heads.c), _ref(tq), _ref(tk), _ref(tv), _ref(to), _ref(tkl),
+                                   len(offs) - 1, _ip(offs), rope_mode, wp, wb, _stream_handle(stream)))
+
+
+def ba_reencode_positions(heads: Heads, k_src, k_dst, src_tok_off, dst_tok_off, lens, old_pos0=None,
+                          new_pos0=None, mode: int = REENC_SHIFT, stream=None) -> None:
+    """k_src / k_dst: [layers, tokens, heads, D] (or [tokens, heads, D] for one layer)."""
+    if k_src.dim() == 3:
+        k_src, k_dst = k_src[None], k_dst[None]
+    n_layers = k_src.shape[0]
+    ts, td = _tensor(k_src[0]), _tensor(k_dst[0])
+    so, do, ln = _ints(src_tok_off), _ints(dst_tok_off), _ints(lens)
+    op, npos = _ints(old_pos0), _ints(new_pos0)
+    _check(load().ba_reencode_positions(ctypes.byref(heads.c), _ref(ts), _ref(td), n_layers, k_src.stride(0),
+                                        k_dst.stride(0), len(ln), _ip(so), _ip(do), _ip(ln), _ip(op), _ip(npos),
+                                        mode, _stream_handle(stream)))
+
+
+def ba_final_block_attention_workspace_bytes(heads: Heads, cu_q, cu_ctx, rope_mode: int = ROPE_APPLY,
+                                             have_k_f_rot_out: bool = False) -> int:
+    cq, cc = _ints(cu_q), _ints(cu_ctx)
+    return int(load().ba_final_block_attention_workspace_bytes(ctypes.byref(heads.c), len(cq) - 1, _ip(cq),
+                                                               _ip(cc), rope_mode, int(have_k_f_rot_out)))
+
+
+def ba_final_block_attention(heads: Heads, q_f, k_ctx, v_ctx, k_f, v_f, o_out, k_f_rot_out, cu_q, cu_ctx,
+                             q_pos0=None, rope_mode: int = ROPE_APPLY, ws=None, stream=None) -> None:
+    cq, cc, qp = _ints(cu_q), _ints(cu_ctx), _ints(q_pos0)
+    wp, wb = _ws(ws)
+    tq, tkc, tvc = _tensor(q_f), _tensor(k_ctx), _tensor(v_ctx)
+    tkf, tvf, to, tkr = _tensor(k_f), _tensor(v_f), _tensor(o_out), _tensor(k_f_rot_out)
+    _check(load().ba_final_block_attention(ctypes.byref(heads.c), _ref(tq), _ref(tkc), _ref(tvc), _ref(tkf),
+                                           _ref(tvf), _ref(to), _ref(tkr), len(cq) - 1, _ip(cq), _ip(cc),
+                                           _ip(qp), rope_mode, wp, wb, _stream_handle(stream)))

@@ -1,0 +1,556 @@
+// C boundary of the Block-attention library: argument validation, host-side
+// scheduling (row tiles, KV splits, launch chunking) and kernel launches.  Nothing in
+// this file touches device memory itself or synchronises.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "../../include/ba.h"
+#include "ba_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int32_t fail(int32_t status, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return status;
+}
+
+int32_t device_fail(hipError_t e, const char *what) {
+  return fail(BA_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+size_t elt_size(int32_t dtype) { return dtype == BA_DTYPE_F32 ? 4 : 2; }
+
+int32_t check_tensor(const ba_tensor *t, const char *name, bool allow_f32, int32_t D, int32_t n_heads) {
+  if (!t || !t->ptr) return fail(BA_ERR_INVALID_ARG, "%s: null tensor", name);
+  if (t->dtype != BA_DTYPE_BF16 && !(allow_f32 && t->dtype == BA_DTYPE_F32))
+    return fail(BA_ERR_UNSUPPORTED, "%s: dtype %d not supported here", name, t->dtype);
+  const size_t es = elt_size(t->dtype);
+  if (((uintptr_t)t->ptr & 15) || ((t->stride_tok * (int64_t)es) & 15) || ((t->stride_head * (int64_t)es) & 15))
+    return fail(BA_ERR_ALIGNMENT, "%s: pointer and strides must be 16-byte aligned", name);
+  if (t->stride_head < D || t->stride_tok < (int64_t)D)
+    return fail(BA_ERR_INVALID_ARG, "%s: strides smaller than head_dim", name);
+  (void)n_heads;
+  return BA_OK;
+}
+
+int32_t check_heads(const ba_heads *h, bool attention) {
+  if (!h) return fail(BA_ERR_INVALID_ARG, "heads: null");
+  if (h->head_dim != 64 && h->head_dim != 128)
+    return fail(BA_ERR_UNSUPPORTED, "head_dim %d: only 64 and 128 are built", h->head_dim);
+  if (h->n_kv_heads <= 0) return fail(BA_ERR_INVALID_ARG, "n_kv_heads must be positive");
+  if (h->rope_layout != BA_ROPE_INTERLEAVED && h->rope_layout != BA_ROPE_HALF)
+    return fail(BA_ERR_INVALID_ARG, "rope_layout %d unknown", h->rope_layout);
+  if (!h->inv_freq && !(h->rope_base > 0.0)) return fail(BA_ERR_INVALID_ARG, "rope_base must be positive");
+  if (attention) {
+    if (h->n_q_heads <= 0 || h->n_q_heads % h->n_kv_heads)
+      return fail(BA_ERR_INVALID_ARG, "n_q_heads must be a positive multiple of n_kv_heads");
+    const int g = h->n_q_heads / h->n_kv_heads;
+    if (h->q_to_kv)
+      for (int i = 0; i < h->n_q_heads; ++i)
+        if (h->q_to_kv[i] != i / g)
+          return fail(BA_ERR_UNSUPPORTED, "q_to_kv: only the map h -> h / group is built");
+  }
+  return BA_OK;
+}
+
+// theta_j / (2 pi) as a Q0.64 fraction, from extended-precision host arithmetic.
+void build_rope_table(const ba_heads *h, ba::RopeTable *rt) {
+  const long double two_pi = 6.283185307179586476925286766559005768L;
+  const int half = h->head_dim / 2;
+  for (int j = 0; j < ba::kMaxFreq; ++j) rt->turns[j] = 0;
+  for (int j = 0; j < half; ++j) {
+    long double th = h->inv_freq ? (long double)h->inv_freq[j]
+                                 : powl((long double)h->rope_base, -2.0L * j / (long double)h->head_dim);
+    long double turns = th / two_pi;
+    turns -= floorl(turns);  // whole turns per position do not change the angle
+    const long double up = ldexpl(turns, 32);  // split so each half fits 32 bits exactly
+    const uint64_t hi = (uint64_t)floorl(up);
+    const uint64_t lo = (uint64_t)floorl(ldexpl(up - floorl(up), 32));
+    rt->turns[j] = (hi << 32) | (lo & 0xffffffffull);
+  }
+}
+
+float scale_log2e(const ba_heads *h) {
+  const double s = h->softmax_scale > 0.f ? (double)h->softmax_scale : 1.0 / sqrt((double)h->head_dim);
+  return (float)(s * 1.4426950408889634074);
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+constexpr int kNumCU = 256;  // MI355X
+
+// Number of KV splits for the final-block launch: enough workgroups to cover the chip,
+// never fewer than four key tiles per split.
+int choose_splits(int64_t base_wgs, int max_tiles_per_problem) {
+  if (base_wgs <= 0) return 1;
+  int64_t s = (kNumCU + base_wgs - 1) / base_wgs;
+  s = std::min<int64_t>(s, std::max(1, max_tiles_per_problem / 4));
+  s = std::min<int64_t>(s, 32);
+  return (int)std::max<int64_t>(s, 1);
+}
+
+struct FinalPlan {
+  int64_t lq_total = 0;
+  int64_t total_tiles = 0;
+  int max_nt = 0;
+  int n_splits = 1;
+  size_t kf_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0;
+  size_t total() const { return align256(kf_bytes) + align256(part_o_bytes) + align256(part_ml_bytes); }
+};
+
+int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_ctx,
+                   int32_t rope_mode, bool have_rot_out, FinalPlan *plan) {
+  if (n_prompts < 0 || (n_prompts > 0 && (!cu_q || !cu_ctx)))
+    return fail(BA_ERR_INVALID_ARG, "cu_q / cu_ctx: null or negative prompt count");
+  const int G = h->n_q_heads / h->n_kv_heads;
+  FinalPlan pl;
+  if (n_prompts > 0 && cu_q[0] != 0) return fail(BA_ERR_INVALID_ARG, "cu_q[0] must be 0");
+  if (n_prompts > 0 && cu_ctx[0] < 0) return fail(BA_ERR_INVALID_ARG, "cu_ctx[0] must not be negative");
+  for (int n = 0; n < n_prompts; ++n) {
+    const int64_t lq = (int64_t)cu_q[n + 1] - cu_q[n];
+    const int64_t tc = (int64_t)cu_ctx[n + 1] - cu_ctx[n];
+    if (lq < 1) return fail(BA_ERR_INVALID_ARG, "prompt %d: the final block needs at least one token", n);
+    if (tc < 0) return fail(BA_ERR_INVALID_ARG, "prompt %d: cu_ctx decreases", n);
+    if (lq * G > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "prompt %d: too many packed rows", n);
+    pl.total_tiles += (lq * G + ba::kTileRows - 1) / ba::kTileRows;
+    const int nt = (int)((tc + ba::kTileKeys - 1) / ba::kTileKeys + (lq + ba::kTileKeys - 1) / ba::kTileKeys);
+    pl.max_nt = std::max(pl.max_nt, nt);
+  }
+  pl.lq_total = n_prompts > 0 ? cu_q[n_prompts] : 0;
+  pl.n_splits = choose_splits(pl.total_tiles * h->n_kv_heads, pl.max_nt);
+  if (rope_mode == BA_ROPE_APPLY && !have_rot_out)
+    pl.kf_bytes = (size_t)pl.lq_total * h->n_kv_heads * h->head_dim * 2;
+  if (pl.n_splits > 1) {
+    const size_t rows = (size_t)pl.lq_total * h->n_q_heads;
+    pl.part_o_bytes = (size_t)pl.n_splits * rows * h->head_dim * 4;
+    pl.part_ml_bytes = (size_t)pl.n_splits * rows * 2 * 4;
+  }
+  *plan = pl;
+  return BA_OK;
+}
+
+int32_t check_offsets(int32_t n_blocks, const int32_t *offs) {
+  if (n_blocks < 0 || !offs) return fail(BA_ERR_INVALID_ARG, "block_offsets: null or negative block count");
+  if (offs[0] != 0) return fail(BA_ERR_INVALID_ARG, "block_offsets[0] must be 0");
+  for (int b = 0; b < n_blocks; ++b)
+    if (offs[b + 1] < offs[b]) return fail(BA_ERR_INVALID_ARG, "block_offsets must not decrease (block %d)", b);
+  return BA_OK;
+}
+
+// Run the rotation kernel over a list of blocks, a launch per kReencMaxBlocks of them.
+int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, const int32_t *src_off,
+                     const int32_t *dst_off, const int32_t *len, const int32_t *pos_old,
+                     const int32_t *pos_new, hipStream_t stream) {
+  for (int b0 = 0; b0 < n_blocks; b0 += ba::kReencMaxBlocks) {
+    ba::ReencBlocks blk;
+    memset(&blk, 0, sizeof(blk));
+    const int n = std::min(ba::kReencMaxBlocks, n_blocks - b0);
+    int filled = 0, max_len = 0;
+    for (int i = 0; i < n; ++i) {
+      const int b = b0 + i;
+      if (len[b] == 0) continue;
+      blk.src_off[filled] = src_off[b];
+      blk.dst_off[filled] = dst_off[b];
+      blk.len[filled] = len[b];
+      blk.pos_old[filled] = pos_old ? pos_old[b] : 0;
+      blk.pos_new[filled] = pos_new ? pos_new[b] : dst_off[b];
+      max_len = std::max(max_len, len[b]);
+      ++filled;
+    }
+    if (!filled) continue;
+    blk.n = filled;
+    p.max_len = max_len;
+    hipError_t e = ba::launch_reencode(p, blk, rt, stream);
+    if (e != hipSuccess) return device_fail(e, "re-encode launch");
+  }
+  return BA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t ba_version(void) { return 100; }
+
+const char *ba_status_string(int32_t status) {
+  switch (status) {
+    case BA_OK: return "BA_OK";
+    case BA_ERR_INVALID_ARG: return "BA_ERR_INVALID_ARG";
+    case BA_ERR_UNSUPPORTED: return "BA_ERR_UNSUPPORTED";
+    case BA_ERR_ALIGNMENT: return "BA_ERR_ALIGNMENT";
+    case BA_ERR_WORKSPACE: return "BA_ERR_WORKSPACE";
+    case BA_ERR_DEVICE: return "BA_ERR_DEVICE";
+    default: return "BA_ERR_UNKNOWN";
+  }
+}
+
+const char *ba_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------------------------------
+size_t ba_encode_blocks_workspace_bytes(const ba_heads *heads, int32_t n_blocks,
+                                        const int32_t *block_offsets, int32_t rope_mode,
+                                        int32_t have_k_local_out) {
+  if (!heads || !block_offsets || n_blocks < 0) return 0;
+  if (rope_mode != BA_ROPE_APPLY || have_k_local_out) return 0;
+  return align256((size_t)block_offsets[n_blocks] * heads->n_kv_heads * heads->head_dim * 2);
+}
+
+int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
+                         const ba_tensor *v, const ba_tensor *o_out, const ba_tensor *k_local_out,
+                         int32_t n_blocks, const int32_t *block_offsets, int32_t rope_mode, void *ws,
+                         size_t ws_bytes, void *stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t rc;
+  if ((rc = check_heads(heads, true))) return rc;
+  if ((rc = check_offsets(n_blocks, block_offsets))) return rc;
+  const int D = heads->head_dim;
+  if ((rc = check_tensor(q, "q", false, D, heads->n_q_heads))) return rc;
+  if ((rc = check_tensor(k, "k", false, D, heads->n_kv_heads))) return rc;
+  if ((rc = check_tensor(v, "v", false, D, heads->n_kv_heads))) return rc;
+  if ((rc = check_tensor(o_out, "o_out", false, D, heads->n_q_heads))) return rc;
+  if (rope_mode != BA_ROPE_NONE && rope_mode != BA_ROPE_APPLY)
+    return fail(BA_ERR_INVALID_ARG, "rope_mode %d unknown", rope_mode);
+  if (k_local_out) {
+    if (rope_mode != BA_ROPE_APPLY)
+      return fail(BA_ERR_INVALID_ARG, "k_local_out needs rope_mode BA_ROPE_APPLY");
+    if ((rc = check_tensor(k_local_out, "k_local_out", false, D, heads->n_kv_heads))) return rc;
+  }
+  const int64_t T = block_offsets[n_blocks];
+  const int G = heads->n_q_heads / heads->n_kv_heads;
+  if (T == 0) return BA_OK;
+
+  ba::RopeTable rt;
+  build_rope_table(heads, &rt);
+
+  // keys the attention kernel reads: the caller's (NONE) or freshly rotated ones (APPLY)
+  ba_tensor k_use = *k;
+  if (rope_mode == BA_ROPE_APPLY) {
+    if (k_local_out) {
+      k_use = *k_local_out;
+    } else {
+      const size_t need = ba_encode_blocks_workspace_bytes(heads, n_blocks, block_offsets, rope_mode, 0);
+      if (!ws || ws_bytes < need || ((uintptr_t)ws & 15))
+        return fail(BA_ERR_WORKSPACE, "encode: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+      k_use.ptr = ws;
+      k_use.stride_head = D;
+      k_use.stride_tok = (int64_t)heads->n_kv_heads * D;
+      k_use.dtype = BA_DTYPE_BF16;
+    }
+    ba::ReencParams rp;
+    memset(&rp, 0, sizeof(rp));
+    rp.src = k->ptr;
+    rp.dst = k_use.ptr;
+    rp.src_st = k->stride_tok;
+    rp.src_sh = k->stride_head;
+    rp.dst_st = k_use.stride_tok;
+    rp.dst_sh = k_use.stride_head;
+    rp.n_layers = 1;
+    rp.n_kv_heads = heads->n_kv_heads;
+    rp.head_dim = D;
+    rp.dtype = BA_DTYPE_BF16;
+    rp.layout = heads->rope_layout;
+    rp.mode = BA_REENC_ABSOLUTE;  // un-rotated keys -> local position u of each block
+    std::vector<int32_t> len(n_blocks), zero(n_blocks, 0);
+    for (int b = 0; b < n_blocks; ++b) len[b] = block_offsets[b + 1] - block_offsets[b];
+    if ((rc = run_reencode(rp, rt, n_blocks, block_offsets, block_offsets, len.data(), zero.data(),
+                           zero.data(), stream)))
+      return rc;
+  }
+
+  ba::AttnParams ap;
+  memset(&ap, 0, sizeof(ap));
+  ap.q = (const uint16_t *)q->ptr;
+  ap.q_st = q->stride_tok;
+  ap.q_sh = q->stride_head;
+  ap.kf = (const uint16_t *)k_use.ptr;
+  ap.kf_st = k_use.stride_tok;
+  ap.kf_sh = k_use.stride_head;
+  ap.vf = (const uint16_t *)v->ptr;
+  ap.vf_st = v->stride_tok;
+  ap.vf_sh = v->stride_head;
+  ap.kc = ap.kf;  // never dereferenced: no context segment
+  ap.kc_st = ap.kf_st;
+  ap.kc_sh = ap.kf_sh;
+  ap.vc = ap.vf;
+  ap.vc_st = ap.vf_st;
+  ap.vc_sh = ap.vf_sh;
+  ap.o = (uint16_t *)o_out->ptr;
+  ap.o_st = o_out->stride_tok;
+  ap.o_sh = o_out->stride_head;
+  ap.n_q_heads = heads->n_q_heads;
+  ap.n_kv_heads = heads->n_kv_heads;
+  ap.group = G;
+  ap.head_dim = D;
+  ap.scale_log2e = scale_log2e(heads);
+  ap.rope_q = rope_mode == BA_ROPE_APPLY;
+  ap.rope_layout = heads->rope_layout;
+  ap.n_splits = 1;
+
+  for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
+    const int n = std::min(ba::kEncMaxBlocks, n_blocks - b0);
+    ba::EncodeMeta meta;
+    memset(&meta, 0, sizeof(meta));
+    meta.n = n;
+    int64_t tiles = 0;
+    for (int i = 0; i < n; ++i) {
+      const int64_t len = (int64_t)block_offsets[b0 + i + 1] - block_offsets[b0 + i];
+      if (len * G > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "block %d: too many packed rows", b0 + i);
+      meta.offs[i] = block_offsets[b0 + i];
+      meta.tile_start[i] = (int32_t)tiles;
+      tiles += (len * G + ba::kTileRows - 1) / ba::kTileRows;
+      if (tiles > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
+    }
+    meta.offs[n] = block_offsets[b0 + n];
+    meta.tile_start[n] = (int32_t)tiles;
+    ap.total_tiles = (int32_t)tiles;
+    if (tiles == 0) continue;
+    hipError_t e = ba::launch_attn_encode(ap, meta, rt, stream);
+    if (e != hipSuccess) return device_fail(e, "encode attention launch");
+  }
+  return BA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+int32_t ba_reencode_positions(const ba_heads *heads, const ba_tensor *k_src, const ba_tensor *k_dst,
+                              int32_t n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
+                              int32_t n_blocks, const int32_t *src_tok_off, const int32_t *dst_tok_off,
+                              const int32_t *len, const int32_t *old_pos0, const int32_t *new_pos0,
+                              int32_t mode, void *stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t rc;
+  if ((rc = check_heads(heads, false))) return rc;
+  const int D = heads->head_dim;
+  if ((rc = check_tensor(k_src, "k_src", true, D, heads->n_kv_heads))) return rc;
+  if ((rc = check_tensor(k_dst, "k_dst", true, D, heads->n_kv_heads))) return rc;
+  if (k_src->dtype != k_dst->dtype) return fail(BA_ERR_UNSUPPORTED, "k_src and k_dst must share a dtype");
+  if (mode != BA_REENC_SHIFT && mode != BA_REENC_ABSOLUTE)
+    return fail(BA_ERR_INVALID_ARG, "mode %d unknown", mode);
+  if (n_layers < 0 || n_blocks < 0) return fail(BA_ERR_INVALID_ARG, "negative layer or block count");
+  if (n_blocks > 0 && (!src_tok_off || !dst_tok_off || !len))
+    return fail(BA_ERR_INVALID_ARG, "src_tok_off / dst_tok_off / len: null");
+  const size_t es = elt_size(k_src->dtype);
+  if (n_layers > 1 && (((layer_stride_src * (int64_t)es) & 15) || ((layer_stride_dst * (int64_t)es) & 15)))
+    return fail(BA_ERR_ALIGNMENT, "layer strides must be 16-byte aligned");
+  if (n_layers > 65535) return fail(BA_ERR_UNSUPPORTED, "more than 65535 layers in one call");
+  for (int b = 0; b < n_blocks; ++b)
+    if (len[b] < 0 || src_tok_off[b] < 0 || dst_tok_off[b] < 0)
+      return fail(BA_ERR_INVALID_ARG, "block %d: negative offset or length", b);
+
+  // aliasing: either exactly in place, or destination spans disjoint from source spans
+  const bool same_buf = k_src->ptr == k_dst->ptr;
+  if (same_buf) {
+    bool in_place = k_src->stride_tok == k_dst->stride_tok && k_src->stride_head == k_dst->stride_head &&
+                    (n_layers <= 1 || layer_stride_src == layer_stride_dst);
+    for (int b = 0; b < n_blocks && in_place; ++b) in_place = src_tok_off[b] == dst_tok_off[b];
+    if (!in_place) return fail(BA_ERR_INVALID_ARG, "k_dst aliases k_src but is not exactly in place");
+  } else {
+    // token extents touched, per layer, in bytes from the base pointers
+    int64_t src_hi = 0, dst_hi = 0;
+    for (int b = 0; b < n_blocks; ++b) {
+      src_hi = std::max<int64_t>(src_hi, (int64_t)src_tok_off[b] + len[b]);
+      dst_hi = std::max<int64_t>(dst_hi, (int64_t)dst_tok_off[b] + len[b]);
+    }
+    const int64_t src_span = ((n_layers - 1) * layer_stride_src + src_hi * k_src->stride_tok) * (int64_t)es;
+    const int64_t dst_span = ((n_layers - 1) * layer_stride_dst + dst_hi * k_dst->stride_tok) * (int64_t)es;
+    const char *s0 = (const char *)k_src->ptr, *d0 = (const char *)k_dst->ptr;
+    if (n_layers > 0 && s0 < d0 + dst_span && d0 < s0 + src_span)
+      return fail(BA_ERR_INVALID_ARG, "k_dst overlaps k_src without being exactly in place");
+  }
+  if (!same_buf) {
+    // destination blocks must not overlap each other
+    std::vector<std::pair<int64_t, int64_t>> spans;
+    for (int b = 0; b < n_blocks; ++b)
+      if (len[b] > 0) spans.emplace_back(dst_tok_off[b], (int64_t)dst_tok_off[b] + len[b]);
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+      if (spans[i].first < spans[i - 1].second)
+        return fail(BA_ERR_INVALID_ARG, "destination blocks overlap each other");
+  }
+  if (n_layers == 0 || n_blocks == 0) return BA_OK;
+
+  ba::RopeTable rt;
+  build_rope_table(heads, &rt);
+  ba::ReencParams rp;
+  memset(&rp, 0, sizeof(rp));
+  rp.src = k_src->ptr;
+  rp.dst = k_dst->ptr;
+  rp.src_st = k_src->stride_tok;
+  rp.src_sh = k_src->stride_head;
+  rp.dst_st = k_dst->stride_tok;
+  rp.dst_sh = k_dst->stride_head;
+  rp.src_sl = layer_stride_src;
+  rp.dst_sl = layer_stride_dst;
+  rp.n_layers = n_layers;
+  rp.n_kv_heads = heads->n_kv_heads;
+  rp.head_dim = D;
+  rp.dtype = k_src->dtype;
+  rp.layout = heads->rope_layout;
+  rp.mode = mode;
+  return run_reencode(rp, rt, n_blocks, src_tok_off, dst_tok_off, len, old_pos0, new_pos0, stream);
+}
+
+// ------------------------------------------------------------------------------------------
+size_t ba_final_block_attention_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
+                                                const int32_t *cu_q, const int32_t *cu_ctx,
+                                                int32_t rope_mode, int32_t have_k_f_rot_out) {
+  if (check_heads(heads, true) != BA_OK) return 0;
+  FinalPlan pl;
+  if (plan_final(heads, n_prompts, cu_q, cu_ctx, rope_mode, have_k_f_rot_out != 0, &pl) != BA_OK) return 0;
+  return pl.total();
+}
+
+int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, const ba_tensor *k_ctx,
+                                 const ba_tensor *v_ctx, const ba_tensor *k_f, const ba_tensor *v_f,
+                                 const ba_tensor *o_out, const ba_tensor *k_f_rot_out, int32_t n_prompts,
+                                 const int32_t *cu_q, const int32_t *cu_ctx, const int32_t *q_pos0,
+                                 int32_t rope_mode, void *ws, size_t ws_bytes, void *stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t rc;
+  if ((rc = check_heads(heads, true))) return rc;
+  const int D = heads->head_dim;
+  if (rope_mode != BA_ROPE_NONE && rope_mode != BA_ROPE_APPLY)
+    return fail(BA_ERR_INVALID_ARG, "rope_mode %d unknown", rope_mode);
+  FinalPlan pl;
+  if ((rc = plan_final(heads, n_prompts, cu_q, cu_ctx, rope_mode, k_f_rot_out != nullptr, &pl))) return rc;
+  if (n_prompts == 0) return BA_OK;
+  if ((rc = check_tensor(q_f, "q_f", false, D, heads->n_q_heads))) return rc;
+  if ((rc = check_tensor(k_f, "k_f", false, D, heads->n_kv_heads))) return rc;
+  if ((rc = check_tensor(v_f, "v_f", false, D, heads->n_kv_heads))) return rc;
+  if ((rc = check_tensor(o_out, "o_out", false, D, heads->n_q_heads))) return rc;
+  const bool any_ctx = cu_ctx[n_prompts] > cu_ctx[0];
+  if (any_ctx) {
+    if ((rc = check_tensor(k_ctx, "k_ctx", false, D, heads->n_kv_heads))) return rc;
+    if ((rc = check_tensor(v_ctx, "v_ctx", false, D, heads->n_kv_heads))) return rc;
+  }
+  if (k_f_rot_out) {
+    if (rope_mode != BA_ROPE_APPLY)
+      return fail(BA_ERR_INVALID_ARG, "k_f_rot_out needs rope_mode BA_ROPE_APPLY");
+    if ((rc = check_tensor(k_f_rot_out, "k_f_rot_out", false, D, heads->n_kv_heads))) return rc;
+  }
+  if (pl.total() > 0 && (!ws || ws_bytes < pl.total() || ((uintptr_t)ws & 255)))
+    return fail(BA_ERR_WORKSPACE, "final block: 256-byte aligned workspace of %zu bytes needed, %zu given",
+                pl.total(), ws_bytes);
+
+  char *wsp = (char *)ws;
+  void *kf_ws = wsp;
+  float *part_o = (float *)(wsp + align256(pl.kf_bytes));
+  float *part_ml = (float *)(wsp + align256(pl.kf_bytes) + align256(pl.part_o_bytes));
+
+  ba::RopeTable rt;
+  build_rope_table(heads, &rt);
+
+  std::vector<int32_t> pos0(n_prompts), lens(n_prompts), starts(n_prompts), zero(n_prompts, 0);
+  for (int n = 0; n < n_prompts; ++n) {
+    pos0[n] = q_pos0 ? q_pos0[n] : cu_ctx[n + 1] - cu_ctx[n];
+    lens[n] = cu_q[n + 1] - cu_q[n];
+    starts[n] = cu_q[n];
+  }
+
+  ba_tensor kf_use = *k_f;
+  if (rope_mode == BA_ROPE_APPLY) {
+    if (k_f_rot_out) {
+      kf_use = *k_f_rot_out;
+    } else {
+      kf_use.ptr = kf_ws;
+      kf_use.stride_head = D;
+      kf_use.stride_tok = (int64_t)heads->n_kv_heads * D;
+    }
+    ba::ReencParams rp;
+    memset(&rp, 0, sizeof(rp));
+    rp.src = k_f->ptr;
+    rp.dst = kf_use.ptr;
+    rp.src_st = k_f->stride_tok;
+    rp.src_sh = k_f->stride_head;
+    rp.dst_st = kf_use.stride_tok;
+    rp.dst_sh = kf_use.stride_head;
+    rp.n_layers = 1;
+    rp.n_kv_heads = heads->n_kv_heads;
+    rp.head_dim = D;
+    rp.dtype = BA_DTYPE_BF16;
+    rp.layout = heads->rope_layout;
+    rp.mode = BA_REENC_ABSOLUTE;  // un-rotated final-block keys -> absolute positions
+    if ((rc = run_reencode(rp, rt, n_prompts, starts.data(), starts.data(), lens.data(), zero.data(),
+                           pos0.data(), stream)))
+      return rc;
+  }
+
+  const int G = heads->n_q_heads / heads->n_kv_heads;
+  ba::AttnParams ap;
+  memset(&ap, 0, sizeof(ap));
+  ap.q = (const uint16_t *)q_f->ptr;
+  ap.q_st = q_f->stride_tok;
+  ap.q_sh = q_f->stride_head;
+  ap.kf = (const uint16_t *)kf_use.ptr;
+  ap.kf_st = kf_use.stride_tok;
+  ap.kf_sh = kf_use.stride_head;
+  ap.vf = (const uint16_t *)v_f->ptr;
+  ap.vf_st = v_f->stride_tok;
+  ap.vf_sh = v_f->stride_head;
+  if (any_ctx) {
+    ap.kc = (const uint16_t *)k_ctx->ptr;
+    ap.kc_st = k_ctx->stride_tok;
+    ap.kc_sh = k_ctx->stride_head;
+    ap.vc = (const uint16_t *)v_ctx->ptr;
+    ap.vc_st = v_ctx->stride_tok;
+    ap.vc_sh = v_ctx->stride_head;
+  } else {
+    ap.kc = ap.kf;
+    ap.kc_st = ap.kf_st;
+    ap.kc_sh = ap.kf_sh;
+    ap.vc = ap.vf;
+    ap.vc_st = ap.vf_st;
+    ap.vc_sh = ap.vf_sh;
+  }
+  ap.o = (uint16_t *)o_out->ptr;
+  ap.o_st = o_out->stride_tok;
+  ap.o_sh = o_out->stride_head;
+  ap.part_o = part_o;
+  ap.part_ml = part_ml;
+  ap.part_rows = pl.lq_total * heads->n_q_heads;
+  ap.n_q_heads = heads->n_q_heads;
+  ap.n_kv_heads = heads->n_kv_heads;
+  ap.group = G;
+  ap.head_dim = D;
+  ap.scale_log2e = scale_log2e(heads);
+  ap.rope_q = rope_mode == BA_ROPE_APPLY;
+  ap.rope_layout = heads->rope_layout;
+  ap.n_splits = pl.n_splits;
+
+  for (int n0 = 0; n0 < n_prompts; n0 += ba::kFinMaxPrompts) {
+    const int n = std::min(ba::kFinMaxPrompts, n_prompts - n0);
+    ba::FinalMeta meta;
+    memset(&meta, 0, sizeof(meta));
+    meta.n = n;
+    int64_t tiles = 0;
+    for (int i = 0; i < n; ++i) {
+      meta.cu_q[i] = cu_q[n0 + i];
+      meta.cu_ctx[i] = cu_ctx[n0 + i];
+      meta.pos0[i] = pos0[n0 + i];
+      meta.tile_start[i] = (int32_t)tiles;
+      tiles += ((int64_t)lens[n0 + i] * G + ba::kTileRows - 1) / ba::kTileRows;
+    }
+    meta.cu_q[n] = cu_q[n0 + n];
+    meta.cu_ctx[n] = cu_ctx[n0 + n];
+    meta.tile_start[n] = (int32_t)tiles;
+    ap.total_tiles = (int32_t)tiles;
+    hipError_t e = ba::launch_attn_final(ap, meta, rt, stream);
+    if (e != hipSuccess) return device_fail(e, "final-block attention launch");
+  }
+  if (pl.n_splits > 1) {
+    hipError_t e = ba::launch_combine(ap, pl.lq_total, stream);
+    if (e != hipSuccess) return device_fail(e, "split combine launch");
+  }
+  return BA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,95 @@
+// Internal interface between the C boundary (ba_api.hip) and the gfx950 kernels.
+// Small per-call metadata travels BY VALUE in the kernel-argument segment, so no call
+// ever copies host memory to the device or needs device-side scratch for schedules;
+// long block lists are cut into several launches by the host code.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ba {
+
+constexpr int kMaxFreq = 64;  // head_dim / 2 <= 64
+
+// theta_j / (2*pi) as an unsigned Q0.64 fraction of a turn.  position * turns[j]
+// (mod 2^64) is then the exact phase of the RoPE angle position * theta_j (Eq. 1).
+struct RopeTable {
+  uint64_t turns[kMaxFreq];
+};
+
+// ---------------------------------------------------------------- re-encode ----------
+constexpr int kReencMaxBlocks = 96;
+
+struct ReencBlocks {
+  int32_t n;
+  int32_t src_off[kReencMaxBlocks];
+  int32_t dst_off[kReencMaxBlocks];
+  int32_t len[kReencMaxBlocks];
+  int32_t pos_old[kReencMaxBlocks];
+  int32_t pos_new[kReencMaxBlocks];
+};
+
+struct ReencParams {
+  const void *src;
+  void *dst;
+  int64_t src_st, src_sh, dst_st, dst_sh;  // token / head strides, elements
+  int64_t src_sl, dst_sl;                  // layer strides, elements
+  int32_t n_layers, n_kv_heads, head_dim;
+  int32_t dtype, layout, mode;
+  int32_t max_len;  // longest block in this launch
+};
+
+hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
+                           hipStream_t stream);
+
+// ---------------------------------------------------------------- attention ----------
+constexpr int kTileRows = 256;  // packed (token, head-in-group) query rows per workgroup
+constexpr int kTileKeys = 64;   // keys per K/V tile
+
+struct AttnParams {
+  const uint16_t *q;
+  int64_t q_st, q_sh;
+  const uint16_t *kc;  // context keys / values (final block only; used as given)
+  int64_t kc_st, kc_sh;
+  const uint16_t *vc;
+  int64_t vc_st, vc_sh;
+  const uint16_t *kf;  // causal-segment keys / values (already rotated)
+  int64_t kf_st, kf_sh;
+  const uint16_t *vf;
+  int64_t vf_st, vf_sh;
+  uint16_t *o;
+  int64_t o_st, o_sh;
+  float *part_o;   // [n_splits][part_rows][D]   un-normalised partial outputs
+  float *part_ml;  // [n_splits][part_rows][2]   (max in log2 units, sum of exponentials)
+  int64_t part_rows;
+  int32_t n_q_heads, n_kv_heads, group, head_dim;
+  float scale_log2e;  // softmax scale * log2(e)
+  int32_t rope_q, rope_layout;
+  int32_t n_splits;
+  int32_t total_tiles;  // row tiles over all problems of this launch
+};
+
+constexpr int kEncMaxBlocks = 320;
+struct EncodeMeta {
+  int32_t n;
+  int32_t offs[kEncMaxBlocks + 1];        // token offsets of the blocks
+  int32_t tile_start[kEncMaxBlocks + 1];  // first row tile of each block
+};
+
+constexpr int kFinMaxPrompts = 64;
+struct FinalMeta {
+  int32_t n;
+  int32_t cu_q[kFinMaxPrompts + 1];
+  int32_t cu_ctx[kFinMaxPrompts + 1];
+  int32_t pos0[kFinMaxPrompts];
+  int32_t tile_start[kFinMaxPrompts + 1];
+};
+
+hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, const RopeTable &rt,
+                              hipStream_t stream);
+hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, const RopeTable &rt,
+                             hipStream_t stream);
+// Merge split-KV partials into the bf16 output.  rows = tokens * n_q_heads.
+hipError_t launch_combine(const AttnParams &p, int64_t n_tokens, hipStream_t stream);
+
+}  // namespace ba

@@ -1,0 +1,177 @@
+// Position re-encoding of cached keys (Section 2.3 of arXiv 2409.15355): the two
+// rotations of Eq. 2 and Eq. 3 collapse into one rotation by the position difference,
+// applied here as a single coalesced HBM pass: 16-byte loads, fp32 rotate, 16-byte
+// stores.  Memory-bound: 2 B read + 2 B written per bf16 element.
+//
+// Thread mapping.  A head vector of D elements is CH = D / VEC 16-byte chunks.  A
+// thread owns chunk c and chunk c + CH/2 of one token and walks over that token's KV
+// heads, so its VEC (cos, sin) pairs are computed once per token (ABSOLUTE mode) or
+// once per workgroup (SHIFT mode: the angle depends on the block only) and reused for
+// every head.  CH/2 neighbouring lanes cover half a head vector contiguously.
+#include "ba_device.h"
+
+namespace ba {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <typename T>
+struct Chunk;  // 16 bytes of T as floats
+
+template <>
+struct Chunk<uint16_t> {
+  static constexpr int VEC = 8;
+  float f[8];
+  __device__ __forceinline__ void load(const uint16_t *p) {
+    u32x4_t w = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = bf16_lo(w[i]);
+      f[2 * i + 1] = bf16_hi(w[i]);
+    }
+  }
+  __device__ __forceinline__ void store(uint16_t *p) const {
+    u32x4_t w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = pack_bf16(f[2 * i], f[2 * i + 1]);
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t *>(p));
+  }
+};
+
+template <>
+struct Chunk<float> {
+  static constexpr int VEC = 4;
+  float f[4];
+  __device__ __forceinline__ void load(const float *p) {
+    f32x4_t w = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(p));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f[i] = w[i];
+  }
+  __device__ __forceinline__ void store(float *p) const {
+    f32x4_t w = {f[0], f[1], f[2], f[3]};
+    __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t *>(p));
+  }
+};
+
+// y = R(angle) x on one (a, b) pair: [[c, -s], [s, c]] (Eq. 1 / Eq. 3).
+__device__ __forceinline__ void rotate(float &a, float &b, float c, float s) {
+  float na = c * a - s * b;
+  float nb = s * a + c * b;
+  a = na;
+  b = nb;
+}
+
+template <typename T, int D, int LAYOUT, int MODE, int TOK_PER_WG>
+__global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, ReencBlocks blocks,
+                                                            RopeTable rt) {
+  constexpr int VEC = Chunk<T>::VEC;
+  constexpr int CH = D / VEC;           // chunks per head vector
+  constexpr int TPV = CH / 2;           // threads per head vector
+  constexpr int TPP = kThreads / TPV;   // tokens per pass
+  static_assert(TOK_PER_WG % TPP == 0, "tokens per workgroup must be whole passes");
+
+  const int b = blockIdx.y;
+  const int layer = blockIdx.z;
+  const int len = blocks.len[b];
+  const int tok0 = blockIdx.x * TOK_PER_WG;
+  if (tok0 >= len) return;
+
+  const int c = threadIdx.x % TPV;
+  const int tl = threadIdx.x / TPV;
+
+  // frequencies of this thread's VEC pairs
+  uint64_t turns[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    int j;
+    if (LAYOUT == 0)  // interleaved: pairs live inside each chunk
+      j = (e < VEC / 2) ? c * (VEC / 2) + e : (c + CH / 2) * (VEC / 2) + (e - VEC / 2);
+    else  // half: element e of chunk c pairs with element e of chunk c + CH/2
+      j = c * VEC + e;
+    turns[e] = rt.turns[j];
+  }
+
+  const int shift0 = blocks.pos_new[b] - blocks.pos_old[b];
+  const T *src = static_cast<const T *>(p.src) + (int64_t)layer * p.src_sl +
+                 (int64_t)blocks.src_off[b] * p.src_st;
+  T *dst = static_cast<T *>(p.dst) + (int64_t)layer * p.dst_sl + (int64_t)blocks.dst_off[b] * p.dst_st;
+
+  float cs[VEC], sn[VEC];
+  if (MODE == 0) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) sincos_phase(rope_phase(shift0, turns[e]), cs[e], sn[e]);
+  }
+  const bool plain_copy = (MODE == 0) && (shift0 == 0);  // zero shift: bit-for-bit copy
+  const int H = p.n_kv_heads;
+
+#pragma unroll 1
+  for (int pass = 0; pass < TOK_PER_WG / TPP; ++pass) {
+    const int u = tok0 + pass * TPP + tl;
+    if (u >= len) break;
+    if (MODE == 1) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sincos_phase(rope_phase(shift0 + u, turns[e]), cs[e], sn[e]);
+    }
+    const T *s0 = src + (int64_t)u * p.src_st + c * VEC;
+    T *d0 = dst + (int64_t)u * p.dst_st + c * VEC;
+#pragma unroll 4
+    for (int g = 0; g < H; ++g) {
+      Chunk<T> x, y;
+      x.load(s0 + g * p.src_sh);
+      y.load(s0 + g * p.src_sh + (CH / 2) * VEC);
+      if (!plain_copy) {
+        if (LAYOUT == 0) {
+#pragma unroll
+          for (int e = 0; e < VEC / 2; ++e) {
+            rotate(x.f[2 * e], x.f[2 * e + 1], cs[e], sn[e]);
+            rotate(y.f[2 * e], y.f[2 * e + 1], cs[VEC / 2 + e], sn[VEC / 2 + e]);
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) rotate(x.f[e], y.f[e], cs[e], sn[e]);
+        }
+      }
+      x.store(d0 + g * p.dst_sh);
+      y.store(d0 + g * p.dst_sh + (CH / 2) * VEC);
+    }
+  }
+}
+
+template <typename T, int D, int LAYOUT, int MODE>
+hipError_t launch_t(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
+                    hipStream_t stream) {
+  constexpr int VEC = Chunk<T>::VEC;
+  constexpr int TPP = kThreads / (D / VEC / 2);
+  constexpr int TOK_PER_WG = TPP * 2;
+  dim3 grid((p.max_len + TOK_PER_WG - 1) / TOK_PER_WG, blocks.n, p.n_layers);
+  if (grid.x == 0 || grid.y == 0 || grid.z == 0) return hipSuccess;
+  hipLaunchKernelGGL((reencode_kernel<T, D, LAYOUT, MODE, TOK_PER_WG>), grid, dim3(kThreads), 0,
+                     stream, p, blocks, rt);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t launch_d(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
+                    hipStream_t stream) {
+  if (p.layout == 0)
+    return p.mode == 0 ? launch_t<T, D, 0, 0>(p, blocks, rt, stream)
+                       : launch_t<T, D, 0, 1>(p, blocks, rt, stream);
+  return p.mode == 0 ? launch_t<T, D, 1, 0>(p, blocks, rt, stream)
+                     : launch_t<T, D, 1, 1>(p, blocks, rt, stream);
+}
+
+}  // namespace
+
+hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
+                           hipStream_t stream) {
+  if (p.dtype == 0) {
+    if (p.head_dim == 128) return launch_d<uint16_t, 128>(p, blocks, rt, stream);
+    if (p.head_dim == 64) return launch_d<uint16_t, 64>(p, blocks, rt, stream);
+  } else {
+    if (p.head_dim == 128) return launch_d<float, 128>(p, blocks, rt, stream);
+    if (p.head_dim == 64) return launch_d<float, 64>(p, blocks, rt, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace ba

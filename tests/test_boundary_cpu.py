@@ -1,0 +1,124 @@
+"""Host-side checks of the C boundary that need no GPU: the shared library loads, exports
+every symbol include/ba.h declares, and turns bad arguments into status codes before any
+device work is attempted."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2409_15355_amd import binding as ba
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ba.LIB_PATH):
+        from paper_2409_15355_amd import build
+        build.build()
+    return ba.load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "ba.h")).read()
+    declared = set(re.findall(r"\b(ba_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(ba.EXPORTS), declared ^ set(ba.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.ba_version() >= 100
+    assert lib.ba_status_string(0) == b"BA_OK"
+    assert lib.ba_status_string(-4) == b"BA_ERR_WORKSPACE"
+
+
+def fake(ptr=0x1000, st=1024, sh=128, dtype=0):
+    return ba.BaTensor(ptr, st, sh, dtype)
+
+
+def call_encode(lib, heads, q, k, v, o, kl, offs, rope=1, ws=None, wsb=0):
+    offs = np.asarray(offs, dtype=np.int32)
+    r = lambda t: None if t is None else ctypes.byref(t)
+    return lib.ba_encode_blocks(ctypes.byref(heads.c), r(q), r(k), r(v), r(o), r(kl), len(offs) - 1,
+                                offs.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), rope, ws, wsb, None)
+
+
+def test_encode_rejects_bad_arguments(lib):
+    h = ba.Heads(8, 2, 128)
+    t = fake()
+    assert call_encode(lib, h, None, t, t, t, None, [0, 4]) == -1
+    assert b"q" in lib.ba_last_error()
+    assert call_encode(lib, h, t, t, t, t, None, [1, 4]) == -1          # c[0] != 0
+    assert call_encode(lib, h, t, t, t, t, None, [0, 5, 4]) == -1       # decreasing
+    assert call_encode(lib, ba.Heads(8, 3, 128), t, t, t, t, None, [0, 4]) == -1   # Hq % Hkv
+    assert call_encode(lib, ba.Heads(8, 2, 96), t, t, t, t, None, [0, 4]) == -2    # head_dim
+    assert call_encode(lib, h, fake(ptr=0x1004), t, t, t, None, [0, 4]) == -3      # alignment
+    assert call_encode(lib, h, fake(st=1028), t, t, t, None, [0, 4]) == -3
+    assert call_encode(lib, h, fake(dtype=1), t, t, t, None, [0, 4]) == -2         # fp32 attention
+    assert call_encode(lib, h, t, t, t, t, None, [0, 4], rope=1, ws=None, wsb=0) == -4  # workspace
+    assert call_encode(lib, h, t, t, t, t, fake(), [0, 4], rope=0) == -1           # k_local_out without rope
+    assert call_encode(lib, ba.Heads(8, 2, 128, q_to_kv=[0, 1, 0, 1, 0, 1, 0, 1]), t, t, t, t, None, [0, 4]) == -2
+    # empty input is a legal no-op that never reaches the device
+    assert call_encode(lib, h, t, t, t, t, None, [0, 0, 0], rope=0) == 0
+    assert call_encode(lib, ba.Heads(8, 2, 128, q_to_kv=[0, 0, 0, 0, 1, 1, 1, 1]), t, t, t, t, None, [0], rope=0) == 0
+
+
+def call_reenc(lib, heads, src, dst, layers, sls, sld, so, do, ln, old=None, new=None, mode=0):
+    a = lambda x: None if x is None else np.asarray(x, dtype=np.int32)
+    so, do, ln, old, new = a(so), a(do), a(ln), a(old), a(new)
+    p = lambda x: None if x is None else x.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    return lib.ba_reencode_positions(ctypes.byref(heads.c), ctypes.byref(src), ctypes.byref(dst), layers, sls, sld,
+                                     len(ln), p(so), p(do), p(ln), p(old), p(new), mode, None)
+
+
+def test_reencode_rejects_bad_arguments(lib):
+    h = ba.Heads(8, 8, 128)
+    src, dst = fake(0x100000), fake(0x900000)
+    assert call_reenc(lib, h, src, dst, 1, 0, 0, [0], [0], [-1]) == -1
+    assert call_reenc(lib, h, src, dst, 1, 0, 0, [0], [0], [4], mode=7) == -1
+    assert call_reenc(lib, h, src, fake(0x900000, dtype=1), 1, 0, 0, [0], [0], [4]) == -2   # dtype mismatch
+    # aliasing: same buffer but moved offsets is not "exactly in place"
+    assert call_reenc(lib, h, src, src, 1, 0, 0, [0], [8], [4]) == -1
+    # partial overlap of distinct pointers
+    assert call_reenc(lib, h, src, fake(0x100000 + 2048), 1, 0, 0, [0], [0], [4]) == -1
+    # overlapping destination blocks
+    assert call_reenc(lib, h, src, dst, 1, 0, 0, [0, 4], [0, 2], [4, 4]) == -1
+    assert call_reenc(lib, h, src, dst, 2, 1028, 1024, [0], [0], [4]) == -3
+    # nothing to do
+    assert call_reenc(lib, h, src, dst, 0, 0, 0, [0], [0], [4]) == 0
+    assert call_reenc(lib, h, src, dst, 1, 0, 0, [], [], []) == 0
+
+
+def test_final_rejects_bad_arguments_and_sizes_workspace(lib):
+    h = ba.Heads(32, 8, 128, 500000.0)
+    t = fake()
+    i32 = lambda x: np.asarray(x, dtype=np.int32)
+    p = lambda x: x.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+    def call(cu_q, cu_ctx, ws=None, wsb=0, q=t):
+        cq, cc = i32(cu_q), i32(cu_ctx)
+        return lib.ba_final_block_attention(ctypes.byref(h.c), ctypes.byref(q), ctypes.byref(t), ctypes.byref(t),
+                                            ctypes.byref(t), ctypes.byref(t), ctypes.byref(t), None, len(cq) - 1,
+                                            p(cq), p(cc), None, 1, ws, wsb, None)
+
+    assert call([0, 0], [0, 10]) == -1        # empty final block
+    assert call([1, 5], [0, 10]) == -1        # cu_q[0] != 0
+    assert call([0, 5], [10, 3]) == -1        # cu_ctx decreases
+    assert call([0, 256], [0, 31744]) == -4   # workspace missing
+    need = ba.ba_final_block_attention_workspace_bytes(h, [0, 256], [0, 31744])
+    # config 5: 8 KV splits x 8192 packed rows x (128 + 2) fp32 + rotated final-block keys
+    assert need == 8 * 8192 * 128 * 4 + 8 * 8192 * 2 * 4 + 256 * 8 * 128 * 2
+    assert call([0, 256], [0, 31744], ws=ctypes.c_void_p(0x10000), wsb=need - 1) == -4
+    # zero prompts: legal no-op
+    cq = i32([0])
+    assert lib.ba_final_block_attention(ctypes.byref(h.c), None, None, None, None, None, None, None, 0, p(cq),
+                                        p(cq), None, 1, None, 0, None) == 0
+
+
+def test_workspace_queries(lib):
+    h = ba.Heads(32, 8, 128)
+    assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 400], ba.ROPE_APPLY, False) == 400 * 8 * 128 * 2
+    assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 400], ba.ROPE_APPLY, True) == 0
+    assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 400], ba.ROPE_NONE, False) == 0
+    # a single small prompt needs no split partials
+    assert ba.ba_final_block_attention_workspace_bytes(ba.Heads(4, 4, 64), [0, 64], [0, 128], ba.ROPE_NONE) == 0
