@@ -1,0 +1,270 @@
+#!/usr/bin/env python3
+"""Benchmark of the Block-attention prefill hot path on one MI355X.
+
+Headline (the metric's configuration): long-context final-block prefill, Llama-3-8B head
+shape (32 query / 8 KV heads, head_dim 128, bf16), 31 cached and re-encoded passage blocks
+of 1024 tokens plus a 256-token final block, 32 layers with distinct Q/K/V buffers.  One
+"step" is the 32-layer loop of ba_final_block_attention calls (RoPE of the final block's
+q/k, the MFMA attention core over all 32,000 keys, the split-KV merge), inputs resident in
+HBM.  value = algorithmic TFLOP/s = 4 * D * visible (query, key, head) triples / time.
+
+The same run also reports, outside the timed steps:
+  * roofline: the attention core's own average launch time from HIP events recorded by the
+    library on the launch stream (a second, event-instrumented pass over the same steps);
+  * rows: ba_reencode_positions at config 4 (GB/s against HBM), ba_encode_blocks on the
+    same 32,000 tokens as a single block (full-attention mode) and on config 3's ragged
+    blocks;
+  * cpu_baseline: the CPU oracle, as it stands, on a bounded sample of the headline
+    workload's rows.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def visible_pairs_final(t_ctx: int, l_q: int) -> int:
+    return l_q * t_ctx + l_q * (l_q + 1) // 2
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows (config 3/4, single block)")
+    ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    from paper_2409_15355_amd import binding as ba
+    from paper_2409_15355_amd import workloads as wl
+    ba.load()  # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def dev_bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    def randn_bf16(seed, shape):
+        g = torch.Generator(device=dev).manual_seed(seed)
+        return torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        return max(e0.elapsed_time(e1), 0.0) / steps, wall_ms / steps
+
+    # ------------------------------------------------------------------ headline: config 5
+    w = wl.config5(n_layers=args.layers)
+    hq, hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
+    t_ctx, l_q = w.prompts[0].t_ctx, w.prompts[0].final_len
+    cu_q, cu_ctx = w.cu_q(), w.cu_ctx()
+    heads = ba.Heads(hq, hkv, d, w.rope_base)
+    layers = []
+    host0 = None
+    for layer in range(w.n_layers):
+        if layer == 0 and not args.no_cpu_baseline:
+            # layer 0 comes from the host generator so that the oracle sees the same arrays
+            host0 = dict(kc=wl.normal_bf16_bits(wl.tensor_seed(5, 0), (t_ctx, hkv, d)),
+                         vc=wl.normal_bf16_bits(wl.tensor_seed(5, 1), (t_ctx, hkv, d)),
+                         q=wl.normal_bf16_bits(wl.tensor_seed(5, 2), (l_q, hq, d)),
+                         kf=wl.normal_bf16_bits(wl.tensor_seed(5, 3), (l_q, hkv, d)),
+                         vf=wl.normal_bf16_bits(wl.tensor_seed(5, 4), (l_q, hkv, d)))
+            t = {k: dev_bf16(v) for k, v in host0.items()}
+        else:
+            s = wl.tensor_seed(5, 100 + 10 * layer)
+            t = dict(kc=randn_bf16(s, (t_ctx, hkv, d)), vc=randn_bf16(s + 1, (t_ctx, hkv, d)),
+                     q=randn_bf16(s + 2, (l_q, hq, d)), kf=randn_bf16(s + 3, (l_q, hkv, d)),
+                     vf=randn_bf16(s + 4, (l_q, hkv, d)))
+        t["o"] = torch.empty((l_q, hq, d), dtype=torch.bfloat16, device=dev)
+        layers.append(t)
+    ws_bytes = ba.ba_final_block_attention_workspace_bytes(heads, cu_q, cu_ctx, ba.ROPE_APPLY, False)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    def step_final():
+        for t in layers:
+            ba.ba_final_block_attention(heads, t["q"], t["kc"], t["vc"], t["kf"], t["vf"], t["o"], None, cu_q, cu_ctx,
+                                        None, ba.ROPE_APPLY, ws)
+
+    if args.only == "":
+        ms_step, wall_ms_step = timed(step_final, args.steps, args.warmup)
+    else:
+        ms_step, wall_ms_step = timed(step_final, 1, 1)
+    flops_layer = 4.0 * d * hq * visible_pairs_final(t_ctx, l_q)
+    ms_layer = ms_step / w.n_layers
+    tflops = flops_layer / (ms_layer * 1e-3) / 1e12
+
+    # per-kernel times of the same steps, from the library's own events on the launch stream
+    ba.ba_profile_begin(1 << 16)
+    prof_steps = min(args.steps, 5) if args.only == "" else 1
+    for _ in range(prof_steps):
+        step_final()
+    torch.cuda.synchronize()
+    prof_ms, prof_n = ba.ba_profile_end()
+    attn_us = prof_ms[ba.PROFILE_ATTENTION] / max(prof_n[ba.PROFILE_ATTENTION], 1) * 1e3
+    achieved = flops_layer / (attn_us * 1e-6) / 1e12
+    roofline = {"bound": "mfma", "kernel": "attn_kernel<128, FinalMeta>", "achieved": round(achieved, 2),
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": None, "avg_launch_us": round(attn_us, 2),
+                "launches_timed": prof_n[ba.PROFILE_ATTENTION],
+                "other_kernels_us_per_layer": {
+                    "rope_final_block_keys": round(prof_ms[ba.PROFILE_REENCODE] / max(prof_n[ba.PROFILE_REENCODE], 1) * 1e3, 2),
+                    "split_combine": round(prof_ms[ba.PROFILE_COMBINE] / max(prof_n[ba.PROFILE_COMBINE], 1) * 1e3, 2)}}
+
+    # ------------------------------------------------------------------ cpu baseline (oracle)
+    cpu_baseline = None
+    if host0 is not None and args.only == "":
+        import oracle
+        f = oracle.bf16_bits_to_f64
+        rows = list(range(0, l_q, 2))  # every other final-block row of layer 0: 128 rows x 32 heads
+        th = oracle.theta(w.rope_base, d)
+        kc64, vc64, q64, kf64, vf64 = f(host0["kc"]), f(host0["vc"]), f(host0["q"]), f(host0["kf"]), f(host0["vf"])
+        t0 = time.perf_counter()
+        ref = oracle.final_block(q64, kc64, vc64, kf64, vf64, cu_q, cu_ctx, th, rows=rows)
+        cpu_s = time.perf_counter() - t0
+        pairs = sum(t_ctx + r + 1 for r in rows) * hq
+        got = layers[0]["o"].float().cpu().numpy().astype(np.float64)[rows]
+        err = np.abs(got - ref)
+        cpu_baseline = {"value": round(4.0 * d * pairs / cpu_s / 1e12, 6), "unit": "TFLOP/s",
+                        "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"layer 0, {len(rows)} of {l_q} final-block rows x {hq} heads over all {t_ctx + l_q} keys "
+                                  f"({cpu_s:.1f} s)",
+                        "parity_on_sample": {"max_abs": float(err.max()), "mean_abs": float(err.mean())}}
+        del kc64, vc64
+    del layers, ws
+    torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------------ secondary rows
+    rows_out = {}
+    if not args.no_rows:
+        # a-2 at config 4: 32 layers x 32 passages x 1000 tokens, permuted slots, gather form
+        if args.only in ("", "reencode"):
+            w4 = wl.config4()
+            P, L = 32, 1000
+            cache = randn_bf16(wl.tensor_seed(4, 0), (w4.n_layers, P * L, hkv, d))
+            dst = torch.empty_like(cache)
+            src_off = (np.arange(P) * L).astype(np.int32)
+            lens = np.full(P, L, dtype=np.int32)
+            new_pos0 = w4.extra["new_pos0"]
+            h4 = ba.Heads(hkv, hkv, d, w4.rope_base)
+            nbytes = 2.0 * cache.numel() * 2
+            reps = 20 if args.only == "" else 200
+
+            def gather():
+                ba.ba_reencode_positions(h4, cache, dst, src_off, new_pos0, lens, None, new_pos0, ba.REENC_SHIFT)
+
+            def inplace():
+                ba.ba_reencode_positions(h4, cache, cache, src_off, src_off, lens, None, new_pos0, ba.REENC_SHIFT)
+
+            ms_g, _ = timed(gather, reps, 3)
+            ms_i, _ = timed(inplace, reps, 3)
+            rows_out["reencode_cfg4"] = {"bytes": nbytes, "gather_ms": round(ms_g, 4),
+                                         "gather_GBps": round(nbytes / ms_g / 1e6, 1),
+                                         "inplace_ms": round(ms_i, 4), "inplace_GBps": round(nbytes / ms_i / 1e6, 1),
+                                         "frac_of_hbm_peak": round(nbytes / min(ms_g, ms_i) / 1e6 / HBM_PEAK_GBS, 4)}
+            del cache, dst
+            torch.cuda.empty_cache()
+        # a-1, full-attention mode: the same 32,000 tokens as ONE block
+        if args.only in ("", "single"):
+            T = t_ctx + l_q
+            q = randn_bf16(wl.tensor_seed(5, 20), (T, hq, d))
+            k = randn_bf16(wl.tensor_seed(5, 21), (T, hkv, d))
+            v = randn_bf16(wl.tensor_seed(5, 22), (T, hkv, d))
+            o = torch.empty_like(q)
+            kl = torch.empty_like(k)
+            offs = np.array([0, T], dtype=np.int32)
+
+            def single():
+                ba.ba_encode_blocks(heads, q, k, v, o, kl, offs, ba.ROPE_APPLY, None)
+
+            ms_s, _ = timed(single, 3 if args.only == "" else 10, 1)
+            fl = 4.0 * d * hq * (T * (T + 1) // 2)
+            rows_out["encode_single_block_32k"] = {"ms_per_layer": round(ms_s, 3), "TFLOPs": round(fl / ms_s / 1e9, 1),
+                                                   "frac_of_mfma_peak": round(fl / ms_s / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}
+            del q, k, v, o, kl
+            torch.cuda.empty_cache()
+        # a-1 on config 3's 160 ragged passage blocks
+        if args.only in ("", "encode3"):
+            w3 = wl.config3()
+            offs3 = w3.passage_block_offsets()
+            T3 = int(offs3[-1])
+            q = randn_bf16(wl.tensor_seed(3, 0), (T3, hq, d))
+            k = randn_bf16(wl.tensor_seed(3, 1), (T3, hkv, d))
+            v = randn_bf16(wl.tensor_seed(3, 2), (T3, hkv, d))
+            o = torch.empty_like(q)
+            kl = torch.empty_like(k)
+            h3 = ba.Heads(hq, hkv, d, w3.rope_base)
+
+            def enc3():
+                ba.ba_encode_blocks(h3, q, k, v, o, kl, offs3, ba.ROPE_APPLY, None)
+
+            ms_e, _ = timed(enc3, 20 if args.only == "" else 200, 3)
+            lens3 = np.diff(offs3).astype(np.int64)
+            fl = 4.0 * d * hq * float((lens3 * (lens3 + 1) // 2).sum())
+            byts = 2.0 * T3 * d * (2 * hq + 4 * hkv)  # q, o, k, k_local(w), k_local(r), v
+            rows_out["encode_cfg3_ragged"] = {"ms": round(ms_e, 4), "algorithmic_TFLOPs": round(fl / ms_e / 1e9, 1),
+                                              "GBps": round(byts / ms_e / 1e6, 1), "tokens": T3}
+
+    out = {
+        "metric": "final-block prefill TFLOP/s at 32K ctx (ms/layer alongside)",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "ms_per_layer": round(ms_layer, 5),
+        "host_wall_ms_per_step": round(wall_ms_step, 4),
+        "frac_of_bf16_mfma_peak": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "layers": w.n_layers, "context_blocks": 31, "block_len": 1024,
+                   "final_len": l_q, "total_tokens": t_ctx + l_q, "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": d,
+                   "rope": "applied to q_f/k_f inside the call", "flops_per_layer": flops_layer},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "rows": rows_out,
+        "paper_context": {"ttft_block_32k_ms": 45, "ttft_vanilla_32k_ms": 3638, "hardware": "NVIDIA H20 (count unstated), bf16",
+                          "note": "whole-model TTFT with a 50-token query; context only"},
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -84,6 +84,22 @@ const char *ba_status_string(int32_t status);
 const char *ba_last_error(void);
 
 /*
+ * Per-kernel timing for benchmarks.  Between ba_profile_begin() and ba_profile_end() every
+ * kernel launch the library makes is bracketed by two HIP events recorded on the launch
+ * stream (at most max_records launches per class; later ones go untimed).
+ * ba_profile_end() waits for the recorded events, writes per class the summed kernel time
+ * in milliseconds and the number of timed launches (arrays of BA_PROFILE_CLASSES entries,
+ * either may be null), frees the events and turns profiling off.  The events cost a few
+ * microseconds per launch, so do not quote throughput from a profiled region.
+ */
+#define BA_PROFILE_ATTENTION 0 /* the MFMA attention core (encode and final block) */
+#define BA_PROFILE_REENCODE 1  /* the RoPE rotation pass                            */
+#define BA_PROFILE_COMBINE 2   /* the split-KV merge                                */
+#define BA_PROFILE_CLASSES 3
+int32_t ba_profile_begin(int32_t max_records);
+int32_t ba_profile_end(double *ms_sum, int32_t *launches);
+
+/*
  * Step 1 -- independent per-block causal attention (Section 1, step 1; Section 2.1).
  *
  * Token t of block b attends to tokens [c[b], t] of its own block only:

@@ -22,7 +22,8 @@ ROPE_INTERLEAVED, ROPE_HALF = 0, 1
 ROPE_NONE, ROPE_APPLY = 0, 1
 REENC_SHIFT, REENC_ABSOLUTE = 0, 1
 
-EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_encode_blocks",
+EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin", "ba_profile_end",
+           "ba_encode_blocks",
            "ba_encode_blocks_workspace_bytes", "ba_reencode_positions",
            "ba_final_block_attention", "ba_final_block_attention_workspace_bytes"]
 
@@ -56,6 +57,9 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime; the process must use exactly one, and the device
+    # memory handed to this library is torch's, so torch's runtime has to be loaded first.
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2409_15355_amd.build`")
     lib = ctypes.CDLL(LIB_PATH)
@@ -63,6 +67,10 @@ def load():
     lib.ba_status_string.restype = ctypes.c_char_p
     lib.ba_status_string.argtypes = [ctypes.c_int32]
     lib.ba_last_error.restype = ctypes.c_char_p
+    lib.ba_profile_begin.restype = ctypes.c_int32
+    lib.ba_profile_begin.argtypes = [ctypes.c_int32]
+    lib.ba_profile_end.restype = ctypes.c_int32
+    lib.ba_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), _I32P]
     lib.ba_encode_blocks.restype = ctypes.c_int32
     lib.ba_encode_blocks.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, ctypes.c_int32, _I32P, ctypes.c_int32,
                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
@@ -145,6 +153,21 @@ def _ws(ws):
 
 def ba_version() -> int:
     return int(load().ba_version())
+
+
+PROFILE_ATTENTION, PROFILE_REENCODE, PROFILE_COMBINE, PROFILE_CLASSES = 0, 1, 2, 3
+
+
+def ba_profile_begin(max_records: int = 65536) -> None:
+    _check(load().ba_profile_begin(max_records))
+
+
+def ba_profile_end():
+    """Returns (ms_sum[3], launches[3]) indexed by PROFILE_*."""
+    ms = (ctypes.c_double * PROFILE_CLASSES)()
+    n = (ctypes.c_int32 * PROFILE_CLASSES)()
+    _check(load().ba_profile_end(ms, n))
+    return list(ms), list(n)
 
 
 def ba_encode_blocks_workspace_bytes(heads: Heads, block_offsets, rope_mode: int = ROPE_APPLY,

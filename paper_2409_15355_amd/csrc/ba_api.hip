@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "../../include/ba.h"
@@ -27,6 +28,40 @@ int32_t fail(int32_t status, const char *fmt, ...) {
 int32_t device_fail(hipError_t e, const char *what) {
   return fail(BA_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
 }
+
+// ---- optional per-kernel timing (ba_profile_begin / ba_profile_end) ------------------------
+struct Profiler {
+  std::mutex mu;
+  bool on = false;
+  int max_records = 0;
+  std::vector<hipEvent_t> start[BA_PROFILE_CLASSES], stop[BA_PROFILE_CLASSES];
+} g_prof;
+
+// Brackets one kernel launch with two events on its stream while profiling is on.
+struct ProfileScope {
+  hipStream_t stream;
+  int cls;
+  bool active = false;
+  ProfileScope(int cls_, hipStream_t s) : stream(s), cls(cls_) {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (!g_prof.on || (int)g_prof.start[cls].size() >= g_prof.max_records) return;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return;
+    if (hipEventCreate(&e1) != hipSuccess) {
+      (void)hipEventDestroy(e0);
+      return;
+    }
+    g_prof.start[cls].push_back(e0);
+    g_prof.stop[cls].push_back(e1);
+    (void)hipEventRecord(e0, stream);
+    active = true;
+  }
+  ~ProfileScope() {
+    if (!active) return;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    (void)hipEventRecord(g_prof.stop[cls].back(), stream);
+  }
+};
 
 size_t elt_size(int32_t dtype) { return dtype == BA_DTYPE_F32 ? 4 : 2; }
 
@@ -170,7 +205,11 @@ int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, c
     if (!filled) continue;
     blk.n = filled;
     p.max_len = max_len;
-    hipError_t e = ba::launch_reencode(p, blk, rt, stream);
+    hipError_t e;
+    {
+      ProfileScope ps(BA_PROFILE_REENCODE, stream);
+      e = ba::launch_reencode(p, blk, rt, stream);
+    }
     if (e != hipSuccess) return device_fail(e, "re-encode launch");
   }
   return BA_OK;
@@ -195,6 +234,44 @@ const char *ba_status_string(int32_t status) {
 }
 
 const char *ba_last_error(void) { return g_err; }
+
+int32_t ba_profile_begin(int32_t max_records) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  if (g_prof.on) return fail(BA_ERR_INVALID_ARG, "profiling is already on");
+  if (max_records < 1 || max_records > (1 << 20)) return fail(BA_ERR_INVALID_ARG, "max_records out of range");
+  g_prof.on = true;
+  g_prof.max_records = max_records;
+  return BA_OK;
+}
+
+int32_t ba_profile_end(double *ms_sum, int32_t *launches) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  if (!g_prof.on) return fail(BA_ERR_INVALID_ARG, "profiling is not on");
+  g_prof.on = false;
+  int32_t rc = BA_OK;
+  for (int c = 0; c < BA_PROFILE_CLASSES; ++c) {
+    double sum = 0.0;
+    int32_t n = 0;
+    for (size_t i = 0; i < g_prof.start[c].size(); ++i) {
+      float ms = 0.f;
+      hipError_t e = hipEventSynchronize(g_prof.stop[c][i]);
+      if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.start[c][i], g_prof.stop[c][i]);
+      if (e == hipSuccess) {
+        sum += ms;
+        ++n;
+      } else {
+        rc = device_fail(e, "profile event");
+      }
+      (void)hipEventDestroy(g_prof.start[c][i]);
+      (void)hipEventDestroy(g_prof.stop[c][i]);
+    }
+    g_prof.start[c].clear();
+    g_prof.stop[c].clear();
+    if (ms_sum) ms_sum[c] = sum;
+    if (launches) launches[c] = n;
+  }
+  return rc;
+}
 
 // ------------------------------------------------------------------------------------------
 size_t ba_encode_blocks_workspace_bytes(const ba_heads *heads, int32_t n_blocks,
@@ -314,7 +391,11 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
     meta.tile_start[n] = (int32_t)tiles;
     ap.total_tiles = (int32_t)tiles;
     if (tiles == 0) continue;
-    hipError_t e = ba::launch_attn_encode(ap, meta, rt, stream);
+    hipError_t e;
+    {
+      ProfileScope ps(BA_PROFILE_ATTENTION, stream);
+      e = ba::launch_attn_encode(ap, meta, rt, stream);
+    }
     if (e != hipSuccess) return device_fail(e, "encode attention launch");
   }
   return BA_OK;
@@ -543,11 +624,19 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
     meta.cu_ctx[n] = cu_ctx[n0 + n];
     meta.tile_start[n] = (int32_t)tiles;
     ap.total_tiles = (int32_t)tiles;
-    hipError_t e = ba::launch_attn_final(ap, meta, rt, stream);
+    hipError_t e;
+    {
+      ProfileScope ps(BA_PROFILE_ATTENTION, stream);
+      e = ba::launch_attn_final(ap, meta, rt, stream);
+    }
     if (e != hipSuccess) return device_fail(e, "final-block attention launch");
   }
   if (pl.n_splits > 1) {
-    hipError_t e = ba::launch_combine(ap, pl.lq_total, stream);
+    hipError_t e;
+    {
+      ProfileScope ps(BA_PROFILE_COMBINE, stream);
+      e = ba::launch_combine(ap, pl.lq_total, stream);
+    }
     if (e != hipSuccess) return device_fail(e, "split combine launch");
   }
   return BA_OK;
