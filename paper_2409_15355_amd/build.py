@@ -13,6 +13,9 @@ LIB = os.path.join(HERE, "libba_hip.so")
 SOURCES = ["ba_api.hip", "reencode.hip", "attention.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA results the softmax reads go to ordinary VGPRs; the allocator moves the
+         # long-lived accumulators to AccVGPRs by itself.  Without this the attention core spills.
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wno-unused-command-line-argument"]
 
 

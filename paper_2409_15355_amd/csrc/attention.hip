@@ -9,20 +9,24 @@
 // masked tiles of the block-diagonal mask are never issued.
 //
 // Mapping onto the hardware
-//   - A workgroup (4 wavefronts) owns 256 packed query rows of one KV head.  Row
-//     r = token * G + head_in_group packs the G query heads of a GQA group next to each
-//     other, so one K/V tile streamed through LDS serves all of them.
+//   - A workgroup (4 wavefronts, one per SIMD) owns 256 packed query rows of one KV head.
+//     Row r = token * G + head_in_group packs the G query heads of a GQA group next to
+//     each other, so one K/V tile streamed through LDS serves all of them.
+//   - K/V tiles (64 keys) go from HBM straight into LDS with LDS-direct loads
+//     (global_load_lds_dwordx4), double buffered, one barrier per tile.
 //   - Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: keys
 //     run along accumulator registers and queries along lanes, so the softmax max/sum
 //     reduce in registers plus a single half-wave exchange, and the exponentials are
 //     already in the B-operand layout of the second contraction O^T = V^T P^T.
 //   - V^T fragments come straight out of the row-major V tile with the LDS transpose
 //     read (ds_read_b64_tr_b16); K fragments with 16-byte reads.  Both tiles use an XOR
-//     swizzle so that neither the 16-byte writes nor the fragment reads conflict.
-//   - Softmax runs in fp32 in the log2 domain; P is rounded to bf16 for the second
-//     MFMA; the output is rounded once.
+//     swizzle so that neither the tile fill nor the fragment reads conflict.
+//   - Softmax runs in fp32 in the log2 domain against a lazily raised reference; P is
+//     rounded to bf16 for the second MFMA; the output is rounded once.
 //   - The KV range can be cut into n_splits pieces; each piece writes un-normalised
-//     fp32 partials (max, sum, O) that combine_kernel merges in a fixed order.
+//     fp32 partials (reference, sum, O) that combine_kernel merges in a fixed order.
+#include <type_traits>
+
 #include "ba_device.h"
 
 namespace ba {
@@ -31,6 +35,8 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kRowsPerWave = kTileRows / kWaves;  // 64 = two 32-query MFMA column groups
+constexpr float kLazyLog2 = 8.0f;                 // exponentials may reach 2^8 before the reference moves
+constexpr int kXcds = 8;                          // MI355X: workgroup ids go round-robin over 8 XCDs
 
 template <int D>
 struct Geo {
@@ -40,21 +46,10 @@ struct Geo {
   static constexpr int ROWB = D * 2;          // bytes per K/V row in LDS
   static constexpr int LPR = 256 / ROWB;      // rows per 256-byte LDS line (1 or 2)
   static constexpr int GPR = ROWB / 64;       // 64-byte granules per row
-  static constexpr int RPP = kThreads / CPR;  // rows loaded per pass
-  static constexpr int NP = kTileKeys / RPP;  // passes per tile
   static constexpr int TILEB = kTileKeys * ROWB;
+  static constexpr int RPI = 1024 / ROWB;     // rows filled by one LDS-direct wave instruction
+  static constexpr int IPW = kTileKeys / RPI / kWaves;  // such instructions per wave per tile
 };
-
-template <int D>
-__device__ __forceinline__ int k_lds_off(int row, int chunk) {
-  using G = Geo<D>;
-  return row * G::ROWB + ((chunk ^ ((row / G::LPR) & (G::CPR - 1))) << 4);
-}
-template <int D>
-__device__ __forceinline__ int v_lds_off(int row, int granule, int within) {
-  using G = Geo<D>;
-  return row * G::ROWB + ((granule ^ ((row / G::LPR) & (G::GPR - 1))) << 6) + within;
-}
 
 struct Problem {
   int q_tok0;   // first query token (row of q / o / kf / vf)
@@ -104,53 +99,33 @@ __device__ __forceinline__ float other_half(float x) {
   return (threadIdx.x & 32) ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
 }
 
-// Stage one K/V tile (64 rows) from global memory into registers.  Rows at or beyond
-// `valid` read as zero so that masked keys give finite scores and 0 * v stays 0.
-template <int D>
-__device__ __forceinline__ void load_tile(u32x4_t (&reg)[Geo<D>::NP], const uint16_t *base,
-                                          int64_t stride_tok, int valid) {
-  using G = Geo<D>;
-  const int chunk = threadIdx.x % G::CPR;
-  const int row0 = threadIdx.x / G::CPR;
-#pragma unroll
-  for (int i = 0; i < G::NP; ++i) {
-    int row = row0 + i * G::RPP;
-    u32x4_t z = {0u, 0u, 0u, 0u};
-    reg[i] = (row < valid)
-                 ? *reinterpret_cast<const u32x4_t *>(base + (int64_t)row * stride_tok + chunk * 8)
-                 : z;
-  }
-}
-template <int D, bool IS_V>
-__device__ __forceinline__ void store_tile(const u32x4_t (&reg)[Geo<D>::NP], char *lds) {
-  using G = Geo<D>;
-  const int chunk = threadIdx.x % G::CPR;
-  const int row0 = threadIdx.x / G::CPR;
-#pragma unroll
-  for (int i = 0; i < G::NP; ++i) {
-    int row = row0 + i * G::RPP;
-    int off = IS_V ? v_lds_off<D>(row, chunk >> 2, (chunk & 3) << 4) : k_lds_off<D>(row, chunk);
-    *reinterpret_cast<u32x4_t *>(lds + off) = reg[i];
-  }
-}
+typedef __attribute__((address_space(3))) char lds_char;
 
 template <int D, typename Meta>
 __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta, RopeTable rt) {
   using G = Geo<D>;
-  extern __shared__ __attribute__((aligned(256))) char smem[];
-  auto ks = [&](int buf) -> char * { return smem + buf * G::TILEB; };
-  auto vs = [&](int buf) -> char * { return smem + (2 + buf) * G::TILEB; };
+  constexpr bool kFinal = std::is_same<Meta, FinalMeta>::value;
+  extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+  lds_char *smem = (lds_char *)smem_generic;
+  // LDS map: K buffers at 0 and TILEB, V buffers at 2*TILEB and 3*TILEB.
 
-  // ---- which work item -------------------------------------------------------------
+  // ---- which work item -------------------------------------------------------------------
   int id = blockIdx.x;
-  const int rowtile = id % p.total_tiles;
+  if (kFinal) {
+    // Consecutive work items share K/V tiles (same KV head and split, different row tile);
+    // the dispatcher deals workgroup ids round-robin to the XCDs, so regroup ids such that
+    // each XCD (and its L2) gets a contiguous run of work items.
+    const int n_wg = gridDim.x, q = n_wg / kXcds, r = n_wg % kXcds, x = id % kXcds;
+    id = x * q + min(x, r) + id / kXcds;
+  }
+  const int rowtile = kFinal ? id % p.total_tiles : p.total_tiles - 1 - id % p.total_tiles;
   id /= p.total_tiles;
   const int kvh = id % p.n_kv_heads;
   const int split = id / p.n_kv_heads;
   const Problem pr = locate(meta, rowtile);
 
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, lives in an SGPR
   const int col = lane & 31;  // query column inside a 32-wide MFMA group
   const int hf = lane >> 5;   // which half of the wave
   const int Gq = p.group;
@@ -168,9 +143,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
 
   // ---- Q fragments (B operand of S^T = K Q^T), rotated in registers if asked -------------
   bf16x8_t qf[2][G::KCH];
-  int tok[2];       // query token (inside the problem) of this lane's two columns
+  int tok[2];        // query token (inside the problem) of this lane's two columns
   bool row_ok[2];
-  int64_t o_off[2];  // element offset of the output row
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     const int r = row0 + wave * kRowsPerWave + b * 32 + col;
@@ -179,7 +153,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
     const int g = r - i * Gq;
     tok[b] = i;
     const int head = kvh * Gq + g;
-    o_off[b] = (int64_t)(pr.q_tok0 + i) * p.o_st + (int64_t)head * p.o_sh;
     const uint16_t *qp = p.q + (int64_t)(pr.q_tok0 + i) * p.q_st + (int64_t)head * p.q_sh + hf * 8;
     u32x4_t raw[G::KCH];
 #pragma unroll
@@ -221,6 +194,34 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
     for (int kk = 0; kk < G::KCH; ++kk) qf[b][kk] = __builtin_bit_cast(bf16x8_t, raw[kk]);
   }
 
+  // ---- per-lane LDS read offsets; everything else about an address is a compile-time
+  //      constant that folds into the instruction's offset field ---------------------------------
+  uint32_t k_rd[G::KCH];  // K fragment (a = 0, buffer 0): row `col`, chunk 2 kk + hf, swizzled
+  {
+    const int swz = (col / G::LPR) & (G::CPR - 1);
+#pragma unroll
+    for (int kk = 0; kk < G::KCH; ++kk) k_rd[kk] = col * G::ROWB + (((kk * 2 + hf) ^ swz) << 4);
+  }
+  uint32_t v_rd[G::DT];  // V^T fragment (kc = 0, low half, buffer 0)
+  {
+    const int vrow = hf * 4 + ((lane & 15) >> 2);
+    const int vwithin = ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+    const int swz = (vrow / G::LPR) & (G::GPR - 1);
+#pragma unroll
+    for (int dt = 0; dt < G::DT; ++dt) v_rd[dt] = 2 * G::TILEB + vrow * G::ROWB + ((dt ^ swz) << 6) + vwithin;
+  }
+  // ---- per-lane pieces of the tile fill: row and (swizzled) source chunk of each LDS-direct load
+  int g_row[G::IPW];
+  uint32_t g_kchunk[G::IPW], g_vchunk[G::IPW];  // byte offset of the source chunk inside its row
+#pragma unroll
+  for (int i = 0; i < G::IPW; ++i) {
+    const int row = (wave * G::IPW + i) * G::RPI + lane / G::CPR;
+    const int pos = lane % G::CPR;
+    g_row[i] = row;
+    g_kchunk[i] = (uint32_t)(pos ^ ((row / G::LPR) & (G::CPR - 1))) << 4;
+    g_vchunk[i] = (uint32_t)((((pos >> 2) ^ ((row / G::LPR) & (G::GPR - 1))) << 2) | (pos & 3)) << 4;
+  }
+
   // ---- running softmax state and O^T accumulators ------------------------------------------
   f32x16_t oacc[G::DT][2];
 #pragma unroll
@@ -229,73 +230,74 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) oacc[dt][b][v] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY};  // running max, raw score units
+  // Online softmax with a LAZY reference: exponentials are taken relative to m_ref, which
+  // is raised only when a tile's maximum exceeds it by more than kLazyLog2 powers of two.
+  // Any reference gives the same quotient sum(p v) / sum(p); keeping it fixed avoids
+  // rescaling the O^T accumulators on almost every tile.
+  float m_ref[2] = {-INFINITY, -INFINITY};  // reference, raw score units
+  float mb[2] = {0.f, 0.f};                 // m_ref * scale_log2e (0 while nothing was seen)
   float l_run[2] = {0.f, 0.f};              // this lane's share of the running sum
   const float c2 = p.scale_log2e;
+  const float tau = kLazyLog2 / c2;
+  const int first_tok_wave = (row0 + wave * kRowsPerWave) / Gq;
 
-  // tile geometry helper
-  auto tile_ptrs = [&](int t, const uint16_t *&kp, const uint16_t *&vp, int64_t &kst, int64_t &vst,
-                       int &valid, int &key0, bool &causal) {
+  // Tile t: base pointers (wave-uniform), row stride in bytes, valid rows, first key, causal?
+  struct Tile {
+    const char *kp, *vp;
+    uint32_t kst, vst;
+    int valid, key0;
+    bool causal;
+  };
+  auto tile_of = [&](int t) {
+    Tile tl;
     if (t < n_ctx_tiles) {
       const int64_t r0 = (int64_t)pr.ctx0 + (int64_t)t * kTileKeys;
-      kp = p.kc + r0 * p.kc_st + (int64_t)kvh * p.kc_sh;
-      vp = p.vc + r0 * p.vc_st + (int64_t)kvh * p.vc_sh;
-      kst = p.kc_st;
-      vst = p.vc_st;
-      valid = min(kTileKeys, pr.tctx - t * kTileKeys);
-      key0 = 0;
-      causal = false;
+      tl.kp = (const char *)(p.kc + r0 * p.kc_st + (int64_t)kvh * p.kc_sh);
+      tl.vp = (const char *)(p.vc + r0 * p.vc_st + (int64_t)kvh * p.vc_sh);
+      tl.kst = (uint32_t)p.kc_st * 2u;
+      tl.vst = (uint32_t)p.vc_st * 2u;
+      tl.valid = min(kTileKeys, pr.tctx - t * kTileKeys);
+      tl.key0 = 0;
+      tl.causal = false;
     } else {
       const int tc = t - n_ctx_tiles;
       const int64_t r0 = (int64_t)pr.q_tok0 + (int64_t)tc * kTileKeys;
-      kp = p.kf + r0 * p.kf_st + (int64_t)kvh * p.kf_sh;
-      vp = p.vf + r0 * p.vf_st + (int64_t)kvh * p.vf_sh;
-      kst = p.kf_st;
-      vst = p.vf_st;
-      valid = min(kTileKeys, pr.lq - tc * kTileKeys);
-      key0 = tc * kTileKeys;
-      causal = true;
+      tl.kp = (const char *)(p.kf + r0 * p.kf_st + (int64_t)kvh * p.kf_sh);
+      tl.vp = (const char *)(p.vf + r0 * p.vf_st + (int64_t)kvh * p.vf_sh);
+      tl.kst = (uint32_t)p.kf_st * 2u;
+      tl.vst = (uint32_t)p.vf_st * 2u;
+      tl.valid = min(kTileKeys, pr.lq - tc * kTileKeys);
+      tl.key0 = tc * kTileKeys;
+      tl.causal = true;
+    }
+    return tl;
+  };
+  // Copy tile t into LDS buffer `buf` with LDS-direct loads: one wave instruction fills
+  // 1024 contiguous LDS bytes, lane i writing bytes [16 i, 16 i + 16); the swizzle is applied
+  // on the GLOBAL side (each lane fetches the chunk that belongs at its LDS position).  Rows
+  // at or beyond `valid` re-read the last valid row: their scores are masked, and a finite
+  // duplicate keeps 0 * v equal to 0.
+  auto issue_tile = [&](const Tile &tl, int buf) {
+#pragma unroll
+    for (int i = 0; i < G::IPW; ++i) {
+      const uint32_t row = (uint32_t)min(g_row[i], tl.valid - 1);
+      const int slot = wave * G::IPW + i;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void *)(tl.kp + (row * tl.kst + g_kchunk[i])),
+          (__attribute__((address_space(3))) void *)(smem + buf * G::TILEB + slot * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void *)(tl.vp + (row * tl.vst + g_vchunk[i])),
+          (__attribute__((address_space(3))) void *)(smem + (2 + buf) * G::TILEB + slot * 1024), 16, 0, 0);
     }
   };
 
-  u32x4_t kreg[G::NP], vreg[G::NP];
-  if (t_begin < t_end) {
-    const uint16_t *kp, *vp;
-    int64_t kst, vst;
-    int valid, key0;
-    bool causal;
-    tile_ptrs(t_begin, kp, vp, kst, vst, valid, key0, causal);
-    load_tile<D>(kreg, kp, kst, valid);
-    load_tile<D>(vreg, vp, vst, valid);
-    store_tile<D, false>(kreg, ks(0));
-    store_tile<D, true>(vreg, vs(0));
-  }
-  __syncthreads();
+  auto tile_body = [&](auto buf_c, int t) {
+    constexpr int BUF = decltype(buf_c)::value;
+    const Tile tl = tile_of(t);
+    // start the next tile's copy into the other buffer; it lands while this tile is consumed
+    if (t + 1 < t_end) issue_tile(tile_of(t + 1), BUF ^ 1);
 
-  const int first_tok_wave = (row0 + wave * kRowsPerWave) / Gq;
-
-#pragma unroll 1
-  for (int t = t_begin; t < t_end; ++t) {
-    const int cur = (t - t_begin) & 1;
-    const uint16_t *kp, *vp;
-    int64_t kst, vst;
-    int valid, key0;
-    bool causal;
-    tile_ptrs(t, kp, vp, kst, vst, valid, key0, causal);
-
-    // prefetch the next tile into registers while this one is consumed from LDS
-    const bool have_next = t + 1 < t_end;
-    if (have_next) {
-      const uint16_t *nkp, *nvp;
-      int64_t nkst, nvst;
-      int nvalid, nkey0;
-      bool ncausal;
-      tile_ptrs(t + 1, nkp, nvp, nkst, nvst, nvalid, nkey0, ncausal);
-      load_tile<D>(kreg, nkp, nkst, nvalid);
-      load_tile<D>(vreg, nvp, nvst, nvalid);
-    }
-
-    // ---- S^T = K Q^T : sacc[a][b] is keys 32a..32a+31 x queries 32b..32b+31 --------------
+    // ---- S^T = K Q^T : sacc[a][b] is keys 32a..32a+31 x queries 32b..32b+31 ----------------
     f32x16_t sacc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -303,26 +305,25 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
       for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int v = 0; v < 16; ++v) sacc[a][b][v] = 0.f;
-    const char *kl = ks(cur);
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
 #pragma unroll
       for (int kk = 0; kk < G::KCH; ++kk) {
-        const int key = a * 32 + col;
-        bf16x8_t kfrag = *reinterpret_cast<const bf16x8_t *>(kl + k_lds_off<D>(key, kk * 2 + hf));
+        const bf16x8_t kfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(
+            smem + k_rd[kk] + (BUF * G::TILEB + a * 32 * G::ROWB));
         sacc[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[0][kk], sacc[a][0], 0, 0, 0);
         sacc[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[1][kk], sacc[a][1], 0, 0, 0);
       }
     }
 
-    // ---- mask (only tiles that need it), online softmax --------------------------------------
-    const bool need_mask = causal ? (key0 + kTileKeys - 1 > first_tok_wave) || (valid < kTileKeys)
-                                  : (valid < kTileKeys);
-    bf16x8_t pf[2][4];  // P^T fragments: [query group][16-key step]
+    // ---- mask (diagonal and ragged tiles only; wave-uniform branch) -----------------------------
+    const bool need_mask = tl.causal ? (tl.key0 + kTileKeys - 1 > first_tok_wave) || (tl.valid < kTileKeys)
+                                     : (tl.valid < kTileKeys);
+    if (need_mask) {
+      asm volatile("" ::: "memory");  // keep this a real branch: never speculate the selects
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      if (need_mask) {
-        int lim = causal ? min(tok[b] - key0 + 1, valid) : valid;  // visible keys in this tile
+      for (int b = 0; b < 2; ++b) {
+        const int lim = tl.causal ? min(tok[b] - tl.key0 + 1, tl.valid) : tl.valid;  // visible keys here
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -331,24 +332,44 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
             if (key >= lim) sacc[a][b][v] = -INFINITY;
           }
       }
-      float mx = sacc[0][b][0];
+    }
+    // ---- online softmax, lazy reference ---------------------------------------------------------------
+    float mx[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      float m0 = sacc[0][b][0];
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[a][b][v]);
-      mx = fmaxf(mx, other_half(mx));
-      const float m_new = fmaxf(m_run[b], mx);
-      const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f((m_run[b] - m_safe) * c2);
-      const float mb = m_safe * c2;
-      m_run[b] = m_new;
+        for (int v = 0; v < 16; ++v) m0 = fmaxf(m0, sacc[a][b][v]);
+      mx[b] = fmaxf(m0, other_half(m0));
+    }
+    const bool raise0 = mx[0] > m_ref[0] + tau, raise1 = mx[1] > m_ref[1] + tau;
+    if (__builtin_amdgcn_ballot_w64(raise0 || raise1) != 0) {  // rare after the first tile
+      asm volatile("" ::: "memory");  // a real branch, so the accumulators are left alone otherwise
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const float m_new = (b == 0 ? raise0 : raise1) ? mx[b] : m_ref[b];
+        const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref[b] - m_new) * c2);
+        m_ref[b] = m_new;
+        mb[b] = (m_new == -INFINITY) ? 0.f : m_new * c2;
+        l_run[b] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < G::DT; ++dt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[dt][b][v] *= alpha;
+      }
+    }
+    bf16x8_t pf[2][4];  // P^T fragments: [query group][16-key step]
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
       float sum = 0.f;
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
         float pv[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          pv[v] = __builtin_amdgcn_exp2f(sacc[a][b][v] * c2 - mb);
+          pv[v] = __builtin_amdgcn_exp2f(sacc[a][b][v] * c2 - mb[b]);
           sum += pv[v];
         }
 #pragma unroll
@@ -359,80 +380,101 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
           pf[b][a * 2 + e] = __builtin_bit_cast(bf16x8_t, w);
         }
       }
-      l_run[b] = l_run[b] * alpha + sum;
-#pragma unroll
-      for (int dt = 0; dt < G::DT; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[dt][b][v] *= alpha;
+      l_run[b] += sum;
     }
 
     // ---- O^T += V^T P^T ---------------------------------------------------------------------------
-    const char *vl = vs(cur);
-    const int vrow = hf * 4 + ((lane & 15) >> 2);
-    const int vwithin = ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc) {
 #pragma unroll
       for (int dt = 0; dt < G::DT; ++dt) {
-        const int r_lo = kc * 16 + vrow;
-        const int r_hi = r_lo + 8;
-        s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (s16x4_t __attribute__((address_space(3))) *)(vl + v_lds_off<D>(r_lo, dt, vwithin)));
-        s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (s16x4_t __attribute__((address_space(3))) *)(vl + v_lds_off<D>(r_hi, dt, vwithin)));
+        typedef __attribute__((address_space(3))) s16x4_t lds_s16x4;
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4 *)(smem + v_rd[dt] + (BUF * G::TILEB + kc * 16 * G::ROWB)));
+        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4 *)(smem + v_rd[dt] + (BUF * G::TILEB + (kc * 16 + 8) * G::ROWB)));
         typedef short s16x8_t __attribute__((ext_vector_type(8)));
-        s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        bf16x8_t vfrag = __builtin_bit_cast(bf16x8_t, both);
+        const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8_t vfrag = __builtin_bit_cast(bf16x8_t, both);
         oacc[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pf[0][kc], oacc[dt][0], 0, 0, 0);
         oacc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pf[1][kc], oacc[dt][1], 0, 0, 0);
       }
     }
+    __syncthreads();  // the next tile has landed (the barrier waits on the copy) and this one is free
+  };
 
-    // ---- hand the prefetched tile to the other LDS buffer ------------------------------------------
-    if (have_next) {
-      store_tile<D, false>(kreg, ks(cur ^ 1));
-      store_tile<D, true>(vreg, vs(cur ^ 1));
+  if (t_begin < t_end) issue_tile(tile_of(t_begin), 0);
+  __syncthreads();
+  {
+    int t = t_begin;
+#pragma unroll 1
+    for (; t + 1 < t_end; t += 2) {
+      tile_body(std::integral_constant<int, 0>{}, t);
+      tile_body(std::integral_constant<int, 1>{}, t + 1);
     }
-    __syncthreads();
+    if (t < t_end) tile_body(std::integral_constant<int, 0>{}, t);
   }
 
-  // ---- epilogue ------------------------------------------------------------------------------------
+  // ---- epilogue: each wave transposes its O^T through its own 16 KB of LDS so that rows leave
+  //      as whole contiguous lines (all waves are past the loop's last barrier) ---------------------
+  lds_char *stage = smem + wave * (32 * D * 4);  // 32 rows x D floats
+  float inv[2], l_tot[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
-    const float l_tot = l_run[b] + other_half(l_run[b]);
-    if (!row_ok[b]) continue;
-    if (p.n_splits == 1) {
-      const float inv = 1.0f / l_tot;
-      uint16_t *op = p.o + o_off[b];
+    l_tot[b] = l_run[b] + other_half(l_run[b]);
+    inv[b] = (p.n_splits == 1) ? 1.0f / l_tot[b] : 1.0f;
+  }
 #pragma unroll
-      for (int dt = 0; dt < G::DT; ++dt)
+  for (int b = 0; b < 2; ++b) {
+    // write: lane (col, hf) owns query row `col`; 16-byte chunk index XOR row keeps banks apart
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int d = dt * 32 + q4 * 8 + hf * 4;
-          uint2 w;
-          w.x = pack_bf16(oacc[dt][b][q4 * 4 + 0] * inv, oacc[dt][b][q4 * 4 + 1] * inv);
-          w.y = pack_bf16(oacc[dt][b][q4 * 4 + 2] * inv, oacc[dt][b][q4 * 4 + 3] * inv);
-          *reinterpret_cast<uint2 *>(op + d) = w;
+    for (int dt = 0; dt < G::DT; ++dt)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int chunk = dt * 8 + q4 * 2 + hf;  // (32 dt + 8 q4 + 4 hf) / 4
+        f32x4_t w = {oacc[dt][b][q4 * 4 + 0] * inv[b], oacc[dt][b][q4 * 4 + 1] * inv[b],
+                     oacc[dt][b][q4 * 4 + 2] * inv[b], oacc[dt][b][q4 * 4 + 3] * inv[b]};
+        *reinterpret_cast<__attribute__((address_space(3))) f32x4_t *>(
+            stage + col * (D * 4) + ((chunk ^ (col & (D / 4 - 1))) << 4)) = w;
+      }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // read back row-major: D/4 lanes per row, 64 / (D/4) rows per pass
+    constexpr int LPRW = D / 4;            // lanes per row
+    constexpr int ROWS_PP = 64 / LPRW;     // rows per pass
+#pragma unroll
+    for (int pass = 0; pass < 32 / ROWS_PP; ++pass) {
+      const int rr = pass * ROWS_PP + lane / LPRW;  // row inside this 32-row group
+      const int ch = lane % LPRW;
+      const f32x4_t w = *reinterpret_cast<const __attribute__((address_space(3))) f32x4_t *>(
+          stage + rr * (D * 4) + ((ch ^ (rr & (LPRW - 1))) << 4));
+      const int r = row0 + wave * kRowsPerWave + b * 32 + rr;
+      if (r < n_rows) {
+        const int i = r / Gq;
+        const int g = r - i * Gq;
+        const int head = kvh * Gq + g;
+        if (p.n_splits == 1) {
+          uint2 o2;
+          o2.x = pack_bf16(w[0], w[1]);
+          o2.y = pack_bf16(w[2], w[3]);
+          *reinterpret_cast<uint2 *>(p.o + (int64_t)(pr.q_tok0 + i) * p.o_st + (int64_t)head * p.o_sh + ch * 4) = o2;
+        } else {
+          const int64_t prow = (int64_t)(pr.q_tok0 + i) * p.n_q_heads + head;
+          *reinterpret_cast<f32x4_t *>(p.part_o + ((int64_t)split * p.part_rows + prow) * D + ch * 4) = w;
         }
-    } else {
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (p.n_splits > 1 && hf == 0 && row_ok[b]) {
       const int r = row0 + wave * kRowsPerWave + b * 32 + col;
       const int i = r / Gq;
       const int g = r - i * Gq;
       const int64_t prow = (int64_t)(pr.q_tok0 + i) * p.n_q_heads + kvh * Gq + g;
-      float *po = p.part_o + ((int64_t)split * p.part_rows + prow) * D;
-#pragma unroll
-      for (int dt = 0; dt < G::DT; ++dt)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int d = dt * 32 + q4 * 8 + hf * 4;
-          f32x4_t w = {oacc[dt][b][q4 * 4 + 0], oacc[dt][b][q4 * 4 + 1], oacc[dt][b][q4 * 4 + 2],
-                       oacc[dt][b][q4 * 4 + 3]};
-          *reinterpret_cast<f32x4_t *>(po + d) = w;
-        }
-      if (hf == 0) {
-        float2 ml = {m_run[b] * c2, l_tot};  // max in log2 units (-inf if nothing was visible)
-        *reinterpret_cast<float2 *>(p.part_ml + ((int64_t)split * p.part_rows + prow) * 2) = ml;
-      }
+      float2 ml = {m_ref[b] == -INFINITY ? -INFINITY : mb[b], l_tot[b]};  // reference in log2 units
+      *reinterpret_cast<float2 *>(p.part_ml + ((int64_t)split * p.part_rows + prow) * 2) = ml;
     }
   }
 }
@@ -473,7 +515,7 @@ hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, const RopeTable 
   const int64_t n_wg = (int64_t)p.total_tiles * p.n_kv_heads * p.n_splits;
   if (n_wg == 0) return hipSuccess;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
-  const size_t lds = 4 * Geo<D>::TILEB;
+  const size_t lds = 4 * Geo<D>::TILEB > (size_t)kWaves * 32 * D * 4 ? 4 * Geo<D>::TILEB : (size_t)kWaves * 32 * D * 4;
   hipLaunchKernelGGL((attn_kernel<D, Meta>), dim3((unsigned)n_wg), dim3(kThreads), lds, stream, p, meta, rt);
   return hipGetLastError();
 }

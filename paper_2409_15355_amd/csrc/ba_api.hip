@@ -74,6 +74,8 @@ int32_t check_tensor(const ba_tensor *t, const char *name, bool allow_f32, int32
     return fail(BA_ERR_ALIGNMENT, "%s: pointer and strides must be 16-byte aligned", name);
   if (t->stride_head < D || t->stride_tok < (int64_t)D)
     return fail(BA_ERR_INVALID_ARG, "%s: strides smaller than head_dim", name);
+  if (t->stride_tok >= (1 << 24))  // tile fills address rows with 32-bit byte offsets
+    return fail(BA_ERR_UNSUPPORTED, "%s: token stride of 2^24 elements or more", name);
   (void)n_heads;
   return BA_OK;
 }
