@@ -9,7 +9,7 @@
 // masked tiles of the block-diagonal mask are never issued.
 //
 // Mapping onto the hardware
-//   - A workgroup (4 wavefronts, one per SIMD) owns 256 packed query rows of one KV head.
+//   - A workgroup (8 wavefronts, two per SIMD) owns 256 packed query rows of one KV head.
 //     Row r = token * G + head_in_group packs the G query heads of a GQA group next to
 //     each other, so one K/V tile streamed through LDS serves all of them.
 //   - K/V tiles (64 keys) go from HBM straight into LDS with LDS-direct loads
@@ -32,9 +32,13 @@
 namespace ba {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
-constexpr int kRowsPerWave = kTileRows / kWaves;  // 64 = two 32-query MFMA column groups
+constexpr int kCombineThreads = 256;
+// A wave owns NB groups of 32 query rows.  NB = 1: 8 waves per workgroup, two per SIMD, so
+// one wave's softmax (VALU) runs under the other's MFMAs; NB = 2: 4 waves, one per SIMD.
+constexpr int kNB = 1;
+constexpr int kWaves = kTileRows / (32 * kNB);
+constexpr int kThreads = kWaves * 64;
+constexpr int kRowsPerWave = 32 * kNB;
 constexpr float kLazyLog2 = 8.0f;                 // exponentials may reach 2^8 before the reference moves
 constexpr int kXcds = 8;                          // MI355X: workgroup ids go round-robin over 8 XCDs
 
@@ -142,11 +146,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
   const int t_end = (int)((int64_t)nt * (split + 1) / p.n_splits);
 
   // ---- Q fragments (B operand of S^T = K Q^T), rotated in registers if asked -------------
-  bf16x8_t qf[2][G::KCH];
-  int tok[2];        // query token (inside the problem) of this lane's two columns
-  bool row_ok[2];
+  bf16x8_t qf[kNB][G::KCH];
+  int tok[kNB];        // query token (inside the problem) of this lane's column(s)
+  bool row_ok[kNB];
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
+  for (int b = 0; b < kNB; ++b) {
     const int r = row0 + wave * kRowsPerWave + b * 32 + col;
     row_ok[b] = r < n_rows;
     const int i = r / Gq;
@@ -223,20 +227,26 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
   }
 
   // ---- running softmax state and O^T accumulators ------------------------------------------
-  f32x16_t oacc[G::DT][2];
+  f32x16_t oacc[G::DT][kNB];
 #pragma unroll
   for (int dt = 0; dt < G::DT; ++dt)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < kNB; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) oacc[dt][b][v] = 0.f;
   // Online softmax with a LAZY reference: exponentials are taken relative to m_ref, which
   // is raised only when a tile's maximum exceeds it by more than kLazyLog2 powers of two.
   // Any reference gives the same quotient sum(p v) / sum(p); keeping it fixed avoids
   // rescaling the O^T accumulators on almost every tile.
-  float m_ref[2] = {-INFINITY, -INFINITY};  // reference, raw score units
-  float mb[2] = {0.f, 0.f};                 // m_ref * scale_log2e (0 while nothing was seen)
-  float l_run[2] = {0.f, 0.f};              // this lane's share of the running sum
+  float m_ref[kNB];  // reference, raw score units
+  float mb[kNB];     // m_ref * scale_log2e (0 while nothing was seen)
+  float l_run[kNB];  // this lane's share of the running sum
+#pragma unroll
+  for (int b = 0; b < kNB; ++b) {
+    m_ref[b] = -INFINITY;
+    mb[b] = 0.f;
+    l_run[b] = 0.f;
+  }
   const float c2 = p.scale_log2e;
   const float tau = kLazyLog2 / c2;
   const int first_tok_wave = (row0 + wave * kRowsPerWave) / Gq;
@@ -298,11 +308,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
     if (t + 1 < t_end) issue_tile(tile_of(t + 1), BUF ^ 1);
 
     // ---- S^T = K Q^T : sacc[a][b] is keys 32a..32a+31 x queries 32b..32b+31 ----------------
-    f32x16_t sacc[2][2];
+    f32x16_t sacc[2][kNB];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < kNB; ++b)
 #pragma unroll
         for (int v = 0; v < 16; ++v) sacc[a][b][v] = 0.f;
 #pragma unroll
@@ -311,8 +321,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
       for (int kk = 0; kk < G::KCH; ++kk) {
         const bf16x8_t kfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(
             smem + k_rd[kk] + (BUF * G::TILEB + a * 32 * G::ROWB));
-        sacc[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[0][kk], sacc[a][0], 0, 0, 0);
-        sacc[a][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[1][kk], sacc[a][1], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < kNB; ++b)
+          sacc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[b][kk], sacc[a][b], 0, 0, 0);
       }
     }
 
@@ -322,7 +333,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
     if (need_mask) {
       asm volatile("" ::: "memory");  // keep this a real branch: never speculate the selects
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
+      for (int b = 0; b < kNB; ++b) {
         const int lim = tl.causal ? min(tok[b] - tl.key0 + 1, tl.valid) : tl.valid;  // visible keys here
 #pragma unroll
         for (int a = 0; a < 2; ++a)
@@ -334,22 +345,24 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
       }
     }
     // ---- online softmax, lazy reference ---------------------------------------------------------------
-    float mx[2];
+    float mx[kNB];
+    bool raise[kNB], any_raise = false;
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < kNB; ++b) {
       float m0 = sacc[0][b][0];
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) m0 = fmaxf(m0, sacc[a][b][v]);
       mx[b] = fmaxf(m0, other_half(m0));
+      raise[b] = mx[b] > m_ref[b] + tau;
+      any_raise = any_raise || raise[b];
     }
-    const bool raise0 = mx[0] > m_ref[0] + tau, raise1 = mx[1] > m_ref[1] + tau;
-    if (__builtin_amdgcn_ballot_w64(raise0 || raise1) != 0) {  // rare after the first tile
+    if (__builtin_amdgcn_ballot_w64(any_raise) != 0) {  // rare after the first tile
       asm volatile("" ::: "memory");  // a real branch, so the accumulators are left alone otherwise
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const float m_new = (b == 0 ? raise0 : raise1) ? mx[b] : m_ref[b];
+      for (int b = 0; b < kNB; ++b) {
+        const float m_new = raise[b] ? mx[b] : m_ref[b];
         const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref[b] - m_new) * c2);
         m_ref[b] = m_new;
         mb[b] = (m_new == -INFINITY) ? 0.f : m_new * c2;
@@ -360,9 +373,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
           for (int v = 0; v < 16; ++v) oacc[dt][b][v] *= alpha;
       }
     }
-    bf16x8_t pf[2][4];  // P^T fragments: [query group][16-key step]
+    bf16x8_t pf[kNB][4];  // P^T fragments: [query group][16-key step]
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < kNB; ++b) {
       float sum = 0.f;
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
@@ -396,8 +409,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
         typedef short s16x8_t __attribute__((ext_vector_type(8)));
         const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         const bf16x8_t vfrag = __builtin_bit_cast(bf16x8_t, both);
-        oacc[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pf[0][kc], oacc[dt][0], 0, 0, 0);
-        oacc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pf[1][kc], oacc[dt][1], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < kNB; ++b)
+          oacc[dt][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pf[b][kc], oacc[dt][b], 0, 0, 0);
       }
     }
     __syncthreads();  // the next tile has landed (the barrier waits on the copy) and this one is free
@@ -415,59 +429,69 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
     if (t < t_end) tile_body(std::integral_constant<int, 0>{}, t);
   }
 
-  // ---- epilogue: each wave transposes its O^T through its own 16 KB of LDS so that rows leave
-  //      as whole contiguous lines (all waves are past the loop's last barrier) ---------------------
-  lds_char *stage = smem + wave * (32 * D * 4);  // 32 rows x D floats
-  float inv[2], l_tot[2];
+  // ---- epilogue: each wave transposes its O^T through its own slice of LDS, half of the head
+  //      dimension at a time, so that rows leave as contiguous lines (all waves are past the
+  //      loop's last barrier, and nothing else touches LDS any more) ---------------------------------
+  constexpr int HD = D / 2;               // floats per staged row piece
+  constexpr int HCH = HD / 4;             // 16-byte chunks per piece (16 or 8)
+  constexpr int PITCH = HD * 4;           // bytes per staged row piece (256 or 128)
+  constexpr int HLPR = 256 / PITCH;       // pieces per 256-byte LDS line
+  lds_char *stage = smem + wave * (32 * PITCH);
+  float inv[kNB], l_tot[kNB];
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
+  for (int b = 0; b < kNB; ++b) {
     l_tot[b] = l_run[b] + other_half(l_run[b]);
     inv[b] = (p.n_splits == 1) ? 1.0f / l_tot[b] : 1.0f;
   }
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    // write: lane (col, hf) owns query row `col`; 16-byte chunk index XOR row keeps banks apart
+  for (int b = 0; b < kNB; ++b) {
 #pragma unroll
-    for (int dt = 0; dt < G::DT; ++dt)
+    for (int half = 0; half < 2; ++half) {
+      // write: lane (col, hf) owns query row `col`; chunk index XOR row keeps banks apart
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int chunk = dt * 8 + q4 * 2 + hf;  // (32 dt + 8 q4 + 4 hf) / 4
-        f32x4_t w = {oacc[dt][b][q4 * 4 + 0] * inv[b], oacc[dt][b][q4 * 4 + 1] * inv[b],
-                     oacc[dt][b][q4 * 4 + 2] * inv[b], oacc[dt][b][q4 * 4 + 3] * inv[b]};
-        *reinterpret_cast<__attribute__((address_space(3))) f32x4_t *>(
-            stage + col * (D * 4) + ((chunk ^ (col & (D / 4 - 1))) << 4)) = w;
-      }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // read back row-major: D/4 lanes per row, 64 / (D/4) rows per pass
-    constexpr int LPRW = D / 4;            // lanes per row
-    constexpr int ROWS_PP = 64 / LPRW;     // rows per pass
+      for (int dh = 0; dh < G::DT / 2; ++dh) {
+        const int dt = half * (G::DT / 2) + dh;
 #pragma unroll
-    for (int pass = 0; pass < 32 / ROWS_PP; ++pass) {
-      const int rr = pass * ROWS_PP + lane / LPRW;  // row inside this 32-row group
-      const int ch = lane % LPRW;
-      const f32x4_t w = *reinterpret_cast<const __attribute__((address_space(3))) f32x4_t *>(
-          stage + rr * (D * 4) + ((ch ^ (rr & (LPRW - 1))) << 4));
-      const int r = row0 + wave * kRowsPerWave + b * 32 + rr;
-      if (r < n_rows) {
-        const int i = r / Gq;
-        const int g = r - i * Gq;
-        const int head = kvh * Gq + g;
-        if (p.n_splits == 1) {
-          uint2 o2;
-          o2.x = pack_bf16(w[0], w[1]);
-          o2.y = pack_bf16(w[2], w[3]);
-          *reinterpret_cast<uint2 *>(p.o + (int64_t)(pr.q_tok0 + i) * p.o_st + (int64_t)head * p.o_sh + ch * 4) = o2;
-        } else {
-          const int64_t prow = (int64_t)(pr.q_tok0 + i) * p.n_q_heads + head;
-          *reinterpret_cast<f32x4_t *>(p.part_o + ((int64_t)split * p.part_rows + prow) * D + ch * 4) = w;
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int chunk = dh * 8 + q4 * 2 + hf;  // 16-byte chunk inside the piece
+          f32x4_t w = {oacc[dt][b][q4 * 4 + 0] * inv[b], oacc[dt][b][q4 * 4 + 1] * inv[b],
+                       oacc[dt][b][q4 * 4 + 2] * inv[b], oacc[dt][b][q4 * 4 + 3] * inv[b]};
+          *reinterpret_cast<__attribute__((address_space(3))) f32x4_t *>(
+              stage + col * PITCH + ((chunk ^ ((col / HLPR) & (HCH - 1))) << 4)) = w;
         }
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      // read back row-major: HCH lanes per row piece, 64 / HCH rows per pass
+      constexpr int ROWS_PP = 64 / HCH;
+#pragma unroll
+      for (int pass = 0; pass < 32 / ROWS_PP; ++pass) {
+        const int rr = pass * ROWS_PP + lane / HCH;  // row inside this 32-row group
+        const int ch = lane % HCH;
+        const f32x4_t w = *reinterpret_cast<const __attribute__((address_space(3))) f32x4_t *>(
+            stage + rr * PITCH + ((ch ^ ((rr / HLPR) & (HCH - 1))) << 4));
+        const int r = row0 + wave * kRowsPerWave + b * 32 + rr;
+        if (r < n_rows) {
+          const int i = r / Gq;
+          const int g = r - i * Gq;
+          const int head = kvh * Gq + g;
+          const int d = half * HD + ch * 4;
+          if (p.n_splits == 1) {
+            uint2 o2;
+            o2.x = pack_bf16(w[0], w[1]);
+            o2.y = pack_bf16(w[2], w[3]);
+            *reinterpret_cast<uint2 *>(p.o + (int64_t)(pr.q_tok0 + i) * p.o_st + (int64_t)head * p.o_sh + d) = o2;
+          } else {
+            const int64_t prow = (int64_t)(pr.q_tok0 + i) * p.n_q_heads + head;
+            *reinterpret_cast<f32x4_t *>(p.part_o + ((int64_t)split * p.part_rows + prow) * D + d) = w;
+          }
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if (p.n_splits > 1 && hf == 0 && row_ok[b]) {
       const int r = row0 + wave * kRowsPerWave + b * 32 + col;
       const int i = r / Gq;
@@ -482,9 +506,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
 // Merge split partials in split order: m = max m_i, w_i = 2^(m_i - m),
 // o = sum_i w_i O_i / sum_i w_i l_i.
 template <int D>
-__global__ __launch_bounds__(kThreads) void combine_kernel(AttnParams p, int64_t n_rows) {
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, int64_t n_rows) {
   constexpr int TPR = D / 4;              // threads per row
-  constexpr int RPB = kThreads / TPR;     // rows per workgroup
+  constexpr int RPB = kCombineThreads / TPR;     // rows per workgroup
   const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / TPR;
   if (row >= n_rows) return;
   const int d = (threadIdx.x % TPR) * 4;
@@ -515,7 +539,8 @@ hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, const RopeTable 
   const int64_t n_wg = (int64_t)p.total_tiles * p.n_kv_heads * p.n_splits;
   if (n_wg == 0) return hipSuccess;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
-  const size_t lds = 4 * Geo<D>::TILEB > (size_t)kWaves * 32 * D * 4 ? 4 * Geo<D>::TILEB : (size_t)kWaves * 32 * D * 4;
+  const size_t lds = 4 * Geo<D>::TILEB;  // two K and two V buffers; the epilogue staging (kWaves * 32 * D * 2 bytes) fits inside
+  static_assert((size_t)kWaves * 32 * D * 2 <= 4 * (size_t)Geo<D>::TILEB, "epilogue staging must fit the tile buffers");
   hipLaunchKernelGGL((attn_kernel<D, Meta>), dim3((unsigned)n_wg), dim3(kThreads), lds, stream, p, meta, rt);
   return hipGetLastError();
 }
@@ -540,12 +565,12 @@ hipError_t launch_combine(const AttnParams &p, int64_t n_tokens, hipStream_t str
   const int64_t n_rows = n_tokens * p.n_q_heads;
   if (n_rows == 0) return hipSuccess;
   if (p.head_dim == 128) {
-    constexpr int RPB = kThreads / (128 / 4);
-    hipLaunchKernelGGL((combine_kernel<128>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kThreads), 0,
+    constexpr int RPB = kCombineThreads / (128 / 4);
+    hipLaunchKernelGGL((combine_kernel<128>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kCombineThreads), 0,
                        stream, p, n_rows);
   } else if (p.head_dim == 64) {
-    constexpr int RPB = kThreads / (64 / 4);
-    hipLaunchKernelGGL((combine_kernel<64>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kThreads), 0,
+    constexpr int RPB = kCombineThreads / (64 / 4);
+    hipLaunchKernelGGL((combine_kernel<64>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kCombineThreads), 0,
                        stream, p, n_rows);
   } else {
     return hipErrorInvalidValue;
