@@ -36,6 +36,7 @@ constexpr int kCombineThreads = 256;
 // A wave owns NB groups of 32 query rows.  NB = 1: 8 waves per workgroup, two per SIMD, so
 // one wave's softmax (VALU) runs under the other's MFMAs; NB = 2: 4 waves, one per SIMD.
 constexpr int kNB = 1;
+constexpr bool kPipelined = false;  // software-pipeline QK of tile t+1 under the softmax of tile t
 constexpr int kWaves = kTileRows / (32 * kNB);
 constexpr int kThreads = kWaves * 64;
 constexpr int kRowsPerWave = 32 * kNB;
@@ -104,6 +105,23 @@ __device__ __forceinline__ float other_half(float x) {
 }
 
 typedef __attribute__((address_space(3))) char lds_char;
+
+// LDS-direct load: every lane fetches 16 bytes from base + offset and the wave writes them to
+// LDS bytes [lds_base + 16 lane, +16).  Issued through inline assembly ON PURPOSE: the compiler
+// would otherwise treat the copy as a store that may alias every later LDS read and wait for
+// it (vmcnt(0)) before the first fragment read of the same iteration, which exposes the whole
+// HBM latency on every tile.  The price is that completion is ours to wait for: dma_wait()
+// must come before the barrier that publishes the buffer.
+__device__ __forceinline__ void lds_dma16(const char *base, uint32_t offset, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(offset), "s"(base), "s"(lds_base)
+               : "memory");
+}
+__device__ __forceinline__ void dma_wait() {
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0), leaving expcnt and lgkmcnt alone (gfx9 encoding)
+  asm volatile("" ::: "memory");
+}
 
 template <int D, typename Meta>
 __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta, RopeTable rt) {
@@ -282,52 +300,70 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
     }
     return tl;
   };
-  // Copy tile t into LDS buffer `buf` with LDS-direct loads: one wave instruction fills
-  // 1024 contiguous LDS bytes, lane i writing bytes [16 i, 16 i + 16); the swizzle is applied
-  // on the GLOBAL side (each lane fetches the chunk that belongs at its LDS position).  Rows
-  // at or beyond `valid` re-read the last valid row: their scores are masked, and a finite
-  // duplicate keeps 0 * v equal to 0.
-  auto issue_tile = [&](const Tile &tl, int buf) {
+  // Copy a K or V tile into LDS buffer `buf` with LDS-direct loads: one wave instruction
+  // fills 1024 contiguous LDS bytes, lane i writing bytes [16 i, 16 i + 16); the swizzle is
+  // applied on the GLOBAL side (each lane fetches the chunk that belongs at its LDS position).
+  // Rows at or beyond `valid` re-read the last valid row: their scores are masked, and a
+  // finite duplicate keeps 0 * v equal to 0.
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+  auto issue_k = [&](const Tile &tl, int buf) {
 #pragma unroll
     for (int i = 0; i < G::IPW; ++i) {
       const uint32_t row = (uint32_t)min(g_row[i], tl.valid - 1);
-      const int slot = wave * G::IPW + i;
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void *)(tl.kp + (row * tl.kst + g_kchunk[i])),
-          (__attribute__((address_space(3))) void *)(smem + buf * G::TILEB + slot * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void *)(tl.vp + (row * tl.vst + g_vchunk[i])),
-          (__attribute__((address_space(3))) void *)(smem + (2 + buf) * G::TILEB + slot * 1024), 16, 0, 0);
+      lds_dma16(tl.kp, row * tl.kst + g_kchunk[i], lds0 + buf * G::TILEB + (wave * G::IPW + i) * 1024);
+    }
+  };
+  auto issue_v = [&](const Tile &tl, int buf) {
+#pragma unroll
+    for (int i = 0; i < G::IPW; ++i) {
+      const uint32_t row = (uint32_t)min(g_row[i], tl.valid - 1);
+      lds_dma16(tl.vp, row * tl.vst + g_vchunk[i], lds0 + (2 + buf) * G::TILEB + (wave * G::IPW + i) * 1024);
     }
   };
 
-  auto tile_body = [&](auto buf_c, int t) {
+  // S^T = K Q^T from K buffer BUF: sacc[a][b] is keys 32a..32a+31 x queries 32b..32b+31.
+  // The 2 * KCH steps go in groups of four; a group's K fragments are read while the previous
+  // group's MFMAs run, so LDS latency stays off the MFMA chain.  sched_barrier(0) pins it.
+  auto qk = [&](auto buf_c, f32x16_t (&sacc)[2][kNB]) {
     constexpr int BUF = decltype(buf_c)::value;
-    const Tile tl = tile_of(t);
-    // start the next tile's copy into the other buffer; it lands while this tile is consumed
-    if (t + 1 < t_end) issue_tile(tile_of(t + 1), BUF ^ 1);
-
-    // ---- S^T = K Q^T : sacc[a][b] is keys 32a..32a+31 x queries 32b..32b+31 ----------------
-    f32x16_t sacc[2][kNB];
+    constexpr int STEPS = 2 * G::KCH;  // step = kk * 2 + a: consecutive MFMAs are independent
+    constexpr int GS = 4;
+    constexpr int NG = STEPS / GS;
+    auto read_k = [&](int step) {
+      const int a = step & 1, kk = step >> 1;
+      return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(
+          smem + k_rd[kk] + (BUF * G::TILEB + a * 32 * G::ROWB));
+    };
+    bf16x8_t fr[2][GS];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int j = 0; j < GS; ++j) fr[0][j] = read_k(j);
 #pragma unroll
-      for (int b = 0; b < kNB; ++b)
+    for (int g = 0; g < NG; ++g) {
+      if (g + 1 < NG) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[a][b][v] = 0.f;
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
-#pragma unroll
-      for (int kk = 0; kk < G::KCH; ++kk) {
-        const bf16x8_t kfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(
-            smem + k_rd[kk] + (BUF * G::TILEB + a * 32 * G::ROWB));
-#pragma unroll
-        for (int b = 0; b < kNB; ++b)
-          sacc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[b][kk], sacc[a][b], 0, 0, 0);
+        for (int j = 0; j < GS; ++j) fr[(g + 1) & 1][j] = read_k((g + 1) * GS + j);
       }
+#pragma unroll
+      for (int j = 0; j < GS; ++j) {
+        const int step = g * GS + j, a = step & 1, kk = step >> 1;
+#pragma unroll
+        for (int b = 0; b < kNB; ++b) {
+          if (kk == 0) {
+            f32x16_t z;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) z[v] = 0.f;
+            sacc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][j], qf[b][kk], z, 0, 0, 0);
+          } else {
+            sacc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][j], qf[b][kk], sacc[a][b], 0, 0, 0);
+          }
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-
-    // ---- mask (diagonal and ragged tiles only; wave-uniform branch) -----------------------------
+  };
+  // Mask a fresh score tile where needed (diagonal and ragged tiles only), take its row maxima
+  // and raise the lazy reference if a row outgrew it.  Both branches are wave-uniform and rare.
+  auto mask_and_reference = [&](const Tile &tl, f32x16_t (&sacc)[2][kNB]) {
     const bool need_mask = tl.causal ? (tl.key0 + kTileKeys - 1 > first_tok_wave) || (tl.valid < kTileKeys)
                                      : (tl.valid < kTileKeys);
     if (need_mask) {
@@ -344,7 +380,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
           }
       }
     }
-    // ---- online softmax, lazy reference ---------------------------------------------------------------
     float mx[kNB];
     bool raise[kNB], any_raise = false;
 #pragma unroll
@@ -373,7 +408,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
           for (int v = 0; v < 16; ++v) oacc[dt][b][v] *= alpha;
       }
     }
-    bf16x8_t pf[kNB][4];  // P^T fragments: [query group][16-key step]
+  };
+  // P = 2^(S * scale_log2e - reference), summed in fp32, rounded to bf16 as the B operand of PV
+  auto exponentials = [&](const f32x16_t (&sacc)[2][kNB], bf16x8_t (&pf)[kNB][4]) {
 #pragma unroll
     for (int b = 0; b < kNB; ++b) {
       float sum = 0.f;
@@ -395,39 +432,204 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
       }
       l_run[b] += sum;
     }
-
-    // ---- O^T += V^T P^T ---------------------------------------------------------------------------
+  };
+  // Phase 1 of the pipelined iteration: the QK MFMAs of the NEXT tile and the exponentials of
+  // the CURRENT one, written out interleaved.  The 2 * KCH MFMA steps (key half a outermost,
+  // so that the first half of the new scores is complete when the first half of the old ones
+  // has been consumed) go in eight groups; the K fragments of a group are read one group
+  // ahead, and after every second group a quarter of the exponentials follows.
+  // sched_barrier(0) pins the groups; inside a group the scheduler interleaves.
+  auto qk_with_exponentials = [&](auto buf_c, f32x16_t (&sacc)[2][kNB], const f32x16_t (&scur)[2][kNB],
+                                  bf16x8_t (&pf)[kNB][4]) {
+    constexpr int BUF = decltype(buf_c)::value;
+    constexpr int STEPS = 2 * G::KCH;   // step = a * KCH + kk
+    constexpr int NG = 8;               // groups
+    constexpr int GS = STEPS / NG;      // steps per group (2 or 1)
+    auto read_k = [&](int step) {
+      const int a = step / G::KCH, kk = step % G::KCH;
+      return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(
+          smem + k_rd[kk] + (BUF * G::TILEB + a * 32 * G::ROWB));
+    };
+    float sum[kNB];
+#pragma unroll
+    for (int b = 0; b < kNB; ++b) sum[b] = 0.f;
+    bf16x8_t fr[2][GS];
+#pragma unroll
+    for (int j = 0; j < GS; ++j) fr[0][j] = read_k(j);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      if (g + 1 < NG) {
+#pragma unroll
+        for (int j = 0; j < GS; ++j) fr[(g + 1) & 1][j] = read_k((g + 1) * GS + j);
+      }
+#pragma unroll
+      for (int j = 0; j < GS; ++j) {
+        const int step = g * GS + j, a = step / G::KCH, kk = step % G::KCH;
+#pragma unroll
+        for (int b = 0; b < kNB; ++b) {
+          if (kk == 0) {
+            f32x16_t z;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) z[v] = 0.f;
+            sacc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][j], qf[b][kk], z, 0, 0, 0);
+          } else {
+            sacc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][j], qf[b][kk], sacc[a][b], 0, 0, 0);
+          }
+        }
+      }
+      if (g & 1) {
+        // exponentials of quarter q of the current tile: exactly the keys of P^T fragment q
+        const int q = g >> 1, ea = q >> 1, ee = q & 1;
+#pragma unroll
+        for (int b = 0; b < kNB; ++b) {
+          float pv[8];
+#pragma unroll
+          for (int v = 0; v < 8; ++v) {
+            pv[v] = __builtin_amdgcn_exp2f(scur[ea][b][ee * 8 + v] * c2 - mb[b]);
+            sum[b] += pv[v];
+          }
+          u32x4_t w;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) w[i] = pack_bf16(pv[2 * i], pv[2 * i + 1]);
+          pf[b][q] = __builtin_bit_cast(bf16x8_t, w);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int b = 0; b < kNB; ++b) l_run[b] += sum[b];
+  };
+  // O^T += V^T P^T from V buffer BUF
+  auto pv_mma = [&](auto buf_c, const bf16x8_t (&pf)[kNB][4]) {
+    constexpr int BUF = decltype(buf_c)::value;
+    typedef __attribute__((address_space(3))) s16x4_t lds_s16x4;
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    auto read_v = [&](int kc, int dt) {
+      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4 *)(smem + v_rd[dt] + (BUF * G::TILEB + kc * 16 * G::ROWB)));
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4 *)(smem + v_rd[dt] + (BUF * G::TILEB + (kc * 16 + 8) * G::ROWB)));
+      const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8_t, both);
+    };
+    bf16x8_t fr[2][G::DT];  // V^T fragments of one 16-key step, read one step ahead
+#pragma unroll
+    for (int dt = 0; dt < G::DT; ++dt) fr[0][dt] = read_v(0, dt);
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc) {
+      if (kc + 1 < 4) {
 #pragma unroll
-      for (int dt = 0; dt < G::DT; ++dt) {
-        typedef __attribute__((address_space(3))) s16x4_t lds_s16x4;
-        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4 *)(smem + v_rd[dt] + (BUF * G::TILEB + kc * 16 * G::ROWB)));
-        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4 *)(smem + v_rd[dt] + (BUF * G::TILEB + (kc * 16 + 8) * G::ROWB)));
-        typedef short s16x8_t __attribute__((ext_vector_type(8)));
-        const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8_t vfrag = __builtin_bit_cast(bf16x8_t, both);
+        for (int dt = 0; dt < G::DT; ++dt) fr[(kc + 1) & 1][dt] = read_v(kc + 1, dt);
+      }
+#pragma unroll
+      for (int dt = 0; dt < G::DT; ++dt)
 #pragma unroll
         for (int b = 0; b < kNB; ++b)
-          oacc[dt][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pf[b][kc], oacc[dt][b], 0, 0, 0);
-      }
+          oacc[dt][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[kc & 1][dt], pf[b][kc], oacc[dt][b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();  // the next tile has landed (the barrier waits on the copy) and this one is free
   };
 
-  if (t_begin < t_end) issue_tile(tile_of(t_begin), 0);
-  __syncthreads();
-  {
+  // ---- software-pipelined walk over the key tiles ------------------------------------------------
+  // In the iteration of tile t a wave issues QK for tile t+1 together with the exponentials of
+  // tile t (independent MFMA and VALU streams), then PV for tile t together with the row maxima
+  // of tile t+1.  Tile t's K sits in K buffer (t - t_begin) & 1, its V in the V buffer of the
+  // same parity; K for t+2 and V for t+1 are in flight meanwhile and land by the barrier.
+  const int n_t = t_end - t_begin;
+  if (kPipelined) {
+  f32x16_t s_cur[2][kNB];
+  Tile tn1;  // tile t+1 of the running iteration
+  if (n_t > 0) {
+    const Tile t0 = tile_of(t_begin);
+    issue_k(t0, 0);
+    issue_v(t0, 0);
+    tn1 = t0;
+    if (n_t > 1) {
+      tn1 = tile_of(t_begin + 1);
+      issue_k(tn1, 1);
+    }
+    dma_wait();
+    __syncthreads();
+    qk(std::integral_constant<int, 0>{}, s_cur);
+    mask_and_reference(t0, s_cur);
+    __syncthreads();  // every wave has read K buffer 0 before the first iteration refills it
+  }
+  auto body = [&](auto par_c, int t) {  // tile t, with t + 1 < t_end
+    constexpr int PAR = decltype(par_c)::value;
+    Tile tn2 = tn1;
+    if (t + 2 < t_end) {
+      tn2 = tile_of(t + 2);
+      issue_k(tn2, PAR);
+    }
+    issue_v(tn1, PAR ^ 1);
+    f32x16_t s_next[2][kNB];
+    bf16x8_t pf[kNB][4];
+    qk_with_exponentials(std::integral_constant<int, PAR ^ 1>{}, s_next, s_cur, pf);
+    pv_mma(std::integral_constant<int, PAR>{}, pf);
+    mask_and_reference(tn1, s_next);
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < kNB; ++b) s_cur[a][b] = s_next[a][b];
+    tn1 = tn2;
+    dma_wait();
+    __syncthreads();  // tiles t+2 (K) and t+1 (V) have landed; the buffers of tile t are free
+  };
+  auto last = [&](auto par_c) {
+    constexpr int PAR = decltype(par_c)::value;
+    bf16x8_t pf[kNB][4];
+    exponentials(s_cur, pf);
+    pv_mma(std::integral_constant<int, PAR>{}, pf);
+  };
+  if (n_t > 0) {
+    int i = 0;
+#pragma unroll 1
+    for (; i + 2 < n_t; i += 2) {
+      body(std::integral_constant<int, 0>{}, t_begin + i);
+      body(std::integral_constant<int, 1>{}, t_begin + i + 1);
+    }
+    if (i + 1 < n_t) {
+      body(std::integral_constant<int, 0>{}, t_begin + i);
+      ++i;
+    }
+    if (i & 1) last(std::integral_constant<int, 1>{}); else last(std::integral_constant<int, 0>{});
+  }
+  } else {
+    // Plain order: fill the next tile, then QK, softmax, PV of this one.  With two waves per
+    // SIMD the hardware overlaps one wave's VALU phase with the other's MFMA phase.
+    auto simple = [&](auto par_c, int t) {
+      constexpr int PAR = decltype(par_c)::value;
+      const Tile tl = tile_of(t);
+      if (t + 1 < t_end) {
+        const Tile tn = tile_of(t + 1);
+        issue_k(tn, PAR ^ 1);
+        issue_v(tn, PAR ^ 1);
+      }
+      f32x16_t sacc[2][kNB];
+      bf16x8_t pf[kNB][4];
+      qk(std::integral_constant<int, PAR>{}, sacc);
+      mask_and_reference(tl, sacc);
+      exponentials(sacc, pf);
+      pv_mma(std::integral_constant<int, PAR>{}, pf);
+      dma_wait();
+      __syncthreads();
+    };
+    if (n_t > 0) {
+      const Tile t0 = tile_of(t_begin);
+      issue_k(t0, 0);
+      issue_v(t0, 0);
+    }
+    dma_wait();  // unconditional: the Q fragment loads are then known to be complete inside the loop
+    __syncthreads();
     int t = t_begin;
 #pragma unroll 1
     for (; t + 1 < t_end; t += 2) {
-      tile_body(std::integral_constant<int, 0>{}, t);
-      tile_body(std::integral_constant<int, 1>{}, t + 1);
+      simple(std::integral_constant<int, 0>{}, t);
+      simple(std::integral_constant<int, 1>{}, t + 1);
     }
-    if (t < t_end) tile_body(std::integral_constant<int, 0>{}, t);
+    if (t < t_end) simple(std::integral_constant<int, 0>{}, t);
   }
+  __syncthreads();  // every wave is done with the tiles before LDS is reused for staging
 
   // ---- epilogue: each wave transposes its O^T through its own slice of LDS, half of the head
   //      dimension at a time, so that rows leave as contiguous lines (all waves are past the
