@@ -624,16 +624,25 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, 
   const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / TPR;
   if (row >= n_rows) return;
   const int d = (threadIdx.x % TPR) * 4;
+  // all loads are unconditional and independent, so they go out together; a split that saw no
+  // visible key wrote O = 0, l = 0 and a reference of -inf, and gets weight 0
+  constexpr int MAXS = 32;  // the host never asks for more splits
+  float wgt[MAXS];
   float m = -INFINITY;
-  for (int s = 0; s < p.n_splits; ++s) m = fmaxf(m, p.part_ml[((int64_t)s * p.part_rows + row) * 2]);
+#pragma unroll 8
+  for (int s = 0; s < p.n_splits; ++s) {
+    wgt[s & (MAXS - 1)] = p.part_ml[((int64_t)s * p.part_rows + row) * 2];
+    m = fmaxf(m, wgt[s & (MAXS - 1)]);
+  }
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   float l = 0.f;
+#pragma unroll 8
   for (int s = 0; s < p.n_splits; ++s) {
-    const float2 ml = *reinterpret_cast<const float2 *>(p.part_ml + ((int64_t)s * p.part_rows + row) * 2);
-    if (ml.x == -INFINITY) continue;  // this split saw no visible key for the row
-    const float w = __builtin_amdgcn_exp2f(ml.x - m);
+    const float ms = wgt[s & (MAXS - 1)];
+    const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m);
+    const float ls = p.part_ml[((int64_t)s * p.part_rows + row) * 2 + 1];
     const f32x4_t o = *reinterpret_cast<const f32x4_t *>(p.part_o + ((int64_t)s * p.part_rows + row) * D + d);
-    l += w * ml.y;
+    l += w * ls;
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] += w * o[i];
   }

@@ -207,6 +207,13 @@ int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, c
     if (!filled) continue;
     blk.n = filled;
     p.max_len = max_len;
+    // few tokens: one head per thread (more workgroups, shorter dependent chains);
+    // many tokens: all heads in one thread (sin/cos computed once per token)
+    int64_t tokens = 0;
+    for (int i = 0; i < filled; ++i) tokens += blk.len[i];
+    tokens *= p.n_layers;
+    p.heads_per_thread = tokens >= 65536 ? p.n_kv_heads : (tokens >= 8192 ? std::min(p.n_kv_heads, 4) : 1);
+    p.n_head_groups = (p.n_kv_heads + p.heads_per_thread - 1) / p.heads_per_thread;
     hipError_t e;
     {
       ProfileScope ps(BA_PROFILE_REENCODE, stream);

@@ -37,6 +37,7 @@ struct ReencParams {
   int32_t n_layers, n_kv_heads, head_dim;
   int32_t dtype, layout, mode;
   int32_t max_len;  // longest block in this launch
+  int32_t heads_per_thread, n_head_groups;  // how the KV heads are split over workgroups
 };
 
 hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,

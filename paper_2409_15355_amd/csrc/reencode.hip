@@ -73,7 +73,10 @@ __global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, Reenc
   const int b = blockIdx.y;
   const int layer = blockIdx.z;
   const int len = blocks.len[b];
-  const int tok0 = blockIdx.x * TOK_PER_WG;
+  // blockIdx.x = token chunk * head groups + head group: small inputs spread their heads over
+  // more workgroups, large ones keep all heads in one thread so that sin/cos are reused
+  const int hg = blockIdx.x % p.n_head_groups;
+  const int tok0 = (blockIdx.x / p.n_head_groups) * TOK_PER_WG;
   if (tok0 >= len) return;
 
   const int c = threadIdx.x % TPV;
@@ -102,7 +105,8 @@ __global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, Reenc
     for (int e = 0; e < VEC; ++e) sincos_phase(rope_phase(shift0, turns[e]), cs[e], sn[e]);
   }
   const bool plain_copy = (MODE == 0) && (shift0 == 0);  // zero shift: bit-for-bit copy
-  const int H = p.n_kv_heads;
+  const int g_begin = hg * p.heads_per_thread;
+  const int g_end = min(p.n_kv_heads, g_begin + p.heads_per_thread);
 
 #pragma unroll 1
   for (int pass = 0; pass < TOK_PER_WG / TPP; ++pass) {
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, Reenc
     const T *s0 = src + (int64_t)u * p.src_st + c * VEC;
     T *d0 = dst + (int64_t)u * p.dst_st + c * VEC;
 #pragma unroll 4
-    for (int g = 0; g < H; ++g) {
+    for (int g = g_begin; g < g_end; ++g) {
       Chunk<T> x, y;
       x.load(s0 + g * p.src_sh);
       y.load(s0 + g * p.src_sh + (CH / 2) * VEC);
@@ -142,8 +146,8 @@ hipError_t launch_t(const ReencParams &p, const ReencBlocks &blocks, const RopeT
                     hipStream_t stream) {
   constexpr int VEC = Chunk<T>::VEC;
   constexpr int TPP = kThreads / (D / VEC / 2);
-  constexpr int TOK_PER_WG = TPP * 2;
-  dim3 grid((p.max_len + TOK_PER_WG - 1) / TOK_PER_WG, blocks.n, p.n_layers);
+  constexpr int TOK_PER_WG = TPP;
+  dim3 grid(((p.max_len + TOK_PER_WG - 1) / TOK_PER_WG) * p.n_head_groups, blocks.n, p.n_layers);
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return hipSuccess;
   hipLaunchKernelGGL((reencode_kernel<T, D, LAYOUT, MODE, TOK_PER_WG>), grid, dim3(kThreads), 0,
                      stream, p, blocks, rt);
