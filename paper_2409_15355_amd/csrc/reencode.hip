@@ -141,6 +141,60 @@ __global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, Reenc
   }
 }
 
+// Fast path: uniform shift (the angle depends on the block only), interleaved pairs (every pair
+// lives inside one 16-byte chunk) and packed [tokens][heads][D] storage.  A block is then one
+// contiguous run of chunks, and because the workgroup size is a multiple of the chunks per head
+// vector, a thread that walks the run with stride 256 always meets the same four frequencies:
+// a pure streaming pass, every wave instruction moving 1 KB of consecutive memory.
+template <typename T, int D, int UNROLL>
+__global__ __launch_bounds__(kThreads) void reencode_shift_linear_kernel(ReencParams p, ReencBlocks blocks,
+                                                                         RopeTable rt) {
+  constexpr int VEC = Chunk<T>::VEC;
+  constexpr int CH = D / VEC;
+  static_assert(kThreads % CH == 0, "a thread must keep its chunk position inside the head vector");
+  const int b = blockIdx.y;
+  const int layer = blockIdx.z;
+  const int64_t n_chunks = (int64_t)blocks.len[b] * p.n_kv_heads * CH;
+  const int64_t first = (int64_t)blockIdx.x * (UNROLL * kThreads) + threadIdx.x;
+  if ((int64_t)blockIdx.x * (UNROLL * kThreads) >= n_chunks) return;
+  const int c = threadIdx.x % CH;
+  const int shift0 = blocks.pos_new[b] - blocks.pos_old[b];
+  float cs[VEC / 2], sn[VEC / 2];
+#pragma unroll
+  for (int e = 0; e < VEC / 2; ++e) sincos_phase(rope_phase(shift0, rt.turns[c * (VEC / 2) + e]), cs[e], sn[e]);
+  const T *src = static_cast<const T *>(p.src) + (int64_t)layer * p.src_sl + (int64_t)blocks.src_off[b] * p.src_st;
+  T *dst = static_cast<T *>(p.dst) + (int64_t)layer * p.dst_sl + (int64_t)blocks.dst_off[b] * p.dst_st;
+  Chunk<T> x[UNROLL];
+#pragma unroll
+  for (int k = 0; k < UNROLL; ++k) {
+    const int64_t L = first + (int64_t)k * kThreads;
+    if (L < n_chunks) x[k].load(src + L * VEC);
+  }
+  if (shift0 != 0) {  // zero shift: bit-for-bit copy
+#pragma unroll
+    for (int k = 0; k < UNROLL; ++k)
+#pragma unroll
+      for (int e = 0; e < VEC / 2; ++e) rotate(x[k].f[2 * e], x[k].f[2 * e + 1], cs[e], sn[e]);
+  }
+#pragma unroll
+  for (int k = 0; k < UNROLL; ++k) {
+    const int64_t L = first + (int64_t)k * kThreads;
+    if (L < n_chunks) x[k].store(dst + L * VEC);
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_linear(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
+                         hipStream_t stream) {
+  constexpr int UNROLL = 8;
+  constexpr int CH = D / Chunk<T>::VEC;
+  const int64_t max_chunks = (int64_t)p.max_len * p.n_kv_heads * CH;
+  dim3 grid((unsigned)((max_chunks + UNROLL * kThreads - 1) / (UNROLL * kThreads)), blocks.n, p.n_layers);
+  if (grid.x == 0 || grid.y == 0 || grid.z == 0) return hipSuccess;
+  hipLaunchKernelGGL((reencode_shift_linear_kernel<T, D, UNROLL>), grid, dim3(kThreads), 0, stream, p, blocks, rt);
+  return hipGetLastError();
+}
+
 template <typename T, int D, int LAYOUT, int MODE>
 hipError_t launch_t(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
                     hipStream_t stream) {
@@ -157,6 +211,9 @@ hipError_t launch_t(const ReencParams &p, const ReencBlocks &blocks, const RopeT
 template <typename T, int D>
 hipError_t launch_d(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
                     hipStream_t stream) {
+  const bool packed = p.src_sh == D && p.dst_sh == D && p.src_st == (int64_t)p.n_kv_heads * D &&
+                      p.dst_st == (int64_t)p.n_kv_heads * D;
+  if (p.layout == 0 && p.mode == 0 && packed) return launch_linear<T, D>(p, blocks, rt, stream);
   if (p.layout == 0)
     return p.mode == 0 ? launch_t<T, D, 0, 0>(p, blocks, rt, stream)
                        : launch_t<T, D, 0, 1>(p, blocks, rt, stream);
