@@ -48,6 +48,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows (config 3/4, single block)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size reference for HBM byte counters")
     ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -135,9 +137,16 @@ def main() -> int:
     prof_ms, prof_n = ba.ba_profile_end()
     attn_us = prof_ms[ba.PROFILE_ATTENTION] / max(prof_n[ba.PROFILE_ATTENTION], 1) * 1e3
     achieved = flops_layer / (attn_us * 1e-6) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):  # HBM bytes per launch from the committed rocprofv3 --pmc summaries
+        try:
+            traffic = json.load(open(tpath)).get("attn_kernel_final_cfg5_bytes_per_launch")
+        except (OSError, ValueError):
+            traffic = None
     roofline = {"bound": "mfma", "kernel": "attn_kernel<128, FinalMeta>", "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": None, "avg_launch_us": round(attn_us, 2),
+                "traffic": traffic, "avg_launch_us": round(attn_us, 2),
                 "launches_timed": prof_n[ba.PROFILE_ATTENTION],
                 "other_kernels_us_per_layer": {
                     "rope_final_block_keys": round(prof_ms[ba.PROFILE_REENCODE] / max(prof_n[ba.PROFILE_REENCODE], 1) * 1e3, 2),
@@ -148,7 +157,7 @@ def main() -> int:
     if host0 is not None and args.only == "":
         import oracle
         f = oracle.bf16_bits_to_f64
-        rows = list(range(0, l_q, 2))  # every other final-block row of layer 0: 128 rows x 32 heads
+        rows = list(range(0, l_q))  # every final-block row of layer 0: 256 rows x 32 heads
         th = oracle.theta(w.rope_base, d)
         kc64, vc64, q64, kf64, vf64 = f(host0["kc"]), f(host0["vc"]), f(host0["q"]), f(host0["kf"]), f(host0["vf"])
         t0 = time.perf_counter()
@@ -165,6 +174,15 @@ def main() -> int:
         del kc64, vc64
     del layers, ws
     torch.cuda.empty_cache()
+
+    if args.calib_copy:
+        # 2^29 bf16 elements = 1 GiB read + 1 GiB written by one elementwise copy kernel
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ secondary rows
     rows_out = {}
