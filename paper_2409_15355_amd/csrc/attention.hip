@@ -13,7 +13,7 @@
 //     each wave owns 32 of them.  Row r = token * G + head_in_group packs the G query heads
 //     of a GQA group next to each other, so one K/V tile streamed through LDS serves all.
 //   - K/V tiles (64 keys) go from HBM straight into LDS with LDS-direct loads
-//     (global_load_lds_dwordx4), several tiles ahead of their use, one barrier per tile.
+//     (global_load_lds_dwordx4), three tiles ahead of their use.
 //   - Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: keys
 //     run along accumulator registers and queries along lanes, so row reductions stay in
 //     registers plus one half-wave exchange, and the exponentials are already in the
@@ -26,8 +26,8 @@
 //     exponent; the reference is set by the first tile and moved only if an exponential
 //     threatens to overflow (any reference gives the same quotient sum(p v) / sum(p)).
 //     P is rounded to bf16 for the second MFMA; row sums stay in fp32; the output is rounded once.
-//   - The two waves of a SIMD run half an iteration apart ("ping-pong"): while one is in its
-//     exponentials (VALU), the other is in an MFMA phase.
+//   - The two waves of a SIMD run half a period apart ("ping-pong"): while one is in its
+//     exponentials (VALU), the other is in its MFMA block (PV of this tile, QK of the next).
 //   - The KV range can be cut into n_splits pieces; each piece writes un-normalised
 //     fp32 partials (reference, sum, O) that combine_kernel merges in a fixed order.
 #include <type_traits>
@@ -41,8 +41,8 @@ constexpr int kCombineThreads = 256;
 constexpr int kWaves = kTileRows / 32;  // 8: each wave owns one 32-query MFMA column group
 constexpr int kThreads = kWaves * 64;
 constexpr int kXcds = 8;        // MI355X: workgroup ids go round-robin over 8 XCDs
-constexpr int kNumKBuf = 4;     // K tiles resident in LDS (role B reads one tile ahead)
-constexpr int kNumVBuf = 3;     // V tiles resident in LDS
+constexpr int kNumKBuf = 4;     // K tiles resident in LDS
+constexpr int kNumVBuf = 4;     // V tiles resident in LDS
 constexpr float kRebaseAbove = 1099511627776.0f;  // 2^40: a tile sum beyond this moves the reference
 
 template <int D>
@@ -116,6 +116,13 @@ typedef __attribute__((address_space(3))) char lds_char;
 // HBM latency on every tile.  The price is that completion is ours to wait for: a dma_wait
 // must come before the barrier that publishes the buffer.
 __device__ __forceinline__ void lds_dma16(const char *base, uint32_t offset, uint32_t lds_base) {
+  // base and lds_base are wave-uniform by construction; say so, or a value the compiler cannot
+  // prove uniform would not fit the scalar operands
+  const uint64_t b = (uint64_t)base;
+  const uint64_t bu = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32)) << 32) |
+                      (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+  base = (const char *)bu;
+  lds_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(offset), "s"(base), "s"(lds_base)
@@ -123,6 +130,13 @@ __device__ __forceinline__ void lds_dma16(const char *base, uint32_t offset, uin
 }
 // Wait until at most NEWER of this wave's vector-memory operations are still in flight
 // (they complete in order), leaving the other counters alone.  gfx9 encoding of s_waitcnt.
+// Workgroup barrier without the memory fence of __syncthreads(): LDS reads that are still in flight
+// (fragments requested ahead of their use) need not drain first.  What a barrier publishes here are
+// LDS-direct copies, and the copying wave has waited for those (dma_wait) before it arrives.
+// (Written as assembly so that the compiler does not drain the LDS counter in front of it.)
+__device__ __forceinline__ void wg_barrier() {
+  asm volatile("s_barrier" ::: "memory");
+}
 template <int NEWER>
 __device__ __forceinline__ void dma_wait() {
   static_assert(NEWER >= 0 && NEWER < 64, "vmcnt is a 6-bit counter");
@@ -134,10 +148,20 @@ __device__ __forceinline__ void dma_wait() {
 // Debug build only: per-phase timestamps of one workgroup, read back by ba_debug_read_trace().
 constexpr int kTraceTiles = 80, kTraceMarks = 8;
 __device__ long long g_trace[8][kTraceTiles][kTraceMarks];
-#define BA_MARK(tile, m)                                                                   \
+#define BA_MARK_ALWAYS(tile, m)                                                            \
   do {                                                                                     \
     if (trace_on && (tile) < kTraceTiles && lane == 0) g_trace[wave][tile][m] = clock64(); \
   } while (0)
+#define BA_WALL(tile, m)                                                                        \
+  do {                                                                                          \
+    if (trace_on && (tile) < kTraceTiles && lane == 0) g_trace[wave][tile][m] = wall_clock64(); \
+  } while (0)
+#else
+#define BA_MARK_ALWAYS(tile, m) do { } while (0)
+#define BA_WALL(tile, m) do { } while (0)
+#endif
+#ifdef BA_TRACE_TILES
+#define BA_MARK(tile, m) BA_MARK_ALWAYS(tile, m)
 #else
 #define BA_MARK(tile, m) do { } while (0)
 #endif
@@ -174,7 +198,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
 #ifdef BA_TRACE
   const bool trace_on = blockIdx.x == 17;
 #endif
-  BA_MARK(79, 0);
+  BA_MARK_ALWAYS(79, 0);
+  BA_WALL(78, 0);
   const int Gq = p.group;
   const int n_rows = pr.lq * Gq;
   const int row0 = pr.jt * kTileRows;
@@ -189,13 +214,333 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
   const int t_end = (int)((int64_t)nt * (split + 1) / p.n_splits);
   const int n_t = t_end - t_begin;
 
-  // ---- Q fragments (B operand of S^T = K Q^T): rotated in registers if asked, and multiplied
-  //      by scale * log2(e) before the one rounding to bf16 -----------------------------------------
-  const float c2 = p.scale_log2e;
-  bf16x8_t qf[G::KCH];
   const int my_row = row0 + wave * 32 + col;
   const bool row_ok = my_row < n_rows;
   const int my_tok = my_row / Gq;  // query token (inside the problem) of this lane's column
+  const float c2 = p.scale_log2e;
+  bf16x8_t qf[G::KCH];  // Q fragments, filled below once the first tile copies are on their way
+
+  // ---- per-lane LDS read offsets, relative to a tile buffer; the rest of an address is a
+  //      wave-uniform buffer offset plus compile-time constants ------------------------------------
+  uint32_t k_rd[G::KCH];  // K fragment (keys 0..31): row `col`, chunk 2 kk + hf, swizzled
+  {
+    const int swz = (col / G::LPR) & (G::CPR - 1);
+#pragma unroll
+    for (int kk = 0; kk < G::KCH; ++kk) k_rd[kk] = col * G::ROWB + (((kk * 2 + hf) ^ swz) << 4);
+  }
+  uint32_t v_rd[G::DT];  // V^T fragment (16-key step 0, low half)
+  {
+    const int vrow = hf * 4 + ((lane & 15) >> 2);
+    const int vwithin = ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+    const int swz = (vrow / G::LPR) & (G::GPR - 1);
+#pragma unroll
+    for (int dt = 0; dt < G::DT; ++dt) v_rd[dt] = vrow * G::ROWB + ((dt ^ swz) << 6) + vwithin;
+  }
+
+  // ---- tile fill: which source chunk each lane fetches for its fixed LDS position ----------------
+  // One wave instruction fills 1024 contiguous LDS bytes, lane i writing [16 i, 16 i + 16); the
+  // swizzle is applied on the GLOBAL side.  Rows at or beyond a tile's valid count re-read its
+  // last valid row: their scores are masked, and a finite duplicate keeps 0 * v equal to 0.
+  const char *kc_base = (const char *)(p.kc + (int64_t)pr.ctx0 * p.kc_st + (int64_t)kvh * p.kc_sh);
+  const char *vc_base = (const char *)(p.vc + (int64_t)pr.ctx0 * p.vc_st + (int64_t)kvh * p.vc_sh);
+  const char *kf_base = (const char *)(p.kf + (int64_t)pr.q_tok0 * p.kf_st + (int64_t)kvh * p.kf_sh);
+  const char *vf_base = (const char *)(p.vf + (int64_t)pr.q_tok0 * p.vf_st + (int64_t)kvh * p.vf_sh);
+  const uint32_t kc_rb = (uint32_t)p.kc_st * 2u, vc_rb = (uint32_t)p.vc_st * 2u;  // row strides, bytes
+  const uint32_t kf_rb = (uint32_t)p.kf_st * 2u, vf_rb = (uint32_t)p.vf_st * 2u;
+  // Waves 0..3 fetch the K tiles and waves 4..7 the V tiles (see the walk below), so each wave
+  // keeps the addressing of one kind only.
+  const bool role_b = wave >= kWaves / 2;
+  const char *c_base = role_b ? vc_base : kc_base;  // context segment of this wave's kind
+  const char *f_base = role_b ? vf_base : kf_base;  // causal segment
+  const uint32_t c_rb = role_b ? vc_rb : kc_rb, f_rb = role_b ? vf_rb : kf_rb;
+  // Tiles [0, n_full_prim) of the problem are full tiles of its first ("primary") segment: they
+  // take the short path with cached lane offsets.
+  const bool prim_ctx = n_ctx_tiles > 0;
+  const char *prim_base = prim_ctx ? c_base : f_base;
+  const uint32_t prim_rb = prim_ctx ? c_rb : f_rb;
+  const int n_full_prim = (prim_ctx ? pr.tctx : pr.lq) / kTileKeys;
+  int g_row[G::IPW];
+  uint32_t g_chunk[G::IPW];  // byte offset of the source chunk inside its row
+  uint32_t g_src[G::IPW];    // full per-lane byte offsets inside a full primary tile
+#pragma unroll
+  for (int i = 0; i < G::IPW; ++i) {
+    const int row = ((wave & (kWaves / 2 - 1)) * G::IPW + i) * G::RPI + lane / G::CPR;
+    const int pos = lane % G::CPR;
+    g_row[i] = row;
+    const uint32_t kchunk = (uint32_t)(pos ^ ((row / G::LPR) & (G::CPR - 1))) << 4;
+    const uint32_t vchunk = (uint32_t)((((pos >> 2) ^ ((row / G::LPR) & (G::GPR - 1))) << 2) | (pos & 3)) << 4;
+    g_chunk[i] = role_b ? vchunk : kchunk;
+    g_src[i] = (uint32_t)row * prim_rb + g_chunk[i];
+  }
+  const uint32_t lds_copy =
+      (uint32_t)(uintptr_t)smem + (role_b ? VBASE : 0u) + (wave & (kWaves / 2 - 1)) * G::IPW * 1024;
+  // Copy of tile t of the problem into buffer `buf` of this wave's kind: a wave-uniform
+  // preparation and IPW wave instructions, kept apart so that the instructions can be spread over
+  // the gaps of an MFMA stream.
+  struct CopyJob {
+    const char *ptr;  // first row of the tile
+    uint32_t dst;     // LDS byte address of this wave's first 1 KB piece
+    uint32_t rb;      // row stride, bytes
+    int valid;        // rows of the tile that exist; kTileKeys on the short path
+    bool full;        // full tile of the primary segment: cached lane offsets
+  };
+  auto copy_prepare = [&](int t, int buf) __attribute__((always_inline)) {
+    CopyJob c;
+    c.dst = lds_copy + (uint32_t)buf * TB;
+    c.full = t < n_full_prim;
+    if (c.full) {
+      c.ptr = prim_base + (uint64_t)(uint32_t)t * (uint64_t)(prim_rb * (uint32_t)kTileKeys);
+      c.rb = prim_rb;
+      c.valid = kTileKeys;
+    } else {
+      asm volatile("" ::: "memory");  // rare: keep it out of the short path
+      const bool isctx = t < n_ctx_tiles;
+      const int tc = isctx ? t : t - n_ctx_tiles;
+      c.rb = isctx ? c_rb : f_rb;
+      c.ptr = (isctx ? c_base : f_base) + (uint64_t)(uint32_t)tc * (uint64_t)(c.rb * (uint32_t)kTileKeys);
+      c.valid = min(kTileKeys, (isctx ? pr.tctx : pr.lq) - tc * kTileKeys);
+    }
+    return c;
+  };
+  auto copy_part = [&](const CopyJob &c, int i) __attribute__((always_inline)) {
+    if (c.full) {
+      lds_dma16(c.ptr, g_src[i], c.dst + i * 1024);
+    } else {
+      asm volatile("" ::: "memory");
+      lds_dma16(c.ptr, (uint32_t)min(g_row[i], c.valid - 1) * c.rb + g_chunk[i], c.dst + i * 1024);
+    }
+  };
+  auto issue_tile = [&](int t, int buf) __attribute__((always_inline)) {
+    const CopyJob c = copy_prepare(t, buf);
+#pragma unroll
+    for (int i = 0; i < G::IPW; ++i) copy_part(c, i);
+  };
+
+  // ---- running state -----------------------------------------------------------------------------
+  f32x16_t oacc[G::DT];
+#pragma unroll
+  for (int dt = 0; dt < G::DT; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
+  float mb = 0.f;      // the row's reference, log2 units
+  float l_run = 0.f;   // this lane's share of the running sum of exponentials
+  const int first_tok_wave = (row0 + wave * 32) / Gq;
+
+  // K fragment of QK step `step` = kk * 2 + a (keys 32a..32a+31, head dims 16kk..16kk+15) and
+  // V^T fragment (key step kc, head dims 32dt..32dt+31), from tile buffers at LDS byte offsets
+  auto read_k = [&](uint32_t kofs, int step) __attribute__((always_inline)) {
+    const int a = step & 1, kk = step >> 1;
+    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(
+        smem + (k_rd[kk] + kofs) + a * 32 * G::ROWB);
+  };
+  auto read_v = [&](uint32_t vofs, int kc, int dt) __attribute__((always_inline)) {
+    typedef __attribute__((address_space(3))) s16x4_t lds_s16x4;
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4 *)(smem + (v_rd[dt] + vofs) + kc * 16 * G::ROWB));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4 *)(smem + (v_rd[dt] + vofs) + (kc * 16 + 8) * G::ROWB));
+    const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, both);
+  };
+  // The MFMA block of one tile: O^T += V^T P^T from the V tile at vofs, then (if there is a next
+  // tile) S'^T = K Q'^T - reference from the K tile at kofs: sacc[a] is keys 32a..32a+31 x this
+  // wave's 32 queries, already the base-2 exponent.  The block is one stream of NS steps, one
+  // MFMA each (PV: 16-key step kc x 32-dim slab dt; QK: 16-dim step kk x key half a), and the
+  // fragment of step s + W - 1 is requested right before the MFMA of step s: a rolling window of
+  // W fragments that keeps W - 1 MFMAs between every LDS read and its use.  The window is primed
+  // (preload) before the barrier that starts the block, so the block opens with an MFMA.
+  constexpr int NPV = 4 * G::DT;
+  constexpr int NQK = 2 * G::KCH;
+  constexpr int NS = NPV + NQK;
+  constexpr int W = 8;
+  static_assert(W - 1 <= NPV, "the window is primed with V fragments only");
+  static_assert(2 * G::IPW <= NPV, "one copy instruction behind every second PV step");
+  auto frag_read = [&](int st, uint32_t vofs, uint32_t kofs) __attribute__((always_inline)) {
+    return st < NPV ? read_v(vofs, st / G::DT, st % G::DT) : read_k(kofs, st - NPV);
+  };
+  auto preload = [&](uint32_t vofs, bf16x8_t (&fr)[W]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int st = 0; st < W - 1; ++st) fr[st] = frag_read(st, vofs, 0);
+  };
+  // (the K fragments are requested whether or not a next tile exists: the buffer is inside LDS
+  // either way and without a next tile nothing consumes them)
+  // The wave has issue slots to spare while its MFMAs execute, so the block also carries this
+  // wave's share of a tile copy (`copy`: tile t_copy into buffer buf_copy), one LDS-direct load
+  // behind every second MFMA, and builds the tuple the score accumulators start from.
+  // `steady` (compile time): a next tile exists and the copy is a full tile of the primary segment
+  // at cp_ptr; otherwise both are decided at run time and the copy source is worked out in full.
+  auto mfma_block = [&](auto steady_c, uint32_t vofs, uint32_t kofs, bool more, bool copy, int t_copy,
+                        int buf_copy, const char *cp_ptr, const bf16x8_t (&pf)[4], f32x16_t (&sacc)[2],
+                        bf16x8_t (&fr)[W]) __attribute__((always_inline)) {
+    constexpr bool steady = decltype(steady_c)::value;
+#ifdef BA_VAR_NOMFMA
+    return;
+#endif
+    CopyJob cj;
+    if (!steady && copy) cj = copy_prepare(t_copy, buf_copy);
+    const uint32_t cp_dst = lds_copy + (uint32_t)buf_copy * TB;
+#pragma unroll
+    for (int st = 0; st < NPV; ++st) {
+      if (st + W - 1 < NS) fr[(st + W - 1) % W] = frag_read(st + W - 1, vofs, kofs);
+      const int kc = st / G::DT, dt = st % G::DT;
+      oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % W], pf[kc], oacc[dt], 0, 0, 0);
+      if ((st & 1) && st / 2 < G::IPW) {
+#ifndef BA_VAR_NOCOPY
+        if (steady) lds_dma16(cp_ptr, g_src[st / 2], cp_dst + (st / 2) * 1024);
+        else if (copy) copy_part(cj, st / 2);
+#endif
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (steady || more) {
+#pragma unroll
+      for (int st = NPV; st < NS; ++st) {
+        if (st + W - 1 < NS) fr[(st + W - 1) % W] = frag_read(st + W - 1, vofs, kofs);
+        const int q = st - NPV, a = q & 1, kk = q >> 1;
+        if (kk == 0) {
+          // the accumulator starts at minus the row's reference: the MFMA result is the exponent
+          f32x16_t negmb;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) negmb[v] = -mb;
+          sacc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % W], qf[kk], negmb, 0, 0, 0);
+        } else {
+          sacc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % W], qf[kk], sacc[a], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+  // QK of the very first tile (nothing to overlap it with; the reference is still 0)
+  auto qk_first = [&](uint32_t kofs, f32x16_t (&sacc)[2]) __attribute__((always_inline)) {
+    bf16x8_t fr[W];
+#pragma unroll
+    for (int q = 0; q < W - 1; ++q) fr[q] = read_k(kofs, q);
+#pragma unroll
+    for (int q = 0; q < NQK; ++q) {
+      if (q + W - 1 < NQK) fr[(q + W - 1) % W] = read_k(kofs, q + W - 1);
+      const int a = q & 1, kk = q >> 1;
+      f32x16_t zero;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+      sacc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[q % W], qf[kk], kk == 0 ? zero : sacc[a], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // Row maxima of a score tile.
+  auto row_max = [&](const f32x16_t (&sacc)[2]) __attribute__((always_inline)) {
+    float m0 = sacc[0][0];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) m0 = fmaxf(m0, sacc[a][v]);
+    return fmaxf(m0, other_half(m0));
+  };
+  // Move the reference by `shift`: exponents, running sum and output accumulators are all
+  // re-expressed relative to the new reference.
+  auto rebase = [&](f32x16_t (&sacc)[2], float shift) __attribute__((always_inline)) {
+    const float alpha = __builtin_amdgcn_exp2f(-shift);
+    mb += shift;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sacc[a][v] -= shift;
+    l_run *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < G::DT; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+  };
+  // P = 2^S' rounded to bf16 (the B operand of PV); returns this lane's fp32 sum of the
+  // exponentials.  (Plain adds on purpose: v_dot2c_f32_bf16 would add a packed pair in one
+  // instruction, but it executes on the matrix pipe and slows to a crawl next to the other
+  // wave's MFMAs.)
+  auto exponentials = [&](const f32x16_t (&sacc)[2], bf16x8_t (&pf)[4]) __attribute__((always_inline)) {
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        u32x4_t w;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float p0 = __builtin_amdgcn_exp2f(sacc[a][e * 8 + 2 * i]);
+          const float p1 = __builtin_amdgcn_exp2f(sacc[a][e * 8 + 2 * i + 1]);
+          s0 += p0;
+          s1 += p1;
+          w[i] = pack_bf16(p0, p1);
+        }
+        pf[a * 2 + e] = __builtin_bit_cast(bf16x8_t, w);
+      }
+    }
+    return s0 + s1;
+  };
+  // The softmax step of one tile: mask where needed (diagonal and ragged tiles only), turn the
+  // exponents into P, and keep the running sum.  All branches are wave-uniform.
+  auto softmax = [&](int t, bool first, f32x16_t (&sacc)[2], bf16x8_t (&pf)[4]) __attribute__((always_inline)) {
+#ifdef BA_VAR_NOSM
+    if (!first) return;
+#endif
+    const bool isctx = t < n_ctx_tiles;
+    const int tc = isctx ? t : t - n_ctx_tiles;
+    const int valid = min(kTileKeys, (isctx ? pr.tctx : pr.lq) - tc * kTileKeys);
+    const int key0 = tc * kTileKeys;
+    const bool need_mask = isctx ? (valid < kTileKeys) : (key0 + kTileKeys - 1 > first_tok_wave) || (valid < kTileKeys);
+    if (need_mask) {
+      asm volatile("" ::: "memory");  // keep this a real branch: never speculate the selects
+      const int lim = isctx ? valid : min(my_tok - key0 + 1, valid);  // visible keys in this tile
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = a * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+          if (key >= lim) sacc[a][v] = -INFINITY;
+        }
+    }
+    if (first) {
+      // the first tile sets the reference: its row maximum whatever the sign (nothing visible
+      // yet: stay at 0), so a row's largest exponential so far is exactly 1
+      asm volatile("" ::: "memory");
+      const float mx = row_max(sacc);
+      const float shift = mx == -INFINITY ? 0.f : mx;
+      mb = shift;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sacc[a][v] -= shift;
+    }
+    float tsum = exponentials(sacc, pf);
+    if (__builtin_amdgcn_ballot_w64(!(tsum < kRebaseAbove)) != 0) {  // overflow guard: practically never
+      asm volatile("" ::: "memory");
+      rebase(sacc, fmaxf(row_max(sacc), 0.f));  // only ever raise the reference here
+      tsum = exponentials(sacc, pf);
+    }
+    l_run += tsum;
+  };
+  // ---- the walk over the key tiles ------------------------------------------------------------------
+  // Tile i (counted from t_begin) has its K in K buffer i % 4 and its V in V buffer i % 4.  Every wave
+  // runs the same chain  softmax(i), PV(i), QK(i+1)  but the two waves of a SIMD (w and w + 4) run
+  // it half a period apart: time is cut into half-periods that end in a workgroup barrier, and in
+  // each of them one wave of a SIMD is in its exponentials (VALU) while the other is in its MFMA
+  // block, so that neither unit waits for the other.
+  //     half-period   -1      0        1            2            3         ...
+  //     waves 0..3   QK(0)  SM(0)  PV(0) QK(1)    SM(1)      PV(1) QK(2)
+  //     waves 4..7     -    QK(0)    SM(0)     PV(0) QK(1)     SM(1)
+  // The softmax half has slack (MFMA is the longer half), so the copies are issued there: waves
+  // 0..3 fetch K(i+3) after softmax(i), waves 4..7 fetch V(i+3), each then waits until the tile it
+  // started two iterations earlier (K(i+1) resp. V(i+1)) has landed, and the barrier that ends the
+  // half-period publishes it.  A buffer is refilled only after the barrier that follows its last
+  // reader (K(i-1): waves 4..7 in half-period 2i-2; V(i-1): waves 4..7 in half-period 2i).
+  if (n_t > 0) {
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      if (j < n_t) issue_tile(t_begin + j, j);
+    }
+  }
+  BA_MARK_ALWAYS(79, 1);
+
+  // ---- Q fragments (B operand of S^T = K Q^T): rotated in registers if asked, and multiplied
+  //      by scale * log2(e) before the one rounding to bf16 -----------------------------------------
   {
     const int g = my_row - my_tok * Gq;
     const int head = kvh * Gq + g;
@@ -248,310 +593,59 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
 #pragma unroll
     for (int kk = 0; kk < G::KCH; ++kk) qf[kk] = __builtin_bit_cast(bf16x8_t, raw[kk]);
   }
-  BA_MARK(79, 1);
-
-  // ---- per-lane LDS read offsets, relative to a tile buffer; the rest of an address is a
-  //      wave-uniform buffer offset plus compile-time constants ------------------------------------
-  uint32_t k_rd[G::KCH];  // K fragment (keys 0..31): row `col`, chunk 2 kk + hf, swizzled
-  {
-    const int swz = (col / G::LPR) & (G::CPR - 1);
-#pragma unroll
-    for (int kk = 0; kk < G::KCH; ++kk) k_rd[kk] = col * G::ROWB + (((kk * 2 + hf) ^ swz) << 4);
-  }
-  uint32_t v_rd[G::DT];  // V^T fragment (16-key step 0, low half)
-  {
-    const int vrow = hf * 4 + ((lane & 15) >> 2);
-    const int vwithin = ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
-    const int swz = (vrow / G::LPR) & (G::GPR - 1);
-#pragma unroll
-    for (int dt = 0; dt < G::DT; ++dt) v_rd[dt] = vrow * G::ROWB + ((dt ^ swz) << 6) + vwithin;
-  }
-
-  // ---- tile fill: which source chunk each lane fetches for its fixed LDS position ----------------
-  // One wave instruction fills 1024 contiguous LDS bytes, lane i writing [16 i, 16 i + 16); the
-  // swizzle is applied on the GLOBAL side.  Rows at or beyond a tile's valid count re-read its
-  // last valid row: their scores are masked, and a finite duplicate keeps 0 * v equal to 0.
-  const char *kc_base = (const char *)(p.kc + (int64_t)pr.ctx0 * p.kc_st + (int64_t)kvh * p.kc_sh);
-  const char *vc_base = (const char *)(p.vc + (int64_t)pr.ctx0 * p.vc_st + (int64_t)kvh * p.vc_sh);
-  const char *kf_base = (const char *)(p.kf + (int64_t)pr.q_tok0 * p.kf_st + (int64_t)kvh * p.kf_sh);
-  const char *vf_base = (const char *)(p.vf + (int64_t)pr.q_tok0 * p.vf_st + (int64_t)kvh * p.vf_sh);
-  const uint32_t kc_rb = (uint32_t)p.kc_st * 2u, vc_rb = (uint32_t)p.vc_st * 2u;  // row strides, bytes
-  const uint32_t kf_rb = (uint32_t)p.kf_st * 2u, vf_rb = (uint32_t)p.vf_st * 2u;
-  const bool prim_ctx = n_ctx_tiles > 0;  // the segment whose full tiles get cached lane offsets
-  int g_row[G::IPW];
-  uint32_t g_kchunk[G::IPW], g_vchunk[G::IPW];  // byte offset of the source chunk inside its row
-  uint32_t k_src[G::IPW], v_src[G::IPW];        // full per-lane byte offsets for a full primary tile
-#pragma unroll
-  for (int i = 0; i < G::IPW; ++i) {
-    const int row = ((wave & (kWaves / 2 - 1)) * G::IPW + i) * G::RPI + lane / G::CPR;
-    const int pos = lane % G::CPR;
-    g_row[i] = row;
-    g_kchunk[i] = (uint32_t)(pos ^ ((row / G::LPR) & (G::CPR - 1))) << 4;
-    g_vchunk[i] = (uint32_t)((((pos >> 2) ^ ((row / G::LPR) & (G::GPR - 1))) << 2) | (pos & 3)) << 4;
-    k_src[i] = (uint32_t)row * (prim_ctx ? kc_rb : kf_rb) + g_kchunk[i];
-    v_src[i] = (uint32_t)row * (prim_ctx ? vc_rb : vf_rb) + g_vchunk[i];
-  }
-  // (only waves 0..3 copy: they have slack at the end of every iteration, see below)
-  const uint32_t lds_wave = (uint32_t)(uintptr_t)smem + (wave & (kWaves / 2 - 1)) * G::IPW * 1024;
-  auto issue_k = [&](int t, uint32_t dst) {  // tile t of the problem -> LDS byte offset dst
-    const bool isctx = t < n_ctx_tiles;
-    const int tc = isctx ? t : t - n_ctx_tiles;
-    const uint32_t rb = isctx ? kc_rb : kf_rb;
-    const char *ptr = (isctx ? kc_base : kf_base) + (uint64_t)(uint32_t)tc * (uint64_t)(rb * (uint32_t)kTileKeys);
-    const int valid = min(kTileKeys, (isctx ? pr.tctx : pr.lq) - tc * kTileKeys);
-    if (valid == kTileKeys && isctx == prim_ctx) {
-#pragma unroll
-      for (int i = 0; i < G::IPW; ++i) lds_dma16(ptr, k_src[i], lds_wave + dst + i * 1024);
+  BA_MARK_ALWAYS(79, 2);
+  dma_wait<0>();  // unconditional: first tiles and Q fragments are complete from here on
+  BA_MARK_ALWAYS(79, 3);
+  f32x16_t sacc[2];
+  bf16x8_t pf[4];
+  bf16x8_t fr[W];
+  if (n_t > 0) {
+    if (!role_b) {
+      wg_barrier();  // tiles 0..2 of both kinds are visible
+      qk_first(0, sacc);
+      wg_barrier();
     } else {
-#pragma unroll
-      for (int i = 0; i < G::IPW; ++i)
-        lds_dma16(ptr, (uint32_t)min(g_row[i], valid - 1) * rb + g_kchunk[i], lds_wave + dst + i * 1024);
+      wg_barrier();
+      wg_barrier();
+      qk_first(0, sacc);
+      wg_barrier();
     }
-  };
-  auto issue_v = [&](int t, uint32_t dst) {
-    const bool isctx = t < n_ctx_tiles;
-    const int tc = isctx ? t : t - n_ctx_tiles;
-    const uint32_t rb = isctx ? vc_rb : vf_rb;
-    const char *ptr = (isctx ? vc_base : vf_base) + (uint64_t)(uint32_t)tc * (uint64_t)(rb * (uint32_t)kTileKeys);
-    const int valid = min(kTileKeys, (isctx ? pr.tctx : pr.lq) - tc * kTileKeys);
-    if (valid == kTileKeys && isctx == prim_ctx) {
-#pragma unroll
-      for (int i = 0; i < G::IPW; ++i) lds_dma16(ptr, v_src[i], lds_wave + dst + i * 1024);
-    } else {
-#pragma unroll
-      for (int i = 0; i < G::IPW; ++i)
-        lds_dma16(ptr, (uint32_t)min(g_row[i], valid - 1) * rb + g_vchunk[i], lds_wave + dst + i * 1024);
-    }
-  };
-
-  // ---- running state -----------------------------------------------------------------------------
-  f32x16_t oacc[G::DT];
-#pragma unroll
-  for (int dt = 0; dt < G::DT; ++dt)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
-  float mb = 0.f;      // the row's reference, log2 units
-  f32x16_t negmb;      // -mb in every entry: where the score accumulators start
-#pragma unroll
-  for (int v = 0; v < 16; ++v) negmb[v] = 0.f;
-  float l_run = 0.f;   // this lane's share of the running sum of exponentials
-  const int first_tok_wave = (row0 + wave * 32) / Gq;
-
-  // S'^T = K Q'^T - reference, from the K tile at LDS byte offset kofs: sacc[a] is keys
-  // 32a..32a+31 x this wave's 32 queries, already the base-2 exponent.  The 2 * KCH steps go in
-  // groups of four; a group's K fragments are read while the previous group's MFMAs run.
-  auto qk = [&](uint32_t kofs, f32x16_t (&sacc)[2]) {
-    constexpr int STEPS = 2 * G::KCH;  // step = kk * 2 + a: consecutive MFMAs are independent
-    constexpr int GS = 4;
-    constexpr int NG = STEPS / GS;
-    auto read_k = [&](int step) {
-      const int a = step & 1, kk = step >> 1;
-      return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(
-          smem + (k_rd[kk] + kofs) + a * 32 * G::ROWB);
-    };
-    bf16x8_t fr[2][GS];
-#pragma unroll
-    for (int j = 0; j < GS; ++j) fr[0][j] = read_k(j);
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      if (g + 1 < NG) {
-#pragma unroll
-        for (int j = 0; j < GS; ++j) fr[(g + 1) & 1][j] = read_k((g + 1) * GS + j);
-      }
-#pragma unroll
-      for (int j = 0; j < GS; ++j) {
-        const int step = g * GS + j, a = step & 1, kk = step >> 1;
-        sacc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[g & 1][j], qf[kk], kk == 0 ? negmb : sacc[a], 0, 0, 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  // Row maxima of a score tile, then move the reference there: exponents, running sum and
-  // output accumulators are all re-expressed relative to the new reference.  Runs on a wave's
-  // first tile and, after that, only when an exponential grew past kRebaseAbove.
-  auto rebase = [&](f32x16_t (&sacc)[2], bool first) {
-    float m0 = sacc[0][0];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) m0 = fmaxf(m0, sacc[a][v]);
-    const float mx = fmaxf(m0, other_half(m0));
-    // first tile: take the maximum whatever its sign (nothing visible: keep 0); later: only raise
-    const float shift = first ? (mx == -INFINITY ? 0.f : mx) : fmaxf(mx, 0.f);
-    const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-shift);
-    mb += shift;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) negmb[v] = -mb;
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sacc[a][v] -= shift;
-    l_run *= alpha;
-#pragma unroll
-    for (int dt = 0; dt < G::DT; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
-  };
-  // P = 2^S' rounded to bf16 (the B operand of PV); returns this lane's fp32 sum of the exponentials
-  auto exponentials = [&](const f32x16_t (&sacc)[2], bf16x8_t (&pf)[4]) {
-    float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        u32x4_t w;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float p0 = __builtin_amdgcn_exp2f(sacc[a][e * 8 + 2 * i]);
-          const float p1 = __builtin_amdgcn_exp2f(sacc[a][e * 8 + 2 * i + 1]);
-          s0 += p0;
-          s1 += p1;
-          w[i] = pack_bf16(p0, p1);
-        }
-        pf[a * 2 + e] = __builtin_bit_cast(bf16x8_t, w);
-      }
-    }
-    return s0 + s1;
-  };
-  // The softmax step of one tile: mask where needed (diagonal and ragged tiles only), turn the
-  // exponents into P, and keep the running sum.  All branches are wave-uniform.
-  auto softmax = [&](int t, bool first, f32x16_t (&sacc)[2], bf16x8_t (&pf)[4]) {
-    const bool isctx = t < n_ctx_tiles;
-    const int tc = isctx ? t : t - n_ctx_tiles;
-    const int valid = min(kTileKeys, (isctx ? pr.tctx : pr.lq) - tc * kTileKeys);
-    const int key0 = tc * kTileKeys;
-    const bool need_mask = isctx ? (valid < kTileKeys) : (key0 + kTileKeys - 1 > first_tok_wave) || (valid < kTileKeys);
-    if (need_mask) {
-      asm volatile("" ::: "memory");  // keep this a real branch: never speculate the selects
-      const int lim = isctx ? valid : min(my_tok - key0 + 1, valid);  // visible keys in this tile
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = a * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-          if (key >= lim) sacc[a][v] = -INFINITY;
-        }
-    }
-    if (first) {
-      asm volatile("" ::: "memory");
-      rebase(sacc, true);
-    }
-    float tsum = exponentials(sacc, pf);
-    if (__builtin_amdgcn_ballot_w64(!(tsum < kRebaseAbove)) != 0) {  // overflow guard: practically never
-      asm volatile("" ::: "memory");
-      rebase(sacc, false);
-      tsum = exponentials(sacc, pf);
-    }
-    l_run += tsum;
-  };
-  // O^T += V^T P^T from the V tile at LDS byte offset vofs; fragments of a 16-key step are
-  // read one step ahead of the MFMAs that consume them.
-  auto pv_mma = [&](uint32_t vofs, const bf16x8_t (&pf)[4]) {
-    typedef __attribute__((address_space(3))) s16x4_t lds_s16x4;
-    typedef short s16x8_t __attribute__((ext_vector_type(8)));
-    auto read_v = [&](int kc, int dt) {
-      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (lds_s16x4 *)(smem + (v_rd[dt] + vofs) + kc * 16 * G::ROWB));
-      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (lds_s16x4 *)(smem + (v_rd[dt] + vofs) + (kc * 16 + 8) * G::ROWB));
-      const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      return __builtin_bit_cast(bf16x8_t, both);
-    };
-    bf16x8_t fr[2][G::DT];
-#pragma unroll
-    for (int dt = 0; dt < G::DT; ++dt) fr[0][dt] = read_v(0, dt);
-#pragma unroll
-    for (int kc = 0; kc < 4; ++kc) {
-      if (kc + 1 < 4) {
-#pragma unroll
-        for (int dt = 0; dt < G::DT; ++dt) fr[(kc + 1) & 1][dt] = read_v(kc + 1, dt);
-      }
-#pragma unroll
-      for (int dt = 0; dt < G::DT; ++dt)
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[kc & 1][dt], pf[kc], oacc[dt], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-
-  // ---- the walk over the key tiles ------------------------------------------------------------------
-  // Tile i (counted from t_begin) has its K in K buffer i % 4 and its V in V buffer i % 3.  At the
-  // start of iteration i the copying waves start the copies of K(i+3) and V(i+2); at its end they wait
-  // for the copies started one iteration EARLIER (K(i+2), V(i+1)), then all waves meet at the
-  // barrier.  Waves 0..3 (role A) run  QK(i), softmax(i), PV(i)  inside iteration i; waves 4..7
-  // (role B) run  softmax(i), PV(i), QK(i+1).  Waves w and w + 4 share a SIMD, so while one is
-  // in its VALU phase the other is in an MFMA phase instead of both queueing for the same unit.
-  // Role B is the longer chain (the SIMD arbitrates oldest wave first), so role A alone issues
-  // the copies and waits for them.
-  const bool role_b = wave >= kWaves / 2;
-  uint32_t vo0 = VBASE, vo1 = VBASE + TB, vo2 = VBASE + 2 * TB;  // V buffers of tiles i, i+1, i+2
-  if (!role_b && n_t > 0) {
-    issue_k(t_begin, 0);
-    issue_v(t_begin, vo0);
-    if (n_t > 1) {
-      issue_k(t_begin + 1, TB);
-      issue_v(t_begin + 1, vo1);
-    }
-    if (n_t > 2) issue_k(t_begin + 2, 2 * TB);
-  }
-  BA_MARK(79, 2);
-  dma_wait<0>();  // unconditional: the Q fragment loads are then known to be complete in the loops
-  __syncthreads();
-  BA_MARK(79, 3);
-  // one iteration's copies (role A only) and the end of an iteration
-  auto start_copies = [&](int i) {
-    if (i + 3 < n_t) issue_k(t_begin + i + 3, ((i + 3) & (kNumKBuf - 1)) * TB);
-    if (i + 2 < n_t) issue_v(t_begin + i + 2, vo2);
-  };
-  auto rotate_v = [&]() {
-    const uint32_t v_t = vo0;
-    vo0 = vo1;
-    vo1 = vo2;
-    vo2 = v_t;
-  };
-  if (!role_b) {
-#pragma unroll 1
-    for (int i = 0; i < n_t; ++i) {
-      start_copies(i);
-      f32x16_t sacc[2];
-      bf16x8_t pf[4];
-      BA_MARK(i, 0);
-      qk((i & (kNumKBuf - 1)) * TB, sacc);
-      BA_MARK(i, 1);
+    // One iteration.  Iterations whose copy (tile i+3) is a full tile of the primary segment run a
+    // version with every such decision made at compile time and the source pointer carried along.
+    auto iteration = [&](auto steady_c, int i, const char *cp_ptr) __attribute__((always_inline)) {
+      constexpr bool steady = decltype(steady_c)::value;
       softmax(t_begin + i, i == 0, sacc, pf);
-      BA_MARK(i, 2);
-      pv_mma(vo0, pf);
-      BA_MARK(i, 3);
-      rotate_v();
-      if (i + 3 < n_t) dma_wait<2 * G::IPW>(); else dma_wait<0>();
-      BA_MARK(i, 4);
-      __syncthreads();  // K(i+2) and V(i+1) have landed; the buffers of tile i are free
-      BA_MARK(i, 5);
-    }
-  } else {
-    f32x16_t sacc[2];
-    if (n_t > 0) qk(0, sacc);
+      // tile i+1 of this wave's kind must have landed before the barrier; the only copy that
+      // may be younger is tile i+2's (tile i+3's starts inside the MFMA block below)
+#ifndef BA_VAR_NOWAIT
+      if (steady || i + 2 < n_t) dma_wait<G::IPW>(); else dma_wait<0>();
+#endif
+      const uint32_t vofs = VBASE + (i & (kNumVBuf - 1)) * TB;
+      preload(vofs, fr);
+      wg_barrier();
+      mfma_block(steady_c, vofs, ((i + 1) & (kNumKBuf - 1)) * TB, i + 1 < n_t, i + 3 < n_t, t_begin + i + 3,
+                 (i + 3) & (kNumKBuf - 1), cp_ptr, pf, sacc, fr);
+      if (steady || !role_b || i + 1 < n_t) wg_barrier();
+    };
+    const int n_steady = max(0, min(n_t, n_full_prim - t_begin) - 3);
+    const uint64_t tile_bytes = (uint64_t)(prim_rb * (uint32_t)kTileKeys);
+    const char *cp_ptr = prim_base + (uint64_t)(uint32_t)(t_begin + 3) * tile_bytes;
+    int i = 0;
 #pragma unroll 1
-    for (int i = 0; i < n_t; ++i) {
-      bf16x8_t pf[4];
-      BA_MARK(i, 0);
-      softmax(t_begin + i, i == 0, sacc, pf);
-      BA_MARK(i, 1);
-      pv_mma(vo0, pf);
-      BA_MARK(i, 2);
-      if (i + 1 < n_t) qk(((i + 1) & (kNumKBuf - 1)) * TB, sacc);
-      BA_MARK(i, 3);
-      rotate_v();
-      BA_MARK(i, 4);
-      __syncthreads();
-      BA_MARK(i, 5);
+    for (; i < n_steady; ++i) {
+      iteration(std::true_type{}, i, cp_ptr);
+      cp_ptr += tile_bytes;
     }
+#pragma unroll 1
+    for (; i < n_t; ++i) iteration(std::false_type{}, i, nullptr);
   }
-  BA_MARK(79, 4);
-  static_assert((kNumKBuf & (kNumKBuf - 1)) == 0 && kNumVBuf == 3, "buffer rotation above assumes 4 and 3");
+  BA_MARK_ALWAYS(79, 4);
+  static_assert(kNumKBuf == 4 && kNumVBuf == 4, "the copy distances above assume four buffers of each kind");
 
   // ---- epilogue: each wave transposes its O^T through its own slice of LDS, half of the head
-  //      dimension at a time, so that rows leave as contiguous lines (all waves are past the
-  //      loop's last barrier, and nothing else touches LDS any more) ---------------------------------
+  //      dimension at a time, so that rows leave as contiguous lines.  The slices lie in the K
+  //      buffers, and every wave's last K read precedes the last barrier the other waves passed;
+  //      waves 4..7 may still be reading their last V tile, which lies elsewhere ------------------
   constexpr int HD = D / 2;               // floats per staged row piece
   constexpr int HCH = HD / 4;             // 16-byte chunks per piece (16 or 8)
   constexpr int PITCH = HD * 4;           // bytes per staged row piece (256 or 128)
@@ -612,7 +706,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
     float2 ml = {l_tot > 0.f ? mb : -INFINITY, l_tot};  // reference in log2 units; -inf: nothing visible
     *reinterpret_cast<float2 *>(p.part_ml + ((int64_t)split * p.part_rows + prow) * 2) = ml;
   }
-  BA_MARK(79, 5);
+  BA_MARK_ALWAYS(79, 5);
+  BA_WALL(78, 1);
 }
 
 // Merge split partials in split order: m = max m_i, w_i = 2^(m_i - m),
