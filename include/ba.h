@@ -111,8 +111,9 @@ int32_t ba_profile_end(double *ms_sum, int32_t *launches);
  * rotated keys -- the cacheable K of Section 2.3 -- are written to k_local_out
  * [T, n_kv_heads, D] if it is non-null, else kept in the workspace.  With
  * BA_ROPE_NONE k is used as given and k_local_out must be null.
- * Zero-length blocks are legal no-ops.  ws/ws_bytes: device workspace of at least
- * ba_encode_blocks_workspace_bytes() bytes (may be null when that is 0).
+ * Zero-length blocks are legal no-ops.  ws/ws_bytes: 256-byte aligned device workspace
+ * of at least ba_encode_blocks_workspace_bytes() bytes (may be null when that is 0; with
+ * BA_ROPE_APPLY it holds the rotated queries, and the rotated keys if k_local_out is null).
  */
 int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
                          const ba_tensor *v, const ba_tensor *o_out,
@@ -157,7 +158,8 @@ int32_t ba_reencode_positions(const ba_heads *heads, const ba_tensor *k_src,
  * the prompt's context length).  With BA_ROPE_APPLY q_f and k_f are rotated at those
  * positions inside; k_ctx is always used as given.  k_f_rot_out (nullable, shaped like
  * k_f) receives the rotated final-block keys for later decoding.
- * All tensors bf16.  ws: at least ba_final_block_attention_workspace_bytes() bytes.
+ * All tensors bf16.  ws: 256-byte aligned, at least
+ * ba_final_block_attention_workspace_bytes() bytes (rotated q_f and k_f, split partials).
  */
 int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f,
                                  const ba_tensor *k_ctx, const ba_tensor *v_ctx,

@@ -64,7 +64,6 @@ struct Problem {
   int lq;       // query tokens
   int ctx0;     // first context row
   int tctx;     // context rows
-  int qpos0;    // position of query token 0
   int jt;       // row tile inside the problem
 };
 
@@ -84,7 +83,6 @@ __device__ __forceinline__ Problem locate(const EncodeMeta &m, int tile) {
   pr.lq = m.offs[b + 1] - m.offs[b];
   pr.ctx0 = 0;
   pr.tctx = 0;
-  pr.qpos0 = 0;
   pr.jt = tile - m.tile_start[b];
   return pr;
 }
@@ -95,7 +93,6 @@ __device__ __forceinline__ Problem locate(const FinalMeta &m, int tile) {
   pr.lq = m.cu_q[n + 1] - m.cu_q[n];
   pr.ctx0 = m.cu_ctx[n];
   pr.tctx = m.cu_ctx[n + 1] - m.cu_ctx[n];
-  pr.qpos0 = m.pos0[n];
   pr.jt = tile - m.tile_start[n];
   return pr;
 }
@@ -148,6 +145,7 @@ __device__ __forceinline__ void dma_wait() {
 // Debug build only: per-phase timestamps of one workgroup, read back by ba_debug_read_trace().
 constexpr int kTraceTiles = 80, kTraceMarks = 8;
 __device__ long long g_trace[8][kTraceTiles][kTraceMarks];
+__device__ long long g_wg[1024][4];  // per workgroup: wall clock at start and end, cycles at start and end
 #define BA_MARK_ALWAYS(tile, m)                                                            \
   do {                                                                                     \
     if (trace_on && (tile) < kTraceTiles && lane == 0) g_trace[wave][tile][m] = clock64(); \
@@ -167,7 +165,7 @@ __device__ long long g_trace[8][kTraceTiles][kTraceMarks];
 #endif
 
 template <int D, typename Meta>
-__global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta, RopeTable rt) {
+__global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta) {
   using G = Geo<D>;
   constexpr bool kFinal = std::is_same<Meta, FinalMeta>::value;
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
@@ -200,6 +198,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
 #endif
   BA_MARK_ALWAYS(79, 0);
   BA_WALL(78, 0);
+#ifdef BA_TRACE
+  if (threadIdx.x == 0 && blockIdx.x < 1024) { g_wg[blockIdx.x][0] = wall_clock64(); g_wg[blockIdx.x][2] = clock64(); }
+#endif
   const int Gq = p.group;
   const int n_rows = pr.lq * Gq;
   const int row0 = pr.jt * kTileRows;
@@ -377,6 +378,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
 #ifdef BA_VAR_NOMFMA
     return;
 #endif
+    // the wave in its MFMA block goes first at the issue arbiter; the other wave of the SIMD, in its
+    // exponentials, fills the slots between
+    __builtin_amdgcn_s_setprio(3);
     CopyJob cj;
     if (!steady && copy) cj = copy_prepare(t_copy, buf_copy);
     const uint32_t cp_dst = lds_copy + (uint32_t)buf_copy * TB;
@@ -410,6 +414,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    __builtin_amdgcn_s_setprio(0);
   };
   // QK of the very first tile (nothing to overlap it with; the reference is still 0)
   auto qk_first = [&](uint32_t kofs, f32x16_t (&sacc)[2]) __attribute__((always_inline)) {
@@ -539,8 +544,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
   }
   BA_MARK_ALWAYS(79, 1);
 
-  // ---- Q fragments (B operand of S^T = K Q^T): rotated in registers if asked, and multiplied
-  //      by scale * log2(e) before the one rounding to bf16 -----------------------------------------
+  // ---- Q fragments (B operand of S^T = K Q^T).  With rotary embedding the rows come from the
+  //      RoPE pre-pass, already rotated and multiplied by scale * log2(e); otherwise they are the
+  //      caller's and are scaled here, before one rounding back to bf16 ------------------------------
   {
     const int g = my_row - my_tok * Gq;
     const int head = kvh * Gq + g;
@@ -551,39 +557,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
       u32x4_t z = {0u, 0u, 0u, 0u};
       raw[kk] = row_ok ? *reinterpret_cast<const u32x4_t *>(qp + kk * 16) : z;
     }
-    if (p.rope_q) {
-      const int pos = pr.qpos0 + my_tok;
-      if (p.rope_layout == 0) {
-#pragma unroll
-        for (int kk = 0; kk < G::KCH; ++kk) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float c, s;
-            sincos_phase(rope_phase(pos, rt.turns[kk * 8 + hf * 4 + e]), c, s);
-            c *= c2;
-            s *= c2;
-            float x = bf16_lo(raw[kk][e]), y = bf16_hi(raw[kk][e]);
-            raw[kk][e] = pack_bf16(c * x - s * y, s * x + c * y);
-          }
-        }
-      } else {
-#pragma unroll
-        for (int kk = 0; kk < G::KCH / 2; ++kk) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float c0, s0, c1, s1;
-            const int j = kk * 16 + hf * 8 + 2 * e;
-            sincos_phase(rope_phase(pos, rt.turns[j]), c0, s0);
-            sincos_phase(rope_phase(pos, rt.turns[j + 1]), c1, s1);
-            c0 *= c2; s0 *= c2; c1 *= c2; s1 *= c2;
-            uint32_t wa = raw[kk][e], wb = raw[kk + G::KCH / 2][e];
-            float xa0 = bf16_lo(wa), xa1 = bf16_hi(wa), xb0 = bf16_lo(wb), xb1 = bf16_hi(wb);
-            raw[kk][e] = pack_bf16(c0 * xa0 - s0 * xb0, c1 * xa1 - s1 * xb1);
-            raw[kk + G::KCH / 2][e] = pack_bf16(s0 * xa0 + c0 * xb0, s1 * xa1 + c1 * xb1);
-          }
-        }
-      }
-    } else {
+    if (!p.q_ready) {
 #pragma unroll
       for (int kk = 0; kk < G::KCH; ++kk)
 #pragma unroll
@@ -708,6 +682,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta,
   }
   BA_MARK_ALWAYS(79, 5);
   BA_WALL(78, 1);
+#ifdef BA_TRACE
+  if (threadIdx.x == 0 && blockIdx.x < 1024) { g_wg[blockIdx.x][1] = wall_clock64(); g_wg[blockIdx.x][3] = clock64(); }
+#endif
 }
 
 // Merge split partials in split order: m = max m_i, w_i = 2^(m_i - m),
@@ -751,7 +728,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, 
 }
 
 template <int D, typename Meta>
-hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, const RopeTable &rt, hipStream_t stream) {
+hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, hipStream_t stream) {
   const int64_t n_wg = (int64_t)p.total_tiles * p.n_kv_heads * p.n_splits;
   if (n_wg == 0) return hipSuccess;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
@@ -765,7 +742,7 @@ hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, const RopeTable 
     if (e != hipSuccess) return e;
     raised = true;
   }
-  hipLaunchKernelGGL((attn_kernel<D, Meta>), dim3((unsigned)n_wg), dim3(kThreads), lds, stream, p, meta, rt);
+  hipLaunchKernelGGL((attn_kernel<D, Meta>), dim3((unsigned)n_wg), dim3(kThreads), lds, stream, p, meta);
   return hipGetLastError();
 }
 
@@ -775,19 +752,20 @@ hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, const RopeTable 
 extern "C" int ba_debug_read_trace(long long *host_out) {
   return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(g_trace));
 }
+extern "C" int ba_debug_read_wg(long long *host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_wg), sizeof(g_wg));
+}
 #endif
 
-hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, const RopeTable &rt,
-                              hipStream_t stream) {
-  if (p.head_dim == 128) return launch_attn_t<128, EncodeMeta>(p, meta, rt, stream);
-  if (p.head_dim == 64) return launch_attn_t<64, EncodeMeta>(p, meta, rt, stream);
+hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream) {
+  if (p.head_dim == 128) return launch_attn_t<128, EncodeMeta>(p, meta, stream);
+  if (p.head_dim == 64) return launch_attn_t<64, EncodeMeta>(p, meta, stream);
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, const RopeTable &rt,
-                             hipStream_t stream) {
-  if (p.head_dim == 128) return launch_attn_t<128, FinalMeta>(p, meta, rt, stream);
-  if (p.head_dim == 64) return launch_attn_t<64, FinalMeta>(p, meta, rt, stream);
+hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, hipStream_t stream) {
+  if (p.head_dim == 128) return launch_attn_t<128, FinalMeta>(p, meta, stream);
+  if (p.head_dim == 64) return launch_attn_t<64, FinalMeta>(p, meta, stream);
   return hipErrorInvalidValue;
 }
 

@@ -141,8 +141,10 @@ struct FinalPlan {
   int64_t total_tiles = 0;
   int max_nt = 0;
   int n_splits = 1;
-  size_t kf_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0;
-  size_t total() const { return align256(kf_bytes) + align256(part_o_bytes) + align256(part_ml_bytes); }
+  size_t kf_bytes = 0, q_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0;
+  size_t total() const {
+    return align256(kf_bytes) + align256(q_bytes) + align256(part_o_bytes) + align256(part_ml_bytes);
+  }
 };
 
 int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_ctx,
@@ -165,8 +167,10 @@ int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, co
   }
   pl.lq_total = n_prompts > 0 ? cu_q[n_prompts] : 0;
   pl.n_splits = choose_splits(pl.total_tiles * h->n_kv_heads, pl.max_nt);
-  if (rope_mode == BA_ROPE_APPLY && !have_rot_out)
-    pl.kf_bytes = (size_t)pl.lq_total * h->n_kv_heads * h->head_dim * 2;
+  if (rope_mode == BA_ROPE_APPLY) {
+    if (!have_rot_out) pl.kf_bytes = (size_t)pl.lq_total * h->n_kv_heads * h->head_dim * 2;
+    pl.q_bytes = (size_t)pl.lq_total * h->n_q_heads * h->head_dim * 2;  // rotated, pre-scaled queries
+  }
   if (pl.n_splits > 1) {
     const size_t rows = (size_t)pl.lq_total * h->n_q_heads;
     pl.part_o_bytes = (size_t)pl.n_splits * rows * h->head_dim * 4;
@@ -221,6 +225,54 @@ int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, c
     }
     if (e != hipSuccess) return device_fail(e, "re-encode launch");
   }
+  return BA_OK;
+}
+
+// Rotate fresh Q (into q_rot, packed, pre-scaled) and fresh K (into k_rot) for segments
+// [seg0, seg0 + n) given by start offsets and first positions.
+int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_tensor *q, uint16_t *q_rot,
+                         const ba_tensor *k, const ba_tensor *k_rot, int n, const int32_t *start,
+                         const int32_t *pos0, hipStream_t stream) {
+  ba::RopeSegs segs;
+  memset(&segs, 0, sizeof(segs));
+  segs.n = n;
+  for (int i = 0; i < n; ++i) {
+    segs.start[i] = start[i];
+    segs.pos0[i] = pos0 ? pos0[i] : 0;
+  }
+  segs.start[n] = start[n];
+  const int64_t tokens = (int64_t)start[n] - start[0];
+  if (tokens <= 0) return BA_OK;
+  ba::RopePrepassParams p;
+  memset(&p, 0, sizeof(p));
+  const int D = h->head_dim;
+  p.q_src = (const uint16_t *)q->ptr;
+  p.q_dst = q_rot;
+  p.q_st = q->stride_tok;
+  p.q_sh = q->stride_head;
+  p.qd_st = (int64_t)h->n_q_heads * D;
+  p.qd_sh = D;
+  p.k_src = (const uint16_t *)k->ptr;
+  p.k_dst = (uint16_t *)k_rot->ptr;
+  p.k_st = k->stride_tok;
+  p.k_sh = k->stride_head;
+  p.kd_st = k_rot->stride_tok;
+  p.kd_sh = k_rot->stride_head;
+  p.q_scale = scale_log2e(h);
+  p.n_q_heads = h->n_q_heads;
+  p.n_kv_heads = h->n_kv_heads;
+  p.head_dim = D;
+  p.layout = h->rope_layout;
+  // few tokens: one head per thread (more, shorter threads); many: sin/cos shared by several heads
+  p.heads_per_thread = tokens >= 16384 ? 8 : (tokens >= 2048 ? 2 : 1);
+  p.do_q = 1;
+  p.do_k = 1;
+  hipError_t e;
+  {
+    ProfileScope ps(BA_PROFILE_REENCODE, stream);
+    e = ba::launch_rope_prepass(p, segs, rt, stream);
+  }
+  if (e != hipSuccess) return device_fail(e, "RoPE pre-pass launch");
   return BA_OK;
 }
 
@@ -287,8 +339,10 @@ size_t ba_encode_blocks_workspace_bytes(const ba_heads *heads, int32_t n_blocks,
                                         const int32_t *block_offsets, int32_t rope_mode,
                                         int32_t have_k_local_out) {
   if (!heads || !block_offsets || n_blocks < 0) return 0;
-  if (rope_mode != BA_ROPE_APPLY || have_k_local_out) return 0;
-  return align256((size_t)block_offsets[n_blocks] * heads->n_kv_heads * heads->head_dim * 2);
+  if (rope_mode != BA_ROPE_APPLY) return 0;
+  const size_t T = (size_t)block_offsets[n_blocks];
+  const size_t k_bytes = have_k_local_out ? 0 : align256(T * heads->n_kv_heads * heads->head_dim * 2);
+  return k_bytes + align256(T * heads->n_q_heads * heads->head_dim * 2);  // rotated K, rotated pre-scaled Q
 }
 
 int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
@@ -318,46 +372,36 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ba::RopeTable rt;
   build_rope_table(heads, &rt);
 
-  // keys the attention kernel reads: the caller's (NONE) or freshly rotated ones (APPLY)
+  // what the attention kernel reads: the caller's q and k (NONE), or freshly rotated ones (APPLY):
+  // K into k_local_out or the workspace, Q (also pre-scaled) into the workspace
   ba_tensor k_use = *k;
+  ba_tensor q_use = *q;
   if (rope_mode == BA_ROPE_APPLY) {
+    const size_t need = ba_encode_blocks_workspace_bytes(heads, n_blocks, block_offsets, rope_mode, k_local_out != nullptr);
+    if (!ws || ws_bytes < need || ((uintptr_t)ws & 255))
+      return fail(BA_ERR_WORKSPACE, "encode: 256-byte aligned workspace of %zu bytes needed, %zu given", need,
+                  ws_bytes);
+    char *wsp = (char *)ws;
     if (k_local_out) {
       k_use = *k_local_out;
     } else {
-      const size_t need = ba_encode_blocks_workspace_bytes(heads, n_blocks, block_offsets, rope_mode, 0);
-      if (!ws || ws_bytes < need || ((uintptr_t)ws & 15))
-        return fail(BA_ERR_WORKSPACE, "encode: workspace of %zu bytes needed, %zu given", need, ws_bytes);
-      k_use.ptr = ws;
+      k_use.ptr = wsp;
       k_use.stride_head = D;
       k_use.stride_tok = (int64_t)heads->n_kv_heads * D;
       k_use.dtype = BA_DTYPE_BF16;
+      wsp += align256((size_t)T * heads->n_kv_heads * D * 2);
     }
-    ba::ReencParams rp;
-    memset(&rp, 0, sizeof(rp));
-    rp.src = k->ptr;
-    rp.dst = k_use.ptr;
-    rp.src_st = k->stride_tok;
-    rp.src_sh = k->stride_head;
-    rp.dst_st = k_use.stride_tok;
-    rp.dst_sh = k_use.stride_head;
-    rp.n_layers = 1;
-    rp.n_kv_heads = heads->n_kv_heads;
-    rp.head_dim = D;
-    rp.dtype = BA_DTYPE_BF16;
-    rp.layout = heads->rope_layout;
-    rp.mode = BA_REENC_ABSOLUTE;  // un-rotated keys -> local position u of each block
-    std::vector<int32_t> len(n_blocks), zero(n_blocks, 0);
-    for (int b = 0; b < n_blocks; ++b) len[b] = block_offsets[b + 1] - block_offsets[b];
-    if ((rc = run_reencode(rp, rt, n_blocks, block_offsets, block_offsets, len.data(), zero.data(),
-                           zero.data(), stream)))
-      return rc;
+    q_use.ptr = wsp;
+    q_use.stride_head = D;
+    q_use.stride_tok = (int64_t)heads->n_q_heads * D;
+    q_use.dtype = BA_DTYPE_BF16;
   }
 
   ba::AttnParams ap;
   memset(&ap, 0, sizeof(ap));
-  ap.q = (const uint16_t *)q->ptr;
-  ap.q_st = q->stride_tok;
-  ap.q_sh = q->stride_head;
+  ap.q = (const uint16_t *)q_use.ptr;
+  ap.q_st = q_use.stride_tok;
+  ap.q_sh = q_use.stride_head;
   ap.kf = (const uint16_t *)k_use.ptr;
   ap.kf_st = k_use.stride_tok;
   ap.kf_sh = k_use.stride_head;
@@ -378,8 +422,7 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ap.group = G;
   ap.head_dim = D;
   ap.scale_log2e = scale_log2e(heads);
-  ap.rope_q = rope_mode == BA_ROPE_APPLY;
-  ap.rope_layout = heads->rope_layout;
+  ap.q_ready = rope_mode == BA_ROPE_APPLY;
   ap.n_splits = 1;
 
   for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
@@ -400,10 +443,14 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
     meta.tile_start[n] = (int32_t)tiles;
     ap.total_tiles = (int32_t)tiles;
     if (tiles == 0) continue;
+    if (rope_mode == BA_ROPE_APPLY) {  // local positions: every block starts at 0
+      if ((rc = run_rope_prepass(heads, rt, q, (uint16_t *)q_use.ptr, k, &k_use, n, meta.offs, nullptr, stream)))
+        return rc;
+    }
     hipError_t e;
     {
       ProfileScope ps(BA_PROFILE_ATTENTION, stream);
-      e = ba::launch_attn_encode(ap, meta, rt, stream);
+      e = ba::launch_attn_encode(ap, meta, stream);
     }
     if (e != hipSuccess) return device_fail(e, "encode attention launch");
   }
@@ -533,8 +580,9 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
 
   char *wsp = (char *)ws;
   void *kf_ws = wsp;
-  float *part_o = (float *)(wsp + align256(pl.kf_bytes));
-  float *part_ml = (float *)(wsp + align256(pl.kf_bytes) + align256(pl.part_o_bytes));
+  uint16_t *q_ws = (uint16_t *)(wsp + align256(pl.kf_bytes));
+  float *part_o = (float *)(wsp + align256(pl.kf_bytes) + align256(pl.q_bytes));
+  float *part_ml = (float *)(wsp + align256(pl.kf_bytes) + align256(pl.q_bytes) + align256(pl.part_o_bytes));
 
   ba::RopeTable rt;
   build_rope_table(heads, &rt);
@@ -555,31 +603,20 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
       kf_use.stride_head = D;
       kf_use.stride_tok = (int64_t)heads->n_kv_heads * D;
     }
-    ba::ReencParams rp;
-    memset(&rp, 0, sizeof(rp));
-    rp.src = k_f->ptr;
-    rp.dst = kf_use.ptr;
-    rp.src_st = k_f->stride_tok;
-    rp.src_sh = k_f->stride_head;
-    rp.dst_st = kf_use.stride_tok;
-    rp.dst_sh = kf_use.stride_head;
-    rp.n_layers = 1;
-    rp.n_kv_heads = heads->n_kv_heads;
-    rp.head_dim = D;
-    rp.dtype = BA_DTYPE_BF16;
-    rp.layout = heads->rope_layout;
-    rp.mode = BA_REENC_ABSOLUTE;  // un-rotated final-block keys -> absolute positions
-    if ((rc = run_reencode(rp, rt, n_prompts, starts.data(), starts.data(), lens.data(), zero.data(),
-                           pos0.data(), stream)))
-      return rc;
   }
 
   const int G = heads->n_q_heads / heads->n_kv_heads;
   ba::AttnParams ap;
   memset(&ap, 0, sizeof(ap));
-  ap.q = (const uint16_t *)q_f->ptr;
-  ap.q_st = q_f->stride_tok;
-  ap.q_sh = q_f->stride_head;
+  if (rope_mode == BA_ROPE_APPLY) {
+    ap.q = q_ws;
+    ap.q_st = (int64_t)heads->n_q_heads * D;
+    ap.q_sh = D;
+  } else {
+    ap.q = (const uint16_t *)q_f->ptr;
+    ap.q_st = q_f->stride_tok;
+    ap.q_sh = q_f->stride_head;
+  }
   ap.kf = (const uint16_t *)kf_use.ptr;
   ap.kf_st = kf_use.stride_tok;
   ap.kf_sh = kf_use.stride_head;
@@ -612,8 +649,7 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   ap.group = G;
   ap.head_dim = D;
   ap.scale_log2e = scale_log2e(heads);
-  ap.rope_q = rope_mode == BA_ROPE_APPLY;
-  ap.rope_layout = heads->rope_layout;
+  ap.q_ready = rope_mode == BA_ROPE_APPLY;
   ap.n_splits = pl.n_splits;
 
   for (int n0 = 0; n0 < n_prompts; n0 += ba::kFinMaxPrompts) {
@@ -625,7 +661,6 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
     for (int i = 0; i < n; ++i) {
       meta.cu_q[i] = cu_q[n0 + i];
       meta.cu_ctx[i] = cu_ctx[n0 + i];
-      meta.pos0[i] = pos0[n0 + i];
       meta.tile_start[i] = (int32_t)tiles;
       tiles += ((int64_t)lens[n0 + i] * G + ba::kTileRows - 1) / ba::kTileRows;
     }
@@ -633,10 +668,14 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
     meta.cu_ctx[n] = cu_ctx[n0 + n];
     meta.tile_start[n] = (int32_t)tiles;
     ap.total_tiles = (int32_t)tiles;
+    if (rope_mode == BA_ROPE_APPLY) {  // absolute positions of the final block's tokens
+      if ((rc = run_rope_prepass(heads, rt, q_f, q_ws, k_f, &kf_use, n, meta.cu_q, pos0.data() + n0, stream)))
+        return rc;
+    }
     hipError_t e;
     {
       ProfileScope ps(BA_PROFILE_ATTENTION, stream);
-      e = ba::launch_attn_final(ap, meta, rt, stream);
+      e = ba::launch_attn_final(ap, meta, stream);
     }
     if (e != hipSuccess) return device_fail(e, "final-block attention launch");
   }

@@ -43,6 +43,33 @@ struct ReencParams {
 hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
                            hipStream_t stream);
 
+// ---------------------------------------------------------------- RoPE pre-pass ------
+// Fresh (un-rotated) Q and K rows of a run of consecutive segments: segment s covers tokens
+// [start[s], start[s+1]) and its first token has position pos0[s].
+constexpr int kRopeMaxSegs = 320;
+
+struct RopeSegs {
+  int32_t n;
+  int32_t start[kRopeMaxSegs + 1];
+  int32_t pos0[kRopeMaxSegs];
+};
+
+struct RopePrepassParams {
+  const uint16_t *q_src;
+  uint16_t *q_dst;
+  int64_t q_st, q_sh, qd_st, qd_sh;  // token / head strides, elements
+  const uint16_t *k_src;
+  uint16_t *k_dst;
+  int64_t k_st, k_sh, kd_st, kd_sh;
+  float q_scale;  // Q is multiplied by this before its one rounding
+  int32_t n_q_heads, n_kv_heads, head_dim, layout;
+  int32_t heads_per_thread;
+  int32_t do_q, do_k;
+};
+
+hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeTable &rt,
+                               hipStream_t stream);
+
 // ---------------------------------------------------------------- attention ----------
 constexpr int kTileRows = 256;  // packed (token, head-in-group) query rows per workgroup
 constexpr int kTileKeys = 64;   // keys per K/V tile
@@ -65,7 +92,7 @@ struct AttnParams {
   int64_t part_rows;
   int32_t n_q_heads, n_kv_heads, group, head_dim;
   float scale_log2e;  // softmax scale * log2(e)
-  int32_t rope_q, rope_layout;
+  int32_t q_ready;    // q is already rotated and multiplied by scale_log2e (the RoPE pre-pass ran)
   int32_t n_splits;
   int32_t total_tiles;  // row tiles over all problems of this launch
 };
@@ -82,14 +109,11 @@ struct FinalMeta {
   int32_t n;
   int32_t cu_q[kFinMaxPrompts + 1];
   int32_t cu_ctx[kFinMaxPrompts + 1];
-  int32_t pos0[kFinMaxPrompts];
   int32_t tile_start[kFinMaxPrompts + 1];
 };
 
-hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, const RopeTable &rt,
-                              hipStream_t stream);
-hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, const RopeTable &rt,
-                             hipStream_t stream);
+hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
+hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, hipStream_t stream);
 // Merge split-KV partials into the bf16 output.  rows = tokens * n_q_heads.
 hipError_t launch_combine(const AttnParams &p, int64_t n_tokens, hipStream_t stream);
 

@@ -1,0 +1,113 @@
+// RoPE pre-pass for fresh queries and keys (Eq. 1 of arXiv 2409.15355, positions per
+// Section 2.3: local to the block for per-block encoding, absolute for the final block).
+//
+// One launch rotates the un-rotated K rows (the result is the cacheable key, an output of the
+// step anyway) and the Q rows of a run of segments; Q is also multiplied by
+// softmax_scale * log2(e) before its one rounding to bf16, so that the attention core's
+// score accumulators hold base-2 exponents directly.  Doing this ahead of the attention core
+// keeps 32 sin/cos evaluations per lane out of every workgroup's start-up.
+//
+// Thread mapping as in the re-encode kernel: a thread owns 16-byte chunk c and chunk c + CH/2
+// of one token and walks a group of heads, its sin/cos computed once.  Few tokens: one head
+// per thread (many short threads); many tokens: several heads per thread.
+#include "ba_device.h"
+
+namespace ba {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <int D, int LAYOUT>
+__global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParams p, RopeSegs segs,
+                                                                RopeTable rt) {
+  constexpr int VEC = 8;
+  constexpr int CH = D / VEC;
+  constexpr int TPV = CH / 2;          // threads per head vector
+  constexpr int TPP = kThreads / TPV;  // tokens per workgroup
+  const int c = threadIdx.x % TPV;
+  const int t = segs.start[0] + blockIdx.x * TPP + threadIdx.x / TPV;
+  if (t >= segs.start[segs.n]) return;
+  int lo = 0, hi = segs.n;  // largest s with start[s] <= t
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (segs.start[mid] <= t) lo = mid; else hi = mid;
+  }
+  const int pos = segs.pos0[lo] + (t - segs.start[lo]);
+
+  // which tensor and which heads this workgroup handles: Q head groups first, then K
+  const int groups_q = p.do_q ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0;
+  const bool is_q = (int)blockIdx.y < groups_q;
+  const int grp = is_q ? blockIdx.y : blockIdx.y - groups_q;
+  const int n_heads = is_q ? p.n_q_heads : p.n_kv_heads;
+  const int h_begin = grp * p.heads_per_thread;
+  const int h_end = min(n_heads, h_begin + p.heads_per_thread);
+  const uint16_t *src = (is_q ? p.q_src : p.k_src) + (int64_t)t * (is_q ? p.q_st : p.k_st) + c * VEC;
+  uint16_t *dst = (is_q ? p.q_dst : p.k_dst) + (int64_t)t * (is_q ? p.qd_st : p.kd_st) + c * VEC;
+  const int64_t src_sh = is_q ? p.q_sh : p.k_sh, dst_sh = is_q ? p.qd_sh : p.kd_sh;
+  const float scale = is_q ? p.q_scale : 1.0f;
+
+  float cs[VEC], sn[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    int j;
+    if (LAYOUT == 0)  // interleaved: pairs live inside each chunk
+      j = (e < VEC / 2) ? c * (VEC / 2) + e : (c + CH / 2) * (VEC / 2) + (e - VEC / 2);
+    else  // half: element e of chunk c pairs with element e of chunk c + CH/2
+      j = c * VEC + e;
+    sincos_phase(rope_phase(pos, rt.turns[j]), cs[e], sn[e]);
+    if (scale != 1.0f) {
+      cs[e] *= scale;
+      sn[e] *= scale;
+    }
+  }
+#pragma unroll 4
+  for (int h = h_begin; h < h_end; ++h) {
+    const u32x4_t xa = *reinterpret_cast<const u32x4_t *>(src + h * src_sh);
+    const u32x4_t xb = *reinterpret_cast<const u32x4_t *>(src + h * src_sh + (CH / 2) * VEC);
+    u32x4_t ya, yb;
+    if (LAYOUT == 0) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a0 = bf16_lo(xa[e]), a1 = bf16_hi(xa[e]);
+        ya[e] = pack_bf16(cs[e] * a0 - sn[e] * a1, sn[e] * a0 + cs[e] * a1);
+        const float b0 = bf16_lo(xb[e]), b1 = bf16_hi(xb[e]);
+        yb[e] = pack_bf16(cs[4 + e] * b0 - sn[4 + e] * b1, sn[4 + e] * b0 + cs[4 + e] * b1);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float a0 = bf16_lo(xa[e]), a1 = bf16_hi(xa[e]), b0 = bf16_lo(xb[e]), b1 = bf16_hi(xb[e]);
+        ya[e] = pack_bf16(cs[2 * e] * a0 - sn[2 * e] * b0, cs[2 * e + 1] * a1 - sn[2 * e + 1] * b1);
+        yb[e] = pack_bf16(sn[2 * e] * a0 + cs[2 * e] * b0, sn[2 * e + 1] * a1 + cs[2 * e + 1] * b1);
+      }
+    }
+    *reinterpret_cast<u32x4_t *>(dst + h * dst_sh) = ya;
+    *reinterpret_cast<u32x4_t *>(dst + h * dst_sh + (CH / 2) * VEC) = yb;
+  }
+}
+
+template <int D>
+hipError_t launch_d(const RopePrepassParams &p, const RopeSegs &segs, const RopeTable &rt, hipStream_t stream) {
+  constexpr int TPP = kThreads / (D / 8 / 2);
+  const int64_t tokens = (int64_t)segs.start[segs.n] - segs.start[0];
+  const int groups = (p.do_q ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0) +
+                     (p.do_k ? (p.n_kv_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0);
+  if (tokens <= 0 || groups == 0) return hipSuccess;
+  dim3 grid((unsigned)((tokens + TPP - 1) / TPP), (unsigned)groups, 1);
+  if (p.layout == 0)
+    hipLaunchKernelGGL((rope_prepass_kernel<D, 0>), grid, dim3(kThreads), 0, stream, p, segs, rt);
+  else
+    hipLaunchKernelGGL((rope_prepass_kernel<D, 1>), grid, dim3(kThreads), 0, stream, p, segs, rt);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeTable &rt,
+                               hipStream_t stream) {
+  if (p.head_dim == 128) return launch_d<128>(p, segs, rt, stream);
+  if (p.head_dim == 64) return launch_d<64>(p, segs, rt, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace ba

@@ -206,7 +206,8 @@ def test_encode_strided_views(ba):
     o = torch.empty((T, hq, d), dtype=torch.bfloat16, device="cuda")
     k_local = torch.empty((T, hkv, d), dtype=torch.bfloat16, device="cuda")
     heads = ba.Heads(hq, hkv, d, 10000.0)
-    ba.ba_encode_blocks(heads, q, k, v, o, k_local, offs, 1, None)
+    ws = torch.empty(ba.ba_encode_blocks_workspace_bytes(heads, offs, 1, True), dtype=torch.uint8, device="cuda")
+    ba.ba_encode_blocks(heads, q, k, v, o, k_local, offs, 1, ws)
     torch.cuda.synchronize()
     th = oracle.theta(10000.0, d)
     ref_o, _ = oracle.encode_blocks(oracle.bf16_bits_to_f64(qb), oracle.bf16_bits_to_f64(kb),
