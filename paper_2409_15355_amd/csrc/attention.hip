@@ -28,8 +28,8 @@
 //     P is rounded to bf16 for the second MFMA; row sums stay in fp32; the output is rounded once.
 //   - The two waves of a SIMD run half a period apart ("ping-pong"): while one is in its
 //     exponentials (VALU), the other is in its MFMA block (PV of this tile, QK of the next).
-//   - The KV range can be cut into n_splits pieces; each piece writes un-normalised
-//     fp32 partials (reference, sum, O) that combine_kernel merges in a fixed order.
+//   - The KV range can be cut into n_splits pieces; each piece writes its own normalised output
+//     (fp16) with its reference and sum (fp32), and combine_kernel merges them in a fixed order.
 #include <type_traits>
 
 #include "ba_device.h"
@@ -626,7 +626,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   constexpr int HLPR = 256 / PITCH;       // pieces per 256-byte LDS line
   lds_char *stage = smem + wave * (32 * PITCH);
   const float l_tot = l_run + other_half(l_run);
-  const float inv = (p.n_splits == 1) ? 1.0f / l_tot : 1.0f;
+  // Every piece is normalised by its own sum (a convex combination of v rows, so it fits fp16 when
+  // it is a split partial); a piece that saw no key is all zeros.
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     // write: lane (col, hf) owns query row `col`; chunk index XOR row keeps banks apart
@@ -666,7 +668,10 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
           *reinterpret_cast<uint2 *>(p.o + (int64_t)(pr.q_tok0 + i) * p.o_st + (int64_t)head * p.o_sh + d) = o2;
         } else {
           const int64_t prow = (int64_t)(pr.q_tok0 + i) * p.n_q_heads + head;
-          *reinterpret_cast<f32x4_t *>(p.part_o + ((int64_t)split * p.part_rows + prow) * D + d) = w;
+          uint2 o2;
+          o2.x = pack_f16(w[0], w[1]);
+          o2.y = pack_f16(w[2], w[3]);
+          *reinterpret_cast<uint2 *>(p.part_o + ((int64_t)split * p.part_rows + prow) * D + d) = o2;
         }
       }
     }
@@ -687,17 +692,17 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
 #endif
 }
 
-// Merge split partials in split order: m = max m_i, w_i = 2^(m_i - m),
-// o = sum_i w_i O_i / sum_i w_i l_i.
+// Merge split partials in split order.  Split i holds its own normalised output o_i (fp16), its
+// reference m_i (log2 units; -inf if it saw no key) and its sum l_i:
+//   m = max m_i,  w_i = 2^(m_i - m) l_i,  o = sum_i w_i o_i / sum_i w_i.
 template <int D>
 __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, int64_t n_rows) {
-  constexpr int TPR = D / 4;                  // threads per row
+  constexpr int TPR = D / 8;                  // threads per row, 8 elements (16 bytes of fp16) each
   constexpr int RPB = kCombineThreads / TPR;  // rows per workgroup
   const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / TPR;
   if (row >= n_rows) return;
-  const int d = (threadIdx.x % TPR) * 4;
-  // all loads are unconditional and independent, so they go out together; a split that saw no
-  // visible key wrote O = 0, l = 0 and a reference of -inf, and gets weight 0
+  const int d = (threadIdx.x % TPR) * 8;
+  // all loads are unconditional and independent, so they go out together
   constexpr int MAXS = 32;  // the host never asks for more splits
   float wgt[MAXS];
   float m = -INFINITY;
@@ -706,25 +711,28 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, 
     wgt[s & (MAXS - 1)] = p.part_ml[((int64_t)s * p.part_rows + row) * 2];
     m = fmaxf(m, wgt[s & (MAXS - 1)]);
   }
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float l = 0.f;
 #pragma unroll 8
   for (int s = 0; s < p.n_splits; ++s) {
     const float ms = wgt[s & (MAXS - 1)];
-    const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m);
     const float ls = p.part_ml[((int64_t)s * p.part_rows + row) * 2 + 1];
-    const f32x4_t o = *reinterpret_cast<const f32x4_t *>(p.part_o + ((int64_t)s * p.part_rows + row) * D + d);
-    l += w * ls;
+    const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m) * ls;
+    const u32x4_t o = *reinterpret_cast<const u32x4_t *>(p.part_o + ((int64_t)s * p.part_rows + row) * D + d);
+    l += w;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i] += w * o[i];
+    for (int i = 0; i < 4; ++i) {
+      acc[2 * i] += w * f16_lo(o[i]);
+      acc[2 * i + 1] += w * f16_hi(o[i]);
+    }
   }
   const float inv = 1.0f / l;
   const int64_t tokn = row / p.n_q_heads;
   const int head = (int)(row - tokn * p.n_q_heads);
-  uint2 w;
-  w.x = pack_bf16(acc[0] * inv, acc[1] * inv);
-  w.y = pack_bf16(acc[2] * inv, acc[3] * inv);
-  *reinterpret_cast<uint2 *>(p.o + tokn * p.o_st + (int64_t)head * p.o_sh + d) = w;
+  u32x4_t w;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = pack_bf16(acc[2 * i] * inv, acc[2 * i + 1] * inv);
+  *reinterpret_cast<u32x4_t *>(p.o + tokn * p.o_st + (int64_t)head * p.o_sh + d) = w;
 }
 
 template <int D, typename Meta>
@@ -773,11 +781,11 @@ hipError_t launch_combine(const AttnParams &p, int64_t n_tokens, hipStream_t str
   const int64_t n_rows = n_tokens * p.n_q_heads;
   if (n_rows == 0) return hipSuccess;
   if (p.head_dim == 128) {
-    constexpr int RPB = kCombineThreads / (128 / 4);
+    constexpr int RPB = kCombineThreads / (128 / 8);
     hipLaunchKernelGGL((combine_kernel<128>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kCombineThreads), 0,
                        stream, p, n_rows);
   } else if (p.head_dim == 64) {
-    constexpr int RPB = kCombineThreads / (64 / 4);
+    constexpr int RPB = kCombineThreads / (64 / 8);
     hipLaunchKernelGGL((combine_kernel<64>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kCombineThreads), 0,
                        stream, p, n_rows);
   } else {

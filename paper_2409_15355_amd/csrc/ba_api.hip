@@ -173,7 +173,7 @@ int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, co
   }
   if (pl.n_splits > 1) {
     const size_t rows = (size_t)pl.lq_total * h->n_q_heads;
-    pl.part_o_bytes = (size_t)pl.n_splits * rows * h->head_dim * 4;
+    pl.part_o_bytes = (size_t)pl.n_splits * rows * h->head_dim * 2;  // fp16
     pl.part_ml_bytes = (size_t)pl.n_splits * rows * 2 * 4;
   }
   *plan = pl;
@@ -581,7 +581,7 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   char *wsp = (char *)ws;
   void *kf_ws = wsp;
   uint16_t *q_ws = (uint16_t *)(wsp + align256(pl.kf_bytes));
-  float *part_o = (float *)(wsp + align256(pl.kf_bytes) + align256(pl.q_bytes));
+  uint16_t *part_o = (uint16_t *)(wsp + align256(pl.kf_bytes) + align256(pl.q_bytes));
   float *part_ml = (float *)(wsp + align256(pl.kf_bytes) + align256(pl.q_bytes) + align256(pl.part_o_bytes));
 
   ba::RopeTable rt;

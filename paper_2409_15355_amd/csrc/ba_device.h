@@ -28,6 +28,22 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
+// two floats -> packed fp16 pair, round to nearest even; and back
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
+  typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+  f32x2_t f = {lo, hi};
+  f16x2_t h = __builtin_convertvector(f, f16x2_t);
+  return __builtin_bit_cast(uint32_t, h);
+}
+__device__ __forceinline__ float f16_lo(uint32_t w) {
+  typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+  return (float)__builtin_bit_cast(f16x2_t, w)[0];
+}
+__device__ __forceinline__ float f16_hi(uint32_t w) {
+  typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+  return (float)__builtin_bit_cast(f16x2_t, w)[1];
+}
+
 // cos and sin of the angle whose fraction of a full turn is phase / 2^64.
 // The quarter turn nearest to the phase is split off exactly in integer arithmetic;
 // the remainder y, |y| <= pi/4, goes through Taylor polynomials whose truncation

@@ -87,8 +87,8 @@ struct AttnParams {
   int64_t vf_st, vf_sh;
   uint16_t *o;
   int64_t o_st, o_sh;
-  float *part_o;   // [n_splits][part_rows][D]   un-normalised partial outputs
-  float *part_ml;  // [n_splits][part_rows][2]   (max in log2 units, sum of exponentials)
+  uint16_t *part_o;  // [n_splits][part_rows][D]   fp16: each split's own normalised output
+  float *part_ml;    // [n_splits][part_rows][2]   (reference in log2 units, sum of exponentials)
   int64_t part_rows;
   int32_t n_q_heads, n_kv_heads, group, head_dim;
   float scale_log2e;  // softmax scale * log2(e)

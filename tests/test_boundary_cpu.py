@@ -106,8 +106,8 @@ def test_final_rejects_bad_arguments_and_sizes_workspace(lib):
     assert call([0, 5], [10, 3]) == -1        # cu_ctx decreases
     assert call([0, 256], [0, 31744]) == -4   # workspace missing
     need = ba.ba_final_block_attention_workspace_bytes(h, [0, 256], [0, 31744])
-    # config 5: 8 KV splits x 8192 packed rows x (128 + 2) fp32 + rotated final-block keys and queries
-    assert need == 8 * 8192 * 128 * 4 + 8 * 8192 * 2 * 4 + 256 * 8 * 128 * 2 + 256 * 32 * 128 * 2
+    # config 5: 8 KV splits x 8192 packed rows x (128 fp16 + 2 fp32) + rotated final-block keys and queries
+    assert need == 8 * 8192 * 128 * 2 + 8 * 8192 * 2 * 4 + 256 * 8 * 128 * 2 + 256 * 32 * 128 * 2
     assert call([0, 256], [0, 31744], ws=ctypes.c_void_p(0x10000), wsb=need - 1) == -4
     # zero prompts: legal no-op
     cq = i32([0])
