@@ -175,18 +175,19 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   constexpr uint32_t VBASE = kNumKBuf * TB;
 
   // ---- which work item -------------------------------------------------------------------
-  int id = blockIdx.x;
+  uint32_t id = blockIdx.x;
   if (kFinal) {
     // Consecutive work items share K/V tiles (same KV head and split, different row tile);
     // the dispatcher deals workgroup ids round-robin to the XCDs, so regroup ids such that
     // each XCD (and its L2) gets a contiguous run of work items.
-    const int n_wg = gridDim.x, q = n_wg / kXcds, r = n_wg % kXcds, x = id % kXcds;
+    const uint32_t n_wg = gridDim.x, q = n_wg / kXcds, r = n_wg % kXcds, x = id % kXcds;
     id = x * q + min(x, r) + id / kXcds;
   }
-  const int rowtile = kFinal ? id % p.total_tiles : p.total_tiles - 1 - id % p.total_tiles;
-  id /= p.total_tiles;
-  const int kvh = id % p.n_kv_heads;
-  const int split = id / p.n_kv_heads;
+  const uint32_t n_rowtiles = (uint32_t)p.total_tiles;
+  const uint32_t id_hi = id / n_rowtiles, id_lo = id - id_hi * n_rowtiles;
+  const int rowtile = kFinal ? (int)id_lo : (int)(n_rowtiles - 1 - id_lo);
+  const int split = (int)(id_hi / (uint32_t)p.n_kv_heads);
+  const int kvh = (int)(id_hi - (uint32_t)split * (uint32_t)p.n_kv_heads);
   const Problem pr = locate(meta, rowtile);
 
   const int lane = threadIdx.x & 63;
@@ -208,16 +209,17 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   // ---- key tiles this work item walks ---------------------------------------------------
   const int n_ctx_tiles = (pr.tctx + kTileKeys - 1) / kTileKeys;
   const int last_row = min(n_rows, row0 + kTileRows) - 1;
-  const int last_tok = last_row / Gq;
+  const int last_tok = (int)fast_div((uint32_t)last_row, p.group_div);
   const int n_causal_tiles = last_tok / kTileKeys + 1;
   const int nt = n_ctx_tiles + n_causal_tiles;
-  const int t_begin = (int)((int64_t)nt * split / p.n_splits);
-  const int t_end = (int)((int64_t)nt * (split + 1) / p.n_splits);
+  // (nt < 2^26 and at most 32 splits: the products fit 32 bits)
+  const int t_begin = (int)((uint32_t)nt * (uint32_t)split / (uint32_t)p.n_splits);
+  const int t_end = (int)((uint32_t)nt * (uint32_t)(split + 1) / (uint32_t)p.n_splits);
   const int n_t = t_end - t_begin;
 
   const int my_row = row0 + wave * 32 + col;
   const bool row_ok = my_row < n_rows;
-  const int my_tok = my_row / Gq;  // query token (inside the problem) of this lane's column
+  const int my_tok = (int)fast_div((uint32_t)my_row, p.group_div);  // query token (inside the problem) of this lane's column
   const float c2 = p.scale_log2e;
   bf16x8_t qf[G::KCH];  // Q fragments, filled below once the first tile copies are on their way
 
@@ -325,7 +327,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
   float mb = 0.f;      // the row's reference, log2 units
   float l_run = 0.f;   // this lane's share of the running sum of exponentials
-  const int first_tok_wave = (row0 + wave * 32) / Gq;
+  const int first_tok_wave = (int)fast_div((uint32_t)(row0 + wave * 32), p.group_div);
 
   // K fragment of QK step `step` = kk * 2 + a (keys 32a..32a+31, head dims 16kk..16kk+15) and
   // V^T fragment (key step kc, head dims 32dt..32dt+31), from tile buffers at LDS byte offsets
@@ -657,7 +659,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
           stage + rr * PITCH + ((ch ^ ((rr / HLPR) & (HCH - 1))) << 4));
       const int r = row0 + wave * 32 + rr;
       if (r < n_rows) {
-        const int i = r / Gq;
+        const int i = (int)fast_div((uint32_t)r, p.group_div);
         const int g = r - i * Gq;
         const int head = kvh * Gq + g;
         const int d = half * HD + ch * 4;

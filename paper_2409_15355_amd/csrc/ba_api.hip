@@ -420,6 +420,7 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ap.n_q_heads = heads->n_q_heads;
   ap.n_kv_heads = heads->n_kv_heads;
   ap.group = G;
+  ap.group_div = ba::make_fast_div((uint32_t)G);
   ap.head_dim = D;
   ap.scale_log2e = scale_log2e(heads);
   ap.q_ready = rope_mode == BA_ROPE_APPLY;
@@ -647,6 +648,7 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   ap.n_q_heads = heads->n_q_heads;
   ap.n_kv_heads = heads->n_kv_heads;
   ap.group = G;
+  ap.group_div = ba::make_fast_div((uint32_t)G);
   ap.head_dim = D;
   ap.scale_log2e = scale_log2e(heads);
   ap.q_ready = rope_mode == BA_ROPE_APPLY;

@@ -28,6 +28,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv &f) {
+  const uint32_t t = __umulhi(n, f.mul);
+  return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
 // two floats -> packed fp16 pair, round to nearest even; and back
 __device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
   typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));

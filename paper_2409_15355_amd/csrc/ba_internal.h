@@ -71,6 +71,21 @@ hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs,
                                hipStream_t stream);
 
 // ---------------------------------------------------------------- attention ----------
+// Division of a 32-bit unsigned number by a divisor fixed on the host (round-up multiplier of
+// Granlund and Montgomery): n / d = (t + ((n - t) >> sh1)) >> sh2 with t = mulhi(n, mul).
+struct FastDiv {
+  uint32_t mul, sh1, sh2;
+};
+inline FastDiv make_fast_div(uint32_t d) {
+  FastDiv f;
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;  // ceil(log2 d)
+  f.mul = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
+  f.sh1 = l < 1 ? l : 1;
+  f.sh2 = l > 0 ? l - 1 : 0;
+  return f;
+}
+
 constexpr int kTileRows = 256;  // packed (token, head-in-group) query rows per workgroup
 constexpr int kTileKeys = 64;   // keys per K/V tile
 
@@ -91,6 +106,7 @@ struct AttnParams {
   float *part_ml;    // [n_splits][part_rows][2]   (reference in log2 units, sum of exponentials)
   int64_t part_rows;
   int32_t n_q_heads, n_kv_heads, group, head_dim;
+  FastDiv group_div;  // division by `group`
   float scale_log2e;  // softmax scale * log2(e)
   int32_t q_ready;    // q is already rotated and multiplied by scale_log2e (the RoPE pre-pass ran)
   int32_t n_splits;
