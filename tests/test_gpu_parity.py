@@ -248,6 +248,46 @@ def test_final_block_matches_oracle(ba, case, layout):
     assert_attention_close(host_f64(o), ref, name)
 
 
+def _with_component(bits, rows, dim, value):
+    """Copy of a bf16 tensor with one head dimension of some rows set to a value (exact in bf16)."""
+    x = wl.bf16_bits_to_f32(bits).copy()
+    x[rows, :, dim] = np.float32(value)
+    return wl.f32_to_bf16_bits(x)
+
+
+@pytest.mark.parametrize("where", ["final", "encode"])
+def test_late_keys_far_above_first_tile_move_the_reference(ba, where):
+    """Every query carries +8 and the first 64 keys carry -32 in a slowly rotating head dimension, so
+    the first key tile scores about 46 (log2 units) below the later ones: a reference taken from
+    the first tile has to move when the second arrives, and across KV splits the partials carry
+    very different references.  The keys that matter have ordinary scores, so the usual
+    tolerance applies."""
+    hq, hkv, d = 4, 2, 64
+    th = oracle.theta(10000.0, d)
+    f = oracle.bf16_bits_to_f64
+    heads = ba.Heads(hq, hkv, d, 10000.0)
+    slow = d - 2  # first element of the last interleaved pair: 1.3e-4 rad per position
+    if where == "final":
+        tc, lq = 1000, 70
+        cu_q, cu_ctx = np.array([0, lq], dtype=np.int32), np.array([0, tc], dtype=np.int32)
+        qb, kfb, vfb = gen_qkv(900, lq, hq, hkv, d)
+        kcb, vcb = wl.normal_bf16_bits(903, (tc, hkv, d)), wl.normal_bf16_bits(904, (tc, hkv, d))
+        qb = _with_component(qb, slice(None), slow, 8.0)
+        kcb = _with_component(_with_component(kcb, slice(None), slow, 0.0), slice(0, 64), slow, -32.0)
+        kfb = _with_component(kfb, slice(None), slow, 0.0)
+        ref = oracle.final_block(f(qb), f(kcb), f(vcb), f(kfb), f(vfb), cu_q, cu_ctx, th)
+        o = gpu_final(ba, heads, dev_bf16(qb), dev_bf16(kcb), dev_bf16(vcb), dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
+    else:
+        offs = np.array([0, 600, 900], dtype=np.int32)
+        qb, kb, vb = gen_qkv(910, 900, hq, hkv, d)
+        qb = _with_component(qb, slice(None), slow, 8.0)
+        kb = _with_component(kb, slice(None), slow, 0.0)
+        kb = _with_component(_with_component(kb, slice(0, 64), slow, -32.0), slice(600, 664), slow, -32.0)
+        ref, _ = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, th)
+        o, _ = gpu_encode(ba, heads, qb, kb, vb, offs)
+    assert_attention_close(host_f64(o), ref, "late keys far above the first tile, " + where)
+
+
 def test_final_block_rope_none_qpos_override_and_rot_out(ba):
     torch = torch_mod()
     hq, hkv, d = 8, 2, 128
