@@ -60,11 +60,13 @@ struct Geo {
 };
 
 struct Problem {
-  int q_tok0;   // first query token (row of q / o / kf / vf)
-  int lq;       // query tokens
-  int ctx0;     // first context row
-  int tctx;     // context rows
-  int jt;       // row tile inside the problem
+  int q_tok0;     // first query token (row of q / o / kf / vf)
+  int lq;         // query tokens
+  int ctx0;       // first context row (contiguous context)
+  int tctx;       // context rows (contiguous context)
+  int blk0, blk1; // cached blocks of the context (block table)
+  int ctx_tiles;  // key tiles of the context
+  int jt;         // row tile inside the problem
 };
 
 __device__ __forceinline__ int find_segment(const int32_t *tile_start, int n, int tile) {
@@ -83,6 +85,8 @@ __device__ __forceinline__ Problem locate(const EncodeMeta &m, int tile) {
   pr.lq = m.offs[b + 1] - m.offs[b];
   pr.ctx0 = 0;
   pr.tctx = 0;
+  pr.blk0 = pr.blk1 = 0;
+  pr.ctx_tiles = 0;
   pr.jt = tile - m.tile_start[b];
   return pr;
 }
@@ -93,6 +97,21 @@ __device__ __forceinline__ Problem locate(const FinalMeta &m, int tile) {
   pr.lq = m.cu_q[n + 1] - m.cu_q[n];
   pr.ctx0 = m.cu_ctx[n];
   pr.tctx = m.cu_ctx[n + 1] - m.cu_ctx[n];
+  pr.blk0 = pr.blk1 = 0;
+  pr.ctx_tiles = (pr.tctx + kTileKeys - 1) / kTileKeys;
+  pr.jt = tile - m.tile_start[n];
+  return pr;
+}
+__device__ __forceinline__ Problem locate(const FinalBlocksMeta &m, int tile) {
+  int n = find_segment(m.tile_start, m.n, tile);
+  Problem pr;
+  pr.q_tok0 = m.cu_q[n];
+  pr.lq = m.cu_q[n + 1] - m.cu_q[n];
+  pr.ctx0 = 0;
+  pr.tctx = 0;
+  pr.blk0 = m.cu_blk[n];
+  pr.blk1 = m.cu_blk[n + 1];
+  pr.ctx_tiles = m.ctx_tiles[n];
   pr.jt = tile - m.tile_start[n];
   return pr;
 }
@@ -167,7 +186,8 @@ __device__ long long g_wg[1024][4];  // per workgroup: wall clock at start and e
 template <int D, typename Meta>
 __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta) {
   using G = Geo<D>;
-  constexpr bool kFinal = std::is_same<Meta, FinalMeta>::value;
+  constexpr bool kBlocks = std::is_same<Meta, FinalBlocksMeta>::value;  // context = table of cached blocks
+  constexpr bool kFinal = std::is_same<Meta, FinalMeta>::value || kBlocks;
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
   lds_char *smem = (lds_char *)smem_generic;
   // LDS map: kNumKBuf K buffers from byte 0, then kNumVBuf V buffers, TILEB bytes each.
@@ -207,7 +227,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const int row0 = pr.jt * kTileRows;
 
   // ---- key tiles this work item walks ---------------------------------------------------
-  const int n_ctx_tiles = (pr.tctx + kTileKeys - 1) / kTileKeys;
+  // The key range is a list of segments: fully visible context segments first (one for a
+  // contiguous context, one per cached block with a block table), then the causal segment (the
+  // problem's own keys).  Tiles never straddle segments.
+  const int n_ctx_tiles = pr.ctx_tiles;
+  const int n_ctx_segs = kBlocks ? pr.blk1 - pr.blk0 : (n_ctx_tiles > 0 ? 1 : 0);
   const int last_row = min(n_rows, row0 + kTileRows) - 1;
   const int last_tok = (int)fast_div((uint32_t)last_row, p.group_div);
   const int n_causal_tiles = last_tok / kTileKeys + 1;
@@ -256,15 +280,12 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const char *c_base = role_b ? vc_base : kc_base;  // context segment of this wave's kind
   const char *f_base = role_b ? vf_base : kf_base;  // causal segment
   const uint32_t c_rb = role_b ? vc_rb : kc_rb, f_rb = role_b ? vf_rb : kf_rb;
-  // Tiles [0, n_full_prim) of the problem are full tiles of its first ("primary") segment: they
-  // take the short path with cached lane offsets.
-  const bool prim_ctx = n_ctx_tiles > 0;
-  const char *prim_base = prim_ctx ? c_base : f_base;
-  const uint32_t prim_rb = prim_ctx ? c_rb : f_rb;
-  const int n_full_prim = (prim_ctx ? pr.tctx : pr.lq) / kTileKeys;
+  // Full tiles of segments with the "primary" row stride (the context's if there is one, else the
+  // causal segment's) take a short path with cached lane offsets.
+  const uint32_t prim_rb = n_ctx_segs > 0 ? c_rb : f_rb;
   int g_row[G::IPW];
   uint32_t g_chunk[G::IPW];  // byte offset of the source chunk inside its row
-  uint32_t g_src[G::IPW];    // full per-lane byte offsets inside a full primary tile
+  uint32_t g_src[G::IPW];    // full per-lane byte offsets inside a full tile of primary stride
 #pragma unroll
   for (int i = 0; i < G::IPW; ++i) {
     const int row = ((wave & (kWaves / 2 - 1)) * G::IPW + i) * G::RPI + lane / G::CPR;
@@ -277,33 +298,74 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   }
   const uint32_t lds_copy =
       (uint32_t)(uintptr_t)smem + (role_b ? VBASE : 0u) + (wave & (kWaves / 2 - 1)) * G::IPW * 1024;
-  // Copy of tile t of the problem into buffer `buf` of this wave's kind: a wave-uniform
+
+  // segment s of this problem: rows that exist, key tiles walked, first row (of this wave's kind)
+  auto seg_len = [&](int sg) __attribute__((always_inline)) {
+    if (sg >= n_ctx_segs) return pr.lq;
+    if constexpr (kBlocks) return (int)meta.blk_len[pr.blk0 + sg];
+    return pr.tctx;
+  };
+  auto seg_tiles = [&](int sg) __attribute__((always_inline)) {
+    return sg >= n_ctx_segs ? n_causal_tiles : (seg_len(sg) + kTileKeys - 1) / kTileKeys;
+  };
+  auto seg_base = [&](int sg) __attribute__((always_inline)) {
+    if (sg >= n_ctx_segs) return f_base;
+    if constexpr (kBlocks) return c_base + (uint64_t)(uint32_t)meta.blk_off[pr.blk0 + sg] * (uint64_t)c_rb;
+    return c_base;
+  };
+  // position in the walk: segment, tile inside it, tiles left in it (this one included)
+  struct Cursor {
+    int seg, ts, rem;
+  };
+  auto cursor_at = [&](int t) __attribute__((always_inline)) {
+    Cursor c;
+    if (t >= n_ctx_tiles) {
+      c.seg = n_ctx_segs;
+      c.ts = t - n_ctx_tiles;
+      c.rem = n_causal_tiles - c.ts;
+    } else if constexpr (kBlocks) {
+      int lo = pr.blk0, hi = pr.blk1;  // largest block whose first tile is <= t
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (meta.blk_tile0[mid] <= t) lo = mid; else hi = mid;
+      }
+      c.seg = lo - pr.blk0;
+      c.ts = t - meta.blk_tile0[lo];
+      c.rem = seg_tiles(c.seg) - c.ts;
+    } else {
+      c.seg = 0;
+      c.ts = t;
+      c.rem = n_ctx_tiles - t;
+    }
+    return c;
+  };
+  auto advance = [&](Cursor &c) __attribute__((always_inline)) {
+    ++c.ts;
+    --c.rem;
+    if (c.rem == 0 && c.seg < n_ctx_segs) {  // (the host drops empty blocks: a segment has a tile)
+      ++c.seg;
+      c.ts = 0;
+      c.rem = seg_tiles(c.seg);
+    }
+  };
+  // Copy of the tile under a cursor into buffer `buf` of this wave's kind: a wave-uniform
   // preparation and IPW wave instructions, kept apart so that the instructions can be spread over
   // the gaps of an MFMA stream.
   struct CopyJob {
     const char *ptr;  // first row of the tile
     uint32_t dst;     // LDS byte address of this wave's first 1 KB piece
     uint32_t rb;      // row stride, bytes
-    int valid;        // rows of the tile that exist; kTileKeys on the short path
-    bool full;        // full tile of the primary segment: cached lane offsets
+    int valid;        // rows of the tile that exist
+    bool full;        // all rows exist and the stride is the primary one: cached lane offsets
   };
-  auto copy_prepare = [&](int t, int buf) __attribute__((always_inline)) {
-    CopyJob c;
-    c.dst = lds_copy + (uint32_t)buf * TB;
-    c.full = t < n_full_prim;
-    if (c.full) {
-      c.ptr = prim_base + (uint64_t)(uint32_t)t * (uint64_t)(prim_rb * (uint32_t)kTileKeys);
-      c.rb = prim_rb;
-      c.valid = kTileKeys;
-    } else {
-      asm volatile("" ::: "memory");  // rare: keep it out of the short path
-      const bool isctx = t < n_ctx_tiles;
-      const int tc = isctx ? t : t - n_ctx_tiles;
-      c.rb = isctx ? c_rb : f_rb;
-      c.ptr = (isctx ? c_base : f_base) + (uint64_t)(uint32_t)tc * (uint64_t)(c.rb * (uint32_t)kTileKeys);
-      c.valid = min(kTileKeys, (isctx ? pr.tctx : pr.lq) - tc * kTileKeys);
-    }
-    return c;
+  auto copy_prepare = [&](const Cursor &c, int buf) __attribute__((always_inline)) {
+    CopyJob j;
+    j.dst = lds_copy + (uint32_t)buf * TB;
+    j.rb = c.seg >= n_ctx_segs ? f_rb : c_rb;
+    j.ptr = seg_base(c.seg) + (uint64_t)(uint32_t)c.ts * (uint64_t)(j.rb * (uint32_t)kTileKeys);
+    j.valid = min(kTileKeys, seg_len(c.seg) - c.ts * kTileKeys);
+    j.full = j.valid == kTileKeys && j.rb == prim_rb;
+    return j;
   };
   auto copy_part = [&](const CopyJob &c, int i) __attribute__((always_inline)) {
     if (c.full) {
@@ -312,11 +374,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       asm volatile("" ::: "memory");
       lds_dma16(c.ptr, (uint32_t)min(g_row[i], c.valid - 1) * c.rb + g_chunk[i], c.dst + i * 1024);
     }
-  };
-  auto issue_tile = [&](int t, int buf) __attribute__((always_inline)) {
-    const CopyJob c = copy_prepare(t, buf);
-#pragma unroll
-    for (int i = 0; i < G::IPW; ++i) copy_part(c, i);
   };
 
   // ---- running state -----------------------------------------------------------------------------
@@ -369,23 +426,18 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   // (the K fragments are requested whether or not a next tile exists: the buffer is inside LDS
   // either way and without a next tile nothing consumes them)
   // The wave has issue slots to spare while its MFMAs execute, so the block also carries this
-  // wave's share of a tile copy (`copy`: tile t_copy into buffer buf_copy), one LDS-direct load
+  // wave's share of a tile copy (prepared by the caller, in the softmax half), one LDS-direct load
   // behind every second MFMA, and builds the tuple the score accumulators start from.
-  // `steady` (compile time): a next tile exists and the copy is a full tile of the primary segment
-  // at cp_ptr; otherwise both are decided at run time and the copy source is worked out in full.
-  auto mfma_block = [&](auto steady_c, uint32_t vofs, uint32_t kofs, bool more, bool copy, int t_copy,
-                        int buf_copy, const char *cp_ptr, const bf16x8_t (&pf)[4], f32x16_t (&sacc)[2],
+  // (copy: whether there is a tile to copy; cp_off: this lane's source offsets for it)
+  auto mfma_block = [&](uint32_t vofs, uint32_t kofs, bool more, bool copy, const CopyJob &cj,
+                        const uint32_t (&cp_off)[G::IPW], const bf16x8_t (&pf)[4], f32x16_t (&sacc)[2],
                         bf16x8_t (&fr)[W]) __attribute__((always_inline)) {
-    constexpr bool steady = decltype(steady_c)::value;
 #ifdef BA_VAR_NOMFMA
     return;
 #endif
     // the wave in its MFMA block goes first at the issue arbiter; the other wave of the SIMD, in its
     // exponentials, fills the slots between
     __builtin_amdgcn_s_setprio(3);
-    CopyJob cj;
-    if (!steady && copy) cj = copy_prepare(t_copy, buf_copy);
-    const uint32_t cp_dst = lds_copy + (uint32_t)buf_copy * TB;
 #pragma unroll
     for (int st = 0; st < NPV; ++st) {
       if (st + W - 1 < NS) fr[(st + W - 1) % W] = frag_read(st + W - 1, vofs, kofs);
@@ -393,13 +445,13 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % W], pf[kc], oacc[dt], 0, 0, 0);
       if ((st & 1) && st / 2 < G::IPW) {
 #ifndef BA_VAR_NOCOPY
-        if (steady) lds_dma16(cp_ptr, g_src[st / 2], cp_dst + (st / 2) * 1024);
-        else if (copy) copy_part(cj, st / 2);
+        const int i = st / 2;
+        if (__builtin_expect(copy, 1)) lds_dma16(cj.ptr, cp_off[i], cj.dst + i * 1024);
 #endif
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (steady || more) {
+    if (more) {
 #pragma unroll
       for (int st = NPV; st < NS; ++st) {
         if (st + W - 1 < NS) fr[(st + W - 1) % W] = frag_read(st + W - 1, vofs, kofs);
@@ -484,14 +536,13 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   };
   // The softmax step of one tile: mask where needed (diagonal and ragged tiles only), turn the
   // exponents into P, and keep the running sum.  All branches are wave-uniform.
-  auto softmax = [&](int t, bool first, f32x16_t (&sacc)[2], bf16x8_t (&pf)[4]) __attribute__((always_inline)) {
+  auto softmax = [&](const Cursor &cm, bool first, f32x16_t (&sacc)[2], bf16x8_t (&pf)[4]) __attribute__((always_inline)) {
 #ifdef BA_VAR_NOSM
     if (!first) return;
 #endif
-    const bool isctx = t < n_ctx_tiles;
-    const int tc = isctx ? t : t - n_ctx_tiles;
-    const int valid = min(kTileKeys, (isctx ? pr.tctx : pr.lq) - tc * kTileKeys);
-    const int key0 = tc * kTileKeys;
+    const bool isctx = cm.seg < n_ctx_segs;
+    const int key0 = cm.ts * kTileKeys;
+    const int valid = min(kTileKeys, seg_len(cm.seg) - key0);
     const bool need_mask = isctx ? (valid < kTileKeys) : (key0 + kTileKeys - 1 > first_tok_wave) || (valid < kTileKeys);
     if (need_mask) {
       asm volatile("" ::: "memory");  // keep this a real branch: never speculate the selects
@@ -533,23 +584,33 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   //     half-period   -1      0        1            2            3         ...
   //     waves 0..3   QK(0)  SM(0)  PV(0) QK(1)    SM(1)      PV(1) QK(2)
   //     waves 4..7     -    QK(0)    SM(0)     PV(0) QK(1)     SM(1)
-  // The softmax half has slack (MFMA is the longer half), so the copies are issued there: waves
-  // 0..3 fetch K(i+3) after softmax(i), waves 4..7 fetch V(i+3), each then waits until the tile it
-  // started two iterations earlier (K(i+1) resp. V(i+1)) has landed, and the barrier that ends the
-  // half-period publishes it.  A buffer is refilled only after the barrier that follows its last
-  // reader (K(i-1): waves 4..7 in half-period 2i-2; V(i-1): waves 4..7 in half-period 2i).
+  // Waves 0..3 fetch K(i+3) and waves 4..7 V(i+3) from inside their MFMA block of iteration i; at
+  // the end of its softmax half a wave waits until the tile it started two iterations earlier
+  // (K(i+1) resp. V(i+1)) has landed, and the barrier that ends the half-period publishes it.  A
+  // buffer is refilled only after the barrier that follows its last reader.
+  Cursor cp = cursor_at(t_begin);  // the next tile to copy
+  const char *cp_ptr = nullptr;    // where the tile after the last copied one starts (same segment)
   if (n_t > 0) {
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
-      if (j < n_t) issue_tile(t_begin + j, j);
+      if (j < n_t) {
+        const CopyJob c = copy_prepare(cp, j);
+#pragma unroll
+        for (int i = 0; i < G::IPW; ++i) copy_part(c, i);
+        cp_ptr = c.ptr + (uint64_t)(c.rb * (uint32_t)kTileKeys);
+        advance(cp);
+      }
     }
   }
   BA_MARK_ALWAYS(79, 1);
 
   // ---- Q fragments (B operand of S^T = K Q^T).  With rotary embedding the rows come from the
   //      RoPE pre-pass, already rotated and multiplied by scale * log2(e); otherwise they are the
-  //      caller's and are scaled here, before one rounding back to bf16 ------------------------------
-  {
+  //      caller's and are scaled here, before one rounding back to bf16.  With a block table the
+  //      cached keys of block b stay at the positions they were encoded at and the queries are
+  //      turned back by the block's shift instead (rot >= 0: row of the table of rotations), which
+  //      gives the same scores as re-encoding the keys (Eq. 2 and 3 applied to q instead of k) ------
+  auto load_q = [&](int rot) __attribute__((always_inline)) {
     const int g = my_row - my_tok * Gq;
     const int head = kvh * Gq + g;
     const uint16_t *qp = p.q + (int64_t)(pr.q_tok0 + my_tok) * p.q_st + (int64_t)head * p.q_sh + hf * 8;
@@ -566,9 +627,48 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
         for (int e = 0; e < 4; ++e)
           raw[kk][e] = pack_bf16(bf16_lo(raw[kk][e]) * c2, bf16_hi(raw[kk][e]) * c2);
     }
+    if (kBlocks && rot >= 0) {
+      // (cos, sin) of minus the block's shift times theta_j, j = 0 .. D/2 - 1
+      const f32x4_t *tab = reinterpret_cast<const f32x4_t *>(p.blk_rot + (int64_t)rot * D);
+      if (p.rope_layout == 0) {
+#pragma unroll
+        for (int kk = 0; kk < G::KCH; ++kk) {
+          // this lane's pairs: frequencies kk * 8 + hf * 4 + e
+          const f32x4_t cs0 = tab[(kk * 8 + hf * 4) / 2], cs1 = tab[(kk * 8 + hf * 4) / 2 + 1];
+          const float c[4] = {cs0[0], cs0[2], cs1[0], cs1[2]}, sn[4] = {cs0[1], cs0[3], cs1[1], cs1[3]};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float x = bf16_lo(raw[kk][e]), y = bf16_hi(raw[kk][e]);
+            raw[kk][e] = pack_bf16(c[e] * x - sn[e] * y, sn[e] * x + c[e] * y);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < G::KCH / 2; ++kk) {
+          // dims kk * 16 + hf * 8 + (0..7) pair with the same dims + D/2: frequencies = those dims
+          f32x4_t cs[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) cs[u] = tab[(kk * 16 + hf * 8) / 2 + u];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float c0 = cs[e][0], s0 = cs[e][1], c1 = cs[e][2], s1 = cs[e][3];
+            const uint32_t wa = raw[kk][e], wb = raw[kk + G::KCH / 2][e];
+            const float xa0 = bf16_lo(wa), xa1 = bf16_hi(wa), xb0 = bf16_lo(wb), xb1 = bf16_hi(wb);
+            raw[kk][e] = pack_bf16(c0 * xa0 - s0 * xb0, c1 * xa1 - s1 * xb1);
+            raw[kk + G::KCH / 2][e] = pack_bf16(s0 * xa0 + c0 * xb0, s1 * xa1 + c1 * xb1);
+          }
+        }
+      }
+    }
 #pragma unroll
     for (int kk = 0; kk < G::KCH; ++kk) qf[kk] = __builtin_bit_cast(bf16x8_t, raw[kk]);
-  }
+  };
+  Cursor cm = cursor_at(t_begin);  // the tile whose softmax comes next
+  auto rot_of = [&](int sg) __attribute__((always_inline)) {
+    if constexpr (kBlocks) return sg < n_ctx_segs ? meta.rot_base + pr.blk0 + sg : -1;
+    return -1;
+  };
+  load_q(rot_of(cm.seg));
   BA_MARK_ALWAYS(79, 2);
   dma_wait<0>();  // unconditional: first tiles and Q fragments are complete from here on
   BA_MARK_ALWAYS(79, 3);
@@ -586,34 +686,68 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       qk_first(0, sacc);
       wg_barrier();
     }
-    // One iteration.  Iterations whose copy (tile i+3) is a full tile of the primary segment run a
-    // version with every such decision made at compile time and the source pointer carried along.
-    auto iteration = [&](auto steady_c, int i, const char *cp_ptr) __attribute__((always_inline)) {
+    // One iteration.  The copy of tile i+3 is prepared here, in the softmax half, where scalar
+    // instructions cost nothing on the matrix pipe: a full tile that follows the last copied one in
+    // memory only needs the pointer carried along; anything else (first tile of a segment, ragged
+    // tile, other stride) is worked out from the cursor.  `steady` (compile time) promises the
+    // common case: tiles i+1 and i+3 exist, tile i+1 lies in the same segment as tile i, and the
+    // copy is such a following full tile.
+    const uint64_t tile_bytes = (uint64_t)(prim_rb * (uint32_t)kTileKeys);
+    auto iteration = [&](auto steady_c, int i) __attribute__((always_inline)) {
       constexpr bool steady = decltype(steady_c)::value;
-      softmax(t_begin + i, i == 0, sacc, pf);
+      softmax(cm, i == 0, sacc, pf);
       // tile i+1 of this wave's kind must have landed before the barrier; the only copy that
       // may be younger is tile i+2's (tile i+3's starts inside the MFMA block below)
 #ifndef BA_VAR_NOWAIT
       if (steady || i + 2 < n_t) dma_wait<G::IPW>(); else dma_wait<0>();
 #endif
+      if (kBlocks && !steady && i + 1 < n_t && cm.rem == 1) load_q(rot_of(cm.seg + 1));  // tile i+1 opens a segment
+      const bool copy = steady || i + 3 < n_t;
+      CopyJob cj;
+      cj.ptr = cp_ptr;
+      cj.dst = lds_copy + (uint32_t)((i + 3) & (kNumKBuf - 1)) * TB;
+      cj.rb = prim_rb;
+      cj.valid = kTileKeys;
+      cj.full = true;
+      uint32_t cp_off[G::IPW];
+#pragma unroll
+      for (int u = 0; u < G::IPW; ++u) cp_off[u] = g_src[u];
+      if (copy) {
+        const uint32_t rb = cp.seg >= n_ctx_segs ? f_rb : c_rb;
+        if (steady || (cp.ts > 0 && rb == prim_rb && (cp.ts + 1) * kTileKeys <= seg_len(cp.seg))) {
+          cp_ptr += tile_bytes;
+        } else {
+          asm volatile("" ::: "memory");
+          cj = copy_prepare(cp, (i + 3) & (kNumKBuf - 1));
+          if (!cj.full) {
+#pragma unroll
+            for (int u = 0; u < G::IPW; ++u)
+              cp_off[u] = (uint32_t)min(g_row[u], cj.valid - 1) * cj.rb + g_chunk[u];
+          }
+          cp_ptr = cj.ptr + (uint64_t)(cj.rb * (uint32_t)kTileKeys);
+        }
+        advance(cp);
+      }
       const uint32_t vofs = VBASE + (i & (kNumVBuf - 1)) * TB;
       preload(vofs, fr);
       wg_barrier();
-      mfma_block(steady_c, vofs, ((i + 1) & (kNumKBuf - 1)) * TB, i + 1 < n_t, i + 3 < n_t, t_begin + i + 3,
-                 (i + 3) & (kNumKBuf - 1), cp_ptr, pf, sacc, fr);
+      mfma_block(vofs, ((i + 1) & (kNumKBuf - 1)) * TB, steady || i + 1 < n_t, copy, cj, cp_off, pf, sacc, fr);
       if (steady || !role_b || i + 1 < n_t) wg_barrier();
+      advance(cm);
     };
-    const int n_steady = max(0, min(n_t, n_full_prim - t_begin) - 3);
-    const uint64_t tile_bytes = (uint64_t)(prim_rb * (uint32_t)kTileKeys);
-    const char *cp_ptr = prim_base + (uint64_t)(uint32_t)(t_begin + 3) * tile_bytes;
+    // With a contiguous context (or none) the steady iterations form one run from the start: until
+    // the copy cursor or the compute cursor reaches the end of the segment they start in.
+    int n_steady = 0;
+    if (!kBlocks) {
+      const int full_tiles = seg_len(cp.seg) / kTileKeys;  // of the segment the copy cursor is in
+      const bool fast = (cp.seg >= n_ctx_segs ? f_rb : c_rb) == prim_rb && cp.ts > 0;
+      n_steady = fast ? max(0, min(min(n_t - 3, full_tiles - cp.ts), cm.rem - 1)) : 0;
+    }
     int i = 0;
 #pragma unroll 1
-    for (; i < n_steady; ++i) {
-      iteration(std::true_type{}, i, cp_ptr);
-      cp_ptr += tile_bytes;
-    }
+    for (; i < n_steady; ++i) iteration(std::true_type{}, i);
 #pragma unroll 1
-    for (; i < n_t; ++i) iteration(std::false_type{}, i, nullptr);
+    for (; i < n_t; ++i) iteration(std::false_type{}, i);
   }
   BA_MARK_ALWAYS(79, 4);
   static_assert(kNumKBuf == 4 && kNumVBuf == 4, "the copy distances above assume four buffers of each kind");
@@ -776,6 +910,12 @@ hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipSt
 hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, hipStream_t stream) {
   if (p.head_dim == 128) return launch_attn_t<128, FinalMeta>(p, meta, stream);
   if (p.head_dim == 64) return launch_attn_t<64, FinalMeta>(p, meta, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMeta &meta, hipStream_t stream) {
+  if (p.head_dim == 128) return launch_attn_t<128, FinalBlocksMeta>(p, meta, stream);
+  if (p.head_dim == 64) return launch_attn_t<64, FinalBlocksMeta>(p, meta, stream);
   return hipErrorInvalidValue;
 }
 

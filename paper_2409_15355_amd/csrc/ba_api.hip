@@ -270,7 +270,7 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
   hipError_t e;
   {
     ProfileScope ps(BA_PROFILE_REENCODE, stream);
-    e = ba::launch_rope_prepass(p, segs, rt, stream);
+    e = ba::launch_rope_prepass(p, segs, nullptr, rt, stream);
   }
   if (e != hipSuccess) return device_fail(e, "RoPE pre-pass launch");
   return BA_OK;
@@ -424,6 +424,7 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ap.head_dim = D;
   ap.scale_log2e = scale_log2e(heads);
   ap.q_ready = rope_mode == BA_ROPE_APPLY;
+  ap.rope_layout = heads->rope_layout;
   ap.n_splits = 1;
 
   for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
@@ -652,6 +653,7 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   ap.head_dim = D;
   ap.scale_log2e = scale_log2e(heads);
   ap.q_ready = rope_mode == BA_ROPE_APPLY;
+  ap.rope_layout = heads->rope_layout;
   ap.n_splits = pl.n_splits;
 
   for (int n0 = 0; n0 < n_prompts; n0 += ba::kFinMaxPrompts) {

@@ -43,6 +43,9 @@ struct ReencParams {
 hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
                            hipStream_t stream);
 
+constexpr int kBlkMaxPrompts = 64;   // final block over a block table: prompts per launch
+constexpr int kBlkMaxBlocks = 1024;  // ... and cached blocks per launch
+
 // ---------------------------------------------------------------- RoPE pre-pass ------
 // Fresh (un-rotated) Q and K rows of a run of consecutive segments: segment s covers tokens
 // [start[s], start[s+1]) and its first token has position pos0[s].
@@ -65,10 +68,17 @@ struct RopePrepassParams {
   int32_t n_q_heads, n_kv_heads, head_dim, layout;
   int32_t heads_per_thread;
   int32_t do_q, do_k;
+  float *rot_dst;    // [n_rot][D/2][2]: (cos, sin) of rot_angle[b] * theta_j, or null
+  int32_t n_rot;
 };
 
-hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeTable &rt,
-                               hipStream_t stream);
+// positions (in tokens) by which the rows of the rotation table turn
+struct RopeRots {
+  int32_t angle[kBlkMaxBlocks];
+};
+
+hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeRots *rots,
+                               const RopeTable &rt, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention ----------
 // Division of a 32-bit unsigned number by a divisor fixed on the host (round-up multiplier of
@@ -109,6 +119,8 @@ struct AttnParams {
   FastDiv group_div;  // division by `group`
   float scale_log2e;  // softmax scale * log2(e)
   int32_t q_ready;    // q is already rotated and multiplied by scale_log2e (the RoPE pre-pass ran)
+  int32_t rope_layout;
+  const float *blk_rot;  // block table only: [blocks][D/2][2] (cos, sin) of minus each block's shift
   int32_t n_splits;
   int32_t total_tiles;  // row tiles over all problems of this launch
 };
@@ -128,7 +140,21 @@ struct FinalMeta {
   int32_t tile_start[kFinMaxPrompts + 1];
 };
 
+// Final block over a table of cached blocks (each at the positions it was encoded at).
+struct FinalBlocksMeta {
+  int32_t n;
+  int32_t rot_base;  // row of AttnParams::blk_rot that belongs to block 0 of this launch
+  int32_t cu_q[kBlkMaxPrompts + 1];
+  int32_t cu_blk[kBlkMaxPrompts + 1];     // blocks of prompt n: [cu_blk[n], cu_blk[n+1])
+  int32_t ctx_tiles[kBlkMaxPrompts];      // key tiles of prompt n's context
+  int32_t tile_start[kBlkMaxPrompts + 1]; // first row tile of each prompt
+  int32_t blk_off[kBlkMaxBlocks];         // first cache row of the block
+  int32_t blk_len[kBlkMaxBlocks];         // rows (>= 1)
+  int32_t blk_tile0[kBlkMaxBlocks];       // first key tile of the block inside its prompt
+};
+
 hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
+hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMeta &meta, hipStream_t stream);
 hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, hipStream_t stream);
 // Merge split-KV partials into the bf16 output.  rows = tokens * n_q_heads.
 hipError_t launch_combine(const AttnParams &p, int64_t n_tokens, hipStream_t stream);

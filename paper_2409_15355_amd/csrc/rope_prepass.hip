@@ -17,6 +17,18 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// Table of rotations for the block-table form of the final block: row b, frequency j holds
+// (cos, sin) of angle[b] * theta_j.  One thread per entry.
+__global__ __launch_bounds__(kThreads) void rope_rot_table_kernel(float *dst, int n_rot, int half_dim, RopeRots rots,
+                                                                  RopeTable rt) {
+  const int idx = blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= n_rot * half_dim) return;
+  const int b = idx / half_dim, j = idx - b * half_dim;
+  float c, s;
+  sincos_phase(rope_phase(rots.angle[b], rt.turns[j]), c, s);
+  reinterpret_cast<float2 *>(dst)[idx] = make_float2(c, s);
+}
+
 template <int D, int LAYOUT>
 __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParams p, RopeSegs segs,
                                                                 RopeTable rt) {
@@ -103,8 +115,15 @@ hipError_t launch_d(const RopePrepassParams &p, const RopeSegs &segs, const Rope
 
 }  // namespace
 
-hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeTable &rt,
-                               hipStream_t stream) {
+hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeRots *rots,
+                               const RopeTable &rt, hipStream_t stream) {
+  if (p.rot_dst && p.n_rot > 0 && rots) {
+    const int entries = p.n_rot * (p.head_dim / 2);
+    hipLaunchKernelGGL(rope_rot_table_kernel, dim3((entries + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
+                       p.rot_dst, p.n_rot, p.head_dim / 2, *rots, rt);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   if (p.head_dim == 128) return launch_d<128>(p, segs, rt, stream);
   if (p.head_dim == 64) return launch_d<64>(p, segs, rt, stream);
   return hipErrorInvalidValue;
