@@ -22,6 +22,7 @@ Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -78,14 +79,21 @@ def main() -> int:
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record()
-        for _ in range(steps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3
+        # a full collection of the interpreter's garbage takes tens of milliseconds in this process
+        # and would land in the middle of a timed region every few hundred calls
+        gc.collect()
+        gc.disable()
+        try:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            wall_ms = (time.perf_counter() - t0) * 1e3
+        finally:
+            gc.enable()
         return max(e0.elapsed_time(e1), 0.0) / steps, wall_ms / steps
 
     # ------------------------------------------------------------------ headline: config 5
@@ -172,6 +180,39 @@ def main() -> int:
                                   f"({cpu_s:.1f} s)",
                         "parity_on_sample": {"max_abs": float(err.max()), "mean_abs": float(err.mean())}}
         del kc64, vc64
+    # ---- the same layers straight from the block cache (re-encoding folded into the attention kernel)
+    #      against the two-step route (re-encode the layer's cached K, then the final block)
+    cached_row = None
+    if not args.no_rows and args.only in ("", "cached"):
+        nb = len(w.prompts[0].passage_lens)
+        L = t_ctx // nb
+        b_off = (np.arange(nb) * L).astype(np.int32)
+        b_len = np.full(nb, L, dtype=np.int32)
+        cu_blk = np.array([0, nb], dtype=np.int32)
+        wsc = torch.empty(ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, b_len),
+                          dtype=torch.uint8, device=dev)
+        k_re = torch.empty_like(layers[0]["kc"])
+
+        def step_cached():
+            for t in layers:
+                ba.ba_final_block_attention_cached(heads, t["q"], t["kc"], t["vc"], t["kf"], t["vf"], t["o"], None,
+                                                   cu_q, cu_blk, b_off, b_len, None, None, None, wsc)
+
+        def step_two():
+            for t in layers:
+                ba.ba_reencode_positions(heads, t["kc"], k_re, b_off, b_off, b_len, None, b_off, ba.REENC_SHIFT)
+                ba.ba_final_block_attention(heads, t["q"], k_re, t["vc"], t["kf"], t["vf"], t["o"], None, cu_q,
+                                            cu_ctx, None, ba.ROPE_APPLY, ws)
+
+        n_rep = args.steps if args.only == "" else 10
+        ms_c, _ = timed(step_cached, n_rep, 3)
+        ms_2, _ = timed(step_two, n_rep, 3)
+        cached_row = {"ms_per_layer": round(ms_c / w.n_layers, 5),
+                      "TFLOPs": round(flops_layer / (ms_c / w.n_layers * 1e-3) / 1e12, 1),
+                      "two_step_ms_per_layer": round(ms_2 / w.n_layers, 5),
+                      "note": "31 cached blocks of 1024 tokens at local positions; two-step = ba_reencode_positions "
+                              "of the layer's K + ba_final_block_attention"}
+        del wsc, k_re
     del layers, ws
     torch.cuda.empty_cache()
 
@@ -186,6 +227,8 @@ def main() -> int:
 
     # ------------------------------------------------------------------ secondary rows
     rows_out = {}
+    if cached_row is not None:
+        rows_out["final_from_block_cache_cfg5"] = cached_row
     if not args.no_rows:
         # a-2 at config 4: 32 layers x 32 passages x 1000 tokens, permuted slots, gather form
         if args.only in ("", "reencode"):

@@ -172,6 +172,43 @@ size_t ba_final_block_attention_workspace_bytes(const ba_heads *heads, int32_t n
                                                 const int32_t *cu_q, const int32_t *cu_ctx,
                                                 int32_t rope_mode, int32_t have_k_f_rot_out);
 
+/*
+ * Steps 2 and 3 in one call -- final-block attention straight from the block cache
+ * (Section 2.3, Eq. 2 and 3; Section 2.5).
+ *
+ * Same result as ba_reencode_positions (BA_REENC_SHIFT) followed by ba_final_block_attention
+ * with BA_ROPE_APPLY, but the cached keys are never rewritten: block b of a prompt stays at
+ * the positions it was encoded at, and because a rotation of the key by the block's shift
+ * equals a rotation of the query by minus that shift (the score only depends on the position
+ * difference), the kernel turns its query fragments back once per block instead.  Many
+ * prompts can therefore attend to one cached copy of a block at different offsets.
+ *
+ * Prompt n owns rows [cu_q[n], cu_q[n+1]) of q_f / k_f / v_f / o_out (cu_q[0] = 0, at least one
+ * token) and blocks [cu_blk[n], cu_blk[n+1]) of the block table (cu_blk[0] = 0), in prompt
+ * order.  Block b is rows [blk_tok_off[b], blk_tok_off[b] + blk_len[b]) of k_cache / v_cache
+ * ([cache tokens, n_kv_heads, D], bf16); its keys carry the rotation of positions
+ * blk_old_pos0[b] + u (null -> 0, the paper's local positions); in this prompt it sits at
+ * positions blk_new_pos0[b] + u (null -> the total length of the prompt's earlier blocks).
+ * Final-block token i sits at q_pos0[n] + i (null -> the prompt's context length); q_f and k_f
+ * are un-rotated and are rotated inside; k_f_rot_out (nullable) receives the rotated k_f.
+ * Empty blocks are skipped.  At most 1024 non-empty blocks per prompt (BA_ERR_UNSUPPORTED
+ * beyond).  All arrays host; ws: 256-byte aligned, at least
+ * ba_final_block_attention_cached_workspace_bytes() bytes.
+ */
+int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *q_f,
+                                        const ba_tensor *k_cache, const ba_tensor *v_cache,
+                                        const ba_tensor *k_f, const ba_tensor *v_f,
+                                        const ba_tensor *o_out, const ba_tensor *k_f_rot_out,
+                                        int32_t n_prompts, const int32_t *cu_q,
+                                        const int32_t *cu_blk, const int32_t *blk_tok_off,
+                                        const int32_t *blk_len, const int32_t *blk_old_pos0,
+                                        const int32_t *blk_new_pos0, const int32_t *q_pos0,
+                                        void *ws, size_t ws_bytes, void *stream);
+size_t ba_final_block_attention_cached_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
+                                                       const int32_t *cu_q, const int32_t *cu_blk,
+                                                       const int32_t *blk_len,
+                                                       int32_t have_k_f_rot_out);
+
 #ifdef __cplusplus
 }
 #endif

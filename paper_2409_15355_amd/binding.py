@@ -25,7 +25,8 @@ REENC_SHIFT, REENC_ABSOLUTE = 0, 1
 EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin", "ba_profile_end",
            "ba_encode_blocks",
            "ba_encode_blocks_workspace_bytes", "ba_reencode_positions",
-           "ba_final_block_attention", "ba_final_block_attention_workspace_bytes"]
+           "ba_final_block_attention", "ba_final_block_attention_workspace_bytes",
+           "ba_final_block_attention_cached", "ba_final_block_attention_cached_workspace_bytes"]
 
 
 class BaTensor(ctypes.Structure):
@@ -87,6 +88,13 @@ def load():
     lib.ba_final_block_attention_workspace_bytes.restype = ctypes.c_size_t
     lib.ba_final_block_attention_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, ctypes.c_int32,
                                                              ctypes.c_int32]
+    lib.ba_final_block_attention_cached.restype = ctypes.c_int32
+    lib.ba_final_block_attention_cached.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, _TP, _TP, ctypes.c_int32, _I32P,
+                                                    _I32P, _I32P, _I32P, _I32P, _I32P, _I32P, ctypes.c_void_p,
+                                                    ctypes.c_size_t, ctypes.c_void_p]
+    lib.ba_final_block_attention_cached_workspace_bytes.restype = ctypes.c_size_t
+    lib.ba_final_block_attention_cached_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, _I32P,
+                                                                    ctypes.c_int32]
     _lib = lib
     return lib
 
@@ -216,3 +224,24 @@ def ba_final_block_attention(heads: Heads, q_f, k_ctx, v_ctx, k_f, v_f, o_out, k
     _check(load().ba_final_block_attention(ctypes.byref(heads.c), _ref(tq), _ref(tkc), _ref(tvc), _ref(tkf),
                                            _ref(tvf), _ref(to), _ref(tkr), len(cq) - 1, _ip(cq), _ip(cc),
                                            _ip(qp), rope_mode, wp, wb, _stream_handle(stream)))
+
+
+def ba_final_block_attention_cached_workspace_bytes(heads: Heads, cu_q, cu_blk, blk_len,
+                                                    have_k_f_rot_out: bool = False) -> int:
+    cq, cb, bl = _ints(cu_q), _ints(cu_blk), _ints(blk_len)
+    return int(load().ba_final_block_attention_cached_workspace_bytes(ctypes.byref(heads.c), len(cq) - 1, _ip(cq),
+                                                                      _ip(cb), _ip(bl), int(have_k_f_rot_out)))
+
+
+def ba_final_block_attention_cached(heads: Heads, q_f, k_cache, v_cache, k_f, v_f, o_out, k_f_rot_out, cu_q, cu_blk,
+                                    blk_tok_off, blk_len, blk_old_pos0=None, blk_new_pos0=None, q_pos0=None,
+                                    ws=None, stream=None) -> None:
+    cq, cb = _ints(cu_q), _ints(cu_blk)
+    bo, bl, op, npos, qp = _ints(blk_tok_off), _ints(blk_len), _ints(blk_old_pos0), _ints(blk_new_pos0), _ints(q_pos0)
+    wp, wb = _ws(ws)
+    tq, tkc, tvc = _tensor(q_f), _tensor(k_cache), _tensor(v_cache)
+    tkf, tvf, to, tkr = _tensor(k_f), _tensor(v_f), _tensor(o_out), _tensor(k_f_rot_out)
+    _check(load().ba_final_block_attention_cached(ctypes.byref(heads.c), _ref(tq), _ref(tkc), _ref(tvc), _ref(tkf),
+                                                  _ref(tvf), _ref(to), _ref(tkr), len(cq) - 1, _ip(cq), _ip(cb),
+                                                  _ip(bo), _ip(bl), _ip(op), _ip(npos), _ip(qp), wp, wb,
+                                                  _stream_handle(stream)))

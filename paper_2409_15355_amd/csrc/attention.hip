@@ -102,7 +102,8 @@ __device__ __forceinline__ Problem locate(const FinalMeta &m, int tile) {
   pr.jt = tile - m.tile_start[n];
   return pr;
 }
-__device__ __forceinline__ Problem locate(const FinalBlocksMeta &m, int tile) {
+template <int NP, int NB>
+__device__ __forceinline__ Problem locate(const FinalBlocksMetaT<NP, NB> &m, int tile) {
   int n = find_segment(m.tile_start, m.n, tile);
   Problem pr;
   pr.q_tok0 = m.cu_q[n];
@@ -186,7 +187,8 @@ __device__ long long g_wg[1024][4];  // per workgroup: wall clock at start and e
 template <int D, typename Meta>
 __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta) {
   using G = Geo<D>;
-  constexpr bool kBlocks = std::is_same<Meta, FinalBlocksMeta>::value;  // context = table of cached blocks
+  // context = table of cached blocks
+  constexpr bool kBlocks = std::is_same<Meta, FinalBlocksMeta>::value || std::is_same<Meta, FinalBlocksMetaSmall>::value;
   constexpr bool kFinal = std::is_same<Meta, FinalMeta>::value || kBlocks;
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
   lds_char *smem = (lds_char *)smem_generic;
@@ -283,19 +285,19 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   // Full tiles of segments with the "primary" row stride (the context's if there is one, else the
   // causal segment's) take a short path with cached lane offsets.
   const uint32_t prim_rb = n_ctx_segs > 0 ? c_rb : f_rb;
-  int g_row[G::IPW];
-  uint32_t g_chunk[G::IPW];  // byte offset of the source chunk inside its row
-  uint32_t g_src[G::IPW];    // full per-lane byte offsets inside a full tile of primary stride
-#pragma unroll
-  for (int i = 0; i < G::IPW; ++i) {
-    const int row = ((wave & (kWaves / 2 - 1)) * G::IPW + i) * G::RPI + lane / G::CPR;
-    const int pos = lane % G::CPR;
-    g_row[i] = row;
+  // this lane's source row (inside the tile) and chunk offset (inside the row) for its i-th piece
+  auto copy_row = [&](int i) __attribute__((always_inline)) {
+    return ((wave & (kWaves / 2 - 1)) * G::IPW + i) * G::RPI + lane / G::CPR;
+  };
+  auto copy_chunk = [&](int i) __attribute__((always_inline)) {
+    const int row = copy_row(i), pos = lane % G::CPR;
     const uint32_t kchunk = (uint32_t)(pos ^ ((row / G::LPR) & (G::CPR - 1))) << 4;
     const uint32_t vchunk = (uint32_t)((((pos >> 2) ^ ((row / G::LPR) & (G::GPR - 1))) << 2) | (pos & 3)) << 4;
-    g_chunk[i] = role_b ? vchunk : kchunk;
-    g_src[i] = (uint32_t)row * prim_rb + g_chunk[i];
-  }
+    return role_b ? vchunk : kchunk;
+  };
+  uint32_t g_src[G::IPW];  // full per-lane byte offsets inside a full tile of primary stride
+#pragma unroll
+  for (int i = 0; i < G::IPW; ++i) g_src[i] = (uint32_t)copy_row(i) * prim_rb + copy_chunk(i);
   const uint32_t lds_copy =
       (uint32_t)(uintptr_t)smem + (role_b ? VBASE : 0u) + (wave & (kWaves / 2 - 1)) * G::IPW * 1024;
 
@@ -305,37 +307,38 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     if constexpr (kBlocks) return (int)meta.blk_len[pr.blk0 + sg];
     return pr.tctx;
   };
-  auto seg_tiles = [&](int sg) __attribute__((always_inline)) {
-    return sg >= n_ctx_segs ? n_causal_tiles : (seg_len(sg) + kTileKeys - 1) / kTileKeys;
-  };
   auto seg_base = [&](int sg) __attribute__((always_inline)) {
     if (sg >= n_ctx_segs) return f_base;
     if constexpr (kBlocks) return c_base + (uint64_t)(uint32_t)meta.blk_off[pr.blk0 + sg] * (uint64_t)c_rb;
     return c_base;
   };
-  // position in the walk: segment, tile inside it, tiles left in it (this one included)
+  // Position in the walk: segment, tile inside it, tiles left in it (this one included), plus the
+  // segment's row count and first row (of this wave's kind), fetched once per segment so that the
+  // loop itself never reads the tables (a scalar load would also wait for the LDS reads in flight).
   struct Cursor {
-    int seg, ts, rem;
+    int seg, ts, rem, len;
+    const char *base;
+  };
+  auto enter = [&](Cursor &c, int sg, int ts) __attribute__((always_inline)) {
+    c.seg = sg;
+    c.ts = ts;
+    c.len = seg_len(sg);
+    c.base = seg_base(sg);
+    c.rem = (sg >= n_ctx_segs ? n_causal_tiles : (c.len + kTileKeys - 1) / kTileKeys) - ts;
   };
   auto cursor_at = [&](int t) __attribute__((always_inline)) {
     Cursor c;
     if (t >= n_ctx_tiles) {
-      c.seg = n_ctx_segs;
-      c.ts = t - n_ctx_tiles;
-      c.rem = n_causal_tiles - c.ts;
+      enter(c, n_ctx_segs, t - n_ctx_tiles);
     } else if constexpr (kBlocks) {
       int lo = pr.blk0, hi = pr.blk1;  // largest block whose first tile is <= t
       while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (meta.blk_tile0[mid] <= t) lo = mid; else hi = mid;
       }
-      c.seg = lo - pr.blk0;
-      c.ts = t - meta.blk_tile0[lo];
-      c.rem = seg_tiles(c.seg) - c.ts;
+      enter(c, lo - pr.blk0, t - meta.blk_tile0[lo]);
     } else {
-      c.seg = 0;
-      c.ts = t;
-      c.rem = n_ctx_tiles - t;
+      enter(c, 0, t);
     }
     return c;
   };
@@ -343,9 +346,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     ++c.ts;
     --c.rem;
     if (c.rem == 0 && c.seg < n_ctx_segs) {  // (the host drops empty blocks: a segment has a tile)
-      ++c.seg;
-      c.ts = 0;
-      c.rem = seg_tiles(c.seg);
+      asm volatile("" ::: "memory");
+      enter(c, c.seg + 1, 0);
     }
   };
   // Copy of the tile under a cursor into buffer `buf` of this wave's kind: a wave-uniform
@@ -362,8 +364,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     CopyJob j;
     j.dst = lds_copy + (uint32_t)buf * TB;
     j.rb = c.seg >= n_ctx_segs ? f_rb : c_rb;
-    j.ptr = seg_base(c.seg) + (uint64_t)(uint32_t)c.ts * (uint64_t)(j.rb * (uint32_t)kTileKeys);
-    j.valid = min(kTileKeys, seg_len(c.seg) - c.ts * kTileKeys);
+    j.ptr = c.base + (uint64_t)(uint32_t)c.ts * (uint64_t)(j.rb * (uint32_t)kTileKeys);
+    j.valid = min(kTileKeys, c.len - c.ts * kTileKeys);
     j.full = j.valid == kTileKeys && j.rb == prim_rb;
     return j;
   };
@@ -372,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       lds_dma16(c.ptr, g_src[i], c.dst + i * 1024);
     } else {
       asm volatile("" ::: "memory");
-      lds_dma16(c.ptr, (uint32_t)min(g_row[i], c.valid - 1) * c.rb + g_chunk[i], c.dst + i * 1024);
+      lds_dma16(c.ptr, (uint32_t)min(copy_row(i), c.valid - 1) * c.rb + copy_chunk(i), c.dst + i * 1024);
     }
   };
 
@@ -542,7 +544,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
 #endif
     const bool isctx = cm.seg < n_ctx_segs;
     const int key0 = cm.ts * kTileKeys;
-    const int valid = min(kTileKeys, seg_len(cm.seg) - key0);
+    const int valid = min(kTileKeys, cm.len - key0);
     const bool need_mask = isctx ? (valid < kTileKeys) : (key0 + kTileKeys - 1 > first_tok_wave) || (valid < kTileKeys);
     if (need_mask) {
       asm volatile("" ::: "memory");  // keep this a real branch: never speculate the selects
@@ -611,9 +613,14 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   //      turned back by the block's shift instead (rot >= 0: row of the table of rotations), which
   //      gives the same scores as re-encoding the keys (Eq. 2 and 3 applied to q instead of k) ------
   auto load_q = [&](int rot) __attribute__((always_inline)) {
-    const int g = my_row - my_tok * Gq;
+    // (addresses are rebuilt from the row number each time: with a block table this runs inside the
+    // loop, and hoisted address registers would not fit next to the accumulators)
+    int row_v = my_row;
+    asm volatile("" : "+v"(row_v));
+    const int tok_v = (int)fast_div((uint32_t)row_v, p.group_div);
+    const int g = row_v - tok_v * Gq;
     const int head = kvh * Gq + g;
-    const uint16_t *qp = p.q + (int64_t)(pr.q_tok0 + my_tok) * p.q_st + (int64_t)head * p.q_sh + hf * 8;
+    const uint16_t *qp = p.q + (int64_t)(pr.q_tok0 + tok_v) * p.q_st + (int64_t)head * p.q_sh + hf * 8;
     u32x4_t raw[G::KCH];
 #pragma unroll
     for (int kk = 0; kk < G::KCH; ++kk) {
@@ -660,8 +667,14 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
         }
       }
     }
+    // (the empty asm makes the compiler wait for these loads HERE: left pending, it would wait for
+    // them at the first use of the fragments inside the loop's MFMA block, on every iteration, and
+    // that wait also covers the tile copies just started there)
 #pragma unroll
-    for (int kk = 0; kk < G::KCH; ++kk) qf[kk] = __builtin_bit_cast(bf16x8_t, raw[kk]);
+    for (int kk = 0; kk < G::KCH; ++kk) {
+      asm volatile("" : "+v"(raw[kk]));
+      qf[kk] = __builtin_bit_cast(bf16x8_t, raw[kk]);
+    }
   };
   Cursor cm = cursor_at(t_begin);  // the tile whose softmax comes next
   auto rot_of = [&](int sg) __attribute__((always_inline)) {
@@ -714,7 +727,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       for (int u = 0; u < G::IPW; ++u) cp_off[u] = g_src[u];
       if (copy) {
         const uint32_t rb = cp.seg >= n_ctx_segs ? f_rb : c_rb;
-        if (steady || (cp.ts > 0 && rb == prim_rb && (cp.ts + 1) * kTileKeys <= seg_len(cp.seg))) {
+        if (steady || (cp.ts > 0 && rb == prim_rb && (cp.ts + 1) * kTileKeys <= cp.len)) {
           cp_ptr += tile_bytes;
         } else {
           asm volatile("" ::: "memory");
@@ -722,7 +735,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
           if (!cj.full) {
 #pragma unroll
             for (int u = 0; u < G::IPW; ++u)
-              cp_off[u] = (uint32_t)min(g_row[u], cj.valid - 1) * cj.rb + g_chunk[u];
+              cp_off[u] = (uint32_t)min(copy_row(u), cj.valid - 1) * cj.rb + copy_chunk(u);
           }
           cp_ptr = cj.ptr + (uint64_t)(cj.rb * (uint32_t)kTileKeys);
         }
@@ -739,7 +752,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     // the copy cursor or the compute cursor reaches the end of the segment they start in.
     int n_steady = 0;
     if (!kBlocks) {
-      const int full_tiles = seg_len(cp.seg) / kTileKeys;  // of the segment the copy cursor is in
+      const int full_tiles = cp.len / kTileKeys;  // of the segment the copy cursor is in
       const bool fast = (cp.seg >= n_ctx_segs ? f_rb : c_rb) == prim_rb && cp.ts > 0;
       n_steady = fast ? max(0, min(min(n_t - 3, full_tiles - cp.ts), cm.rem - 1)) : 0;
     }
@@ -916,6 +929,11 @@ hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, hipStre
 hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMeta &meta, hipStream_t stream) {
   if (p.head_dim == 128) return launch_attn_t<128, FinalBlocksMeta>(p, meta, stream);
   if (p.head_dim == 64) return launch_attn_t<64, FinalBlocksMeta>(p, meta, stream);
+  return hipErrorInvalidValue;
+}
+hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMetaSmall &meta, hipStream_t stream) {
+  if (p.head_dim == 128) return launch_attn_t<128, FinalBlocksMetaSmall>(p, meta, stream);
+  if (p.head_dim == 64) return launch_attn_t<64, FinalBlocksMetaSmall>(p, meta, stream);
   return hipErrorInvalidValue;
 }
 

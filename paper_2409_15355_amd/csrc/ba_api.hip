@@ -8,6 +8,7 @@
 
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/ba.h"
@@ -232,7 +233,8 @@ int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, c
 // [seg0, seg0 + n) given by start offsets and first positions.
 int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_tensor *q, uint16_t *q_rot,
                          const ba_tensor *k, const ba_tensor *k_rot, int n, const int32_t *start,
-                         const int32_t *pos0, hipStream_t stream) {
+                         const int32_t *pos0, hipStream_t stream, const ba::RopeRots *rots = nullptr,
+                         const ba::RopeRotsSmall *rots_small = nullptr, float *rot_dst = nullptr, int n_rot = 0) {
   ba::RopeSegs segs;
   memset(&segs, 0, sizeof(segs));
   segs.n = n;
@@ -267,10 +269,12 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
   p.heads_per_thread = tokens >= 16384 ? 8 : (tokens >= 2048 ? 2 : 1);
   p.do_q = 1;
   p.do_k = 1;
+  p.rot_dst = rot_dst;
+  p.n_rot = n_rot;
   hipError_t e;
   {
     ProfileScope ps(BA_PROFILE_REENCODE, stream);
-    e = ba::launch_rope_prepass(p, segs, nullptr, rt, stream);
+    e = ba::launch_rope_prepass(p, segs, rots, rots_small, rt, stream);
   }
   if (e != hipSuccess) return device_fail(e, "RoPE pre-pass launch");
   return BA_OK;
@@ -683,6 +687,275 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
     }
     if (e != hipSuccess) return device_fail(e, "final-block attention launch");
   }
+  if (pl.n_splits > 1) {
+    hipError_t e;
+    {
+      ProfileScope ps(BA_PROFILE_COMBINE, stream);
+      e = ba::launch_combine(ap, pl.lq_total, stream);
+    }
+    if (e != hipSuccess) return device_fail(e, "split combine launch");
+  }
+  return BA_OK;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+namespace {
+
+struct BlocksPlan {
+  int64_t lq_total = 0;
+  int64_t total_tiles = 0;
+  int64_t n_blocks = 0;  // non-empty blocks over all prompts
+  int max_nt = 0;
+  int n_splits = 1;
+  size_t kf_bytes = 0, q_bytes = 0, rot_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0;
+  size_t total() const {
+    return align256(kf_bytes) + align256(q_bytes) + align256(rot_bytes) + align256(part_o_bytes) +
+           align256(part_ml_bytes);
+  }
+};
+
+int32_t plan_final_blocks(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_blk,
+                          const int32_t *blk_len, bool have_rot_out, BlocksPlan *plan) {
+  if (n_prompts < 0 || (n_prompts > 0 && (!cu_q || !cu_blk)))
+    return fail(BA_ERR_INVALID_ARG, "cu_q / cu_blk: null or negative prompt count");
+  BlocksPlan pl;
+  if (n_prompts > 0 && (cu_q[0] != 0 || cu_blk[0] != 0)) return fail(BA_ERR_INVALID_ARG, "cu_q[0] and cu_blk[0] must be 0");
+  const int G = h->n_q_heads / h->n_kv_heads;
+  for (int n = 0; n < n_prompts; ++n) {
+    const int64_t lq = (int64_t)cu_q[n + 1] - cu_q[n];
+    if (lq < 1) return fail(BA_ERR_INVALID_ARG, "prompt %d: the final block needs at least one token", n);
+    if (cu_blk[n + 1] < cu_blk[n]) return fail(BA_ERR_INVALID_ARG, "prompt %d: cu_blk decreases", n);
+    if (cu_blk[n + 1] > cu_blk[n] && !blk_len) return fail(BA_ERR_INVALID_ARG, "blk_len is null");
+    if (lq * G > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "prompt %d: too many packed rows", n);
+    int64_t tiles = (lq + ba::kTileKeys - 1) / ba::kTileKeys, ctx = 0, nb = 0;
+    for (int b = cu_blk[n]; b < cu_blk[n + 1]; ++b) {
+      if (blk_len[b] < 0) return fail(BA_ERR_INVALID_ARG, "block %d: negative length", b);
+      if (blk_len[b] == 0) continue;
+      tiles += (blk_len[b] + ba::kTileKeys - 1) / ba::kTileKeys;
+      ctx += blk_len[b];
+      ++nb;
+    }
+    if (ctx > 0x3fffffff || tiles > 0x1ffffff) return fail(BA_ERR_INVALID_ARG, "prompt %d: context too long", n);
+    if (nb > ba::kBlkMaxBlocks)
+      return fail(BA_ERR_UNSUPPORTED, "prompt %d: %lld cached blocks, at most %d per prompt", n, (long long)nb,
+                  ba::kBlkMaxBlocks);
+    pl.n_blocks += nb;
+    pl.total_tiles += (lq * G + ba::kTileRows - 1) / ba::kTileRows;
+    pl.max_nt = std::max(pl.max_nt, (int)tiles);
+  }
+  pl.lq_total = n_prompts > 0 ? cu_q[n_prompts] : 0;
+  pl.n_splits = choose_splits(pl.total_tiles * h->n_kv_heads, pl.max_nt);
+  if (!have_rot_out) pl.kf_bytes = (size_t)pl.lq_total * h->n_kv_heads * h->head_dim * 2;
+  pl.q_bytes = (size_t)pl.lq_total * h->n_q_heads * h->head_dim * 2;
+  pl.rot_bytes = (size_t)pl.n_blocks * h->head_dim * 4;  // D/2 (cos, sin) pairs per block
+  if (pl.n_splits > 1) {
+    const size_t rows = (size_t)pl.lq_total * h->n_q_heads;
+    pl.part_o_bytes = (size_t)pl.n_splits * rows * h->head_dim * 2;
+    pl.part_ml_bytes = (size_t)pl.n_splits * rows * 2 * 4;
+  }
+  *plan = pl;
+  return BA_OK;
+}
+
+struct BlocksCall {
+  const ba_heads *heads;
+  const ba::RopeTable *rt;
+  const ba_tensor *q_f;
+  uint16_t *q_ws;
+  const ba_tensor *k_f;
+  const ba_tensor *kf_use;
+  float *rot_ws;
+  int32_t n_prompts;
+  const int32_t *cu_q, *cu_blk, *blk_tok_off, *blk_len, *blk_old_pos0, *blk_new_pos0, *q_pos0;
+  hipStream_t stream;
+};
+
+// Launches of at most MetaT::kPrompts prompts and MetaT::kBlocks non-empty blocks each: the RoPE
+// pre-pass (fresh q and k of the chunk, rotations of its blocks), then the attention core.
+template <typename MetaT, typename RotsT>
+int32_t run_final_blocks(const BlocksCall &c, ba::AttnParams ap) {
+  const int D = c.heads->head_dim, G = c.heads->n_q_heads / c.heads->n_kv_heads;
+  std::vector<MetaT> metas(1);
+  std::vector<RotsT> rots(1);
+  int n0 = 0;
+  int64_t rot_base = 0;
+  while (n0 < c.n_prompts) {
+    MetaT &meta = metas[0];
+    RotsT &rr = rots[0];
+    memset(&meta, 0, sizeof(meta));
+    memset(&rr, 0, sizeof(rr));
+    int np = 0, nb = 0;
+    int64_t tiles = 0;
+    std::vector<int32_t> pos0;
+    while (n0 + np < c.n_prompts && np < MetaT::kPrompts) {
+      const int n = n0 + np;
+      int cnt = 0;
+      for (int b = c.cu_blk[n]; b < c.cu_blk[n + 1]; ++b) cnt += c.blk_len[b] > 0;
+      if (nb + cnt > MetaT::kBlocks) break;  // (a single prompt always fits: checked by the plan)
+      meta.cu_q[np] = c.cu_q[n];
+      meta.cu_blk[np] = nb;
+      meta.tile_start[np] = (int32_t)tiles;
+      int32_t ctx_tiles = 0;
+      int64_t run = 0;  // the prompt's context so far = default position of the next block
+      for (int b = c.cu_blk[n]; b < c.cu_blk[n + 1]; ++b) {
+        const int32_t new0 = c.blk_new_pos0 ? c.blk_new_pos0[b] : (int32_t)run;
+        run += c.blk_len[b];
+        if (c.blk_len[b] == 0) continue;
+        if (c.blk_tok_off[b] < 0) return fail(BA_ERR_INVALID_ARG, "block %d: negative cache offset", b);
+        meta.blk_off[nb] = c.blk_tok_off[b];
+        meta.blk_len[nb] = c.blk_len[b];
+        meta.blk_tile0[nb] = ctx_tiles;
+        ctx_tiles += (c.blk_len[b] + ba::kTileKeys - 1) / ba::kTileKeys;
+        // the queries are turned back by the block's shift: angle = -(new - old) positions
+        rr.angle[nb] = -(new0 - (c.blk_old_pos0 ? c.blk_old_pos0[b] : 0));
+        ++nb;
+      }
+      meta.ctx_tiles[np] = ctx_tiles;
+      pos0.push_back(c.q_pos0 ? c.q_pos0[n] : (int32_t)run);
+      tiles += ((int64_t)(c.cu_q[n + 1] - c.cu_q[n]) * G + ba::kTileRows - 1) / ba::kTileRows;
+      ++np;
+    }
+    meta.n = np;
+    meta.cu_q[np] = c.cu_q[n0 + np];
+    meta.cu_blk[np] = nb;
+    meta.tile_start[np] = (int32_t)tiles;
+    meta.rot_base = (int32_t)rot_base;
+    ap.total_tiles = (int32_t)tiles;
+    const ba::RopeRots *big = nullptr;
+    const ba::RopeRotsSmall *small = nullptr;
+    if constexpr (std::is_same<RotsT, ba::RopeRots>::value) big = &rr; else small = &rr;
+    int32_t rc = run_rope_prepass(c.heads, *c.rt, c.q_f, c.q_ws, c.k_f, c.kf_use, np, meta.cu_q, pos0.data(), c.stream,
+                                  big, small, c.rot_ws + rot_base * D, nb);
+    if (rc) return rc;
+    hipError_t e;
+    {
+      ProfileScope ps(BA_PROFILE_ATTENTION, c.stream);
+      e = ba::launch_attn_final_blocks(ap, meta, c.stream);
+    }
+    if (e != hipSuccess) return device_fail(e, "final-block (cached) attention launch");
+    rot_base += nb;
+    n0 += np;
+  }
+  return BA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ba_final_block_attention_cached_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
+                                                       const int32_t *cu_q, const int32_t *cu_blk,
+                                                       const int32_t *blk_len, int32_t have_k_f_rot_out) {
+  if (check_heads(heads, true) != BA_OK) return 0;
+  BlocksPlan pl;
+  if (plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, have_k_f_rot_out != 0, &pl) != BA_OK) return 0;
+  return pl.total();
+}
+
+int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *q_f, const ba_tensor *k_cache,
+                                        const ba_tensor *v_cache, const ba_tensor *k_f, const ba_tensor *v_f,
+                                        const ba_tensor *o_out, const ba_tensor *k_f_rot_out, int32_t n_prompts,
+                                        const int32_t *cu_q, const int32_t *cu_blk, const int32_t *blk_tok_off,
+                                        const int32_t *blk_len, const int32_t *blk_old_pos0,
+                                        const int32_t *blk_new_pos0, const int32_t *q_pos0, void *ws,
+                                        size_t ws_bytes, void *stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t rc;
+  if ((rc = check_heads(heads, true))) return rc;
+  const int D = heads->head_dim;
+  BlocksPlan pl;
+  if ((rc = plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, k_f_rot_out != nullptr, &pl))) return rc;
+  if (n_prompts == 0) return BA_OK;
+  if ((rc = check_tensor(q_f, "q_f", false, D, heads->n_q_heads))) return rc;
+  if ((rc = check_tensor(k_f, "k_f", false, D, heads->n_kv_heads))) return rc;
+  if ((rc = check_tensor(v_f, "v_f", false, D, heads->n_kv_heads))) return rc;
+  if ((rc = check_tensor(o_out, "o_out", false, D, heads->n_q_heads))) return rc;
+  if (pl.n_blocks > 0) {
+    if (!blk_tok_off) return fail(BA_ERR_INVALID_ARG, "blk_tok_off is null");
+    if ((rc = check_tensor(k_cache, "k_cache", false, D, heads->n_kv_heads))) return rc;
+    if ((rc = check_tensor(v_cache, "v_cache", false, D, heads->n_kv_heads))) return rc;
+  }
+  if (k_f_rot_out && (rc = check_tensor(k_f_rot_out, "k_f_rot_out", false, D, heads->n_kv_heads))) return rc;
+  if (!ws || ws_bytes < pl.total() || ((uintptr_t)ws & 255))
+    return fail(BA_ERR_WORKSPACE, "final block (cached): 256-byte aligned workspace of %zu bytes needed, %zu given",
+                pl.total(), ws_bytes);
+
+  char *wsp = (char *)ws;
+  void *kf_ws = wsp;
+  wsp += align256(pl.kf_bytes);
+  uint16_t *q_ws = (uint16_t *)wsp;
+  wsp += align256(pl.q_bytes);
+  float *rot_ws = (float *)wsp;
+  wsp += align256(pl.rot_bytes);
+  uint16_t *part_o = (uint16_t *)wsp;
+  wsp += align256(pl.part_o_bytes);
+  float *part_ml = (float *)wsp;
+
+  ba::RopeTable rt;
+  build_rope_table(heads, &rt);
+
+  ba_tensor kf_use = *k_f;
+  if (k_f_rot_out) {
+    kf_use = *k_f_rot_out;
+  } else {
+    kf_use.ptr = kf_ws;
+    kf_use.stride_head = D;
+    kf_use.stride_tok = (int64_t)heads->n_kv_heads * D;
+  }
+
+  const int G = heads->n_q_heads / heads->n_kv_heads;
+  ba::AttnParams ap;
+  memset(&ap, 0, sizeof(ap));
+  ap.q = q_ws;
+  ap.q_st = (int64_t)heads->n_q_heads * D;
+  ap.q_sh = D;
+  ap.kf = (const uint16_t *)kf_use.ptr;
+  ap.kf_st = kf_use.stride_tok;
+  ap.kf_sh = kf_use.stride_head;
+  ap.vf = (const uint16_t *)v_f->ptr;
+  ap.vf_st = v_f->stride_tok;
+  ap.vf_sh = v_f->stride_head;
+  if (pl.n_blocks > 0) {
+    ap.kc = (const uint16_t *)k_cache->ptr;
+    ap.kc_st = k_cache->stride_tok;
+    ap.kc_sh = k_cache->stride_head;
+    ap.vc = (const uint16_t *)v_cache->ptr;
+    ap.vc_st = v_cache->stride_tok;
+    ap.vc_sh = v_cache->stride_head;
+  } else {
+    ap.kc = ap.kf;
+    ap.kc_st = ap.kf_st;
+    ap.kc_sh = ap.kf_sh;
+    ap.vc = ap.vf;
+    ap.vc_st = ap.vf_st;
+    ap.vc_sh = ap.vf_sh;
+  }
+  ap.o = (uint16_t *)o_out->ptr;
+  ap.o_st = o_out->stride_tok;
+  ap.o_sh = o_out->stride_head;
+  ap.part_o = part_o;
+  ap.part_ml = part_ml;
+  ap.part_rows = pl.lq_total * heads->n_q_heads;
+  ap.n_q_heads = heads->n_q_heads;
+  ap.n_kv_heads = heads->n_kv_heads;
+  ap.group = G;
+  ap.group_div = ba::make_fast_div((uint32_t)G);
+  ap.head_dim = D;
+  ap.scale_log2e = scale_log2e(heads);
+  ap.q_ready = 1;
+  ap.rope_layout = heads->rope_layout;
+  ap.blk_rot = rot_ws;
+  ap.n_splits = pl.n_splits;
+
+  BlocksCall call{heads, &rt, q_f, q_ws, k_f, &kf_use, rot_ws, n_prompts, cu_q, cu_blk, blk_tok_off, blk_len,
+                  blk_old_pos0, blk_new_pos0, q_pos0, stream};
+  if (n_prompts <= ba::kBlkSmallPrompts && pl.n_blocks <= ba::kBlkSmallBlocks)
+    rc = run_final_blocks<ba::FinalBlocksMetaSmall, ba::RopeRotsSmall>(call, ap);
+  else
+    rc = run_final_blocks<ba::FinalBlocksMeta, ba::RopeRots>(call, ap);
+  if (rc) return rc;
   if (pl.n_splits > 1) {
     hipError_t e;
     {

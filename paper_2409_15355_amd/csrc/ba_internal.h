@@ -43,8 +43,11 @@ struct ReencParams {
 hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
                            hipStream_t stream);
 
-constexpr int kBlkMaxPrompts = 64;   // final block over a block table: prompts per launch
-constexpr int kBlkMaxBlocks = 1024;  // ... and cached blocks per launch
+// Final block over a block table: prompts and cached blocks per launch.  Two capacities, because
+// the tables travel by value in the kernel arguments and many large argument blocks in flight
+// throttle the launch queue: the small one covers retrieval-sized prompts.
+constexpr int kBlkMaxPrompts = 64, kBlkMaxBlocks = 1024;
+constexpr int kBlkSmallPrompts = 16, kBlkSmallBlocks = 64;
 
 // ---------------------------------------------------------------- RoPE pre-pass ------
 // Fresh (un-rotated) Q and K rows of a run of consecutive segments: segment s covers tokens
@@ -73,12 +76,16 @@ struct RopePrepassParams {
 };
 
 // positions (in tokens) by which the rows of the rotation table turn
-struct RopeRots {
-  int32_t angle[kBlkMaxBlocks];
+template <int NB>
+struct RopeRotsT {
+  int32_t angle[NB];
 };
+using RopeRots = RopeRotsT<kBlkMaxBlocks>;
+using RopeRotsSmall = RopeRotsT<kBlkSmallBlocks>;
 
+// rots / rots_small: at most one non-null, and only with p.rot_dst
 hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeRots *rots,
-                               const RopeTable &rt, hipStream_t stream);
+                               const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention ----------
 // Division of a 32-bit unsigned number by a divisor fixed on the host (round-up multiplier of
@@ -141,20 +148,25 @@ struct FinalMeta {
 };
 
 // Final block over a table of cached blocks (each at the positions it was encoded at).
-struct FinalBlocksMeta {
+template <int NP, int NB>
+struct FinalBlocksMetaT {
+  static constexpr int kPrompts = NP, kBlocks = NB;
   int32_t n;
-  int32_t rot_base;  // row of AttnParams::blk_rot that belongs to block 0 of this launch
-  int32_t cu_q[kBlkMaxPrompts + 1];
-  int32_t cu_blk[kBlkMaxPrompts + 1];     // blocks of prompt n: [cu_blk[n], cu_blk[n+1])
-  int32_t ctx_tiles[kBlkMaxPrompts];      // key tiles of prompt n's context
-  int32_t tile_start[kBlkMaxPrompts + 1]; // first row tile of each prompt
-  int32_t blk_off[kBlkMaxBlocks];         // first cache row of the block
-  int32_t blk_len[kBlkMaxBlocks];         // rows (>= 1)
-  int32_t blk_tile0[kBlkMaxBlocks];       // first key tile of the block inside its prompt
+  int32_t rot_base;            // row of AttnParams::blk_rot that belongs to block 0 of this launch
+  int32_t cu_q[NP + 1];
+  int32_t cu_blk[NP + 1];      // blocks of prompt n: [cu_blk[n], cu_blk[n+1])
+  int32_t ctx_tiles[NP];       // key tiles of prompt n's context
+  int32_t tile_start[NP + 1];  // first row tile of each prompt
+  int32_t blk_off[NB];         // first cache row of the block
+  int32_t blk_len[NB];         // rows (>= 1)
+  int32_t blk_tile0[NB];       // first key tile of the block inside its prompt
 };
+using FinalBlocksMeta = FinalBlocksMetaT<kBlkMaxPrompts, kBlkMaxBlocks>;
+using FinalBlocksMetaSmall = FinalBlocksMetaT<kBlkSmallPrompts, kBlkSmallBlocks>;
 
 hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
 hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMeta &meta, hipStream_t stream);
+hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMetaSmall &meta, hipStream_t stream);
 hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, hipStream_t stream);
 // Merge split-KV partials into the bf16 output.  rows = tokens * n_q_heads.
 hipError_t launch_combine(const AttnParams &p, int64_t n_tokens, hipStream_t stream);

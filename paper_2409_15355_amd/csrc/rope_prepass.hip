@@ -19,8 +19,9 @@ constexpr int kThreads = 256;
 
 // Table of rotations for the block-table form of the final block: row b, frequency j holds
 // (cos, sin) of angle[b] * theta_j.  One thread per entry.
-__global__ __launch_bounds__(kThreads) void rope_rot_table_kernel(float *dst, int n_rot, int half_dim, RopeRots rots,
-                                                                  RopeTable rt) {
+template <int NB>
+__global__ __launch_bounds__(kThreads) void rope_rot_table_kernel(float *dst, int n_rot, int half_dim,
+                                                                  RopeRotsT<NB> rots, RopeTable rt) {
   const int idx = blockIdx.x * kThreads + threadIdx.x;
   if (idx >= n_rot * half_dim) return;
   const int b = idx / half_dim, j = idx - b * half_dim;
@@ -116,11 +117,16 @@ hipError_t launch_d(const RopePrepassParams &p, const RopeSegs &segs, const Rope
 }  // namespace
 
 hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeRots *rots,
-                               const RopeTable &rt, hipStream_t stream) {
-  if (p.rot_dst && p.n_rot > 0 && rots) {
+                               const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream) {
+  if (p.rot_dst && p.n_rot > 0 && (rots || rots_small)) {
     const int entries = p.n_rot * (p.head_dim / 2);
-    hipLaunchKernelGGL(rope_rot_table_kernel, dim3((entries + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
-                       p.rot_dst, p.n_rot, p.head_dim / 2, *rots, rt);
+    const dim3 grid((entries + kThreads - 1) / kThreads);
+    if (rots_small)
+      hipLaunchKernelGGL((rope_rot_table_kernel<kBlkSmallBlocks>), grid, dim3(kThreads), 0, stream, p.rot_dst, p.n_rot,
+                         p.head_dim / 2, *rots_small, rt);
+    else
+      hipLaunchKernelGGL((rope_rot_table_kernel<kBlkMaxBlocks>), grid, dim3(kThreads), 0, stream, p.rot_dst, p.n_rot,
+                         p.head_dim / 2, *rots, rt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -123,3 +123,29 @@ def test_workspace_queries(lib):
     assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 400], ba.ROPE_NONE, False) == 0
     # a single small prompt needs no split partials
     assert ba.ba_final_block_attention_workspace_bytes(ba.Heads(4, 4, 64), [0, 64], [0, 128], ba.ROPE_NONE) == 0
+
+
+def test_final_cached_rejects_bad_arguments_and_sizes_workspace(lib):
+    h = ba.Heads(32, 8, 128, 500000.0)
+    t = fake()
+    i32 = lambda x: np.asarray(x, dtype=np.int32)
+    p = lambda x: x.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+    def call(cu_q, cu_blk, off, ln, ws=None, wsb=0):
+        cq, cb, bo, bl = i32(cu_q), i32(cu_blk), i32(off), i32(ln)
+        return lib.ba_final_block_attention_cached(ctypes.byref(h.c), ctypes.byref(t), ctypes.byref(t), ctypes.byref(t),
+                                                   ctypes.byref(t), ctypes.byref(t), ctypes.byref(t), None, len(cq) - 1,
+                                                   p(cq), p(cb), p(bo), p(bl), None, None, None, ws, wsb, None)
+
+    assert call([0, 0], [0, 1], [0], [10]) == -1          # empty final block
+    assert call([0, 5], [1, 2], [0, 0], [10, 10]) == -1   # cu_blk[0] != 0
+    assert call([0, 5], [0, 1], [0], [-3]) == -1          # negative block length
+    assert call([0, 5], [0, 1100], [0] * 1100, [1] * 1100) == -2  # more blocks in one prompt than a launch takes
+    assert call([0, 256], [0, 31], [1024 * b for b in range(31)], [1024] * 31) == -4  # workspace missing
+    need = ba.ba_final_block_attention_cached_workspace_bytes(h, [0, 256], [0, 31], [1024] * 31)
+    # config 5 as 31 cached blocks: split partials + rotated final-block keys and queries + 31 rows of rotations
+    assert need == 8 * 8192 * 128 * 2 + 8 * 8192 * 2 * 4 + 256 * 8 * 128 * 2 + 256 * 32 * 128 * 2 + 31 * 128 * 4
+    # zero prompts: legal no-op
+    z = i32([0])
+    assert lib.ba_final_block_attention_cached(ctypes.byref(h.c), None, None, None, None, None, None, None, 0, p(z),
+                                               p(z), None, None, None, None, None, None, 0, None) == 0

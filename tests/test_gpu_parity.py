@@ -452,6 +452,40 @@ def test_config_5_final_block_full_size_sampled(ba):
     assert_attention_close(host_f64(o)[rows], ref, "cfg5 final (sampled rows)")
 
 
+def test_config_5_final_block_from_block_cache_full_size_sampled(ba):
+    """Config 5 through the block-cache entry point: the 31 cached passages stay at local positions
+    (stored in shuffled order in the cache), the kernel turns the queries instead; sampled rows against
+    the oracle's re-encode + final block."""
+    torch = torch_mod()
+    w = wl.config5(n_layers=1)
+    hq, hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
+    Tc, Lq = w.prompts[0].t_ctx, w.prompts[0].final_len
+    L = 1024
+    nb = Tc // L
+    kcache_b = wl.normal_bf16_bits(wl.tensor_seed(5, 40), (Tc, hkv, d))
+    vcache_b = wl.normal_bf16_bits(wl.tensor_seed(5, 41), (Tc, hkv, d))
+    qb, kfb, vfb = gen_qkv(wl.tensor_seed(5, 42), Lq, hq, hkv, d)
+    order = np.random.default_rng(55).permutation(nb)  # prompt slot s holds cache block order[s]
+    b_off = (order * L).astype(np.int32)
+    b_len = np.full(nb, L, dtype=np.int32)
+    heads = heads_of(ba, w)
+    cu_q, cu_blk = np.array([0, Lq], dtype=np.int32), np.array([0, nb], dtype=np.int32)
+    o = torch.full((Lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, b_len), dtype=torch.uint8,
+                     device="cuda")
+    ba.ba_final_block_attention_cached(heads, dev_bf16(qb), dev_bf16(kcache_b), dev_bf16(vcache_b), dev_bf16(kfb),
+                                       dev_bf16(vfb), o, None, cu_q, cu_blk, b_off, b_len, None, None, None, ws)
+    torch.cuda.synchronize()
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(w.rope_base, d)
+    dst = (np.arange(nb) * L).astype(np.int32)
+    k_ctx = oracle.reencode(f(kcache_b), b_off, dst, b_len, th, new_pos0=dst)
+    v_ctx = f(vcache_b).reshape(nb, L, hkv, d)[order].reshape(Tc, hkv, d)
+    rows = sorted(set([0, 1, 63, 64, 128, 255] + np.random.default_rng(6).integers(0, Lq, 8).tolist()))
+    ref = oracle.final_block(f(qb), k_ctx, v_ctx, f(kfb), f(vfb), cu_q, [0, Tc], th, rows=rows)
+    assert_attention_close(host_f64(o)[rows], ref, "cfg5 final from block cache (sampled rows)")
+
+
 def test_config_5_single_block_full_attention_sampled(ba):
     """The same 32,000 tokens as ONE block through ba_encode_blocks (full-attention mode);
     sampled rows (first rows, tile edges, last row, random) against the oracle."""
@@ -466,6 +500,102 @@ def test_config_5_single_block_full_attention_sampled(ba):
     f = oracle.bf16_bits_to_f64
     ref, _ = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, oracle.theta(w.rope_base, d), rows=rows, want_k_local=False)
     assert_attention_close(host_f64(o)[rows], ref, "cfg5 single block (sampled rows)")
+
+
+# --------------------------------------------------------------------------------------------
+# final block straight from the block cache (re-encoding folded into the attention kernel)
+def _cached_case(name):
+    """Returns hq, hkv, d, base, cache block table (offset, len, old_pos0) and prompts
+    [(block ids, final len, explicit new positions or None, explicit q_pos0 or None)]."""
+    if name == "rag-shared-blocks":
+        blocks = [(700, 100, 0), (0, 257, 0), (300, 64, 0), (1100, 1, 0), (400, 300, 0), (900, 129, 0), (1150, 0, 0)]
+        prompts = [([3, 0, 6, 4], 33, None, None), ([4, 1, 2, 5, 0], 70, None, None), ([], 9, None, None)]
+        return 8, 2, 128, 500000.0, 1200, blocks, prompts
+    if name == "deep-split-d64":
+        blocks = [(b * 210, 200 + (b % 3), 0) for b in range(20)]
+        prompts = [(list(range(19, -1, -1)), 17, None, None)]
+        return 2, 2, 64, 10000.0, 4300, blocks, prompts
+    if name == "moved-cache-positions":
+        # keys cached at other positions than 0, explicit (gapped) new positions and query position
+        blocks = [(0, 150, 1000), (150, 90, 37), (240, 64, 0)]
+        prompts = [([1, 2, 0], 40, [5, 200, 300], 777), ([0], 3, [10], None)]
+        return 8, 8, 128, 10000.0, 310, blocks, prompts
+    raise KeyError(name)
+
+
+@pytest.mark.parametrize("name", ["rag-shared-blocks", "deep-split-d64", "moved-cache-positions"])
+@pytest.mark.parametrize("layout", [0, 1])
+def test_final_block_from_block_cache_matches_oracle(ba, name, layout):
+    torch = torch_mod()
+    hq, hkv, d, base, t_cache, blocks, prompts = _cached_case(name)
+    th = oracle.theta(base, d)
+    f = oracle.bf16_bits_to_f64
+    seed = 1200 + len(name) + layout
+    kcache_b = wl.normal_bf16_bits(seed, (t_cache, hkv, d))
+    vcache_b = wl.normal_bf16_bits(seed + 1, (t_cache, hkv, d))
+    lq_total = sum(p[1] for p in prompts)
+    qb, kfb, vfb = gen_qkv(seed + 2, lq_total, hq, hkv, d)
+    # block table in prompt order + the oracle's route: re-encode each use of a block (fp64), concatenate
+    cu_q, cu_blk, b_off, b_len, b_old, b_new, q_pos0 = [0], [0], [], [], [], [], []
+    k_ctx, v_ctx, cu_ctx = [], [], [0]
+    explicit_new = any(p[2] is not None for p in prompts)
+    for ids, lq, new_pos, qp in prompts:
+        run = 0
+        for j, b in enumerate(ids):
+            off, ln, old = blocks[b]
+            new0 = new_pos[j] if new_pos is not None else run
+            b_off.append(off); b_len.append(ln); b_old.append(old); b_new.append(new0)
+            if ln:
+                k_ctx.append(oracle.reencode(f(kcache_b), [off], [0], [ln], th, old_pos0=[old], new_pos0=[new0],
+                                             layout=layout, out=np.zeros((ln, hkv, d)))[:ln])
+                v_ctx.append(f(vcache_b)[off:off + ln])
+            run += ln
+        cu_q.append(cu_q[-1] + lq); cu_blk.append(len(b_off)); cu_ctx.append(cu_ctx[-1] + run)
+        q_pos0.append(qp if qp is not None else run)
+    k_ctx = np.concatenate(k_ctx) if k_ctx else np.zeros((1, hkv, d))
+    v_ctx = np.concatenate(v_ctx) if v_ctx else np.zeros((1, hkv, d))
+    ref = oracle.final_block(f(qb), k_ctx, v_ctx, f(kfb), f(vfb), cu_q, cu_ctx, th, layout=layout, q_pos0=q_pos0)
+    heads = ba.Heads(hq, hkv, d, base, rope_layout=layout)
+    o = torch.full((lq_total, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    kf_rot = torch.full((lq_total, hkv, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    nbytes = ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, b_len, True)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    ba.ba_final_block_attention_cached(heads, dev_bf16(qb), dev_bf16(kcache_b), dev_bf16(vcache_b), dev_bf16(kfb),
+                                       dev_bf16(vfb), o, kf_rot, cu_q, cu_blk, b_off, b_len,
+                                       b_old if any(b_old) else None, b_new if explicit_new else None,
+                                       q_pos0 if any(p[3] is not None for p in prompts) else None, ws)
+    torch.cuda.synchronize()
+    assert_attention_close(host_f64(o), ref, "block cache, " + name)
+    # the rotated final-block keys come out as in the plain entry point
+    kf_ref = np.concatenate([oracle.rope_dense(f(kfb)[cu_q[n]:cu_q[n + 1]], np.arange(cu_q[n + 1] - cu_q[n]) + q_pos0[n], th,
+                                               layout=layout) for n in range(len(prompts))])
+    assert_reencode_bf16(host_bits(kf_rot), kf_ref, layout, "k_f_rot_out, " + name)
+
+
+def test_final_block_from_block_cache_agrees_with_two_step_path(ba):
+    """Same inputs through ba_reencode_positions + ba_final_block_attention: the two GPU routes differ
+    only by where the extra bf16 rounding falls (re-encoded keys there, re-turned queries here)."""
+    torch = torch_mod()
+    hq, hkv, d, base = 8, 2, 128, 500000.0
+    lens = [300, 128, 77, 513]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T, lq = int(offs[-1]), 50
+    kcache_b, vcache_b = wl.normal_bf16_bits(1300, (T, hkv, d)), wl.normal_bf16_bits(1301, (T, hkv, d))
+    qb, kfb, vfb = gen_qkv(1302, lq, hq, hkv, d)
+    heads = ba.Heads(hq, hkv, d, base)
+    kc, vc = dev_bf16(kcache_b), dev_bf16(vcache_b)
+    cu_q, cu_ctx = np.array([0, lq], dtype=np.int32), np.array([0, T], dtype=np.int32)
+    k_ctx = torch.empty_like(kc)
+    ba.ba_reencode_positions(heads, kc, k_ctx, offs[:-1], offs[:-1], lens, None, offs[:-1], ba.REENC_SHIFT)
+    o2 = gpu_final(ba, heads, dev_bf16(qb), k_ctx, vc, dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
+    o1 = torch.full_like(o2, float("nan"))
+    cu_blk = np.array([0, len(lens)], dtype=np.int32)
+    ws = torch.empty(max(ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, lens), 256),
+                     dtype=torch.uint8, device="cuda")
+    ba.ba_final_block_attention_cached(heads, dev_bf16(qb), kc, vc, dev_bf16(kfb), dev_bf16(vfb), o1, None, cu_q,
+                                       cu_blk, offs[:-1], lens, None, None, None, ws)
+    torch.cuda.synchronize()
+    assert_attention_close(host_f64(o1), host_f64(o2), "block cache vs two-step")
 
 
 def test_determinism_bitwise(ba):
