@@ -10,6 +10,8 @@
 // Thread mapping as in the re-encode kernel: a thread owns 16-byte chunk c and chunk c + CH/2
 // of one token and walks a group of heads, its sin/cos computed once.  Few tokens: one head
 // per thread (many short threads); many tokens: several heads per thread.
+#include <string.h>
+
 #include "ba_device.h"
 
 namespace ba {
@@ -31,12 +33,27 @@ __global__ __launch_bounds__(kThreads) void rope_rot_table_kernel(float *dst, in
 }
 
 template <int D, int LAYOUT>
-__global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParams p, RopeSegs segs,
-                                                                RopeTable rt) {
+__global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParams p, RopeSegs segs, RopeTable rt,
+                                                                RopeRotsSmall rots) {
   constexpr int VEC = 8;
   constexpr int CH = D / VEC;
   constexpr int TPV = CH / 2;          // threads per head vector
   constexpr int TPP = kThreads / TPV;  // tokens per workgroup
+  {
+    // workgroup rows beyond the head groups fill a (small) table of rotations, one thread per entry
+    const int head_groups = (p.do_q ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0) +
+                            (p.do_k ? (p.n_kv_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0);
+    if ((int)blockIdx.y >= head_groups) {
+      const int idx = (((int)blockIdx.y - head_groups) * (int)gridDim.x + (int)blockIdx.x) * kThreads + (int)threadIdx.x;
+      if (idx < p.n_rot * (D / 2)) {
+        const int b = idx / (D / 2), j = idx - b * (D / 2);
+        float c, s;
+        sincos_phase(rope_phase(rots.angle[b], rt.turns[j]), c, s);
+        reinterpret_cast<float2 *>(p.rot_dst)[idx] = make_float2(c, s);
+      }
+      return;
+    }
+  }
   const int c = threadIdx.x % TPV;
   const int t = segs.start[0] + blockIdx.x * TPP + threadIdx.x / TPV;
   if (t >= segs.start[segs.n]) return;
@@ -99,18 +116,30 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
   }
 }
 
+// rots: a small table of rotations to fill in the same launch, or null
 template <int D>
-hipError_t launch_d(const RopePrepassParams &p, const RopeSegs &segs, const RopeTable &rt, hipStream_t stream) {
+hipError_t launch_d(RopePrepassParams p, const RopeSegs &segs, const RopeTable &rt, const RopeRotsSmall *rots,
+                    hipStream_t stream) {
   constexpr int TPP = kThreads / (D / 8 / 2);
   const int64_t tokens = (int64_t)segs.start[segs.n] - segs.start[0];
   const int groups = (p.do_q ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0) +
                      (p.do_k ? (p.n_kv_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0);
   if (tokens <= 0 || groups == 0) return hipSuccess;
-  dim3 grid((unsigned)((tokens + TPP - 1) / TPP), (unsigned)groups, 1);
+  const unsigned gx = (unsigned)((tokens + TPP - 1) / TPP);
+  RopeRotsSmall none;
+  unsigned rot_rows = 0;
+  if (rots) {
+    const int64_t entries = (int64_t)p.n_rot * (D / 2);
+    rot_rows = (unsigned)((entries + (int64_t)gx * kThreads - 1) / ((int64_t)gx * kThreads));
+  } else {
+    p.n_rot = 0;
+    memset(&none, 0, sizeof(none));
+  }
+  dim3 grid(gx, (unsigned)groups + rot_rows, 1);
   if (p.layout == 0)
-    hipLaunchKernelGGL((rope_prepass_kernel<D, 0>), grid, dim3(kThreads), 0, stream, p, segs, rt);
+    hipLaunchKernelGGL((rope_prepass_kernel<D, 0>), grid, dim3(kThreads), 0, stream, p, segs, rt, rots ? *rots : none);
   else
-    hipLaunchKernelGGL((rope_prepass_kernel<D, 1>), grid, dim3(kThreads), 0, stream, p, segs, rt);
+    hipLaunchKernelGGL((rope_prepass_kernel<D, 1>), grid, dim3(kThreads), 0, stream, p, segs, rt, rots ? *rots : none);
   return hipGetLastError();
 }
 
@@ -118,20 +147,18 @@ hipError_t launch_d(const RopePrepassParams &p, const RopeSegs &segs, const Rope
 
 hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeRots *rots,
                                const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream) {
-  if (p.rot_dst && p.n_rot > 0 && (rots || rots_small)) {
+  // a large table of rotations gets a launch of its own; a small one rides along with the rows
+  const bool want_rot = p.rot_dst && p.n_rot > 0;
+  if (want_rot && rots) {
     const int entries = p.n_rot * (p.head_dim / 2);
-    const dim3 grid((entries + kThreads - 1) / kThreads);
-    if (rots_small)
-      hipLaunchKernelGGL((rope_rot_table_kernel<kBlkSmallBlocks>), grid, dim3(kThreads), 0, stream, p.rot_dst, p.n_rot,
-                         p.head_dim / 2, *rots_small, rt);
-    else
-      hipLaunchKernelGGL((rope_rot_table_kernel<kBlkMaxBlocks>), grid, dim3(kThreads), 0, stream, p.rot_dst, p.n_rot,
-                         p.head_dim / 2, *rots, rt);
+    hipLaunchKernelGGL((rope_rot_table_kernel<kBlkMaxBlocks>), dim3((entries + kThreads - 1) / kThreads),
+                       dim3(kThreads), 0, stream, p.rot_dst, p.n_rot, p.head_dim / 2, *rots, rt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  if (p.head_dim == 128) return launch_d<128>(p, segs, rt, stream);
-  if (p.head_dim == 64) return launch_d<64>(p, segs, rt, stream);
+  const RopeRotsSmall *ride = (want_rot && !rots) ? rots_small : nullptr;
+  if (p.head_dim == 128) return launch_d<128>(p, segs, rt, ride, stream);
+  if (p.head_dim == 64) return launch_d<64>(p, segs, rt, ride, stream);
   return hipErrorInvalidValue;
 }
 
