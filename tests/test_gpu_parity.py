@@ -598,6 +598,80 @@ def test_final_block_from_block_cache_agrees_with_two_step_path(ba):
     assert_attention_close(host_f64(o1), host_f64(o2), "block cache vs two-step")
 
 
+def test_many_small_blocks_incremental_frame_update(ba):
+    """Appendix A's workload in miniature: a prompt of 320 small state blocks, of which one changes
+    (and changes length) from one frame to the next.  Only the changed block is encoded again
+    (ba_encode_blocks, cacheable keys at local positions); every other block is reused from the
+    cache as it is, although all blocks behind the changed one move; both frames against the oracle."""
+    torch = torch_mod()
+    hq, hkv, d, base = 8, 2, 64, 10000.0
+    th = oracle.theta(base, d)
+    f = oracle.bf16_bits_to_f64
+    heads = ba.Heads(hq, hkv, d, base)
+    rng = np.random.default_rng(77)
+    n_blk = 320
+    lens = rng.integers(20, 61, n_blk).astype(np.int32)
+    slot = 64  # cache rows reserved per block
+    cap = (n_blk + 1) * slot
+    # un-rotated q, k, v of every block's tokens, laid out in their cache slots
+    qb, kb, vb = gen_qkv(1400, cap, hq, hkv, d)
+    offs = (np.arange(n_blk) * slot).astype(np.int32)
+    kcache = torch.zeros((cap, hkv, d), dtype=torch.bfloat16, device="cuda")
+    vcache = dev_bf16(vb)
+    k_local_ref = np.zeros((cap, hkv, d))
+
+    def encode_into_cache(b_ids):
+        """ba_encode_blocks on the given blocks (each its own call list entry), k_local written to the slots"""
+        for b in b_ids:
+            o0, ln = int(offs[b]), int(lens[b])
+            blk = np.array([0, ln], dtype=np.int32)
+            q, k, v = dev_bf16(qb[o0:o0 + ln]), dev_bf16(kb[o0:o0 + ln]), dev_bf16(vb[o0:o0 + ln])
+            o = torch.empty_like(q)
+            ws = torch.empty(ba.ba_encode_blocks_workspace_bytes(heads, blk, 1, True), dtype=torch.uint8, device="cuda")
+            ba.ba_encode_blocks(heads, q, k, v, o, kcache[o0:o0 + ln], blk, 1, ws)
+            k_local_ref[o0:o0 + ln] = oracle.rope_dense(f(kb[o0:o0 + ln]), np.arange(ln), th, 0)
+
+    lq = 30
+    qf, kff, vff = gen_qkv(1410, lq, hq, hkv, d)
+    cu_q, cu_blk = np.array([0, lq], dtype=np.int32), np.array([0, n_blk], dtype=np.int32)
+
+    def frame(order):
+        b_off, b_len = offs[order], lens[order]
+        ws = torch.empty(ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, b_len), dtype=torch.uint8,
+                         device="cuda")
+        o = torch.full((lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        ba.ba_final_block_attention_cached(heads, dev_bf16(qf), kcache, vcache, dev_bf16(kff), dev_bf16(vff), o, None,
+                                           cu_q, cu_blk, b_off, b_len, None, None, None, ws)
+        torch.cuda.synchronize()
+        # oracle: its own cache (its fp64 rotation of the seeded keys, rounded to bf16 as a cache stores it),
+        # re-encoded in fp64, then the final block
+        kc64 = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(k_local_ref.astype(np.float32))).astype(np.float64)
+        new0 = np.concatenate([[0], np.cumsum(b_len)[:-1]]).astype(np.int32)
+        T = int(b_len.sum())
+        k_ctx = oracle.reencode(kc64, b_off, new0, b_len, th, new_pos0=new0, out=np.zeros((T, hkv, d)))
+        v_ctx = np.concatenate([f(vb)[o0:o0 + ln] for o0, ln in zip(b_off, b_len)])
+        ref = oracle.final_block(f(qf), k_ctx, v_ctx, f(kff), f(vff), cu_q, [0, T], th)
+        assert_attention_close(host_f64(o), ref, "many small blocks")
+
+    order = np.arange(n_blk)
+    encode_into_cache(range(n_blk))
+    torch.cuda.synchronize()
+    # the cached keys themselves against the oracle's rotation at local positions
+    for b in (0, 17, n_blk - 1):
+        o0, ln = int(offs[b]), int(lens[b])
+        assert_reencode_bf16(host_bits(kcache[o0:o0 + ln]), k_local_ref[o0:o0 + ln], 0, "cached block %d" % b)
+    frame(order)
+    # next frame: block 100 is replaced by new content of another length, stored in the spare slot
+    spare = n_blk
+    offs2 = np.concatenate([offs, [spare * slot]]).astype(np.int32)
+    lens2 = np.concatenate([lens, [int(lens[100]) + 9]]).astype(np.int32)
+    offs, lens = offs2, lens2
+    encode_into_cache([spare])
+    order2 = order.copy()
+    order2[100] = spare
+    frame(order2)
+
+
 def test_determinism_bitwise(ba):
     """Same inputs -> bitwise-same outputs across runs (the split merge has a fixed order)."""
     hq, hkv, d = 32, 8, 128
