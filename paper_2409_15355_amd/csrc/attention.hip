@@ -178,11 +178,6 @@ __device__ long long g_wg[1024][4];  // per workgroup: wall clock at start and e
 #define BA_MARK_ALWAYS(tile, m) do { } while (0)
 #define BA_WALL(tile, m) do { } while (0)
 #endif
-#ifdef BA_TRACE_TILES
-#define BA_MARK(tile, m) BA_MARK_ALWAYS(tile, m)
-#else
-#define BA_MARK(tile, m) do { } while (0)
-#endif
 
 template <int D, typename Meta>
 __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta) {
@@ -434,9 +429,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   auto mfma_block = [&](uint32_t vofs, uint32_t kofs, bool more, bool copy, const CopyJob &cj,
                         const uint32_t (&cp_off)[G::IPW], const bf16x8_t (&pf)[4], f32x16_t (&sacc)[2],
                         bf16x8_t (&fr)[W]) __attribute__((always_inline)) {
-#ifdef BA_VAR_NOMFMA
-    return;
-#endif
     // the wave in its MFMA block goes first at the issue arbiter; the other wave of the SIMD, in its
     // exponentials, fills the slots between
     __builtin_amdgcn_s_setprio(3);
@@ -446,10 +438,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       const int kc = st / G::DT, dt = st % G::DT;
       oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % W], pf[kc], oacc[dt], 0, 0, 0);
       if ((st & 1) && st / 2 < G::IPW) {
-#ifndef BA_VAR_NOCOPY
         const int i = st / 2;
         if (__builtin_expect(copy, 1)) lds_dma16(cj.ptr, cp_off[i], cj.dst + i * 1024);
-#endif
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -539,9 +529,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   // The softmax step of one tile: mask where needed (diagonal and ragged tiles only), turn the
   // exponents into P, and keep the running sum.  All branches are wave-uniform.
   auto softmax = [&](const Cursor &cm, bool first, f32x16_t (&sacc)[2], bf16x8_t (&pf)[4]) __attribute__((always_inline)) {
-#ifdef BA_VAR_NOSM
-    if (!first) return;
-#endif
     const bool isctx = cm.seg < n_ctx_segs;
     const int key0 = cm.ts * kTileKeys;
     const int valid = min(kTileKeys, cm.len - key0);
@@ -711,9 +698,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       softmax(cm, i == 0, sacc, pf);
       // tile i+1 of this wave's kind must have landed before the barrier; the only copy that
       // may be younger is tile i+2's (tile i+3's starts inside the MFMA block below)
-#ifndef BA_VAR_NOWAIT
       if (steady || i + 2 < n_t) dma_wait<G::IPW>(); else dma_wait<0>();
-#endif
       if (kBlocks && !steady && i + 1 < n_t && cm.rem == 1) load_q(rot_of(cm.seg + 1));  // tile i+1 opens a segment
       const bool copy = steady || i + 3 < n_t;
       CopyJob cj;
