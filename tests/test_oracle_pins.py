@@ -380,3 +380,38 @@ def test_table3_flops_are_linear_in_tokens():
     for length, vanilla, block in rows:
         assert float(block) == 7.5e11
         assert abs(float(vanilla) - per_token * int(length)) / float(vanilla) < 0.03
+
+
+@pytest.mark.parametrize("layout", [oracle.LAYOUT_INTERLEAVED, oracle.LAYOUT_HALF])
+def test_shift_of_the_key_equals_opposite_shift_of_the_query(layout):
+    """The identity the block-cache entry point rests on (Eq. 2-3 applied to q instead of k): a score
+    depends on positions only through their difference, so re-encoding a cached key by a shift
+    gives the same score as turning the query back by that shift and leaving the key alone; and a
+    final block computed from per-block re-encoded keys does not care where in the cache the
+    blocks were stored."""
+    D = 16
+    th = oracle.theta(10000.0, D)
+    rng = np.random.default_rng(31)
+    q, k = rng.standard_normal(D), rng.standard_normal(D)
+    for p_q, u, old0, new0 in [(900, 3, 0, 512), (40, 0, 17, 5), (12345, 77, 1000, 0)]:
+        k_cached = oracle.rope(k, old0 + u, th, layout)                    # as it sits in the cache
+        k_moved = oracle.reencode(k_cached[None, None, :], [0], [0], [1], th, old_pos0=[old0 + u], new_pos0=[new0 + u],
+                                  layout=layout)[0, 0]
+        s_reencoded = oracle.rope(q, p_q, th, layout) @ k_moved
+        s_turned_q = oracle.rope(q, p_q - (new0 - old0), th, layout) @ k_cached
+        s_direct = oracle.rope(q, p_q, th, layout) @ oracle.rope(k, new0 + u, th, layout)
+        assert abs(s_reencoded - s_direct) < 1e-9 and abs(s_turned_q - s_direct) < 1e-9
+    # cache placement does not matter
+    Hq = Hkv = 1
+    lens, slots = [5, 3, 4], [20, 0, 9]
+    cache_k, cache_v = rng.standard_normal((30, Hkv, D)), rng.standard_normal((30, Hkv, D))
+    qf, kf, vf = rng.standard_normal((2, Hq, D)), rng.standard_normal((2, Hkv, D)), rng.standard_normal((2, Hkv, D))
+    new0 = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int32)
+    T = sum(lens)
+    k_ctx = oracle.reencode(cache_k, slots, new0, lens, th, new_pos0=new0, layout=layout, out=np.zeros((T, Hkv, D)))
+    v_ctx = np.concatenate([cache_v[s:s + n] for s, n in zip(slots, lens)])
+    o1 = oracle.final_block(qf, k_ctx, v_ctx, kf, vf, [0, 2], [0, T], th, layout=layout)
+    packed_k = np.concatenate([cache_k[s:s + n] for s, n in zip(slots, lens)])
+    k_ctx2 = oracle.reencode(packed_k, new0, new0, lens, th, new_pos0=new0, layout=layout)
+    o2 = oracle.final_block(qf, k_ctx2, v_ctx, kf, vf, [0, 2], [0, T], th, layout=layout)
+    np.testing.assert_allclose(o1, o2, rtol=0, atol=1e-12)
