@@ -113,7 +113,7 @@ int32_t ba_profile_end(double *ms_sum, int32_t *launches);
  * BA_ROPE_NONE k is used as given and k_local_out must be null.
  * Zero-length blocks are legal no-ops.  ws/ws_bytes: 256-byte aligned device workspace
  * of at least ba_encode_blocks_workspace_bytes() bytes (may be null when that is 0; with
- * BA_ROPE_APPLY it holds the rotated queries, and the rotated keys if k_local_out is null).
+ * BA_ROPE_APPLY it holds a table of rotation factors, and the rotated keys if k_local_out is null).
  */
 int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
                          const ba_tensor *v, const ba_tensor *o_out,

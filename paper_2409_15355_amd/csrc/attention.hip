@@ -614,16 +614,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       u32x4_t z = {0u, 0u, 0u, 0u};
       raw[kk] = row_ok ? *reinterpret_cast<const u32x4_t *>(qp + kk * 16) : z;
     }
-    if (!p.q_ready) {
-#pragma unroll
-      for (int kk = 0; kk < G::KCH; ++kk)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          raw[kk][e] = pack_bf16(bf16_lo(raw[kk][e]) * c2, bf16_hi(raw[kk][e]) * c2);
-    }
-    if (kBlocks && rot >= 0) {
-      // (cos, sin) of minus the block's shift times theta_j, j = 0 .. D/2 - 1
-      const f32x4_t *tab = reinterpret_cast<const f32x4_t *>(p.blk_rot + (int64_t)rot * D);
+    // rotate the fragments by the angles of a table row: entry j = (cos, sin) (times a scale, if any)
+    auto rotate_by = [&](const f32x4_t *tab) __attribute__((always_inline)) {
       if (p.rope_layout == 0) {
 #pragma unroll
         for (int kk = 0; kk < G::KCH; ++kk) {
@@ -653,6 +645,24 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
           }
         }
       }
+    };
+    if (!p.q_ready) {
+      if (p.q_table) {
+        // un-rotated rows and the pre-pass's table of scale * (cos, sin) per token: rotate here, so that
+        // the rotated queries never make a round trip through memory
+        // (lanes beyond the problem's rows hold zeros: any row of the table will do, take an existing one)
+        rotate_by(reinterpret_cast<const f32x4_t *>(p.q_table + (int64_t)(pr.q_tok0 + (row_ok ? tok_v : 0)) * D));
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < G::KCH; ++kk)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            raw[kk][e] = pack_bf16(bf16_lo(raw[kk][e]) * c2, bf16_hi(raw[kk][e]) * c2);
+      }
+    }
+    if (kBlocks && rot >= 0) {
+      // (cos, sin) of minus the block's shift times theta_j, j = 0 .. D/2 - 1
+      rotate_by(reinterpret_cast<const f32x4_t *>(p.blk_rot + (int64_t)rot * D));
     }
     // (the empty asm makes the compiler wait for these loads HERE: left pending, it would wait for
     // them at the first use of the fragments inside the loop's MFMA block, on every iteration, and

@@ -234,7 +234,8 @@ int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, c
 int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_tensor *q, uint16_t *q_rot,
                          const ba_tensor *k, const ba_tensor *k_rot, int n, const int32_t *start,
                          const int32_t *pos0, hipStream_t stream, const ba::RopeRots *rots = nullptr,
-                         const ba::RopeRotsSmall *rots_small = nullptr, float *rot_dst = nullptr, int n_rot = 0) {
+                         const ba::RopeRotsSmall *rots_small = nullptr, float *rot_dst = nullptr, int n_rot = 0,
+                         float *q_table = nullptr) {
   ba::RopeSegs segs;
   memset(&segs, 0, sizeof(segs));
   segs.n = n;
@@ -267,7 +268,8 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
   p.layout = h->rope_layout;
   // few tokens: one head per thread (more, shorter threads); many: sin/cos shared by several heads
   p.heads_per_thread = tokens >= 16384 ? 8 : (tokens >= 2048 ? 2 : 1);
-  p.do_q = 1;
+  p.do_q = q_table ? 2 : 1;  // a table of factors for the attention core, or rotated rows
+  p.q_table = q_table;
   p.do_k = 1;
   p.rot_dst = rot_dst;
   p.n_rot = n_rot;
@@ -346,7 +348,7 @@ size_t ba_encode_blocks_workspace_bytes(const ba_heads *heads, int32_t n_blocks,
   if (rope_mode != BA_ROPE_APPLY) return 0;
   const size_t T = (size_t)block_offsets[n_blocks];
   const size_t k_bytes = have_k_local_out ? 0 : align256(T * heads->n_kv_heads * heads->head_dim * 2);
-  return k_bytes + align256(T * heads->n_q_heads * heads->head_dim * 2);  // rotated K, rotated pre-scaled Q
+  return k_bytes + align256(T * heads->head_dim * 4);  // rotated K; scale * (cos, sin) per token and pair
 }
 
 int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
@@ -376,10 +378,12 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ba::RopeTable rt;
   build_rope_table(heads, &rt);
 
-  // what the attention kernel reads: the caller's q and k (NONE), or freshly rotated ones (APPLY):
-  // K into k_local_out or the workspace, Q (also pre-scaled) into the workspace
+  // what the attention kernel reads: the caller's q and k (NONE), or with APPLY freshly rotated keys
+  // (in k_local_out or the workspace) and the caller's q next to a table of rotation factors (in
+  // the workspace) with which the kernel rotates its query rows itself: at this step's sizes a
+  // round trip of the rotated queries through memory would cost more than the attention saves
   ba_tensor k_use = *k;
-  ba_tensor q_use = *q;
+  float *q_table = nullptr;
   if (rope_mode == BA_ROPE_APPLY) {
     const size_t need = ba_encode_blocks_workspace_bytes(heads, n_blocks, block_offsets, rope_mode, k_local_out != nullptr);
     if (!ws || ws_bytes < need || ((uintptr_t)ws & 255))
@@ -395,17 +399,15 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
       k_use.dtype = BA_DTYPE_BF16;
       wsp += align256((size_t)T * heads->n_kv_heads * D * 2);
     }
-    q_use.ptr = wsp;
-    q_use.stride_head = D;
-    q_use.stride_tok = (int64_t)heads->n_q_heads * D;
-    q_use.dtype = BA_DTYPE_BF16;
+    q_table = (float *)wsp;
   }
 
   ba::AttnParams ap;
   memset(&ap, 0, sizeof(ap));
-  ap.q = (const uint16_t *)q_use.ptr;
-  ap.q_st = q_use.stride_tok;
-  ap.q_sh = q_use.stride_head;
+  ap.q = (const uint16_t *)q->ptr;
+  ap.q_st = q->stride_tok;
+  ap.q_sh = q->stride_head;
+  ap.q_table = q_table;
   ap.kf = (const uint16_t *)k_use.ptr;
   ap.kf_st = k_use.stride_tok;
   ap.kf_sh = k_use.stride_head;
@@ -427,7 +429,7 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ap.group_div = ba::make_fast_div((uint32_t)G);
   ap.head_dim = D;
   ap.scale_log2e = scale_log2e(heads);
-  ap.q_ready = rope_mode == BA_ROPE_APPLY;
+  ap.q_ready = 0;
   ap.rope_layout = heads->rope_layout;
   ap.n_splits = 1;
 
@@ -450,7 +452,8 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
     ap.total_tiles = (int32_t)tiles;
     if (tiles == 0) continue;
     if (rope_mode == BA_ROPE_APPLY) {  // local positions: every block starts at 0
-      if ((rc = run_rope_prepass(heads, rt, q, (uint16_t *)q_use.ptr, k, &k_use, n, meta.offs, nullptr, stream)))
+      if ((rc = run_rope_prepass(heads, rt, q, nullptr, k, &k_use, n, meta.offs, nullptr, stream, nullptr, nullptr,
+                                 nullptr, 0, q_table)))
         return rc;
     }
     hipError_t e;

@@ -73,6 +73,7 @@ struct RopePrepassParams {
   int32_t do_q, do_k;
   float *rot_dst;    // [n_rot][D/2][2]: (cos, sin) of rot_angle[b] * theta_j, or null
   int32_t n_rot;
+  float *q_table;    // do_q == 2: instead of rotating Q rows, write q_scale * (cos, sin) per token: [tokens][D/2][2]
 };
 
 // positions (in tokens) by which the rows of the rotation table turn
@@ -126,6 +127,8 @@ struct AttnParams {
   FastDiv group_div;  // division by `group`
   float scale_log2e;  // softmax scale * log2(e)
   int32_t q_ready;    // q is already rotated and multiplied by scale_log2e (the RoPE pre-pass ran)
+  const float *q_table;  // else, if non-null: [tokens][D/2][2] = scale_log2e * (cos, sin) of each
+                         // token's position times theta_j; the kernel rotates q with it
   int32_t rope_layout;
   const float *blk_rot;  // block table only: [blocks][D/2][2] (cos, sin) of minus each block's shift
   int32_t n_splits;

@@ -32,6 +32,11 @@ __global__ __launch_bounds__(kThreads) void rope_rot_table_kernel(float *dst, in
   reinterpret_cast<float2 *>(dst)[idx] = make_float2(c, s);
 }
 
+// workgroup rows of the Q job: head groups, or one row when only the table of factors is written
+__host__ __device__ inline int q_groups(const RopePrepassParams &p) {
+  return p.do_q == 1 ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : (p.do_q == 2 ? 1 : 0);
+}
+
 template <int D, int LAYOUT>
 __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParams p, RopeSegs segs, RopeTable rt,
                                                                 RopeRotsSmall rots) {
@@ -41,8 +46,7 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
   constexpr int TPP = kThreads / TPV;  // tokens per workgroup
   {
     // workgroup rows beyond the head groups fill a (small) table of rotations, one thread per entry
-    const int head_groups = (p.do_q ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0) +
-                            (p.do_k ? (p.n_kv_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0);
+    const int head_groups = q_groups(p) + (p.do_k ? (p.n_kv_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0);
     if ((int)blockIdx.y >= head_groups) {
       const int idx = (((int)blockIdx.y - head_groups) * (int)gridDim.x + (int)blockIdx.x) * kThreads + (int)threadIdx.x;
       if (idx < p.n_rot * (D / 2)) {
@@ -65,7 +69,7 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
   const int pos = segs.pos0[lo] + (t - segs.start[lo]);
 
   // which tensor and which heads this workgroup handles: Q head groups first, then K
-  const int groups_q = p.do_q ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0;
+  const int groups_q = q_groups(p);
   const bool is_q = (int)blockIdx.y < groups_q;
   const int grp = is_q ? blockIdx.y : blockIdx.y - groups_q;
   const int n_heads = is_q ? p.n_q_heads : p.n_kv_heads;
@@ -89,6 +93,20 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
       cs[e] *= scale;
       sn[e] *= scale;
     }
+  }
+  if (is_q && p.do_q == 2) {
+    // the factors themselves, for the attention core to rotate q with: entry j at [t][j] = (cos, sin)
+    float2 *row = reinterpret_cast<float2 *>(p.q_table) + (int64_t)t * (D / 2);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      int j;
+      if (LAYOUT == 0)
+        j = (e < VEC / 2) ? c * (VEC / 2) + e : (c + CH / 2) * (VEC / 2) + (e - VEC / 2);
+      else
+        j = c * VEC + e;
+      row[j] = make_float2(cs[e], sn[e]);
+    }
+    return;
   }
 #pragma unroll 4
   for (int h = h_begin; h < h_end; ++h) {
@@ -122,8 +140,7 @@ hipError_t launch_d(RopePrepassParams p, const RopeSegs &segs, const RopeTable &
                     hipStream_t stream) {
   constexpr int TPP = kThreads / (D / 8 / 2);
   const int64_t tokens = (int64_t)segs.start[segs.n] - segs.start[0];
-  const int groups = (p.do_q ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0) +
-                     (p.do_k ? (p.n_kv_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0);
+  const int groups = q_groups(p) + (p.do_k ? (p.n_kv_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0);
   if (tokens <= 0 || groups == 0) return hipSuccess;
   const unsigned gx = (unsigned)((tokens + TPP - 1) / TPP);
   RopeRotsSmall none;

@@ -117,9 +117,9 @@ def test_final_rejects_bad_arguments_and_sizes_workspace(lib):
 
 def test_workspace_queries(lib):
     h = ba.Heads(32, 8, 128)
-    # rotated keys (unless the caller takes them) and rotated, pre-scaled queries
-    assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 400], ba.ROPE_APPLY, False) == 400 * (8 + 32) * 128 * 2
-    assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 400], ba.ROPE_APPLY, True) == 400 * 32 * 128 * 2
+    # rotated keys (unless the caller takes them) and the table of rotation factors (2 floats per token and pair)
+    assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 400], ba.ROPE_APPLY, False) == 400 * 8 * 128 * 2 + 400 * 64 * 8
+    assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 400], ba.ROPE_APPLY, True) == 400 * 64 * 8
     assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 400], ba.ROPE_NONE, False) == 0
     # a single small prompt needs no split partials
     assert ba.ba_final_block_attention_workspace_bytes(ba.Heads(4, 4, 64), [0, 64], [0, 128], ba.ROPE_NONE) == 0
