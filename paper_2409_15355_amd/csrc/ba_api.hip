@@ -433,6 +433,14 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ap.rope_layout = heads->rope_layout;
   ap.n_splits = 1;
 
+  // short blocks only: the schedule with small workgroups, several to a compute unit
+  int64_t max_len = 0;
+  for (int i = 0; i < n_blocks; ++i) max_len = std::max<int64_t>(max_len, (int64_t)block_offsets[i + 1] - block_offsets[i]);
+  int64_t short_max = ba::kShortMaxLen;
+  if (const char *e = getenv("BA_SHORT_MAX")) short_max = atoll(e);
+  const bool short_blocks = max_len <= short_max;
+  const int tile_rows = short_blocks ? ba::kShortTileRows : ba::kTileRows;
+
   for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
     const int n = std::min(ba::kEncMaxBlocks, n_blocks - b0);
     ba::EncodeMeta meta;
@@ -444,7 +452,7 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
       if (len * G > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "block %d: too many packed rows", b0 + i);
       meta.offs[i] = block_offsets[b0 + i];
       meta.tile_start[i] = (int32_t)tiles;
-      tiles += (len * G + ba::kTileRows - 1) / ba::kTileRows;
+      tiles += (len * G + tile_rows - 1) / tile_rows;
       if (tiles > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
     }
     meta.offs[n] = block_offsets[b0 + n];
@@ -459,7 +467,7 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
     hipError_t e;
     {
       ProfileScope ps(BA_PROFILE_ATTENTION, stream);
-      e = ba::launch_attn_encode(ap, meta, stream);
+      e = short_blocks ? ba::launch_attn_encode_short(ap, meta, stream) : ba::launch_attn_encode(ap, meta, stream);
     }
     if (e != hipSuccess) return device_fail(e, "encode attention launch");
   }

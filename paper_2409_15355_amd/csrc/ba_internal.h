@@ -106,6 +106,10 @@ inline FastDiv make_fast_div(uint32_t d) {
 
 constexpr int kTileRows = 256;  // packed (token, head-in-group) query rows per workgroup
 constexpr int kTileKeys = 64;   // keys per K/V tile
+constexpr int kShortTileRows = 128;  // packed query rows per workgroup of the short-block schedule
+// Per-block encoding takes the short-block schedule when no block of the call is longer than this
+// (beyond it the deep pipeline of the main core has filled and wins).
+constexpr int kShortMaxLen = 512;
 
 struct AttnParams {
   const uint16_t *q;
@@ -168,6 +172,8 @@ using FinalBlocksMeta = FinalBlocksMetaT<kBlkMaxPrompts, kBlkMaxBlocks>;
 using FinalBlocksMetaSmall = FinalBlocksMetaT<kBlkSmallPrompts, kBlkSmallBlocks>;
 
 hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
+// the same for short blocks: meta.tile_start counts row tiles of kShortTileRows rows
+hipError_t launch_attn_encode_short(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
 hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMeta &meta, hipStream_t stream);
 hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMetaSmall &meta, hipStream_t stream);
 hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, hipStream_t stream);

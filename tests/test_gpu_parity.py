@@ -144,6 +144,10 @@ ENC_CASES = [
     ("ragged-mha-d64", 2, 2, 64, 10000.0, [300, 5, 0, 0, 511, 256]),
     ("gqa8-d128", 8, 1, 128, 10000.0, [33, 100]),
     ("gqa3-odd-group", 6, 2, 64, 10000.0, [90, 171]),
+    # a block beyond the short-block schedule's limit sends the whole call through the main core
+    ("long-and-short-gqa4", 8, 2, 128, 500000.0, [700, 1, 63, 130]),
+    ("long-mha-d64", 2, 2, 64, 10000.0, [530, 300, 5]),
+    ("at-the-limit-gqa2", 4, 2, 128, 10000.0, [512, 31]),
 ]
 
 
