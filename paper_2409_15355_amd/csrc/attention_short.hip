@@ -43,17 +43,34 @@ struct SGeo {
   static_assert((size_t)kSWaves * 32 * ROWB <= LDS, "the output staging must fit the tile buffers");
 };
 
+#ifdef BA_TRACE
+// Debug build only: clock marks of wave 0 of every workgroup, read back by ba_debug_read_short().
+__device__ long long g_swg[16384][16];
+#define BA_SMARK(m)                                                                               \
+  do {                                                                                            \
+    if (threadIdx.x == 0 && blockIdx.x < 16384) g_swg[blockIdx.x][m] = (long long)clock64(); \
+  } while (0)
+#define BA_SNOTE(m, val)                                                                          \
+  do {                                                                                            \
+    if (threadIdx.x == 0 && blockIdx.x < 16384) g_swg[blockIdx.x][m] = (long long)(val);          \
+  } while (0)
+#else
+#define BA_SMARK(m) do { } while (0)
+#define BA_SNOTE(m, val) do { } while (0)
+#endif
+
 template <int D>
 __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p, EncodeMeta meta) {
   using G = SGeo<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
   lds_char *smem = (lds_char *)smem_generic;
+  // LDS map: buffer b = bytes [2 b TB, 2 (b + 1) TB): its K tile, then its V tile
   constexpr uint32_t TB = G::TILEB;
-  constexpr uint32_t VBASE = kSBuf * TB;
 
   // ---- which work item: consecutive items are the row tiles of one block at one KV head, and
   //      they share its K/V rows.  Workgroup ids are dealt round-robin to the 8 XCDs, so regroup
   //      them such that each XCD (and its L2) gets a contiguous run of items ---------------------
+  BA_SMARK(0);
   uint32_t id = blockIdx.x;
   {
     constexpr uint32_t kXcds = 8;
@@ -61,13 +78,38 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
     id = x * q + min(x, r) + id / kXcds;
   }
   const uint32_t n_rowtiles = (uint32_t)p.total_tiles;
-  const int kvh = (int)(id / n_rowtiles);
+  const int kvh = (int)fast_div(id, p.tiles_div);
   const int rowtile = (int)(n_rowtiles - 1 - (id - (uint32_t)kvh * n_rowtiles));  // a block's long row tiles first
-  const int b = find_segment(meta.tile_start, meta.n, rowtile);
+  // block of this row tile: the largest b with tile_start[b] <= rowtile, found in three rounds of
+  // independent table reads (every 32nd entry, every 4th, every one) instead of a bisection's nine
+  // dependent ones: the reads are scalar loads, and a work item this short feels each round trip
+  int b = 0;
+  static_assert(kEncMaxBlocks <= 320, "ten coarse samples cover the table");
+  {
+    // (entries past the last block hold INT_MAX, so no candidate needs a bounds check)
+    int hit[10];
+#pragma unroll
+    for (int k = 1; k < 10; ++k) hit[k] = meta.tile_start[k * 32];
+#pragma unroll
+    for (int k = 1; k < 10; ++k) b += hit[k] <= rowtile ? 32 : 0;
+    int fine = 0;
+#pragma unroll
+    for (int k = 1; k < 8; ++k) hit[k] = meta.tile_start[min(b + 4 * k, kEncMaxBlocks)];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) fine += hit[k] <= rowtile ? 4 : 0;
+    b += fine;
+    fine = 0;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) hit[k] = meta.tile_start[min(b + k, kEncMaxBlocks)];
+#pragma unroll
+    for (int k = 1; k < 4; ++k) fine += hit[k] <= rowtile ? 1 : 0;
+    b += fine;
+  }
   const int q_tok0 = meta.offs[b];
   const int lq = meta.offs[b + 1] - q_tok0;
   const int jt = rowtile - meta.tile_start[b];
 
+  BA_SMARK(1);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 31;  // query column inside the 32-wide MFMA group
@@ -85,8 +127,81 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   const int first_tok_wave = (int)fast_div((uint32_t)wave_row0, p.group_div);
 
   const int my_row = wave_row0 + col;
-  const bool row_ok = my_row < n_rows;
   const int my_tok = (int)fast_div((uint32_t)my_row, p.group_div);
+
+  // ---- Q rows (B operand of S^T = K Q^T) and, if they are to be rotated, the rows of the pre-pass's
+  //      table of scale * log2(e) * (cos, sin) for this wave's tokens: requested first and all at
+  //      once, so that the set-up below runs under their latency.  Both arrive as whole rows (a
+  //      lane fetching only its own 16 bytes of a row would cost a cache line each); the Q rows are
+  //      then turned into the fragment layout (lane = row) through this wave's slice of LDS ---------
+  // (rows beyond the block's take its last row: finite numbers that are never stored)
+  constexpr int QRPI = 64 / G::CPR;  // Q rows per load instruction
+  static_assert(32 / QRPI == G::KCH, "as many row loads as fragments");
+  u32x4_t ld[G::KCH];
+  constexpr uint32_t TROW = D * 4;    // bytes of a table row
+  constexpr int TCH = TROW / 16;      // its 16-byte chunks
+  constexpr int kTabOps = 8 * TROW / 1024;  // LDS-direct loads per wave for 8 table rows
+  static_assert(kSBuf == 3, "tile buffers 0 and 1 take the first tiles, 2 the waves' slices");
+  static_assert(kSWaves * 8 * TROW <= 2 * TB, "the table slices fit one tile buffer");
+  static_assert(kSWaves * 16 * G::ROWB <= 2 * TB, "the Q slices (16 rows at a time) fit one tile buffer");
+  static_assert(16 * G::ROWB == 8 * TROW, "one slice serves both uses");
+  const uint32_t tab_ofs = 2 * (2 * TB) + wave * (8 * TROW);  // first the table rows ...
+  const uint32_t q_ofs = tab_ofs;                              // ... then, once those are in registers, Q rows
+  int tab_tl = 0;  // this lane's row of the table slice
+  // Whole rows move QRPI at a time: this lane's row in step u is wave_row0 + u * QRPI + lane / CPR and
+  // its piece chunk lane % CPR.  Its element offset tok * st + g * sh (relative to the block's first
+  // token and the group's first head; 32 bits by the host's check) is carried from step to step:
+  // four rows on is either four heads on or, past the group's last head, into the next token.
+  // (worked out afresh by each of the two walks, load and store: kept, the row numbers would occupy
+  // registers all through the tile loop)
+  auto walk_rows = [&](int ln, uint32_t st, uint32_t sh, auto &&visit) __attribute__((always_inline)) {
+    const int wr_r0 = wave_row0 + ln / G::CPR;
+    const int wr_tok0 = (int)fast_div((uint32_t)wr_r0, p.group_div);
+    const int wr_g0 = wr_r0 - wr_tok0 * Gq;
+    uint32_t off = (uint32_t)wr_tok0 * st + (uint32_t)wr_g0 * sh;
+    int g = wr_g0;
+    const uint32_t d_in = 4u * sh, d_wrap = st + (uint32_t)(4 - Gq) * sh;
+#pragma unroll
+    for (int u = 0; u < G::KCH; ++u) {
+      visit(u, off, wr_r0);
+#pragma unroll
+      for (int s4 = 0; s4 < QRPI / 4; ++s4) {
+        g += 4;
+        const bool wrap = g >= Gq;
+        g = wrap ? g - Gq : g;
+        off += wrap ? d_wrap : d_in;
+      }
+    }
+  };
+  {
+    const char *qbase = (const char *)(p.q + (int64_t)q_tok0 * p.q_st + (int64_t)(kvh * Gq) * p.q_sh);
+    const uint32_t q_st = (uint32_t)p.q_st, q_sh = (uint32_t)p.q_sh;
+    const uint32_t last_off = (uint32_t)(lq - 1) * q_st + (uint32_t)(Gq - 1) * q_sh;  // the block's last row
+    walk_rows(lane, q_st, q_sh, [&](int u, uint32_t off, int wr_r0) __attribute__((always_inline)) {
+      const uint32_t o = wr_r0 < n_rows - u * QRPI ? off : last_off;
+      ld[u] = *reinterpret_cast<const u32x4_t *>(qbase + (o * 2u + (uint32_t)(lane % G::CPR) * 16u));
+    });
+#ifdef BA_TRACE
+    __builtin_amdgcn_sched_barrier(0);
+    BA_SMARK(11);
+#endif
+    if (p.q_table) {
+      // The rows of a wave span at most 8 tokens (the host sends only groups of 4 or more query
+      // heads here).  Chunk c of token row t sits at chunk c ^ (t & 7), which keeps the reads of
+      // different tokens off each other's banks.
+      const char *tbase = (const char *)(p.q_table + (int64_t)q_tok0 * D);
+#pragma unroll
+      for (int u = 0; u < kTabOps; ++u) {
+        const int t = u * (1024 / TROW) + lane / TCH, pc = lane % TCH;
+        const uint32_t tok = (uint32_t)min(first_tok_wave + t, lq - 1);
+        lds_dma16(tbase, tok * TROW + (uint32_t)((pc ^ (t & 7)) << 4), (uint32_t)(uintptr_t)smem + tab_ofs + u * 1024);
+      }
+      const int ld_tok = (int)fast_div((uint32_t)min(my_row, n_rows - 1), p.group_div);
+      tab_tl = max(ld_tok - first_tok_wave, 0);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  BA_SMARK(12);
 
   // ---- per-lane LDS read offsets inside a tile buffer (same swizzles as the tile fill below) ----
   uint32_t k_rd[G::KCH];  // K fragment: row `col`, chunk 2 kk + hf
@@ -128,74 +243,104 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
 #pragma unroll
     for (int u = 0; u < G::IPW; ++u) {
       const uint32_t row = (uint32_t)min(c_row[u], valid - 1);
-      lds_dma16(kp, row * k_rb + c_kchunk[u], lds_copy + (uint32_t)buf * TB + u * 1024);
-      lds_dma16(vp, row * v_rb + c_vchunk[u], lds_copy + VBASE + (uint32_t)buf * TB + u * 1024);
+      lds_dma16(kp, row * k_rb + c_kchunk[u], lds_copy + (uint32_t)buf * (2 * TB) + u * 1024);
+      lds_dma16(vp, row * v_rb + c_vchunk[u], lds_copy + (uint32_t)buf * (2 * TB) + TB + u * 1024);
     }
   };
   constexpr int kOpsPerTile = 2 * G::IPW;  // vector-memory operations of one wave per tile
-#pragma unroll
-  for (int j = 0; j < kSBuf - 1; ++j)
-    if (j < n_t) issue_copy(j, j);
+#ifdef BA_TRACE
+  __builtin_amdgcn_sched_barrier(0);
+  BA_SMARK(13);
+#endif
+  issue_copy(0, 0);  // (buffer 2 holds the waves' slices until the first barrier)
+  if (1 < n_t) issue_copy(1, 1);
+  __builtin_amdgcn_sched_barrier(0);  // the copies go out before anything waits for the Q rows
+  BA_SMARK(2);
+  BA_SNOTE(7, n_t);
 
-  // ---- Q fragments (B operand of S^T = K Q^T): the caller's rows, rotated here with the pre-pass's
-  //      table of scale * log2(e) * (cos, sin) per token, or just scaled if they need no rotation ----
-  bf16x8_t qf[G::KCH];
-  {
-    const int g = my_row - my_tok * Gq;
-    const int head = kvh * Gq + g;
-    const uint16_t *qp = p.q + (int64_t)(q_tok0 + my_tok) * p.q_st + (int64_t)head * p.q_sh + hf * 8;
-    u32x4_t raw[G::KCH];
+  // ---- rotate (or just scale) the Q rows into the fragments ---------------------------------------
+  BA_SMARK(3);
+  dma_wait<0>();  // the table rows and the first tile (this wave's share) have landed
+  BA_SMARK(4);
+  // The table first: entry j of a table row = (cos, sin) of pair j.  Interleaved pairs: fragment kk
+  // holds pairs kk * 8 + hf * 4 + (0..3); half-split pairs: fragments kk and kk + KCH/2 hold dims
+  // kk * 16 + hf * 8 + (0..7) and their partners, i.e. pairs of those same numbers.
+  f32x4_t cs[2 * G::KCH];
+  if (p.q_table) {
+    const bool halves = p.rope_layout != 0;
 #pragma unroll
-    for (int kk = 0; kk < G::KCH; ++kk) {
-      u32x4_t z = {0u, 0u, 0u, 0u};
-      raw[kk] = row_ok ? *reinterpret_cast<const u32x4_t *>(qp + kk * 16) : z;
-    }
-    if (p.q_table) {
-      // (lanes beyond the block's rows hold zeros: any row of the table will do, take an existing one)
-      const f32x4_t *tab = reinterpret_cast<const f32x4_t *>(p.q_table + (int64_t)(q_tok0 + (row_ok ? my_tok : 0)) * D);
-      if (p.rope_layout == 0) {
-#pragma unroll
-        for (int kk = 0; kk < G::KCH; ++kk) {
-          // this lane's pairs: frequencies kk * 8 + hf * 4 + e
-          const f32x4_t cs0 = tab[(kk * 8 + hf * 4) / 2], cs1 = tab[(kk * 8 + hf * 4) / 2 + 1];
-          const float c[4] = {cs0[0], cs0[2], cs1[0], cs1[2]}, sn[4] = {cs0[1], cs0[3], cs1[1], cs1[3]};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float x = bf16_lo(raw[kk][e]), y = bf16_hi(raw[kk][e]);
-            raw[kk][e] = pack_bf16(c[e] * x - sn[e] * y, sn[e] * x + c[e] * y);
-          }
-        }
-      } else {
-#pragma unroll
-        for (int kk = 0; kk < G::KCH / 2; ++kk) {
-          // dims kk * 16 + hf * 8 + (0..7) pair with the same dims + D/2: frequencies = those dims
-          f32x4_t cs[4];
-#pragma unroll
-          for (int u = 0; u < 4; ++u) cs[u] = tab[(kk * 16 + hf * 8) / 2 + u];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float c0 = cs[e][0], s0 = cs[e][1], c1 = cs[e][2], s1 = cs[e][3];
-            const uint32_t wa = raw[kk][e], wb = raw[kk + G::KCH / 2][e];
-            const float xa0 = bf16_lo(wa), xa1 = bf16_hi(wa), xb0 = bf16_lo(wb), xb1 = bf16_hi(wb);
-            raw[kk][e] = pack_bf16(c0 * xa0 - s0 * xb0, c1 * xa1 - s1 * xb1);
-            raw[kk + G::KCH / 2][e] = pack_bf16(s0 * xa0 + c0 * xb0, s1 * xa1 + c1 * xb1);
-          }
-        }
-      }
-    } else if (!p.q_ready) {
-      const float c2 = p.scale_log2e;
-#pragma unroll
-      for (int kk = 0; kk < G::KCH; ++kk)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) raw[kk][e] = pack_bf16(bf16_lo(raw[kk][e]) * c2, bf16_hi(raw[kk][e]) * c2);
-    }
-#pragma unroll
-    for (int kk = 0; kk < G::KCH; ++kk) {
-      asm volatile("" : "+v"(raw[kk]));  // the loads are waited for here, not inside the loop
-      qf[kk] = __builtin_bit_cast(bf16x8_t, raw[kk]);
+    for (int j = 0; j < 2 * G::KCH; ++j) {
+      const int c = halves ? (j / 4) * 8 + (j & 3) + hf * 4 : (j / 2) * 4 + (j & 1) + hf * 2;
+      cs[j] = *reinterpret_cast<const __attribute__((address_space(3))) f32x4_t *>(
+          smem + tab_ofs + (uint32_t)(tab_tl * TROW + ((c ^ (tab_tl & 7)) << 4)));
     }
   }
-  dma_wait<0>();  // the first tiles (this wave's share) have landed too
+  // whole rows -> fragments: 16 rows at a time through the slice (LDS serves a wave's accesses in
+  // order, so the slice needs no barrier); every lane reads the chunks of row `col mod 16` in both
+  // passes and keeps those of the pass its row was in
+  u32x4_t raw[G::KCH];
+  {
+    u32x4_t got[2][G::KCH];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+      for (int u = 0; u < G::KCH / 2; ++u) {
+        const int rp = u * QRPI + lane / G::CPR, c = lane % G::CPR;
+        *reinterpret_cast<__attribute__((address_space(3))) u32x4_t *>(
+            smem + q_ofs + rp * G::ROWB + ((c ^ (rp & (G::CPR - 1))) << 4)) = ld[pass * (G::KCH / 2) + u];
+      }
+      const int rp = col & 15;
+#pragma unroll
+      for (int kk = 0; kk < G::KCH; ++kk)
+        got[pass][kk] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t *>(
+            smem + q_ofs + rp * G::ROWB + (((kk * 2 + hf) ^ (rp & (G::CPR - 1))) << 4));
+    }
+#pragma unroll
+    for (int kk = 0; kk < G::KCH; ++kk)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) raw[kk][e] = (col >> 4) ? got[1][kk][e] : got[0][kk][e];
+  }
+  bf16x8_t qf[G::KCH];
+  if (p.q_table) {
+    const bool halves = p.rope_layout != 0;
+    if (!halves) {
+#pragma unroll
+      for (int kk = 0; kk < G::KCH; ++kk) {
+        const f32x4_t cs0 = cs[2 * kk], cs1 = cs[2 * kk + 1];
+        const float c[4] = {cs0[0], cs0[2], cs1[0], cs1[2]}, sn[4] = {cs0[1], cs0[3], cs1[1], cs1[3]};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x = bf16_lo(raw[kk][e]), y = bf16_hi(raw[kk][e]);
+          raw[kk][e] = pack_bf16(c[e] * x - sn[e] * y, sn[e] * x + c[e] * y);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < G::KCH / 2; ++kk) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const f32x4_t t = cs[4 * kk + e];  // pairs kk * 16 + hf * 8 + 2 e and the next
+          const float c0 = t[0], s0 = t[1], c1 = t[2], s1 = t[3];
+          const uint32_t wa = raw[kk][e], wb = raw[kk + G::KCH / 2][e];
+          const float xa0 = bf16_lo(wa), xa1 = bf16_hi(wa), xb0 = bf16_lo(wb), xb1 = bf16_hi(wb);
+          raw[kk][e] = pack_bf16(c0 * xa0 - s0 * xb0, c1 * xa1 - s1 * xb1);
+          raw[kk + G::KCH / 2][e] = pack_bf16(s0 * xa0 + c0 * xb0, s1 * xa1 + c1 * xb1);
+        }
+      }
+    }
+  } else if (!p.q_ready) {
+    const float c2 = p.scale_log2e;
+#pragma unroll
+    for (int kk = 0; kk < G::KCH; ++kk)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) raw[kk][e] = pack_bf16(bf16_lo(raw[kk][e]) * c2, bf16_hi(raw[kk][e]) * c2);
+  }
+#pragma unroll
+  for (int kk = 0; kk < G::KCH; ++kk) {
+    asm volatile("" : "+v"(raw[kk]));  // the loads are waited for here, not inside the loop
+    qf[kk] = __builtin_bit_cast(bf16x8_t, raw[kk]);
+  }
+  BA_SMARK(10);
 
   // ---- running state -----------------------------------------------------------------------------
   f32x16_t oacc[G::DT];
@@ -231,17 +376,18 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
     return s0 + s1;
   };
 
-  // ---- the walk over the key tiles: tile i lives in buffer i % kSBuf of each kind.  The barrier
-  //      at the head of iteration i says two things: every wave's share of tile i has landed, and
-  //      every wave is done with tile i-1, whose buffer the copy of tile i+2 may now overwrite -----
+  // ---- the walk over the key tiles: tile i lives in buffer i % 3.  The barrier at the head of
+  //      iteration i says two things: every wave's share of tile i has landed, and every wave is
+  //      done with tile i-1 (at i = 0: with its slice of buffer 2), so the copy of tile i+2 may
+  //      overwrite that buffer ------------------------------------------------------------------------
   int buf = 0;
 #pragma unroll 1
   for (int i = 0; i < n_t; ++i) {
-    if (i + kSBuf - 2 < n_t) dma_wait<(kSBuf - 2) * kOpsPerTile>(); else dma_wait<0>();
+    if (i + 1 < n_t) dma_wait<kOpsPerTile>(); else dma_wait<0>();  // tile i + 1 may still be on its way
     wg_barrier();
-    if (i + kSBuf - 1 < n_t) issue_copy(i + kSBuf - 1, buf == 0 ? kSBuf - 1 : buf - 1);
+    if (i + 2 < n_t) issue_copy(i + 2, buf == 0 ? 2 : buf - 1);
     if (i < wave_n_t) {
-      const uint32_t kofs = (uint32_t)buf * TB, vofs = VBASE + (uint32_t)buf * TB;
+      const uint32_t kofs = (uint32_t)buf * (2 * TB), vofs = kofs + TB;
       // S'^T = K Q'^T - reference: the accumulator starts at minus the row's reference, so the MFMA
       // result is directly the base-2 exponent
       f32x16_t sacc;
@@ -309,7 +455,13 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   //      slice of LDS so that rows leave as contiguous lines.  The slices lie in the tile buffers:
   //      every wave must be done with the last tile first -----------------------------------------
   // (all of this wave's LDS reads were consumed by its MFMAs, so only the barrier is needed)
+  BA_SMARK(5);
   wg_barrier();
+  BA_SMARK(8);
+  // (lane-dependent addresses are worked out from here on, not carried through the loop in registers)
+  int ln = lane;
+  asm volatile("" : "+v"(ln));
+  const int ecol = ln & 31, ehf = ln >> 5;
   lds_char *stage = smem + wave * (32 * G::ROWB);
   const float l_tot = l_run + other_half(l_run);
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
@@ -318,6 +470,7 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
       // dims dt * 32 + q4 * 8 + hf * 4 + (0..3) of query row `col`
+      const int col = ecol, hf = ehf;
       const int chunk = dt * 4 + q4;
       typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
       u32x2_t w;
@@ -329,20 +482,25 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  constexpr int ROWS_PP = 64 / G::CPR;  // rows per pass: CPR lanes, 16 bytes each, per row
+  BA_SMARK(9);
+  {
+    // (all the pieces are read back before the first store, so that the stores do not each wait
+    // for their own read)
+    u32x4_t w[G::KCH];
 #pragma unroll
-  for (int pass = 0; pass < 32 / ROWS_PP; ++pass) {
-    const int rr = pass * ROWS_PP + lane / G::CPR;
-    const int ch = lane % G::CPR;
-    const u32x4_t w = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t *>(
-        stage + rr * G::ROWB + ((ch ^ (rr & (G::CPR - 1))) << 4));
-    const int r = wave_row0 + rr;
-    if (r < n_rows) {
-      const int tok = (int)fast_div((uint32_t)r, p.group_div);
-      const int head = kvh * Gq + (r - tok * Gq);
-      *reinterpret_cast<u32x4_t *>(p.o + (int64_t)(q_tok0 + tok) * p.o_st + (int64_t)head * p.o_sh + ch * 8) = w;
+    for (int u = 0; u < G::KCH; ++u) {
+      const int rr = u * QRPI + ln / G::CPR;  // row inside this wave's 32
+      const int ch = ln % G::CPR;
+      w[u] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t *>(
+          stage + rr * G::ROWB + ((ch ^ (rr & (G::CPR - 1))) << 4));
     }
+    char *obase = (char *)(p.o + (int64_t)q_tok0 * p.o_st + (int64_t)(kvh * Gq) * p.o_sh);
+    walk_rows(ln, (uint32_t)p.o_st, (uint32_t)p.o_sh, [&](int u, uint32_t off, int wr_r0) __attribute__((always_inline)) {
+      if (wr_r0 < n_rows - u * QRPI)
+        *reinterpret_cast<u32x4_t *>(obase + (off * 2u + (uint32_t)(ln % G::CPR) * 16u)) = w[u];
+    });
   }
+  BA_SMARK(6);
 }
 
 template <int D>
@@ -356,6 +514,12 @@ hipError_t launch_short_t(const AttnParams &p, const EncodeMeta &meta, hipStream
 }
 
 }  // namespace
+
+#ifdef BA_TRACE
+extern "C" int ba_debug_read_short(long long *host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_swg), sizeof(g_swg));
+}
+#endif
 
 hipError_t launch_attn_encode_short(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream) {
   if (p.n_splits != 1) return hipErrorInvalidValue;

@@ -438,7 +438,11 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   for (int i = 0; i < n_blocks; ++i) max_len = std::max<int64_t>(max_len, (int64_t)block_offsets[i + 1] - block_offsets[i]);
   int64_t short_max = ba::kShortMaxLen;
   if (const char *e = getenv("BA_SHORT_MAX")) short_max = atoll(e);
-  const bool short_blocks = max_len <= short_max;
+  // (its query load assumes at most 8 tokens per 32 rows, and it addresses the rows of a block with
+  // 32-bit element offsets)
+  const int64_t widest = std::max(std::max(q->stride_tok, o_out->stride_tok),
+                                  (int64_t)G * std::max(q->stride_head, o_out->stride_head));
+  const bool short_blocks = max_len <= short_max && G >= 4 && (max_len + 1) * widest < 0x40000000;
   const int tile_rows = short_blocks ? ba::kShortTileRows : ba::kTileRows;
 
   for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
@@ -457,8 +461,10 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
     }
     meta.offs[n] = block_offsets[b0 + n];
     meta.tile_start[n] = (int32_t)tiles;
+    for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta.tile_start[i] = 0x7fffffff;
     ap.total_tiles = (int32_t)tiles;
     if (tiles == 0) continue;
+    ap.tiles_div = ba::make_fast_div((uint32_t)tiles);
     if (rope_mode == BA_ROPE_APPLY) {  // local positions: every block starts at 0
       if ((rc = run_rope_prepass(heads, rt, q, nullptr, k, &k_use, n, meta.offs, nullptr, stream, nullptr, nullptr,
                                  nullptr, 0, q_table)))

@@ -137,13 +137,14 @@ struct AttnParams {
   const float *blk_rot;  // block table only: [blocks][D/2][2] (cos, sin) of minus each block's shift
   int32_t n_splits;
   int32_t total_tiles;  // row tiles over all problems of this launch
+  FastDiv tiles_div;    // division by total_tiles (short-block schedule)
 };
 
 constexpr int kEncMaxBlocks = 320;
 struct EncodeMeta {
   int32_t n;
   int32_t offs[kEncMaxBlocks + 1];        // token offsets of the blocks
-  int32_t tile_start[kEncMaxBlocks + 1];  // first row tile of each block
+  int32_t tile_start[kEncMaxBlocks + 1];  // first row tile of each block; [n] = all tiles, INT_MAX beyond
 };
 
 constexpr int kFinMaxPrompts = 64;
