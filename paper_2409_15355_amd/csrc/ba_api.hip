@@ -433,49 +433,56 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ap.rope_layout = heads->rope_layout;
   ap.n_splits = 1;
 
-  // short blocks only: the schedule with small workgroups, several to a compute unit
-  int64_t max_len = 0;
-  for (int i = 0; i < n_blocks; ++i) max_len = std::max<int64_t>(max_len, (int64_t)block_offsets[i + 1] - block_offsets[i]);
-  int64_t short_max = ba::kShortMaxLen;
-  if (const char *e = getenv("BA_SHORT_MAX")) short_max = atoll(e);
-  // (its query load assumes at most 8 tokens per 32 rows, and it addresses the rows of a block with
-  // 32-bit element offsets)
+  // Blocks up to kShortMaxLen tokens take the schedule with small workgroups, several to a compute
+  // unit; longer ones the main core.  (The short-block kernel assumes at most 8 tokens per 32 packed
+  // rows, and addresses the rows of a block with 32-bit element offsets.)
   const int64_t widest = std::max(std::max(q->stride_tok, o_out->stride_tok),
                                   (int64_t)G * std::max(q->stride_head, o_out->stride_head));
-  const bool short_blocks = max_len <= short_max && G >= 4 && (max_len + 1) * widest < 0x40000000;
-  const int tile_rows = short_blocks ? ba::kShortTileRows : ba::kTileRows;
+  const int64_t short_max =
+      (G >= 4 && ((int64_t)ba::kShortMaxLen + 1) * widest < 0x40000000) ? ba::kShortMaxLen : -1;
 
   for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
     const int n = std::min(ba::kEncMaxBlocks, n_blocks - b0);
-    ba::EncodeMeta meta;
-    memset(&meta, 0, sizeof(meta));
-    meta.n = n;
-    int64_t tiles = 0;
+    // one table of blocks per schedule: a block has row tiles in the table of its own schedule only,
+    // and the kernels never land on a block without tiles
+    ba::EncodeMeta meta[2];  // [0] main core, [1] short blocks
+    int64_t tiles[2] = {0, 0};
+    memset(meta, 0, sizeof(meta));
     for (int i = 0; i < n; ++i) {
       const int64_t len = (int64_t)block_offsets[b0 + i + 1] - block_offsets[b0 + i];
       if (len * G > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "block %d: too many packed rows", b0 + i);
-      meta.offs[i] = block_offsets[b0 + i];
-      meta.tile_start[i] = (int32_t)tiles;
-      tiles += (len * G + tile_rows - 1) / tile_rows;
-      if (tiles > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
+      const int which = len <= short_max ? 1 : 0;
+      for (int m = 0; m < 2; ++m) {
+        meta[m].offs[i] = block_offsets[b0 + i];
+        meta[m].tile_start[i] = (int32_t)tiles[m];
+      }
+      const int tile_rows = which ? ba::kShortTileRows : ba::kTileRows;
+      tiles[which] += (len * G + tile_rows - 1) / tile_rows;
+      if (tiles[which] > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
     }
-    meta.offs[n] = block_offsets[b0 + n];
-    meta.tile_start[n] = (int32_t)tiles;
-    for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta.tile_start[i] = 0x7fffffff;
-    ap.total_tiles = (int32_t)tiles;
-    if (tiles == 0) continue;
-    ap.tiles_div = ba::make_fast_div((uint32_t)tiles);
+    for (int m = 0; m < 2; ++m) {
+      meta[m].n = n;
+      meta[m].offs[n] = block_offsets[b0 + n];
+      meta[m].tile_start[n] = (int32_t)tiles[m];
+      for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta[m].tile_start[i] = 0x7fffffff;
+    }
+    if (tiles[0] + tiles[1] == 0) continue;
     if (rope_mode == BA_ROPE_APPLY) {  // local positions: every block starts at 0
-      if ((rc = run_rope_prepass(heads, rt, q, nullptr, k, &k_use, n, meta.offs, nullptr, stream, nullptr, nullptr,
+      if ((rc = run_rope_prepass(heads, rt, q, nullptr, k, &k_use, n, meta[0].offs, nullptr, stream, nullptr, nullptr,
                                  nullptr, 0, q_table)))
         return rc;
     }
-    hipError_t e;
-    {
-      ProfileScope ps(BA_PROFILE_ATTENTION, stream);
-      e = short_blocks ? ba::launch_attn_encode_short(ap, meta, stream) : ba::launch_attn_encode(ap, meta, stream);
+    for (int m = 1; m >= 0; --m) {
+      if (tiles[m] == 0) continue;
+      ap.total_tiles = (int32_t)tiles[m];
+      ap.tiles_div = ba::make_fast_div((uint32_t)tiles[m]);
+      hipError_t e;
+      {
+        ProfileScope ps(BA_PROFILE_ATTENTION, stream);
+        e = m ? ba::launch_attn_encode_short(ap, meta[m], stream) : ba::launch_attn_encode(ap, meta[m], stream);
+      }
+      if (e != hipSuccess) return device_fail(e, "encode attention launch");
     }
-    if (e != hipSuccess) return device_fail(e, "encode attention launch");
   }
   return BA_OK;
 }

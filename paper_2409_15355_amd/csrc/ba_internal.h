@@ -107,9 +107,9 @@ inline FastDiv make_fast_div(uint32_t d) {
 constexpr int kTileRows = 256;  // packed (token, head-in-group) query rows per workgroup
 constexpr int kTileKeys = 64;   // keys per K/V tile
 constexpr int kShortTileRows = 128;  // packed query rows per workgroup of the short-block schedule
-// Per-block encoding takes the short-block schedule when no block of the call is longer than this
-// (beyond it the deep pipeline of the main core has filled and wins).
-constexpr int kShortMaxLen = 512;
+// Per-block encoding sends blocks up to this length through the short-block schedule (measured
+// crossover: beyond about 6,000 to 8,000 tokens the deep pipeline of the main core wins).
+constexpr int kShortMaxLen = 6144;
 
 struct AttnParams {
   const uint16_t *q;

@@ -144,10 +144,12 @@ ENC_CASES = [
     ("ragged-mha-d64", 2, 2, 64, 10000.0, [300, 5, 0, 0, 511, 256]),
     ("gqa8-d128", 8, 1, 128, 10000.0, [33, 100]),
     ("gqa3-odd-group", 6, 2, 64, 10000.0, [90, 171]),
-    # a block beyond the short-block schedule's limit sends the whole call through the main core
-    ("long-and-short-gqa4", 8, 2, 128, 500000.0, [700, 1, 63, 130]),
+    # groups of fewer than four query heads take the main core whatever the block length
     ("long-mha-d64", 2, 2, 64, 10000.0, [530, 300, 5]),
-    ("at-the-limit-gqa2", 4, 2, 128, 10000.0, [512, 31]),
+    ("gqa2", 4, 2, 128, 10000.0, [512, 31]),
+    # medium blocks: many key tiles per work item of the short-block schedule
+    ("medium-gqa4", 8, 2, 128, 500000.0, [700, 1, 63, 130]),
+    ("medium-gqa8-d64", 8, 1, 64, 10000.0, [1000, 333]),
 ]
 
 
@@ -504,6 +506,29 @@ def test_config_5_single_block_full_attention_sampled(ba):
     f = oracle.bf16_bits_to_f64
     ref, _ = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, oracle.theta(w.rope_base, d), rows=rows, want_k_local=False)
     assert_attention_close(host_f64(o)[rows], ref, "cfg5 single block (sampled rows)")
+
+
+def test_encode_long_and_short_blocks_in_one_call_sampled(ba):
+    """One call whose blocks fall on both sides of the length at which per-block encoding changes
+    schedule (one launch of each kernel), the long ones right at that length and well beyond it;
+    sampled rows of every block against the oracle, and the cached keys of all rows."""
+    hq, hkv, d, base = 4, 1, 128, 500000.0
+    lens = [6144, 100, 6145, 3, 9000, 257]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(offs[-1])
+    qb, kb, vb = gen_qkv(230, T, hq, hkv, d)
+    heads = ba.Heads(hq, hkv, d, base)
+    o, k_local = gpu_encode(ba, heads, qb, kb, vb, offs)
+    rng = np.random.default_rng(7)
+    rows = []
+    for b, L in enumerate(lens):
+        inside = sorted(set([0, 1, min(31, L - 1), min(32, L - 1), L // 2, L - 1] + rng.integers(0, L, 3).tolist()))
+        rows += [int(offs[b]) + r for r in inside]
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(base, d)
+    ref, ref_k = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, th, rows=rows)
+    assert_attention_close(host_f64(o)[rows], ref, "long and short blocks (sampled rows)")
+    assert_reencode_bf16(host_bits(k_local), ref_k, 0, "long and short blocks k_local")
 
 
 # --------------------------------------------------------------------------------------------
