@@ -127,14 +127,24 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 constexpr int kNumCU = 256;  // MI355X
 
-// Number of KV splits for the final-block launch: enough workgroups to cover the chip,
-// never fewer than four key tiles per split.
+// Number of KV splits for the final-block launch.  One workgroup runs per compute unit, so a launch
+// takes ceil(workgroups / CUs) rounds, each as long as one workgroup: a fixed part (prologue, output,
+// worth about four key tiles) plus its share of the key tiles; every split also adds a little to
+// the merge.  Take the cheapest count, never fewer than four key tiles per split.
 int choose_splits(int64_t base_wgs, int max_tiles_per_problem) {
   if (base_wgs <= 0) return 1;
-  int64_t s = (kNumCU + base_wgs - 1) / base_wgs;
-  s = std::min<int64_t>(s, std::max(1, max_tiles_per_problem / 4));
-  s = std::min<int64_t>(s, 32);
-  return (int)std::max<int64_t>(s, 1);
+  const int s_max = (int)std::min<int64_t>(32, std::max(1, max_tiles_per_problem / 4));
+  int best = 1;
+  double best_cost = 0;
+  for (int s = 1; s <= s_max; ++s) {
+    const double rounds = (double)((base_wgs * s + kNumCU - 1) / kNumCU);
+    const double cost = rounds * (4.0 + (max_tiles_per_problem + s - 1) / s) + 0.5 * s;
+    if (s == 1 || cost < best_cost) {
+      best = s;
+      best_cost = cost;
+    }
+  }
+  return best;
 }
 
 struct FinalPlan {
