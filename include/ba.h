@@ -209,6 +209,34 @@ size_t ba_final_block_attention_cached_workspace_bytes(const ba_heads *heads, in
                                                        const int32_t *blk_len,
                                                        int32_t have_k_f_rot_out);
 
+/*
+ * Whole prompts in one call -- the attention mask of Section 2.4 (what a block fine-tune step
+ * runs forward): the lower-triangular mask, cut so that a token sees its own block only, except
+ * the tokens of a prompt's LAST block, which see every earlier token of the prompt.
+ *
+ * Prompt n owns blocks [cu_blk[n], cu_blk[n+1]) (cu_blk[0] = 0, at least one block each; the last
+ * one is the block that sees the others); block b is tokens [block_offsets[b], block_offsets[b+1])
+ * of q / k / v / o_out ([T, heads, D], bf16; block_offsets[0] = 0, non-decreasing, prompts packed
+ * back to back).  With BA_ROPE_APPLY q and k are rotated inside at the token's position in its
+ * prompt (first token of a prompt at 0) -- by Eq. 1's relative-position property the same scores
+ * as local positions plus re-encoding -- and the rotated keys go to k_rot_out if non-null; with
+ * BA_ROPE_NONE q and k are used as given.  lse_out (device, nullable): [T][n_q_heads] floats, the
+ * natural-log sum of exp(scale * <q^, k^>) over each row's visible keys, as a backward pass needs.
+ * Built for training-sized prompts: every row tile walks its key range alone (no KV splits), so a
+ * short last block behind tens of thousands of context tokens is better served by
+ * ba_final_block_attention.  Needs n_q_heads / n_kv_heads >= 4 (BA_ERR_UNSUPPORTED otherwise).
+ * ws: 256-byte aligned, at least ba_block_attention_prompts_workspace_bytes() bytes.
+ */
+int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
+                                   const ba_tensor *v, const ba_tensor *o_out,
+                                   const ba_tensor *k_rot_out, float *lse_out, int32_t n_prompts,
+                                   const int32_t *cu_blk, const int32_t *block_offsets,
+                                   int32_t rope_mode, void *ws, size_t ws_bytes, void *stream);
+size_t ba_block_attention_prompts_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
+                                                  const int32_t *cu_blk,
+                                                  const int32_t *block_offsets, int32_t rope_mode,
+                                                  int32_t have_k_rot_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,8 @@ EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin"
            "ba_encode_blocks",
            "ba_encode_blocks_workspace_bytes", "ba_reencode_positions",
            "ba_final_block_attention", "ba_final_block_attention_workspace_bytes",
-           "ba_final_block_attention_cached", "ba_final_block_attention_cached_workspace_bytes"]
+           "ba_final_block_attention_cached", "ba_final_block_attention_cached_workspace_bytes",
+           "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes"]
 
 
 class BaTensor(ctypes.Structure):
@@ -95,6 +96,13 @@ def load():
     lib.ba_final_block_attention_cached_workspace_bytes.restype = ctypes.c_size_t
     lib.ba_final_block_attention_cached_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, _I32P,
                                                                     ctypes.c_int32]
+    lib.ba_block_attention_prompts.restype = ctypes.c_int32
+    lib.ba_block_attention_prompts.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, ctypes.c_void_p, ctypes.c_int32, _I32P,
+                                               _I32P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t,
+                                               ctypes.c_void_p]
+    lib.ba_block_attention_prompts_workspace_bytes.restype = ctypes.c_size_t
+    lib.ba_block_attention_prompts_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, ctypes.c_int32,
+                                                               ctypes.c_int32]
     _lib = lib
     return lib
 
@@ -245,3 +253,22 @@ def ba_final_block_attention_cached(heads: Heads, q_f, k_cache, v_cache, k_f, v_
                                                   _ref(tvf), _ref(to), _ref(tkr), len(cq) - 1, _ip(cq), _ip(cb),
                                                   _ip(bo), _ip(bl), _ip(op), _ip(npos), _ip(qp), wp, wb,
                                                   _stream_handle(stream)))
+
+
+def ba_block_attention_prompts_workspace_bytes(heads: Heads, cu_blk, block_offsets, rope_mode: int = ROPE_APPLY,
+                                               have_k_rot_out: bool = False) -> int:
+    cb, offs = _ints(cu_blk), _ints(block_offsets)
+    return int(load().ba_block_attention_prompts_workspace_bytes(ctypes.byref(heads.c), len(cb) - 1, _ip(cb),
+                                                                 _ip(offs), rope_mode, int(have_k_rot_out)))
+
+
+def ba_block_attention_prompts(heads: Heads, q, k, v, o_out, k_rot_out, lse_out, cu_blk, block_offsets,
+                               rope_mode: int = ROPE_APPLY, ws=None, stream=None) -> None:
+    """lse_out: float32 tensor [T, n_q_heads] (contiguous) or None."""
+    cb, offs = _ints(cu_blk), _ints(block_offsets)
+    wp, wb = _ws(ws)
+    tq, tk, tv, to, tkr = _tensor(q), _tensor(k), _tensor(v), _tensor(o_out), _tensor(k_rot_out)
+    lse_p = None if lse_out is None else ctypes.c_void_p(lse_out.data_ptr())
+    _check(load().ba_block_attention_prompts(ctypes.byref(heads.c), _ref(tq), _ref(tk), _ref(tv), _ref(to), _ref(tkr),
+                                             lse_p, len(cb) - 1, _ip(cb), _ip(offs), rope_mode, wp, wb,
+                                             _stream_handle(stream)))

@@ -15,6 +15,8 @@
 //   - Arithmetic, operand layouts, softmax (reference set by the first tile, moved only to avoid
 //     overflow) and rounding are those of the main core, so both give the same numbers for the
 //     same rows.
+#include <type_traits>
+
 #include "ba_device.h"
 #include "ba_lds.h"
 
@@ -59,9 +61,14 @@ __device__ long long g_swg[16384][16];
 #define BA_SNOTE(m, val) do { } while (0)
 #endif
 
-template <int D>
-__global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p, EncodeMeta meta) {
+// Meta = EncodeMeta: a block sees its own tokens only (Section 2.1).  Meta = PromptMeta: a block's keys
+// start wherever the table says -- at the block itself for a passage, at the first token of the
+// prompt for its last block (Section 2.4: the lower-triangular mask with only the last block seeing
+// the others); keys and queries then carry positions inside the prompt.
+template <int D, typename Meta>
+__global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p, Meta meta) {
   using G = SGeo<D>;
+  constexpr bool kPrompt = std::is_same<Meta, PromptMeta>::value;
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
   lds_char *smem = (lds_char *)smem_generic;
   // LDS map: buffer b = bytes [2 b TB, 2 (b + 1) TB): its K tile, then its V tile
@@ -107,6 +114,10 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   }
   const int q_tok0 = meta.offs[b];
   const int lq = meta.offs[b + 1] - q_tok0;
+  int k_tok0 = q_tok0;  // first key the block sees
+  if constexpr (kPrompt) k_tok0 = meta.kstart[b];
+  const int dq = q_tok0 - k_tok0;  // the block's first token, counted in keys
+  const int lk = dq + lq;          // keys up to the block's end
   const int jt = rowtile - meta.tile_start[b];
 
   BA_SMARK(1);
@@ -120,14 +131,17 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
 
   // key tiles of the workgroup (up to its last row's token) and of this wave
   const int last_row = min(n_rows, row0 + kShortTileRows) - 1;
-  const int n_t = (int)fast_div((uint32_t)last_row, p.group_div) / kSKeys + 1;
+  const int n_t = (dq + (int)fast_div((uint32_t)last_row, p.group_div)) / kSKeys + 1;
   const int wave_row0 = row0 + wave * 32;
   const int wave_last_row = min(n_rows, wave_row0 + 32) - 1;
-  const int wave_n_t = wave_last_row >= wave_row0 ? (int)fast_div((uint32_t)wave_last_row, p.group_div) / kSKeys + 1 : 0;
+  const int wave_n_t =
+      wave_last_row >= wave_row0 ? (dq + (int)fast_div((uint32_t)wave_last_row, p.group_div)) / kSKeys + 1 : 0;
   const int first_tok_wave = (int)fast_div((uint32_t)wave_row0, p.group_div);
+  const int first_key_wave = dq + first_tok_wave;  // the key that is the wave's first token
 
   const int my_row = wave_row0 + col;
   const int my_tok = (int)fast_div((uint32_t)my_row, p.group_div);
+  const int my_key = dq + my_tok;  // the key that is this lane's token: the last one it sees
 
   // ---- Q rows (B operand of S^T = K Q^T) and, if they are to be rotated, the rows of the pre-pass's
   //      table of scale * log2(e) * (cos, sin) for this wave's tokens: requested first and all at
@@ -223,8 +237,8 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   //      [16 i, 16 i + 16); the swizzle is applied on the global side.  Rows at or beyond a tile's
   //      valid count re-read its last valid row: their scores are masked, and a finite duplicate
   //      keeps 0 * v equal to 0 ------------------------------------------------------------------
-  const char *k_base = (const char *)(p.kf + (int64_t)q_tok0 * p.kf_st + (int64_t)kvh * p.kf_sh);
-  const char *v_base = (const char *)(p.vf + (int64_t)q_tok0 * p.vf_st + (int64_t)kvh * p.vf_sh);
+  const char *k_base = (const char *)(p.kf + (int64_t)k_tok0 * p.kf_st + (int64_t)kvh * p.kf_sh);
+  const char *v_base = (const char *)(p.vf + (int64_t)k_tok0 * p.vf_st + (int64_t)kvh * p.vf_sh);
   const uint32_t k_rb = (uint32_t)p.kf_st * 2u, v_rb = (uint32_t)p.vf_st * 2u;  // row strides, bytes
   int c_row[G::IPW];
   uint32_t c_kchunk[G::IPW], c_vchunk[G::IPW];
@@ -237,7 +251,7 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   }
   const uint32_t lds_copy = (uint32_t)(uintptr_t)smem + wave * G::IPW * 1024;
   auto issue_copy = [&](int t, int buf) __attribute__((always_inline)) {
-    const int valid = min(kSKeys, lq - t * kSKeys);
+    const int valid = min(kSKeys, lk - t * kSKeys);
     const char *kp = k_base + (uint64_t)(uint32_t)(t * kSKeys) * (uint64_t)k_rb;
     const char *vp = v_base + (uint64_t)(uint32_t)(t * kSKeys) * (uint64_t)v_rb;
 #pragma unroll
@@ -400,9 +414,9 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
       }
       // mask (diagonal and ragged tiles only); all branches are wave-uniform
       const int key0 = i * kSKeys;
-      const int valid = min(kSKeys, lq - key0);
-      if (key0 + kSKeys - 1 > first_tok_wave || valid < kSKeys) {
-        const int lim = min(my_tok - key0 + 1, valid);  // visible keys in this tile
+      const int valid = min(kSKeys, lk - key0);
+      if (key0 + kSKeys - 1 > first_key_wave || valid < kSKeys) {
+        const int lim = min(my_key - key0 + 1, valid);  // visible keys in this tile
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = (v >> 2) * 8 + hf * 4 + (v & 3);
@@ -500,16 +514,24 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
         *reinterpret_cast<u32x4_t *>(obase + (off * 2u + (uint32_t)(ln % G::CPR) * 16u)) = w[u];
     });
   }
+  // the row's log-sum-exp of its scaled scores (natural logarithm), for a backward pass
+  if (p.lse != nullptr && ehf == 0 && wave_row0 + ecol < n_rows) {
+    const int r = wave_row0 + ecol;
+    const int tok = (int)fast_div((uint32_t)r, p.group_div);
+    p.lse[(int64_t)(q_tok0 + tok) * p.n_q_heads + kvh * Gq + (r - tok * Gq)] =
+        (mb + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;  // (v_log_f32 is the base-2 logarithm)
+  }
   BA_SMARK(6);
 }
 
-template <int D>
-hipError_t launch_short_t(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream) {
+template <int D, typename Meta>
+hipError_t launch_short_t(const AttnParams &p, const Meta &meta, hipStream_t stream) {
   const int64_t n_wg = (int64_t)p.total_tiles * p.n_kv_heads;
   if (n_wg == 0) return hipSuccess;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
   static_assert(SGeo<D>::LDS <= 64 * 1024, "fits the default dynamic LDS limit");
-  hipLaunchKernelGGL((encode_short_kernel<D>), dim3((unsigned)n_wg), dim3(kSThreads), SGeo<D>::LDS, stream, p, meta);
+  hipLaunchKernelGGL((encode_short_kernel<D, Meta>), dim3((unsigned)n_wg), dim3(kSThreads), SGeo<D>::LDS, stream, p,
+                     meta);
   return hipGetLastError();
 }
 
@@ -523,8 +545,15 @@ extern "C" int ba_debug_read_short(long long *host_out) {
 
 hipError_t launch_attn_encode_short(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream) {
   if (p.n_splits != 1) return hipErrorInvalidValue;
-  if (p.head_dim == 128) return launch_short_t<128>(p, meta, stream);
-  if (p.head_dim == 64) return launch_short_t<64>(p, meta, stream);
+  if (p.head_dim == 128) return launch_short_t<128, EncodeMeta>(p, meta, stream);
+  if (p.head_dim == 64) return launch_short_t<64, EncodeMeta>(p, meta, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_prompt_short(const AttnParams &p, const PromptMeta &meta, hipStream_t stream) {
+  if (p.n_splits != 1) return hipErrorInvalidValue;
+  if (p.head_dim == 128) return launch_short_t<128, PromptMeta>(p, meta, stream);
+  if (p.head_dim == 64) return launch_short_t<64, PromptMeta>(p, meta, stream);
   return hipErrorInvalidValue;
 }
 

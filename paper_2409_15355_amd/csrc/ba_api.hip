@@ -498,6 +498,156 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
 }
 
 // ------------------------------------------------------------------------------------------
+size_t ba_block_attention_prompts_workspace_bytes(const ba_heads *heads, int32_t n_prompts, const int32_t *cu_blk,
+                                                  const int32_t *block_offsets, int32_t rope_mode,
+                                                  int32_t have_k_rot_out) {
+  if (!heads || !cu_blk || !block_offsets || n_prompts < 0) return 0;
+  if (rope_mode != BA_ROPE_APPLY) return 0;
+  const size_t T = (size_t)block_offsets[cu_blk[n_prompts]];
+  const size_t k_bytes = have_k_rot_out ? 0 : align256(T * heads->n_kv_heads * heads->head_dim * 2);
+  return k_bytes + align256(T * heads->head_dim * 4);  // rotated K; scale * (cos, sin) per token and pair
+}
+
+int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k, const ba_tensor *v,
+                                   const ba_tensor *o_out, const ba_tensor *k_rot_out, float *lse_out,
+                                   int32_t n_prompts, const int32_t *cu_blk, const int32_t *block_offsets,
+                                   int32_t rope_mode, void *ws, size_t ws_bytes, void *stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t rc;
+  if ((rc = check_heads(heads, true))) return rc;
+  if (n_prompts < 0 || !cu_blk) return fail(BA_ERR_INVALID_ARG, "cu_blk: null or negative prompt count");
+  if (cu_blk[0] != 0) return fail(BA_ERR_INVALID_ARG, "cu_blk[0] must be 0");
+  for (int n = 0; n < n_prompts; ++n)
+    if (cu_blk[n + 1] <= cu_blk[n]) return fail(BA_ERR_INVALID_ARG, "prompt %d: at least one block needed", n);
+  const int n_blocks = cu_blk[n_prompts];
+  if ((rc = check_offsets(n_blocks, block_offsets))) return rc;
+  const int D = heads->head_dim;
+  if ((rc = check_tensor(q, "q", false, D, heads->n_q_heads))) return rc;
+  if ((rc = check_tensor(k, "k", false, D, heads->n_kv_heads))) return rc;
+  if ((rc = check_tensor(v, "v", false, D, heads->n_kv_heads))) return rc;
+  if ((rc = check_tensor(o_out, "o_out", false, D, heads->n_q_heads))) return rc;
+  if (rope_mode != BA_ROPE_NONE && rope_mode != BA_ROPE_APPLY)
+    return fail(BA_ERR_INVALID_ARG, "rope_mode %d unknown", rope_mode);
+  if (k_rot_out) {
+    if (rope_mode != BA_ROPE_APPLY) return fail(BA_ERR_INVALID_ARG, "k_rot_out needs rope_mode BA_ROPE_APPLY");
+    if ((rc = check_tensor(k_rot_out, "k_rot_out", false, D, heads->n_kv_heads))) return rc;
+  }
+  if (lse_out && ((uintptr_t)lse_out & 3)) return fail(BA_ERR_ALIGNMENT, "lse_out must be 4-byte aligned");
+  const int64_t T = block_offsets[n_blocks];
+  const int G = heads->n_q_heads / heads->n_kv_heads;
+  if (T == 0) return BA_OK;
+  // what the kernel of this call is built for (see its header): groups of at least four query heads
+  // per KV head, and blocks whose row offsets fit 32 bits
+  int64_t max_len = 0;
+  for (int b = 0; b < n_blocks; ++b) max_len = std::max<int64_t>(max_len, (int64_t)block_offsets[b + 1] - block_offsets[b]);
+  const int64_t widest = std::max(std::max(q->stride_tok, o_out->stride_tok),
+                                  (int64_t)G * std::max(q->stride_head, o_out->stride_head));
+  if (G < 4) return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention needs at least 4 query heads per KV head");
+  if ((max_len + 1) * widest >= 0x40000000 || max_len * G > 0x3fffffff)
+    return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention: a block of %lld tokens at these strides is too long",
+                (long long)max_len);
+
+  ba::RopeTable rt;
+  build_rope_table(heads, &rt);
+  ba_tensor k_use = *k;
+  float *q_table = nullptr;
+  if (rope_mode == BA_ROPE_APPLY) {
+    const size_t need =
+        ba_block_attention_prompts_workspace_bytes(heads, n_prompts, cu_blk, block_offsets, rope_mode, k_rot_out != nullptr);
+    if (!ws || ws_bytes < need || ((uintptr_t)ws & 255))
+      return fail(BA_ERR_WORKSPACE, "whole prompts: 256-byte aligned workspace of %zu bytes needed, %zu given", need,
+                  ws_bytes);
+    char *wsp = (char *)ws;
+    if (k_rot_out) {
+      k_use = *k_rot_out;
+    } else {
+      k_use.ptr = wsp;
+      k_use.stride_head = D;
+      k_use.stride_tok = (int64_t)heads->n_kv_heads * D;
+      k_use.dtype = BA_DTYPE_BF16;
+      wsp += align256((size_t)T * heads->n_kv_heads * D * 2);
+    }
+    q_table = (float *)wsp;
+    // positions count from each prompt's first token: one segment per prompt
+    std::vector<int32_t> starts(n_prompts + 1);
+    for (int n = 0; n <= n_prompts; ++n) starts[n] = block_offsets[cu_blk[n]];
+    for (int n0 = 0; n0 < n_prompts; n0 += ba::kRopeMaxSegs) {
+      const int n = std::min(ba::kRopeMaxSegs, n_prompts - n0);
+      if ((rc = run_rope_prepass(heads, rt, q, nullptr, k, &k_use, n, starts.data() + n0, nullptr, stream, nullptr,
+                                 nullptr, nullptr, 0, q_table)))
+        return rc;
+    }
+  }
+
+  ba::AttnParams ap;
+  memset(&ap, 0, sizeof(ap));
+  ap.q = (const uint16_t *)q->ptr;
+  ap.q_st = q->stride_tok;
+  ap.q_sh = q->stride_head;
+  ap.q_table = q_table;
+  ap.kf = (const uint16_t *)k_use.ptr;
+  ap.kf_st = k_use.stride_tok;
+  ap.kf_sh = k_use.stride_head;
+  ap.vf = (const uint16_t *)v->ptr;
+  ap.vf_st = v->stride_tok;
+  ap.vf_sh = v->stride_head;
+  ap.kc = ap.kf;
+  ap.kc_st = ap.kf_st;
+  ap.kc_sh = ap.kf_sh;
+  ap.vc = ap.vf;
+  ap.vc_st = ap.vf_st;
+  ap.vc_sh = ap.vf_sh;
+  ap.o = (uint16_t *)o_out->ptr;
+  ap.o_st = o_out->stride_tok;
+  ap.o_sh = o_out->stride_head;
+  ap.lse = lse_out;
+  ap.n_q_heads = heads->n_q_heads;
+  ap.n_kv_heads = heads->n_kv_heads;
+  ap.group = G;
+  ap.group_div = ba::make_fast_div((uint32_t)G);
+  ap.head_dim = D;
+  ap.scale_log2e = scale_log2e(heads);
+  ap.q_ready = 0;
+  ap.rope_layout = heads->rope_layout;
+  ap.n_splits = 1;
+
+  // first key of every block: its own first token, or for a prompt's last block the prompt's
+  std::vector<int32_t> kstart(n_blocks);
+  for (int n = 0; n < n_prompts; ++n)
+    for (int b = cu_blk[n]; b < cu_blk[n + 1]; ++b)
+      kstart[b] = b == cu_blk[n + 1] - 1 ? block_offsets[cu_blk[n]] : block_offsets[b];
+
+  for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
+    const int n = std::min(ba::kEncMaxBlocks, n_blocks - b0);
+    ba::PromptMeta meta;
+    memset(&meta, 0, sizeof(meta));
+    meta.n = n;
+    int64_t tiles = 0;
+    for (int i = 0; i < n; ++i) {
+      const int64_t len = (int64_t)block_offsets[b0 + i + 1] - block_offsets[b0 + i];
+      meta.offs[i] = block_offsets[b0 + i];
+      meta.kstart[i] = kstart[b0 + i];
+      meta.tile_start[i] = (int32_t)tiles;
+      tiles += (len * G + ba::kShortTileRows - 1) / ba::kShortTileRows;
+      if (tiles > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
+    }
+    meta.offs[n] = block_offsets[b0 + n];
+    meta.tile_start[n] = (int32_t)tiles;
+    for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta.tile_start[i] = 0x7fffffff;
+    if (tiles == 0) continue;
+    ap.total_tiles = (int32_t)tiles;
+    ap.tiles_div = ba::make_fast_div((uint32_t)tiles);
+    hipError_t e;
+    {
+      ProfileScope ps(BA_PROFILE_ATTENTION, stream);
+      e = ba::launch_attn_prompt_short(ap, meta, stream);
+    }
+    if (e != hipSuccess) return device_fail(e, "whole-prompt attention launch");
+  }
+  return BA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 int32_t ba_reencode_positions(const ba_heads *heads, const ba_tensor *k_src, const ba_tensor *k_dst,
                               int32_t n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                               int32_t n_blocks, const int32_t *src_tok_off, const int32_t *dst_tok_off,

@@ -138,6 +138,7 @@ struct AttnParams {
   int32_t n_splits;
   int32_t total_tiles;  // row tiles over all problems of this launch
   FastDiv tiles_div;    // division by total_tiles (short-block schedule)
+  float *lse;           // short-block schedule: [tokens][n_q_heads] log-sum-exp of the scaled scores, or null
 };
 
 constexpr int kEncMaxBlocks = 320;
@@ -145,6 +146,14 @@ struct EncodeMeta {
   int32_t n;
   int32_t offs[kEncMaxBlocks + 1];        // token offsets of the blocks
   int32_t tile_start[kEncMaxBlocks + 1];  // first row tile of each block; [n] = all tiles, INT_MAX beyond
+};
+
+// Whole prompts (Section 2.4): like EncodeMeta, plus the first key each block sees.
+struct PromptMeta {
+  int32_t n;
+  int32_t offs[kEncMaxBlocks + 1];
+  int32_t tile_start[kEncMaxBlocks + 1];  // in row tiles of kShortTileRows rows; INT_MAX beyond [n]
+  int32_t kstart[kEncMaxBlocks];          // token offset of the first visible key
 };
 
 constexpr int kFinMaxPrompts = 64;
@@ -175,6 +184,7 @@ using FinalBlocksMetaSmall = FinalBlocksMetaT<kBlkSmallPrompts, kBlkSmallBlocks>
 hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
 // the same for short blocks: meta.tile_start counts row tiles of kShortTileRows rows
 hipError_t launch_attn_encode_short(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
+hipError_t launch_attn_prompt_short(const AttnParams &p, const PromptMeta &meta, hipStream_t stream);
 hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMeta &meta, hipStream_t stream);
 hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMetaSmall &meta, hipStream_t stream);
 hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, hipStream_t stream);

@@ -149,3 +149,30 @@ def test_final_cached_rejects_bad_arguments_and_sizes_workspace(lib):
     z = i32([0])
     assert lib.ba_final_block_attention_cached(ctypes.byref(h.c), None, None, None, None, None, None, None, 0, p(z),
                                                p(z), None, None, None, None, None, None, 0, None) == 0
+
+
+def test_whole_prompts_rejects_bad_arguments_and_sizes_workspace(lib):
+    h = ba.Heads(32, 8, 128, 500000.0)
+    t = fake()
+    i32 = lambda x: np.asarray(x, dtype=np.int32)
+    p = lambda x: x.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+    def call(heads, cu_blk, offs, rope=1, ws=None, wsb=0):
+        cb, of = i32(cu_blk), i32(offs)
+        return lib.ba_block_attention_prompts(ctypes.byref(heads.c), ctypes.byref(t), ctypes.byref(t), ctypes.byref(t),
+                                              ctypes.byref(t), None, None, len(cb) - 1, p(cb), p(of), rope, ws, wsb, None)
+
+    assert call(h, [1, 2], [0, 5, 9]) == -1                 # cu_blk[0] != 0
+    assert call(h, [0, 2, 2], [0, 5, 9]) == -1              # a prompt without a block
+    assert call(h, [0, 2], [0, 9, 5]) == -1                 # offsets decrease
+    assert call(h, [0, 2], [0, 5, 9], rope=7) == -1         # unknown rope mode
+    assert call(ba.Heads(4, 4, 64), [0, 2], [0, 5, 9]) == -2   # fewer than four query heads per KV head
+    assert call(h, [0, 2], [0, 5, 9]) == -4                 # workspace missing
+    assert b"workspace" in lib.ba_last_error()
+    # rotated keys + the table of factors (one (cos, sin) pair per token and dimension pair)
+    assert ba.ba_block_attention_prompts_workspace_bytes(h, [0, 2], [0, 100, 164]) == \
+        164 * 8 * 128 * 2 + (164 * 128 * 4 + 255) // 256 * 256
+    assert ba.ba_block_attention_prompts_workspace_bytes(h, [0, 2], [0, 100, 164], have_k_rot_out=True) == \
+        (164 * 128 * 4 + 255) // 256 * 256
+    assert ba.ba_block_attention_prompts_workspace_bytes(h, [0, 2], [0, 100, 164], ba.ROPE_NONE) == 0
+    assert call(h, [0, 2], [0, 0, 0]) == 0                  # no tokens: legal no-op

@@ -712,3 +712,139 @@ def test_determinism_bitwise(ba):
     a = host_bits(gpu_final(ba, heads, *args))
     for _ in range(3):
         assert np.array_equal(a, host_bits(gpu_final(ba, heads, *args)))
+
+
+# --------------------------------------------------------------------------------------------
+# whole prompts in one call (the mask of Section 2.4)
+# --------------------------------------------------------------------------------------------
+def gpu_prompts(ba, heads, qb, kb, vb, cu_blk, offs, rope_mode=1, want_k_rot=True):
+    torch = torch_mod()
+    T, hq, d = qb.shape
+    q, k, v = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb)
+    o = torch.full_like(q, float("nan"))
+    k_rot = torch.full_like(k, float("nan")) if (want_k_rot and rope_mode == 1) else None
+    lse = torch.full((T, hq), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(1, ba.ba_block_attention_prompts_workspace_bytes(heads, cu_blk, offs, rope_mode, k_rot is not None)),
+                     dtype=torch.uint8, device="cuda")
+    ba.ba_block_attention_prompts(heads, q, k, v, o, k_rot, lse, cu_blk, offs, rope_mode, ws)
+    torch.cuda.synchronize()
+    return o, k_rot, lse
+
+
+def oracle_prompt_lse(q, k, offs, th, layout, scale):
+    """log-sum-exp of the scaled scores over each row's visible keys, from the explicit mask."""
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    pos = np.arange(T)
+    qr, kr = oracle.rope_dense(q, pos, th, layout), oracle.rope_dense(k, pos, th, layout)
+    M = oracle.block_mask(offs)
+    out = np.empty((T, hq))
+    for h in range(hq):
+        S = scale * (qr[:, h, :] @ kr[:, h // (hq // hkv), :].T)
+        S = np.where(M, S, -np.inf)
+        m = S.max(axis=1)
+        out[:, h] = m + np.log(np.exp(S - m[:, None]).sum(axis=1))
+    return out
+
+
+PROMPT_CASES = [
+    # (name, Hq, Hkv, D, base, per-prompt block lengths; the last block of a prompt sees the others)
+    ("two-prompts-gqa4", 8, 2, 128, 500000.0, [[40, 33, 1, 70, 50], [5, 64, 31]]),
+    ("one-block-prompts", 4, 1, 64, 10000.0, [[90], [1], [33]]),
+    ("empty-blocks-gqa8", 8, 1, 64, 10000.0, [[0, 65, 0, 20], [32, 0, 96]]),
+    ("ragged-gqa4-d128", 4, 1, 128, 10000.0, [[129, 64, 63, 130], [200, 57]]),
+]
+
+
+@pytest.mark.parametrize("case", PROMPT_CASES, ids=[c[0] for c in PROMPT_CASES])
+@pytest.mark.parametrize("layout", [0, 1])
+def test_whole_prompts_match_the_masked_attention_definition(ba, case, layout):
+    """ba_block_attention_prompts against dense softmax under the explicit Block-attention mask
+    (positions inside the prompt), prompt by prompt; the row log-sum-exps and the rotated keys too."""
+    name, hq, hkv, d, base, prompts = case
+    lens = [l for p in prompts for l in p]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cu_blk = np.concatenate([[0], np.cumsum([len(p) for p in prompts])]).astype(np.int32)
+    T = int(offs[-1])
+    qb, kb, vb = gen_qkv(300 + len(name) + layout, T, hq, hkv, d)
+    heads = ba.Heads(hq, hkv, d, base, rope_layout=layout)
+    o, k_rot, lse = gpu_prompts(ba, heads, qb, kb, vb, cu_blk, offs)
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(base, d)
+    og, lg, kg = host_f64(o), lse.cpu().numpy().astype(np.float64), host_bits(k_rot)
+    for n in range(len(prompts)):
+        t0, t1 = int(offs[cu_blk[n]]), int(offs[cu_blk[n + 1]])
+        if t1 == t0:
+            continue
+        po = offs[cu_blk[n]:cu_blk[n + 1] + 1] - t0
+        q, k, v = f(qb[t0:t1]), f(kb[t0:t1]), f(vb[t0:t1])
+        ref = oracle.masked_attention_bruteforce(q, k, v, po, th, layout=layout)
+        assert_attention_close(og[t0:t1], ref, f"{name} prompt {n}")
+        ref_lse = oracle_prompt_lse(q, k, po, th, layout, 1.0 / np.sqrt(d))
+        assert np.max(np.abs(lg[t0:t1] - ref_lse)) < 2e-2, name  # bf16 q^ and k^ in the scores
+        ref_k = oracle.rope_dense(k, np.arange(t1 - t0), th, layout)
+        assert_reencode_bf16(kg[t0:t1], ref_k, layout, f"{name} rotated keys, prompt {n}")
+
+
+def test_whole_prompts_agree_with_the_three_step_path(ba):
+    """Passage rows of the one-call path equal ba_encode_blocks' (the same kernel at other
+    positions) and last-block rows equal the re-encode + final-block route, both within the
+    output tolerance; rope_mode NONE on pre-rotated inputs gives the one-call result bit for bit."""
+    torch = torch_mod()
+    hq, hkv, d, base = 8, 2, 128, 500000.0
+    prompts = [[100, 37, 64], [70, 129, 20]]
+    lens = [l for p in prompts for l in p]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cu_blk = np.array([0, 3, 6], dtype=np.int32)
+    T = int(offs[-1])
+    qb, kb, vb = gen_qkv(320, T, hq, hkv, d)
+    heads = ba.Heads(hq, hkv, d, base)
+    o, k_rot, _ = gpu_prompts(ba, heads, qb, kb, vb, cu_blk, offs)
+    o_enc, _ = gpu_encode(ba, heads, qb, kb, vb, offs)
+    og, oe = host_f64(o), host_f64(o_enc)
+    for n in range(2):
+        for b in range(cu_blk[n], cu_blk[n + 1] - 1):  # passages: every block but the prompt's last
+            sl = slice(int(offs[b]), int(offs[b + 1]))
+            assert np.max(np.abs(og[sl] - oe[sl])) <= 2e-2
+    # pre-rotated route: rotate q with the oracle at prompt positions, take the kernel's own rotated keys
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(base, d)
+    pos = np.concatenate([np.arange(int(offs[cu_blk[n + 1]]) - int(offs[cu_blk[n]])) for n in range(2)])
+    q_rot_bits = wl.f32_to_bf16_bits(oracle.rope_dense(f(qb), pos, th, 0).astype(np.float32))
+    o2, _, _ = gpu_prompts(ba, heads, q_rot_bits, host_bits(k_rot), vb, cu_blk, offs, rope_mode=0)
+    assert np.max(np.abs(host_f64(o2) - og)) <= 2e-2
+
+
+def test_whole_prompts_config_3_sampled(ba):
+    """Config 3's eight prompts (20 ragged passages each) with their query blocks appended, in one
+    call; sampled rows against the oracle's per-block encoding (passages) and final-block attention
+    over keys rotated at prompt positions (query blocks)."""
+    w = wl.config3()
+    hq, hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
+    prompts = [list(p.passage_lens) + [p.final_len] for p in w.prompts]
+    lens = [l for p in prompts for l in p]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cu_blk = np.concatenate([[0], np.cumsum([len(p) for p in prompts])]).astype(np.int32)
+    T = int(offs[-1])
+    qb, kb, vb = gen_qkv(wl.tensor_seed(3, 60), T, hq, hkv, d)
+    heads = heads_of(ba, w)
+    o, k_rot, lse = gpu_prompts(ba, heads, qb, kb, vb, cu_blk, offs)
+    og = host_f64(o)
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(w.rope_base, d)
+    rng = np.random.default_rng(11)
+    # passages: the oracle's per-block encoding at local positions (relative positions are what count)
+    rows = sorted(set(offs[:-1].tolist() + (offs[1:] - 1).tolist() + rng.integers(0, T, 150).tolist()))
+    last_blocks = set(int(cu_blk[n + 1]) - 1 for n in range(len(prompts)))
+    blk_of = np.searchsorted(offs, np.arange(T), side="right") - 1
+    prow = [t for t in rows if 0 <= t < T and int(blk_of[t]) not in last_blocks]
+    ref_p, _ = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, th, rows=prow, want_k_local=False)
+    assert_attention_close(og[prow], ref_p, "whole prompts, passage rows")
+    # query blocks: context keys rotated at their position in the prompt
+    for n in (0, 3, 7):
+        t0, tf, t1 = int(offs[cu_blk[n]]), int(offs[cu_blk[n + 1] - 1]), int(offs[cu_blk[n + 1]])
+        k_ctx = oracle.rope_dense(f(kb[t0:tf]), np.arange(tf - t0), th, 0)
+        ref_f = oracle.final_block(f(qb[tf:t1]), k_ctx, f(vb[t0:tf]), f(kb[tf:t1]), f(vb[tf:t1]), [0, t1 - tf],
+                                   [0, tf - t0], th)
+        assert_attention_close(og[tf:t1], ref_f, f"whole prompts, query block of prompt {n}")
+    assert np.isfinite(lse.cpu().numpy()).all()
