@@ -51,7 +51,7 @@ def main() -> int:
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows (config 3/4, single block)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for HBM byte counters")
-    ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3")
+    ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3|prompts|smallblocks|cached")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -301,6 +301,67 @@ def main() -> int:
             byts = 2.0 * T3 * d * (2 * hq + 4 * hkv)  # q, o, k, k_local(w), k_local(r), v
             rows_out["encode_cfg3_ragged"] = {"ms": round(ms_e, 4), "algorithmic_TFLOPs": round(fl / ms_e / 1e9, 1),
                                               "GBps": round(byts / ms_e / 1e6, 1), "tokens": T3}
+            del q, k, v, o, kl, ws_3
+        # whole prompts in one call: config 3's eight prompts with their query blocks appended
+        if args.only in ("", "prompts"):
+            w3 = wl.config3()
+            prompts = [list(pr.passage_lens) + [pr.final_len] for pr in w3.prompts]
+            lens_p = np.array([l for pr in prompts for l in pr], dtype=np.int64)
+            offs_p = np.concatenate([[0], np.cumsum(lens_p)]).astype(np.int32)
+            cu_blk_p = np.concatenate([[0], np.cumsum([len(pr) for pr in prompts])]).astype(np.int32)
+            Tp = int(offs_p[-1])
+            q = randn_bf16(wl.tensor_seed(3, 60), (Tp, hq, d))
+            k = randn_bf16(wl.tensor_seed(3, 61), (Tp, hkv, d))
+            v = randn_bf16(wl.tensor_seed(3, 62), (Tp, hkv, d))
+            o = torch.empty_like(q)
+            kr = torch.empty_like(k)
+            lse = torch.empty((Tp, hq), dtype=torch.float32, device="cuda")
+            hp = ba.Heads(hq, hkv, d, w3.rope_base)
+            ws_p = torch.empty(ba.ba_block_attention_prompts_workspace_bytes(hp, cu_blk_p, offs_p, ba.ROPE_APPLY, True),
+                               dtype=torch.uint8, device="cuda")
+
+            def whole():
+                ba.ba_block_attention_prompts(hp, q, k, v, o, kr, lse, cu_blk_p, offs_p, ba.ROPE_APPLY, ws_p)
+
+            ms_w, _ = timed(whole, 20 if args.only == "" else 200, 3)
+            pairs = 0.0
+            for n, pr in enumerate(prompts):
+                pl = np.array(pr[:-1], dtype=np.int64)
+                ctx, lf = int(pl.sum()), int(pr[-1])
+                pairs += float((pl * (pl + 1) // 2).sum()) + lf * ctx + lf * (lf + 1) // 2
+            byts = 2.0 * Tp * d * (2 * hq + 4 * hkv)
+            rows_out["whole_prompts_cfg3"] = {"ms": round(ms_w, 4), "algorithmic_TFLOPs": round(4.0 * d * hq * pairs / ms_w / 1e9, 1),
+                                              "GBps": round(byts / ms_w / 1e6, 1), "tokens": Tp,
+                                              "note": "8 prompts x (20 ragged passages + query block), one call, mask of Section 2.4"}
+            del q, k, v, o, kr, lse, ws_p
+        # Appendix A's workload: a prompt of many small state blocks read straight from the block cache
+        if args.only in ("", "smallblocks"):
+            rng = np.random.Generator(np.random.Philox(wl.tensor_seed(6, 900)))
+            n_blk, slot = 512, 64
+            lens_s = rng.integers(20, 61, n_blk).astype(np.int32)
+            offs_s = (np.arange(n_blk) * slot).astype(np.int32)
+            cap, lq_s = n_blk * slot, 64
+            kc = randn_bf16(wl.tensor_seed(6, 0), (cap, hkv, d))
+            vc = randn_bf16(wl.tensor_seed(6, 1), (cap, hkv, d))
+            qf = randn_bf16(wl.tensor_seed(6, 2), (lq_s, hq, d))
+            kf = randn_bf16(wl.tensor_seed(6, 3), (lq_s, hkv, d))
+            vf = randn_bf16(wl.tensor_seed(6, 4), (lq_s, hkv, d))
+            o = torch.empty_like(qf)
+            hs = ba.Heads(hq, hkv, d, 500000.0)
+            cu_q_s, cu_blk_s = np.array([0, lq_s], dtype=np.int32), np.array([0, n_blk], dtype=np.int32)
+            ws_s2 = torch.empty(ba.ba_final_block_attention_cached_workspace_bytes(hs, cu_q_s, cu_blk_s, lens_s),
+                                dtype=torch.uint8, device="cuda")
+
+            def small():
+                ba.ba_final_block_attention_cached(hs, qf, kc, vc, kf, vf, o, None, cu_q_s, cu_blk_s, offs_s, lens_s,
+                                                   None, None, None, ws_s2)
+
+            ms_b, _ = timed(small, 20 if args.only == "" else 200, 3)
+            ctx = int(lens_s.sum())
+            pairs = lq_s * ctx + lq_s * (lq_s + 1) // 2
+            rows_out["final_from_512_small_blocks"] = {"ms": round(ms_b, 4), "context_tokens": ctx, "final_len": lq_s,
+                                                       "TFLOPs": round(4.0 * d * hq * pairs / ms_b / 1e9, 1),
+                                                       "note": "512 cached blocks of 20-60 tokens (Appendix A's many small state blocks), none rewritten"}
 
     out = {
         "metric": "final-block prefill TFLOP/s at 32K ctx (ms/layer alongside)",

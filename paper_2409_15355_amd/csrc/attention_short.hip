@@ -86,7 +86,9 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   }
   const uint32_t n_rowtiles = (uint32_t)p.total_tiles;
   const int kvh = (int)fast_div(id, p.tiles_div);
-  const int rowtile = (int)(n_rowtiles - 1 - (id - (uint32_t)kvh * n_rowtiles));  // a block's long row tiles first
+  // (per-block encoding: a block's long row tiles first; whole prompts: the host's order)
+  const uint32_t id_lo = id - (uint32_t)kvh * n_rowtiles;
+  const int rowtile = kPrompt ? (int)id_lo : (int)(n_rowtiles - 1 - id_lo);
   // block of this row tile: the largest b with tile_start[b] <= rowtile, found in three rounds of
   // independent table reads (every 32nd entry, every 4th, every one) instead of a bisection's nine
   // dependent ones: the reads are scalar loads, and a work item this short feels each round trip
@@ -112,10 +114,16 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
     for (int k = 1; k < 4; ++k) fine += hit[k] <= rowtile ? 1 : 0;
     b += fine;
   }
-  const int q_tok0 = meta.offs[b];
-  const int lq = meta.offs[b + 1] - q_tok0;
-  int k_tok0 = q_tok0;  // first key the block sees
-  if constexpr (kPrompt) k_tok0 = meta.kstart[b];
+  int q_tok0, lq, k_tok0;  // the block's first token, its length, the first key it sees
+  if constexpr (kPrompt) {
+    q_tok0 = meta.start[b];
+    lq = meta.len[b];
+    k_tok0 = meta.kstart[b];
+  } else {
+    q_tok0 = meta.offs[b];
+    lq = meta.offs[b + 1] - q_tok0;
+    k_tok0 = q_tok0;
+  }
   const int dq = q_tok0 - k_tok0;  // the block's first token, counted in keys
   const int lk = dq + lq;          // keys up to the block's end
   const int jt = rowtile - meta.tile_start[b];

@@ -611,27 +611,39 @@ int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, co
   ap.rope_layout = heads->rope_layout;
   ap.n_splits = 1;
 
-  // first key of every block: its own first token, or for a prompt's last block the prompt's
-  std::vector<int32_t> kstart(n_blocks);
+  // First key of every block: its own first token, or for a prompt's last block the prompt's.
+  // Blocks go to the kernel longest key range first (a prompt's last block walks the whole prompt,
+  // and a launch should not end on a few of those).
+  struct Blk {
+    int32_t start, len, kstart;
+  };
+  std::vector<Blk> blks;
+  blks.reserve(n_blocks);
   for (int n = 0; n < n_prompts; ++n)
-    for (int b = cu_blk[n]; b < cu_blk[n + 1]; ++b)
-      kstart[b] = b == cu_blk[n + 1] - 1 ? block_offsets[cu_blk[n]] : block_offsets[b];
+    for (int b = cu_blk[n]; b < cu_blk[n + 1]; ++b) {
+      const int32_t len = block_offsets[b + 1] - block_offsets[b];
+      if (len == 0) continue;
+      blks.push_back({block_offsets[b], len, b == cu_blk[n + 1] - 1 ? block_offsets[cu_blk[n]] : block_offsets[b]});
+    }
+  std::stable_sort(blks.begin(), blks.end(), [](const Blk &a, const Blk &b) {
+    return (int64_t)a.start + a.len - a.kstart > (int64_t)b.start + b.len - b.kstart;
+  });
+  const int n_live = (int)blks.size();
 
-  for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
-    const int n = std::min(ba::kEncMaxBlocks, n_blocks - b0);
+  for (int b0 = 0; b0 < n_live; b0 += ba::kEncMaxBlocks) {
+    const int n = std::min(ba::kEncMaxBlocks, n_live - b0);
     ba::PromptMeta meta;
     memset(&meta, 0, sizeof(meta));
     meta.n = n;
     int64_t tiles = 0;
     for (int i = 0; i < n; ++i) {
-      const int64_t len = (int64_t)block_offsets[b0 + i + 1] - block_offsets[b0 + i];
-      meta.offs[i] = block_offsets[b0 + i];
-      meta.kstart[i] = kstart[b0 + i];
+      meta.start[i] = blks[b0 + i].start;
+      meta.len[i] = blks[b0 + i].len;
+      meta.kstart[i] = blks[b0 + i].kstart;
       meta.tile_start[i] = (int32_t)tiles;
-      tiles += (len * G + ba::kShortTileRows - 1) / ba::kShortTileRows;
+      tiles += ((int64_t)blks[b0 + i].len * G + ba::kShortTileRows - 1) / ba::kShortTileRows;
       if (tiles > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
     }
-    meta.offs[n] = block_offsets[b0 + n];
     meta.tile_start[n] = (int32_t)tiles;
     for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta.tile_start[i] = 0x7fffffff;
     if (tiles == 0) continue;

@@ -148,10 +148,12 @@ struct EncodeMeta {
   int32_t tile_start[kEncMaxBlocks + 1];  // first row tile of each block; [n] = all tiles, INT_MAX beyond
 };
 
-// Whole prompts (Section 2.4): like EncodeMeta, plus the first key each block sees.
+// Whole prompts (Section 2.4): blocks in any order (the host lists the ones with the longest key
+// ranges first), each with its first token, its length and the first key it sees.
 struct PromptMeta {
   int32_t n;
-  int32_t offs[kEncMaxBlocks + 1];
+  int32_t start[kEncMaxBlocks];
+  int32_t len[kEncMaxBlocks];
   int32_t tile_start[kEncMaxBlocks + 1];  // in row tiles of kShortTileRows rows; INT_MAX beyond [n]
   int32_t kstart[kEncMaxBlocks];          // token offset of the first visible key
 };
