@@ -27,7 +27,7 @@ EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin"
            "ba_encode_blocks_workspace_bytes", "ba_reencode_positions",
            "ba_final_block_attention", "ba_final_block_attention_workspace_bytes",
            "ba_final_block_attention_cached", "ba_final_block_attention_cached_workspace_bytes",
-           "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes"]
+           "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes", "ba_set_gather_below"]
 
 
 class BaTensor(ctypes.Structure):
@@ -96,6 +96,8 @@ def load():
     lib.ba_final_block_attention_cached_workspace_bytes.restype = ctypes.c_size_t
     lib.ba_final_block_attention_cached_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, _I32P,
                                                                     ctypes.c_int32]
+    lib.ba_set_gather_below.restype = ctypes.c_int32
+    lib.ba_set_gather_below.argtypes = [ctypes.c_int32]
     lib.ba_block_attention_prompts.restype = ctypes.c_int32
     lib.ba_block_attention_prompts.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, ctypes.c_void_p, ctypes.c_int32, _I32P,
                                                _I32P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t,
@@ -272,3 +274,8 @@ def ba_block_attention_prompts(heads: Heads, q, k, v, o_out, k_rot_out, lse_out,
     _check(load().ba_block_attention_prompts(ctypes.byref(heads.c), _ref(tq), _ref(tk), _ref(tv), _ref(to), _ref(tkr),
                                              lse_p, len(cb) - 1, _ip(cb), _ip(offs), rope_mode, wp, wb,
                                              _stream_handle(stream)))
+
+
+def ba_set_gather_below(mean_block_tokens: int) -> int:
+    """Mean cached-block length below which ba_final_block_attention_cached gathers; returns the old value."""
+    return int(load().ba_set_gather_below(int(mean_block_tokens)))

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <type_traits>
 #include <vector>
@@ -199,14 +200,16 @@ int32_t check_offsets(int32_t n_blocks, const int32_t *offs) {
   return BA_OK;
 }
 
-// Run the rotation kernel over a list of blocks, a launch per kReencMaxBlocks of them.
-int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, const int32_t *src_off,
-                     const int32_t *dst_off, const int32_t *len, const int32_t *pos_old,
-                     const int32_t *pos_new, hipStream_t stream) {
-  for (int b0 = 0; b0 < n_blocks; b0 += ba::kReencMaxBlocks) {
-    ba::ReencBlocks blk;
+// Run the rotation kernel over a list of blocks, a launch per table-full of them.
+template <typename Blocks>
+int32_t run_reencode_t(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, const int32_t *src_off,
+                       const int32_t *dst_off, const int32_t *len, const int32_t *pos_old,
+                       const int32_t *pos_new, hipStream_t stream) {
+  std::vector<Blocks> tab(1);  // (the large table is too big for the stack of a small thread)
+  Blocks &blk = tab[0];
+  for (int b0 = 0; b0 < n_blocks; b0 += Blocks::kBlocks) {
     memset(&blk, 0, sizeof(blk));
-    const int n = std::min(ba::kReencMaxBlocks, n_blocks - b0);
+    const int n = std::min(Blocks::kBlocks, n_blocks - b0);
     int filled = 0, max_len = 0;
     for (int i = 0; i < n; ++i) {
       const int b = b0 + i;
@@ -237,6 +240,14 @@ int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, c
     if (e != hipSuccess) return device_fail(e, "re-encode launch");
   }
   return BA_OK;
+}
+
+int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, const int32_t *src_off,
+                     const int32_t *dst_off, const int32_t *len, const int32_t *pos_old,
+                     const int32_t *pos_new, hipStream_t stream) {
+  if (n_blocks > ba::kReencMaxBlocks)
+    return run_reencode_t<ba::ReencBlocksLarge>(p, rt, n_blocks, src_off, dst_off, len, pos_old, pos_new, stream);
+  return run_reencode_t<ba::ReencBlocks>(p, rt, n_blocks, src_off, dst_off, len, pos_old, pos_new, stream);
 }
 
 // Rotate fresh Q (into q_rot, packed, pre-scaled) and fresh K (into k_rot) for segments
@@ -906,11 +917,21 @@ struct BlocksPlan {
   int max_nt = 0;
   int n_splits = 1;
   size_t kf_bytes = 0, q_bytes = 0, rot_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0;
+  // Small blocks: the context is first gathered (K re-encoded, V copied) into the workspace and the
+  // call continues as ba_final_block_attention.
+  bool gather = false;
+  std::vector<int32_t> cu_ctx;    // per prompt, gathered route only
+  size_t gather_kv_bytes = 0;     // one of the two gathered tensors
+  size_t gather_final_bytes = 0;  // workspace of the final-block step behind them
   size_t total() const {
+    if (gather) return 2 * align256(gather_kv_bytes) + gather_final_bytes;
     return align256(kf_bytes) + align256(q_bytes) + align256(rot_bytes) + align256(part_o_bytes) +
            align256(part_ml_bytes);
   }
 };
+
+// Mean length (tokens) of a call's cached blocks below which ba_final_block_attention_cached gathers.
+std::atomic<int32_t> g_gather_below{256};
 
 int32_t plan_final_blocks(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_blk,
                           const int32_t *blk_len, bool have_rot_out, BlocksPlan *plan) {
@@ -919,6 +940,7 @@ int32_t plan_final_blocks(const ba_heads *h, int32_t n_prompts, const int32_t *c
   BlocksPlan pl;
   if (n_prompts > 0 && (cu_q[0] != 0 || cu_blk[0] != 0)) return fail(BA_ERR_INVALID_ARG, "cu_q[0] and cu_blk[0] must be 0");
   const int G = h->n_q_heads / h->n_kv_heads;
+  int64_t max_nb = 0;  // most non-empty blocks in one prompt
   for (int n = 0; n < n_prompts; ++n) {
     const int64_t lq = (int64_t)cu_q[n + 1] - cu_q[n];
     if (lq < 1) return fail(BA_ERR_INVALID_ARG, "prompt %d: the final block needs at least one token", n);
@@ -934,14 +956,34 @@ int32_t plan_final_blocks(const ba_heads *h, int32_t n_prompts, const int32_t *c
       ++nb;
     }
     if (ctx > 0x3fffffff || tiles > 0x1ffffff) return fail(BA_ERR_INVALID_ARG, "prompt %d: context too long", n);
-    if (nb > ba::kBlkMaxBlocks)
-      return fail(BA_ERR_UNSUPPORTED, "prompt %d: %lld cached blocks, at most %d per prompt", n, (long long)nb,
-                  ba::kBlkMaxBlocks);
+    max_nb = std::max(max_nb, nb);
     pl.n_blocks += nb;
     pl.total_tiles += (lq * G + ba::kTileRows - 1) / ba::kTileRows;
     pl.max_nt = std::max(pl.max_nt, (int)tiles);
   }
   pl.lq_total = n_prompts > 0 ? cu_q[n_prompts] : 0;
+  // The kernel that reads the block table pays a fixed price per block (it turns its queries at
+  // every block boundary), a gathered copy a price per token: short blocks are gathered.
+  int64_t ctx_total = 0;
+  pl.cu_ctx.assign(n_prompts + 1, 0);
+  for (int n = 0; n < n_prompts; ++n) {
+    for (int b = cu_blk[n]; b < cu_blk[n + 1]; ++b) ctx_total += blk_len[b];
+    if (ctx_total > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "context too long");
+    pl.cu_ctx[n + 1] = (int32_t)ctx_total;
+  }
+  if (pl.n_blocks > 0 && ctx_total < (int64_t)g_gather_below.load() * pl.n_blocks) {
+    FinalPlan fp;
+    int32_t rc = plan_final(h, n_prompts, cu_q, pl.cu_ctx.data(), BA_ROPE_APPLY, have_rot_out, &fp);
+    if (rc) return rc;
+    pl.gather = true;
+    pl.gather_kv_bytes = (size_t)ctx_total * h->n_kv_heads * h->head_dim * 2;
+    pl.gather_final_bytes = fp.total();
+    *plan = pl;
+    return BA_OK;
+  }
+  if (max_nb > ba::kBlkMaxBlocks)
+    return fail(BA_ERR_UNSUPPORTED, "%lld cached blocks in one prompt, at most %d when the kernel reads the block table",
+                (long long)max_nb, ba::kBlkMaxBlocks);
   pl.n_splits = choose_splits(pl.total_tiles * h->n_kv_heads, pl.max_nt);
   if (!have_rot_out) pl.kf_bytes = (size_t)pl.lq_total * h->n_kv_heads * h->head_dim * 2;
   pl.q_bytes = (size_t)pl.lq_total * h->n_q_heads * h->head_dim * 2;
@@ -1041,6 +1083,10 @@ int32_t run_final_blocks(const BlocksCall &c, ba::AttnParams ap) {
 
 extern "C" {
 
+int32_t ba_set_gather_below(int32_t mean_block_tokens) {
+  return g_gather_below.exchange(mean_block_tokens < 0 ? 0 : mean_block_tokens);
+}
+
 size_t ba_final_block_attention_cached_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
                                                        const int32_t *cu_q, const int32_t *cu_blk,
                                                        const int32_t *blk_len, int32_t have_k_f_rot_out) {
@@ -1077,6 +1123,43 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
   if (!ws || ws_bytes < pl.total() || ((uintptr_t)ws & 255))
     return fail(BA_ERR_WORKSPACE, "final block (cached): 256-byte aligned workspace of %zu bytes needed, %zu given",
                 pl.total(), ws_bytes);
+
+  if (pl.gather) {
+    // non-empty blocks in prompt order: where they lie in the cache, where they go, and their positions
+    std::vector<int32_t> src, dst, len, oldp, newp, zero;
+    for (int n = 0; n < n_prompts; ++n) {
+      int32_t at = pl.cu_ctx[n], pos = 0;
+      for (int b = cu_blk[n]; b < cu_blk[n + 1]; ++b) {
+        if (blk_len[b] == 0) continue;
+        src.push_back(blk_tok_off[b]);
+        dst.push_back(at);
+        len.push_back(blk_len[b]);
+        oldp.push_back(blk_old_pos0 ? blk_old_pos0[b] : 0);
+        newp.push_back(blk_new_pos0 ? blk_new_pos0[b] : pos);
+        at += blk_len[b];
+        pos += blk_len[b];
+      }
+    }
+    zero.assign(src.size(), 0);
+    ba_tensor kg, vg;
+    kg.ptr = ws;
+    kg.stride_head = D;
+    kg.stride_tok = (int64_t)heads->n_kv_heads * D;
+    kg.dtype = BA_DTYPE_BF16;
+    vg = kg;
+    vg.ptr = (char *)ws + align256(pl.gather_kv_bytes);
+    const int nb = (int)src.size();
+    if ((rc = ba_reencode_positions(heads, k_cache, &kg, 1, 0, 0, nb, src.data(), dst.data(), len.data(), oldp.data(),
+                                    newp.data(), BA_REENC_SHIFT, stream_)))
+      return rc;
+    // (a shift of zero positions is a plain copy)
+    if ((rc = ba_reencode_positions(heads, v_cache, &vg, 1, 0, 0, nb, src.data(), dst.data(), len.data(), zero.data(),
+                                    zero.data(), BA_REENC_SHIFT, stream_)))
+      return rc;
+    return ba_final_block_attention(heads, q_f, &kg, &vg, k_f, v_f, o_out, k_f_rot_out, n_prompts, cu_q,
+                                    pl.cu_ctx.data(), q_pos0, BA_ROPE_APPLY,
+                                    (char *)ws + 2 * align256(pl.gather_kv_bytes), pl.gather_final_bytes, stream_);
+  }
 
   char *wsp = (char *)ws;
   void *kf_ws = wsp;

@@ -18,16 +18,22 @@ struct RopeTable {
 };
 
 // ---------------------------------------------------------------- re-encode ----------
-constexpr int kReencMaxBlocks = 96;
+// Two capacities (the table travels by value in the kernel arguments): retrieval-sized block lists,
+// and the long lists of small blocks that a gathered context is made of.
+constexpr int kReencMaxBlocks = 96, kReencMaxBlocksLarge = 1024;
 
-struct ReencBlocks {
+template <int NB>
+struct ReencBlocksT {
+  static constexpr int kBlocks = NB;
   int32_t n;
-  int32_t src_off[kReencMaxBlocks];
-  int32_t dst_off[kReencMaxBlocks];
-  int32_t len[kReencMaxBlocks];
-  int32_t pos_old[kReencMaxBlocks];
-  int32_t pos_new[kReencMaxBlocks];
+  int32_t src_off[NB];
+  int32_t dst_off[NB];
+  int32_t len[NB];
+  int32_t pos_old[NB];
+  int32_t pos_new[NB];
 };
+using ReencBlocks = ReencBlocksT<kReencMaxBlocks>;
+using ReencBlocksLarge = ReencBlocksT<kReencMaxBlocksLarge>;
 
 struct ReencParams {
   const void *src;
@@ -41,6 +47,8 @@ struct ReencParams {
 };
 
 hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
+                           hipStream_t stream);
+hipError_t launch_reencode(const ReencParams &p, const ReencBlocksLarge &blocks, const RopeTable &rt,
                            hipStream_t stream);
 
 // Final block over a block table: prompts and cached blocks per launch.  Two capacities, because

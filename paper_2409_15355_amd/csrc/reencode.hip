@@ -61,9 +61,8 @@ __device__ __forceinline__ void rotate(float &a, float &b, float c, float s) {
   b = nb;
 }
 
-template <typename T, int D, int LAYOUT, int MODE, int TOK_PER_WG>
-__global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, ReencBlocks blocks,
-                                                            RopeTable rt) {
+template <typename T, int D, int LAYOUT, int MODE, int TOK_PER_WG, typename Blocks>
+__global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, Blocks blocks, RopeTable rt) {
   constexpr int VEC = Chunk<T>::VEC;
   constexpr int CH = D / VEC;           // chunks per head vector
   constexpr int TPV = CH / 2;           // threads per head vector
@@ -146,9 +145,8 @@ __global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, Reenc
 // contiguous run of chunks, and because the workgroup size is a multiple of the chunks per head
 // vector, a thread that walks the run with stride 256 always meets the same four frequencies:
 // a pure streaming pass, every wave instruction moving 1 KB of consecutive memory.
-template <typename T, int D, int UNROLL>
-__global__ __launch_bounds__(kThreads) void reencode_shift_linear_kernel(ReencParams p, ReencBlocks blocks,
-                                                                         RopeTable rt) {
+template <typename T, int D, int UNROLL, typename Blocks>
+__global__ __launch_bounds__(kThreads) void reencode_shift_linear_kernel(ReencParams p, Blocks blocks, RopeTable rt) {
   constexpr int VEC = Chunk<T>::VEC;
   constexpr int CH = D / VEC;
   static_assert(kThreads % CH == 0, "a thread must keep its chunk position inside the head vector");
@@ -183,34 +181,31 @@ __global__ __launch_bounds__(kThreads) void reencode_shift_linear_kernel(ReencPa
   }
 }
 
-template <typename T, int D>
-hipError_t launch_linear(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
-                         hipStream_t stream) {
+template <typename T, int D, typename Blocks>
+hipError_t launch_linear(const ReencParams &p, const Blocks &blocks, const RopeTable &rt, hipStream_t stream) {
   constexpr int UNROLL = 8;
   constexpr int CH = D / Chunk<T>::VEC;
   const int64_t max_chunks = (int64_t)p.max_len * p.n_kv_heads * CH;
   dim3 grid((unsigned)((max_chunks + UNROLL * kThreads - 1) / (UNROLL * kThreads)), blocks.n, p.n_layers);
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return hipSuccess;
-  hipLaunchKernelGGL((reencode_shift_linear_kernel<T, D, UNROLL>), grid, dim3(kThreads), 0, stream, p, blocks, rt);
+  hipLaunchKernelGGL((reencode_shift_linear_kernel<T, D, UNROLL, Blocks>), grid, dim3(kThreads), 0, stream, p, blocks, rt);
   return hipGetLastError();
 }
 
-template <typename T, int D, int LAYOUT, int MODE>
-hipError_t launch_t(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
-                    hipStream_t stream) {
+template <typename T, int D, int LAYOUT, int MODE, typename Blocks>
+hipError_t launch_t(const ReencParams &p, const Blocks &blocks, const RopeTable &rt, hipStream_t stream) {
   constexpr int VEC = Chunk<T>::VEC;
   constexpr int TPP = kThreads / (D / VEC / 2);
   constexpr int TOK_PER_WG = TPP;
   dim3 grid(((p.max_len + TOK_PER_WG - 1) / TOK_PER_WG) * p.n_head_groups, blocks.n, p.n_layers);
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return hipSuccess;
-  hipLaunchKernelGGL((reencode_kernel<T, D, LAYOUT, MODE, TOK_PER_WG>), grid, dim3(kThreads), 0,
+  hipLaunchKernelGGL((reencode_kernel<T, D, LAYOUT, MODE, TOK_PER_WG, Blocks>), grid, dim3(kThreads), 0,
                      stream, p, blocks, rt);
   return hipGetLastError();
 }
 
-template <typename T, int D>
-hipError_t launch_d(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
-                    hipStream_t stream) {
+template <typename T, int D, typename Blocks>
+hipError_t launch_d(const ReencParams &p, const Blocks &blocks, const RopeTable &rt, hipStream_t stream) {
   const bool packed = p.src_sh == D && p.dst_sh == D && p.src_st == (int64_t)p.n_kv_heads * D &&
                       p.dst_st == (int64_t)p.n_kv_heads * D;
   if (p.layout == 0 && p.mode == 0 && packed) return launch_linear<T, D>(p, blocks, rt, stream);
@@ -223,8 +218,8 @@ hipError_t launch_d(const ReencParams &p, const ReencBlocks &blocks, const RopeT
 
 }  // namespace
 
-hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,
-                           hipStream_t stream) {
+template <typename Blocks>
+hipError_t launch_reencode_any(const ReencParams &p, const Blocks &blocks, const RopeTable &rt, hipStream_t stream) {
   if (p.dtype == 0) {
     if (p.head_dim == 128) return launch_d<uint16_t, 128>(p, blocks, rt, stream);
     if (p.head_dim == 64) return launch_d<uint16_t, 64>(p, blocks, rt, stream);
@@ -233,6 +228,14 @@ hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, cons
     if (p.head_dim == 64) return launch_d<float, 64>(p, blocks, rt, stream);
   }
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt, hipStream_t stream) {
+  return launch_reencode_any(p, blocks, rt, stream);
+}
+hipError_t launch_reencode(const ReencParams &p, const ReencBlocksLarge &blocks, const RopeTable &rt,
+                           hipStream_t stream) {
+  return launch_reencode_any(p, blocks, rt, stream);
 }
 
 }  // namespace ba

@@ -140,7 +140,15 @@ def test_final_cached_rejects_bad_arguments_and_sizes_workspace(lib):
     assert call([0, 0], [0, 1], [0], [10]) == -1          # empty final block
     assert call([0, 5], [1, 2], [0, 0], [10, 10]) == -1   # cu_blk[0] != 0
     assert call([0, 5], [0, 1], [0], [-3]) == -1          # negative block length
-    assert call([0, 5], [0, 1100], [0] * 1100, [1] * 1100) == -2  # more blocks in one prompt than a launch takes
+    assert call([0, 5], [0, 1100], [0] * 1100, [300] * 1100) == -2  # more blocks in one prompt than the kernel's table takes
+    assert call([0, 5], [0, 1100], [0] * 1100, [1] * 1100) == -4    # short blocks are gathered: no such limit; workspace missing
+    # the gathered route's workspace: K and V of the context, then the final-block step's own
+    small = ba.ba_final_block_attention_cached_workspace_bytes(h, [0, 5], [0, 1100], [1] * 1100)
+    assert small == 2 * ((1100 * 8 * 128 * 2 + 255) // 256 * 256) + \
+        ba.ba_final_block_attention_workspace_bytes(h, [0, 5], [0, 1100], ba.ROPE_APPLY)
+    old = ba.ba_set_gather_below(0)                                   # never gather: the table limit is back
+    assert old == 256 and call([0, 5], [0, 1100], [0] * 1100, [1] * 1100) == -2
+    assert ba.ba_set_gather_below(old) == 0
     assert call([0, 256], [0, 31], [1024 * b for b in range(31)], [1024] * 31) == -4  # workspace missing
     need = ba.ba_final_block_attention_cached_workspace_bytes(h, [0, 256], [0, 31], [1024] * 31)
     # config 5 as 31 cached blocks: split partials + rotated final-block keys and queries + 31 rows of rotations

@@ -552,9 +552,18 @@ def _cached_case(name):
     raise KeyError(name)
 
 
+@pytest.fixture(params=["table", "gathered"])
+def cached_route(ba, request):
+    """Both routes of ba_final_block_attention_cached: the kernel that reads the block table, and
+    the gathered copy it takes for short blocks (forced either way through the tuning call)."""
+    old = ba.ba_set_gather_below(0 if request.param == "table" else 1 << 30)
+    yield request.param
+    ba.ba_set_gather_below(old)
+
+
 @pytest.mark.parametrize("name", ["rag-shared-blocks", "deep-split-d64", "moved-cache-positions"])
 @pytest.mark.parametrize("layout", [0, 1])
-def test_final_block_from_block_cache_matches_oracle(ba, name, layout):
+def test_final_block_from_block_cache_matches_oracle(ba, name, layout, cached_route):
     torch = torch_mod()
     hq, hkv, d, base, t_cache, blocks, prompts = _cached_case(name)
     th = oracle.theta(base, d)
@@ -601,7 +610,7 @@ def test_final_block_from_block_cache_matches_oracle(ba, name, layout):
     assert_reencode_bf16(host_bits(kf_rot), kf_ref, layout, "k_f_rot_out, " + name)
 
 
-def test_final_block_from_block_cache_agrees_with_two_step_path(ba):
+def test_final_block_from_block_cache_agrees_with_two_step_path(ba, cached_route):
     """Same inputs through ba_reencode_positions + ba_final_block_attention: the two GPU routes differ
     only by where the extra bf16 rounding falls (re-encoded keys there, re-turned queries here)."""
     torch = torch_mod()
@@ -627,7 +636,7 @@ def test_final_block_from_block_cache_agrees_with_two_step_path(ba):
     assert_attention_close(host_f64(o1), host_f64(o2), "block cache vs two-step")
 
 
-def test_many_small_blocks_incremental_frame_update(ba):
+def test_many_small_blocks_incremental_frame_update(ba, cached_route):
     """Appendix A's workload in miniature: a prompt of 320 small state blocks, of which one changes
     (and changes length) from one frame to the next.  Only the changed block is encoded again
     (ba_encode_blocks, cacheable keys at local positions); every other block is reused from the
