@@ -17,6 +17,8 @@ What each function follows in arXiv 2409.15355:
 * :func:`final_block` -- Section 1 step 3, Section 2.5.
 * :func:`masked_attention_bruteforce` -- Section 2.4: the lower-triangular mask
   modified so that only the last block sees other blocks; dense softmax.
+* :func:`masked_attention_backward_bruteforce` -- the gradient of the same function
+  (Section 2.4's mask inside a block fine-tune step), by the chain rule written out.
 * :func:`merge_partials` -- softmax associativity (not in the paper; pins the
   split-KV combine).
 """
@@ -263,6 +265,47 @@ def masked_attention_bruteforce(q, k, v, offs, th, *, scale=None, layout=LAYOUT_
         P = P / P.sum(axis=1, keepdims=True)
         out[:, h, :] = P @ v[:, g, :]
     return out
+
+
+def masked_attention_backward_bruteforce(q, k, v, d_out, offs, th, *, scale=None, layout=LAYOUT_INTERLEAVED):
+    """Gradients of sum(out * d_out), out = masked_attention_bruteforce(q, k, v, ...), with respect
+    to q, k, v (all un-rotated).  With P the masked softmax of S = scale * q^ k^T:
+    dV = P^T dO;  dP = dO V^T;  dS = P * (dP - rowsum(dO * O));  dq^ = scale * dS k^;
+    dk^ = scale * dS^T q^;  and Eq. 1 is an orthogonal map, so dq = R(pos)^T dq^ = R(-pos) dq^.
+    Heads that share a KV head add up in dk and dv.  Returns (dq, dk, dv, lse) with lse the row
+    log-sum-exp of the masked scaled scores.  Tiny inputs only."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    d_out = np.asarray(d_out, dtype=np.float64)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    sc = float(scale) if scale is not None else 1.0 / np.sqrt(D)
+    pos = np.arange(T)
+    qr = rope_dense(q, pos, th, layout)
+    kr = rope_dense(k, pos, th, layout)
+    M = block_mask(offs)
+    dqr = np.zeros_like(q)
+    dkr = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    lse = np.empty((T, Hq))
+    for h in range(Hq):
+        g = h // G
+        S = np.where(M, sc * (qr[:, h, :] @ kr[:, g, :].T), -np.inf)
+        m = S.max(axis=1, keepdims=True)
+        E = np.exp(S - m)
+        l = E.sum(axis=1, keepdims=True)
+        P = E / l
+        lse[:, h] = (m + np.log(l))[:, 0]
+        O = P @ v[:, g, :]
+        dO = d_out[:, h, :]
+        dv[:, g, :] += P.T @ dO
+        dP = dO @ v[:, g, :].T
+        dS = P * (dP - (dO * O).sum(axis=1, keepdims=True))
+        dqr[:, h, :] = sc * (dS @ kr[:, g, :])
+        dkr[:, g, :] += sc * (dS.T @ qr[:, h, :])
+    return rope_dense(dqr, -pos, th, layout), rope_dense(dkr, -pos, th, layout), dv, lse
 
 
 def merge_partials(o_parts, m_parts, l_parts) -> np.ndarray:

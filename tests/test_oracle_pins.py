@@ -415,3 +415,89 @@ def test_shift_of_the_key_equals_opposite_shift_of_the_query(layout):
     k_ctx2 = oracle.reencode(packed_k, new0, new0, lens, th, new_pos0=new0, layout=layout)
     o2 = oracle.final_block(qf, k_ctx2, v_ctx, kf, vf, [0, 2], [0, T], th, layout=layout)
     np.testing.assert_allclose(o1, o2, rtol=0, atol=1e-12)
+
+
+# --------------------------------------------------------------------------------------------
+# gradient of the masked attention (what a block fine-tune step runs backward)
+# --------------------------------------------------------------------------------------------
+def _torch_masked_attention(q, k, v, offs, th, layout):
+    """The definition again, in plain torch ops on fp64 tensors (so that autograd can differentiate
+    it): rotate at positions 0..T-1, mask, softmax, weighted sum.  Written apart from the oracle."""
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    pos = torch.arange(T, dtype=torch.float64)
+    ang = pos[:, None] * torch.as_tensor(th)[None, :]
+    c, s = torch.cos(ang)[:, None, :], torch.sin(ang)[:, None, :]
+
+    def rot(x):
+        if layout == oracle.LAYOUT_HALF:
+            a, b = x[..., : d // 2], x[..., d // 2:]
+            return torch.cat([c * a - s * b, s * a + c * b], dim=-1)
+        a, b = x[..., 0::2], x[..., 1::2]
+        return torch.stack([c * a - s * b, s * a + c * b], dim=-1).reshape(x.shape)
+
+    qr, kr = rot(q), rot(k)
+    blk = torch.zeros(T, dtype=torch.long)
+    for b in range(len(offs) - 1):
+        blk[offs[b]:offs[b + 1]] = b
+    t, s_ = torch.arange(T)[:, None], torch.arange(T)[None, :]
+    mask = (s_ <= t) & ((blk[None, :] == blk[:, None]) | (blk[:, None] == len(offs) - 2))
+    outs = []
+    for h in range(hq):
+        g = h // (hq // hkv)
+        sc = (qr[:, h] @ kr[:, g].T) / math.sqrt(d)
+        sc = sc.masked_fill(~mask, float("-inf"))
+        outs.append(torch.softmax(sc, dim=1) @ v[:, g])
+    return torch.stack(outs, dim=1)
+
+
+@pytest.mark.parametrize("layout", [oracle.LAYOUT_INTERLEAVED, oracle.LAYOUT_HALF])
+def test_backward_equals_autograd_of_the_definition(layout):
+    rng = np.random.default_rng(41 + layout)
+    offs = [0, 5, 6, 13, 20]
+    T, hq, hkv, d = 20, 4, 2, 8
+    th = oracle.theta(10000.0, d)
+    q, k, v, do = (rng.standard_normal((T, h, d)) for h in (hq, hkv, hkv, hq))
+    dq, dk, dv, lse = oracle.masked_attention_backward_bruteforce(q, k, v, do, offs, th, layout=layout)
+    tq, tk, tv = (torch.tensor(x, requires_grad=True) for x in (q, k, v))
+    out = _torch_masked_attention(tq, tk, tv, offs, th, layout)
+    assert np.allclose(out.detach().numpy(), oracle.masked_attention_bruteforce(q, k, v, offs, th, layout=layout), atol=1e-12)
+    (out * torch.tensor(do)).sum().backward()
+    assert np.allclose(dq, tq.grad.numpy(), atol=1e-11)
+    assert np.allclose(dk, tk.grad.numpy(), atol=1e-11)
+    assert np.allclose(dv, tv.grad.numpy(), atol=1e-11)
+
+
+def test_backward_equals_finite_differences_and_respects_the_mask():
+    rng = np.random.default_rng(43)
+    offs = [0, 4, 9, 12]
+    T, hq, hkv, d = 12, 2, 1, 4
+    th = oracle.theta(10000.0, d)
+    q, k, v, do = (rng.standard_normal((T, h, d)) for h in (hq, hkv, hkv, hq))
+    dq, dk, dv, lse = oracle.masked_attention_backward_bruteforce(q, k, v, do, offs, th)
+    loss = lambda q_, k_, v_: float((oracle.masked_attention_bruteforce(q_, k_, v_, offs, th) * do).sum())
+    eps = 1e-6
+    for arr, grad, which in ((q, dq, 0), (k, dk, 1), (v, dv, 2)):
+        for _ in range(6):
+            idx = tuple(int(rng.integers(0, n)) for n in arr.shape)
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += eps
+            lo[idx] -= eps
+            args_hi = [q, k, v]; args_lo = [q, k, v]
+            args_hi[which], args_lo[which] = hi, lo
+            fd = (loss(*args_hi) - loss(*args_lo)) / (2 * eps)
+            assert abs(fd - grad[idx]) < 1e-7 * max(1.0, abs(fd)), (which, idx)
+    # a key of passage 0 is seen by passage 0 and by the last block only: with the output gradient
+    # zero on those rows its gradient vanishes, whatever the rows of passage 1 carry
+    do2 = do.copy()
+    do2[0:4] = 0.0
+    do2[9:12] = 0.0
+    _, dk2, dv2, _ = oracle.masked_attention_backward_bruteforce(q, k, v, do2, offs, th)
+    assert np.all(dk2[0:4] == 0.0) and np.all(dv2[0:4] == 0.0)
+    assert np.any(dk2[4:9] != 0.0)
+    # log-sum-exp: exp(lse) is the sum of exp(scaled scores) over the visible keys
+    pos = np.arange(T)
+    qr, kr = oracle.rope_dense(q, pos, th, 0), oracle.rope_dense(k, pos, th, 0)
+    M = oracle.block_mask(offs)
+    S = (qr[:, 1] @ kr[:, 0].T) / math.sqrt(d)
+    assert np.allclose(np.exp(lse[:, 1]), (np.exp(S) * M).sum(axis=1), rtol=1e-12)
