@@ -247,6 +247,34 @@ size_t ba_block_attention_prompts_workspace_bytes(const ba_heads *heads, int32_t
                                                   const int32_t *block_offsets, int32_t rope_mode,
                                                   int32_t have_k_rot_out);
 
+/*
+ * Backward pass of ba_block_attention_prompts (rope_mode BA_ROPE_APPLY): given the gradient d_out
+ * of the output, the gradients of the un-rotated q, k and v under the mask of Section 2.4.  With P
+ * the masked softmax of the scaled scores of the rotated q^ and k^:
+ *   dV = P^T dO,  dS = P o (dO V^T - rowsum(dO o O)),  dq^ = scale * dS k^,  dk^ = scale * dS^T q^,
+ * and dq, dk are dq^, dk^ turned back by the rotation of Eq. 1 (an orthogonal map).  Query heads
+ * that share a KV head add up in dk and dv.  P is recomputed from q, k and the rows' log-sum-exps;
+ * nothing else of the forward pass is kept.
+ *
+ * q, k, v, cu_blk, block_offsets: as given to the forward call.  o [T, n_q_heads, D] and lse
+ * (device, [T][n_q_heads] floats): its outputs.  d_out [T, n_q_heads, D]; dq_out like q, dk_out and
+ * dv_out like k and v; all bf16, fully overwritten.  Deterministic: every sum has one owner, no
+ * atomics.  Needs n_q_heads / n_kv_heads >= 4.  ws: 256-byte aligned, at least
+ * ba_block_attention_prompts_backward_workspace_bytes() bytes.
+ */
+int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tensor *q,
+                                            const ba_tensor *k, const ba_tensor *v,
+                                            const ba_tensor *o, const float *lse,
+                                            const ba_tensor *d_out, const ba_tensor *dq_out,
+                                            const ba_tensor *dk_out, const ba_tensor *dv_out,
+                                            int32_t n_prompts, const int32_t *cu_blk,
+                                            const int32_t *block_offsets, void *ws,
+                                            size_t ws_bytes, void *stream);
+size_t ba_block_attention_prompts_backward_workspace_bytes(const ba_heads *heads,
+                                                           int32_t n_prompts,
+                                                           const int32_t *cu_blk,
+                                                           const int32_t *block_offsets);
+
 #ifdef __cplusplus
 }
 #endif

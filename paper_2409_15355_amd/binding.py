@@ -27,7 +27,8 @@ EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin"
            "ba_encode_blocks_workspace_bytes", "ba_reencode_positions",
            "ba_final_block_attention", "ba_final_block_attention_workspace_bytes",
            "ba_final_block_attention_cached", "ba_final_block_attention_cached_workspace_bytes",
-           "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes", "ba_set_gather_below"]
+           "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes", "ba_set_gather_below",
+           "ba_block_attention_prompts_backward", "ba_block_attention_prompts_backward_workspace_bytes"]
 
 
 class BaTensor(ctypes.Structure):
@@ -96,6 +97,12 @@ def load():
     lib.ba_final_block_attention_cached_workspace_bytes.restype = ctypes.c_size_t
     lib.ba_final_block_attention_cached_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, _I32P,
                                                                     ctypes.c_int32]
+    lib.ba_block_attention_prompts_backward.restype = ctypes.c_int32
+    lib.ba_block_attention_prompts_backward.argtypes = [_HP, _TP, _TP, _TP, _TP, ctypes.c_void_p, _TP, _TP, _TP, _TP,
+                                                        ctypes.c_int32, _I32P, _I32P, ctypes.c_void_p, ctypes.c_size_t,
+                                                        ctypes.c_void_p]
+    lib.ba_block_attention_prompts_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.ba_block_attention_prompts_backward_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P]
     lib.ba_set_gather_below.restype = ctypes.c_int32
     lib.ba_set_gather_below.argtypes = [ctypes.c_int32]
     lib.ba_block_attention_prompts.restype = ctypes.c_int32
@@ -279,3 +286,21 @@ def ba_block_attention_prompts(heads: Heads, q, k, v, o_out, k_rot_out, lse_out,
 def ba_set_gather_below(mean_block_tokens: int) -> int:
     """Mean cached-block length below which ba_final_block_attention_cached gathers; returns the old value."""
     return int(load().ba_set_gather_below(int(mean_block_tokens)))
+
+
+def ba_block_attention_prompts_backward_workspace_bytes(heads: Heads, cu_blk, block_offsets) -> int:
+    cb, offs = _ints(cu_blk), _ints(block_offsets)
+    return int(load().ba_block_attention_prompts_backward_workspace_bytes(ctypes.byref(heads.c), len(cb) - 1, _ip(cb),
+                                                                          _ip(offs)))
+
+
+def ba_block_attention_prompts_backward(heads: Heads, q, k, v, o, lse, d_out, dq_out, dk_out, dv_out, cu_blk,
+                                        block_offsets, ws=None, stream=None) -> None:
+    """lse: the forward call's float32 [T, n_q_heads] tensor."""
+    cb, offs = _ints(cu_blk), _ints(block_offsets)
+    wp, wb = _ws(ws)
+    ts = [_tensor(x) for x in (q, k, v, o, d_out, dq_out, dk_out, dv_out)]
+    _check(load().ba_block_attention_prompts_backward(ctypes.byref(heads.c), _ref(ts[0]), _ref(ts[1]), _ref(ts[2]),
+                                                      _ref(ts[3]), ctypes.c_void_p(lse.data_ptr()), _ref(ts[4]),
+                                                      _ref(ts[5]), _ref(ts[6]), _ref(ts[7]), len(cb) - 1, _ip(cb),
+                                                      _ip(offs), wp, wb, _stream_handle(stream)))

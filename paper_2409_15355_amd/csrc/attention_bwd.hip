@@ -1,0 +1,654 @@
+// Backward pass of whole-prompt Block-attention (arXiv 2409.15355, Section 2.4: the mask a block
+// fine-tune step trains under).  With P the masked softmax of S = scale * q^ k^T (q^, k^ rotated at
+// their positions inside the prompt), O = P V and dO given:
+//   delta_r = sum_d dO_rd O_rd,   dV = P^T dO,   dP = dO V^T,   dS = P o (dP - delta),
+//   dq^ = scale * dS k^,          dk^ = scale * dS^T q^.
+// Nothing of the forward pass is kept but O and the rows' log-sum-exps L: P is recomputed as
+// exp(S - L).  Two kernels, so that every sum has one owner and no atomics are needed:
+//   - bwd_dq_kernel: a workgroup owns 128 packed query rows (as the forward kernel for short items
+//     does) and walks the key tiles its rows see; it accumulates dq^.
+//   - bwd_dkv_kernel: a workgroup owns 128 keys of one block and KV head and walks the 32-row
+//     query tiles that see them (the rest of its own block, and the prompt's last block if it is a
+//     passage); it accumulates dk^ and dV over all query heads of the group.
+// Both write gradients in the rotated frame; the RoPE pre-pass kernel, run backwards, turns dq^ and
+// dk^ into dq and dk (Eq. 1 is orthogonal: the transposed map is the rotation by minus the angle).
+//
+// Operand layouts are the forward kernel's: products are computed transposed with
+// v_mfma_f32_32x32x16_bf16, the owner's side along lanes and in registers as B operands, the
+// walked side from LDS tiles as A operands (16-byte row reads for the products that contract over
+// head_dim, LDS transpose reads for those that contract over the walked index), and a probability
+// tile in accumulator layout is directly the B operand of the next product.
+#include <type_traits>
+
+#include "ba_device.h"
+#include "ba_lds.h"
+
+namespace ba {
+namespace {
+
+constexpr int kBWaves = 4;
+constexpr int kBThreads = kBWaves * 64;
+constexpr int kBKeys = 32;  // walked rows (keys, or packed query rows) per tile
+constexpr int kBBuf = 3;    // tile buffers
+constexpr float kLn2 = 0.6931471805599453f, kLog2e = 1.4426950408889634f;
+
+template <int D>
+struct BGeo {
+  static constexpr int KCH = D / 16;
+  static constexpr int DT = D / 32;
+  static constexpr int CPR = D / 8;
+  static constexpr int ROWB = D * 2;
+  static constexpr int LPR = 256 / ROWB;
+  static constexpr int TILEB = kBKeys * ROWB;
+  static constexpr int RPI = 1024 / ROWB;             // rows filled by one LDS-direct wave instruction
+  static constexpr int IPW = kBKeys / RPI / kBWaves;  // such instructions per wave and tile
+  static constexpr int QRPI = 64 / CPR;               // whole rows per plain load instruction
+  static_assert(IPW >= 1 && 32 / QRPI == KCH, "tile geometry");
+};
+
+// row `row` of a tile, 16-byte chunk `chunk`: every tile here uses the one swizzle
+template <int D>
+__device__ __forceinline__ uint32_t tile_ofs(int row, int chunk) {
+  using G = BGeo<D>;
+  return (uint32_t)(row * G::ROWB + ((chunk ^ ((row / G::LPR) & (G::CPR - 1))) << 4));
+}
+
+// delta and the log-sum-exp in the order the kernels want them: ld[kvh][token][g] = (L / ln 2, delta)
+// for query head kvh * G + g, i.e. contiguous in packed-row order for a fixed KV head.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_delta_kernel(const uint16_t *o, int64_t o_st, int64_t o_sh, const uint16_t *dout,
+                                                        int64_t do_st, int64_t do_sh, const float *lse, float2 *ld,
+                                                        int64_t T, int n_q_heads, int group) {
+  constexpr int TPR = D / 8;  // threads per (token, head) row, 8 elements each
+  const int64_t row = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+  if (row >= T * n_q_heads) return;  // (whole groups of TPR lanes leave together)
+  const int64_t t = row / n_q_heads;
+  const int h = (int)(row - t * n_q_heads);
+  const int c = threadIdx.x % TPR;
+  const u32x4_t a = *reinterpret_cast<const u32x4_t *>(o + t * o_st + (int64_t)h * o_sh + c * 8);
+  const u32x4_t b = *reinterpret_cast<const u32x4_t *>(dout + t * do_st + (int64_t)h * do_sh + c * 8);
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) s += bf16_lo(a[e]) * bf16_lo(b[e]) + bf16_hi(a[e]) * bf16_hi(b[e]);
+#pragma unroll
+  for (int m = 1; m < TPR; m <<= 1) s += __shfl_xor(s, m, 64);
+  if (c == 0) {
+    const int kvh = h / group, g = h - kvh * group;
+    ld[((int64_t)kvh * T + t) * group + g] = make_float2(lse[row] * kLog2e, s);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBThreads, 2) void bwd_dq_kernel(AttnParams p, PromptMeta meta, BwdParams bp) {
+  using G = BGeo<D>;
+  extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+  lds_char *smem = (lds_char *)smem_generic;
+  // LDS map: buffer b = bytes [2 b TB, 2 (b + 1) TB): its K tile, then its V tile
+  constexpr uint32_t TB = G::TILEB;
+
+  uint32_t id = blockIdx.x;
+  {
+    constexpr uint32_t kXcds = 8;
+    const uint32_t n_wg = gridDim.x, q = n_wg / kXcds, r = n_wg % kXcds, x = id % kXcds;
+    id = x * q + min(x, r) + id / kXcds;
+  }
+  const uint32_t n_rowtiles = (uint32_t)p.total_tiles;
+  const int kvh = (int)fast_div(id, p.tiles_div);
+  const int rowtile = (int)(id - (uint32_t)kvh * n_rowtiles);
+  const int b = find_segment(meta.tile_start, meta.n, rowtile);
+  const int q_tok0 = meta.start[b], lq = meta.len[b], k_tok0 = meta.kstart[b];
+  const int jt = rowtile - meta.tile_start[b];
+  const int dq = q_tok0 - k_tok0;  // the block's first token, counted in keys
+  const int lk = dq + lq;          // keys up to the block's end
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int col = lane & 31, hf = lane >> 5;
+  const int Gq = p.group;
+  const int n_rows = lq * Gq;
+  const int row0 = jt * kShortTileRows;
+  const int last_row = min(n_rows, row0 + kShortTileRows) - 1;
+  const int n_t = (dq + (int)fast_div((uint32_t)last_row, p.group_div)) / kBKeys + 1;
+  const int wave_row0 = row0 + wave * 32;
+  const int wave_last_row = min(n_rows, wave_row0 + 32) - 1;
+  const int wave_n_t =
+      wave_last_row >= wave_row0 ? (dq + (int)fast_div((uint32_t)wave_last_row, p.group_div)) / kBKeys + 1 : 0;
+  const int first_key_wave = dq + (int)fast_div((uint32_t)wave_row0, p.group_div);
+  const int my_row = min(wave_row0 + col, n_rows - 1);  // (lanes beyond the block's rows repeat its last row)
+  const int my_tok = (int)fast_div((uint32_t)my_row, p.group_div);
+  const int my_key = dq + my_tok;
+
+  // ---- whole rows of q^ and dO for this wave, requested first (see the forward kernel) -----------
+  auto walk_rows = [&](uint32_t st, uint32_t sh, auto &&visit) __attribute__((always_inline)) {
+    const int wr_r0 = wave_row0 + lane / G::CPR;
+    const int wr_tok0 = (int)fast_div((uint32_t)wr_r0, p.group_div);
+    const int wr_g0 = wr_r0 - wr_tok0 * Gq;
+    uint32_t off = (uint32_t)wr_tok0 * st + (uint32_t)wr_g0 * sh;
+    int g = wr_g0;
+    const uint32_t d_in = 4u * sh, d_wrap = st + (uint32_t)(4 - Gq) * sh;
+#pragma unroll
+    for (int u = 0; u < G::KCH; ++u) {
+      visit(u, off, wr_r0);
+#pragma unroll
+      for (int s4 = 0; s4 < G::QRPI / 4; ++s4) {
+        g += 4;
+        const bool wrap = g >= Gq;
+        g = wrap ? g - Gq : g;
+        off += wrap ? d_wrap : d_in;
+      }
+    }
+  };
+  u32x4_t ld_q[G::KCH], ld_do[G::KCH];
+  {
+    const char *qbase = (const char *)(p.q + (int64_t)q_tok0 * p.q_st + (int64_t)(kvh * Gq) * p.q_sh);
+    const uint32_t st = (uint32_t)p.q_st, sh = (uint32_t)p.q_sh;
+    const uint32_t last_off = (uint32_t)(lq - 1) * st + (uint32_t)(Gq - 1) * sh;
+    walk_rows(st, sh, [&](int u, uint32_t off, int wr_r0) __attribute__((always_inline)) {
+      const uint32_t o = wr_r0 < n_rows - u * G::QRPI ? off : last_off;
+      ld_q[u] = *reinterpret_cast<const u32x4_t *>(qbase + (o * 2u + (uint32_t)(lane % G::CPR) * 16u));
+    });
+  }
+  {
+    const char *dbase = (const char *)(bp.dout + (int64_t)q_tok0 * bp.do_st + (int64_t)(kvh * Gq) * bp.do_sh);
+    const uint32_t st = (uint32_t)bp.do_st, sh = (uint32_t)bp.do_sh;
+    const uint32_t last_off = (uint32_t)(lq - 1) * st + (uint32_t)(Gq - 1) * sh;
+    walk_rows(st, sh, [&](int u, uint32_t off, int wr_r0) __attribute__((always_inline)) {
+      const uint32_t o = wr_r0 < n_rows - u * G::QRPI ? off : last_off;
+      ld_do[u] = *reinterpret_cast<const u32x4_t *>(dbase + (o * 2u + (uint32_t)(lane % G::CPR) * 16u));
+    });
+  }
+  // this lane's row: log-sum-exp (base-2 units) and delta
+  const float2 my_ld = bp.ld[((int64_t)kvh * bp.T + q_tok0 + my_tok) * Gq + (my_row - my_tok * Gq)];
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- per-lane LDS read offsets inside a tile ---------------------------------------------------
+  uint32_t k_rd[G::KCH];  // rows as A operand: row `col`, chunk 2 kk + hf
+#pragma unroll
+  for (int kk = 0; kk < G::KCH; ++kk) k_rd[kk] = tile_ofs<D>(col, kk * 2 + hf);
+  // transposed A operand (16-row step 0): 8-byte piece of row trow (+8), head dims 32 dt + ...
+  uint32_t t_rd[2][G::DT];
+  {
+    const int trow = hf * 4 + ((lane & 15) >> 2);
+#pragma unroll
+    for (int dt = 0; dt < G::DT; ++dt) {
+      const int byte = dt * 64 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+      t_rd[0][dt] = tile_ofs<D>(trow, byte >> 4) + (byte & 15);
+      t_rd[1][dt] = tile_ofs<D>(trow + 8, byte >> 4) + (byte & 15);
+    }
+  }
+
+  // ---- tile fill (K and V rows of 32 keys; rows beyond the valid ones repeat the last valid row) ----
+  const char *k_base = (const char *)(p.kf + (int64_t)k_tok0 * p.kf_st + (int64_t)kvh * p.kf_sh);
+  const char *v_base = (const char *)(p.vf + (int64_t)k_tok0 * p.vf_st + (int64_t)kvh * p.vf_sh);
+  const uint32_t k_rb = (uint32_t)p.kf_st * 2u, v_rb = (uint32_t)p.vf_st * 2u;
+  int c_row[G::IPW];
+  uint32_t c_chunk[G::IPW];
+#pragma unroll
+  for (int u = 0; u < G::IPW; ++u) {
+    const int row = (wave * G::IPW + u) * G::RPI + lane / G::CPR, pos = lane % G::CPR;
+    c_row[u] = row;
+    c_chunk[u] = (uint32_t)(pos ^ ((row / G::LPR) & (G::CPR - 1))) << 4;
+  }
+  const uint32_t lds_copy = (uint32_t)(uintptr_t)smem + wave * G::IPW * 1024;
+  auto issue_copy = [&](int t, int buf) __attribute__((always_inline)) {
+    const int valid = min(kBKeys, lk - t * kBKeys);
+    const char *kp = k_base + (uint64_t)(uint32_t)(t * kBKeys) * (uint64_t)k_rb;
+    const char *vp = v_base + (uint64_t)(uint32_t)(t * kBKeys) * (uint64_t)v_rb;
+#pragma unroll
+    for (int u = 0; u < G::IPW; ++u) {
+      const uint32_t row = (uint32_t)min(c_row[u], valid - 1);
+      lds_dma16(kp, row * k_rb + c_chunk[u], lds_copy + (uint32_t)buf * (2 * TB) + u * 1024);
+      lds_dma16(vp, row * v_rb + c_chunk[u], lds_copy + (uint32_t)buf * (2 * TB) + TB + u * 1024);
+    }
+  };
+  constexpr int kOpsPerTile = 2 * G::IPW;
+  issue_copy(0, 0);  // (buffer 2 holds the waves' slices until the first barrier)
+  if (1 < n_t) issue_copy(1, 1);
+  __builtin_amdgcn_sched_barrier(0);
+  dma_wait<0>();
+
+  // ---- whole rows -> B-operand fragments (lane = row), 16 rows at a time through this wave's slice ----
+  static_assert(kBWaves * 16 * G::ROWB <= 2 * TB, "the slices fit one tile buffer");
+  const uint32_t s_ofs = 2 * (2 * TB) + wave * (16 * G::ROWB);
+  auto rows_to_frags = [&](const u32x4_t (&ld)[G::KCH], bf16x8_t (&out)[G::KCH]) __attribute__((always_inline)) {
+    u32x4_t got[2][G::KCH];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+      for (int u = 0; u < G::KCH / 2; ++u)
+        *reinterpret_cast<__attribute__((address_space(3))) u32x4_t *>(
+            smem + s_ofs + tile_ofs<D>(u * G::QRPI + lane / G::CPR, lane % G::CPR)) = ld[pass * (G::KCH / 2) + u];
+#pragma unroll
+      for (int kk = 0; kk < G::KCH; ++kk)
+        got[pass][kk] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t *>(
+            smem + s_ofs + tile_ofs<D>(col & 15, kk * 2 + hf));
+    }
+#pragma unroll
+    for (int kk = 0; kk < G::KCH; ++kk) {
+      u32x4_t w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = (col >> 4) ? got[1][kk][e] : got[0][kk][e];
+      asm volatile("" : "+v"(w));
+      out[kk] = __builtin_bit_cast(bf16x8_t, w);
+    }
+  };
+  bf16x8_t qf[G::KCH], dof[G::KCH];
+  rows_to_frags(ld_q, qf);
+  rows_to_frags(ld_do, dof);
+
+  f32x16_t acc[G::DT];
+#pragma unroll
+  for (int dt = 0; dt < G::DT; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
+
+  // ---- the walk over the key tiles ---------------------------------------------------------------
+  int buf = 0;
+#pragma unroll 1
+  for (int i = 0; i < n_t; ++i) {
+    if (i + 1 < n_t) dma_wait<kOpsPerTile>(); else dma_wait<0>();
+    wg_barrier();
+    if (i + 2 < n_t) issue_copy(i + 2, buf == 0 ? 2 : buf - 1);
+    if (i < wave_n_t) {
+      const uint32_t kofs = (uint32_t)buf * (2 * TB), vofs = kofs + TB;
+      // S'^T - L: the base-2 exponent of P;  dP^T - delta
+      f32x16_t sacc, dpacc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        sacc[v] = -my_ld.x;
+        dpacc[v] = -my_ld.y;
+      }
+#pragma unroll
+      for (int kk = 0; kk < G::KCH; ++kk) {
+        const bf16x8_t kfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(smem + (k_rd[kk] + kofs));
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[kk], sacc, 0, 0, 0);
+        const bf16x8_t vfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(smem + (k_rd[kk] + vofs));
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, dof[kk], dpacc, 0, 0, 0);
+      }
+      const int key0 = i * kBKeys;
+      const int valid = min(kBKeys, lk - key0);
+      if (key0 + kBKeys - 1 > first_key_wave || valid < kBKeys) {
+        const int lim = min(my_key - key0 + 1, valid);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = (v >> 2) * 8 + hf * 4 + (v & 3);
+          if (key >= lim) sacc[v] = -INFINITY;
+        }
+      }
+      // dS^T = P^T o (dP^T - delta), rounded to bf16: the B operand of dq^^T += K^T dS^T
+      bf16x8_t dsf[2];
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        u32x4_t w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float d0 = __builtin_amdgcn_exp2f(sacc[e * 8 + 2 * j]) * dpacc[e * 8 + 2 * j];
+          const float d1 = __builtin_amdgcn_exp2f(sacc[e * 8 + 2 * j + 1]) * dpacc[e * 8 + 2 * j + 1];
+          w[j] = pack_bf16(d0, d1);
+        }
+        dsf[e] = __builtin_bit_cast(bf16x8_t, w);
+      }
+#pragma unroll
+      for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+        for (int dt = 0; dt < G::DT; ++dt) {
+          typedef __attribute__((address_space(3))) s16x4_t lds_s16x4;
+          typedef short s16x8_t __attribute__((ext_vector_type(8)));
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + (t_rd[0][dt] + kofs) + kc * 16 * G::ROWB));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + (t_rd[1][dt] + kofs) + kc * 16 * G::ROWB));
+          const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both), dsf[kc], acc[dt], 0, 0, 0);
+        }
+    }
+    buf = buf == kBBuf - 1 ? 0 : buf + 1;
+  }
+
+  // ---- epilogue: dq^ = scale * acc, bf16, as whole rows through each wave's slice of LDS ------------
+  wg_barrier();
+  int ln = lane;
+  asm volatile("" : "+v"(ln));
+  const int ecol = ln & 31, ehf = ln >> 5;
+  lds_char *stage = smem + wave * (32 * G::ROWB);
+#pragma unroll
+  for (int dt = 0; dt < G::DT; ++dt)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+      u32x2_t w;
+      w[0] = pack_bf16(acc[dt][q4 * 4 + 0] * bp.scale, acc[dt][q4 * 4 + 1] * bp.scale);
+      w[1] = pack_bf16(acc[dt][q4 * 4 + 2] * bp.scale, acc[dt][q4 * 4 + 3] * bp.scale);
+      *reinterpret_cast<__attribute__((address_space(3))) u32x2_t *>(stage + tile_ofs<D>(ecol, dt * 4 + q4) + ehf * 8) = w;
+    }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  {
+    u32x4_t w[G::KCH];
+#pragma unroll
+    for (int u = 0; u < G::KCH; ++u)
+      w[u] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t *>(
+          stage + tile_ofs<D>(u * G::QRPI + ln / G::CPR, ln % G::CPR));
+    // dq^ rows are packed [token][query head][D]
+    char *obase = (char *)(bp.dqr + ((int64_t)q_tok0 * p.n_q_heads + kvh * Gq) * D);
+    walk_rows((uint32_t)(p.n_q_heads * D), (uint32_t)D, [&](int u, uint32_t off, int wr_r0) __attribute__((always_inline)) {
+      if (wr_r0 < n_rows - u * G::QRPI)
+        *reinterpret_cast<u32x4_t *>(obase + (off * 2u + (uint32_t)(ln % G::CPR) * 16u)) = w[u];
+    });
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kBThreads, 1) void bwd_dkv_kernel(AttnParams p, BwdKvMeta meta, BwdParams bp) {
+  using G = BGeo<D>;
+  extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+  lds_char *smem = (lds_char *)smem_generic;
+  // LDS map: buffer b = bytes [b BUFB, (b + 1) BUFB): a q^ tile, a dO tile (32 packed query rows each),
+  // then per wave 1 KB whose first 256 bytes hold the rows' (L / ln 2, delta)
+  constexpr uint32_t TB = G::TILEB;
+  constexpr uint32_t BUFB = 2 * TB + kBWaves * 1024;
+
+  uint32_t id = blockIdx.x;
+  {
+    constexpr uint32_t kXcds = 8;
+    const uint32_t n_wg = gridDim.x, q = n_wg / kXcds, r = n_wg % kXcds, x = id % kXcds;
+    id = x * q + min(x, r) + id / kXcds;
+  }
+  const uint32_t n_keytiles = (uint32_t)p.total_tiles;
+  const int kvh = (int)fast_div(id, p.tiles_div);
+  const int keytile = (int)(id - (uint32_t)kvh * n_keytiles);
+  const int b = find_segment(meta.tile_start, meta.n, keytile);
+  const int k_tok0 = meta.start[b], lk = meta.len[b];  // the block that owns the keys
+  const int f_tok0 = meta.fin_start[b], lf = meta.fin_len[b];  // its prompt's last block, if it is a passage
+  const int k0 = (keytile - meta.tile_start[b]) * kShortTileRows;  // the workgroup's first key, inside the block
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int col = lane & 31, hf = lane >> 5;
+  const int Gq = p.group;
+  const int kw0 = k0 + wave * 32;  // this wave's first key
+  const bool wave_has_keys = kw0 < lk;
+  const int my_key = kw0 + col;    // (may lie beyond the block: such columns are never stored)
+
+  // ---- query row tiles that see these keys: the block's own rows from the first key's token on,
+  //      then every row of the prompt's last block ------------------------------------------------
+  const int n_rows_a = lk * Gq, n_rows_f = lf * Gq;
+  const int tile_a0 = (k0 * Gq) / kBKeys;
+  const int n_a = (n_rows_a + kBKeys - 1) / kBKeys - tile_a0;
+  const int n_t = n_a + (n_rows_f + kBKeys - 1) / kBKeys;
+
+  // ---- this wave's keys as B operands: k^ and v rows, whole, then into fragments through LDS ----
+  u32x4_t ld_k[G::KCH], ld_v[G::KCH];
+  {
+    const char *kb = (const char *)(p.kf + (int64_t)k_tok0 * p.kf_st + (int64_t)kvh * p.kf_sh);
+    const char *vb = (const char *)(p.vf + (int64_t)k_tok0 * p.vf_st + (int64_t)kvh * p.vf_sh);
+#pragma unroll
+    for (int u = 0; u < G::KCH; ++u) {
+      const uint32_t tok = (uint32_t)min(kw0 + u * G::QRPI + lane / G::CPR, lk - 1);
+      ld_k[u] = *reinterpret_cast<const u32x4_t *>(kb + ((uint64_t)tok * (uint64_t)p.kf_st + (uint32_t)(lane % G::CPR) * 8u) * 2u);
+      ld_v[u] = *reinterpret_cast<const u32x4_t *>(vb + ((uint64_t)tok * (uint64_t)p.vf_st + (uint32_t)(lane % G::CPR) * 8u) * 2u);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  uint32_t k_rd[G::KCH];
+#pragma unroll
+  for (int kk = 0; kk < G::KCH; ++kk) k_rd[kk] = tile_ofs<D>(col, kk * 2 + hf);
+  uint32_t t_rd[2][G::DT];
+  {
+    const int trow = hf * 4 + ((lane & 15) >> 2);
+#pragma unroll
+    for (int dt = 0; dt < G::DT; ++dt) {
+      const int byte = dt * 64 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+      t_rd[0][dt] = tile_ofs<D>(trow, byte >> 4) + (byte & 15);
+      t_rd[1][dt] = tile_ofs<D>(trow + 8, byte >> 4) + (byte & 15);
+    }
+  }
+
+  // ---- tile fill: 32 packed query rows of q^ and of dO, and the rows' (L, delta) ---------------------
+  const uint32_t q_st = (uint32_t)p.q_st, q_sh = (uint32_t)p.q_sh, do_st = (uint32_t)bp.do_st, do_sh = (uint32_t)bp.do_sh;
+  const uint32_t lds_copy = (uint32_t)(uintptr_t)smem + wave * G::IPW * 1024;
+  const uint32_t lds_ld = (uint32_t)(uintptr_t)smem + 2 * TB + wave * 1024;
+  auto issue_copy = [&](int t, int buf) __attribute__((always_inline)) {
+    const bool own = t < n_a;
+    const int r0 = (own ? tile_a0 + t : t - n_a) * kBKeys;  // first packed row of the tile, inside its block
+    const int tok0 = own ? k_tok0 : f_tok0;
+    const int n_rows = own ? n_rows_a : n_rows_f;
+    const char *qb = (const char *)(p.q + (int64_t)tok0 * p.q_st + (int64_t)(kvh * Gq) * p.q_sh);
+    const char *db = (const char *)(bp.dout + (int64_t)tok0 * bp.do_st + (int64_t)(kvh * Gq) * bp.do_sh);
+#pragma unroll
+    for (int u = 0; u < G::IPW; ++u) {
+      const int rt = (wave * G::IPW + u) * G::RPI + lane / G::CPR, pos = lane % G::CPR;
+      const uint32_t r = (uint32_t)min(r0 + rt, n_rows - 1);  // rows beyond the block repeat its last row
+      const uint32_t tok = fast_div(r, p.group_div), g = r - tok * (uint32_t)Gq;
+      const uint32_t chunk = (uint32_t)(pos ^ ((rt / G::LPR) & (G::CPR - 1))) << 4;
+      lds_dma16(qb, (tok * q_st + g * q_sh) * 2u + chunk, lds_copy + (uint32_t)buf * BUFB + u * 1024);
+      lds_dma16(db, (tok * do_st + g * do_sh) * 2u + chunk, lds_copy + (uint32_t)buf * BUFB + TB + u * 1024);
+    }
+    // (L, delta) of the 32 rows: 256 contiguous bytes in packed-row order; every wave fetches its own
+    // copy (16 lanes' worth; the other lanes re-read the same bytes), so that all waves count alike
+    const char *lb = (const char *)(bp.ld + ((int64_t)kvh * bp.T + tok0) * Gq);
+    const uint32_t r = (uint32_t)min(r0 + (lane & 15) * 2, n_rows - 2 + (n_rows & 1));
+    lds_dma16(lb, (r & ~1u) * 8u, lds_ld + (uint32_t)buf * BUFB);
+  };
+  constexpr int kOpsPerTile = 2 * G::IPW + 1;
+  if (0 < n_t) issue_copy(0, 0);
+  if (1 < n_t) issue_copy(1, 1);
+  __builtin_amdgcn_sched_barrier(0);
+  dma_wait<0>();
+
+  // ---- k^ and v rows -> B-operand fragments through this wave's slice of buffer 2 -------------------
+  static_assert(kBWaves * 16 * G::ROWB <= 2 * TB, "the slices fit the tiles of one buffer");
+  const uint32_t s_ofs = 2 * BUFB + wave * (16 * G::ROWB);
+  auto rows_to_frags = [&](const u32x4_t (&ld)[G::KCH], bf16x8_t (&out)[G::KCH]) __attribute__((always_inline)) {
+    u32x4_t got[2][G::KCH];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+      for (int u = 0; u < G::KCH / 2; ++u)
+        *reinterpret_cast<__attribute__((address_space(3))) u32x4_t *>(
+            smem + s_ofs + tile_ofs<D>(u * G::QRPI + lane / G::CPR, lane % G::CPR)) = ld[pass * (G::KCH / 2) + u];
+#pragma unroll
+      for (int kk = 0; kk < G::KCH; ++kk)
+        got[pass][kk] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t *>(
+            smem + s_ofs + tile_ofs<D>(col & 15, kk * 2 + hf));
+    }
+#pragma unroll
+    for (int kk = 0; kk < G::KCH; ++kk) {
+      u32x4_t w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = (col >> 4) ? got[1][kk][e] : got[0][kk][e];
+      asm volatile("" : "+v"(w));
+      out[kk] = __builtin_bit_cast(bf16x8_t, w);
+    }
+  };
+  bf16x8_t kf[G::KCH], vf[G::KCH];
+  rows_to_frags(ld_k, kf);
+  rows_to_frags(ld_v, vf);
+
+  f32x16_t dk[G::DT], dv[G::DT];
+#pragma unroll
+  for (int dt = 0; dt < G::DT; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      dk[dt][v] = 0.f;
+      dv[dt][v] = 0.f;
+    }
+
+  // ---- the walk over the query row tiles ------------------------------------------------------------
+  int buf = 0;
+#pragma unroll 1
+  for (int i = 0; i < n_t; ++i) {
+    if (i + 1 < n_t) dma_wait<kOpsPerTile>(); else dma_wait<0>();
+    wg_barrier();
+    if (i + 2 < n_t) issue_copy(i + 2, buf == 0 ? 2 : buf - 1);
+    const bool own = i < n_a;
+    const int r0 = (own ? tile_a0 + i : i - n_a) * kBKeys;
+    const int n_rows = own ? n_rows_a : n_rows_f;
+    // a tile of the block's own rows whose tokens all lie before this wave's first key sees none of them
+    const int last_tok = (int)fast_div((uint32_t)min(r0 + kBKeys - 1, n_rows - 1), p.group_div);
+    if (wave_has_keys && !(own && last_tok < kw0)) {
+      const uint32_t qofs = (uint32_t)buf * BUFB, dofs = qofs + TB;
+      f32x16_t sacc, dpacc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        sacc[v] = 0.f;
+        dpacc[v] = 0.f;
+      }
+#pragma unroll
+      for (int kk = 0; kk < G::KCH; ++kk) {
+        const bf16x8_t qfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(smem + (k_rd[kk] + qofs));
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfrag, kf[kk], sacc, 0, 0, 0);
+        const bf16x8_t dfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(smem + (k_rd[kk] + dofs));
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dfrag, vf[kk], dpacc, 0, 0, 0);
+      }
+      // register v of an accumulator is tile row (v >> 2) * 8 + hf * 4 + (v & 3): four runs of four rows
+      f32x4_t ldv[8];
+#pragma unroll
+      for (int run = 0; run < 4; ++run)
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+          ldv[run * 2 + h2] = *reinterpret_cast<const __attribute__((address_space(3))) f32x4_t *>(
+              smem + 2 * TB + wave * 1024 + qofs + (run * 8 + hf * 4 + h2 * 2) * 8);
+      // which rows this key may not see: rows beyond the block, and (own block) tokens before the key
+      const bool ragged = r0 + kBKeys > n_rows;
+      const int first_tok = (int)fast_div((uint32_t)r0, p.group_div);
+      const bool diagonal = own && first_tok < kw0 + 32;
+      bf16x8_t pf[2], dsf[2];
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        u32x4_t wp, wd;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float pv[2], dsv[2];
+#pragma unroll
+          for (int h2 = 0; h2 < 2; ++h2) {
+            const int v = e * 8 + 2 * j + h2;
+            const f32x4_t two = ldv[(v >> 2) * 2 + ((v & 3) >> 1)];  // (L, delta) of rows v & ~1 and (v & ~1) + 1
+            const float L = (v & 1) ? two[2] : two[0], delta = (v & 1) ? two[3] : two[1];
+            float pr = __builtin_amdgcn_exp2f(sacc[v] - L);
+            const int row = r0 + (v >> 2) * 8 + hf * 4 + (v & 3);
+            if (ragged && row >= n_rows) pr = 0.f;
+            if (diagonal && (int)fast_div((uint32_t)row, p.group_div) < my_key) pr = 0.f;
+            pv[h2] = pr;
+            dsv[h2] = pr * (dpacc[v] - delta);
+          }
+          wp[j] = pack_bf16(pv[0], pv[1]);
+          wd[j] = pack_bf16(dsv[0], dsv[1]);
+        }
+        pf[e] = __builtin_bit_cast(bf16x8_t, wp);
+        dsf[e] = __builtin_bit_cast(bf16x8_t, wd);
+      }
+#pragma unroll
+      for (int kc = 0; kc < 2; ++kc)
+#pragma unroll
+        for (int dt = 0; dt < G::DT; ++dt) {
+          typedef __attribute__((address_space(3))) s16x4_t lds_s16x4;
+          typedef short s16x8_t __attribute__((ext_vector_type(8)));
+          const s16x4_t dlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + (t_rd[0][dt] + dofs) + kc * 16 * G::ROWB));
+          const s16x4_t dhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + (t_rd[1][dt] + dofs) + kc * 16 * G::ROWB));
+          const s16x8_t dboth = __builtin_shufflevector(dlo, dhi, 0, 1, 2, 3, 4, 5, 6, 7);
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, dboth), pf[kc], dv[dt], 0, 0, 0);
+          const s16x4_t qlo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + (t_rd[0][dt] + qofs) + kc * 16 * G::ROWB));
+          const s16x4_t qhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(smem + (t_rd[1][dt] + qofs) + kc * 16 * G::ROWB));
+          const s16x8_t qboth = __builtin_shufflevector(qlo, qhi, 0, 1, 2, 3, 4, 5, 6, 7);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, qboth), dsf[kc], dk[dt], 0, 0, 0);
+        }
+    }
+    buf = buf == kBBuf - 1 ? 0 : buf + 1;
+  }
+
+  // ---- epilogue: dV as it is, dk^ = ln 2 * acc (the q^ tiles carry scale * log2 e), bf16, whole rows ----
+  wg_barrier();
+  int ln = lane;
+  asm volatile("" : "+v"(ln));
+  const int ecol = ln & 31, ehf = ln >> 5;
+  lds_char *stage = smem + wave * (32 * G::ROWB);
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+    for (int dt = 0; dt < G::DT; ++dt)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+        const float m = pass == 0 ? 1.0f : kLn2;
+        const f32x16_t &a = pass == 0 ? dv[dt] : dk[dt];
+        u32x2_t w;
+        w[0] = pack_bf16(a[q4 * 4 + 0] * m, a[q4 * 4 + 1] * m);
+        w[1] = pack_bf16(a[q4 * 4 + 2] * m, a[q4 * 4 + 3] * m);
+        *reinterpret_cast<__attribute__((address_space(3))) u32x2_t *>(stage + tile_ofs<D>(ecol, dt * 4 + q4) + ehf * 8) = w;
+      }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    uint16_t *dst = pass == 0 ? bp.dv : bp.dkr;
+    const int64_t st = pass == 0 ? bp.dv_st : (int64_t)p.n_kv_heads * D, sh = pass == 0 ? bp.dv_sh : (int64_t)D;
+#pragma unroll
+    for (int u = 0; u < G::KCH; ++u) {
+      const int rr = u * G::QRPI + ln / G::CPR;
+      const u32x4_t w = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t *>(stage + tile_ofs<D>(rr, ln % G::CPR));
+      if (kw0 + rr < lk)
+        *reinterpret_cast<u32x4_t *>(dst + (int64_t)(k_tok0 + kw0 + rr) * st + (int64_t)kvh * sh + (ln % G::CPR) * 8) = w;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+template <int D>
+hipError_t launch_dkv_t(const AttnParams &p, const BwdKvMeta &meta, const BwdParams &bp, hipStream_t stream) {
+  const int64_t n_wg = (int64_t)p.total_tiles * p.n_kv_heads;
+  if (n_wg == 0) return hipSuccess;
+  if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
+  constexpr size_t lds = (size_t)kBBuf * (2 * BGeo<D>::TILEB + kBWaves * 1024);
+  static_assert(lds <= 64 * 1024, "fits the default dynamic LDS limit");
+  hipLaunchKernelGGL((bwd_dkv_kernel<D>), dim3((unsigned)n_wg), dim3(kBThreads), lds, stream, p, meta, bp);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_dq_t(const AttnParams &p, const PromptMeta &meta, const BwdParams &bp, hipStream_t stream) {
+  const int64_t n_wg = (int64_t)p.total_tiles * p.n_kv_heads;
+  if (n_wg == 0) return hipSuccess;
+  if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
+  constexpr size_t lds = (size_t)2 * kBBuf * BGeo<D>::TILEB;
+  static_assert(lds <= 64 * 1024, "fits the default dynamic LDS limit");
+  hipLaunchKernelGGL((bwd_dq_kernel<D>), dim3((unsigned)n_wg), dim3(kBThreads), lds, stream, p, meta, bp);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_bwd_delta(const BwdParams &bp, const uint16_t *o, int64_t o_st, int64_t o_sh, const float *lse,
+                            int n_q_heads, int group, int head_dim, hipStream_t stream) {
+  const int64_t rows = bp.T * n_q_heads;
+  if (rows == 0) return hipSuccess;
+  if (head_dim == 128) {
+    const int rpb = 256 / 16;
+    hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256), 0, stream, o, o_st,
+                       o_sh, bp.dout, bp.do_st, bp.do_sh, lse, bp.ld, bp.T, n_q_heads, group);
+  } else if (head_dim == 64) {
+    const int rpb = 256 / 8;
+    hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256), 0, stream, o, o_st,
+                       o_sh, bp.dout, bp.do_st, bp.do_sh, lse, bp.ld, bp.T, n_q_heads, group);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_dkv(const AttnParams &p, const BwdKvMeta &meta, const BwdParams &bp, hipStream_t stream) {
+  if (p.head_dim == 128) return launch_dkv_t<128>(p, meta, bp, stream);
+  if (p.head_dim == 64) return launch_dkv_t<64>(p, meta, bp, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_bwd_dq(const AttnParams &p, const PromptMeta &meta, const BwdParams &bp, hipStream_t stream) {
+  if (p.head_dim == 128) return launch_dq_t<128>(p, meta, bp, stream);
+  if (p.head_dim == 64) return launch_dq_t<64>(p, meta, bp, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace ba

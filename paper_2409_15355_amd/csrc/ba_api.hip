@@ -671,6 +671,230 @@ int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, co
 }
 
 // ------------------------------------------------------------------------------------------
+size_t ba_block_attention_prompts_backward_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
+                                                           const int32_t *cu_blk, const int32_t *block_offsets) {
+  if (!heads || !cu_blk || !block_offsets || n_prompts < 0) return 0;
+  const size_t T = (size_t)block_offsets[cu_blk[n_prompts]];
+  const size_t D = heads->head_dim, hq = heads->n_q_heads, hkv = heads->n_kv_heads;
+  // rotated scaled q, rotated k, (log-sum-exp, delta) per row (+ padding), gradients of the rotated q and k
+  return 2 * align256(T * hq * D * 2) + 2 * align256(T * hkv * D * 2) + align256(T * hq * 8 + 16);
+}
+
+int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
+                                            const ba_tensor *v, const ba_tensor *o, const float *lse,
+                                            const ba_tensor *d_out, const ba_tensor *dq_out,
+                                            const ba_tensor *dk_out, const ba_tensor *dv_out, int32_t n_prompts,
+                                            const int32_t *cu_blk, const int32_t *block_offsets, void *ws,
+                                            size_t ws_bytes, void *stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t rc;
+  if ((rc = check_heads(heads, true))) return rc;
+  if (n_prompts < 0 || !cu_blk) return fail(BA_ERR_INVALID_ARG, "cu_blk: null or negative prompt count");
+  if (cu_blk[0] != 0) return fail(BA_ERR_INVALID_ARG, "cu_blk[0] must be 0");
+  for (int n = 0; n < n_prompts; ++n)
+    if (cu_blk[n + 1] <= cu_blk[n]) return fail(BA_ERR_INVALID_ARG, "prompt %d: at least one block needed", n);
+  const int n_blocks = cu_blk[n_prompts];
+  if ((rc = check_offsets(n_blocks, block_offsets))) return rc;
+  const int D = heads->head_dim, hq = heads->n_q_heads, hkv = heads->n_kv_heads;
+  if ((rc = check_tensor(q, "q", false, D, hq))) return rc;
+  if ((rc = check_tensor(k, "k", false, D, hkv))) return rc;
+  if ((rc = check_tensor(v, "v", false, D, hkv))) return rc;
+  if ((rc = check_tensor(o, "o", false, D, hq))) return rc;
+  if ((rc = check_tensor(d_out, "d_out", false, D, hq))) return rc;
+  if ((rc = check_tensor(dq_out, "dq_out", false, D, hq))) return rc;
+  if ((rc = check_tensor(dk_out, "dk_out", false, D, hkv))) return rc;
+  if ((rc = check_tensor(dv_out, "dv_out", false, D, hkv))) return rc;
+  if (!lse || ((uintptr_t)lse & 3)) return fail(BA_ERR_INVALID_ARG, "lse: null or misaligned");
+  const int64_t T = block_offsets[n_blocks];
+  const int G = hq / hkv;
+  if (T == 0) return BA_OK;
+  int64_t max_len = 0;
+  for (int b = 0; b < n_blocks; ++b) max_len = std::max<int64_t>(max_len, (int64_t)block_offsets[b + 1] - block_offsets[b]);
+  const int64_t widest = std::max(std::max((int64_t)hq * D, d_out->stride_tok), (int64_t)G * std::max((int64_t)D, d_out->stride_head));
+  if (G < 4) return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention needs at least 4 query heads per KV head");
+  if ((max_len + 1) * widest >= 0x40000000 || max_len * G > 0x3fffffff)
+    return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention: a block of %lld tokens at these strides is too long",
+                (long long)max_len);
+  const size_t need = ba_block_attention_prompts_backward_workspace_bytes(heads, n_prompts, cu_blk, block_offsets);
+  if (!ws || ws_bytes < need || ((uintptr_t)ws & 255))
+    return fail(BA_ERR_WORKSPACE, "whole prompts, backward: 256-byte aligned workspace of %zu bytes needed, %zu given",
+                need, ws_bytes);
+  char *wsp = (char *)ws;
+  uint16_t *q_rot = (uint16_t *)wsp;
+  wsp += align256((size_t)T * hq * D * 2);
+  uint16_t *dq_rot = (uint16_t *)wsp;
+  wsp += align256((size_t)T * hq * D * 2);
+  ba_tensor k_rot;
+  k_rot.ptr = wsp;
+  k_rot.stride_head = D;
+  k_rot.stride_tok = (int64_t)hkv * D;
+  k_rot.dtype = BA_DTYPE_BF16;
+  wsp += align256((size_t)T * hkv * D * 2);
+  uint16_t *dk_rot = (uint16_t *)wsp;
+  wsp += align256((size_t)T * hkv * D * 2);
+  float2 *ld = (float2 *)wsp;
+
+  ba::RopeTable rt;
+  build_rope_table(heads, &rt);
+  // positions count from each prompt's first token: one segment per prompt
+  std::vector<int32_t> starts(n_prompts + 1);
+  for (int n = 0; n <= n_prompts; ++n) starts[n] = block_offsets[cu_blk[n]];
+  for (int n0 = 0; n0 < n_prompts; n0 += ba::kRopeMaxSegs) {
+    const int n = std::min(ba::kRopeMaxSegs, n_prompts - n0);
+    if ((rc = run_rope_prepass(heads, rt, q, q_rot, k, &k_rot, n, starts.data() + n0, nullptr, stream))) return rc;
+  }
+
+  ba::BwdParams bp;
+  memset(&bp, 0, sizeof(bp));
+  bp.dout = (const uint16_t *)d_out->ptr;
+  bp.do_st = d_out->stride_tok;
+  bp.do_sh = d_out->stride_head;
+  bp.ld = ld;
+  bp.T = T;
+  bp.dqr = dq_rot;
+  bp.dkr = dk_rot;
+  bp.dv = (uint16_t *)dv_out->ptr;
+  bp.dv_st = dv_out->stride_tok;
+  bp.dv_sh = dv_out->stride_head;
+  bp.scale = heads->softmax_scale > 0.f ? heads->softmax_scale : 1.0f / sqrtf((float)D);
+  hipError_t e;
+  {
+    ProfileScope ps(BA_PROFILE_REENCODE, stream);
+    e = ba::launch_bwd_delta(bp, (const uint16_t *)o->ptr, o->stride_tok, o->stride_head, lse, hq, G, D, stream);
+  }
+  if (e != hipSuccess) return device_fail(e, "backward: delta launch");
+
+  ba::AttnParams ap;
+  memset(&ap, 0, sizeof(ap));
+  ap.q = q_rot;
+  ap.q_st = (int64_t)hq * D;
+  ap.q_sh = D;
+  ap.kf = (const uint16_t *)k_rot.ptr;
+  ap.kf_st = k_rot.stride_tok;
+  ap.kf_sh = k_rot.stride_head;
+  ap.vf = (const uint16_t *)v->ptr;
+  ap.vf_st = v->stride_tok;
+  ap.vf_sh = v->stride_head;
+  ap.n_q_heads = hq;
+  ap.n_kv_heads = hkv;
+  ap.group = G;
+  ap.group_div = ba::make_fast_div((uint32_t)G);
+  ap.head_dim = D;
+  ap.n_splits = 1;
+
+  // non-empty blocks with the first key they see and (for passages) their prompt's last block
+  struct Blk {
+    int32_t start, len, kstart, fin_start, fin_len;
+  };
+  std::vector<Blk> blks;
+  for (int n = 0; n < n_prompts; ++n) {
+    const int last = cu_blk[n + 1] - 1;
+    const int32_t fs = block_offsets[last], fl = block_offsets[last + 1] - fs;
+    for (int b = cu_blk[n]; b <= last; ++b) {
+      const int32_t len = block_offsets[b + 1] - block_offsets[b];
+      if (len == 0) continue;
+      blks.push_back({block_offsets[b], len, b == last ? block_offsets[cu_blk[n]] : block_offsets[b], fs, b == last ? 0 : fl});
+    }
+  }
+  // dq: query rows own the sums; longest key range first
+  std::vector<Blk> by_q = blks;
+  std::stable_sort(by_q.begin(), by_q.end(), [](const Blk &a, const Blk &b) {
+    return (int64_t)a.start + a.len - a.kstart > (int64_t)b.start + b.len - b.kstart;
+  });
+  for (size_t b0 = 0; b0 < by_q.size(); b0 += ba::kEncMaxBlocks) {
+    const int n = (int)std::min<size_t>(ba::kEncMaxBlocks, by_q.size() - b0);
+    ba::PromptMeta meta;
+    memset(&meta, 0, sizeof(meta));
+    meta.n = n;
+    int64_t tiles = 0;
+    for (int i = 0; i < n; ++i) {
+      meta.start[i] = by_q[b0 + i].start;
+      meta.len[i] = by_q[b0 + i].len;
+      meta.kstart[i] = by_q[b0 + i].kstart;
+      meta.tile_start[i] = (int32_t)tiles;
+      tiles += ((int64_t)by_q[b0 + i].len * G + ba::kShortTileRows - 1) / ba::kShortTileRows;
+    }
+    meta.tile_start[n] = (int32_t)tiles;
+    for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta.tile_start[i] = 0x7fffffff;
+    if (tiles == 0 || tiles > 0x3fffffff) continue;
+    ap.total_tiles = (int32_t)tiles;
+    ap.tiles_div = ba::make_fast_div((uint32_t)tiles);
+    {
+      ProfileScope ps(BA_PROFILE_ATTENTION, stream);
+      e = ba::launch_bwd_dq(ap, meta, bp, stream);
+    }
+    if (e != hipSuccess) return device_fail(e, "backward: dq launch");
+  }
+  // dk, dv: keys own the sums; most query rows first
+  std::vector<Blk> by_k = blks;
+  std::stable_sort(by_k.begin(), by_k.end(),
+                   [](const Blk &a, const Blk &b) { return a.len + a.fin_len > b.len + b.fin_len; });
+  for (size_t b0 = 0; b0 < by_k.size(); b0 += ba::kEncMaxBlocks) {
+    const int n = (int)std::min<size_t>(ba::kEncMaxBlocks, by_k.size() - b0);
+    ba::BwdKvMeta meta;
+    memset(&meta, 0, sizeof(meta));
+    meta.n = n;
+    int64_t tiles = 0;
+    for (int i = 0; i < n; ++i) {
+      meta.start[i] = by_k[b0 + i].start;
+      meta.len[i] = by_k[b0 + i].len;
+      meta.fin_start[i] = by_k[b0 + i].fin_start;
+      meta.fin_len[i] = by_k[b0 + i].fin_len;
+      meta.tile_start[i] = (int32_t)tiles;
+      tiles += ((int64_t)by_k[b0 + i].len + ba::kShortTileRows - 1) / ba::kShortTileRows;
+    }
+    meta.tile_start[n] = (int32_t)tiles;
+    if (tiles == 0 || tiles > 0x3fffffff) continue;
+    ap.total_tiles = (int32_t)tiles;
+    ap.tiles_div = ba::make_fast_div((uint32_t)tiles);
+    {
+      ProfileScope ps(BA_PROFILE_ATTENTION, stream);
+      e = ba::launch_bwd_dkv(ap, meta, bp, stream);
+    }
+    if (e != hipSuccess) return device_fail(e, "backward: dk/dv launch");
+  }
+  // back to the un-rotated frame: the pre-pass kernel with the angles negated (scales already applied)
+  for (int n0 = 0; n0 < n_prompts; n0 += ba::kRopeMaxSegs) {
+    const int n = std::min(ba::kRopeMaxSegs, n_prompts - n0);
+    ba::RopeSegs segs;
+    memset(&segs, 0, sizeof(segs));
+    segs.n = n;
+    for (int i = 0; i <= n; ++i) segs.start[i] = starts[n0 + i];
+    const int64_t tokens = (int64_t)segs.start[n] - segs.start[0];
+    if (tokens <= 0) continue;
+    ba::RopePrepassParams pp;
+    memset(&pp, 0, sizeof(pp));
+    pp.q_src = dq_rot;
+    pp.q_st = (int64_t)hq * D;
+    pp.q_sh = D;
+    pp.q_dst = (uint16_t *)dq_out->ptr;
+    pp.qd_st = dq_out->stride_tok;
+    pp.qd_sh = dq_out->stride_head;
+    pp.k_src = dk_rot;
+    pp.k_st = (int64_t)hkv * D;
+    pp.k_sh = D;
+    pp.k_dst = (uint16_t *)dk_out->ptr;
+    pp.kd_st = dk_out->stride_tok;
+    pp.kd_sh = dk_out->stride_head;
+    pp.q_scale = 1.0f;
+    pp.n_q_heads = hq;
+    pp.n_kv_heads = hkv;
+    pp.head_dim = D;
+    pp.layout = heads->rope_layout;
+    pp.heads_per_thread = tokens >= 16384 ? 8 : (tokens >= 2048 ? 2 : 1);
+    pp.do_q = 1;
+    pp.do_k = 1;
+    pp.inverse = 1;
+    {
+      ProfileScope ps(BA_PROFILE_REENCODE, stream);
+      e = ba::launch_rope_prepass(pp, segs, nullptr, nullptr, rt, stream);
+    }
+    if (e != hipSuccess) return device_fail(e, "backward: inverse RoPE launch");
+  }
+  return BA_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 int32_t ba_reencode_positions(const ba_heads *heads, const ba_tensor *k_src, const ba_tensor *k_dst,
                               int32_t n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                               int32_t n_blocks, const int32_t *src_tok_off, const int32_t *dst_tok_off,

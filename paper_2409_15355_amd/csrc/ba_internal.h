@@ -82,6 +82,7 @@ struct RopePrepassParams {
   float *rot_dst;    // [n_rot][D/2][2]: (cos, sin) of rot_angle[b] * theta_j, or null
   int32_t n_rot;
   float *q_table;    // do_q == 2: instead of rotating Q rows, write q_scale * (cos, sin) per token: [tokens][D/2][2]
+  int32_t inverse;   // rotate by minus the angle (the transposed map: gradients back to the un-rotated frame)
 };
 
 // positions (in tokens) by which the rows of the rotation table turn
@@ -165,6 +166,35 @@ struct PromptMeta {
   int32_t tile_start[kEncMaxBlocks + 1];  // in row tiles of kShortTileRows rows; INT_MAX beyond [n]
   int32_t kstart[kEncMaxBlocks];          // token offset of the first visible key
 };
+
+// ---------------------------------------------------------------- backward of whole prompts ----
+struct BwdParams {
+  const uint16_t *dout;  // gradient of the output, [T][n_q_heads][D] with these strides
+  int64_t do_st, do_sh;
+  float2 *ld;            // [n_kv_heads][T][group]: (log-sum-exp / ln 2, delta) of query head kvh * group + g
+  int64_t T;
+  uint16_t *dqr;         // [T][n_q_heads][D]: gradient of the rotated queries
+  uint16_t *dkr;         // [T][n_kv_heads][D]: gradient of the rotated keys
+  uint16_t *dv;          // gradient of the values, with these strides
+  int64_t dv_st, dv_sh;
+  float scale;           // softmax scale
+};
+
+// Owners of keys: blocks in any order, and for a passage the last block of its prompt (whose rows
+// see the passage's keys as well).
+struct BwdKvMeta {
+  int32_t n;
+  int32_t start[kEncMaxBlocks];
+  int32_t len[kEncMaxBlocks];
+  int32_t tile_start[kEncMaxBlocks + 1];  // in key tiles of kShortTileRows keys
+  int32_t fin_start[kEncMaxBlocks];
+  int32_t fin_len[kEncMaxBlocks];          // 0: the block is its prompt's last
+};
+
+hipError_t launch_bwd_delta(const BwdParams &bp, const uint16_t *o, int64_t o_st, int64_t o_sh, const float *lse,
+                            int n_q_heads, int group, int head_dim, hipStream_t stream);
+hipError_t launch_bwd_dq(const AttnParams &p, const PromptMeta &meta, const BwdParams &bp, hipStream_t stream);
+hipError_t launch_bwd_dkv(const AttnParams &p, const BwdKvMeta &meta, const BwdParams &bp, hipStream_t stream);
 
 constexpr int kFinMaxPrompts = 64;
 struct FinalMeta {

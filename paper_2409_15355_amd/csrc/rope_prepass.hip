@@ -89,6 +89,7 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
     else  // half: element e of chunk c pairs with element e of chunk c + CH/2
       j = c * VEC + e;
     sincos_phase(rope_phase(pos, rt.turns[j]), cs[e], sn[e]);
+    if (p.inverse) sn[e] = -sn[e];
     if (scale != 1.0f) {
       cs[e] *= scale;
       sn[e] *= scale;

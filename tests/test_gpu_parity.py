@@ -857,3 +857,48 @@ def test_whole_prompts_config_3_sampled(ba):
                                    [0, tf - t0], th)
         assert_attention_close(og[tf:t1], ref_f, f"whole prompts, query block of prompt {n}")
     assert np.isfinite(lse.cpu().numpy()).all()
+
+
+# --------------------------------------------------------------------------------------------
+# backward of whole prompts
+# --------------------------------------------------------------------------------------------
+def assert_grad_close(got, ref, what):
+    """Gradients are sums of many bf16-rounded products: compare against the tensor's own scale
+    (the output tolerances of the forward pass, relative to the largest reference entry)."""
+    scale = max(1.0, float(np.max(np.abs(ref))))
+    err = np.abs(got - ref) / scale
+    assert float(err.max()) <= 2e-2, f"{what}: max abs err {err.max() * scale:.4g} at scale {scale:.3g}"
+    assert float(err.mean()) <= 2e-3, f"{what}: mean abs err {err.mean() * scale:.4g} at scale {scale:.3g}"
+
+
+@pytest.mark.parametrize("case", PROMPT_CASES, ids=[c[0] for c in PROMPT_CASES])
+@pytest.mark.parametrize("layout", [0, 1])
+def test_whole_prompts_backward_matches_the_gradient_of_the_definition(ba, case, layout):
+    torch = torch_mod()
+    name, hq, hkv, d, base, prompts = case
+    lens = [l for p in prompts for l in p]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cu_blk = np.concatenate([[0], np.cumsum([len(p) for p in prompts])]).astype(np.int32)
+    T = int(offs[-1])
+    qb, kb, vb = gen_qkv(400 + len(name) + layout, T, hq, hkv, d)
+    dob = wl.normal_bf16_bits(440 + len(name) + layout, (T, hq, d))
+    heads = ba.Heads(hq, hkv, d, base, rope_layout=layout)
+    o, _, lse = gpu_prompts(ba, heads, qb, kb, vb, cu_blk, offs, want_k_rot=False)
+    q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+    dq, dk, dv = (torch.full_like(x, float("nan")) for x in (q, k, v))
+    ws = torch.empty(ba.ba_block_attention_prompts_backward_workspace_bytes(heads, cu_blk, offs), dtype=torch.uint8, device="cuda")
+    ba.ba_block_attention_prompts_backward(heads, q, k, v, o, lse, do, dq, dk, dv, cu_blk, offs, ws)
+    torch.cuda.synchronize()
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(base, d)
+    gq, gk, gv = host_f64(dq), host_f64(dk), host_f64(dv)
+    for n in range(len(prompts)):
+        t0, t1 = int(offs[cu_blk[n]]), int(offs[cu_blk[n + 1]])
+        if t1 == t0:
+            continue
+        po = offs[cu_blk[n]:cu_blk[n + 1] + 1] - t0
+        rq, rk, rv, _ = oracle.masked_attention_backward_bruteforce(f(qb[t0:t1]), f(kb[t0:t1]), f(vb[t0:t1]), f(dob[t0:t1]),
+                                                                   po, th, layout=layout)
+        assert_grad_close(gq[t0:t1], rq, f"{name} dq, prompt {n}")
+        assert_grad_close(gk[t0:t1], rk, f"{name} dk, prompt {n}")
+        assert_grad_close(gv[t0:t1], rv, f"{name} dv, prompt {n}")
