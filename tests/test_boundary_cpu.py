@@ -184,3 +184,29 @@ def test_whole_prompts_rejects_bad_arguments_and_sizes_workspace(lib):
         (164 * 128 * 4 + 255) // 256 * 256
     assert ba.ba_block_attention_prompts_workspace_bytes(h, [0, 2], [0, 100, 164], ba.ROPE_NONE) == 0
     assert call(h, [0, 2], [0, 0, 0]) == 0                  # no tokens: legal no-op
+
+
+def test_whole_prompts_backward_rejects_bad_arguments_and_sizes_workspace(lib):
+    h = ba.Heads(32, 8, 128, 500000.0)
+    t = fake()
+    i32 = lambda x: np.asarray(x, dtype=np.int32)
+    p = lambda x: x.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    lse = ctypes.c_void_p(256)
+
+    def call(heads, cu_blk, offs, lse_p=lse, ws=None, wsb=0):
+        cb, of = i32(cu_blk), i32(offs)
+        r = ctypes.byref(t)
+        return lib.ba_block_attention_prompts_backward(ctypes.byref(heads.c), r, r, r, r, lse_p, r, r, r, r, len(cb) - 1,
+                                                       p(cb), p(of), ws, wsb, None)
+
+    assert call(h, [1, 2], [0, 5, 9]) == -1                   # cu_blk[0] != 0
+    assert call(h, [0, 2], [0, 9, 5]) == -1                   # offsets decrease
+    assert call(h, [0, 2], [0, 5, 9], lse_p=None) == -1       # no log-sum-exps
+    assert call(ba.Heads(4, 4, 64), [0, 2], [0, 5, 9]) == -2  # fewer than four query heads per KV head
+    assert call(h, [0, 2], [0, 5, 9]) == -4                   # workspace missing
+    # rotated q and its gradient, rotated k and its gradient, (log-sum-exp, delta) per row + padding
+    T = 164
+    a256 = lambda n: (n + 255) // 256 * 256
+    assert ba.ba_block_attention_prompts_backward_workspace_bytes(h, [0, 2], [0, 100, T]) == \
+        2 * a256(T * 32 * 128 * 2) + 2 * a256(T * 8 * 128 * 2) + a256(T * 32 * 8 + 16)
+    assert call(h, [0, 2], [0, 0, 0]) == 0                    # no tokens: legal no-op

@@ -902,3 +902,40 @@ def test_whole_prompts_backward_matches_the_gradient_of_the_definition(ba, case,
         assert_grad_close(gq[t0:t1], rq, f"{name} dq, prompt {n}")
         assert_grad_close(gk[t0:t1], rk, f"{name} dk, prompt {n}")
         assert_grad_close(gv[t0:t1], rv, f"{name} dv, prompt {n}")
+
+
+def test_whole_prompts_backward_medium_prompts(ba):
+    """Blocks of several key tiles and row tiles (a 700-token passage, a 300-token last block), a
+    second prompt that is one block; every gradient entry against the oracle.  The call is repeated
+    and must give the same bits (no atomics, every sum has one owner)."""
+    torch = torch_mod()
+    hq, hkv, d, base = 8, 2, 128, 500000.0
+    prompts = [[700, 129, 5, 300], [450]]
+    lens = [l for p in prompts for l in p]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cu_blk = np.array([0, 4, 5], dtype=np.int32)
+    T = int(offs[-1])
+    qb, kb, vb = gen_qkv(460, T, hq, hkv, d)
+    dob = wl.normal_bf16_bits(463, (T, hq, d))
+    heads = ba.Heads(hq, hkv, d, base)
+    o, _, lse = gpu_prompts(ba, heads, qb, kb, vb, cu_blk, offs, want_k_rot=False)
+    q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+    ws = torch.empty(ba.ba_block_attention_prompts_backward_workspace_bytes(heads, cu_blk, offs), dtype=torch.uint8, device="cuda")
+    outs = []
+    for _ in range(2):
+        dq, dk, dv = (torch.full_like(x, float("nan")) for x in (q, k, v))
+        ba.ba_block_attention_prompts_backward(heads, q, k, v, o, lse, do, dq, dk, dv, cu_blk, offs, ws)
+        torch.cuda.synchronize()
+        outs.append((host_bits(dq), host_bits(dk), host_bits(dv)))
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(base, d)
+    gq, gk, gv = (oracle.bf16_bits_to_f64(x) for x in outs[0])
+    for n in range(2):
+        t0, t1 = int(offs[cu_blk[n]]), int(offs[cu_blk[n + 1]])
+        po = offs[cu_blk[n]:cu_blk[n + 1] + 1] - t0
+        rq, rk, rv, _ = oracle.masked_attention_backward_bruteforce(f(qb[t0:t1]), f(kb[t0:t1]), f(vb[t0:t1]), f(dob[t0:t1]), po, th)
+        assert_grad_close(gq[t0:t1], rq, f"dq, prompt {n}")
+        assert_grad_close(gk[t0:t1], rk, f"dk, prompt {n}")
+        assert_grad_close(gv[t0:t1], rv, f"dv, prompt {n}")
