@@ -333,7 +333,20 @@ def main() -> int:
             rows_out["whole_prompts_cfg3"] = {"ms": round(ms_w, 4), "algorithmic_TFLOPs": round(4.0 * d * hq * pairs / ms_w / 1e9, 1),
                                               "GBps": round(byts / ms_w / 1e6, 1), "tokens": Tp,
                                               "note": "8 prompts x (20 ragged passages + query block), one call, mask of Section 2.4"}
-            del q, k, v, o, kr, lse, ws_p
+            # ... and its backward pass (five products per visible pair against the forward's two)
+            do = randn_bf16(wl.tensor_seed(3, 63), (Tp, hq, d))
+            dq_, dk_, dv_ = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+            ws_b = torch.empty(ba.ba_block_attention_prompts_backward_workspace_bytes(hp, cu_blk_p, offs_p),
+                               dtype=torch.uint8, device="cuda")
+
+            def bwd():
+                ba.ba_block_attention_prompts_backward(hp, q, k, v, o, lse, do, dq_, dk_, dv_, cu_blk_p, offs_p, ws_b)
+
+            ms_bw, _ = timed(bwd, 20 if args.only == "" else 200, 3)
+            rows_out["whole_prompts_backward_cfg3"] = {"ms": round(ms_bw, 4),
+                                                       "algorithmic_TFLOPs": round(10.0 * d * hq * pairs / ms_bw / 1e9, 1),
+                                                       "note": "gradients of q, k, v for the same prompts; deterministic (no atomics)"}
+            del q, k, v, o, kr, lse, ws_p, do, dq_, dk_, dv_, ws_b
         # Appendix A's workload: a prompt of many small state blocks read straight from the block cache
         if args.only in ("", "smallblocks"):
             rng = np.random.Generator(np.random.Philox(wl.tensor_seed(6, 900)))
