@@ -30,6 +30,7 @@ constexpr int kBWaves = 4;
 constexpr int kBThreads = kBWaves * 64;
 constexpr int kBKeys = 32;  // walked rows (keys, or packed query rows) per tile
 constexpr int kBBuf = 3;    // tile buffers
+constexpr int kKvRows = 32; // packed query rows per tile of the dk/dv kernel
 constexpr float kLn2 = 0.6931471805599453f, kLog2e = 1.4426950408889634f;
 
 template <int D>
@@ -340,14 +341,18 @@ __global__ __launch_bounds__(kBThreads, 2) void bwd_dq_kernel(AttnParams p, Prom
 
 // ---------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kBThreads, 1) void bwd_dkv_kernel(AttnParams p, BwdKvMeta meta, BwdParams bp) {
+__global__ __launch_bounds__(kBThreads, 2) void bwd_dkv_kernel(AttnParams p, BwdKvMeta meta, BwdParams bp) {
   using G = BGeo<D>;
   extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
   lds_char *smem = (lds_char *)smem_generic;
-  // LDS map: buffer b = bytes [b BUFB, (b + 1) BUFB): a q^ tile, a dO tile (32 packed query rows each),
-  // then per wave 1 KB whose first 256 bytes hold the rows' (L / ln 2, delta)
-  constexpr uint32_t TB = G::TILEB;
+  // LDS map: buffer b = bytes [b BUFB, (b + 1) BUFB): a q^ tile, a dO tile (kKvRows packed query rows
+  // each, i.e. RG groups of 32: two independent chains of products per iteration, which a single
+  // wave per SIMD needs to keep the matrix pipe fed), then per wave 1 KB whose first kKvRows * 8
+  // bytes hold the rows' (L / ln 2, delta)
+  constexpr int RG = kKvRows / 32;
+  constexpr uint32_t TB = RG * G::TILEB;
   constexpr uint32_t BUFB = 2 * TB + kBWaves * 1024;
+  constexpr int IPW = RG * G::IPW;  // LDS-direct loads per wave, tile and tensor
 
   uint32_t id = blockIdx.x;
   {
@@ -374,9 +379,9 @@ __global__ __launch_bounds__(kBThreads, 1) void bwd_dkv_kernel(AttnParams p, Bwd
   // ---- query row tiles that see these keys: the block's own rows from the first key's token on,
   //      then every row of the prompt's last block ------------------------------------------------
   const int n_rows_a = lk * Gq, n_rows_f = lf * Gq;
-  const int tile_a0 = (k0 * Gq) / kBKeys;
-  const int n_a = (n_rows_a + kBKeys - 1) / kBKeys - tile_a0;
-  const int n_t = n_a + (n_rows_f + kBKeys - 1) / kBKeys;
+  const int tile_a0 = (k0 * Gq) / kKvRows;
+  const int n_a = (n_rows_a + kKvRows - 1) / kKvRows - tile_a0;
+  const int n_t = n_a + (n_rows_f + kKvRows - 1) / kKvRows;
 
   // ---- this wave's keys as B operands: k^ and v rows, whole, then into fragments through LDS ----
   u32x4_t ld_k[G::KCH], ld_v[G::KCH];
@@ -392,9 +397,10 @@ __global__ __launch_bounds__(kBThreads, 1) void bwd_dkv_kernel(AttnParams p, Bwd
   }
   __builtin_amdgcn_sched_barrier(0);
 
-  uint32_t k_rd[G::KCH];
-#pragma unroll
-  for (int kk = 0; kk < G::KCH; ++kk) k_rd[kk] = tile_ofs<D>(col, kk * 2 + hf);
+  // rows as A operand: row `col`, chunk 2 kk + hf, i.e. byte (32 kk) ^ row_x inside the row (worked
+  // out at each use: eight more address registers would not fit two waves per SIMD)
+  const uint32_t row_b = (uint32_t)col * G::ROWB;
+  const uint32_t row_x = (uint32_t)(hf ^ ((col / G::LPR) & (G::CPR - 1))) << 4;
   uint32_t t_rd[2][G::DT];
   {
     const int trow = hf * 4 + ((lane & 15) >> 2);
@@ -406,33 +412,33 @@ __global__ __launch_bounds__(kBThreads, 1) void bwd_dkv_kernel(AttnParams p, Bwd
     }
   }
 
-  // ---- tile fill: 32 packed query rows of q^ and of dO, and the rows' (L, delta) ---------------------
+  // ---- tile fill: kKvRows packed query rows of q^ and of dO, and the rows' (L, delta) ------------------
   const uint32_t q_st = (uint32_t)p.q_st, q_sh = (uint32_t)p.q_sh, do_st = (uint32_t)bp.do_st, do_sh = (uint32_t)bp.do_sh;
-  const uint32_t lds_copy = (uint32_t)(uintptr_t)smem + wave * G::IPW * 1024;
+  const uint32_t lds_copy = (uint32_t)(uintptr_t)smem + wave * IPW * 1024;
   const uint32_t lds_ld = (uint32_t)(uintptr_t)smem + 2 * TB + wave * 1024;
   auto issue_copy = [&](int t, int buf) __attribute__((always_inline)) {
     const bool own = t < n_a;
-    const int r0 = (own ? tile_a0 + t : t - n_a) * kBKeys;  // first packed row of the tile, inside its block
+    const int r0 = (own ? tile_a0 + t : t - n_a) * kKvRows;  // first packed row of the tile, inside its block
     const int tok0 = own ? k_tok0 : f_tok0;
     const int n_rows = own ? n_rows_a : n_rows_f;
     const char *qb = (const char *)(p.q + (int64_t)tok0 * p.q_st + (int64_t)(kvh * Gq) * p.q_sh);
     const char *db = (const char *)(bp.dout + (int64_t)tok0 * bp.do_st + (int64_t)(kvh * Gq) * bp.do_sh);
 #pragma unroll
-    for (int u = 0; u < G::IPW; ++u) {
-      const int rt = (wave * G::IPW + u) * G::RPI + lane / G::CPR, pos = lane % G::CPR;
+    for (int u = 0; u < IPW; ++u) {
+      const int rt = (wave * IPW + u) * G::RPI + lane / G::CPR, pos = lane % G::CPR;
       const uint32_t r = (uint32_t)min(r0 + rt, n_rows - 1);  // rows beyond the block repeat its last row
       const uint32_t tok = fast_div(r, p.group_div), g = r - tok * (uint32_t)Gq;
       const uint32_t chunk = (uint32_t)(pos ^ ((rt / G::LPR) & (G::CPR - 1))) << 4;
       lds_dma16(qb, (tok * q_st + g * q_sh) * 2u + chunk, lds_copy + (uint32_t)buf * BUFB + u * 1024);
       lds_dma16(db, (tok * do_st + g * do_sh) * 2u + chunk, lds_copy + (uint32_t)buf * BUFB + TB + u * 1024);
     }
-    // (L, delta) of the 32 rows: 256 contiguous bytes in packed-row order; every wave fetches its own
-    // copy (16 lanes' worth; the other lanes re-read the same bytes), so that all waves count alike
+    // (L, delta) of the rows: contiguous in packed-row order, 16 bytes (two rows) per lane; every wave
+    // fetches its own copy (the upper lanes re-read the same bytes), so that all waves count alike
     const char *lb = (const char *)(bp.ld + ((int64_t)kvh * bp.T + tok0) * Gq);
-    const uint32_t r = (uint32_t)min(r0 + (lane & 15) * 2, n_rows - 2 + (n_rows & 1));
+    const uint32_t r = (uint32_t)min(r0 + (lane & (kKvRows / 2 - 1)) * 2, n_rows - 2 + (n_rows & 1));
     lds_dma16(lb, (r & ~1u) * 8u, lds_ld + (uint32_t)buf * BUFB);
   };
-  constexpr int kOpsPerTile = 2 * G::IPW + 1;
+  constexpr int kOpsPerTile = 2 * IPW + 1;
   if (0 < n_t) issue_copy(0, 0);
   if (1 < n_t) issue_copy(1, 1);
   __builtin_amdgcn_sched_barrier(0);
@@ -440,6 +446,7 @@ __global__ __launch_bounds__(kBThreads, 1) void bwd_dkv_kernel(AttnParams p, Bwd
 
   // ---- k^ and v rows -> B-operand fragments through this wave's slice of buffer 2 -------------------
   static_assert(kBWaves * 16 * G::ROWB <= 2 * TB, "the slices fit the tiles of one buffer");
+  static_assert(kKvRows * 8 <= 1024 && kKvRows / 2 <= 64, "a wave's (L, delta) copy fits its 1 KB");
   const uint32_t s_ofs = 2 * BUFB + wave * (16 * G::ROWB);
   auto rows_to_frags = [&](const u32x4_t (&ld)[G::KCH], bf16x8_t (&out)[G::KCH]) __attribute__((always_inline)) {
     u32x4_t got[2][G::KCH];
@@ -484,64 +491,74 @@ __global__ __launch_bounds__(kBThreads, 1) void bwd_dkv_kernel(AttnParams p, Bwd
     wg_barrier();
     if (i + 2 < n_t) issue_copy(i + 2, buf == 0 ? 2 : buf - 1);
     const bool own = i < n_a;
-    const int r0 = (own ? tile_a0 + i : i - n_a) * kBKeys;
+    const int r0 = (own ? tile_a0 + i : i - n_a) * kKvRows;
     const int n_rows = own ? n_rows_a : n_rows_f;
     // a tile of the block's own rows whose tokens all lie before this wave's first key sees none of them
-    const int last_tok = (int)fast_div((uint32_t)min(r0 + kBKeys - 1, n_rows - 1), p.group_div);
+    const int last_tok = (int)fast_div((uint32_t)min(r0 + kKvRows - 1, n_rows - 1), p.group_div);
     if (wave_has_keys && !(own && last_tok < kw0)) {
       const uint32_t qofs = (uint32_t)buf * BUFB, dofs = qofs + TB;
-      f32x16_t sacc, dpacc;
+      uint32_t rx = row_x;
+      asm volatile("" : "+v"(rx));  // (keeps the eight offsets below from being carried through the loop)
+      // The accumulators start at minus the rows' log-sum-exp and minus their delta, so that the
+      // products come out as the exponent of P and as dP - delta.  Register v of an accumulator is
+      // row (v >> 2) * 8 + hf * 4 + (v & 3) of the group: four runs of four rows, two pairs per 16 bytes.
+      f32x16_t sacc[RG], dpacc[RG];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        sacc[v] = 0.f;
-        dpacc[v] = 0.f;
-      }
+      for (int rg = 0; rg < RG; ++rg)
 #pragma unroll
-      for (int kk = 0; kk < G::KCH; ++kk) {
-        const bf16x8_t qfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(smem + (k_rd[kk] + qofs));
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfrag, kf[kk], sacc, 0, 0, 0);
-        const bf16x8_t dfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(smem + (k_rd[kk] + dofs));
-        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dfrag, vf[kk], dpacc, 0, 0, 0);
-      }
-      // register v of an accumulator is tile row (v >> 2) * 8 + hf * 4 + (v & 3): four runs of four rows
-      f32x4_t ldv[8];
-#pragma unroll
-      for (int run = 0; run < 4; ++run)
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
-          ldv[run * 2 + h2] = *reinterpret_cast<const __attribute__((address_space(3))) f32x4_t *>(
-              smem + 2 * TB + wave * 1024 + qofs + (run * 8 + hf * 4 + h2 * 2) * 8);
-      // which rows this key may not see: rows beyond the block, and (own block) tokens before the key
-      const bool ragged = r0 + kBKeys > n_rows;
-      const int first_tok = (int)fast_div((uint32_t)r0, p.group_div);
-      const bool diagonal = own && first_tok < kw0 + 32;
-      bf16x8_t pf[2], dsf[2];
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        u32x4_t wp, wd;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float pv[2], dsv[2];
+        for (int run = 0; run < 4; ++run)
 #pragma unroll
           for (int h2 = 0; h2 < 2; ++h2) {
-            const int v = e * 8 + 2 * j + h2;
-            const f32x4_t two = ldv[(v >> 2) * 2 + ((v & 3) >> 1)];  // (L, delta) of rows v & ~1 and (v & ~1) + 1
-            const float L = (v & 1) ? two[2] : two[0], delta = (v & 1) ? two[3] : two[1];
-            float pr = __builtin_amdgcn_exp2f(sacc[v] - L);
-            const int row = r0 + (v >> 2) * 8 + hf * 4 + (v & 3);
-            if (ragged && row >= n_rows) pr = 0.f;
-            if (diagonal && (int)fast_div((uint32_t)row, p.group_div) < my_key) pr = 0.f;
-            pv[h2] = pr;
-            dsv[h2] = pr * (dpacc[v] - delta);
+            const f32x4_t two = *reinterpret_cast<const __attribute__((address_space(3))) f32x4_t *>(
+                smem + 2 * TB + wave * 1024 + qofs + (rg * 32 + run * 8 + hf * 4 + h2 * 2) * 8);
+            sacc[rg][run * 4 + h2 * 2] = -two[0];
+            dpacc[rg][run * 4 + h2 * 2] = -two[1];
+            sacc[rg][run * 4 + h2 * 2 + 1] = -two[2];
+            dpacc[rg][run * 4 + h2 * 2 + 1] = -two[3];
           }
-          wp[j] = pack_bf16(pv[0], pv[1]);
-          wd[j] = pack_bf16(dsv[0], dsv[1]);
+#pragma unroll
+      for (int kk = 0; kk < G::KCH; ++kk)
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) {
+          const bf16x8_t qfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(
+              smem + (row_b + (((uint32_t)kk * 32u) ^ rx) + qofs) + rg * 32 * G::ROWB);
+          sacc[rg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfrag, kf[kk], sacc[rg], 0, 0, 0);
+          const bf16x8_t dfrag = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8_t *>(
+              smem + (row_b + (((uint32_t)kk * 32u) ^ rx) + dofs) + rg * 32 * G::ROWB);
+          dpacc[rg] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dfrag, vf[kk], dpacc[rg], 0, 0, 0);
         }
-        pf[e] = __builtin_bit_cast(bf16x8_t, wp);
-        dsf[e] = __builtin_bit_cast(bf16x8_t, wd);
+      // which rows this key may not see: rows beyond the block, and (own block) tokens before the key
+      const bool ragged = r0 + kKvRows > n_rows;
+      const int first_tok = (int)fast_div((uint32_t)r0, p.group_div);
+      const bool diagonal = own && first_tok < kw0 + 32;
+      bf16x8_t pf[2 * RG], dsf[2 * RG];
+#pragma unroll
+      for (int rg = 0; rg < RG; ++rg) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          u32x4_t wp, wd;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            float pv[2], dsv[2];
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+              const int v = e * 8 + 2 * j + h2;
+              float pr = __builtin_amdgcn_exp2f(sacc[rg][v]);
+              const int row = r0 + rg * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+              if (ragged && row >= n_rows) pr = 0.f;
+              if (diagonal && (int)fast_div((uint32_t)row, p.group_div) < my_key) pr = 0.f;
+              pv[h2] = pr;
+              dsv[h2] = pr * dpacc[rg][v];
+            }
+            wp[j] = pack_bf16(pv[0], pv[1]);
+            wd[j] = pack_bf16(dsv[0], dsv[1]);
+          }
+          pf[rg * 2 + e] = __builtin_bit_cast(bf16x8_t, wp);
+          dsf[rg * 2 + e] = __builtin_bit_cast(bf16x8_t, wd);
+        }
       }
 #pragma unroll
-      for (int kc = 0; kc < 2; ++kc)
+      for (int kc = 0; kc < 2 * RG; ++kc)
 #pragma unroll
         for (int dt = 0; dt < G::DT; ++dt) {
           typedef __attribute__((address_space(3))) s16x4_t lds_s16x4;
@@ -602,8 +619,15 @@ hipError_t launch_dkv_t(const AttnParams &p, const BwdKvMeta &meta, const BwdPar
   const int64_t n_wg = (int64_t)p.total_tiles * p.n_kv_heads;
   if (n_wg == 0) return hipSuccess;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
-  constexpr size_t lds = (size_t)kBBuf * (2 * BGeo<D>::TILEB + kBWaves * 1024);
-  static_assert(lds <= 64 * 1024, "fits the default dynamic LDS limit");
+  constexpr size_t lds = (size_t)kBBuf * (2 * (kKvRows / 32) * BGeo<D>::TILEB + kBWaves * 1024);
+  static_assert(lds <= 160 * 1024, "gfx950 has 160 KB of LDS per workgroup");
+  static bool raised = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
+  if (!raised && lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
   hipLaunchKernelGGL((bwd_dkv_kernel<D>), dim3((unsigned)n_wg), dim3(kBThreads), lds, stream, p, meta, bp);
   return hipGetLastError();
 }
