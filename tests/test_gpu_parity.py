@@ -939,3 +939,51 @@ def test_whole_prompts_backward_medium_prompts(ba):
         assert_grad_close(gq[t0:t1], rq, f"dq, prompt {n}")
         assert_grad_close(gk[t0:t1], rk, f"dk, prompt {n}")
         assert_grad_close(gv[t0:t1], rv, f"dv, prompt {n}")
+
+
+def test_calls_can_be_captured_in_a_hip_graph(ba):
+    """The library only enqueues kernels on the caller's stream (no allocation, no copy, no
+    synchronisation), so a sequence of calls can be captured and replayed: several replays, with
+    eager work and synchronisations in between, give the eager result bit for bit."""
+    torch = torch_mod()
+    w = wl.config2()
+    hq, hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
+    offs = w.passage_block_offsets()
+    T, lq = int(offs[-1]), w.prompts[0].final_len
+    qb, kb, vb = gen_qkv(500, T, hq, hkv, d)
+    qfb, kfb, vfb = gen_qkv(503, lq, hq, hkv, d)
+    heads = heads_of(ba, w)
+    q, k, v, qf, kf, vf = (dev_bf16(x) for x in (qb, kb, vb, qfb, kfb, vfb))
+    o_p, k_local, k_ctx = torch.empty_like(q), torch.empty_like(k), torch.empty_like(k)
+    o_f = torch.empty_like(qf)
+    cu_q, cu_ctx = w.cu_q(), w.cu_ctx()
+    ws_e = torch.empty(ba.ba_encode_blocks_workspace_bytes(heads, offs, 1, True), dtype=torch.uint8, device="cuda")
+    ws_f = torch.empty(ba.ba_final_block_attention_workspace_bytes(heads, cu_q, cu_ctx), dtype=torch.uint8, device="cuda")
+    lens, new_pos0 = np.diff(offs), w.passage_new_pos0()
+
+    def pipeline():
+        ba.ba_encode_blocks(heads, q, k, v, o_p, k_local, offs, 1, ws_e)
+        ba.ba_reencode_positions(heads, k_local, k_ctx, offs[:-1], offs[:-1], lens, None, new_pos0, ba.REENC_SHIFT)
+        ba.ba_final_block_attention(heads, qf, k_ctx, v, kf, vf, o_f, None, cu_q, cu_ctx, None, 1, ws_f)
+
+    pipeline()
+    torch.cuda.synchronize()
+    ref = (o_p.clone(), k_ctx.clone(), o_f.clone())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pipeline()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pipeline()
+    for rep in range(3):
+        for t in (o_p, k_ctx, o_f):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((o_p, k_ctx, o_f), ref):
+            assert torch.equal(got, want), f"replay {rep}"
+        pipeline()  # eager work between the replays
+        torch.cuda.synchronize()
