@@ -987,3 +987,37 @@ def test_calls_can_be_captured_in_a_hip_graph(ba):
             assert torch.equal(got, want), f"replay {rep}"
         pipeline()  # eager work between the replays
         torch.cuda.synchronize()
+
+
+def test_whole_prompts_many_tiny_blocks_forward_and_backward(ba):
+    """More blocks than one launch's table holds (two prompts of 230 blocks of 1 to 9 tokens each):
+    the host cuts the list into several launches; outputs and gradients against the oracle."""
+    torch = torch_mod()
+    hq, hkv, d, base = 4, 1, 64, 10000.0
+    rng = np.random.default_rng(91)
+    prompts = [rng.integers(1, 10, 230).tolist(), rng.integers(1, 10, 230).tolist()]
+    lens = [l for p in prompts for l in p]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cu_blk = np.array([0, 230, 460], dtype=np.int32)
+    T = int(offs[-1])
+    qb, kb, vb = gen_qkv(520, T, hq, hkv, d)
+    dob = wl.normal_bf16_bits(523, (T, hq, d))
+    heads = ba.Heads(hq, hkv, d, base)
+    o, _, lse = gpu_prompts(ba, heads, qb, kb, vb, cu_blk, offs, want_k_rot=False)
+    q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+    dq, dk, dv = (torch.full_like(x, float("nan")) for x in (q, k, v))
+    ws = torch.empty(ba.ba_block_attention_prompts_backward_workspace_bytes(heads, cu_blk, offs), dtype=torch.uint8, device="cuda")
+    ba.ba_block_attention_prompts_backward(heads, q, k, v, o, lse, do, dq, dk, dv, cu_blk, offs, ws)
+    torch.cuda.synchronize()
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(base, d)
+    og, gq, gk, gv = host_f64(o), host_f64(dq), host_f64(dk), host_f64(dv)
+    for n in range(2):
+        t0, t1 = int(offs[cu_blk[n]]), int(offs[cu_blk[n + 1]])
+        po = offs[cu_blk[n]:cu_blk[n + 1] + 1] - t0
+        ref = oracle.masked_attention_bruteforce(f(qb[t0:t1]), f(kb[t0:t1]), f(vb[t0:t1]), po, th)
+        assert_attention_close(og[t0:t1], ref, f"many tiny blocks, prompt {n}")
+        rq, rk, rv, _ = oracle.masked_attention_backward_bruteforce(f(qb[t0:t1]), f(kb[t0:t1]), f(vb[t0:t1]), f(dob[t0:t1]), po, th)
+        assert_grad_close(gq[t0:t1], rq, f"dq, prompt {n}")
+        assert_grad_close(gk[t0:t1], rk, f"dk, prompt {n}")
+        assert_grad_close(gv[t0:t1], rv, f"dv, prompt {n}")
