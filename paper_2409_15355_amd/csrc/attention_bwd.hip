@@ -54,31 +54,6 @@ __device__ __forceinline__ uint32_t tile_ofs(int row, int chunk) {
   return (uint32_t)(row * G::ROWB + ((chunk ^ ((row / G::LPR) & (G::CPR - 1))) << 4));
 }
 
-// delta and the log-sum-exp in the order the kernels want them: ld[kvh][token][g] = (L / ln 2, delta)
-// for query head kvh * G + g, i.e. contiguous in packed-row order for a fixed KV head.
-template <int D>
-__global__ __launch_bounds__(256) void bwd_delta_kernel(const uint16_t *o, int64_t o_st, int64_t o_sh, const uint16_t *dout,
-                                                        int64_t do_st, int64_t do_sh, const float *lse, float2 *ld,
-                                                        int64_t T, int n_q_heads, int group) {
-  constexpr int TPR = D / 8;  // threads per (token, head) row, 8 elements each
-  const int64_t row = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
-  if (row >= T * n_q_heads) return;  // (whole groups of TPR lanes leave together)
-  const int64_t t = row / n_q_heads;
-  const int h = (int)(row - t * n_q_heads);
-  const int c = threadIdx.x % TPR;
-  const u32x4_t a = *reinterpret_cast<const u32x4_t *>(o + t * o_st + (int64_t)h * o_sh + c * 8);
-  const u32x4_t b = *reinterpret_cast<const u32x4_t *>(dout + t * do_st + (int64_t)h * do_sh + c * 8);
-  float s = 0.f;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) s += bf16_lo(a[e]) * bf16_lo(b[e]) + bf16_hi(a[e]) * bf16_hi(b[e]);
-#pragma unroll
-  for (int m = 1; m < TPR; m <<= 1) s += __shfl_xor(s, m, 64);
-  if (c == 0) {
-    const int kvh = h / group, g = h - kvh * group;
-    ld[((int64_t)kvh * T + t) * group + g] = make_float2(lse[row] * kLog2e, s);
-  }
-}
-
 // ---------------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kBThreads, 2) void bwd_dq_kernel(AttnParams p, PromptMeta meta, BwdParams bp) {
@@ -159,8 +134,18 @@ __global__ __launch_bounds__(kBThreads, 2) void bwd_dq_kernel(AttnParams p, Prom
       ld_do[u] = *reinterpret_cast<const u32x4_t *>(dbase + (o * 2u + (uint32_t)(lane % G::CPR) * 16u));
     });
   }
-  // this lane's row: log-sum-exp (base-2 units) and delta
-  const float2 my_ld = bp.ld[((int64_t)kvh * bp.T + q_tok0 + my_tok) * Gq + (my_row - my_tok * Gq)];
+  // ... and of O, for delta = rowsum(dO o O); this lane's row's log-sum-exp (to base-2 units below)
+  u32x4_t ld_o[G::KCH];
+  {
+    const char *obase = (const char *)(bp.o + (int64_t)q_tok0 * bp.o_st + (int64_t)(kvh * Gq) * bp.o_sh);
+    const uint32_t st = (uint32_t)bp.o_st, sh = (uint32_t)bp.o_sh;
+    const uint32_t last_off = (uint32_t)(lq - 1) * st + (uint32_t)(Gq - 1) * sh;
+    walk_rows(st, sh, [&](int u, uint32_t off, int wr_r0) __attribute__((always_inline)) {
+      const uint32_t o = wr_r0 < n_rows - u * G::QRPI ? off : last_off;
+      ld_o[u] = *reinterpret_cast<const u32x4_t *>(obase + (o * 2u + (uint32_t)(lane % G::CPR) * 16u));
+    });
+  }
+  const float my_lse = bp.lse[(int64_t)(q_tok0 + my_tok) * p.n_q_heads + kvh * Gq + (my_row - my_tok * Gq)];
   __builtin_amdgcn_sched_barrier(0);
 
   // ---- per-lane LDS read offsets inside a tile ---------------------------------------------------
@@ -234,6 +219,27 @@ __global__ __launch_bounds__(kBThreads, 2) void bwd_dq_kernel(AttnParams p, Prom
       out[kk] = __builtin_bit_cast(bf16x8_t, w);
     }
   };
+  // delta of this wave's rows: a row's CPR lanes add up their pieces, one of them hands the sum over
+  // through the slice to the lane that owns the row; the pair (L / ln 2, delta) also goes to memory in
+  // packed-row order per KV head, where the dk/dv kernel finds the 32 pairs of a row tile side by side
+  float2 my_ld;
+  {
+#pragma unroll
+    for (int u = 0; u < G::KCH; ++u) {
+      float part = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        part += bf16_lo(ld_o[u][e]) * bf16_lo(ld_do[u][e]) + bf16_hi(ld_o[u][e]) * bf16_hi(ld_do[u][e]);
+#pragma unroll
+      for (int m = 1; m < G::CPR; m <<= 1) part += __shfl_xor(part, m, 64);
+      if (lane % G::CPR == 0)
+        *reinterpret_cast<__attribute__((address_space(3))) float *>(smem + s_ofs + (u * G::QRPI + lane / G::CPR) * 4) = part;
+    }
+    const int r_in_wave = min(col, max(wave_last_row - wave_row0, 0));  // (lanes beyond the block's rows: its last row)
+    my_ld.y = *reinterpret_cast<const __attribute__((address_space(3))) float *>(smem + s_ofs + r_in_wave * 4);
+    my_ld.x = my_lse * kLog2e;
+    if (hf == 0 && wave_row0 + col < n_rows) bp.ld[((int64_t)kvh * bp.T + q_tok0) * Gq + wave_row0 + col] = my_ld;
+  }
   bf16x8_t qf[G::KCH], dof[G::KCH];
   rows_to_frags(ld_q, qf);
   rows_to_frags(ld_do, dof);
@@ -644,24 +650,6 @@ hipError_t launch_dq_t(const AttnParams &p, const PromptMeta &meta, const BwdPar
 }
 
 }  // namespace
-
-hipError_t launch_bwd_delta(const BwdParams &bp, const uint16_t *o, int64_t o_st, int64_t o_sh, const float *lse,
-                            int n_q_heads, int group, int head_dim, hipStream_t stream) {
-  const int64_t rows = bp.T * n_q_heads;
-  if (rows == 0) return hipSuccess;
-  if (head_dim == 128) {
-    const int rpb = 256 / 16;
-    hipLaunchKernelGGL((bwd_delta_kernel<128>), dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256), 0, stream, o, o_st,
-                       o_sh, bp.dout, bp.do_st, bp.do_sh, lse, bp.ld, bp.T, n_q_heads, group);
-  } else if (head_dim == 64) {
-    const int rpb = 256 / 8;
-    hipLaunchKernelGGL((bwd_delta_kernel<64>), dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(256), 0, stream, o, o_st,
-                       o_sh, bp.dout, bp.do_st, bp.do_sh, lse, bp.ld, bp.T, n_q_heads, group);
-  } else {
-    return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
-}
 
 hipError_t launch_bwd_dkv(const AttnParams &p, const BwdKvMeta &meta, const BwdParams &bp, hipStream_t stream) {
   if (p.head_dim == 128) return launch_dkv_t<128>(p, meta, bp, stream);

@@ -710,7 +710,8 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   if (T == 0) return BA_OK;
   int64_t max_len = 0;
   for (int b = 0; b < n_blocks; ++b) max_len = std::max<int64_t>(max_len, (int64_t)block_offsets[b + 1] - block_offsets[b]);
-  const int64_t widest = std::max(std::max((int64_t)hq * D, d_out->stride_tok), (int64_t)G * std::max((int64_t)D, d_out->stride_head));
+  const int64_t widest = std::max(std::max((int64_t)hq * D, std::max(d_out->stride_tok, o->stride_tok)),
+                                  (int64_t)G * std::max((int64_t)D, std::max(d_out->stride_head, o->stride_head)));
   if (G < 4) return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention needs at least 4 query heads per KV head");
   if ((max_len + 1) * widest >= 0x40000000 || max_len * G > 0x3fffffff)
     return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention: a block of %lld tokens at these strides is too long",
@@ -749,6 +750,10 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   bp.dout = (const uint16_t *)d_out->ptr;
   bp.do_st = d_out->stride_tok;
   bp.do_sh = d_out->stride_head;
+  bp.o = (const uint16_t *)o->ptr;
+  bp.o_st = o->stride_tok;
+  bp.o_sh = o->stride_head;
+  bp.lse = lse;
   bp.ld = ld;
   bp.T = T;
   bp.dqr = dq_rot;
@@ -758,11 +763,6 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   bp.dv_sh = dv_out->stride_head;
   bp.scale = heads->softmax_scale > 0.f ? heads->softmax_scale : 1.0f / sqrtf((float)D);
   hipError_t e;
-  {
-    ProfileScope ps(BA_PROFILE_REENCODE, stream);
-    e = ba::launch_bwd_delta(bp, (const uint16_t *)o->ptr, o->stride_tok, o->stride_head, lse, hq, G, D, stream);
-  }
-  if (e != hipSuccess) return device_fail(e, "backward: delta launch");
 
   ba::AttnParams ap;
   memset(&ap, 0, sizeof(ap));

@@ -171,7 +171,11 @@ struct PromptMeta {
 struct BwdParams {
   const uint16_t *dout;  // gradient of the output, [T][n_q_heads][D] with these strides
   int64_t do_st, do_sh;
-  float2 *ld;            // [n_kv_heads][T][group]: (log-sum-exp / ln 2, delta) of query head kvh * group + g
+  const uint16_t *o;     // the forward output, [T][n_q_heads][D] with these strides
+  int64_t o_st, o_sh;
+  const float *lse;      // [T][n_q_heads]: the forward pass's log-sum-exps
+  float2 *ld;            // [n_kv_heads][T][group]: (log-sum-exp / ln 2, delta) of query head kvh * group + g,
+                         // written by the dq kernel, read by the dk/dv kernel
   int64_t T;
   uint16_t *dqr;         // [T][n_q_heads][D]: gradient of the rotated queries
   uint16_t *dkr;         // [T][n_kv_heads][D]: gradient of the rotated keys
@@ -191,8 +195,6 @@ struct BwdKvMeta {
   int32_t fin_len[kEncMaxBlocks];          // 0: the block is its prompt's last
 };
 
-hipError_t launch_bwd_delta(const BwdParams &bp, const uint16_t *o, int64_t o_st, int64_t o_sh, const float *lse,
-                            int n_q_heads, int group, int head_dim, hipStream_t stream);
 hipError_t launch_bwd_dq(const AttnParams &p, const PromptMeta &meta, const BwdParams &bp, hipStream_t stream);
 hipError_t launch_bwd_dkv(const AttnParams &p, const BwdKvMeta &meta, const BwdParams &bp, hipStream_t stream);
 
