@@ -10,8 +10,9 @@
 //   - bwd_dkv_kernel: a workgroup owns 128 keys of one block and KV head and walks the 32-row
 //     query tiles that see them (the rest of its own block, and the prompt's last block if it is a
 //     passage); it accumulates dk^ and dV over all query heads of the group.
-// Both write gradients in the rotated frame; the RoPE pre-pass kernel, run backwards, turns dq^ and
-// dk^ into dq and dk (Eq. 1 is orthogonal: the transposed map is the rotation by minus the angle).
+// Each turns its gradient of the rotated tensor back to the un-rotated frame in its epilogue, with the
+// (cos, sin) table of the RoPE pre-pass (Eq. 1 is orthogonal: the transposed map is the rotation by
+// minus the angle).
 //
 // Operand layouts are the forward kernel's: products are computed transposed with
 // v_mfma_f32_32x32x16_bf16, the owner's side along lanes and in registers as B operands, the
@@ -52,6 +53,49 @@ template <int D>
 __device__ __forceinline__ uint32_t tile_ofs(int row, int chunk) {
   using G = BGeo<D>;
   return (uint32_t)(row * G::ROWB + ((chunk ^ ((row / G::LPR) & (G::CPR - 1))) << 4));
+}
+
+// A gradient in the rotated frame, held in accumulator layout (lane = row `col`, register v of slab dt =
+// head dim 32 dt + (v >> 2) * 8 + hf * 4 + (v & 3)), turned back to the un-rotated frame: the
+// transposed map of Eq. 1, [x', y'] = [c x + s y, -s x + c y] per pair, times `mul`.  tab = the row's
+// entry of the pre-pass's table, (cos, sin) per pair times some factor that `mul` takes out again.
+template <int D>
+__device__ __forceinline__ void rotate_back(f32x16_t (&acc)[D / 32], const f32x4_t *tab, int hf, bool halves, float mul) {
+  constexpr int DT = D / 32;
+  if (!halves) {
+    // pairs (d, d + 1): the four values of (dt, q4) are pairs 2 m and 2 m + 1 with m = dt * 8 + q4 * 2 + hf
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4_t t = tab[dt * 8 + q4 * 2 + hf];
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          const float c = t[2 * h2] * mul, sn = t[2 * h2 + 1] * mul;
+          const float x = acc[dt][q4 * 4 + 2 * h2], y = acc[dt][q4 * 4 + 2 * h2 + 1];
+          acc[dt][q4 * 4 + 2 * h2] = c * x + sn * y;
+          acc[dt][q4 * 4 + 2 * h2 + 1] = c * y - sn * x;
+        }
+      }
+  } else {
+    // pairs (d, d + D/2): slab dt pairs with slab dt + DT/2; the four values of (dt, q4) are pairs
+    // j .. j + 3 with j = dt * 32 + q4 * 8 + hf * 4
+#pragma unroll
+    for (int dt = 0; dt < DT / 2; ++dt)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          const f32x4_t t = tab[(dt * 32 + q4 * 8 + hf * 4) / 2 + h2];
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const float c = t[2 * e] * mul, sn = t[2 * e + 1] * mul;
+            const float x = acc[dt][q4 * 4 + 2 * h2 + e], y = acc[dt + DT / 2][q4 * 4 + 2 * h2 + e];
+            acc[dt][q4 * 4 + 2 * h2 + e] = c * x + sn * y;
+            acc[dt + DT / 2][q4 * 4 + 2 * h2 + e] = c * y - sn * x;
+          }
+        }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -311,11 +355,15 @@ __global__ __launch_bounds__(kBThreads, 2) void bwd_dq_kernel(AttnParams p, Prom
     buf = buf == kBBuf - 1 ? 0 : buf + 1;
   }
 
-  // ---- epilogue: dq^ = scale * acc, bf16, as whole rows through each wave's slice of LDS ------------
+  // ---- epilogue: dq^ = scale * acc, turned back to dq with the row's entry of the pre-pass's table
+  //      (which carries scale * log2 e: scale / (scale * log2 e) = ln 2 remains), bf16, as whole rows
+  //      through each wave's slice of LDS -------------------------------------------------------------
   wg_barrier();
   int ln = lane;
   asm volatile("" : "+v"(ln));
   const int ecol = ln & 31, ehf = ln >> 5;
+  rotate_back<D>(acc, reinterpret_cast<const f32x4_t *>(p.q_table + (int64_t)(q_tok0 + my_tok) * D), ehf,
+                 p.rope_layout != 0, kLn2);
   lds_char *stage = smem + wave * (32 * G::ROWB);
 #pragma unroll
   for (int dt = 0; dt < G::DT; ++dt)
@@ -323,8 +371,8 @@ __global__ __launch_bounds__(kBThreads, 2) void bwd_dq_kernel(AttnParams p, Prom
     for (int q4 = 0; q4 < 4; ++q4) {
       typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
       u32x2_t w;
-      w[0] = pack_bf16(acc[dt][q4 * 4 + 0] * bp.scale, acc[dt][q4 * 4 + 1] * bp.scale);
-      w[1] = pack_bf16(acc[dt][q4 * 4 + 2] * bp.scale, acc[dt][q4 * 4 + 3] * bp.scale);
+      w[0] = pack_bf16(acc[dt][q4 * 4 + 0], acc[dt][q4 * 4 + 1]);
+      w[1] = pack_bf16(acc[dt][q4 * 4 + 2], acc[dt][q4 * 4 + 3]);
       *reinterpret_cast<__attribute__((address_space(3))) u32x2_t *>(stage + tile_ofs<D>(ecol, dt * 4 + q4) + ehf * 8) = w;
     }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -336,9 +384,8 @@ __global__ __launch_bounds__(kBThreads, 2) void bwd_dq_kernel(AttnParams p, Prom
     for (int u = 0; u < G::KCH; ++u)
       w[u] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t *>(
           stage + tile_ofs<D>(u * G::QRPI + ln / G::CPR, ln % G::CPR));
-    // dq^ rows are packed [token][query head][D]
-    char *obase = (char *)(bp.dqr + ((int64_t)q_tok0 * p.n_q_heads + kvh * Gq) * D);
-    walk_rows((uint32_t)(p.n_q_heads * D), (uint32_t)D, [&](int u, uint32_t off, int wr_r0) __attribute__((always_inline)) {
+    char *obase = (char *)(bp.dq + (int64_t)q_tok0 * bp.dq_st + (int64_t)(kvh * Gq) * bp.dq_sh);
+    walk_rows((uint32_t)bp.dq_st, (uint32_t)bp.dq_sh, [&](int u, uint32_t off, int wr_r0) __attribute__((always_inline)) {
       if (wr_r0 < n_rows - u * G::QRPI)
         *reinterpret_cast<u32x4_t *>(obase + (off * 2u + (uint32_t)(ln % G::CPR) * 16u)) = w[u];
     });
@@ -582,11 +629,15 @@ __global__ __launch_bounds__(kBThreads, 2) void bwd_dkv_kernel(AttnParams p, Bwd
     buf = buf == kBBuf - 1 ? 0 : buf + 1;
   }
 
-  // ---- epilogue: dV as it is, dk^ = ln 2 * acc (the q^ tiles carry scale * log2 e), bf16, whole rows ----
+  // ---- epilogue: dV as it is; dk^ = ln 2 * acc (the q^ tiles carry scale * log2 e), turned back to dk
+  //      with the key's entry of the pre-pass's table (which carries scale * log2 e once more); bf16,
+  //      whole rows ------------------------------------------------------------------------------------
   wg_barrier();
   int ln = lane;
   asm volatile("" : "+v"(ln));
   const int ecol = ln & 31, ehf = ln >> 5;
+  rotate_back<D>(dk, reinterpret_cast<const f32x4_t *>(p.q_table + (int64_t)(k_tok0 + min(kw0 + ecol, lk - 1)) * D), ehf,
+                 p.rope_layout != 0, kLn2 / p.scale_log2e);
   lds_char *stage = smem + wave * (32 * G::ROWB);
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
@@ -595,18 +646,17 @@ __global__ __launch_bounds__(kBThreads, 2) void bwd_dkv_kernel(AttnParams p, Bwd
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-        const float m = pass == 0 ? 1.0f : kLn2;
         const f32x16_t &a = pass == 0 ? dv[dt] : dk[dt];
         u32x2_t w;
-        w[0] = pack_bf16(a[q4 * 4 + 0] * m, a[q4 * 4 + 1] * m);
-        w[1] = pack_bf16(a[q4 * 4 + 2] * m, a[q4 * 4 + 3] * m);
+        w[0] = pack_bf16(a[q4 * 4 + 0], a[q4 * 4 + 1]);
+        w[1] = pack_bf16(a[q4 * 4 + 2], a[q4 * 4 + 3]);
         *reinterpret_cast<__attribute__((address_space(3))) u32x2_t *>(stage + tile_ofs<D>(ecol, dt * 4 + q4) + ehf * 8) = w;
       }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    uint16_t *dst = pass == 0 ? bp.dv : bp.dkr;
-    const int64_t st = pass == 0 ? bp.dv_st : (int64_t)p.n_kv_heads * D, sh = pass == 0 ? bp.dv_sh : (int64_t)D;
+    uint16_t *dst = pass == 0 ? bp.dv : bp.dk;
+    const int64_t st = pass == 0 ? bp.dv_st : bp.dk_st, sh = pass == 0 ? bp.dv_sh : bp.dk_sh;
 #pragma unroll
     for (int u = 0; u < G::KCH; ++u) {
       const int rr = u * G::QRPI + ln / G::CPR;

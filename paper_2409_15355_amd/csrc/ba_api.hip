@@ -256,7 +256,7 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
                          const ba_tensor *k, const ba_tensor *k_rot, int n, const int32_t *start,
                          const int32_t *pos0, hipStream_t stream, const ba::RopeRots *rots = nullptr,
                          const ba::RopeRotsSmall *rots_small = nullptr, float *rot_dst = nullptr, int n_rot = 0,
-                         float *q_table = nullptr) {
+                         float *q_table = nullptr, bool rows_too = false) {
   ba::RopeSegs segs;
   memset(&segs, 0, sizeof(segs));
   segs.n = n;
@@ -289,7 +289,7 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
   p.layout = h->rope_layout;
   // few tokens: one head per thread (more, shorter threads); many: sin/cos shared by several heads
   p.heads_per_thread = tokens >= 16384 ? 8 : (tokens >= 2048 ? 2 : 1);
-  p.do_q = q_table ? 2 : 1;  // a table of factors for the attention core, or rotated rows
+  p.do_q = q_table ? (rows_too ? 3 : 2) : 1;  // a table of factors for the attention core, rotated rows, or both
   p.q_table = q_table;
   p.do_k = 1;
   p.rot_dst = rot_dst;
@@ -676,8 +676,8 @@ size_t ba_block_attention_prompts_backward_workspace_bytes(const ba_heads *heads
   if (!heads || !cu_blk || !block_offsets || n_prompts < 0) return 0;
   const size_t T = (size_t)block_offsets[cu_blk[n_prompts]];
   const size_t D = heads->head_dim, hq = heads->n_q_heads, hkv = heads->n_kv_heads;
-  // rotated scaled q, rotated k, (log-sum-exp, delta) per row (+ padding), gradients of the rotated q and k
-  return 2 * align256(T * hq * D * 2) + 2 * align256(T * hkv * D * 2) + align256(T * hq * 8 + 16);
+  // rotated scaled q, rotated k, the table of rotation factors, (log-sum-exp, delta) per row (+ padding)
+  return align256(T * hq * D * 2) + align256(T * hkv * D * 2) + align256(T * D * 4) + align256(T * hq * 8 + 16);
 }
 
 int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
@@ -710,8 +710,9 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   if (T == 0) return BA_OK;
   int64_t max_len = 0;
   for (int b = 0; b < n_blocks; ++b) max_len = std::max<int64_t>(max_len, (int64_t)block_offsets[b + 1] - block_offsets[b]);
-  const int64_t widest = std::max(std::max((int64_t)hq * D, std::max(d_out->stride_tok, o->stride_tok)),
-                                  (int64_t)G * std::max((int64_t)D, std::max(d_out->stride_head, o->stride_head)));
+  const int64_t widest =
+      std::max(std::max((int64_t)hq * D, std::max(std::max(d_out->stride_tok, o->stride_tok), dq_out->stride_tok)),
+               (int64_t)G * std::max((int64_t)D, std::max(std::max(d_out->stride_head, o->stride_head), dq_out->stride_head)));
   if (G < 4) return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention needs at least 4 query heads per KV head");
   if ((max_len + 1) * widest >= 0x40000000 || max_len * G > 0x3fffffff)
     return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention: a block of %lld tokens at these strides is too long",
@@ -723,16 +724,14 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   char *wsp = (char *)ws;
   uint16_t *q_rot = (uint16_t *)wsp;
   wsp += align256((size_t)T * hq * D * 2);
-  uint16_t *dq_rot = (uint16_t *)wsp;
-  wsp += align256((size_t)T * hq * D * 2);
   ba_tensor k_rot;
   k_rot.ptr = wsp;
   k_rot.stride_head = D;
   k_rot.stride_tok = (int64_t)hkv * D;
   k_rot.dtype = BA_DTYPE_BF16;
   wsp += align256((size_t)T * hkv * D * 2);
-  uint16_t *dk_rot = (uint16_t *)wsp;
-  wsp += align256((size_t)T * hkv * D * 2);
+  float *q_table = (float *)wsp;
+  wsp += align256((size_t)T * D * 4);
   float2 *ld = (float2 *)wsp;
 
   ba::RopeTable rt;
@@ -742,7 +741,9 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   for (int n = 0; n <= n_prompts; ++n) starts[n] = block_offsets[cu_blk[n]];
   for (int n0 = 0; n0 < n_prompts; n0 += ba::kRopeMaxSegs) {
     const int n = std::min(ba::kRopeMaxSegs, n_prompts - n0);
-    if ((rc = run_rope_prepass(heads, rt, q, q_rot, k, &k_rot, n, starts.data() + n0, nullptr, stream))) return rc;
+    if ((rc = run_rope_prepass(heads, rt, q, q_rot, k, &k_rot, n, starts.data() + n0, nullptr, stream, nullptr, nullptr,
+                               nullptr, 0, q_table, true)))
+      return rc;
   }
 
   ba::BwdParams bp;
@@ -756,8 +757,12 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   bp.lse = lse;
   bp.ld = ld;
   bp.T = T;
-  bp.dqr = dq_rot;
-  bp.dkr = dk_rot;
+  bp.dq = (uint16_t *)dq_out->ptr;
+  bp.dq_st = dq_out->stride_tok;
+  bp.dq_sh = dq_out->stride_head;
+  bp.dk = (uint16_t *)dk_out->ptr;
+  bp.dk_st = dk_out->stride_tok;
+  bp.dk_sh = dk_out->stride_head;
   bp.dv = (uint16_t *)dv_out->ptr;
   bp.dv_st = dv_out->stride_tok;
   bp.dv_sh = dv_out->stride_head;
@@ -775,6 +780,9 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   ap.vf = (const uint16_t *)v->ptr;
   ap.vf_st = v->stride_tok;
   ap.vf_sh = v->stride_head;
+  ap.q_table = q_table;
+  ap.scale_log2e = scale_log2e(heads);
+  ap.rope_layout = heads->rope_layout;
   ap.n_q_heads = hq;
   ap.n_kv_heads = hkv;
   ap.group = G;
@@ -852,44 +860,6 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
       e = ba::launch_bwd_dkv(ap, meta, bp, stream);
     }
     if (e != hipSuccess) return device_fail(e, "backward: dk/dv launch");
-  }
-  // back to the un-rotated frame: the pre-pass kernel with the angles negated (scales already applied)
-  for (int n0 = 0; n0 < n_prompts; n0 += ba::kRopeMaxSegs) {
-    const int n = std::min(ba::kRopeMaxSegs, n_prompts - n0);
-    ba::RopeSegs segs;
-    memset(&segs, 0, sizeof(segs));
-    segs.n = n;
-    for (int i = 0; i <= n; ++i) segs.start[i] = starts[n0 + i];
-    const int64_t tokens = (int64_t)segs.start[n] - segs.start[0];
-    if (tokens <= 0) continue;
-    ba::RopePrepassParams pp;
-    memset(&pp, 0, sizeof(pp));
-    pp.q_src = dq_rot;
-    pp.q_st = (int64_t)hq * D;
-    pp.q_sh = D;
-    pp.q_dst = (uint16_t *)dq_out->ptr;
-    pp.qd_st = dq_out->stride_tok;
-    pp.qd_sh = dq_out->stride_head;
-    pp.k_src = dk_rot;
-    pp.k_st = (int64_t)hkv * D;
-    pp.k_sh = D;
-    pp.k_dst = (uint16_t *)dk_out->ptr;
-    pp.kd_st = dk_out->stride_tok;
-    pp.kd_sh = dk_out->stride_head;
-    pp.q_scale = 1.0f;
-    pp.n_q_heads = hq;
-    pp.n_kv_heads = hkv;
-    pp.head_dim = D;
-    pp.layout = heads->rope_layout;
-    pp.heads_per_thread = tokens >= 16384 ? 8 : (tokens >= 2048 ? 2 : 1);
-    pp.do_q = 1;
-    pp.do_k = 1;
-    pp.inverse = 1;
-    {
-      ProfileScope ps(BA_PROFILE_REENCODE, stream);
-      e = ba::launch_rope_prepass(pp, segs, nullptr, nullptr, rt, stream);
-    }
-    if (e != hipSuccess) return device_fail(e, "backward: inverse RoPE launch");
   }
   return BA_OK;
 }

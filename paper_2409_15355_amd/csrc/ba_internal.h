@@ -81,8 +81,8 @@ struct RopePrepassParams {
   int32_t do_q, do_k;
   float *rot_dst;    // [n_rot][D/2][2]: (cos, sin) of rot_angle[b] * theta_j, or null
   int32_t n_rot;
-  float *q_table;    // do_q == 2: instead of rotating Q rows, write q_scale * (cos, sin) per token: [tokens][D/2][2]
-  int32_t inverse;   // rotate by minus the angle (the transposed map: gradients back to the un-rotated frame)
+  float *q_table;    // do_q == 2: instead of rotating Q rows, write q_scale * (cos, sin) per token: [tokens][D/2][2];
+                     // do_q == 3: both the rotated rows and the table
 };
 
 // positions (in tokens) by which the rows of the rotation table turn
@@ -177,10 +177,8 @@ struct BwdParams {
   float2 *ld;            // [n_kv_heads][T][group]: (log-sum-exp / ln 2, delta) of query head kvh * group + g,
                          // written by the dq kernel, read by the dk/dv kernel
   int64_t T;
-  uint16_t *dqr;         // [T][n_q_heads][D]: gradient of the rotated queries
-  uint16_t *dkr;         // [T][n_kv_heads][D]: gradient of the rotated keys
-  uint16_t *dv;          // gradient of the values, with these strides
-  int64_t dv_st, dv_sh;
+  uint16_t *dq, *dk, *dv;  // the gradients, with these strides
+  int64_t dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
   float scale;           // softmax scale
 };
 

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kThreads) void rope_rot_table_kernel(float *dst, in
 
 // workgroup rows of the Q job: head groups, or one row when only the table of factors is written
 __host__ __device__ inline int q_groups(const RopePrepassParams &p) {
-  return p.do_q == 1 ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : (p.do_q == 2 ? 1 : 0);
+  return (p.do_q == 1 || p.do_q == 3) ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : (p.do_q == 2 ? 1 : 0);
 }
 
 template <int D, int LAYOUT>
@@ -89,13 +89,12 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
     else  // half: element e of chunk c pairs with element e of chunk c + CH/2
       j = c * VEC + e;
     sincos_phase(rope_phase(pos, rt.turns[j]), cs[e], sn[e]);
-    if (p.inverse) sn[e] = -sn[e];
     if (scale != 1.0f) {
       cs[e] *= scale;
       sn[e] *= scale;
     }
   }
-  if (is_q && p.do_q == 2) {
+  if (is_q && (p.do_q == 2 || (p.do_q == 3 && grp == 0))) {
     // the factors themselves, for the attention core to rotate q with: entry j at [t][j] = (cos, sin)
     float2 *row = reinterpret_cast<float2 *>(p.q_table) + (int64_t)t * (D / 2);
 #pragma unroll
@@ -107,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
         j = c * VEC + e;
       row[j] = make_float2(cs[e], sn[e]);
     }
-    return;
+    if (p.do_q == 2) return;
   }
 #pragma unroll 4
   for (int h = h_begin; h < h_end; ++h) {

@@ -204,9 +204,9 @@ def test_whole_prompts_backward_rejects_bad_arguments_and_sizes_workspace(lib):
     assert call(h, [0, 2], [0, 5, 9], lse_p=None) == -1       # no log-sum-exps
     assert call(ba.Heads(4, 4, 64), [0, 2], [0, 5, 9]) == -2  # fewer than four query heads per KV head
     assert call(h, [0, 2], [0, 5, 9]) == -4                   # workspace missing
-    # rotated q and its gradient, rotated k and its gradient, (log-sum-exp, delta) per row + padding
+    # rotated q, rotated k, the table of rotation factors, (log-sum-exp, delta) per row + padding
     T = 164
     a256 = lambda n: (n + 255) // 256 * 256
     assert ba.ba_block_attention_prompts_backward_workspace_bytes(h, [0, 2], [0, 100, T]) == \
-        2 * a256(T * 32 * 128 * 2) + 2 * a256(T * 8 * 128 * 2) + a256(T * 32 * 8 + 16)
+        a256(T * 32 * 128 * 2) + a256(T * 8 * 128 * 2) + a256(T * 128 * 4) + a256(T * 32 * 8 + 16)
     assert call(h, [0, 2], [0, 0, 0]) == 0                    # no tokens: legal no-op
