@@ -657,7 +657,14 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       // tile i+1 of this wave's kind must have landed before the barrier; the only copy that
       // may be younger is tile i+2's (tile i+3's starts inside the MFMA block below)
       if (steady || i + 2 < n_t) dma_wait<G::IPW>(); else dma_wait<0>();
-      if (kBlocks && !steady && i + 1 < n_t && cm.rem == 1) load_q(rot_of(cm.seg + 1));  // tile i+1 opens a segment
+      // Tile i+1 opens a segment of a block table: new query fragments.  Waves 0..3 turn theirs here;
+      // waves 4..7 have done so right behind their previous MFMA block (see below), in the same
+      // half-period, so that the workgroup stalls once per boundary, not twice.
+      if (kBlocks && !steady && i + 1 < n_t && cm.rem == 1 && (!role_b || i == 0)) {
+        __builtin_amdgcn_s_setprio(3);
+        load_q(rot_of(cm.seg + 1));
+        __builtin_amdgcn_s_setprio(0);
+      }
       const bool copy = steady || i + 3 < n_t;
       CopyJob cj;
       cj.ptr = cp_ptr;
@@ -688,8 +695,18 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       preload(vofs, fr);
       wg_barrier();
       mfma_block(vofs, ((i + 1) & (kNumKBuf - 1)) * TB, steady || i + 1 < n_t, copy, cj, cp_off, pf, sacc, fr);
-      if (steady || !role_b || i + 1 < n_t) wg_barrier();
-      advance(cm);
+      if constexpr (kBlocks && !steady) {
+        advance(cm);
+        if (role_b && i + 2 < n_t && cm.rem == 1) {  // (QK of tile i+1 is done: the fragments are free)
+          __builtin_amdgcn_s_setprio(3);
+          load_q(rot_of(cm.seg + 1));
+          __builtin_amdgcn_s_setprio(0);
+        }
+        if (!role_b || i + 1 < n_t) wg_barrier();
+      } else {
+        if (steady || !role_b || i + 1 < n_t) wg_barrier();
+        advance(cm);
+      }
     };
     // With a contiguous context (or none) the steady iterations form one run from the start: until
     // the copy cursor or the compute cursor reaches the end of the segment they start in.
