@@ -51,7 +51,7 @@ def main() -> int:
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows (config 3/4, single block)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for HBM byte counters")
-    ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3|prompts|smallblocks|cached")
+    ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3|final3|cfg2|prompts|smallblocks|cached")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -302,6 +302,75 @@ def main() -> int:
             rows_out["encode_cfg3_ragged"] = {"ms": round(ms_e, 4), "algorithmic_TFLOPs": round(fl / ms_e / 1e9, 1),
                                               "GBps": round(byts / ms_e / 1e6, 1), "tokens": T3}
             del q, k, v, o, kl, ws_3
+        # a-3 batched: config 3's eight final blocks (32..128 query tokens over about 4,000 context tokens each)
+        if args.only in ("", "final3"):
+            w3 = wl.config3()
+            cu_q3, cu_ctx3 = w3.cu_q(), w3.cu_ctx()
+            Tq, Tc = int(cu_q3[-1]), int(cu_ctx3[-1])
+            qf3 = randn_bf16(wl.tensor_seed(3, 40), (Tq, hq, d))
+            kc3 = randn_bf16(wl.tensor_seed(3, 41), (Tc, hkv, d))
+            vc3 = randn_bf16(wl.tensor_seed(3, 42), (Tc, hkv, d))
+            kf3 = randn_bf16(wl.tensor_seed(3, 43), (Tq, hkv, d))
+            vf3 = randn_bf16(wl.tensor_seed(3, 44), (Tq, hkv, d))
+            o3 = torch.empty_like(qf3)
+            h3 = ba.Heads(hq, hkv, d, w3.rope_base)
+            ws_f3 = torch.empty(max(ba.ba_final_block_attention_workspace_bytes(h3, cu_q3, cu_ctx3, ba.ROPE_APPLY, False), 256),
+                                dtype=torch.uint8, device="cuda")
+
+            def fin3():
+                ba.ba_final_block_attention(h3, qf3, kc3, vc3, kf3, vf3, o3, None, cu_q3, cu_ctx3, None, ba.ROPE_APPLY, ws_f3)
+
+            ms_f3, _ = timed(fin3, 20 if args.only == "" else 200, 3)
+            pairs3 = sum(visible_pairs_final(int(cu_ctx3[n + 1] - cu_ctx3[n]), int(cu_q3[n + 1] - cu_q3[n]))
+                         for n in range(len(cu_q3) - 1))
+            byts3 = 2.0 * d * (2 * Tc * hkv + 2 * Tq * hkv + 2 * Tq * hq)
+            rows_out["final_cfg3_batched"] = {"ms": round(ms_f3, 4), "TFLOPs": round(4.0 * d * hq * pairs3 / ms_f3 / 1e9, 1),
+                                              "GBps": round(byts3 / ms_f3 / 1e6, 1), "query_tokens": Tq, "context_tokens": Tc}
+            del qf3, kc3, vc3, kf3, vf3, o3, ws_f3
+        # config 2 end to end (10 passages of 200 tokens + 64 query tokens): the three steps one after
+        # the other; microseconds each, bound by launch latency and by the host side of the calls
+        if args.only in ("", "cfg2"):
+            w2 = wl.config2()
+            offs2 = w2.passage_block_offsets()
+            cu_q2, cu_ctx2 = w2.cu_q(), w2.cu_ctx()
+            T2, Lq2 = int(offs2[-1]), int(cu_q2[-1])
+            h2 = ba.Heads(hq, hkv, d, w2.rope_base)
+            q2 = randn_bf16(wl.tensor_seed(2, 0), (T2, hq, d))
+            k2 = randn_bf16(wl.tensor_seed(2, 1), (T2, hkv, d))
+            v2 = randn_bf16(wl.tensor_seed(2, 2), (T2, hkv, d))
+            o2, kl2, kre2 = torch.empty_like(q2), torch.empty_like(k2), torch.empty_like(k2)
+            qf2 = randn_bf16(wl.tensor_seed(2, 3), (Lq2, hq, d))
+            kf2 = randn_bf16(wl.tensor_seed(2, 4), (Lq2, hkv, d))
+            vf2 = randn_bf16(wl.tensor_seed(2, 5), (Lq2, hkv, d))
+            of2 = torch.empty_like(qf2)
+            ws_e2 = torch.empty(max(ba.ba_encode_blocks_workspace_bytes(h2, offs2, ba.ROPE_APPLY, True), 256),
+                                dtype=torch.uint8, device="cuda")
+            ws_f2 = torch.empty(max(ba.ba_final_block_attention_workspace_bytes(h2, cu_q2, cu_ctx2, ba.ROPE_APPLY, False), 256),
+                                dtype=torch.uint8, device="cuda")
+            src2 = offs2[:-1].astype(np.int32)
+            len2 = np.diff(offs2).astype(np.int32)
+
+            def enc2():
+                ba.ba_encode_blocks(h2, q2, k2, v2, o2, kl2, offs2, ba.ROPE_APPLY, ws_e2)
+
+            def re2():
+                ba.ba_reencode_positions(h2, kl2, kre2, src2, src2, len2, None, src2, ba.REENC_SHIFT)
+
+            def fin2():
+                ba.ba_final_block_attention(h2, qf2, kre2, v2, kf2, vf2, of2, None, cu_q2, cu_ctx2, None, ba.ROPE_APPLY, ws_f2)
+
+            def all2():
+                enc2(); re2(); fin2()
+
+            n2 = 50 if args.only == "" else 500
+            ms_e2, _ = timed(enc2, n2, 5)
+            ms_r2, _ = timed(re2, n2, 5)
+            ms_f2, _ = timed(fin2, n2, 5)
+            ms_a2, _ = timed(all2, n2, 5)
+            rows_out["cfg2_three_steps"] = {"encode_us": round(ms_e2 * 1e3, 1), "reencode_us": round(ms_r2 * 1e3, 1),
+                                            "final_us": round(ms_f2 * 1e3, 1), "all_three_us": round(ms_a2 * 1e3, 1),
+                                            "note": "calls issued back to back from Python; latency-bound, no roofline claim"}
+            del q2, k2, v2, o2, kl2, kre2, qf2, kf2, vf2, of2, ws_e2, ws_f2
         # whole prompts in one call: config 3's eight prompts with their query blocks appended
         if args.only in ("", "prompts"):
             w3 = wl.config3()

@@ -50,7 +50,7 @@ class BaError(RuntimeError):
 
 
 _lib = None
-_I32P = ctypes.POINTER(ctypes.c_int32)
+_I32P = ctypes.c_void_p  # const int32_t*: host arrays travel as plain addresses (numpy's typed pointers cost microseconds each)
 _TP = ctypes.POINTER(BaTensor)
 _HP = ctypes.POINTER(BaHeads)
 
@@ -131,25 +131,32 @@ class Heads:
         self._q_to_kv = None if q_to_kv is None else np.ascontiguousarray(q_to_kv, dtype=np.int32)
         self._inv_freq = None if inv_freq is None else np.ascontiguousarray(inv_freq, dtype=np.float64)
         self.c = BaHeads(n_q_heads, n_kv_heads, head_dim,
-                         None if self._q_to_kv is None else self._q_to_kv.ctypes.data_as(_I32P),
+                         None if self._q_to_kv is None else self._q_to_kv.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
                          float(softmax_scale), float(rope_base),
                          None if self._inv_freq is None else self._inv_freq.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
                          rope_layout)
         self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
 
 
+_dtype_codes = None  # torch dtype -> BA_DTYPE_*, filled on first use (torch is imported lazily)
+
+
 def _tensor(t, dtype_code: Optional[int] = None) -> Optional[BaTensor]:
     """[tokens, heads, D] torch tensor (any token / head strides, D contiguous)."""
+    global _dtype_codes
     if t is None:
         return None
-    import torch
-    if t.dim() != 3 or t.stride(2) != 1:
+    st = t.stride()
+    if len(st) != 3 or st[2] != 1:
         raise ValueError("expected a [tokens, heads, head_dim] tensor with contiguous head_dim")
     if dtype_code is None:
-        dtype_code = DTYPE_F32 if t.dtype == torch.float32 else DTYPE_BF16
-        if t.dtype not in (torch.float32, torch.bfloat16):
+        if _dtype_codes is None:
+            import torch
+            _dtype_codes = {torch.float32: DTYPE_F32, torch.bfloat16: DTYPE_BF16}
+        dtype_code = _dtype_codes.get(t.dtype)
+        if dtype_code is None:
             raise ValueError(f"dtype {t.dtype} not supported")
-    return BaTensor(t.data_ptr(), t.stride(0), t.stride(1), dtype_code)
+    return BaTensor(t.data_ptr(), st[0], st[1], dtype_code)
 
 
 def _ref(x):
@@ -161,13 +168,22 @@ def _ints(a) -> Optional[np.ndarray]:
 
 
 def _ip(a: Optional[np.ndarray]):
-    return None if a is None else a.ctypes.data_as(_I32P)
+    return None if a is None else a.ctypes.data
+
+
+_raw_stream = None  # fast path to the current stream's handle, looked up once
 
 
 def _stream_handle(stream) -> int:
+    global _raw_stream
+    if stream is not None:
+        return int(stream.cuda_stream)
     import torch
-    s = torch.cuda.current_stream() if stream is None else stream
-    return int(s.cuda_stream)
+    if _raw_stream is None:
+        _raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", False)
+    if _raw_stream:
+        return int(_raw_stream(torch.cuda.current_device()))
+    return int(torch.cuda.current_stream().cuda_stream)
 
 
 def _ws(ws):

@@ -104,6 +104,19 @@ int32_t check_heads(const ba_heads *h, bool attention) {
 
 // theta_j / (2 pi) as a Q0.64 fraction, from extended-precision host arithmetic.
 void build_rope_table(const ba_heads *h, ba::RopeTable *rt) {
+  // (64 extended-precision powers cost tens of microseconds, more than the launch of a small call:
+  // the table of the last (base, head_dim) is kept per thread)
+  struct Memo {
+    bool valid = false;
+    double base = 0.0;
+    int head_dim = 0;
+    ba::RopeTable rt;
+  };
+  static thread_local Memo memo;
+  if (!h->inv_freq && memo.valid && memo.base == h->rope_base && memo.head_dim == h->head_dim) {
+    *rt = memo.rt;
+    return;
+  }
   const long double two_pi = 6.283185307179586476925286766559005768L;
   const int half = h->head_dim / 2;
   for (int j = 0; j < ba::kMaxFreq; ++j) rt->turns[j] = 0;
@@ -116,6 +129,12 @@ void build_rope_table(const ba_heads *h, ba::RopeTable *rt) {
     const uint64_t hi = (uint64_t)floorl(up);
     const uint64_t lo = (uint64_t)floorl(ldexpl(up - floorl(up), 32));
     rt->turns[j] = (hi << 32) | (lo & 0xffffffffull);
+  }
+  if (!h->inv_freq) {
+    memo.valid = true;
+    memo.base = h->rope_base;
+    memo.head_dim = h->head_dim;
+    memo.rt = *rt;
   }
 }
 
