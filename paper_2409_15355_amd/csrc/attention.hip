@@ -181,9 +181,14 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const int last_tok = (int)fast_div((uint32_t)last_row, p.group_div);
   const int n_causal_tiles = last_tok / kTileKeys + 1;
   const int nt = n_ctx_tiles + n_causal_tiles;
+  // Tiles of the causal segment cost more than context tiles (masks on the diagonal, the change of
+  // segment, the general path of the loop): the split that ends with them gets fewer tiles, as if
+  // `pad` more tiles followed, so that all splits of a launch end together.
   // (nt < 2^26 and at most 32 splits: the products fit 32 bits)
-  const int t_begin = (int)((uint32_t)nt * (uint32_t)split / (uint32_t)p.n_splits);
-  const int t_end = (int)((uint32_t)nt * (uint32_t)(split + 1) / (uint32_t)p.n_splits);
+  const int pad = p.n_splits > 1 ? min((3 + n_causal_tiles) / 2, nt / (2 * p.n_splits)) : 0;
+  const uint32_t nt_v = (uint32_t)(nt + pad);
+  const int t_begin = (int)(nt_v * (uint32_t)split / (uint32_t)p.n_splits);
+  const int t_end = min(nt, (int)(nt_v * (uint32_t)(split + 1) / (uint32_t)p.n_splits));
   const int n_t = t_end - t_begin;
 
   const int my_row = row0 + wave * 32 + col;
