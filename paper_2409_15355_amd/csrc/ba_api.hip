@@ -843,7 +843,8 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
     }
     meta.tile_start[n] = (int32_t)tiles;
     for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta.tile_start[i] = 0x7fffffff;
-    if (tiles == 0 || tiles > 0x3fffffff) continue;
+    if (tiles > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
+    if (tiles == 0) continue;
     ap.total_tiles = (int32_t)tiles;
     ap.tiles_div = ba::make_fast_div((uint32_t)tiles);
     {
@@ -871,7 +872,8 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
       tiles += ((int64_t)by_k[b0 + i].len + ba::kShortTileRows - 1) / ba::kShortTileRows;
     }
     meta.tile_start[n] = (int32_t)tiles;
-    if (tiles == 0 || tiles > 0x3fffffff) continue;
+    if (tiles > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
+    if (tiles == 0) continue;
     ap.total_tiles = (int32_t)tiles;
     ap.tiles_div = ba::make_fast_div((uint32_t)tiles);
     {

@@ -941,6 +941,51 @@ def test_whole_prompts_backward_medium_prompts(ba):
         assert_grad_close(gv[t0:t1], rv, f"dv, prompt {n}")
 
 
+def test_whole_prompts_forward_and_backward_on_strided_views(ba):
+    """q, k, v as views into one fused [T, Hq + 2 Hkv, D] projection buffer, the gradients written
+    into views of a buffer of the same shape, o and d_out with padded head strides: every tensor of
+    both calls has token and head strides of its own.  Memory outside the views must stay untouched."""
+    torch = torch_mod()
+    hq, hkv, d, base = 8, 2, 128, 500000.0
+    prompts = [[150, 64, 33], [200]]
+    lens = [l for p in prompts for l in p]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cu_blk = np.array([0, 3, 4], dtype=np.int32)
+    T = int(offs[-1])
+    qb, kb, vb = gen_qkv(480, T, hq, hkv, d)
+    dob = wl.normal_bf16_bits(483, (T, hq, d))
+    fused = torch.zeros((T, hq + 2 * hkv, d), dtype=torch.bfloat16, device="cuda")
+    fused[:, :hq], fused[:, hq:hq + hkv], fused[:, hq + hkv:] = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb)
+    q, k, v = fused[:, :hq], fused[:, hq:hq + hkv], fused[:, hq + hkv:]
+    o_big = torch.full((T, hq, 2, d), 7.0, dtype=torch.bfloat16, device="cuda")
+    o = o_big[:, :, 1]
+    do_big = torch.zeros((T + 3, hq + 1, d), dtype=torch.bfloat16, device="cuda")
+    do_big[3:, 1:] = dev_bf16(dob)
+    do = do_big[3:, 1:]
+    grads = torch.full((T, hq + 2 * hkv, d), 5.0, dtype=torch.bfloat16, device="cuda")
+    dv, dq, dk = grads[:, :hkv], grads[:, hkv:hkv + hq], grads[:, hkv + hq:]  # (another order than the inputs')
+    lse = torch.full((T, hq), float("nan"), dtype=torch.float32, device="cuda")
+    heads = ba.Heads(hq, hkv, d, base)
+    ws_f = torch.empty(ba.ba_block_attention_prompts_workspace_bytes(heads, cu_blk, offs, 1, False), dtype=torch.uint8, device="cuda")
+    ba.ba_block_attention_prompts(heads, q, k, v, o, None, lse, cu_blk, offs, 1, ws_f)
+    ws_b = torch.empty(ba.ba_block_attention_prompts_backward_workspace_bytes(heads, cu_blk, offs), dtype=torch.uint8, device="cuda")
+    ba.ba_block_attention_prompts_backward(heads, q, k, v, o, lse, do, dq, dk, dv, cu_blk, offs, ws_b)
+    torch.cuda.synchronize()
+    assert float((o_big[:, :, 0] - 7.0).abs().max()) == 0.0
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(base, d)
+    og, gq, gk, gv = host_f64(o), host_f64(dq), host_f64(dk), host_f64(dv)
+    for n in range(2):
+        t0, t1 = int(offs[cu_blk[n]]), int(offs[cu_blk[n + 1]])
+        po = offs[cu_blk[n]:cu_blk[n + 1] + 1] - t0
+        ref = oracle.masked_attention_bruteforce(f(qb[t0:t1]), f(kb[t0:t1]), f(vb[t0:t1]), po, th)
+        assert_attention_close(og[t0:t1], ref, f"strided o, prompt {n}")
+        rq, rk, rv, _ = oracle.masked_attention_backward_bruteforce(f(qb[t0:t1]), f(kb[t0:t1]), f(vb[t0:t1]), f(dob[t0:t1]), po, th)
+        assert_grad_close(gq[t0:t1], rq, f"strided dq, prompt {n}")
+        assert_grad_close(gk[t0:t1], rk, f"strided dk, prompt {n}")
+        assert_grad_close(gv[t0:t1], rv, f"strided dv, prompt {n}")
+
+
 def test_calls_can_be_captured_in_a_hip_graph(ba):
     """The library only enqueues kernels on the caller's stream (no allocation, no copy, no
     synchronisation), so a sequence of calls can be captured and replayed: several replays, with
