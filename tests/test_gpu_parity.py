@@ -261,14 +261,15 @@ def _with_component(bits, rows, dim, value):
     return wl.f32_to_bf16_bits(x)
 
 
-@pytest.mark.parametrize("where", ["final", "encode"])
+@pytest.mark.parametrize("where", ["final", "encode", "encode-short-blocks-schedule", "whole-prompt"])
 def test_late_keys_far_above_first_tile_move_the_reference(ba, where):
     """Every query carries +8 and the first 64 keys carry -32 in a slowly rotating head dimension, so
     the first key tile scores about 46 (log2 units) below the later ones: a reference taken from
     the first tile has to move when the second arrives, and across KV splits the partials carry
     very different references.  The keys that matter have ordinary scores, so the usual
     tolerance applies."""
-    hq, hkv, d = 4, 2, 64
+    # (two query heads per KV head take the main schedule in per-block encoding, four the short-block one)
+    hq, hkv, d = (4, 2, 64) if where in ("final", "encode") else (8, 2, 64)
     th = oracle.theta(10000.0, d)
     f = oracle.bf16_bits_to_f64
     heads = ba.Heads(hq, hkv, d, 10000.0)
@@ -289,8 +290,12 @@ def test_late_keys_far_above_first_tile_move_the_reference(ba, where):
         qb = _with_component(qb, slice(None), slow, 8.0)
         kb = _with_component(kb, slice(None), slow, 0.0)
         kb = _with_component(_with_component(kb, slice(0, 64), slow, -32.0), slice(600, 664), slow, -32.0)
-        ref, _ = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, th)
-        o, _ = gpu_encode(ba, heads, qb, kb, vb, offs)
+        if where == "whole-prompt":  # one prompt: a passage and a last block that sees it
+            ref = oracle.masked_attention_bruteforce(f(qb), f(kb), f(vb), offs, th)
+            o, _, _ = gpu_prompts(ba, heads, qb, kb, vb, np.array([0, 2], dtype=np.int32), offs, want_k_rot=False)
+        else:
+            ref, _ = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, th)
+            o, _ = gpu_encode(ba, heads, qb, kb, vb, offs)
     assert_attention_close(host_f64(o), ref, "late keys far above the first tile, " + where)
 
 
