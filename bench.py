@@ -51,7 +51,7 @@ def main() -> int:
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows (config 3/4, single block)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for HBM byte counters")
-    ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3|final3|cfg2|prompts|smallblocks|cached")
+    ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3|final3|query50|cfg2|prompts|smallblocks|cached")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -327,6 +327,28 @@ def main() -> int:
             rows_out["final_cfg3_batched"] = {"ms": round(ms_f3, 4), "TFLOPs": round(4.0 * d * hq * pairs3 / ms_f3 / 1e9, 1),
                                               "GBps": round(byts3 / ms_f3 / 1e6, 1), "query_tokens": Tq, "context_tokens": Tc}
             del qf3, kc3, vc3, kf3, vf3, o3, ws_f3
+        # the paper's own efficiency shape (Section 3.4): a 50-token query block behind a 32K-token prompt
+        if args.only in ("", "query50"):
+            Lq5, Tc5 = 50, 32000 - 50
+            cu_q5, cu_ctx5 = np.array([0, Lq5], dtype=np.int32), np.array([0, Tc5], dtype=np.int32)
+            qf5 = randn_bf16(wl.tensor_seed(5, 50), (Lq5, hq, d))
+            kc5 = randn_bf16(wl.tensor_seed(5, 51), (Tc5, hkv, d))
+            vc5 = randn_bf16(wl.tensor_seed(5, 52), (Tc5, hkv, d))
+            kf5 = randn_bf16(wl.tensor_seed(5, 53), (Lq5, hkv, d))
+            vf5 = randn_bf16(wl.tensor_seed(5, 54), (Lq5, hkv, d))
+            o5 = torch.empty_like(qf5)
+            ws_5 = torch.empty(max(ba.ba_final_block_attention_workspace_bytes(heads, cu_q5, cu_ctx5, ba.ROPE_APPLY, False), 256),
+                               dtype=torch.uint8, device="cuda")
+
+            def fin5():
+                ba.ba_final_block_attention(heads, qf5, kc5, vc5, kf5, vf5, o5, None, cu_q5, cu_ctx5, None, ba.ROPE_APPLY, ws_5)
+
+            ms_5, _ = timed(fin5, 50 if args.only == "" else 500, 5)
+            fl5 = 4.0 * d * hq * visible_pairs_final(Tc5, Lq5)
+            rows_out["final_50_query_tokens_32k"] = {"ms_per_layer": round(ms_5, 4), "TFLOPs": round(fl5 / ms_5 / 1e9, 1),
+                                                     "GBps": round(2.0 * d * 2 * Tc5 * hkv / ms_5 / 1e6, 1),
+                                                     "note": "50 query tokens over 31,950 context tokens, one layer's K/V (131 MB) read once"}
+            del qf5, kc5, vc5, kf5, vf5, o5, ws_5
         # config 2 end to end (10 passages of 200 tokens + 64 query tokens): the three steps one after
         # the other; microseconds each, bound by launch latency and by the host side of the calls
         if args.only in ("", "cfg2"):

@@ -809,27 +809,36 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
 // Merge split partials in split order.  Split i holds its own normalised output o_i (fp16), its
 // reference m_i (log2 units; -inf if it saw no key) and its sum l_i:
 //   m = max m_i,  w_i = 2^(m_i - m) l_i,  o = sum_i w_i o_i / sum_i w_i.
-template <int D>
+// SG = 1: a row's splits are merged by the 16-byte columns' threads one after the other.  SG = 4
+// (many splits, few rows): four groups of threads take every fourth split each, so that all loads of
+// a row are in flight at once, and the groups' sums are merged through LDS, group 0 first.
+template <int D, int SG>
 __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, int64_t n_rows) {
-  constexpr int TPR = D / 8;                  // threads per row, 8 elements (16 bytes of fp16) each
-  constexpr int RPB = kCombineThreads / TPR;  // rows per workgroup
-  const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / TPR;
-  if (row >= n_rows) return;
+  constexpr int TPR = D / 8;                         // threads per row, 8 elements (16 bytes of fp16) each
+  constexpr int RPB = kCombineThreads / (TPR * SG);  // rows per workgroup
+  const int g = threadIdx.x / (TPR * RPB);           // which group of splits
+  const int rl = (threadIdx.x / TPR) % RPB;
+  const int64_t row_raw = (int64_t)blockIdx.x * RPB + rl;
+  if (SG == 1 && row_raw >= n_rows) return;
+  const int64_t row = row_raw < n_rows ? row_raw : n_rows - 1;  // (SG > 1: every thread reaches the barrier)
   const int d = (threadIdx.x % TPR) * 8;
   // all loads are unconditional and independent, so they go out together
   constexpr int MAXS = 32;  // the host never asks for more splits
   float wgt[MAXS];
   float m = -INFINITY;
+  const int n_mine = (p.n_splits - g + SG - 1) / SG;  // splits g, g + SG, ...
 #pragma unroll 8
-  for (int s = 0; s < p.n_splits; ++s) {
-    wgt[s & (MAXS - 1)] = p.part_ml[((int64_t)s * p.part_rows + row) * 2];
-    m = fmaxf(m, wgt[s & (MAXS - 1)]);
+  for (int j = 0; j < n_mine; ++j) {
+    const int s = g + j * SG;
+    wgt[j & (MAXS - 1)] = p.part_ml[((int64_t)s * p.part_rows + row) * 2];
+    m = fmaxf(m, wgt[j & (MAXS - 1)]);
   }
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float l = 0.f;
 #pragma unroll 8
-  for (int s = 0; s < p.n_splits; ++s) {
-    const float ms = wgt[s & (MAXS - 1)];
+  for (int j = 0; j < n_mine; ++j) {
+    const int s = g + j * SG;
+    const float ms = wgt[j & (MAXS - 1)];
     const float ls = p.part_ml[((int64_t)s * p.part_rows + row) * 2 + 1];
     const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m) * ls;
     const u32x4_t o = *reinterpret_cast<const u32x4_t *>(p.part_o + ((int64_t)s * p.part_rows + row) * D + d);
@@ -838,6 +847,32 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, 
     for (int i = 0; i < 4; ++i) {
       acc[2 * i] += w * f16_lo(o[i]);
       acc[2 * i + 1] += w * f16_hi(o[i]);
+    }
+  }
+  if constexpr (SG > 1) {
+    // (reference, sum, eight partial outputs) of every thread; group 0 merges them in group order
+    __shared__ float part[SG][TPR * RPB][10 + 1];
+    float *mine = part[g][threadIdx.x % (TPR * RPB)];
+    mine[0] = m;
+    mine[1] = l;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mine[2 + i] = acc[i];
+    __syncthreads();
+    if (g != 0 || row_raw >= n_rows) return;
+    float mm = m;
+#pragma unroll
+    for (int h = 1; h < SG; ++h) mm = fmaxf(mm, part[h][threadIdx.x][0]);
+    const float w0 = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mm);
+    l *= w0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] *= w0;
+#pragma unroll
+    for (int h = 1; h < SG; ++h) {
+      const float *o = part[h][threadIdx.x];
+      const float wh = (o[0] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(o[0] - mm);
+      l += wh * o[1];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += wh * o[2 + i];
     }
   }
   const float inv = 1.0f / l;
@@ -902,17 +937,21 @@ hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMetaSm
   return hipErrorInvalidValue;
 }
 
+template <int D, int SG>
+void launch_combine_t(const AttnParams &p, int64_t n_rows, hipStream_t stream) {
+  constexpr int RPB = kCombineThreads / ((D / 8) * SG);
+  hipLaunchKernelGGL((combine_kernel<D, SG>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kCombineThreads), 0,
+                     stream, p, n_rows);
+}
+
 hipError_t launch_combine(const AttnParams &p, int64_t n_tokens, hipStream_t stream) {
   const int64_t n_rows = n_tokens * p.n_q_heads;
   if (n_rows == 0) return hipSuccess;
+  const bool many = p.n_splits > 8;  // more splits than one thread keeps in flight: four groups of threads per row
   if (p.head_dim == 128) {
-    constexpr int RPB = kCombineThreads / (128 / 8);
-    hipLaunchKernelGGL((combine_kernel<128>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kCombineThreads), 0,
-                       stream, p, n_rows);
+    if (many) launch_combine_t<128, 4>(p, n_rows, stream); else launch_combine_t<128, 1>(p, n_rows, stream);
   } else if (p.head_dim == 64) {
-    constexpr int RPB = kCombineThreads / (64 / 8);
-    hipLaunchKernelGGL((combine_kernel<64>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kCombineThreads), 0,
-                       stream, p, n_rows);
+    if (many) launch_combine_t<64, 4>(p, n_rows, stream); else launch_combine_t<64, 1>(p, n_rows, stream);
   } else {
     return hipErrorInvalidValue;
   }
