@@ -232,6 +232,11 @@ FIN_CASES = [
     ("ragged-batch", 8, 2, 128, 500000.0, [(130, 33), (0, 5), (1, 1), (700, 128), (63, 65)]),
     ("long-query-mha-d64", 2, 2, 64, 10000.0, [(100, 300), (5, 257)]),
     ("deep-split", 8, 8, 128, 500000.0, [(4100, 17)]),
+    # more than eight splits (the merge's four-group form), a row count that does not fill its last workgroup
+    ("many-splits-d64-odd-rows", 6, 2, 64, 10000.0, [(5000, 7)]),
+    ("many-splits-d128-batch", 8, 2, 128, 500000.0, [(3000, 3), (2500, 9)]),
+    # more prompts than one launch's table holds
+    ("seventy-prompts", 4, 1, 64, 10000.0, [(20 + (3 * i) % 50, 1 + i % 5) for i in range(70)]),
 ]
 
 
