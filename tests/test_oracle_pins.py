@@ -10,6 +10,7 @@ import math
 import numpy as np
 import pytest
 import torch
+from hypothesis import given, settings, strategies as st
 
 import oracle
 
@@ -186,6 +187,23 @@ def test_p4_pipeline_equals_bruteforce(offs, layout):
     T, Hq, Hkv, D = offs[-1], 4, 2, 8
     th = oracle.theta(10000.0, D)
     q, k, v = rnd(31, T, Hq, D), rnd(32, T, Hkv, D), rnd(33, T, Hkv, D)
+    got = run_pipeline(q, k, v, offs, th, layout)
+    ref = oracle.masked_attention_bruteforce(q, k, v, offs, th, layout=layout)
+    assert np.abs(got - ref).max() < 1e-11
+
+
+@settings(max_examples=25, deadline=None, derandomize=True)
+@given(lens=st.lists(st.integers(min_value=0, max_value=9), min_size=0, max_size=5),
+       l_q=st.integers(min_value=1, max_value=9), hkv=st.integers(min_value=1, max_value=2),
+       g=st.integers(min_value=1, max_value=3), layout=st.sampled_from([oracle.LAYOUT_INTERLEAVED, oracle.LAYOUT_HALF]),
+       seed=st.integers(min_value=0, max_value=10**6))
+def test_p4_pipeline_equals_bruteforce_on_drawn_splits(lens, l_q, hkv, g, layout, seed):
+    """The same pin on block splits, head groupings and layouts drawn by the test framework: empty
+    passages, no passages at all, one-token blocks, one to three query heads per KV head."""
+    offs = np.concatenate([[0], np.cumsum(lens + [l_q])]).astype(np.int64)
+    T, D = int(offs[-1]), 8
+    th = oracle.theta(10000.0, D)
+    q, k, v = rnd(seed, T, hkv * g, D), rnd(seed + 1, T, hkv, D), rnd(seed + 2, T, hkv, D)
     got = run_pipeline(q, k, v, offs, th, layout)
     ref = oracle.masked_attention_bruteforce(q, k, v, offs, th, layout=layout)
     assert np.abs(got - ref).max() < 1e-11
