@@ -552,15 +552,29 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   //      cached keys of block b stay at the positions they were encoded at and the queries are
   //      turned back by the block's shift instead (rot >= 0: row of the table of rotations), which
   //      gives the same scores as re-encoding the keys (Eq. 2 and 3 applied to q instead of k) ------
+  // With a block table the walk keeps more scalars alive than the register file holds (two cursors
+  // over the table on top of everything the epilogue needs), and what does not fit is parked in
+  // lanes of a vector register and fetched back on every iteration.  The rare parts of that
+  // kernel (this reload, the epilogue) therefore read their kernel arguments again from the
+  // argument segment (`p` is its first member) through a pointer the compiler cannot see through.
+  typedef const __attribute__((address_space(4))) AttnParams *KParams;
+  auto args_again = [&]() __attribute__((always_inline)) {
+    KParams kp = (KParams)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(kp));
+    return kp;
+  };
+#define BA_ARG(field) (kBlocks ? kp->field : p.field)
   auto load_q = [&](int rot) __attribute__((always_inline)) {
+    KParams kp = kBlocks ? args_again() : nullptr;
+    const FastDiv gdiv = {BA_ARG(group_div.mul), BA_ARG(group_div.sh1), BA_ARG(group_div.sh2)};
     // (addresses are rebuilt from the row number each time: with a block table this runs inside the
     // loop, and hoisted address registers would not fit next to the accumulators)
     int row_v = my_row;
     asm volatile("" : "+v"(row_v));
-    const int tok_v = (int)fast_div((uint32_t)row_v, p.group_div);
+    const int tok_v = (int)fast_div((uint32_t)row_v, gdiv);
     const int g = row_v - tok_v * Gq;
     const int head = kvh * Gq + g;
-    const uint16_t *qp = p.q + (int64_t)(pr.q_tok0 + tok_v) * p.q_st + (int64_t)head * p.q_sh + hf * 8;
+    const uint16_t *qp = BA_ARG(q) + (int64_t)(pr.q_tok0 + tok_v) * BA_ARG(q_st) + (int64_t)head * BA_ARG(q_sh) + hf * 8;
     u32x4_t raw[G::KCH];
 #pragma unroll
     for (int kk = 0; kk < G::KCH; ++kk) {
@@ -569,7 +583,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     }
     // rotate the fragments by the angles of a table row: entry j = (cos, sin) (times a scale, if any)
     auto rotate_by = [&](const f32x4_t *tab) __attribute__((always_inline)) {
-      if (p.rope_layout == 0) {
+      if (BA_ARG(rope_layout) == 0) {
 #pragma unroll
         for (int kk = 0; kk < G::KCH; ++kk) {
           // this lane's pairs: frequencies kk * 8 + hf * 4 + e
@@ -599,23 +613,23 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
         }
       }
     };
-    if (!p.q_ready) {
-      if (p.q_table) {
+    if (!BA_ARG(q_ready)) {
+      if (BA_ARG(q_table)) {
         // un-rotated rows and the pre-pass's table of scale * (cos, sin) per token: rotate here, so that
         // the rotated queries never make a round trip through memory
         // (lanes beyond the problem's rows hold zeros: any row of the table will do, take an existing one)
-        rotate_by(reinterpret_cast<const f32x4_t *>(p.q_table + (int64_t)(pr.q_tok0 + (row_ok ? tok_v : 0)) * D));
+        rotate_by(reinterpret_cast<const f32x4_t *>(BA_ARG(q_table) + (int64_t)(pr.q_tok0 + (row_ok ? tok_v : 0)) * D));
       } else {
 #pragma unroll
         for (int kk = 0; kk < G::KCH; ++kk)
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            raw[kk][e] = pack_bf16(bf16_lo(raw[kk][e]) * c2, bf16_hi(raw[kk][e]) * c2);
+            raw[kk][e] = pack_bf16(bf16_lo(raw[kk][e]) * BA_ARG(scale_log2e), bf16_hi(raw[kk][e]) * BA_ARG(scale_log2e));
       }
     }
     if (kBlocks && rot >= 0) {
       // (cos, sin) of minus the block's shift times theta_j, j = 0 .. D/2 - 1
-      rotate_by(reinterpret_cast<const f32x4_t *>(p.blk_rot + (int64_t)rot * D));
+      rotate_by(reinterpret_cast<const f32x4_t *>(BA_ARG(blk_rot) + (int64_t)rot * D));
     }
     // (the empty asm makes the compiler wait for these loads HERE: left pending, it would wait for
     // them at the first use of the fragments inside the loop's MFMA block, on every iteration, and
@@ -734,6 +748,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   //      dimension at a time, so that rows leave as contiguous lines.  The slices lie in the K
   //      buffers, and every wave's last K read precedes the last barrier the other waves passed;
   //      waves 4..7 may still be reading their last V tile, which lies elsewhere ------------------
+  KParams kp = kBlocks ? args_again() : nullptr;
+  const FastDiv gdiv_e = {BA_ARG(group_div.mul), BA_ARG(group_div.sh1), BA_ARG(group_div.sh2)};
   constexpr int HD = D / 2;               // floats per staged row piece
   constexpr int HCH = HD / 4;             // 16-byte chunks per piece (16 or 8)
   constexpr int PITCH = HD * 4;           // bytes per staged row piece (256 or 128)
@@ -771,21 +787,21 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
           stage + rr * PITCH + ((ch ^ ((rr / HLPR) & (HCH - 1))) << 4));
       const int r = row0 + wave * 32 + rr;
       if (r < n_rows) {
-        const int i = (int)fast_div((uint32_t)r, p.group_div);
+        const int i = (int)fast_div((uint32_t)r, gdiv_e);
         const int g = r - i * Gq;
         const int head = kvh * Gq + g;
         const int d = half * HD + ch * 4;
-        if (p.n_splits == 1) {
+        if (BA_ARG(n_splits) == 1) {
           uint2 o2;
           o2.x = pack_bf16(w[0], w[1]);
           o2.y = pack_bf16(w[2], w[3]);
-          *reinterpret_cast<uint2 *>(p.o + (int64_t)(pr.q_tok0 + i) * p.o_st + (int64_t)head * p.o_sh + d) = o2;
+          *reinterpret_cast<uint2 *>(BA_ARG(o) + (int64_t)(pr.q_tok0 + i) * BA_ARG(o_st) + (int64_t)head * BA_ARG(o_sh) + d) = o2;
         } else {
-          const int64_t prow = (int64_t)(pr.q_tok0 + i) * p.n_q_heads + head;
+          const int64_t prow = (int64_t)(pr.q_tok0 + i) * BA_ARG(n_q_heads) + head;
           uint2 o2;
           o2.x = pack_f16(w[0], w[1]);
           o2.y = pack_f16(w[2], w[3]);
-          *reinterpret_cast<uint2 *>(p.part_o + ((int64_t)split * p.part_rows + prow) * D + d) = o2;
+          *reinterpret_cast<uint2 *>(BA_ARG(part_o) + ((int64_t)split * BA_ARG(part_rows) + prow) * D + d) = o2;
         }
       }
     }
@@ -793,11 +809,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
-  if (p.n_splits > 1 && hf == 0 && row_ok) {
+  if (BA_ARG(n_splits) > 1 && hf == 0 && row_ok) {
     const int g = my_row - my_tok * Gq;
-    const int64_t prow = (int64_t)(pr.q_tok0 + my_tok) * p.n_q_heads + kvh * Gq + g;
+    const int64_t prow = (int64_t)(pr.q_tok0 + my_tok) * BA_ARG(n_q_heads) + kvh * Gq + g;
     float2 ml = {l_tot > 0.f ? mb : -INFINITY, l_tot};  // reference in log2 units; -inf: nothing visible
-    *reinterpret_cast<float2 *>(p.part_ml + ((int64_t)split * p.part_rows + prow) * 2) = ml;
+    *reinterpret_cast<float2 *>(BA_ARG(part_ml) + ((int64_t)split * BA_ARG(part_rows) + prow) * 2) = ml;
   }
   BA_MARK_ALWAYS(79, 5);
   BA_WALL(78, 1);
@@ -805,6 +821,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   if (threadIdx.x == 0 && blockIdx.x < 1024) { g_wg[blockIdx.x][1] = wall_clock64(); g_wg[blockIdx.x][3] = clock64(); }
 #endif
 }
+
+#undef BA_ARG
 
 // Merge split partials in split order.  Split i holds its own normalised output o_i (fp16), its
 // reference m_i (log2 units; -inf if it saw no key) and its sum l_i:
