@@ -961,6 +961,7 @@ int32_t ba_reencode_positions(const ba_heads *heads, const ba_tensor *k_src, con
   rp.dtype = k_src->dtype;
   rp.layout = heads->rope_layout;
   rp.mode = mode;
+  rp.copy_from_layer = 0x7fffffff;
   return run_reencode(rp, rt, n_blocks, src_tok_off, dst_tok_off, len, old_pos0, new_pos0, stream);
 }
 
@@ -1364,13 +1365,40 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
     vg = kg;
     vg.ptr = (char *)ws + align256(pl.gather_kv_bytes);
     const int nb = (int)src.size();
-    if ((rc = ba_reencode_positions(heads, k_cache, &kg, 1, 0, 0, nb, src.data(), dst.data(), len.data(), oldp.data(),
-                                    newp.data(), BA_REENC_SHIFT, stream_)))
-      return rc;
-    // (a shift of zero positions is a plain copy)
-    if ((rc = ba_reencode_positions(heads, v_cache, &vg, 1, 0, 0, nb, src.data(), dst.data(), len.data(), zero.data(),
-                                    zero.data(), BA_REENC_SHIFT, stream_)))
-      return rc;
+    const int64_t v_after_k = ((const char *)v_cache->ptr - (const char *)k_cache->ptr) / 2;  // in elements
+    if (k_cache->stride_tok == v_cache->stride_tok && k_cache->stride_head == v_cache->stride_head) {
+      // One launch for both: the values ride along as a second "layer" of the key cache (the layer
+      // strides are the distances between the two tensors) that is copied, not rotated.
+      ba::RopeTable rt;
+      build_rope_table(heads, &rt);
+      ba::ReencParams rp;
+      memset(&rp, 0, sizeof(rp));
+      rp.src = k_cache->ptr;
+      rp.dst = kg.ptr;
+      rp.src_st = k_cache->stride_tok;
+      rp.src_sh = k_cache->stride_head;
+      rp.dst_st = kg.stride_tok;
+      rp.dst_sh = kg.stride_head;
+      rp.src_sl = v_after_k;
+      rp.dst_sl = (int64_t)(align256(pl.gather_kv_bytes) / 2);
+      rp.n_layers = 2;
+      rp.n_kv_heads = heads->n_kv_heads;
+      rp.head_dim = D;
+      rp.dtype = BA_DTYPE_BF16;
+      rp.layout = heads->rope_layout;
+      rp.mode = BA_REENC_SHIFT;
+      rp.copy_from_layer = 1;
+      if ((rc = run_reencode(rp, rt, nb, src.data(), dst.data(), len.data(), oldp.data(), newp.data(), stream)))
+        return rc;
+    } else {
+      if ((rc = ba_reencode_positions(heads, k_cache, &kg, 1, 0, 0, nb, src.data(), dst.data(), len.data(), oldp.data(),
+                                      newp.data(), BA_REENC_SHIFT, stream_)))
+        return rc;
+      // (a shift of zero positions is a plain copy)
+      if ((rc = ba_reencode_positions(heads, v_cache, &vg, 1, 0, 0, nb, src.data(), dst.data(), len.data(), zero.data(),
+                                      zero.data(), BA_REENC_SHIFT, stream_)))
+        return rc;
+    }
     return ba_final_block_attention(heads, q_f, &kg, &vg, k_f, v_f, o_out, k_f_rot_out, n_prompts, cu_q,
                                     pl.cu_ctx.data(), q_pos0, BA_ROPE_APPLY,
                                     (char *)ws + 2 * align256(pl.gather_kv_bytes), pl.gather_final_bytes, stream_);

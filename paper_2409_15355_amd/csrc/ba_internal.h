@@ -44,6 +44,7 @@ struct ReencParams {
   int32_t dtype, layout, mode;
   int32_t max_len;  // longest block in this launch
   int32_t heads_per_thread, n_head_groups;  // how the KV heads are split over workgroups
+  int32_t copy_from_layer;  // layers from this one on are copied as they are (a gathered V rides along as a layer)
 };
 
 hipError_t launch_reencode(const ReencParams &p, const ReencBlocks &blocks, const RopeTable &rt,

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, Block
     turns[e] = rt.turns[j];
   }
 
-  const int shift0 = blocks.pos_new[b] - blocks.pos_old[b];
+  const int shift0 = layer >= p.copy_from_layer ? 0 : blocks.pos_new[b] - blocks.pos_old[b];
   const T *src = static_cast<const T *>(p.src) + (int64_t)layer * p.src_sl +
                  (int64_t)blocks.src_off[b] * p.src_st;
   T *dst = static_cast<T *>(p.dst) + (int64_t)layer * p.dst_sl + (int64_t)blocks.dst_off[b] * p.dst_st;
@@ -103,7 +103,8 @@ __global__ __launch_bounds__(kThreads) void reencode_kernel(ReencParams p, Block
 #pragma unroll
     for (int e = 0; e < VEC; ++e) sincos_phase(rope_phase(shift0, turns[e]), cs[e], sn[e]);
   }
-  const bool plain_copy = (MODE == 0) && (shift0 == 0);  // zero shift: bit-for-bit copy
+  // zero shift, or a layer that only rides along: bit-for-bit copy
+  const bool plain_copy = ((MODE == 0) && (shift0 == 0)) || layer >= p.copy_from_layer;
   const int g_begin = hg * p.heads_per_thread;
   const int g_end = min(p.n_kv_heads, g_begin + p.heads_per_thread);
 
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(kThreads) void reencode_shift_linear_kernel(ReencPa
   const int64_t first = (int64_t)blockIdx.x * (UNROLL * kThreads) + threadIdx.x;
   if ((int64_t)blockIdx.x * (UNROLL * kThreads) >= n_chunks) return;
   const int c = threadIdx.x % CH;
-  const int shift0 = blocks.pos_new[b] - blocks.pos_old[b];
+  const int shift0 = layer >= p.copy_from_layer ? 0 : blocks.pos_new[b] - blocks.pos_old[b];
   float cs[VEC / 2], sn[VEC / 2];
 #pragma unroll
   for (int e = 0; e < VEC / 2; ++e) sincos_phase(rope_phase(shift0, rt.turns[c * (VEC / 2) + e]), cs[e], sn[e]);
