@@ -210,3 +210,26 @@ def test_whole_prompts_backward_rejects_bad_arguments_and_sizes_workspace(lib):
     assert ba.ba_block_attention_prompts_backward_workspace_bytes(h, [0, 2], [0, 100, T]) == \
         a256(T * 32 * 128 * 2) + a256(T * 8 * 128 * 2) + a256(T * 128 * 4) + a256(T * 32 * 8 + 16)
     assert call(h, [0, 2], [0, 0, 0]) == 0                    # no tokens: legal no-op
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/ba.h is the boundary of a C-ABI library: a C99 compiler takes it as it is, with
+    warnings as errors, and the structs it declares have the layout the Python face assumes."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler here")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_header.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "ba.h"\n'
+                   'int main(void) {\n'
+                   '  printf("%zu %zu %zu %zu\\n", sizeof(ba_tensor), sizeof(ba_heads),\n'
+                   '         offsetof(ba_heads, rope_base), offsetof(ba_heads, rope_layout));\n'
+                   '  return 0;\n}\n')
+    exe = tmp_path / "use_header"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(x) for x in out] == [ctypes.sizeof(ba.BaTensor), ctypes.sizeof(ba.BaHeads),
+                                     ba.BaHeads.rope_base.offset, ba.BaHeads.rope_layout.offset]
