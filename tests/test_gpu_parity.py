@@ -1076,3 +1076,116 @@ def test_whole_prompts_many_tiny_blocks_forward_and_backward(ba):
         assert_grad_close(gq[t0:t1], rq, f"dq, prompt {n}")
         assert_grad_close(gk[t0:t1], rk, f"dk, prompt {n}")
         assert_grad_close(gv[t0:t1], rv, f"dv, prompt {n}")
+
+
+# --------------------------------------------------------------------------------------------
+# drawn shapes: every entry point on shapes nobody picked by hand
+# --------------------------------------------------------------------------------------------
+def _drawn_lengths(rng, k, hi):
+    kind = int(rng.integers(0, 3))
+    if kind == 0:
+        return [int(x) for x in rng.integers(0, hi, k)]
+    if kind == 1:  # around the tile sizes
+        return [int(x) for x in rng.choice([1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257], k)]
+    return [int(x) for x in rng.integers(1, 40, k)]
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
+def test_drawn_shapes_match_the_oracle(ba, seed):
+    """Twelve cases per seed, drawn from: head_dim 64 / 128, 1-3 KV heads, 1-8 query heads per KV head,
+    both pair layouts, two RoPE bases; per-block encoding, batched final blocks, whole prompts forward
+    and backward, and the final block over a permuted block cache on both of its routes."""
+    torch = torch_mod()
+    rng = np.random.default_rng(seed)
+    f = oracle.bf16_bits_to_f64
+    for case in range(12):
+        d, hkv, g = int(rng.choice([64, 128])), int(rng.choice([1, 2, 3])), int(rng.choice([1, 2, 3, 4, 5, 8]))
+        base, layout = float(rng.choice([1e4, 5e5])), int(rng.integers(0, 2))
+        kind, s0 = case % 4, int(rng.integers(0, 10 ** 6))
+        if kind == 2:
+            g = max(g, 4)  # whole prompts are built for groups of at least four
+        hq = hkv * g
+        th = oracle.theta(base, d)
+        heads = ba.Heads(hq, hkv, d, base, rope_layout=layout)
+        tag = f"seed {seed} case {case}: D {d}, {hq}/{hkv} heads, layout {layout}"
+        if kind == 0:
+            lens = _drawn_lengths(rng, int(rng.integers(1, 7)), 400)
+            offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+            if offs[-1] == 0:
+                continue
+            qb, kb, vb = gen_qkv(s0, int(offs[-1]), hq, hkv, d)
+            ref_o, ref_k = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, th, layout=layout)
+            o, k_local = gpu_encode(ba, heads, qb, kb, vb, offs)
+            assert_attention_close(host_f64(o), ref_o, f"{tag}, encode {lens}")
+            assert_reencode_bf16(host_bits(k_local), ref_k, layout, f"{tag}, k_local {lens}")
+        elif kind == 1:
+            shapes = [(int(rng.choice([0, 1, 63, 64, 65, 200, 700, 1500, 3000])), int(rng.choice([1, 2, 17, 64, 65, 130])))
+                      for _ in range(int(rng.integers(1, 5)))]
+            cu_ctx = np.concatenate([[0], np.cumsum([s[0] for s in shapes])]).astype(np.int32)
+            cu_q = np.concatenate([[0], np.cumsum([s[1] for s in shapes])]).astype(np.int32)
+            qb, kfb, vfb = gen_qkv(s0, int(cu_q[-1]), hq, hkv, d)
+            kcb = wl.normal_bf16_bits(s0 + 3, (max(int(cu_ctx[-1]), 1), hkv, d))
+            vcb = wl.normal_bf16_bits(s0 + 4, (max(int(cu_ctx[-1]), 1), hkv, d))
+            ref = oracle.final_block(f(qb), f(kcb)[:cu_ctx[-1]], f(vcb)[:cu_ctx[-1]], f(kfb), f(vfb), cu_q, cu_ctx, th,
+                                     layout=layout)
+            o = gpu_final(ba, heads, dev_bf16(qb), dev_bf16(kcb), dev_bf16(vcb), dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
+            assert_attention_close(host_f64(o), ref, f"{tag}, final {shapes}")
+        elif kind == 2:
+            prompts = [_drawn_lengths(rng, int(rng.integers(1, 5)), 150) for _ in range(int(rng.integers(1, 4)))]
+            prompts = [p if sum(p) > 0 else p + [5] for p in prompts]
+            lens = [l for p in prompts for l in p]
+            offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+            cu_blk = np.concatenate([[0], np.cumsum([len(p) for p in prompts])]).astype(np.int32)
+            T = int(offs[-1])
+            qb, kb, vb = gen_qkv(s0, T, hq, hkv, d)
+            dob = wl.normal_bf16_bits(s0 + 9, (T, hq, d))
+            o, _, lse = gpu_prompts(ba, heads, qb, kb, vb, cu_blk, offs, want_k_rot=False)
+            q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+            dq, dk, dv = (torch.full_like(x, float("nan")) for x in (q, k, v))
+            ws = torch.empty(ba.ba_block_attention_prompts_backward_workspace_bytes(heads, cu_blk, offs), dtype=torch.uint8,
+                             device="cuda")
+            ba.ba_block_attention_prompts_backward(heads, q, k, v, o, lse, do, dq, dk, dv, cu_blk, offs, ws)
+            torch.cuda.synchronize()
+            og, gq, gk, gv = host_f64(o), host_f64(dq), host_f64(dk), host_f64(dv)
+            for n in range(len(prompts)):
+                t0, t1 = int(offs[cu_blk[n]]), int(offs[cu_blk[n + 1]])
+                po = offs[cu_blk[n]:cu_blk[n + 1] + 1] - t0
+                ref = oracle.masked_attention_bruteforce(f(qb[t0:t1]), f(kb[t0:t1]), f(vb[t0:t1]), po, th, layout=layout)
+                assert_attention_close(og[t0:t1], ref, f"{tag}, prompts {prompts}")
+                rq, rk, rv, _ = oracle.masked_attention_backward_bruteforce(f(qb[t0:t1]), f(kb[t0:t1]), f(vb[t0:t1]),
+                                                                           f(dob[t0:t1]), po, th, layout=layout)
+                assert_grad_close(gq[t0:t1], rq, f"{tag}, dq {prompts}")
+                assert_grad_close(gk[t0:t1], rk, f"{tag}, dk {prompts}")
+                assert_grad_close(gv[t0:t1], rv, f"{tag}, dv {prompts}")
+        else:
+            nb, lq, gathered = int(rng.integers(1, 9)), int(rng.choice([1, 17, 64, 90])), bool(rng.integers(0, 2))
+            lens = [max(1, x) for x in _drawn_lengths(rng, nb, 300)]
+            Tc, order = int(sum(lens)), rng.permutation(nb)
+            k_raw, vb = wl.normal_bf16_bits(s0, (Tc, hkv, d)), wl.normal_bf16_bits(s0 + 1, (Tc, hkv, d))
+            qb, kfb, vfb = gen_qkv(s0 + 2, lq, hq, hkv, d)
+            cache_off, at = np.zeros(nb, dtype=np.int32), 0
+            for b in order:  # the cache holds the blocks in another order than the prompt
+                cache_off[b] = at
+                at += lens[b]
+            k_cache, v_cache = np.zeros((Tc, hkv, d), dtype=np.uint16), np.zeros((Tc, hkv, d), dtype=np.uint16)
+            k_ctx, pos = np.zeros((Tc, hkv, d)), 0
+            for b in range(nb):
+                L = lens[b]
+                k_local = wl.f32_to_bf16_bits(oracle.rope_dense(f(k_raw[pos:pos + L]), np.arange(L), th, layout).astype(np.float32))
+                k_cache[cache_off[b]:cache_off[b] + L] = k_local
+                v_cache[cache_off[b]:cache_off[b] + L] = vb[pos:pos + L]
+                k_ctx[pos:pos + L] = oracle.reencode(f(k_local), [0], [0], [L], th, layout=layout, old_pos0=[0], new_pos0=[pos])
+                pos += L
+            ref = oracle.final_block(f(qb), k_ctx, f(vb), f(kfb), f(vfb), [0, lq], [0, Tc], th, layout=layout)
+            cu_q, cu_blk, bl = np.array([0, lq], dtype=np.int32), np.array([0, nb], dtype=np.int32), np.array(lens, dtype=np.int32)
+            old = ba.ba_set_gather_below(10 ** 6 if gathered else 0)
+            try:
+                o = torch.full((lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+                ws = torch.empty(max(256, ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, bl)),
+                                 dtype=torch.uint8, device="cuda")
+                ba.ba_final_block_attention_cached(heads, dev_bf16(qb), dev_bf16(k_cache), dev_bf16(v_cache), dev_bf16(kfb),
+                                                   dev_bf16(vfb), o, None, cu_q, cu_blk, cache_off, bl, None, None, None, ws)
+                torch.cuda.synchronize()
+            finally:
+                ba.ba_set_gather_below(old)
+            assert_attention_close(host_f64(o), ref, f"{tag}, cached {lens} x {lq}, {'gathered' if gathered else 'table'}")
