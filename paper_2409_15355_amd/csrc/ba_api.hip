@@ -925,10 +925,15 @@ int32_t ba_reencode_positions(const ba_heads *heads, const ba_tensor *k_src, con
       src_hi = std::max<int64_t>(src_hi, (int64_t)src_tok_off[b] + len[b]);
       dst_hi = std::max<int64_t>(dst_hi, (int64_t)dst_tok_off[b] + len[b]);
     }
-    const int64_t src_span = ((n_layers - 1) * layer_stride_src + src_hi * k_src->stride_tok) * (int64_t)es;
-    const int64_t dst_span = ((n_layers - 1) * layer_stride_dst + dst_hi * k_dst->stride_tok) * (int64_t)es;
+    // (up to the last element touched: the last token's last head, not a whole token stride beyond it,
+    // or a view into a wider buffer would seem to reach into whatever is allocated behind that buffer)
+    const int64_t last_head = (int64_t)(heads->n_kv_heads - 1);
+    const int64_t src_span =
+        ((n_layers - 1) * layer_stride_src + (src_hi - 1) * k_src->stride_tok + last_head * k_src->stride_head + D) * (int64_t)es;
+    const int64_t dst_span =
+        ((n_layers - 1) * layer_stride_dst + (dst_hi - 1) * k_dst->stride_tok + last_head * k_dst->stride_head + D) * (int64_t)es;
     const char *s0 = (const char *)k_src->ptr, *d0 = (const char *)k_dst->ptr;
-    if (n_layers > 0 && s0 < d0 + dst_span && d0 < s0 + src_span)
+    if (n_layers > 0 && src_hi > 0 && dst_hi > 0 && s0 < d0 + dst_span && d0 < s0 + src_span)
       return fail(BA_ERR_INVALID_ARG, "k_dst overlaps k_src without being exactly in place");
   }
   if (!same_buf) {

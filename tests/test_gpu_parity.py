@@ -1189,3 +1189,53 @@ def test_drawn_shapes_match_the_oracle(ba, seed):
             finally:
                 ba.ba_set_gather_below(old)
             assert_attention_close(host_f64(o), ref, f"{tag}, cached {lens} x {lq}, {'gathered' if gathered else 'table'}")
+
+
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_drawn_reencode_cases_match_the_oracle(ba, seed):
+    """Sixteen re-encode cases per seed: 1-3 layers, 1-6 blocks (some empty) gathered into a permuted
+    destination, both dtypes, both modes, both layouts, old and new positions anywhere in 0..131071
+    (so shifts of either sign), head counts that take the kernel's different head splits, and for
+    half of the bf16 cases a head-strided source (a view into a wider cache)."""
+    torch = torch_mod()
+    rng = np.random.default_rng(seed)
+    for case in range(16):
+        d, hkv = int(rng.choice([64, 128])), int(rng.choice([1, 2, 8]))
+        layout, mode, f32 = int(rng.integers(0, 2)), int(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        base, n_layers, nb = float(rng.choice([1e4, 5e5])), int(rng.integers(1, 4)), int(rng.integers(1, 7))
+        lens = [int(x) for x in rng.choice([0, 1, 7, 64, 100, 257, 600], nb)]
+        src_off = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int32)
+        T = max(int(np.sum(lens)), 1)
+        dst_off, at = np.zeros(nb, dtype=np.int32), 0
+        for b in rng.permutation(nb):
+            dst_off[b] = at
+            at += lens[b]
+        old = (np.zeros(nb) if mode == 1 else rng.integers(0, 131072, nb)).astype(np.int32)
+        new = rng.integers(0, 131072, nb).astype(np.int32)
+        th = oracle.theta(base, d)
+        heads = ba.Heads(hkv, hkv, d, base, rope_layout=layout)
+        tag = f"seed {seed} case {case}: D {d}, {hkv} heads, layout {layout}, mode {mode}, {'f32' if f32 else 'bf16'}, {lens}"
+        if f32:
+            k = wl.normal_f32(seed * 100 + case, (n_layers, T, hkv, d))
+            ref = oracle.reencode(k.astype(np.float64), src_off, dst_off, lens, th, old_pos0=old, new_pos0=new, mode=mode,
+                                  layout=layout)
+            src = torch.from_numpy(k).cuda()
+            dst = torch.zeros_like(src)
+            ba.ba_reencode_positions(heads, src, dst, src_off, dst_off, lens, old, new, mode)
+            torch.cuda.synchronize()
+            rel = pair_norm_rel_err(host_f64(dst), ref, layout)
+            assert rel <= REENC_F32_REL_TOL, f"{tag}: relative error {rel:.3e}"
+        else:
+            kb = wl.normal_bf16_bits(seed * 100 + case, (n_layers, T, hkv, d))
+            ref = oracle.reencode(oracle.bf16_bits_to_f64(kb), src_off, dst_off, lens, th, old_pos0=old, new_pos0=new,
+                                  mode=mode, layout=layout)
+            if case % 2:  # the source as a view into a cache with twice the heads
+                wide = torch.zeros((n_layers, T, 2 * hkv, d), dtype=torch.bfloat16, device="cuda")
+                wide[:, :, hkv:] = dev_bf16(kb)
+                src = wide[:, :, hkv:]
+            else:
+                src = dev_bf16(kb)
+            dst = torch.zeros((n_layers, T, hkv, d), dtype=torch.bfloat16, device="cuda")
+            ba.ba_reencode_positions(heads, src, dst, src_off, dst_off, lens, old, new, mode)
+            torch.cuda.synchronize()
+            assert_reencode_bf16(host_bits(dst), ref, layout, tag)
