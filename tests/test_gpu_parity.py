@@ -259,6 +259,61 @@ def test_final_block_matches_oracle(ba, case, layout):
     assert_attention_close(host_f64(o), ref, name)
 
 
+@pytest.mark.parametrize("route", ["contiguous", "block-table"])
+def test_final_block_context_rows_beyond_four_gigabytes(ba, route):
+    """The context's rows lie 16 MB apart (views with a token stride of 2^23 elements into 5 GB
+    buffers), so the byte offsets of the later key tiles do not fit 32 bits; through
+    ba_final_block_attention on a re-encoded context, and through the block table on two cached
+    blocks stored in the opposite order."""
+    torch = torch_mod()
+    hq, hkv, d, base = 4, 1, 128, 10000.0
+    tc, lq, stride = 300, 40, 1 << 23
+    cu_q, cu_ctx = np.array([0, lq], dtype=np.int32), np.array([0, tc], dtype=np.int32)
+    qb, kfb, vfb = gen_qkv(950, lq, hq, hkv, d)
+    k_raw, vcb = wl.normal_bf16_bits(953, (tc, hkv, d)), wl.normal_bf16_bits(954, (tc, hkv, d))
+    th = oracle.theta(base, d)
+    f = oracle.bf16_bits_to_f64
+    heads = ba.Heads(hq, hkv, d, base)
+
+    def spread(bits):
+        big = torch.empty(tc * stride, dtype=torch.bfloat16, device="cuda")
+        view = big.as_strided((tc, hkv, d), (stride, d, 1))
+        view.copy_(dev_bf16(bits))
+        assert view.stride(0) * 2 * (tc - 1) > 1 << 32
+        return view
+
+    if route == "contiguous":
+        k_view, v_view = spread(k_raw), spread(vcb)
+        ref = oracle.final_block(f(qb), f(k_raw), f(vcb), f(kfb), f(vfb), cu_q, cu_ctx, th)
+        o = gpu_final(ba, heads, dev_bf16(qb), k_view, v_view, dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
+    else:
+        # prompt = block 0 (tokens 0..149) then block 1 (150..299); the cache holds block 1 first,
+        # each block's keys rotated at its local positions
+        lens, cache_off = [150, 150], np.array([150, 0], dtype=np.int32)
+        k_cache, v_cache, k_ctx = np.zeros_like(k_raw), np.zeros_like(vcb), np.zeros((tc, hkv, d))
+        for b, (p0, L) in enumerate(((0, 150), (150, 150))):
+            k_local = wl.f32_to_bf16_bits(oracle.rope_dense(f(k_raw[p0:p0 + L]), np.arange(L), th, 0).astype(np.float32))
+            k_cache[cache_off[b]:cache_off[b] + L] = k_local
+            v_cache[cache_off[b]:cache_off[b] + L] = vcb[p0:p0 + L]
+            k_ctx[p0:p0 + L] = oracle.reencode(f(k_local), [0], [0], [L], th, old_pos0=[0], new_pos0=[p0])
+        ref = oracle.final_block(f(qb), k_ctx, f(vcb), f(kfb), f(vfb), cu_q, cu_ctx, th)
+        k_view, v_view = spread(k_cache), spread(v_cache)
+        cu_blk, bl = np.array([0, 2], dtype=np.int32), np.array(lens, dtype=np.int32)
+        old = ba.ba_set_gather_below(0)
+        try:
+            o = torch.full((lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+            ws = torch.empty(max(256, ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, bl)),
+                             dtype=torch.uint8, device="cuda")
+            ba.ba_final_block_attention_cached(heads, dev_bf16(qb), k_view, v_view, dev_bf16(kfb), dev_bf16(vfb), o, None,
+                                               cu_q, cu_blk, cache_off, bl, None, None, None, ws)
+            torch.cuda.synchronize()
+        finally:
+            ba.ba_set_gather_below(old)
+    assert_attention_close(host_f64(o), ref, "context rows 16 MB apart, " + route)
+    del k_view, v_view
+    torch.cuda.empty_cache()
+
+
 def _with_component(bits, rows, dim, value):
     """Copy of a bf16 tensor with one head dimension of some rows set to a value (exact in bf16)."""
     x = wl.bf16_bits_to_f32(bits).copy()
