@@ -184,6 +184,14 @@ def test_whole_prompts_rejects_bad_arguments_and_sizes_workspace(lib):
         (164 * 128 * 4 + 255) // 256 * 256
     assert ba.ba_block_attention_prompts_workspace_bytes(h, [0, 2], [0, 100, 164], ba.ROPE_NONE) == 0
     assert call(h, [0, 2], [0, 0, 0]) == 0                  # no tokens: legal no-op
+    # a block whose row offsets would not fit the kernel's 32-bit arithmetic: 3,000 tokens at a token
+    # stride of 2^19 elements
+    wide = fake()
+    wide.stride_tok = 1 << 19
+    cb, of = i32([0, 2]), i32([0, 3000, 3064])
+    rc = lib.ba_block_attention_prompts(ctypes.byref(h.c), ctypes.byref(wide), ctypes.byref(t), ctypes.byref(t),
+                                        ctypes.byref(wide), None, None, 1, p(cb), p(of), 1, None, 0, None)
+    assert rc == -2 and b"too long" in lib.ba_last_error()
 
 
 def test_whole_prompts_backward_rejects_bad_arguments_and_sizes_workspace(lib):

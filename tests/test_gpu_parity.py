@@ -221,6 +221,35 @@ def test_encode_strided_views(ba):
     assert_attention_close(host_f64(o), ref_o, "strided")
 
 
+def test_encode_with_token_strides_too_wide_for_the_short_block_schedule(ba):
+    """q and o as views with a token stride of 2^18 elements: the short-block schedule keeps 32-bit row
+    offsets inside a block, which such strides would overflow at its longest blocks, so the call takes
+    the main schedule (64-bit row addresses) whatever the block lengths; same results."""
+    torch = torch_mod()
+    hq, hkv, d, base = 8, 2, 128, 500000.0
+    lens = [150, 64, 33]
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T, stride = int(offs[-1]), 1 << 18
+    qb, kb, vb = gen_qkv(240, T, hq, hkv, d)
+    q_big = torch.zeros(T * stride, dtype=torch.bfloat16, device="cuda")
+    o_big = torch.zeros(T * stride, dtype=torch.bfloat16, device="cuda")
+    q = q_big.as_strided((T, hq, d), (stride, d, 1))
+    o = o_big.as_strided((T, hq, d), (stride, d, 1))
+    q.copy_(dev_bf16(qb))
+    k, v = dev_bf16(kb), dev_bf16(vb)
+    k_local = torch.empty_like(k)
+    heads = ba.Heads(hq, hkv, d, base)
+    ws = torch.empty(max(1, ba.ba_encode_blocks_workspace_bytes(heads, offs, ba.ROPE_APPLY, True)), dtype=torch.uint8, device="cuda")
+    ba.ba_encode_blocks(heads, q, k, v, o, k_local, offs, ba.ROPE_APPLY, ws)
+    torch.cuda.synchronize()
+    f = oracle.bf16_bits_to_f64
+    ref_o, ref_k = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, oracle.theta(base, d))
+    assert_attention_close(host_f64(o), ref_o, "wide token strides")
+    assert_reencode_bf16(host_bits(k_local), ref_k, 0, "wide token strides, k_local")
+    del q_big, o_big, q, o
+    torch.cuda.empty_cache()
+
+
 # --------------------------------------------------------------------------------------------
 # a-3: final-block attention
 # --------------------------------------------------------------------------------------------
