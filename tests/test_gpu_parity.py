@@ -250,6 +250,34 @@ def test_encode_with_token_strides_too_wide_for_the_short_block_schedule(ba):
     torch.cuda.empty_cache()
 
 
+def test_encode_short_block_schedule_near_the_end_of_its_row_offsets(ba):
+    """A 6,000-token block with q and o at a token stride of 2^17 elements: the largest row offsets
+    the short-block schedule accepts (1.5 GB from the block's first row), checked on sampled rows
+    including the last ones."""
+    torch = torch_mod()
+    hq, hkv, d, base = 4, 1, 64, 10000.0
+    L, stride = 6000, 1 << 17
+    offs = np.array([0, L], dtype=np.int32)
+    qb, kb, vb = gen_qkv(250, L, hq, hkv, d)
+    q_big = torch.zeros(L * stride, dtype=torch.bfloat16, device="cuda")
+    o_big = torch.zeros(L * stride, dtype=torch.bfloat16, device="cuda")
+    q = q_big.as_strided((L, hq, d), (stride, d, 1))
+    o = o_big.as_strided((L, hq, d), (stride, d, 1))
+    q.copy_(dev_bf16(qb))
+    k, v = dev_bf16(kb), dev_bf16(vb)
+    heads = ba.Heads(hq, hkv, d, base)
+    ws = torch.empty(max(1, ba.ba_encode_blocks_workspace_bytes(heads, offs, ba.ROPE_APPLY, False)), dtype=torch.uint8, device="cuda")
+    ba.ba_encode_blocks(heads, q, k, v, o, None, offs, ba.ROPE_APPLY, ws)
+    torch.cuda.synchronize()
+    rows = sorted(set([0, 1, 31, 32, 127, 128, 2999, 4095, 4096, L - 129, L - 2, L - 1] +
+                      np.random.default_rng(5).integers(0, L, 40).tolist()))
+    f = oracle.bf16_bits_to_f64
+    ref, _ = oracle.encode_blocks(f(qb), f(kb), f(vb), offs, oracle.theta(base, d), rows=rows, want_k_local=False)
+    assert_attention_close(host_f64(o[rows]), ref, "row offsets up to 1.5 GB")
+    del q_big, o_big, q, o
+    torch.cuda.empty_cache()
+
+
 # --------------------------------------------------------------------------------------------
 # a-3: final-block attention
 # --------------------------------------------------------------------------------------------
