@@ -1108,6 +1108,44 @@ def test_whole_prompts_forward_and_backward_on_strided_views(ba):
         assert_grad_close(gv[t0:t1], rv, f"strided dv, prompt {n}")
 
 
+def test_whole_prompts_backward_near_the_end_of_its_row_offsets(ba):
+    """o, d_out and dq_out at a token stride of 2^19 elements with a 2,000-token passage: row offsets
+    of almost 2^31 bytes inside a block, the most the two calls accept."""
+    torch = torch_mod()
+    hq, hkv, d, base = 4, 1, 64, 10000.0
+    prompts, stride = [[2000, 1000]], 1 << 19
+    offs, cu_blk = np.array([0, 2000, 3000], dtype=np.int32), np.array([0, 2], dtype=np.int32)
+    T = 3000
+    qb, kb, vb = gen_qkv(490, T, hq, hkv, d)
+    dob = wl.normal_bf16_bits(493, (T, hq, d))
+
+    def wide():
+        big = torch.zeros(T * stride, dtype=torch.bfloat16, device="cuda")
+        return big, big.as_strided((T, hq, d), (stride, d, 1))
+
+    (o_big, o), (do_big, do), (dq_big, dq) = wide(), wide(), wide()
+    do.copy_(dev_bf16(dob))
+    q, k, v = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb)
+    dk, dv = torch.empty_like(k), torch.empty_like(v)
+    lse = torch.empty((T, hq), dtype=torch.float32, device="cuda")
+    heads = ba.Heads(hq, hkv, d, base)
+    ws_f = torch.empty(ba.ba_block_attention_prompts_workspace_bytes(heads, cu_blk, offs, 1, False), dtype=torch.uint8, device="cuda")
+    ba.ba_block_attention_prompts(heads, q, k, v, o, None, lse, cu_blk, offs, 1, ws_f)
+    ws_b = torch.empty(ba.ba_block_attention_prompts_backward_workspace_bytes(heads, cu_blk, offs), dtype=torch.uint8, device="cuda")
+    ba.ba_block_attention_prompts_backward(heads, q, k, v, o, lse, do, dq, dk, dv, cu_blk, offs, ws_b)
+    torch.cuda.synchronize()
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(base, d)
+    ref = oracle.masked_attention_bruteforce(f(qb), f(kb), f(vb), offs, th)
+    assert_attention_close(host_f64(o), ref, "wide strides, forward")
+    rq, rk, rv, _ = oracle.masked_attention_backward_bruteforce(f(qb), f(kb), f(vb), f(dob), offs, th)
+    assert_grad_close(host_f64(dq), rq, "wide strides, dq")
+    assert_grad_close(host_f64(dk), rk, "wide strides, dk")
+    assert_grad_close(host_f64(dv), rv, "wide strides, dv")
+    del o_big, do_big, dq_big, o, do, dq
+    torch.cuda.empty_cache()
+
+
 def test_calls_can_be_captured_in_a_hip_graph(ba):
     """The library only enqueues kernels on the caller's stream (no allocation, no copy, no
     synchronisation), so a sequence of calls can be captured and replayed: several replays, with
