@@ -371,6 +371,22 @@ def test_final_block_context_rows_beyond_four_gigabytes(ba, route):
     torch.cuda.empty_cache()
 
 
+def test_final_block_over_300k_context_tokens_sampled(ba):
+    """300,007 context tokens (4,688 key tiles, the last one ragged) behind 33 query tokens: the most
+    splits the host plans, long walks per split; every fourth query row against the oracle."""
+    hq, hkv, d, base = 4, 1, 128, 500000.0
+    tc, lq = 300_007, 33
+    cu_q, cu_ctx = np.array([0, lq], dtype=np.int32), np.array([0, tc], dtype=np.int32)
+    qb, kfb, vfb = gen_qkv(960, lq, hq, hkv, d)
+    kcb, vcb = wl.normal_bf16_bits(963, (tc, hkv, d)), wl.normal_bf16_bits(964, (tc, hkv, d))
+    heads = ba.Heads(hq, hkv, d, base)
+    o = gpu_final(ba, heads, dev_bf16(qb), dev_bf16(kcb), dev_bf16(vcb), dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
+    rows = list(range(0, lq, 4)) + [lq - 1]
+    f = oracle.bf16_bits_to_f64
+    ref = oracle.final_block(f(qb), f(kcb), f(vcb), f(kfb), f(vfb), cu_q, cu_ctx, oracle.theta(base, d), rows=rows)
+    assert_attention_close(host_f64(o)[rows], ref, "300,007 context tokens")
+
+
 def _with_component(bits, rows, dim, value):
     """Copy of a bf16 tensor with one head dimension of some rows set to a value (exact in bf16)."""
     x = wl.bf16_bits_to_f32(bits).copy()
