@@ -116,6 +116,27 @@ def test_reencode_f32_relative_error(ba, layout, mode):
     assert rel <= REENC_F32_REL_TOL, f"relative error {rel:.3e}"
 
 
+def test_reencode_2500_blocks_in_one_call(ba):
+    """More blocks than the larger of the two block tables holds (three launches), gathered into the
+    reverse order, two layers."""
+    torch = torch_mod()
+    d, hkv, nb = 64, 2, 2500
+    lens = [(3 * i) % 7 for i in range(nb)]  # some empty
+    src_off = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int32)
+    T = int(np.sum(lens))
+    dst_off = (T - src_off - np.array(lens)).astype(np.int32)
+    new_pos0 = ((np.arange(nb) * 37) % 9000).astype(np.int32)
+    kb = wl.normal_bf16_bits(41, (2, T, hkv, d))
+    th = oracle.theta(10000.0, d)
+    heads = ba.Heads(hkv, hkv, d, 10000.0)
+    ref = oracle.reencode(oracle.bf16_bits_to_f64(kb), src_off, dst_off, lens, th, new_pos0=new_pos0)
+    src = dev_bf16(kb)
+    dst = torch.zeros_like(src)
+    ba.ba_reencode_positions(heads, src, dst, src_off, dst_off, lens, None, new_pos0, ba.REENC_SHIFT)
+    torch.cuda.synchronize()
+    assert_reencode_bf16(host_bits(dst), ref, 0, "2500 blocks")
+
+
 def test_reencode_negative_shift_and_strided_layers(ba):
     """Moving a block to a smaller position (negative shift) and a destination whose layer
     stride differs from the source's."""
@@ -150,6 +171,9 @@ ENC_CASES = [
     # medium blocks: many key tiles per work item of the short-block schedule
     ("medium-gqa4", 8, 2, 128, 500000.0, [700, 1, 63, 130]),
     ("medium-gqa8-d64", 8, 1, 64, 10000.0, [1000, 333]),
+    # more blocks than one launch's table holds, on either schedule
+    ("700-blocks-gqa4", 4, 1, 64, 10000.0, [1 + (7 * i) % 23 for i in range(700)]),
+    ("700-blocks-mha", 2, 2, 64, 10000.0, [1 + (5 * i) % 17 for i in range(700)]),
 ]
 
 
