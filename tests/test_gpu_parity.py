@@ -711,6 +711,12 @@ def _cached_case(name):
         blocks = [(0, 150, 1000), (150, 90, 37), (240, 64, 0)]
         prompts = [([1, 2, 0], 40, [5, 200, 300], 777), ([0], 3, [10], None)]
         return 8, 8, 128, 10000.0, 310, blocks, prompts
+    if name == "seventy-prompts-shared-cache":
+        # more prompts than one launch's tables hold (and more than the small tables: the large ones);
+        # every prompt picks three of twelve cached blocks, so blocks are shared between prompts
+        blocks = [(b * 130, 100 + 7 * (b % 5), 0) for b in range(12)]
+        prompts = [([(5 * n) % 12, (5 * n + 3) % 12, (7 * n + 1) % 12], 1 + n % 4, None, None) for n in range(70)]
+        return 4, 1, 64, 10000.0, 12 * 130, blocks, prompts
     raise KeyError(name)
 
 
@@ -723,7 +729,8 @@ def cached_route(ba, request):
     ba.ba_set_gather_below(old)
 
 
-@pytest.mark.parametrize("name", ["rag-shared-blocks", "deep-split-d64", "moved-cache-positions"])
+@pytest.mark.parametrize("name", ["rag-shared-blocks", "deep-split-d64", "moved-cache-positions",
+                                  "seventy-prompts-shared-cache"])
 @pytest.mark.parametrize("layout", [0, 1])
 def test_final_block_from_block_cache_matches_oracle(ba, name, layout, cached_route):
     torch = torch_mod()
