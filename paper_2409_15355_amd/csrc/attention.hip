@@ -194,7 +194,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const int my_row = row0 + wave * 32 + col;
   const bool row_ok = my_row < n_rows;
   const int my_tok = (int)fast_div((uint32_t)my_row, p.group_div);  // query token (inside the problem) of this lane's column
-  const float c2 = p.scale_log2e;
   bf16x8_t qf[G::KCH];  // Q fragments, filled below once the first tile copies are on their way
 
   // ---- per-lane LDS read offsets, relative to a tile buffer; the rest of an address is a
