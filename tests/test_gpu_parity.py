@@ -1193,6 +1193,43 @@ def test_whole_prompts_backward_near_the_end_of_its_row_offsets(ba):
     torch.cuda.empty_cache()
 
 
+def test_calls_on_two_streams_at_once_do_not_disturb_each_other(ba):
+    """Two independent final-block problems (their own tensors and workspaces) issued alternately on
+    two streams, thirty calls each without a synchronisation in between, give the bits of the same
+    calls issued alone: the library keeps no state between calls that two streams could share."""
+    torch = torch_mod()
+    hq, hkv, d = 8, 2, 128
+    heads = ba.Heads(hq, hkv, d, 500000.0)
+    probs = []
+    for j, (tc, lq) in enumerate(((3000, 70), (1111, 130))):
+        cu_q, cu_ctx = np.array([0, lq], dtype=np.int32), np.array([0, tc], dtype=np.int32)
+        qb, kfb, vfb = gen_qkv(1500 + 10 * j, lq, hq, hkv, d)
+        kcb, vcb = wl.normal_bf16_bits(1503 + 10 * j, (tc, hkv, d)), wl.normal_bf16_bits(1504 + 10 * j, (tc, hkv, d))
+        t = [dev_bf16(x) for x in (qb, kcb, vcb, kfb, vfb)]
+        ws = torch.empty(max(256, ba.ba_final_block_attention_workspace_bytes(heads, cu_q, cu_ctx, 1, False)), dtype=torch.uint8,
+                         device="cuda")
+        probs.append((t, cu_q, cu_ctx, ws, torch.empty((lq, hq, d), dtype=torch.bfloat16, device="cuda")))
+
+    def call(j, stream=None):
+        t, cu_q, cu_ctx, ws, o = probs[j]
+        ba.ba_final_block_attention(heads, t[0], t[1], t[2], t[3], t[4], o, None, cu_q, cu_ctx, None, 1, ws, stream=stream)
+
+    alone = []
+    for j in range(2):
+        call(j)
+        torch.cuda.synchronize()
+        alone.append(host_bits(probs[j][4]).copy())
+        probs[j][4].fill_(float("nan"))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for _ in range(30):
+        for j in range(2):
+            call(j, streams[j])
+    torch.cuda.synchronize()
+    for j in range(2):
+        assert np.array_equal(host_bits(probs[j][4]), alone[j]), f"problem {j}"
+
+
 def test_calls_can_be_captured_in_a_hip_graph(ba):
     """The library only enqueues kernels on the caller's stream (no allocation, no copy, no
     synchronisation), so a sequence of calls can be captured and replayed: several replays, with
