@@ -255,7 +255,33 @@ def main() -> int:
                                          "gather_GBps": round(nbytes / ms_g / 1e6, 1),
                                          "inplace_ms": round(ms_i, 4), "inplace_GBps": round(nbytes / ms_i / 1e6, 1),
                                          "frac_of_hbm_peak": round(nbytes / min(ms_g, ms_i) / 1e6 / HBM_PEAK_GBS, 4)}
-            del cache, dst
+            # the other forms of the same pass: every token at its own angle (a cache of un-rotated keys),
+            # the half-split pair layout, and fp32 keys (twice the bytes)
+            def absolute():
+                ba.ba_reencode_positions(h4, cache, dst, src_off, new_pos0, lens, None, new_pos0, ba.REENC_ABSOLUTE)
+
+            h4_half = ba.Heads(hkv, hkv, d, w4.rope_base, rope_layout=ba.ROPE_HALF)
+
+            def half_layout():
+                ba.ba_reencode_positions(h4_half, cache, dst, src_off, new_pos0, lens, None, new_pos0, ba.REENC_SHIFT)
+
+            reps_o = max(reps // 2, 5)
+            ms_abs, _ = timed(absolute, reps_o, 2)
+            ms_half, _ = timed(half_layout, reps_o, 2)
+            del dst
+            torch.cuda.empty_cache()
+            cache32 = cache.float()
+            dst32 = torch.empty_like(cache32)
+            del cache
+
+            def f32_keys():
+                ba.ba_reencode_positions(h4, cache32, dst32, src_off, new_pos0, lens, None, new_pos0, ba.REENC_SHIFT)
+
+            ms_f32, _ = timed(f32_keys, reps_o, 2)
+            rows_out["reencode_cfg4"].update({"absolute_mode_GBps": round(nbytes / ms_abs / 1e6, 1),
+                                              "half_layout_GBps": round(nbytes / ms_half / 1e6, 1),
+                                              "fp32_GBps": round(2 * nbytes / ms_f32 / 1e6, 1)})
+            del cache32, dst32
             torch.cuda.empty_cache()
         # a-1, full-attention mode: the same 32,000 tokens as ONE block
         if args.only in ("", "single"):
