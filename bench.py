@@ -325,7 +325,18 @@ def main() -> int:
             lens3 = np.diff(offs3).astype(np.int64)
             fl = 4.0 * d * hq * float((lens3 * (lens3 + 1) // 2).sum())
             byts = 2.0 * T3 * d * (2 * hq + 4 * hkv)  # q, o, k, k_local(w), k_local(r), v
+            # issued work: every (128-row tile, 32-key tile) pair the short-block schedule walks is computed
+            # in full, masked or not (rows = tokens x query heads of a KV group)
+            G3 = hq // hkv
+            issued = 0
+            for L in lens3.tolist():
+                n_rows = L * G3
+                for rt in range((n_rows + 127) // 128):
+                    last_tok = (min(n_rows, (rt + 1) * 128) - 1) // G3
+                    issued += 128 * 32 * (last_tok // 32 + 1)
+            fl_issued = 4.0 * d * hkv * issued
             rows_out["encode_cfg3_ragged"] = {"ms": round(ms_e, 4), "algorithmic_TFLOPs": round(fl / ms_e / 1e9, 1),
+                                              "issued_TFLOPs": round(fl_issued / ms_e / 1e9, 1),
                                               "GBps": round(byts / ms_e / 1e6, 1), "tokens": T3}
             del q, k, v, o, kl, ws_3
         # a-3 batched: config 3's eight final blocks (32..128 query tokens over about 4,000 context tokens each)
