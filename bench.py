@@ -45,7 +45,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=8)  # (the first six steps run below the steady clock)
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows (config 3/4, single block)")
@@ -76,25 +76,30 @@ def main() -> int:
         return torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
 
     def timed(fn, steps, warmup):
-        for _ in range(warmup):
-            fn()
-        torch.cuda.synchronize()
         # a full collection of the interpreter's garbage takes tens of milliseconds in this process
-        # and would land in the middle of a timed region every few hundred calls
+        # and would land in the middle of a timed region every few hundred calls; it runs before the
+        # warm-up, so that the GPU does not sit idle (and drop its clock) right before the timed region
         gc.collect()
         gc.disable()
         try:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            t0 = time.perf_counter()
-            e0.record()
-            for _ in range(steps):
+            # one event behind every step (no synchronisation between them): the mean over the whole
+            # region is the figure reported, the steps' own times give its median and minimum
+            marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+            for _ in range(warmup):
                 fn()
-            e1.record()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            marks[0].record()
+            for i in range(steps):
+                fn()
+                marks[i + 1].record()
             torch.cuda.synchronize()
             wall_ms = (time.perf_counter() - t0) * 1e3
         finally:
             gc.enable()
-        return max(e0.elapsed_time(e1), 0.0) / steps, wall_ms / steps
+        per_step = sorted(max(marks[i].elapsed_time(marks[i + 1]), 0.0) for i in range(steps))
+        timed.last_median_min = (per_step[len(per_step) // 2], per_step[0], per_step[-1]) if per_step else (0.0, 0.0, 0.0)
+        return max(marks[0].elapsed_time(marks[-1]), 0.0) / steps, wall_ms / steps
 
     # ------------------------------------------------------------------ headline: config 5
     w = wl.config5(n_layers=args.layers)
@@ -132,6 +137,7 @@ def main() -> int:
         ms_step, wall_ms_step = timed(step_final, args.steps, args.warmup)
     else:
         ms_step, wall_ms_step = timed(step_final, 1, 1)
+    step_median_ms, step_min_ms, step_max_ms = timed.last_median_min
     flops_layer = 4.0 * d * hq * visible_pairs_final(t_ctx, l_q)
     ms_layer = ms_step / w.n_layers
     tflops = flops_layer / (ms_layer * 1e-3) / 1e12
@@ -513,6 +519,9 @@ def main() -> int:
         "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4),
         "ms_per_layer": round(ms_layer, 5),
+        "ms_per_layer_median": round(step_median_ms / w.n_layers, 5),
+        "ms_per_layer_min": round(step_min_ms / w.n_layers, 5),
+        "ms_per_layer_max": round(step_max_ms / w.n_layers, 5),
         "host_wall_ms_per_step": round(wall_ms_step, 4),
         "frac_of_bf16_mfma_peak": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "higher_is_better": True,
