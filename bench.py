@@ -142,9 +142,14 @@ def main() -> int:
     ms_layer = ms_step / w.n_layers
     tflops = flops_layer / (ms_layer * 1e-3) / 1e12
 
-    # per-kernel times of the same steps, from the library's own events on the launch stream
+    # per-kernel times of the same steps, from the library's own events on the launch stream (a few
+    # steps without events go first, with no synchronisation in between, so that the recorded ones run
+    # at the steady clock like the timed region did)
+    prof_steps = min(args.steps, 10) if args.only == "" else 1
+    if args.only == "":
+        for _ in range(min(args.warmup, 4)):
+            step_final()
     ba.ba_profile_begin(1 << 16)
-    prof_steps = min(args.steps, 5) if args.only == "" else 1
     for _ in range(prof_steps):
         step_final()
     torch.cuda.synchronize()
