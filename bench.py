@@ -75,30 +75,40 @@ def main() -> int:
         g = torch.Generator(device=dev).manual_seed(seed)
         return torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
 
-    def timed(fn, steps, warmup):
+    def timed(fn, steps, warmup, per_step=False):
         # a full collection of the interpreter's garbage takes tens of milliseconds in this process
         # and would land in the middle of a timed region every few hundred calls; it runs before the
         # warm-up, so that the GPU does not sit idle (and drop its clock) right before the timed region
         gc.collect()
         gc.disable()
         try:
-            # one event behind every step (no synchronisation between them): the mean over the whole
-            # region is the figure reported, the steps' own times give its median and minimum
+            # per_step: one event behind every step (no synchronisation between them): the mean over the
+            # whole region is the figure reported, the steps' own times give its median and minimum
             marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
-            for _ in range(warmup):
+            # at least `warmup` calls, and at least about 30 ms of work: the clock needs that long to
+            # settle after an idle spell (allocating the next row's tensors is one)
+            fn()
+            torch.cuda.synchronize()
+            t_est = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            est = max(time.perf_counter() - t_est, 1e-6)
+            for _ in range(max(warmup - 2, 0, min(3000, int(0.03 / est)))):
                 fn()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             marks[0].record()
             for i in range(steps):
                 fn()
-                marks[i + 1].record()
+                if per_step or i == steps - 1:  # (an event costs microseconds: only where a step lasts milliseconds)
+                    marks[i + 1].record()
             torch.cuda.synchronize()
             wall_ms = (time.perf_counter() - t0) * 1e3
         finally:
             gc.enable()
-        per_step = sorted(max(marks[i].elapsed_time(marks[i + 1]), 0.0) for i in range(steps))
-        timed.last_median_min = (per_step[len(per_step) // 2], per_step[0], per_step[-1]) if per_step else (0.0, 0.0, 0.0)
+        if per_step:
+            each = sorted(max(marks[i].elapsed_time(marks[i + 1]), 0.0) for i in range(steps))
+            timed.last_median_min = (each[len(each) // 2], each[0], each[-1]) if each else (0.0, 0.0, 0.0)
         return max(marks[0].elapsed_time(marks[-1]), 0.0) / steps, wall_ms / steps
 
     # ------------------------------------------------------------------ headline: config 5
@@ -134,9 +144,9 @@ def main() -> int:
                                         None, ba.ROPE_APPLY, ws)
 
     if args.only == "":
-        ms_step, wall_ms_step = timed(step_final, args.steps, args.warmup)
+        ms_step, wall_ms_step = timed(step_final, args.steps, args.warmup, per_step=True)
     else:
-        ms_step, wall_ms_step = timed(step_final, 1, 1)
+        ms_step, wall_ms_step = timed(step_final, 1, 1, per_step=True)
     step_median_ms, step_min_ms, step_max_ms = timed.last_median_min
     flops_layer = 4.0 * d * hq * visible_pairs_final(t_ctx, l_q)
     ms_layer = ms_step / w.n_layers
