@@ -173,6 +173,26 @@ size_t ba_final_block_attention_workspace_bytes(const ba_heads *heads, int32_t n
                                                 int32_t rope_mode, int32_t have_k_f_rot_out);
 
 /*
+ * ba_final_block_attention for callers that cannot allocate device memory or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (without ws / ws_bytes), same kernels and bit-identical results; the workspace is a
+ * file-scope device array of BA_STATIC_SCRATCH_BYTES bytes that every GPU the library runs on holds
+ * until the process ends.  The call allocates nothing on the device and frees nothing.  A call whose
+ * ba_final_block_attention_workspace_bytes() exceeds BA_STATIC_SCRATCH_BYTES returns
+ * BA_ERR_WORKSPACE and launches nothing.  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on one GPU (two streams, two threads) race; calls on one stream are safe.
+ * Nothing in the array has to be cleared between calls: a call writes every byte it later reads.
+ */
+#define BA_STATIC_SCRATCH_BYTES (32u << 20)
+int32_t ba_final_block_attention_static(const ba_heads *heads, const ba_tensor *q_f,
+                                        const ba_tensor *k_ctx, const ba_tensor *v_ctx,
+                                        const ba_tensor *k_f, const ba_tensor *v_f,
+                                        const ba_tensor *o_out, const ba_tensor *k_f_rot_out,
+                                        int32_t n_prompts, const int32_t *cu_q,
+                                        const int32_t *cu_ctx, const int32_t *q_pos0,
+                                        int32_t rope_mode, void *stream);
+
+/*
  * Steps 2 and 3 in one call -- final-block attention straight from the block cache
  * (Section 2.3, Eq. 2 and 3; Section 2.5).
  *

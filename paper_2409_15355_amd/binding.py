@@ -26,6 +26,7 @@ EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin"
            "ba_encode_blocks",
            "ba_encode_blocks_workspace_bytes", "ba_reencode_positions",
            "ba_final_block_attention", "ba_final_block_attention_workspace_bytes",
+           "ba_final_block_attention_static",
            "ba_final_block_attention_cached", "ba_final_block_attention_cached_workspace_bytes",
            "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes", "ba_set_gather_below",
            "ba_block_attention_prompts_backward", "ba_block_attention_prompts_backward_workspace_bytes"]
@@ -87,6 +88,9 @@ def load():
     lib.ba_final_block_attention.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, _TP, _TP, ctypes.c_int32, _I32P,
                                              _I32P, _I32P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t,
                                              ctypes.c_void_p]
+    lib.ba_final_block_attention_static.restype = ctypes.c_int32
+    lib.ba_final_block_attention_static.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, _TP, _TP, ctypes.c_int32, _I32P,
+                                                    _I32P, _I32P, ctypes.c_int32, ctypes.c_void_p]
     lib.ba_final_block_attention_workspace_bytes.restype = ctypes.c_size_t
     lib.ba_final_block_attention_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, ctypes.c_int32,
                                                              ctypes.c_int32]
@@ -257,6 +261,20 @@ def ba_final_block_attention(heads: Heads, q_f, k_ctx, v_ctx, k_f, v_f, o_out, k
     _check(load().ba_final_block_attention(ctypes.byref(heads.c), _ref(tq), _ref(tkc), _ref(tvc), _ref(tkf),
                                            _ref(tvf), _ref(to), _ref(tkr), len(cq) - 1, _ip(cq), _ip(cc),
                                            _ip(qp), rope_mode, wp, wb, _stream_handle(stream)))
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def ba_final_block_attention_static(heads: Heads, q_f, k_ctx, v_ctx, k_f, v_f, o_out, k_f_rot_out, cu_q, cu_ctx,
+                                    q_pos0=None, rope_mode: int = ROPE_APPLY, stream=None) -> None:
+    """ba_final_block_attention with the workspace in the library's static device array (no allocation)."""
+    cq, cc, qp = _ints(cu_q), _ints(cu_ctx), _ints(q_pos0)
+    tq, tkc, tvc = _tensor(q_f), _tensor(k_ctx), _tensor(v_ctx)
+    tkf, tvf, to, tkr = _tensor(k_f), _tensor(v_f), _tensor(o_out), _tensor(k_f_rot_out)
+    _check(load().ba_final_block_attention_static(ctypes.byref(heads.c), _ref(tq), _ref(tkc), _ref(tvc), _ref(tkf),
+                                                  _ref(tvf), _ref(to), _ref(tkr), len(cq) - 1, _ip(cq), _ip(cc),
+                                                  _ip(qp), rope_mode, _stream_handle(stream)))
 
 
 def ba_final_block_attention_cached_workspace_bytes(heads: Heads, cu_q, cu_blk, blk_len,

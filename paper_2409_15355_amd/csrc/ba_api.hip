@@ -1129,6 +1129,58 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
 }  // extern "C"
 
 // ------------------------------------------------------------------------------------------
+// The allocation-free variant of ba_final_block_attention keeps its workspace (rotated final-block
+// q and k, split partials) in this array.  The name is a host-side stand-in for the symbol: host
+// code only ever uses the device address looked up per device below.
+static __device__ __align__(256) unsigned char scratch[BA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (every GPU holds its own copy of the array).
+int32_t scratch_address(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return device_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(BA_ERR_UNSUPPORTED, "device ordinal %d beyond %d", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return device_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!ptr || ((uintptr_t)ptr & 255)) return fail(BA_ERR_DEVICE, "static scratch: null or misaligned address");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return BA_OK;
+}
+}  // namespace
+
+extern "C" int32_t ba_final_block_attention_static(const ba_heads *heads, const ba_tensor *q_f, const ba_tensor *k_ctx,
+                                        const ba_tensor *v_ctx, const ba_tensor *k_f, const ba_tensor *v_f,
+                                        const ba_tensor *o_out, const ba_tensor *k_f_rot_out, int32_t n_prompts,
+                                        const int32_t *cu_q, const int32_t *cu_ctx, const int32_t *q_pos0,
+                                        int32_t rope_mode, void *stream_) {
+  int32_t rc;
+  if ((rc = check_heads(heads, true))) return rc;
+  if (rope_mode != BA_ROPE_NONE && rope_mode != BA_ROPE_APPLY)
+    return fail(BA_ERR_INVALID_ARG, "rope_mode %d unknown", rope_mode);
+  FinalPlan pl;
+  if ((rc = plan_final(heads, n_prompts, cu_q, cu_ctx, rope_mode, k_f_rot_out != nullptr, &pl))) return rc;
+  if (pl.total() > (size_t)BA_STATIC_SCRATCH_BYTES)
+    return fail(BA_ERR_WORKSPACE, "final block (static scratch): this call needs %zu bytes of workspace, the array holds %zu",
+                pl.total(), (size_t)BA_STATIC_SCRATCH_BYTES);
+  void *ws = nullptr;
+  if ((rc = scratch_address(&ws))) return rc;
+  // Every byte of the workspace that a call reads it has written before (rotated rows by the RoPE
+  // pre-pass, every split's partial of every row by the attention core), so nothing needs clearing.
+  return ba_final_block_attention(heads, q_f, k_ctx, v_ctx, k_f, v_f, o_out, k_f_rot_out, n_prompts, cu_q, cu_ctx,
+                                  q_pos0, rope_mode, ws, (size_t)BA_STATIC_SCRATCH_BYTES, stream_);
+}
+
+// ------------------------------------------------------------------------------------------
 namespace {
 
 struct BlocksPlan {
