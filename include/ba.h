@@ -211,10 +211,20 @@ int32_t ba_final_block_attention_static(const ba_heads *heads, const ba_tensor *
  * positions blk_new_pos0[b] + u (null -> the total length of the prompt's earlier blocks).
  * Final-block token i sits at q_pos0[n] + i (null -> the prompt's context length); q_f and k_f
  * are un-rotated and are rotated inside; k_f_rot_out (nullable) receives the rotated k_f.
- * Empty blocks are skipped.  At most 1024 non-empty blocks per prompt when the kernel reads the
- * block table (BA_ERR_UNSUPPORTED beyond; see ba_set_gather_below for the other route).  All arrays host; ws: 256-byte aligned, at least
- * ba_final_block_attention_cached_workspace_bytes() bytes.
+ * Empty blocks are skipped.
+ *
+ * gather_below: reading the block table in the kernel costs a fixed amount per block, a gathered
+ * copy of the context an amount per token; when the mean length of the call's non-empty blocks is
+ * below this many tokens (BA_GATHER_DEFAULT = 256 tokens; 0 = never gather) the call gathers the
+ * context into its workspace first (keys re-encoded on the way, values copied; the cache itself
+ * stays as it is) and continues as ba_final_block_attention.  Same results either way, to
+ * rounding.  The two routes need different workspaces: pass the same value to the size query.
+ * At most 1024 non-empty blocks per prompt when the kernel reads the block table
+ * (BA_ERR_UNSUPPORTED beyond); no such limit on the gathered route.
+ * All arrays host; ws: 256-byte aligned, at least
+ * ba_final_block_attention_cached_workspace_bytes() bytes for the same gather_below.
  */
+#define BA_GATHER_DEFAULT (-1)
 int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *q_f,
                                         const ba_tensor *k_cache, const ba_tensor *v_cache,
                                         const ba_tensor *k_f, const ba_tensor *v_f,
@@ -223,21 +233,13 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
                                         const int32_t *cu_blk, const int32_t *blk_tok_off,
                                         const int32_t *blk_len, const int32_t *blk_old_pos0,
                                         const int32_t *blk_new_pos0, const int32_t *q_pos0,
-                                        void *ws, size_t ws_bytes, void *stream);
+                                        int32_t gather_below, void *ws, size_t ws_bytes,
+                                        void *stream);
 size_t ba_final_block_attention_cached_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
                                                        const int32_t *cu_q, const int32_t *cu_blk,
                                                        const int32_t *blk_len,
-                                                       int32_t have_k_f_rot_out);
-/*
- * Tuning of ba_final_block_attention_cached.  Reading the block table in the kernel costs a fixed
- * amount per block, a gathered copy of the context an amount per token; when the mean length of a
- * call's non-empty blocks is below this many tokens (default 256) the call therefore gathers the
- * context into its workspace first (keys re-encoded on the way, values copied; the cache itself
- * stays as it is) and continues as ba_final_block_attention.  Same results either way, to
- * rounding.  0 = never gather.  Process-wide; set it before sizing a workspace, since the two
- * routes need different amounts.  Returns the previous value.
- */
-int32_t ba_set_gather_below(int32_t mean_block_tokens);
+                                                       int32_t have_k_f_rot_out,
+                                                       int32_t gather_below);
 
 /*
  * Whole prompts in one call -- the attention mask of Section 2.4 (what a block fine-tune step

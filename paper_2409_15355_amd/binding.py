@@ -28,7 +28,7 @@ EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin"
            "ba_final_block_attention", "ba_final_block_attention_workspace_bytes",
            "ba_final_block_attention_static",
            "ba_final_block_attention_cached", "ba_final_block_attention_cached_workspace_bytes",
-           "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes", "ba_set_gather_below",
+           "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes",
            "ba_block_attention_prompts_backward", "ba_block_attention_prompts_backward_workspace_bytes"]
 
 
@@ -96,19 +96,17 @@ def load():
                                                              ctypes.c_int32]
     lib.ba_final_block_attention_cached.restype = ctypes.c_int32
     lib.ba_final_block_attention_cached.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, _TP, _TP, ctypes.c_int32, _I32P,
-                                                    _I32P, _I32P, _I32P, _I32P, _I32P, _I32P, ctypes.c_void_p,
-                                                    ctypes.c_size_t, ctypes.c_void_p]
+                                                    _I32P, _I32P, _I32P, _I32P, _I32P, _I32P, ctypes.c_int32,
+                                                    ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.ba_final_block_attention_cached_workspace_bytes.restype = ctypes.c_size_t
     lib.ba_final_block_attention_cached_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, _I32P,
-                                                                    ctypes.c_int32]
+                                                                    ctypes.c_int32, ctypes.c_int32]
     lib.ba_block_attention_prompts_backward.restype = ctypes.c_int32
     lib.ba_block_attention_prompts_backward.argtypes = [_HP, _TP, _TP, _TP, _TP, ctypes.c_void_p, _TP, _TP, _TP, _TP,
                                                         ctypes.c_int32, _I32P, _I32P, ctypes.c_void_p, ctypes.c_size_t,
                                                         ctypes.c_void_p]
     lib.ba_block_attention_prompts_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.ba_block_attention_prompts_backward_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P]
-    lib.ba_set_gather_below.restype = ctypes.c_int32
-    lib.ba_set_gather_below.argtypes = [ctypes.c_int32]
     lib.ba_block_attention_prompts.restype = ctypes.c_int32
     lib.ba_block_attention_prompts.argtypes = [_HP, _TP, _TP, _TP, _TP, _TP, ctypes.c_void_p, ctypes.c_int32, _I32P,
                                                _I32P, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t,
@@ -145,22 +143,68 @@ class Heads:
 _dtype_codes = None  # torch dtype -> BA_DTYPE_*, filled on first use (torch is imported lazily)
 
 
-def _tensor(t, dtype_code: Optional[int] = None) -> Optional[BaTensor]:
-    """[tokens, heads, D] torch tensor (any token / head strides, D contiguous)."""
+def _tensor(t, name: str = "tensor", n_heads: Optional[int] = None, head_dim: Optional[int] = None,
+            min_tokens: int = 0, allow_f32: bool = False) -> Optional[BaTensor]:
+    """[tokens, heads, D] torch tensor on the GPU (any token / head strides, D contiguous).
+
+    The C boundary sees a pointer and two strides, not an extent: everything it cannot check is
+    checked here, before anything is launched -- the device, the dtype, heads and head_dim against
+    the call's head description, and that the tensor has at least the rows the call's offset
+    arrays reach."""
     global _dtype_codes
     if t is None:
         return None
-    st = t.stride()
-    if len(st) != 3 or st[2] != 1:
-        raise ValueError("expected a [tokens, heads, head_dim] tensor with contiguous head_dim")
-    if dtype_code is None:
-        if _dtype_codes is None:
-            import torch
-            _dtype_codes = {torch.float32: DTYPE_F32, torch.bfloat16: DTYPE_BF16}
-        dtype_code = _dtype_codes.get(t.dtype)
-        if dtype_code is None:
-            raise ValueError(f"dtype {t.dtype} not supported")
+    if _dtype_codes is None:
+        import torch
+        _dtype_codes = {torch.float32: DTYPE_F32, torch.bfloat16: DTYPE_BF16}
+    if not getattr(t, "is_cuda", False):
+        raise ValueError(f"{name}: expected a tensor in GPU memory, got one on {getattr(t, 'device', '?')}")
+    dtype_code = _dtype_codes.get(t.dtype)
+    if dtype_code is None or (dtype_code == DTYPE_F32 and not allow_f32):
+        raise ValueError(f"{name}: dtype {t.dtype} not supported here")
+    st, shp = t.stride(), tuple(t.shape)
+    if len(st) != 3 or (shp[2] > 1 and st[2] != 1):
+        raise ValueError(f"{name}: expected a [tokens, heads, head_dim] tensor with contiguous head_dim")
+    if n_heads is not None and shp[1] != n_heads:
+        raise ValueError(f"{name}: {shp[1]} heads, the call's head description says {n_heads}")
+    if head_dim is not None and shp[2] != head_dim:
+        raise ValueError(f"{name}: head_dim {shp[2]}, the call's head description says {head_dim}")
+    if shp[0] < min_tokens:
+        raise ValueError(f"{name}: {shp[0]} tokens, the call's offsets reach {min_tokens}")
     return BaTensor(t.data_ptr(), st[0], st[1], dtype_code)
+
+
+def _last(a: Optional[np.ndarray]) -> int:
+    """Rows a cumulative offset array reaches (0 for none)."""
+    return int(a[-1]) if a is not None and len(a) else 0
+
+
+def _reach(off: Optional[np.ndarray], ln: Optional[np.ndarray]) -> int:
+    """Rows that blocks [off[b], off[b] + len[b]) reach (empty blocks touch nothing)."""
+    if off is None or ln is None or not len(ln):
+        return 0
+    if len(off) != len(ln):
+        raise ValueError("per-block arrays of different lengths")
+    live = ln > 0
+    return int((off[live].astype(np.int64) + ln[live]).max()) if live.any() else 0
+
+
+def _same_len(n: int, **arrays) -> None:
+    for name, a in arrays.items():
+        if a is not None and len(a) != n:
+            raise ValueError(f"{name}: {len(a)} entries, expected {n}")
+
+
+def _lse(t, name: str, tokens: int, n_q_heads: int):
+    """float32 [tokens, n_q_heads], contiguous, on the GPU -> pointer (None stays None)."""
+    if t is None:
+        return None
+    import torch
+    if not t.is_cuda or t.dtype != torch.float32 or t.dim() != 2 or not t.is_contiguous():
+        raise ValueError(f"{name}: expected a contiguous float32 [tokens, n_q_heads] tensor in GPU memory")
+    if t.shape[1] != n_q_heads or t.shape[0] < tokens:
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, the call needs [{tokens}, {n_q_heads}]")
+    return ctypes.c_void_p(t.data_ptr())
 
 
 def _ref(x):
@@ -193,6 +237,8 @@ def _stream_handle(stream) -> int:
 def _ws(ws):
     if ws is None:
         return None, 0
+    if not getattr(ws, "is_cuda", False) or not ws.is_contiguous():
+        raise ValueError("workspace: expected a contiguous tensor in GPU memory")
     return ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
 
 
@@ -226,7 +272,9 @@ def ba_encode_blocks(heads: Heads, q, k, v, o_out, k_local_out, block_offsets, r
                      ws=None, stream=None) -> None:
     offs = _ints(block_offsets)
     wp, wb = _ws(ws)
-    tq, tk, tv, to, tkl = _tensor(q), _tensor(k), _tensor(v), _tensor(o_out), _tensor(k_local_out)
+    T, hq, hkv, d = _last(offs), heads.n_q_heads, heads.n_kv_heads, heads.head_dim
+    tq, tk, tv = _tensor(q, "q", hq, d, T), _tensor(k, "k", hkv, d, T), _tensor(v, "v", hkv, d, T)
+    to, tkl = _tensor(o_out, "o_out", hq, d, T), _tensor(k_local_out, "k_local_out", hkv, d, T)
     _check(load().ba_encode_blocks(ctypes.byref(heads.c), _ref(tq), _ref(tk), _ref(tv), _ref(to), _ref(tkl),
                                    len(offs) - 1, _ip(offs), rope_mode, wp, wb, _stream_handle(stream)))
 
@@ -236,13 +284,30 @@ def ba_reencode_positions(heads: Heads, k_src, k_dst, src_tok_off, dst_tok_off, 
     """k_src / k_dst: [layers, tokens, heads, D] (or [tokens, heads, D] for one layer)."""
     if k_src.dim() == 3:
         k_src, k_dst = k_src[None], k_dst[None]
+    if k_src.dim() != 4 or k_dst.dim() != 4 or k_src.shape[0] != k_dst.shape[0]:
+        raise ValueError("k_src / k_dst: expected [layers, tokens, heads, head_dim] with equal layer counts")
     n_layers = k_src.shape[0]
-    ts, td = _tensor(k_src[0]), _tensor(k_dst[0])
     so, do, ln = _ints(src_tok_off), _ints(dst_tok_off), _ints(lens)
     op, npos = _ints(old_pos0), _ints(new_pos0)
+    _same_len(len(ln), src_tok_off=so, dst_tok_off=do, old_pos0=op, new_pos0=npos)
+    hkv, d = heads.n_kv_heads, heads.head_dim
+    if n_layers == 0:
+        return
+    ts = _tensor(k_src[0], "k_src", hkv, d, _reach(so, ln), allow_f32=True)
+    td = _tensor(k_dst[0], "k_dst", hkv, d, _reach(do, ln), allow_f32=True)
     _check(load().ba_reencode_positions(ctypes.byref(heads.c), _ref(ts), _ref(td), n_layers, k_src.stride(0),
                                         k_dst.stride(0), len(ln), _ip(so), _ip(do), _ip(ln), _ip(op), _ip(npos),
                                         mode, _stream_handle(stream)))
+
+
+def _final_tensors(heads: Heads, q_f, k_ctx, v_ctx, k_f, v_f, o_out, k_f_rot_out, cq, cc, qp):
+    if len(cq) != len(cc):
+        raise ValueError("cu_q and cu_ctx: one entry per prompt plus one, each")
+    _same_len(len(cq) - 1, q_pos0=qp)
+    hq, hkv, d, tq_, tc_ = heads.n_q_heads, heads.n_kv_heads, heads.head_dim, _last(cq), _last(cc)
+    return (_tensor(q_f, "q_f", hq, d, tq_), _tensor(k_ctx, "k_ctx", hkv, d, tc_), _tensor(v_ctx, "v_ctx", hkv, d, tc_),
+            _tensor(k_f, "k_f", hkv, d, tq_), _tensor(v_f, "v_f", hkv, d, tq_), _tensor(o_out, "o_out", hq, d, tq_),
+            _tensor(k_f_rot_out, "k_f_rot_out", hkv, d, tq_))
 
 
 def ba_final_block_attention_workspace_bytes(heads: Heads, cu_q, cu_ctx, rope_mode: int = ROPE_APPLY,
@@ -256,8 +321,7 @@ def ba_final_block_attention(heads: Heads, q_f, k_ctx, v_ctx, k_f, v_f, o_out, k
                              q_pos0=None, rope_mode: int = ROPE_APPLY, ws=None, stream=None) -> None:
     cq, cc, qp = _ints(cu_q), _ints(cu_ctx), _ints(q_pos0)
     wp, wb = _ws(ws)
-    tq, tkc, tvc = _tensor(q_f), _tensor(k_ctx), _tensor(v_ctx)
-    tkf, tvf, to, tkr = _tensor(k_f), _tensor(v_f), _tensor(o_out), _tensor(k_f_rot_out)
+    tq, tkc, tvc, tkf, tvf, to, tkr = _final_tensors(heads, q_f, k_ctx, v_ctx, k_f, v_f, o_out, k_f_rot_out, cq, cc, qp)
     _check(load().ba_final_block_attention(ctypes.byref(heads.c), _ref(tq), _ref(tkc), _ref(tvc), _ref(tkf),
                                            _ref(tvf), _ref(to), _ref(tkr), len(cq) - 1, _ip(cq), _ip(cc),
                                            _ip(qp), rope_mode, wp, wb, _stream_handle(stream)))
@@ -270,32 +334,44 @@ def ba_final_block_attention_static(heads: Heads, q_f, k_ctx, v_ctx, k_f, v_f, o
                                     q_pos0=None, rope_mode: int = ROPE_APPLY, stream=None) -> None:
     """ba_final_block_attention with the workspace in the library's static device array (no allocation)."""
     cq, cc, qp = _ints(cu_q), _ints(cu_ctx), _ints(q_pos0)
-    tq, tkc, tvc = _tensor(q_f), _tensor(k_ctx), _tensor(v_ctx)
-    tkf, tvf, to, tkr = _tensor(k_f), _tensor(v_f), _tensor(o_out), _tensor(k_f_rot_out)
+    tq, tkc, tvc, tkf, tvf, to, tkr = _final_tensors(heads, q_f, k_ctx, v_ctx, k_f, v_f, o_out, k_f_rot_out, cq, cc, qp)
     _check(load().ba_final_block_attention_static(ctypes.byref(heads.c), _ref(tq), _ref(tkc), _ref(tvc), _ref(tkf),
                                                   _ref(tvf), _ref(to), _ref(tkr), len(cq) - 1, _ip(cq), _ip(cc),
                                                   _ip(qp), rope_mode, _stream_handle(stream)))
 
 
+GATHER_DEFAULT = -1
+
+
 def ba_final_block_attention_cached_workspace_bytes(heads: Heads, cu_q, cu_blk, blk_len,
-                                                    have_k_f_rot_out: bool = False) -> int:
+                                                    have_k_f_rot_out: bool = False,
+                                                    gather_below: int = GATHER_DEFAULT) -> int:
     cq, cb, bl = _ints(cu_q), _ints(cu_blk), _ints(blk_len)
     return int(load().ba_final_block_attention_cached_workspace_bytes(ctypes.byref(heads.c), len(cq) - 1, _ip(cq),
-                                                                      _ip(cb), _ip(bl), int(have_k_f_rot_out)))
+                                                                      _ip(cb), _ip(bl), int(have_k_f_rot_out),
+                                                                      int(gather_below)))
 
 
 def ba_final_block_attention_cached(heads: Heads, q_f, k_cache, v_cache, k_f, v_f, o_out, k_f_rot_out, cu_q, cu_blk,
                                     blk_tok_off, blk_len, blk_old_pos0=None, blk_new_pos0=None, q_pos0=None,
-                                    ws=None, stream=None) -> None:
+                                    ws=None, stream=None, gather_below: int = GATHER_DEFAULT) -> None:
+    """gather_below: mean cached-block length (tokens) below which the context is gathered first
+    (GATHER_DEFAULT: 256; 0: never); pass the same value to the workspace query."""
     cq, cb = _ints(cu_q), _ints(cu_blk)
     bo, bl, op, npos, qp = _ints(blk_tok_off), _ints(blk_len), _ints(blk_old_pos0), _ints(blk_new_pos0), _ints(q_pos0)
     wp, wb = _ws(ws)
-    tq, tkc, tvc = _tensor(q_f), _tensor(k_cache), _tensor(v_cache)
-    tkf, tvf, to, tkr = _tensor(k_f), _tensor(v_f), _tensor(o_out), _tensor(k_f_rot_out)
+    if len(cq) != len(cb):
+        raise ValueError("cu_q and cu_blk: one entry per prompt plus one, each")
+    _same_len(_last(cb), blk_tok_off=bo, blk_len=bl, blk_old_pos0=op, blk_new_pos0=npos)
+    _same_len(len(cq) - 1, q_pos0=qp)
+    hq, hkv, d, tq_, tc_ = heads.n_q_heads, heads.n_kv_heads, heads.head_dim, _last(cq), _reach(bo, bl)
+    tq, tkc, tvc = _tensor(q_f, "q_f", hq, d, tq_), _tensor(k_cache, "k_cache", hkv, d, tc_), _tensor(v_cache, "v_cache", hkv, d, tc_)
+    tkf, tvf = _tensor(k_f, "k_f", hkv, d, tq_), _tensor(v_f, "v_f", hkv, d, tq_)
+    to, tkr = _tensor(o_out, "o_out", hq, d, tq_), _tensor(k_f_rot_out, "k_f_rot_out", hkv, d, tq_)
     _check(load().ba_final_block_attention_cached(ctypes.byref(heads.c), _ref(tq), _ref(tkc), _ref(tvc), _ref(tkf),
                                                   _ref(tvf), _ref(to), _ref(tkr), len(cq) - 1, _ip(cq), _ip(cb),
-                                                  _ip(bo), _ip(bl), _ip(op), _ip(npos), _ip(qp), wp, wb,
-                                                  _stream_handle(stream)))
+                                                  _ip(bo), _ip(bl), _ip(op), _ip(npos), _ip(qp), int(gather_below),
+                                                  wp, wb, _stream_handle(stream)))
 
 
 def ba_block_attention_prompts_workspace_bytes(heads: Heads, cu_blk, block_offsets, rope_mode: int = ROPE_APPLY,
@@ -310,16 +386,15 @@ def ba_block_attention_prompts(heads: Heads, q, k, v, o_out, k_rot_out, lse_out,
     """lse_out: float32 tensor [T, n_q_heads] (contiguous) or None."""
     cb, offs = _ints(cu_blk), _ints(block_offsets)
     wp, wb = _ws(ws)
-    tq, tk, tv, to, tkr = _tensor(q), _tensor(k), _tensor(v), _tensor(o_out), _tensor(k_rot_out)
-    lse_p = None if lse_out is None else ctypes.c_void_p(lse_out.data_ptr())
+    if _last(cb) != len(offs) - 1:
+        raise ValueError("block_offsets: one entry per block of cu_blk plus one")
+    T, hq, hkv, d = _last(offs), heads.n_q_heads, heads.n_kv_heads, heads.head_dim
+    tq, tk, tv = _tensor(q, "q", hq, d, T), _tensor(k, "k", hkv, d, T), _tensor(v, "v", hkv, d, T)
+    to, tkr = _tensor(o_out, "o_out", hq, d, T), _tensor(k_rot_out, "k_rot_out", hkv, d, T)
+    lse_p = _lse(lse_out, "lse_out", T, hq)
     _check(load().ba_block_attention_prompts(ctypes.byref(heads.c), _ref(tq), _ref(tk), _ref(tv), _ref(to), _ref(tkr),
                                              lse_p, len(cb) - 1, _ip(cb), _ip(offs), rope_mode, wp, wb,
                                              _stream_handle(stream)))
-
-
-def ba_set_gather_below(mean_block_tokens: int) -> int:
-    """Mean cached-block length below which ba_final_block_attention_cached gathers; returns the old value."""
-    return int(load().ba_set_gather_below(int(mean_block_tokens)))
 
 
 def ba_block_attention_prompts_backward_workspace_bytes(heads: Heads, cu_blk, block_offsets) -> int:
@@ -333,8 +408,15 @@ def ba_block_attention_prompts_backward(heads: Heads, q, k, v, o, lse, d_out, dq
     """lse: the forward call's float32 [T, n_q_heads] tensor."""
     cb, offs = _ints(cu_blk), _ints(block_offsets)
     wp, wb = _ws(ws)
-    ts = [_tensor(x) for x in (q, k, v, o, d_out, dq_out, dk_out, dv_out)]
+    if _last(cb) != len(offs) - 1:
+        raise ValueError("block_offsets: one entry per block of cu_blk plus one")
+    T, hq, hkv, d = _last(offs), heads.n_q_heads, heads.n_kv_heads, heads.head_dim
+    if lse is None:
+        raise ValueError("lse: the forward call's log-sum-exps are needed")
+    ts = [_tensor(x, nm, nh, d, T) for x, nm, nh in ((q, "q", hq), (k, "k", hkv), (v, "v", hkv), (o, "o", hq),
+                                                     (d_out, "d_out", hq), (dq_out, "dq_out", hq),
+                                                     (dk_out, "dk_out", hkv), (dv_out, "dv_out", hkv))]
     _check(load().ba_block_attention_prompts_backward(ctypes.byref(heads.c), _ref(ts[0]), _ref(ts[1]), _ref(ts[2]),
-                                                      _ref(ts[3]), ctypes.c_void_p(lse.data_ptr()), _ref(ts[4]),
+                                                      _ref(ts[3]), _lse(lse, "lse", T, hq), _ref(ts[4]),
                                                       _ref(ts[5]), _ref(ts[6]), _ref(ts[7]), len(cb) - 1, _ip(cb),
                                                       _ip(offs), wp, wb, _stream_handle(stream)))

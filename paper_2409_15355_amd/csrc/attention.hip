@@ -30,6 +30,7 @@
 //     exponentials (VALU), the other is in its MFMA block (PV of this tile, QK of the next).
 //   - The KV range can be cut into n_splits pieces; each piece writes its own normalised output
 //     (fp16) with its reference and sum (fp32), and combine_kernel merges them in a fixed order.
+#include <atomic>
 #include <type_traits>
 
 #include "ba_device.h"
@@ -109,23 +110,6 @@ __device__ __forceinline__ Problem locate(const FinalBlocksMetaT<NP, NB> &m, int
   return pr;
 }
 
-#ifdef BA_TRACE
-// Debug build only: per-phase timestamps of one workgroup, read back by ba_debug_read_trace().
-constexpr int kTraceTiles = 80, kTraceMarks = 8;
-__device__ long long g_trace[8][kTraceTiles][kTraceMarks];
-__device__ long long g_wg[1024][4];  // per workgroup: wall clock at start and end, cycles at start and end
-#define BA_MARK_ALWAYS(tile, m)                                                            \
-  do {                                                                                     \
-    if (trace_on && (tile) < kTraceTiles && lane == 0) g_trace[wave][tile][m] = clock64(); \
-  } while (0)
-#define BA_WALL(tile, m)                                                                        \
-  do {                                                                                          \
-    if (trace_on && (tile) < kTraceTiles && lane == 0) g_trace[wave][tile][m] = wall_clock64(); \
-  } while (0)
-#else
-#define BA_MARK_ALWAYS(tile, m) do { } while (0)
-#define BA_WALL(tile, m) do { } while (0)
-#endif
 
 template <int D, typename Meta>
 __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta) {
@@ -159,14 +143,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, lives in an SGPR
   const int col = lane & 31;  // query column inside the 32-wide MFMA group
   const int hf = lane >> 5;   // which half of the wave
-#ifdef BA_TRACE
-  const bool trace_on = blockIdx.x == 17;
-#endif
-  BA_MARK_ALWAYS(79, 0);
-  BA_WALL(78, 0);
-#ifdef BA_TRACE
-  if (threadIdx.x == 0 && blockIdx.x < 1024) { g_wg[blockIdx.x][0] = wall_clock64(); g_wg[blockIdx.x][2] = clock64(); }
-#endif
   const int Gq = p.group;
   const int n_rows = pr.lq * Gq;
   const int row0 = pr.jt * kTileRows;
@@ -543,7 +519,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       }
     }
   }
-  BA_MARK_ALWAYS(79, 1);
 
   // ---- Q fragments (B operand of S^T = K Q^T).  With rotary embedding the rows come from the
   //      RoPE pre-pass, already rotated and multiplied by scale * log2(e); otherwise they are the
@@ -645,9 +620,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     return -1;
   };
   load_q(rot_of(cm.seg));
-  BA_MARK_ALWAYS(79, 2);
   dma_wait<0>();  // unconditional: first tiles and Q fragments are complete from here on
-  BA_MARK_ALWAYS(79, 3);
   f32x16_t sacc[2];
   bf16x8_t pf[4];
   bf16x8_t fr[W];
@@ -740,7 +713,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
 #pragma unroll 1
     for (; i < n_t; ++i) iteration(std::false_type{}, i);
   }
-  BA_MARK_ALWAYS(79, 4);
   static_assert(kNumKBuf == 4 && kNumVBuf == 4, "the copy distances above assume four buffers of each kind");
 
   // ---- epilogue: each wave transposes its O^T through its own slice of LDS, half of the head
@@ -814,11 +786,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     float2 ml = {l_tot > 0.f ? mb : -INFINITY, l_tot};  // reference in log2 units; -inf: nothing visible
     *reinterpret_cast<float2 *>(BA_ARG(part_ml) + ((int64_t)split * BA_ARG(part_rows) + prow) * 2) = ml;
   }
-  BA_MARK_ALWAYS(79, 5);
-  BA_WALL(78, 1);
-#ifdef BA_TRACE
-  if (threadIdx.x == 0 && blockIdx.x < 1024) { g_wg[blockIdx.x][1] = wall_clock64(); g_wg[blockIdx.x][3] = clock64(); }
-#endif
 }
 
 #undef BA_ARG
@@ -909,12 +876,14 @@ hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, hipStream_t stre
   constexpr size_t lds = Geo<D>::LDS;
   static_assert((size_t)kWaves * 32 * D * 2 <= lds, "epilogue staging must fit the tile buffers");
   static_assert(lds <= 160 * 1024, "gfx950 has 160 KB of LDS per workgroup");
-  static bool raised = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
-  if (!raised && lds > 64 * 1024) {
+  // more than 64 KB of dynamic LDS has to be asked for once per kernel (setting it twice, from two
+  // host threads at once, is harmless)
+  static std::atomic<bool> raised{false};
+  if (lds > 64 * 1024 && !raised.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<D, Meta>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    raised = true;
+    raised.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL((attn_kernel<D, Meta>), dim3((unsigned)n_wg), dim3(kThreads), lds, stream, p, meta);
   return hipGetLastError();
@@ -922,14 +891,6 @@ hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, hipStream_t stre
 
 }  // namespace
 
-#ifdef BA_TRACE
-extern "C" int ba_debug_read_trace(long long *host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(g_trace));
-}
-extern "C" int ba_debug_read_wg(long long *host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_wg), sizeof(g_wg));
-}
-#endif
 
 hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream) {
   if (p.head_dim == 128) return launch_attn_t<128, EncodeMeta>(p, meta, stream);

@@ -19,6 +19,7 @@
 // walked side from LDS tiles as A operands (16-byte row reads for the products that contract over
 // head_dim, LDS transpose reads for those that contract over the walked index), and a probability
 // tile in accumulator layout is directly the B operand of the next product.
+#include <atomic>
 #include <type_traits>
 
 #include "ba_device.h"
@@ -677,12 +678,14 @@ hipError_t launch_dkv_t(const AttnParams &p, const BwdKvMeta &meta, const BwdPar
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
   constexpr size_t lds = (size_t)kBBuf * (2 * (kKvRows / 32) * BGeo<D>::TILEB + kBWaves * 1024);
   static_assert(lds <= 160 * 1024, "gfx950 has 160 KB of LDS per workgroup");
-  static bool raised = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
-  if (!raised && lds > 64 * 1024) {
+  // more than 64 KB of dynamic LDS has to be asked for once per kernel (setting it twice, from two
+  // host threads at once, is harmless)
+  static std::atomic<bool> raised{false};
+  if (lds > 64 * 1024 && !raised.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&bwd_dkv_kernel<D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    raised = true;
+    raised.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL((bwd_dkv_kernel<D>), dim3((unsigned)n_wg), dim3(kBThreads), lds, stream, p, meta, bp);
   return hipGetLastError();

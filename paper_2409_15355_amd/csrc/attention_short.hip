@@ -45,21 +45,6 @@ struct SGeo {
   static_assert((size_t)kSWaves * 32 * ROWB <= LDS, "the output staging must fit the tile buffers");
 };
 
-#ifdef BA_TRACE
-// Debug build only: clock marks of wave 0 of every workgroup, read back by ba_debug_read_short().
-__device__ long long g_swg[16384][16];
-#define BA_SMARK(m)                                                                               \
-  do {                                                                                            \
-    if (threadIdx.x == 0 && blockIdx.x < 16384) g_swg[blockIdx.x][m] = (long long)clock64(); \
-  } while (0)
-#define BA_SNOTE(m, val)                                                                          \
-  do {                                                                                            \
-    if (threadIdx.x == 0 && blockIdx.x < 16384) g_swg[blockIdx.x][m] = (long long)(val);          \
-  } while (0)
-#else
-#define BA_SMARK(m) do { } while (0)
-#define BA_SNOTE(m, val) do { } while (0)
-#endif
 
 // Meta = EncodeMeta: a block sees its own tokens only (Section 2.1).  Meta = PromptMeta: a block's keys
 // start wherever the table says -- at the block itself for a passage, at the first token of the
@@ -77,7 +62,6 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   // ---- which work item: consecutive items are the row tiles of one block at one KV head, and
   //      they share its K/V rows.  Workgroup ids are dealt round-robin to the 8 XCDs, so regroup
   //      them such that each XCD (and its L2) gets a contiguous run of items ---------------------
-  BA_SMARK(0);
   uint32_t id = blockIdx.x;
   {
     constexpr uint32_t kXcds = 8;
@@ -128,7 +112,6 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   const int lk = dq + lq;          // keys up to the block's end
   const int jt = rowtile - meta.tile_start[b];
 
-  BA_SMARK(1);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 31;  // query column inside the 32-wide MFMA group
@@ -203,10 +186,6 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
       const uint32_t o = wr_r0 < n_rows - u * QRPI ? off : last_off;
       ld[u] = *reinterpret_cast<const u32x4_t *>(qbase + (o * 2u + (uint32_t)(lane % G::CPR) * 16u));
     });
-#ifdef BA_TRACE
-    __builtin_amdgcn_sched_barrier(0);
-    BA_SMARK(11);
-#endif
     if (p.q_table) {
       // The rows of a wave span at most 8 tokens (the host sends only groups of 4 or more query
       // heads here).  Chunk c of token row t sits at chunk c ^ (t & 7), which keeps the reads of
@@ -223,7 +202,6 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
     }
   }
   __builtin_amdgcn_sched_barrier(0);
-  BA_SMARK(12);
 
   // ---- per-lane LDS read offsets inside a tile buffer (same swizzles as the tile fill below) ----
   uint32_t k_rd[G::KCH];  // K fragment: row `col`, chunk 2 kk + hf
@@ -270,20 +248,12 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
     }
   };
   constexpr int kOpsPerTile = 2 * G::IPW;  // vector-memory operations of one wave per tile
-#ifdef BA_TRACE
-  __builtin_amdgcn_sched_barrier(0);
-  BA_SMARK(13);
-#endif
   issue_copy(0, 0);  // (buffer 2 holds the waves' slices until the first barrier)
   if (1 < n_t) issue_copy(1, 1);
   __builtin_amdgcn_sched_barrier(0);  // the copies go out before anything waits for the Q rows
-  BA_SMARK(2);
-  BA_SNOTE(7, n_t);
 
   // ---- rotate (or just scale) the Q rows into the fragments ---------------------------------------
-  BA_SMARK(3);
   dma_wait<0>();  // the table rows and the first tile (this wave's share) have landed
-  BA_SMARK(4);
   // The table first: entry j of a table row = (cos, sin) of pair j.  Interleaved pairs: fragment kk
   // holds pairs kk * 8 + hf * 4 + (0..3); half-split pairs: fragments kk and kk + KCH/2 hold dims
   // kk * 16 + hf * 8 + (0..7) and their partners, i.e. pairs of those same numbers.
@@ -362,7 +332,6 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
     asm volatile("" : "+v"(raw[kk]));  // the loads are waited for here, not inside the loop
     qf[kk] = __builtin_bit_cast(bf16x8_t, raw[kk]);
   }
-  BA_SMARK(10);
 
   // ---- running state -----------------------------------------------------------------------------
   f32x16_t oacc[G::DT];
@@ -477,9 +446,7 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   //      slice of LDS so that rows leave as contiguous lines.  The slices lie in the tile buffers:
   //      every wave must be done with the last tile first -----------------------------------------
   // (all of this wave's LDS reads were consumed by its MFMAs, so only the barrier is needed)
-  BA_SMARK(5);
   wg_barrier();
-  BA_SMARK(8);
   // (lane-dependent addresses are worked out from here on, not carried through the loop in registers)
   int ln = lane;
   asm volatile("" : "+v"(ln));
@@ -504,7 +471,6 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  BA_SMARK(9);
   {
     // (all the pieces are read back before the first store, so that the stores do not each wait
     // for their own read)
@@ -529,7 +495,6 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
     p.lse[(int64_t)(q_tok0 + tok) * p.n_q_heads + kvh * Gq + (r - tok * Gq)] =
         (mb + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;  // (v_log_f32 is the base-2 logarithm)
   }
-  BA_SMARK(6);
 }
 
 template <int D, typename Meta>
@@ -545,11 +510,6 @@ hipError_t launch_short_t(const AttnParams &p, const Meta &meta, hipStream_t str
 
 }  // namespace
 
-#ifdef BA_TRACE
-extern "C" int ba_debug_read_short(long long *host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_swg), sizeof(g_swg));
-}
-#endif
 
 hipError_t launch_attn_encode_short(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream) {
   if (p.n_splits != 1) return hipErrorInvalidValue;

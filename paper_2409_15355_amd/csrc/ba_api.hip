@@ -44,6 +44,7 @@ struct ProfileScope {
   hipStream_t stream;
   int cls;
   bool active = false;
+  hipEvent_t stop_event = nullptr;  // this scope's own: another thread may open a scope of the class meanwhile
   ProfileScope(int cls_, hipStream_t s) : stream(s), cls(cls_) {
     std::lock_guard<std::mutex> lk(g_prof.mu);
     if (!g_prof.on || (int)g_prof.start[cls].size() >= g_prof.max_records) return;
@@ -56,12 +57,15 @@ struct ProfileScope {
     g_prof.start[cls].push_back(e0);
     g_prof.stop[cls].push_back(e1);
     (void)hipEventRecord(e0, stream);
+    stop_event = e1;
     active = true;
   }
   ~ProfileScope() {
     if (!active) return;
+    // (under the lock: ba_profile_end destroys the events, and must not do so between the
+    // constructor and this record)
     std::lock_guard<std::mutex> lk(g_prof.mu);
-    (void)hipEventRecord(g_prof.stop[cls].back(), stream);
+    if (g_prof.on) (void)hipEventRecord(stop_event, stream);
   }
 };
 
@@ -145,7 +149,19 @@ float scale_log2e(const ba_heads *h) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-constexpr int kNumCU = 256;  // MI355X
+// Compute units of the current device, asked once (256 on MI355X, which is also the fallback
+// when no device can be asked, e.g. a workspace query on a machine without a GPU).
+int num_cus() {
+  static std::once_flag once;
+  static int n = 256;
+  std::call_once(once, [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+  });
+  return n;
+}
 
 // Number of KV splits for the final-block launch.  One workgroup runs per compute unit, so a launch
 // takes ceil(workgroups / CUs) rounds, each as long as one workgroup: a fixed part (prologue, output,
@@ -153,11 +169,12 @@ constexpr int kNumCU = 256;  // MI355X
 // the merge.  Take the cheapest count, never fewer than four key tiles per split.
 int choose_splits(int64_t base_wgs, int max_tiles_per_problem) {
   if (base_wgs <= 0) return 1;
+  const int n_cu = num_cus();
   const int s_max = (int)std::min<int64_t>(32, std::max(1, max_tiles_per_problem / 4));
   int best = 1;
   double best_cost = 0;
   for (int s = 1; s <= s_max; ++s) {
-    const double rounds = (double)((base_wgs * s + kNumCU - 1) / kNumCU);
+    const double rounds = (double)((base_wgs * s + n_cu - 1) / n_cu);
     const double cost = rounds * (4.0 + (max_tiles_per_problem + s - 1) / s) + 0.5 * s;
     if (s == 1 || cost < best_cost) {
       best = s;
@@ -217,6 +234,15 @@ int32_t check_offsets(int32_t n_blocks, const int32_t *offs) {
   for (int b = 0; b < n_blocks; ++b)
     if (offs[b + 1] < offs[b]) return fail(BA_ERR_INVALID_ARG, "block_offsets must not decrease (block %d)", b);
   return BA_OK;
+}
+
+// cu_blk of a whole-prompt call (cu_blk[0] = 0, at least one block per prompt) and the block offsets behind it.
+int32_t check_prompt_blocks(int32_t n_prompts, const int32_t *cu_blk, const int32_t *block_offsets) {
+  if (n_prompts < 0 || !cu_blk) return fail(BA_ERR_INVALID_ARG, "cu_blk: null or negative prompt count");
+  if (cu_blk[0] != 0) return fail(BA_ERR_INVALID_ARG, "cu_blk[0] must be 0");
+  for (int n = 0; n < n_prompts; ++n)
+    if (cu_blk[n + 1] <= cu_blk[n]) return fail(BA_ERR_INVALID_ARG, "prompt %d: at least one block needed", n);
+  return check_offsets(cu_blk[n_prompts], block_offsets);
 }
 
 // Run the rotation kernel over a list of blocks, a launch per table-full of them.
@@ -384,7 +410,7 @@ int32_t ba_profile_end(double *ms_sum, int32_t *launches) {
 size_t ba_encode_blocks_workspace_bytes(const ba_heads *heads, int32_t n_blocks,
                                         const int32_t *block_offsets, int32_t rope_mode,
                                         int32_t have_k_local_out) {
-  if (!heads || !block_offsets || n_blocks < 0) return 0;
+  if (check_heads(heads, true) != BA_OK || check_offsets(n_blocks, block_offsets) != BA_OK) return 0;
   if (rope_mode != BA_ROPE_APPLY) return 0;
   const size_t T = (size_t)block_offsets[n_blocks];
   const size_t k_bytes = have_k_local_out ? 0 : align256(T * heads->n_kv_heads * heads->head_dim * 2);
@@ -531,7 +557,7 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
 size_t ba_block_attention_prompts_workspace_bytes(const ba_heads *heads, int32_t n_prompts, const int32_t *cu_blk,
                                                   const int32_t *block_offsets, int32_t rope_mode,
                                                   int32_t have_k_rot_out) {
-  if (!heads || !cu_blk || !block_offsets || n_prompts < 0) return 0;
+  if (check_heads(heads, true) != BA_OK || check_prompt_blocks(n_prompts, cu_blk, block_offsets) != BA_OK) return 0;
   if (rope_mode != BA_ROPE_APPLY) return 0;
   const size_t T = (size_t)block_offsets[cu_blk[n_prompts]];
   const size_t k_bytes = have_k_rot_out ? 0 : align256(T * heads->n_kv_heads * heads->head_dim * 2);
@@ -545,12 +571,8 @@ int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, co
   hipStream_t stream = (hipStream_t)stream_;
   int32_t rc;
   if ((rc = check_heads(heads, true))) return rc;
-  if (n_prompts < 0 || !cu_blk) return fail(BA_ERR_INVALID_ARG, "cu_blk: null or negative prompt count");
-  if (cu_blk[0] != 0) return fail(BA_ERR_INVALID_ARG, "cu_blk[0] must be 0");
-  for (int n = 0; n < n_prompts; ++n)
-    if (cu_blk[n + 1] <= cu_blk[n]) return fail(BA_ERR_INVALID_ARG, "prompt %d: at least one block needed", n);
+  if ((rc = check_prompt_blocks(n_prompts, cu_blk, block_offsets))) return rc;
   const int n_blocks = cu_blk[n_prompts];
-  if ((rc = check_offsets(n_blocks, block_offsets))) return rc;
   const int D = heads->head_dim;
   if ((rc = check_tensor(q, "q", false, D, heads->n_q_heads))) return rc;
   if ((rc = check_tensor(k, "k", false, D, heads->n_kv_heads))) return rc;
@@ -692,7 +714,7 @@ int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, co
 // ------------------------------------------------------------------------------------------
 size_t ba_block_attention_prompts_backward_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
                                                            const int32_t *cu_blk, const int32_t *block_offsets) {
-  if (!heads || !cu_blk || !block_offsets || n_prompts < 0) return 0;
+  if (check_heads(heads, true) != BA_OK || check_prompt_blocks(n_prompts, cu_blk, block_offsets) != BA_OK) return 0;
   const size_t T = (size_t)block_offsets[cu_blk[n_prompts]];
   const size_t D = heads->head_dim, hq = heads->n_q_heads, hkv = heads->n_kv_heads;
   // rotated scaled q, rotated k, the table of rotation factors, (log-sum-exp, delta) per row (+ padding)
@@ -708,12 +730,8 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   hipStream_t stream = (hipStream_t)stream_;
   int32_t rc;
   if ((rc = check_heads(heads, true))) return rc;
-  if (n_prompts < 0 || !cu_blk) return fail(BA_ERR_INVALID_ARG, "cu_blk: null or negative prompt count");
-  if (cu_blk[0] != 0) return fail(BA_ERR_INVALID_ARG, "cu_blk[0] must be 0");
-  for (int n = 0; n < n_prompts; ++n)
-    if (cu_blk[n + 1] <= cu_blk[n]) return fail(BA_ERR_INVALID_ARG, "prompt %d: at least one block needed", n);
+  if ((rc = check_prompt_blocks(n_prompts, cu_blk, block_offsets))) return rc;
   const int n_blocks = cu_blk[n_prompts];
-  if ((rc = check_offsets(n_blocks, block_offsets))) return rc;
   const int D = heads->head_dim, hq = heads->n_q_heads, hkv = heads->n_kv_heads;
   if ((rc = check_tensor(q, "q", false, D, hq))) return rc;
   if ((rc = check_tensor(k, "k", false, D, hkv))) return rc;
@@ -936,8 +954,9 @@ int32_t ba_reencode_positions(const ba_heads *heads, const ba_tensor *k_src, con
     if (n_layers > 0 && src_hi > 0 && dst_hi > 0 && s0 < d0 + dst_span && d0 < s0 + src_span)
       return fail(BA_ERR_INVALID_ARG, "k_dst overlaps k_src without being exactly in place");
   }
-  if (!same_buf) {
-    // destination blocks must not overlap each other
+  {
+    // destination blocks must not overlap each other (in place as well: a token listed twice would
+    // be rotated twice, or by two workgroups at once)
     std::vector<std::pair<int64_t, int64_t>> spans;
     for (int b = 0; b < n_blocks; ++b)
       if (len[b] > 0) spans.emplace_back(dst_tok_off[b], (int64_t)dst_tok_off[b] + len[b]);
@@ -1203,11 +1222,13 @@ struct BlocksPlan {
   }
 };
 
-// Mean length (tokens) of a call's cached blocks below which ba_final_block_attention_cached gathers.
-std::atomic<int32_t> g_gather_below{256};
-
+// gather_below: mean length (tokens) of a call's cached blocks below which the call gathers
+// (BA_GATHER_DEFAULT: 256; 0: never).
 int32_t plan_final_blocks(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_blk,
-                          const int32_t *blk_len, bool have_rot_out, BlocksPlan *plan) {
+                          const int32_t *blk_len, bool have_rot_out, int32_t gather_below, BlocksPlan *plan) {
+  if (gather_below < 0 && gather_below != BA_GATHER_DEFAULT)
+    return fail(BA_ERR_INVALID_ARG, "gather_below %d: a token count, 0 or BA_GATHER_DEFAULT", gather_below);
+  if (gather_below == BA_GATHER_DEFAULT) gather_below = 256;
   if (n_prompts < 0 || (n_prompts > 0 && (!cu_q || !cu_blk)))
     return fail(BA_ERR_INVALID_ARG, "cu_q / cu_blk: null or negative prompt count");
   BlocksPlan pl;
@@ -1244,7 +1265,7 @@ int32_t plan_final_blocks(const ba_heads *h, int32_t n_prompts, const int32_t *c
     if (ctx_total > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "context too long");
     pl.cu_ctx[n + 1] = (int32_t)ctx_total;
   }
-  if (pl.n_blocks > 0 && ctx_total < (int64_t)g_gather_below.load() * pl.n_blocks) {
+  if (pl.n_blocks > 0 && ctx_total < (int64_t)gather_below * pl.n_blocks) {
     FinalPlan fp;
     int32_t rc = plan_final(h, n_prompts, cu_q, pl.cu_ctx.data(), BA_ROPE_APPLY, have_rot_out, &fp);
     if (rc) return rc;
@@ -1314,7 +1335,6 @@ int32_t run_final_blocks(const BlocksCall &c, ba::AttnParams ap) {
         const int32_t new0 = c.blk_new_pos0 ? c.blk_new_pos0[b] : (int32_t)run;
         run += c.blk_len[b];
         if (c.blk_len[b] == 0) continue;
-        if (c.blk_tok_off[b] < 0) return fail(BA_ERR_INVALID_ARG, "block %d: negative cache offset", b);
         meta.blk_off[nb] = c.blk_tok_off[b];
         meta.blk_len[nb] = c.blk_len[b];
         meta.blk_tile0[nb] = ctx_tiles;
@@ -1356,16 +1376,14 @@ int32_t run_final_blocks(const BlocksCall &c, ba::AttnParams ap) {
 
 extern "C" {
 
-int32_t ba_set_gather_below(int32_t mean_block_tokens) {
-  return g_gather_below.exchange(mean_block_tokens < 0 ? 0 : mean_block_tokens);
-}
-
 size_t ba_final_block_attention_cached_workspace_bytes(const ba_heads *heads, int32_t n_prompts,
                                                        const int32_t *cu_q, const int32_t *cu_blk,
-                                                       const int32_t *blk_len, int32_t have_k_f_rot_out) {
+                                                       const int32_t *blk_len, int32_t have_k_f_rot_out,
+                                                       int32_t gather_below) {
   if (check_heads(heads, true) != BA_OK) return 0;
   BlocksPlan pl;
-  if (plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, have_k_f_rot_out != 0, &pl) != BA_OK) return 0;
+  if (plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, have_k_f_rot_out != 0, gather_below, &pl) != BA_OK)
+    return 0;
   return pl.total();
 }
 
@@ -1374,14 +1392,15 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
                                         const ba_tensor *o_out, const ba_tensor *k_f_rot_out, int32_t n_prompts,
                                         const int32_t *cu_q, const int32_t *cu_blk, const int32_t *blk_tok_off,
                                         const int32_t *blk_len, const int32_t *blk_old_pos0,
-                                        const int32_t *blk_new_pos0, const int32_t *q_pos0, void *ws,
-                                        size_t ws_bytes, void *stream_) {
+                                        const int32_t *blk_new_pos0, const int32_t *q_pos0,
+                                        int32_t gather_below, void *ws, size_t ws_bytes, void *stream_) {
   hipStream_t stream = (hipStream_t)stream_;
   int32_t rc;
   if ((rc = check_heads(heads, true))) return rc;
   const int D = heads->head_dim;
   BlocksPlan pl;
-  if ((rc = plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, k_f_rot_out != nullptr, &pl))) return rc;
+  if ((rc = plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, k_f_rot_out != nullptr, gather_below, &pl)))
+    return rc;
   if (n_prompts == 0) return BA_OK;
   if ((rc = check_tensor(q_f, "q_f", false, D, heads->n_q_heads))) return rc;
   if ((rc = check_tensor(k_f, "k_f", false, D, heads->n_kv_heads))) return rc;
@@ -1389,6 +1408,8 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
   if ((rc = check_tensor(o_out, "o_out", false, D, heads->n_q_heads))) return rc;
   if (pl.n_blocks > 0) {
     if (!blk_tok_off) return fail(BA_ERR_INVALID_ARG, "blk_tok_off is null");
+    for (int b = 0; b < cu_blk[n_prompts]; ++b)
+      if (blk_len[b] > 0 && blk_tok_off[b] < 0) return fail(BA_ERR_INVALID_ARG, "block %d: negative cache offset", b);
     if ((rc = check_tensor(k_cache, "k_cache", false, D, heads->n_kv_heads))) return rc;
     if ((rc = check_tensor(v_cache, "v_cache", false, D, heads->n_kv_heads))) return rc;
   }

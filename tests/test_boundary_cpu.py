@@ -131,11 +131,12 @@ def test_final_cached_rejects_bad_arguments_and_sizes_workspace(lib):
     i32 = lambda x: np.asarray(x, dtype=np.int32)
     p = lambda x: x.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
 
-    def call(cu_q, cu_blk, off, ln, ws=None, wsb=0):
+    def call(cu_q, cu_blk, off, ln, ws=None, wsb=0, gather_below=-1):
         cq, cb, bo, bl = i32(cu_q), i32(cu_blk), i32(off), i32(ln)
         return lib.ba_final_block_attention_cached(ctypes.byref(h.c), ctypes.byref(t), ctypes.byref(t), ctypes.byref(t),
                                                    ctypes.byref(t), ctypes.byref(t), ctypes.byref(t), None, len(cq) - 1,
-                                                   p(cq), p(cb), p(bo), p(bl), None, None, None, ws, wsb, None)
+                                                   p(cq), p(cb), p(bo), p(bl), None, None, None, gather_below, ws, wsb,
+                                                   None)
 
     assert call([0, 0], [0, 1], [0], [10]) == -1          # empty final block
     assert call([0, 5], [1, 2], [0, 0], [10, 10]) == -1   # cu_blk[0] != 0
@@ -146,9 +147,13 @@ def test_final_cached_rejects_bad_arguments_and_sizes_workspace(lib):
     small = ba.ba_final_block_attention_cached_workspace_bytes(h, [0, 5], [0, 1100], [1] * 1100)
     assert small == 2 * ((1100 * 8 * 128 * 2 + 255) // 256 * 256) + \
         ba.ba_final_block_attention_workspace_bytes(h, [0, 5], [0, 1100], ba.ROPE_APPLY)
-    old = ba.ba_set_gather_below(0)                                   # never gather: the table limit is back
-    assert old == 256 and call([0, 5], [0, 1100], [0] * 1100, [1] * 1100) == -2
-    assert ba.ba_set_gather_below(old) == 0
+    # never gather: the table limit is back; the threshold is the call's own argument, nothing is kept
+    assert call([0, 5], [0, 1100], [0] * 1100, [1] * 1100, gather_below=0) == -2
+    assert call([0, 5], [0, 1100], [0] * 1100, [1] * 1100) == -4
+    assert call([0, 5], [0, 1100], [0] * 1100, [1] * 1100, gather_below=-7) == -1  # neither a count nor the default
+    # 300-token blocks are gathered when the caller's threshold says so, and sized accordingly
+    assert ba.ba_final_block_attention_cached_workspace_bytes(h, [0, 5], [0, 3], [300] * 3, gather_below=301) == \
+        2 * (900 * 8 * 128 * 2) + ba.ba_final_block_attention_workspace_bytes(h, [0, 5], [0, 900], ba.ROPE_APPLY)
     assert call([0, 256], [0, 31], [1024 * b for b in range(31)], [1024] * 31) == -4  # workspace missing
     need = ba.ba_final_block_attention_cached_workspace_bytes(h, [0, 256], [0, 31], [1024] * 31)
     # config 5 as 31 cached blocks: split partials + rotated final-block keys and queries + 31 rows of rotations
@@ -156,7 +161,7 @@ def test_final_cached_rejects_bad_arguments_and_sizes_workspace(lib):
     # zero prompts: legal no-op
     z = i32([0])
     assert lib.ba_final_block_attention_cached(ctypes.byref(h.c), None, None, None, None, None, None, None, 0, p(z),
-                                               p(z), None, None, None, None, None, None, 0, None) == 0
+                                               p(z), None, None, None, None, None, -1, None, 0, None) == 0
 
 
 def test_whole_prompts_rejects_bad_arguments_and_sizes_workspace(lib):
@@ -241,3 +246,132 @@ def test_header_is_plain_c(tmp_path):
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
     assert [int(x) for x in out] == [ctypes.sizeof(ba.BaTensor), ctypes.sizeof(ba.BaHeads),
                                      ba.BaHeads.rope_base.offset, ba.BaHeads.rope_layout.offset]
+
+
+def test_reencode_rejects_overlapping_blocks_in_place(lib):
+    """A token listed in two blocks of an in-place call would be rotated twice (or by two workgroups
+    at once): rejected like overlapping destinations of a gathered call."""
+    h = ba.Heads(8, 8, 128)
+    src = fake(0x100000)
+    assert call_reenc(lib, h, src, src, 1, 0, 0, [0, 2], [0, 2], [4, 4]) == -1
+    assert b"overlap" in lib.ba_last_error()
+
+
+def test_final_cached_rejects_negative_cache_offsets_on_both_routes(lib):
+    h = ba.Heads(32, 8, 128, 500000.0)
+    t = fake()
+    i32 = lambda x: np.asarray(x, dtype=np.int32)
+    p = lambda x: x.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    cq, cb, bo, bl = i32([0, 5]), i32([0, 2]), i32([0, -8]), i32([300, 300])
+    for gather_below in (0, 1 << 30):  # the kernel that reads the table; the gathered copy
+        need = ba.ba_final_block_attention_cached_workspace_bytes(h, cq, cb, bl, gather_below=gather_below)
+        rc = lib.ba_final_block_attention_cached(ctypes.byref(h.c), ctypes.byref(t), ctypes.byref(t), ctypes.byref(t),
+                                                 ctypes.byref(t), ctypes.byref(t), ctypes.byref(t), None, 1, p(cq), p(cb),
+                                                 p(bo), p(bl), None, None, None, gather_below, ctypes.c_void_p(0x10000),
+                                                 need, None)
+        assert rc == -1 and b"negative cache offset" in lib.ba_last_error()
+
+
+def test_workspace_queries_reject_what_the_calls_reject(lib):
+    """The size queries read their host arrays with the checks of the calls: a bad array gives 0,
+    never an index out of range or a size wrapped from a negative number."""
+    h = ba.Heads(32, 8, 128)
+    assert ba.ba_encode_blocks_workspace_bytes(h, [0, 200, 100]) == 0          # offsets decrease
+    assert ba.ba_encode_blocks_workspace_bytes(h, [5, 200]) == 0               # offsets do not start at 0
+    assert ba.ba_encode_blocks_workspace_bytes(ba.Heads(32, 8, 96), [0, 200]) == 0
+    assert ba.ba_block_attention_prompts_workspace_bytes(h, [0, -1], [0, 10]) == 0    # a prompt without blocks
+    assert ba.ba_block_attention_prompts_workspace_bytes(h, [1, 2], [0, 10, 20]) == 0
+    assert ba.ba_block_attention_prompts_workspace_bytes(h, [0, 2], [0, 10, 5]) == 0
+    assert ba.ba_block_attention_prompts_backward_workspace_bytes(h, [0, -1], [0, 10]) == 0
+    assert ba.ba_block_attention_prompts_backward_workspace_bytes(h, [0, 2], [0, 10, 5]) == 0
+
+
+class FakeGpuTensor:
+    """What the Python face reads of a torch tensor; claims to live on the GPU so that the checks
+    behind the device check can be reached without one.  Every call below is rejected before
+    anything is launched."""
+
+    def __init__(self, shape, dtype=None, strides=None, is_cuda=True):
+        import torch
+        self.shape = tuple(shape)
+        self.dtype = dtype or torch.bfloat16
+        if strides is None:
+            strides, acc = [], 1
+            for n in reversed(self.shape):
+                strides.insert(0, acc)
+                acc *= n
+        self._strides = tuple(strides)
+        self.is_cuda = is_cuda
+        self.device = "cuda:0" if is_cuda else "cpu"
+
+    def stride(self, i=None):
+        return self._strides if i is None else self._strides[i]
+
+    def dim(self):
+        return len(self.shape)
+
+    def data_ptr(self):
+        return 0x10000
+
+    def is_contiguous(self):
+        return True
+
+    def numel(self):
+        return int(np.prod(self.shape))
+
+    def element_size(self):
+        return 2
+
+    def __getitem__(self, i):
+        assert i == 0 or i is None
+        if i is None:
+            return FakeGpuTensor((1,) + self.shape, self.dtype, (0,) + self._strides, self.is_cuda)
+        return FakeGpuTensor(self.shape[1:], self.dtype, self._strides[1:], self.is_cuda)
+
+
+def test_python_face_rejects_tensors_the_boundary_cannot_check(lib):
+    import torch
+    h = ba.Heads(32, 8, 128, 500000.0)
+    F = FakeGpuTensor
+    q, kv = F((64, 32, 128)), F((64, 8, 128))
+    ctx = F((1000, 8, 128))
+    cu_q, cu_ctx = [0, 64], [0, 1000]
+    ok = dict(heads=h, q_f=q, k_ctx=ctx, v_ctx=ctx, k_f=kv, v_f=kv, o_out=q, k_f_rot_out=None, cu_q=cu_q, cu_ctx=cu_ctx)
+
+    def rejected(match, **over):
+        with pytest.raises(ValueError, match=match):
+            ba.ba_final_block_attention(**{**ok, **over})
+
+    rejected("GPU memory", q_f=torch.zeros(64, 32, 128, dtype=torch.bfloat16))           # a CPU tensor
+    rejected("GPU memory", k_ctx=torch.zeros(1000, 8, 128, dtype=torch.bfloat16))
+    rejected("head_dim 64", q_f=F((64, 32, 64)))                                          # D = 64 tensor, Heads(..., 128)
+    rejected("32 heads", k_f=F((64, 32, 128)))                                            # query-shaped keys
+    rejected("tokens", k_ctx=F((999, 8, 128)))                                            # context shorter than cu_ctx[-1]
+    rejected("tokens", o_out=F((63, 32, 128)))                                            # output shorter than cu_q[-1]
+    rejected("dtype", v_ctx=F((1000, 8, 128), dtype=torch.float16))
+    rejected("dtype", q_f=F((64, 32, 128), dtype=torch.float32))                          # fp32 attention is not built
+    rejected("contiguous head_dim", q_f=F((64, 32, 128), strides=(32 * 256, 256, 2)))
+    rejected("workspace", ws=torch.zeros(16, dtype=torch.uint8))                          # a CPU workspace
+    rejected("q_pos0", q_pos0=[0, 1])
+    # the other entry points go through the same checks
+    with pytest.raises(ValueError, match="tokens"):
+        ba.ba_encode_blocks(h, F((399, 32, 128)), F((400, 8, 128)), F((400, 8, 128)), F((400, 32, 128)), None, [0, 200, 400])
+    with pytest.raises(ValueError, match="tokens"):   # the last block's last row lies outside the destination
+        ba.ba_reencode_positions(ba.Heads(8, 8, 128), F((2, 500, 8, 128)), F((2, 450, 8, 128)), [0, 200], [0, 300],
+                                 [200, 200])
+    with pytest.raises(ValueError, match="entries"):
+        ba.ba_reencode_positions(ba.Heads(8, 8, 128), F((2, 500, 8, 128)), F((2, 500, 8, 128)), [0, 200], [0], [200, 200])
+    with pytest.raises(ValueError, match="tokens"):   # a cached block reaches beyond the cache
+        ba.ba_final_block_attention_cached(h, q, F((1000, 8, 128)), F((1000, 8, 128)), kv, kv, q, None, cu_q, [0, 2],
+                                           [0, 900], [300, 101])
+    with pytest.raises(ValueError, match="entries"):
+        ba.ba_final_block_attention_cached(h, q, ctx, ctx, kv, kv, q, None, cu_q, [0, 2], [0], [300, 100])
+    lse_bad = F((164, 32), dtype=torch.float16)
+    t164q, t164k = F((164, 32, 128)), F((164, 8, 128))
+    with pytest.raises(ValueError, match="lse_out"):
+        ba.ba_block_attention_prompts(h, t164q, t164k, t164k, t164q, None, lse_bad, [0, 2], [0, 100, 164])
+    with pytest.raises(ValueError, match="lse"):
+        ba.ba_block_attention_prompts_backward(h, t164q, t164k, t164k, t164q, F((100, 32), dtype=torch.float32), t164q,
+                                               t164q, t164k, t164k, [0, 2], [0, 100, 164])
+    with pytest.raises(ValueError, match="block_offsets"):
+        ba.ba_block_attention_prompts(h, t164q, t164k, t164k, t164q, None, None, [0, 3], [0, 100, 164])

@@ -380,16 +380,13 @@ def test_final_block_context_rows_beyond_four_gigabytes(ba, route):
         ref = oracle.final_block(f(qb), k_ctx, f(vcb), f(kfb), f(vfb), cu_q, cu_ctx, th)
         k_view, v_view = spread(k_cache), spread(v_cache)
         cu_blk, bl = np.array([0, 2], dtype=np.int32), np.array(lens, dtype=np.int32)
-        old = ba.ba_set_gather_below(0)
-        try:
-            o = torch.full((lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
-            ws = torch.empty(max(256, ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, bl)),
-                             dtype=torch.uint8, device="cuda")
-            ba.ba_final_block_attention_cached(heads, dev_bf16(qb), k_view, v_view, dev_bf16(kfb), dev_bf16(vfb), o, None,
-                                               cu_q, cu_blk, cache_off, bl, None, None, None, ws)
-            torch.cuda.synchronize()
-        finally:
-            ba.ba_set_gather_below(old)
+        o = torch.full((lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty(max(256, ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, bl,
+                                                                                     gather_below=0)),
+                         dtype=torch.uint8, device="cuda")
+        ba.ba_final_block_attention_cached(heads, dev_bf16(qb), k_view, v_view, dev_bf16(kfb), dev_bf16(vfb), o, None,
+                                           cu_q, cu_blk, cache_off, bl, None, None, None, ws, gather_below=0)
+        torch.cuda.synchronize()
     assert_attention_close(host_f64(o), ref, "context rows 16 MB apart, " + route)
     del k_view, v_view
     torch.cuda.empty_cache()
@@ -721,12 +718,10 @@ def _cached_case(name):
 
 
 @pytest.fixture(params=["table", "gathered"])
-def cached_route(ba, request):
+def cached_route(request):
     """Both routes of ba_final_block_attention_cached: the kernel that reads the block table, and
-    the gathered copy it takes for short blocks (forced either way through the tuning call)."""
-    old = ba.ba_set_gather_below(0 if request.param == "table" else 1 << 30)
-    yield request.param
-    ba.ba_set_gather_below(old)
+    the gathered copy it takes for short blocks (forced either way through the call's gather_below)."""
+    return 0 if request.param == "table" else 1 << 30
 
 
 @pytest.mark.parametrize("name", ["rag-shared-blocks", "deep-split-d64", "moved-cache-positions",
@@ -765,12 +760,13 @@ def test_final_block_from_block_cache_matches_oracle(ba, name, layout, cached_ro
     heads = ba.Heads(hq, hkv, d, base, rope_layout=layout)
     o = torch.full((lq_total, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
     kf_rot = torch.full((lq_total, hkv, d), float("nan"), dtype=torch.bfloat16, device="cuda")
-    nbytes = ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, b_len, True)
+    nbytes = ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, b_len, True, gather_below=cached_route)
     ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
     ba.ba_final_block_attention_cached(heads, dev_bf16(qb), dev_bf16(kcache_b), dev_bf16(vcache_b), dev_bf16(kfb),
                                        dev_bf16(vfb), o, kf_rot, cu_q, cu_blk, b_off, b_len,
                                        b_old if any(b_old) else None, b_new if explicit_new else None,
-                                       q_pos0 if any(p[3] is not None for p in prompts) else None, ws)
+                                       q_pos0 if any(p[3] is not None for p in prompts) else None, ws,
+                                       gather_below=cached_route)
     torch.cuda.synchronize()
     assert_attention_close(host_f64(o), ref, "block cache, " + name)
     # the rotated final-block keys come out as in the plain entry point
@@ -797,10 +793,11 @@ def test_final_block_from_block_cache_agrees_with_two_step_path(ba, cached_route
     o2 = gpu_final(ba, heads, dev_bf16(qb), k_ctx, vc, dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
     o1 = torch.full_like(o2, float("nan"))
     cu_blk = np.array([0, len(lens)], dtype=np.int32)
-    ws = torch.empty(max(ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, lens), 256),
+    ws = torch.empty(max(ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, lens,
+                                                                            gather_below=cached_route), 256),
                      dtype=torch.uint8, device="cuda")
     ba.ba_final_block_attention_cached(heads, dev_bf16(qb), kc, vc, dev_bf16(kfb), dev_bf16(vfb), o1, None, cu_q,
-                                       cu_blk, offs[:-1], lens, None, None, None, ws)
+                                       cu_blk, offs[:-1], lens, None, None, None, ws, gather_below=cached_route)
     torch.cuda.synchronize()
     assert_attention_close(host_f64(o1), host_f64(o2), "block cache vs two-step")
 
@@ -844,11 +841,12 @@ def test_many_small_blocks_incremental_frame_update(ba, cached_route):
 
     def frame(order):
         b_off, b_len = offs[order], lens[order]
-        ws = torch.empty(ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, b_len), dtype=torch.uint8,
-                         device="cuda")
+        ws = torch.empty(ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, b_len,
+                                                                            gather_below=cached_route),
+                         dtype=torch.uint8, device="cuda")
         o = torch.full((lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
         ba.ba_final_block_attention_cached(heads, dev_bf16(qf), kcache, vcache, dev_bf16(kff), dev_bf16(vff), o, None,
-                                           cu_q, cu_blk, b_off, b_len, None, None, None, ws)
+                                           cu_q, cu_blk, b_off, b_len, None, None, None, ws, gather_below=cached_route)
         torch.cuda.synchronize()
         # oracle: its own cache (its fp64 rotation of the seeded keys, rounded to bf16 as a cache stores it),
         # re-encoded in fp64, then the final block
@@ -1412,16 +1410,15 @@ def test_drawn_shapes_match_the_oracle(ba, seed):
                 pos += L
             ref = oracle.final_block(f(qb), k_ctx, f(vb), f(kfb), f(vfb), [0, lq], [0, Tc], th, layout=layout)
             cu_q, cu_blk, bl = np.array([0, lq], dtype=np.int32), np.array([0, nb], dtype=np.int32), np.array(lens, dtype=np.int32)
-            old = ba.ba_set_gather_below(10 ** 6 if gathered else 0)
-            try:
-                o = torch.full((lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
-                ws = torch.empty(max(256, ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, bl)),
-                                 dtype=torch.uint8, device="cuda")
-                ba.ba_final_block_attention_cached(heads, dev_bf16(qb), dev_bf16(k_cache), dev_bf16(v_cache), dev_bf16(kfb),
-                                                   dev_bf16(vfb), o, None, cu_q, cu_blk, cache_off, bl, None, None, None, ws)
-                torch.cuda.synchronize()
-            finally:
-                ba.ba_set_gather_below(old)
+            gb = 10 ** 6 if gathered else 0
+            o = torch.full((lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+            ws = torch.empty(max(256, ba.ba_final_block_attention_cached_workspace_bytes(heads, cu_q, cu_blk, bl,
+                                                                                         gather_below=gb)),
+                             dtype=torch.uint8, device="cuda")
+            ba.ba_final_block_attention_cached(heads, dev_bf16(qb), dev_bf16(k_cache), dev_bf16(v_cache), dev_bf16(kfb),
+                                               dev_bf16(vfb), o, None, cu_q, cu_blk, cache_off, bl, None, None, None, ws,
+                                               gather_below=gb)
+            torch.cuda.synchronize()
             assert_attention_close(host_f64(o), ref, f"{tag}, cached {lens} x {lq}, {'gathered' if gathered else 'table'}")
 
 
