@@ -297,6 +297,45 @@ size_t ba_block_attention_prompts_backward_workspace_bytes(const ba_heads *heads
                                                            const int32_t *cu_blk,
                                                            const int32_t *block_offsets);
 
+/*
+ * The schedule of a call, for inspection and tests: the work items the host planner hands to the
+ * kernels, computed by the code the calls themselves use.  Host only: no device is touched, so
+ * these run on a machine without a GPU.
+ *
+ * A work item is one workgroup's job at one KV head (every item runs once per KV head): packed query
+ * rows [row_begin, row_end) of a "problem" (row = token_in_problem * group + head_in_group, group =
+ * n_q_heads / n_kv_heads) against two key ranges -- context keys [ctx_begin, ctx_end), counted from
+ * the problem's first visible context key and all visible to every row, and the problem's own
+ * tokens [self_begin, self_end) as keys, of which token i sees those <= i (Section 2.1's causal
+ * block; Section 2.5's final block; Section 2.4's mask for whole prompts).  Key ranges are whole
+ * key tiles of tile_keys keys, cut at the end of the segment.  Items of one (problem, row range)
+ * that differ in `split` are merged by the split merge.
+ * Each query returns the number of items (also when `items` is null or max_items is smaller: then
+ * only the first max_items are written), or a negative BA_ERR_* status.
+ */
+typedef struct ba_work_item {
+  int32_t launch;      /* which kernel launch of the call                                       */
+  int32_t problem;     /* prompt (final block, whole prompts) or block (per-block encoding)     */
+  int32_t first_token; /* row of q / o that is the problem's token 0                            */
+  int32_t tile_rows, tile_keys;
+  int32_t row_begin, row_end;
+  int32_t split, n_splits;
+  int32_t ctx_begin, ctx_end;
+  int32_t self_begin, self_end;
+} ba_work_item;
+/* ba_final_block_attention on a device of n_compute_units compute units (256 on MI355X). */
+int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const int32_t *cu_q,
+                                const int32_t *cu_ctx, int32_t n_compute_units,
+                                ba_work_item *items, int64_t max_items);
+/* ba_encode_blocks with packed tensors ([tokens][heads][head_dim]). */
+int64_t ba_schedule_encode_blocks(const ba_heads *heads, int32_t n_blocks,
+                                  const int32_t *block_offsets, ba_work_item *items,
+                                  int64_t max_items);
+/* ba_block_attention_prompts: `problem` is the prompt, first_token the block's first token; the
+ * context range counts from the first token of the prompt (a passage block has none). */
+int64_t ba_schedule_prompts(const ba_heads *heads, int32_t n_prompts, const int32_t *cu_blk,
+                            const int32_t *block_offsets, ba_work_item *items, int64_t max_items);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,8 @@ EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin"
            "ba_final_block_attention_static",
            "ba_final_block_attention_cached", "ba_final_block_attention_cached_workspace_bytes",
            "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes",
-           "ba_block_attention_prompts_backward", "ba_block_attention_prompts_backward_workspace_bytes"]
+           "ba_block_attention_prompts_backward", "ba_block_attention_prompts_backward_workspace_bytes",
+           "ba_schedule_final_block", "ba_schedule_encode_blocks", "ba_schedule_prompts"]
 
 
 class BaTensor(ctypes.Structure):
@@ -42,6 +43,12 @@ class BaHeads(ctypes.Structure):
                 ("head_dim", ctypes.c_int32), ("q_to_kv", ctypes.POINTER(ctypes.c_int32)),
                 ("softmax_scale", ctypes.c_float), ("rope_base", ctypes.c_double),
                 ("inv_freq", ctypes.POINTER(ctypes.c_double)), ("rope_layout", ctypes.c_int32)]
+
+
+class BaWorkItem(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("launch", "problem", "first_token", "tile_rows", "tile_keys", "row_begin",
+                                               "row_end", "split", "n_splits", "ctx_begin", "ctx_end", "self_begin",
+                                               "self_end")]
 
 
 class BaError(RuntimeError):
@@ -114,6 +121,13 @@ def load():
     lib.ba_block_attention_prompts_workspace_bytes.restype = ctypes.c_size_t
     lib.ba_block_attention_prompts_workspace_bytes.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, ctypes.c_int32,
                                                                ctypes.c_int32]
+    _WP = ctypes.POINTER(BaWorkItem)
+    lib.ba_schedule_final_block.restype = ctypes.c_int64
+    lib.ba_schedule_final_block.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, ctypes.c_int32, _WP, ctypes.c_int64]
+    lib.ba_schedule_encode_blocks.restype = ctypes.c_int64
+    lib.ba_schedule_encode_blocks.argtypes = [_HP, ctypes.c_int32, _I32P, _WP, ctypes.c_int64]
+    lib.ba_schedule_prompts.restype = ctypes.c_int64
+    lib.ba_schedule_prompts.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, _WP, ctypes.c_int64]
     _lib = lib
     return lib
 
@@ -420,3 +434,32 @@ def ba_block_attention_prompts_backward(heads: Heads, q, k, v, o, lse, d_out, dq
                                                       _ref(ts[3]), _lse(lse, "lse", T, hq), _ref(ts[4]),
                                                       _ref(ts[5]), _ref(ts[6]), _ref(ts[7]), len(cb) - 1, _ip(cb),
                                                       _ip(offs), wp, wb, _stream_handle(stream)))
+
+
+def _schedule(fn, *args):
+    """Two calls: count the work items, then fetch them.  Returns a list of BaWorkItem."""
+    n = int(fn(*args, None, 0))
+    if n < 0:
+        _check(n)
+    items = (BaWorkItem * max(n, 1))()
+    got = int(fn(*args, items, n))
+    if got < 0:
+        _check(got)
+    return list(items[:got])
+
+
+def ba_schedule_final_block(heads: Heads, cu_q, cu_ctx, n_compute_units: int = 256):
+    """Work items of ba_final_block_attention (host only; see include/ba.h)."""
+    cq, cc = _ints(cu_q), _ints(cu_ctx)
+    return _schedule(load().ba_schedule_final_block, ctypes.byref(heads.c), len(cq) - 1, _ip(cq), _ip(cc),
+                     int(n_compute_units))
+
+
+def ba_schedule_encode_blocks(heads: Heads, block_offsets):
+    offs = _ints(block_offsets)
+    return _schedule(load().ba_schedule_encode_blocks, ctypes.byref(heads.c), len(offs) - 1, _ip(offs))
+
+
+def ba_schedule_prompts(heads: Heads, cu_blk, block_offsets):
+    cb, offs = _ints(cu_blk), _ints(block_offsets)
+    return _schedule(load().ba_schedule_prompts, ctypes.byref(heads.c), len(cb) - 1, _ip(cb), _ip(offs))

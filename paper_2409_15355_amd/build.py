@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libba_hip.so")
-SOURCES = ["ba_api.hip", "reencode.hip", "rope_prepass.hip", "attention.hip", "attention_short.hip", "attention_bwd.hip"]
+SOURCES = ["ba_api.hip", "ba_plan.cpp", "reencode.hip", "rope_prepass.hip", "attention.hip", "attention_short.hip", "attention_bwd.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # MFMA results the softmax reads go to ordinary VGPRs; the allocator moves the
@@ -36,8 +36,13 @@ def build(verbose: bool = False) -> str:
     objs = []
 
     def compile_one(src: str) -> str:
-        obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
-        cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(HERE, "_build", os.path.splitext(src)[0] + ".o")
+        if src.endswith(".cpp"):
+            # the host-side planner holds no device code: the host compiler takes it as it is
+            cmd = [os.environ.get("CXX", "g++"), "-std=c++17", "-O2", "-fPIC", "-Wall", "-Wextra", "-Werror",
+                   "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-c", os.path.join(CSRC, src), "-o", obj]
+        else:
+            cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{_filter(r.stderr)}")

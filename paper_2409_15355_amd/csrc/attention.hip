@@ -35,6 +35,7 @@
 
 #include "ba_device.h"
 #include "ba_lds.h"
+#include "ba_schedule.h"
 
 namespace ba {
 namespace {
@@ -155,16 +156,10 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const int n_ctx_segs = kBlocks ? pr.blk1 - pr.blk0 : (n_ctx_tiles > 0 ? 1 : 0);
   const int last_row = min(n_rows, row0 + kTileRows) - 1;
   const int last_tok = (int)fast_div((uint32_t)last_row, p.group_div);
-  const int n_causal_tiles = last_tok / kTileKeys + 1;
-  const int nt = n_ctx_tiles + n_causal_tiles;
-  // Tiles of the causal segment cost more than context tiles (masks on the diagonal, the change of
-  // segment, the general path of the loop): the split that ends with them gets fewer tiles, as if
-  // `pad` more tiles followed, so that all splits of a launch end together.
-  // (nt < 2^26 and at most 32 splits: the products fit 32 bits)
-  const int pad = p.n_splits > 1 ? min((3 + n_causal_tiles) / 2, nt / (2 * p.n_splits)) : 0;
-  const uint32_t nt_v = (uint32_t)(nt + pad);
-  const int t_begin = (int)(nt_v * (uint32_t)split / (uint32_t)p.n_splits);
-  const int t_end = min(nt, (int)(nt_v * (uint32_t)(split + 1) / (uint32_t)p.n_splits));
+  const int n_causal_tiles = causal_key_tiles(last_tok, kTileKeys);
+  // this split's share of the walk (the arithmetic is the host planner's: one definition)
+  const TileRange tr = split_tile_range(n_ctx_tiles, n_causal_tiles, p.n_splits, split);
+  const int t_begin = tr.begin, t_end = tr.end;
   const int n_t = t_end - t_begin;
 
   const int my_row = row0 + wave * 32 + col;

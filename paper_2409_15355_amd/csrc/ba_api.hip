@@ -1,6 +1,6 @@
-// C boundary of the Block-attention library: argument validation, host-side
-// scheduling (row tiles, KV splits, launch chunking) and kernel launches.  Nothing in
-// this file touches device memory itself or synchronises.
+// C boundary of the Block-attention library: validation of the device tensors, workspace layout
+// and kernel launches.  The planning (host arrays, KV splits, tables of row tiles) is ba_plan.cpp's.
+// Nothing in this file touches device memory itself or synchronises.
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
@@ -14,18 +14,17 @@
 
 #include "../../include/ba.h"
 #include "ba_internal.h"
+#include "ba_plan.h"
 
 namespace {
 
-thread_local char g_err[512] = "";
-
-int32_t fail(int32_t status, const char *fmt, ...) {
-  va_list ap;
-  va_start(ap, fmt);
-  vsnprintf(g_err, sizeof(g_err), fmt, ap);
-  va_end(ap);
-  return status;
-}
+using ba::align256;
+using ba::check_heads;
+using ba::check_offsets;
+using ba::check_prompt_blocks;
+using ba::fail;
+using ba::FinalPlan;
+using ba::BlocksPlan;
 
 int32_t device_fail(hipError_t e, const char *what) {
   return fail(BA_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
@@ -86,26 +85,6 @@ int32_t check_tensor(const ba_tensor *t, const char *name, bool allow_f32, int32
   return BA_OK;
 }
 
-int32_t check_heads(const ba_heads *h, bool attention) {
-  if (!h) return fail(BA_ERR_INVALID_ARG, "heads: null");
-  if (h->head_dim != 64 && h->head_dim != 128)
-    return fail(BA_ERR_UNSUPPORTED, "head_dim %d: only 64 and 128 are built", h->head_dim);
-  if (h->n_kv_heads <= 0) return fail(BA_ERR_INVALID_ARG, "n_kv_heads must be positive");
-  if (h->rope_layout != BA_ROPE_INTERLEAVED && h->rope_layout != BA_ROPE_HALF)
-    return fail(BA_ERR_INVALID_ARG, "rope_layout %d unknown", h->rope_layout);
-  if (!h->inv_freq && !(h->rope_base > 0.0)) return fail(BA_ERR_INVALID_ARG, "rope_base must be positive");
-  if (attention) {
-    if (h->n_q_heads <= 0 || h->n_q_heads % h->n_kv_heads)
-      return fail(BA_ERR_INVALID_ARG, "n_q_heads must be a positive multiple of n_kv_heads");
-    const int g = h->n_q_heads / h->n_kv_heads;
-    if (h->q_to_kv)
-      for (int i = 0; i < h->n_q_heads; ++i)
-        if (h->q_to_kv[i] != i / g)
-          return fail(BA_ERR_UNSUPPORTED, "q_to_kv: only the map h -> h / group is built");
-  }
-  return BA_OK;
-}
-
 // theta_j / (2 pi) as a Q0.64 fraction, from extended-precision host arithmetic.
 void build_rope_table(const ba_heads *h, ba::RopeTable *rt) {
   // (64 extended-precision powers cost tens of microseconds, more than the launch of a small call:
@@ -147,8 +126,6 @@ float scale_log2e(const ba_heads *h) {
   return (float)(s * 1.4426950408889634074);
 }
 
-size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-
 // Compute units of the current device, asked once (256 on MI355X, which is also the fallback
 // when no device can be asked, e.g. a workspace query on a machine without a GPU).
 int num_cus() {
@@ -161,88 +138,6 @@ int num_cus() {
       n = v;
   });
   return n;
-}
-
-// Number of KV splits for the final-block launch.  One workgroup runs per compute unit, so a launch
-// takes ceil(workgroups / CUs) rounds, each as long as one workgroup: a fixed part (prologue, output,
-// worth about four key tiles) plus its share of the key tiles; every split also adds a little to
-// the merge.  Take the cheapest count, never fewer than four key tiles per split.
-int choose_splits(int64_t base_wgs, int max_tiles_per_problem) {
-  if (base_wgs <= 0) return 1;
-  const int n_cu = num_cus();
-  const int s_max = (int)std::min<int64_t>(32, std::max(1, max_tiles_per_problem / 4));
-  int best = 1;
-  double best_cost = 0;
-  for (int s = 1; s <= s_max; ++s) {
-    const double rounds = (double)((base_wgs * s + n_cu - 1) / n_cu);
-    const double cost = rounds * (4.0 + (max_tiles_per_problem + s - 1) / s) + 0.5 * s;
-    if (s == 1 || cost < best_cost) {
-      best = s;
-      best_cost = cost;
-    }
-  }
-  return best;
-}
-
-struct FinalPlan {
-  int64_t lq_total = 0;
-  int64_t total_tiles = 0;
-  int max_nt = 0;
-  int n_splits = 1;
-  size_t kf_bytes = 0, q_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0;
-  size_t total() const {
-    return align256(kf_bytes) + align256(q_bytes) + align256(part_o_bytes) + align256(part_ml_bytes);
-  }
-};
-
-int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_ctx,
-                   int32_t rope_mode, bool have_rot_out, FinalPlan *plan) {
-  if (n_prompts < 0 || (n_prompts > 0 && (!cu_q || !cu_ctx)))
-    return fail(BA_ERR_INVALID_ARG, "cu_q / cu_ctx: null or negative prompt count");
-  const int G = h->n_q_heads / h->n_kv_heads;
-  FinalPlan pl;
-  if (n_prompts > 0 && cu_q[0] != 0) return fail(BA_ERR_INVALID_ARG, "cu_q[0] must be 0");
-  if (n_prompts > 0 && cu_ctx[0] < 0) return fail(BA_ERR_INVALID_ARG, "cu_ctx[0] must not be negative");
-  for (int n = 0; n < n_prompts; ++n) {
-    const int64_t lq = (int64_t)cu_q[n + 1] - cu_q[n];
-    const int64_t tc = (int64_t)cu_ctx[n + 1] - cu_ctx[n];
-    if (lq < 1) return fail(BA_ERR_INVALID_ARG, "prompt %d: the final block needs at least one token", n);
-    if (tc < 0) return fail(BA_ERR_INVALID_ARG, "prompt %d: cu_ctx decreases", n);
-    if (lq * G > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "prompt %d: too many packed rows", n);
-    pl.total_tiles += (lq * G + ba::kTileRows - 1) / ba::kTileRows;
-    const int nt = (int)((tc + ba::kTileKeys - 1) / ba::kTileKeys + (lq + ba::kTileKeys - 1) / ba::kTileKeys);
-    pl.max_nt = std::max(pl.max_nt, nt);
-  }
-  pl.lq_total = n_prompts > 0 ? cu_q[n_prompts] : 0;
-  pl.n_splits = choose_splits(pl.total_tiles * h->n_kv_heads, pl.max_nt);
-  if (rope_mode == BA_ROPE_APPLY) {
-    if (!have_rot_out) pl.kf_bytes = (size_t)pl.lq_total * h->n_kv_heads * h->head_dim * 2;
-    pl.q_bytes = (size_t)pl.lq_total * h->n_q_heads * h->head_dim * 2;  // rotated, pre-scaled queries
-  }
-  if (pl.n_splits > 1) {
-    const size_t rows = (size_t)pl.lq_total * h->n_q_heads;
-    pl.part_o_bytes = (size_t)pl.n_splits * rows * h->head_dim * 2;  // fp16
-    pl.part_ml_bytes = (size_t)pl.n_splits * rows * 2 * 4;
-  }
-  *plan = pl;
-  return BA_OK;
-}
-
-int32_t check_offsets(int32_t n_blocks, const int32_t *offs) {
-  if (n_blocks < 0 || !offs) return fail(BA_ERR_INVALID_ARG, "block_offsets: null or negative block count");
-  if (offs[0] != 0) return fail(BA_ERR_INVALID_ARG, "block_offsets[0] must be 0");
-  for (int b = 0; b < n_blocks; ++b)
-    if (offs[b + 1] < offs[b]) return fail(BA_ERR_INVALID_ARG, "block_offsets must not decrease (block %d)", b);
-  return BA_OK;
-}
-
-// cu_blk of a whole-prompt call (cu_blk[0] = 0, at least one block per prompt) and the block offsets behind it.
-int32_t check_prompt_blocks(int32_t n_prompts, const int32_t *cu_blk, const int32_t *block_offsets) {
-  if (n_prompts < 0 || !cu_blk) return fail(BA_ERR_INVALID_ARG, "cu_blk: null or negative prompt count");
-  if (cu_blk[0] != 0) return fail(BA_ERR_INVALID_ARG, "cu_blk[0] must be 0");
-  for (int n = 0; n < n_prompts; ++n)
-    if (cu_blk[n + 1] <= cu_blk[n]) return fail(BA_ERR_INVALID_ARG, "prompt %d: at least one block needed", n);
-  return check_offsets(cu_blk[n_prompts], block_offsets);
 }
 
 // Run the rotation kernel over a list of blocks, a launch per table-full of them.
@@ -365,8 +260,6 @@ const char *ba_status_string(int32_t status) {
     default: return "BA_ERR_UNKNOWN";
   }
 }
-
-const char *ba_last_error(void) { return g_err; }
 
 int32_t ba_profile_begin(int32_t max_records) {
   std::lock_guard<std::mutex> lk(g_prof.mu);
@@ -499,39 +392,16 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ap.rope_layout = heads->rope_layout;
   ap.n_splits = 1;
 
-  // Blocks up to kShortMaxLen tokens take the schedule with small workgroups, several to a compute
-  // unit; longer ones the main core.  (The short-block kernel assumes at most 8 tokens per 32 packed
-  // rows, and addresses the rows of a block with 32-bit element offsets.)
+  // short blocks take the schedule with small workgroups, several to a compute unit; longer ones the main core
   const int64_t widest = std::max(std::max(q->stride_tok, o_out->stride_tok),
                                   (int64_t)G * std::max(q->stride_head, o_out->stride_head));
-  const int64_t short_max =
-      (G >= 4 && ((int64_t)ba::kShortMaxLen + 1) * widest < 0x40000000) ? ba::kShortMaxLen : -1;
+  const int64_t short_max = ba::encode_short_max(G, widest);
 
   for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
     const int n = std::min(ba::kEncMaxBlocks, n_blocks - b0);
-    // one table of blocks per schedule: a block has row tiles in the table of its own schedule only,
-    // and the kernels never land on a block without tiles
     ba::EncodeMeta meta[2];  // [0] main core, [1] short blocks
-    int64_t tiles[2] = {0, 0};
-    memset(meta, 0, sizeof(meta));
-    for (int i = 0; i < n; ++i) {
-      const int64_t len = (int64_t)block_offsets[b0 + i + 1] - block_offsets[b0 + i];
-      if (len * G > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "block %d: too many packed rows", b0 + i);
-      const int which = len <= short_max ? 1 : 0;
-      for (int m = 0; m < 2; ++m) {
-        meta[m].offs[i] = block_offsets[b0 + i];
-        meta[m].tile_start[i] = (int32_t)tiles[m];
-      }
-      const int tile_rows = which ? ba::kShortTileRows : ba::kTileRows;
-      tiles[which] += (len * G + tile_rows - 1) / tile_rows;
-      if (tiles[which] > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
-    }
-    for (int m = 0; m < 2; ++m) {
-      meta[m].n = n;
-      meta[m].offs[n] = block_offsets[b0 + n];
-      meta[m].tile_start[n] = (int32_t)tiles[m];
-      for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta[m].tile_start[i] = 0x7fffffff;
-    }
+    int64_t tiles[2];
+    if ((rc = ba::build_encode_metas(block_offsets, b0, n, G, short_max, meta, tiles))) return rc;
     if (tiles[0] + tiles[1] == 0) continue;
     if (rope_mode == BA_ROPE_APPLY) {  // local positions: every block starts at 0
       if ((rc = run_rope_prepass(heads, rt, q, nullptr, k, &k_use, n, meta[0].offs, nullptr, stream, nullptr, nullptr,
@@ -663,41 +533,16 @@ int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, co
   ap.rope_layout = heads->rope_layout;
   ap.n_splits = 1;
 
-  // First key of every block: its own first token, or for a prompt's last block the prompt's.
-  // Blocks go to the kernel longest key range first (a prompt's last block walks the whole prompt,
-  // and a launch should not end on a few of those).
-  struct Blk {
-    int32_t start, len, kstart;
-  };
-  std::vector<Blk> blks;
-  blks.reserve(n_blocks);
-  for (int n = 0; n < n_prompts; ++n)
-    for (int b = cu_blk[n]; b < cu_blk[n + 1]; ++b) {
-      const int32_t len = block_offsets[b + 1] - block_offsets[b];
-      if (len == 0) continue;
-      blks.push_back({block_offsets[b], len, b == cu_blk[n + 1] - 1 ? block_offsets[cu_blk[n]] : block_offsets[b]});
-    }
-  std::stable_sort(blks.begin(), blks.end(), [](const Blk &a, const Blk &b) {
-    return (int64_t)a.start + a.len - a.kstart > (int64_t)b.start + b.len - b.kstart;
-  });
+  // Blocks go to the kernel longest key range first (see the planner).
+  std::vector<ba::PromptBlock> blks = ba::list_prompt_blocks(n_prompts, cu_blk, block_offsets);
+  ba::sort_by_key_range(&blks);
   const int n_live = (int)blks.size();
 
   for (int b0 = 0; b0 < n_live; b0 += ba::kEncMaxBlocks) {
     const int n = std::min(ba::kEncMaxBlocks, n_live - b0);
     ba::PromptMeta meta;
-    memset(&meta, 0, sizeof(meta));
-    meta.n = n;
-    int64_t tiles = 0;
-    for (int i = 0; i < n; ++i) {
-      meta.start[i] = blks[b0 + i].start;
-      meta.len[i] = blks[b0 + i].len;
-      meta.kstart[i] = blks[b0 + i].kstart;
-      meta.tile_start[i] = (int32_t)tiles;
-      tiles += ((int64_t)blks[b0 + i].len * G + ba::kShortTileRows - 1) / ba::kShortTileRows;
-      if (tiles > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
-    }
-    meta.tile_start[n] = (int32_t)tiles;
-    for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta.tile_start[i] = 0x7fffffff;
+    const int64_t tiles = ba::build_prompt_meta(blks, (size_t)b0, n, G, &meta);
+    if (tiles < 0) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
     if (tiles == 0) continue;
     ap.total_tiles = (int32_t)tiles;
     ap.tiles_div = ba::make_fast_div((uint32_t)tiles);
@@ -827,41 +672,16 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   ap.head_dim = D;
   ap.n_splits = 1;
 
-  // non-empty blocks with the first key they see and (for passages) their prompt's last block
-  struct Blk {
-    int32_t start, len, kstart, fin_start, fin_len;
-  };
-  std::vector<Blk> blks;
-  for (int n = 0; n < n_prompts; ++n) {
-    const int last = cu_blk[n + 1] - 1;
-    const int32_t fs = block_offsets[last], fl = block_offsets[last + 1] - fs;
-    for (int b = cu_blk[n]; b <= last; ++b) {
-      const int32_t len = block_offsets[b + 1] - block_offsets[b];
-      if (len == 0) continue;
-      blks.push_back({block_offsets[b], len, b == last ? block_offsets[cu_blk[n]] : block_offsets[b], fs, b == last ? 0 : fl});
-    }
-  }
+  const std::vector<ba::PromptBlock> blks = ba::list_prompt_blocks(n_prompts, cu_blk, block_offsets);
+  typedef ba::PromptBlock Blk;
   // dq: query rows own the sums; longest key range first
   std::vector<Blk> by_q = blks;
-  std::stable_sort(by_q.begin(), by_q.end(), [](const Blk &a, const Blk &b) {
-    return (int64_t)a.start + a.len - a.kstart > (int64_t)b.start + b.len - b.kstart;
-  });
+  ba::sort_by_key_range(&by_q);
   for (size_t b0 = 0; b0 < by_q.size(); b0 += ba::kEncMaxBlocks) {
     const int n = (int)std::min<size_t>(ba::kEncMaxBlocks, by_q.size() - b0);
     ba::PromptMeta meta;
-    memset(&meta, 0, sizeof(meta));
-    meta.n = n;
-    int64_t tiles = 0;
-    for (int i = 0; i < n; ++i) {
-      meta.start[i] = by_q[b0 + i].start;
-      meta.len[i] = by_q[b0 + i].len;
-      meta.kstart[i] = by_q[b0 + i].kstart;
-      meta.tile_start[i] = (int32_t)tiles;
-      tiles += ((int64_t)by_q[b0 + i].len * G + ba::kShortTileRows - 1) / ba::kShortTileRows;
-    }
-    meta.tile_start[n] = (int32_t)tiles;
-    for (int i = n + 1; i <= ba::kEncMaxBlocks; ++i) meta.tile_start[i] = 0x7fffffff;
-    if (tiles > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
+    const int64_t tiles = ba::build_prompt_meta(by_q, b0, n, G, &meta);
+    if (tiles < 0) return fail(BA_ERR_INVALID_ARG, "too many row tiles in one call");
     if (tiles == 0) continue;
     ap.total_tiles = (int32_t)tiles;
     ap.tiles_div = ba::make_fast_div((uint32_t)tiles);
@@ -995,7 +815,7 @@ size_t ba_final_block_attention_workspace_bytes(const ba_heads *heads, int32_t n
                                                 int32_t rope_mode, int32_t have_k_f_rot_out) {
   if (check_heads(heads, true) != BA_OK) return 0;
   FinalPlan pl;
-  if (plan_final(heads, n_prompts, cu_q, cu_ctx, rope_mode, have_k_f_rot_out != 0, &pl) != BA_OK) return 0;
+  if (ba::plan_final(heads, n_prompts, cu_q, cu_ctx, rope_mode, have_k_f_rot_out != 0, num_cus(), &pl) != BA_OK) return 0;
   return pl.total();
 }
 
@@ -1011,7 +831,7 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   if (rope_mode != BA_ROPE_NONE && rope_mode != BA_ROPE_APPLY)
     return fail(BA_ERR_INVALID_ARG, "rope_mode %d unknown", rope_mode);
   FinalPlan pl;
-  if ((rc = plan_final(heads, n_prompts, cu_q, cu_ctx, rope_mode, k_f_rot_out != nullptr, &pl))) return rc;
+  if ((rc = ba::plan_final(heads, n_prompts, cu_q, cu_ctx, rope_mode, k_f_rot_out != nullptr, num_cus(), &pl))) return rc;
   if (n_prompts == 0) return BA_OK;
   if ((rc = check_tensor(q_f, "q_f", false, D, heads->n_q_heads))) return rc;
   if ((rc = check_tensor(k_f, "k_f", false, D, heads->n_kv_heads))) return rc;
@@ -1110,18 +930,7 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   for (int n0 = 0; n0 < n_prompts; n0 += ba::kFinMaxPrompts) {
     const int n = std::min(ba::kFinMaxPrompts, n_prompts - n0);
     ba::FinalMeta meta;
-    memset(&meta, 0, sizeof(meta));
-    meta.n = n;
-    int64_t tiles = 0;
-    for (int i = 0; i < n; ++i) {
-      meta.cu_q[i] = cu_q[n0 + i];
-      meta.cu_ctx[i] = cu_ctx[n0 + i];
-      meta.tile_start[i] = (int32_t)tiles;
-      tiles += ((int64_t)lens[n0 + i] * G + ba::kTileRows - 1) / ba::kTileRows;
-    }
-    meta.cu_q[n] = cu_q[n0 + n];
-    meta.cu_ctx[n] = cu_ctx[n0 + n];
-    meta.tile_start[n] = (int32_t)tiles;
+    const int64_t tiles = ba::build_final_meta(cu_q, cu_ctx, n0, n, G, &meta);
     ap.total_tiles = (int32_t)tiles;
     if (rope_mode == BA_ROPE_APPLY) {  // absolute positions of the final block's tokens
       if ((rc = run_rope_prepass(heads, rt, q_f, q_ws, k_f, &kf_use, n, meta.cu_q, pos0.data() + n0, stream)))
@@ -1187,7 +996,7 @@ extern "C" int32_t ba_final_block_attention_static(const ba_heads *heads, const 
   if (rope_mode != BA_ROPE_NONE && rope_mode != BA_ROPE_APPLY)
     return fail(BA_ERR_INVALID_ARG, "rope_mode %d unknown", rope_mode);
   FinalPlan pl;
-  if ((rc = plan_final(heads, n_prompts, cu_q, cu_ctx, rope_mode, k_f_rot_out != nullptr, &pl))) return rc;
+  if ((rc = ba::plan_final(heads, n_prompts, cu_q, cu_ctx, rope_mode, k_f_rot_out != nullptr, num_cus(), &pl))) return rc;
   if (pl.total() > (size_t)BA_STATIC_SCRATCH_BYTES)
     return fail(BA_ERR_WORKSPACE, "final block (static scratch): this call needs %zu bytes of workspace, the array holds %zu",
                 pl.total(), (size_t)BA_STATIC_SCRATCH_BYTES);
@@ -1201,95 +1010,6 @@ extern "C" int32_t ba_final_block_attention_static(const ba_heads *heads, const 
 
 // ------------------------------------------------------------------------------------------
 namespace {
-
-struct BlocksPlan {
-  int64_t lq_total = 0;
-  int64_t total_tiles = 0;
-  int64_t n_blocks = 0;  // non-empty blocks over all prompts
-  int max_nt = 0;
-  int n_splits = 1;
-  size_t kf_bytes = 0, q_bytes = 0, rot_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0;
-  // Small blocks: the context is first gathered (K re-encoded, V copied) into the workspace and the
-  // call continues as ba_final_block_attention.
-  bool gather = false;
-  std::vector<int32_t> cu_ctx;    // per prompt, gathered route only
-  size_t gather_kv_bytes = 0;     // one of the two gathered tensors
-  size_t gather_final_bytes = 0;  // workspace of the final-block step behind them
-  size_t total() const {
-    if (gather) return 2 * align256(gather_kv_bytes) + gather_final_bytes;
-    return align256(kf_bytes) + align256(q_bytes) + align256(rot_bytes) + align256(part_o_bytes) +
-           align256(part_ml_bytes);
-  }
-};
-
-// gather_below: mean length (tokens) of a call's cached blocks below which the call gathers
-// (BA_GATHER_DEFAULT: 256; 0: never).
-int32_t plan_final_blocks(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_blk,
-                          const int32_t *blk_len, bool have_rot_out, int32_t gather_below, BlocksPlan *plan) {
-  if (gather_below < 0 && gather_below != BA_GATHER_DEFAULT)
-    return fail(BA_ERR_INVALID_ARG, "gather_below %d: a token count, 0 or BA_GATHER_DEFAULT", gather_below);
-  if (gather_below == BA_GATHER_DEFAULT) gather_below = 256;
-  if (n_prompts < 0 || (n_prompts > 0 && (!cu_q || !cu_blk)))
-    return fail(BA_ERR_INVALID_ARG, "cu_q / cu_blk: null or negative prompt count");
-  BlocksPlan pl;
-  if (n_prompts > 0 && (cu_q[0] != 0 || cu_blk[0] != 0)) return fail(BA_ERR_INVALID_ARG, "cu_q[0] and cu_blk[0] must be 0");
-  const int G = h->n_q_heads / h->n_kv_heads;
-  int64_t max_nb = 0;  // most non-empty blocks in one prompt
-  for (int n = 0; n < n_prompts; ++n) {
-    const int64_t lq = (int64_t)cu_q[n + 1] - cu_q[n];
-    if (lq < 1) return fail(BA_ERR_INVALID_ARG, "prompt %d: the final block needs at least one token", n);
-    if (cu_blk[n + 1] < cu_blk[n]) return fail(BA_ERR_INVALID_ARG, "prompt %d: cu_blk decreases", n);
-    if (cu_blk[n + 1] > cu_blk[n] && !blk_len) return fail(BA_ERR_INVALID_ARG, "blk_len is null");
-    if (lq * G > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "prompt %d: too many packed rows", n);
-    int64_t tiles = (lq + ba::kTileKeys - 1) / ba::kTileKeys, ctx = 0, nb = 0;
-    for (int b = cu_blk[n]; b < cu_blk[n + 1]; ++b) {
-      if (blk_len[b] < 0) return fail(BA_ERR_INVALID_ARG, "block %d: negative length", b);
-      if (blk_len[b] == 0) continue;
-      tiles += (blk_len[b] + ba::kTileKeys - 1) / ba::kTileKeys;
-      ctx += blk_len[b];
-      ++nb;
-    }
-    if (ctx > 0x3fffffff || tiles > 0x1ffffff) return fail(BA_ERR_INVALID_ARG, "prompt %d: context too long", n);
-    max_nb = std::max(max_nb, nb);
-    pl.n_blocks += nb;
-    pl.total_tiles += (lq * G + ba::kTileRows - 1) / ba::kTileRows;
-    pl.max_nt = std::max(pl.max_nt, (int)tiles);
-  }
-  pl.lq_total = n_prompts > 0 ? cu_q[n_prompts] : 0;
-  // The kernel that reads the block table pays a fixed price per block (it turns its queries at
-  // every block boundary), a gathered copy a price per token: short blocks are gathered.
-  int64_t ctx_total = 0;
-  pl.cu_ctx.assign(n_prompts + 1, 0);
-  for (int n = 0; n < n_prompts; ++n) {
-    for (int b = cu_blk[n]; b < cu_blk[n + 1]; ++b) ctx_total += blk_len[b];
-    if (ctx_total > 0x3fffffff) return fail(BA_ERR_INVALID_ARG, "context too long");
-    pl.cu_ctx[n + 1] = (int32_t)ctx_total;
-  }
-  if (pl.n_blocks > 0 && ctx_total < (int64_t)gather_below * pl.n_blocks) {
-    FinalPlan fp;
-    int32_t rc = plan_final(h, n_prompts, cu_q, pl.cu_ctx.data(), BA_ROPE_APPLY, have_rot_out, &fp);
-    if (rc) return rc;
-    pl.gather = true;
-    pl.gather_kv_bytes = (size_t)ctx_total * h->n_kv_heads * h->head_dim * 2;
-    pl.gather_final_bytes = fp.total();
-    *plan = pl;
-    return BA_OK;
-  }
-  if (max_nb > ba::kBlkMaxBlocks)
-    return fail(BA_ERR_UNSUPPORTED, "%lld cached blocks in one prompt, at most %d when the kernel reads the block table",
-                (long long)max_nb, ba::kBlkMaxBlocks);
-  pl.n_splits = choose_splits(pl.total_tiles * h->n_kv_heads, pl.max_nt);
-  if (!have_rot_out) pl.kf_bytes = (size_t)pl.lq_total * h->n_kv_heads * h->head_dim * 2;
-  pl.q_bytes = (size_t)pl.lq_total * h->n_q_heads * h->head_dim * 2;
-  pl.rot_bytes = (size_t)pl.n_blocks * h->head_dim * 4;  // D/2 (cos, sin) pairs per block
-  if (pl.n_splits > 1) {
-    const size_t rows = (size_t)pl.lq_total * h->n_q_heads;
-    pl.part_o_bytes = (size_t)pl.n_splits * rows * h->head_dim * 2;
-    pl.part_ml_bytes = (size_t)pl.n_splits * rows * 2 * 4;
-  }
-  *plan = pl;
-  return BA_OK;
-}
 
 struct BlocksCall {
   const ba_heads *heads;
@@ -1382,7 +1102,7 @@ size_t ba_final_block_attention_cached_workspace_bytes(const ba_heads *heads, in
                                                        int32_t gather_below) {
   if (check_heads(heads, true) != BA_OK) return 0;
   BlocksPlan pl;
-  if (plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, have_k_f_rot_out != 0, gather_below, &pl) != BA_OK)
+  if (ba::plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, have_k_f_rot_out != 0, gather_below, num_cus(), &pl) != BA_OK)
     return 0;
   return pl.total();
 }
@@ -1399,7 +1119,7 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
   if ((rc = check_heads(heads, true))) return rc;
   const int D = heads->head_dim;
   BlocksPlan pl;
-  if ((rc = plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, k_f_rot_out != nullptr, gather_below, &pl)))
+  if ((rc = ba::plan_final_blocks(heads, n_prompts, cu_q, cu_blk, blk_len, k_f_rot_out != nullptr, gather_below, num_cus(), &pl)))
     return rc;
   if (n_prompts == 0) return BA_OK;
   if ((rc = check_tensor(q_f, "q_f", false, D, heads->n_q_heads))) return rc;
