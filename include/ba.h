@@ -256,7 +256,10 @@ size_t ba_final_block_attention_cached_workspace_bytes(const ba_heads *heads, in
  * natural-log sum of exp(scale * <q^, k^>) over each row's visible keys, as a backward pass needs.
  * Built for training-sized prompts: every row tile walks its key range alone (no KV splits), so a
  * short last block behind tens of thousands of context tokens is better served by
- * ba_final_block_attention.  Needs n_q_heads / n_kv_heads >= 4 (BA_ERR_UNSUPPORTED otherwise).
+ * ba_final_block_attention.  The schedule packs the query heads of a KV head next to each other and
+ * is laid out for groups of four or more; a smaller group (down to one query head per KV head) is
+ * run as a group of four with zero phantom heads, through padded copies of q and o in the workspace
+ * (correct, at up to four times the attention work).
  * ws: 256-byte aligned, at least ba_block_attention_prompts_workspace_bytes() bytes.
  */
 int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
@@ -281,7 +284,8 @@ size_t ba_block_attention_prompts_workspace_bytes(const ba_heads *heads, int32_t
  * q, k, v, cu_blk, block_offsets: as given to the forward call.  o [T, n_q_heads, D] and lse
  * (device, [T][n_q_heads] floats): its outputs.  d_out [T, n_q_heads, D]; dq_out like q, dk_out and
  * dv_out like k and v; all bf16, fully overwritten.  Deterministic: every sum has one owner, no
- * atomics.  Needs n_q_heads / n_kv_heads >= 4.  ws: 256-byte aligned, at least
+ * atomics.  Fewer than four query heads per KV head: run as groups of four, as in the forward call
+ * (phantom heads have a zero output gradient and add nothing to dk and dv).  ws: 256-byte aligned, at least
  * ba_block_attention_prompts_backward_workspace_bytes() bytes.
  */
 int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tensor *q,

@@ -308,6 +308,48 @@ def masked_attention_backward_bruteforce(q, k, v, d_out, offs, th, *, scale=None
     return rope_dense(dqr, -pos, th, layout), rope_dense(dkr, -pos, th, layout), dv, lse
 
 
+def masked_attention_backward_term_sums(q, k, v, d_out, offs, th, *, scale=None, layout=LAYOUT_INTERLEAVED):
+    """For every element of the gradients that masked_attention_backward_bruteforce returns, the sum
+    of the ABSOLUTE values of the products it is the sum of (dV = sum_i P_ij dO_i, dq^ = scale sum_j
+    dS_ij k^_j, dk^ = scale sum_i dS_ij q^_i).  Not a gradient: the scale a rounding-error bound is
+    stated against (|fl(sum a_i b_i) - sum a_i b_i| <= eps sum |a_i b_i|).  dq and dk are turned back
+    by an orthogonal map of each dimension pair, so both members of a pair get the pair's Euclidean
+    norm of the rotated-frame sums.  Returns (aq, ak, av).  Tiny inputs only."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    d_out = np.asarray(d_out, dtype=np.float64)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    sc = float(scale) if scale is not None else 1.0 / np.sqrt(D)
+    pos = np.arange(T)
+    qr = rope_dense(q, pos, th, layout)
+    kr = rope_dense(k, pos, th, layout)
+    M = block_mask(offs)
+    aq = np.zeros_like(q)
+    ak = np.zeros_like(k)
+    av = np.zeros_like(v)
+    for h in range(Hq):
+        g = h // G
+        S = np.where(M, sc * (qr[:, h, :] @ kr[:, g, :].T), -np.inf)
+        E = np.exp(S - S.max(axis=1, keepdims=True))
+        P = E / E.sum(axis=1, keepdims=True)
+        dO = d_out[:, h, :]
+        dS = P * (dO @ v[:, g, :].T - (dO * (P @ v[:, g, :])).sum(axis=1, keepdims=True))
+        av[:, g, :] += P.T @ np.abs(dO)
+        aq[:, h, :] = sc * (np.abs(dS) @ np.abs(kr[:, g, :]))
+        ak[:, g, :] += sc * (np.abs(dS).T @ np.abs(qr[:, h, :]))
+
+    def pair_norm(a):
+        if layout == LAYOUT_HALF:
+            n = np.sqrt(a[..., :D // 2] ** 2 + a[..., D // 2:] ** 2)
+            return np.concatenate([n, n], axis=-1)
+        return np.repeat(np.sqrt(a[..., 0::2] ** 2 + a[..., 1::2] ** 2), 2, axis=-1)
+
+    return pair_norm(aq), pair_norm(ak), av
+
+
 def merge_partials(o_parts, m_parts, l_parts) -> np.ndarray:
     """Merge softmax partials over disjoint key sets.  o_parts[i] is the normalised
     output over key set i, m_parts[i] its max scaled score, l_parts[i] its sum of

@@ -710,21 +710,53 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   }
   static_assert(kNumKBuf == 4 && kNumVBuf == 4, "the copy distances above assume four buffers of each kind");
 
-  // ---- epilogue: each wave transposes its O^T through its own slice of LDS, half of the head
-  //      dimension at a time, so that rows leave as contiguous lines.  The slices lie in the K
-  //      buffers, and every wave's last K read precedes the last barrier the other waves passed;
-  //      waves 4..7 may still be reading their last V tile, which lies elsewhere ------------------
+  // ---- epilogue -----------------------------------------------------------------------------------
   KParams kp = kBlocks ? args_again() : nullptr;
+  const float l_tot = l_run + other_half(l_run);
+  // Every piece is normalised by its own sum (a convex combination of v rows, so it fits fp16 when
+  // it is a split partial); a piece that saw no key is all zeros.
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  if (BA_ARG(n_splits) > 1) {
+    // A split partial leaves in the layout the accumulators have: lane (col, hf) holds, of query row
+    // `col`, the head dims 32 dt + 8 q4 + 4 hf + (0..3); store k = 2 dt + q4 / 2 carries two such
+    // groups of four (q4 even, q4 odd) as eight fp16, and the wave's 64 lanes write 1 KB of consecutive
+    // memory per store.  No transposition, no per-row addresses: the merge kernel undoes the layout.
+    const int64_t unit = ((int64_t)(BA_ARG(tile_base) + rowtile) * BA_ARG(n_kv_heads) + kvh) * kWaves + wave;
+    const int64_t slot = (int64_t)split * BA_ARG(part_units) + unit;
+    char *dst = (char *)BA_ARG(part_o) + slot * (int64_t)(32 * D * 2) + lane * 16;
+#pragma unroll
+    for (int dt = 0; dt < G::DT; ++dt)
+#pragma unroll
+      for (int qp = 0; qp < 2; ++qp) {
+        u32x4_t w;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int v0 = (qp * 2 + u) * 4;
+          w[u * 2] = pack_f16(oacc[dt][v0] * inv, oacc[dt][v0 + 1] * inv);
+          w[u * 2 + 1] = pack_f16(oacc[dt][v0 + 2] * inv, oacc[dt][v0 + 3] * inv);
+        }
+        *reinterpret_cast<u32x4_t *>(dst + (dt * 2 + qp) * 1024) = w;
+      }
+    if (hf == 0) {
+      float2 ml = {l_tot > 0.f ? mb : -INFINITY, l_tot};  // reference in log2 units; -inf: nothing visible
+      *reinterpret_cast<float2 *>(BA_ARG(part_ml) + (slot * 32 + col) * 2) = ml;
+      if (split == 0) {
+        const int g = my_row - my_tok * Gq;
+        BA_ARG(part_idx)[unit * 32 + col] = row_ok ? (pr.q_tok0 + my_tok) * BA_ARG(n_q_heads) + kvh * Gq + g : -1;
+      }
+    }
+    return;
+  }
+  // One piece (no splits): each wave transposes its O^T through its own slice of LDS, half of the head
+  // dimension at a time, so that rows leave as contiguous lines.  The slices lie in the K buffers,
+  // and every wave's last K read precedes the last barrier the other waves passed; waves 4..7 may
+  // still be reading their last V tile, which lies elsewhere.
   const FastDiv gdiv_e = {BA_ARG(group_div.mul), BA_ARG(group_div.sh1), BA_ARG(group_div.sh2)};
   constexpr int HD = D / 2;               // floats per staged row piece
   constexpr int HCH = HD / 4;             // 16-byte chunks per piece (16 or 8)
   constexpr int PITCH = HD * 4;           // bytes per staged row piece (256 or 128)
   constexpr int HLPR = 256 / PITCH;       // pieces per 256-byte LDS line
   lds_char *stage = smem + wave * (32 * PITCH);
-  const float l_tot = l_run + other_half(l_run);
-  // Every piece is normalised by its own sum (a convex combination of v rows, so it fits fp16 when
-  // it is a split partial); a piece that saw no key is all zeros.
-  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     // write: lane (col, hf) owns query row `col`; chunk index XOR row keeps banks apart
@@ -757,29 +789,15 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
         const int g = r - i * Gq;
         const int head = kvh * Gq + g;
         const int d = half * HD + ch * 4;
-        if (BA_ARG(n_splits) == 1) {
-          uint2 o2;
-          o2.x = pack_bf16(w[0], w[1]);
-          o2.y = pack_bf16(w[2], w[3]);
-          *reinterpret_cast<uint2 *>(BA_ARG(o) + (int64_t)(pr.q_tok0 + i) * BA_ARG(o_st) + (int64_t)head * BA_ARG(o_sh) + d) = o2;
-        } else {
-          const int64_t prow = (int64_t)(pr.q_tok0 + i) * BA_ARG(n_q_heads) + head;
-          uint2 o2;
-          o2.x = pack_f16(w[0], w[1]);
-          o2.y = pack_f16(w[2], w[3]);
-          *reinterpret_cast<uint2 *>(BA_ARG(part_o) + ((int64_t)split * BA_ARG(part_rows) + prow) * D + d) = o2;
-        }
+        uint2 o2;
+        o2.x = pack_bf16(w[0], w[1]);
+        o2.y = pack_bf16(w[2], w[3]);
+        *reinterpret_cast<uint2 *>(BA_ARG(o) + (int64_t)(pr.q_tok0 + i) * BA_ARG(o_st) + (int64_t)head * BA_ARG(o_sh) + d) = o2;
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  }
-  if (BA_ARG(n_splits) > 1 && hf == 0 && row_ok) {
-    const int g = my_row - my_tok * Gq;
-    const int64_t prow = (int64_t)(pr.q_tok0 + my_tok) * BA_ARG(n_q_heads) + kvh * Gq + g;
-    float2 ml = {l_tot > 0.f ? mb : -INFINITY, l_tot};  // reference in log2 units; -inf: nothing visible
-    *reinterpret_cast<float2 *>(BA_ARG(part_ml) + ((int64_t)split * BA_ARG(part_rows) + prow) * 2) = ml;
   }
 }
 
@@ -788,28 +806,35 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
 // Merge split partials in split order.  Split i holds its own normalised output o_i (fp16), its
 // reference m_i (log2 units; -inf if it saw no key) and its sum l_i:
 //   m = max m_i,  w_i = 2^(m_i - m) l_i,  o = sum_i w_i o_i / sum_i w_i.
-// SG = 1: a row's splits are merged by the 16-byte columns' threads one after the other.  SG = 4
-// (many splits, few rows): four groups of threads take every fourth split each, so that all loads of
-// a row are in flight at once, and the groups' sums are merged through LDS, group 0 first.
+// The partials lie as the attention kernel's accumulators held them (AttnParams::part_o): a thread
+// here is (unit, store k, lane) of that layout and owns eight output elements of one row -- head dims
+// 32 (k / 2) + 16 (k & 1) + 4 hf + (0..3) and the same + 8 -- so every load is 16 bytes and a wave
+// reads 1 KB of consecutive memory per split.  SG = 1: a thread merges all splits one after the
+// other.  SG = 4 (many splits, few rows): four groups of threads take every fourth split each, so that
+// all loads of a row are in flight at once, and the groups' sums are merged through LDS, group 0 first.
 template <int D, int SG>
-__global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, int64_t n_rows) {
-  constexpr int TPR = D / 8;                         // threads per row, 8 elements (16 bytes of fp16) each
-  constexpr int RPB = kCombineThreads / (TPR * SG);  // rows per workgroup
-  const int g = threadIdx.x / (TPR * RPB);           // which group of splits
-  const int rl = (threadIdx.x / TPR) % RPB;
-  const int64_t row_raw = (int64_t)blockIdx.x * RPB + rl;
-  if (SG == 1 && row_raw >= n_rows) return;
-  const int64_t row = row_raw < n_rows ? row_raw : n_rows - 1;  // (SG > 1: every thread reaches the barrier)
-  const int d = (threadIdx.x % TPR) * 8;
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p) {
+  constexpr int K = D / 16;                          // 16-byte stores per lane of the layout
+  constexpr int KPB = kCombineThreads / (64 * SG);   // layout stores (k values) per workgroup
+  static_assert(KPB >= 1 && K % KPB == 0, "a workgroup covers whole k values of one unit");
+  constexpr int BPU = K / KPB;                       // workgroups per unit
+  const int g = threadIdx.x / (64 * KPB);            // which group of splits
+  const int kl = (threadIdx.x / 64) % KPB;
+  const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
+  const int64_t unit = blockIdx.x / BPU;
+  const int k = (int)(blockIdx.x % BPU) * KPB + kl;
   // all loads are unconditional and independent, so they go out together
   constexpr int MAXS = 32;  // the host never asks for more splits
   float wgt[MAXS];
   float m = -INFINITY;
   const int n_mine = (p.n_splits - g + SG - 1) / SG;  // splits g, g + SG, ...
+  const float2 *ml = reinterpret_cast<const float2 *>(p.part_ml) + unit * 32 + col;
+  const char *po = (const char *)p.part_o + unit * (int64_t)(32 * D * 2) + k * 1024 + lane * 16;
+  const int64_t ml_stride = p.part_units * 32, o_stride = p.part_units * (int64_t)(32 * D * 2);
 #pragma unroll 8
   for (int j = 0; j < n_mine; ++j) {
     const int s = g + j * SG;
-    wgt[j & (MAXS - 1)] = p.part_ml[((int64_t)s * p.part_rows + row) * 2];
+    wgt[j & (MAXS - 1)] = ml[s * ml_stride].x;
     m = fmaxf(m, wgt[j & (MAXS - 1)]);
   }
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -818,9 +843,9 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, 
   for (int j = 0; j < n_mine; ++j) {
     const int s = g + j * SG;
     const float ms = wgt[j & (MAXS - 1)];
-    const float ls = p.part_ml[((int64_t)s * p.part_rows + row) * 2 + 1];
+    const float ls = ml[s * ml_stride].y;
     const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m) * ls;
-    const u32x4_t o = *reinterpret_cast<const u32x4_t *>(p.part_o + ((int64_t)s * p.part_rows + row) * D + d);
+    const u32x4_t o = *reinterpret_cast<const u32x4_t *>(po + s * o_stride);
     l += w;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -828,16 +853,17 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, 
       acc[2 * i + 1] += w * f16_hi(o[i]);
     }
   }
+  const int idx = p.part_idx[unit * 32 + col];
   if constexpr (SG > 1) {
     // (reference, sum, eight partial outputs) of every thread; group 0 merges them in group order
-    __shared__ float part[SG][TPR * RPB][10 + 1];
-    float *mine = part[g][threadIdx.x % (TPR * RPB)];
+    __shared__ float part[SG][64 * KPB][10 + 1];
+    float *mine = part[g][threadIdx.x % (64 * KPB)];
     mine[0] = m;
     mine[1] = l;
 #pragma unroll
     for (int i = 0; i < 8; ++i) mine[2 + i] = acc[i];
     __syncthreads();
-    if (g != 0 || row_raw >= n_rows) return;
+    if (g != 0) return;
     float mm = m;
 #pragma unroll
     for (int h = 1; h < SG; ++h) mm = fmaxf(mm, part[h][threadIdx.x][0]);
@@ -854,13 +880,19 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p, 
       for (int i = 0; i < 8; ++i) acc[i] += wh * o[2 + i];
     }
   }
+  if (idx < 0) return;  // a row beyond the problem's last
   const float inv = 1.0f / l;
-  const int64_t tokn = row / p.n_q_heads;
-  const int head = (int)(row - tokn * p.n_q_heads);
-  u32x4_t w;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) w[i] = pack_bf16(acc[2 * i] * inv, acc[2 * i + 1] * inv);
-  *reinterpret_cast<u32x4_t *>(p.o + tokn * p.o_st + (int64_t)head * p.o_sh + d) = w;
+  const int tokn = idx / p.n_q_heads;
+  const int head = idx - tokn * p.n_q_heads;
+  const int d = 32 * (k >> 1) + 16 * (k & 1) + 4 * hf;
+  uint16_t *orow = p.o + (int64_t)tokn * p.o_st + (int64_t)head * p.o_sh + d;
+  uint2 lo, hi;
+  lo.x = pack_bf16(acc[0] * inv, acc[1] * inv);
+  lo.y = pack_bf16(acc[2] * inv, acc[3] * inv);
+  hi.x = pack_bf16(acc[4] * inv, acc[5] * inv);
+  hi.y = pack_bf16(acc[6] * inv, acc[7] * inv);
+  *reinterpret_cast<uint2 *>(orow) = lo;
+  *reinterpret_cast<uint2 *>(orow + 8) = hi;
 }
 
 template <int D, typename Meta>
@@ -911,20 +943,19 @@ hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMetaSm
 }
 
 template <int D, int SG>
-void launch_combine_t(const AttnParams &p, int64_t n_rows, hipStream_t stream) {
-  constexpr int RPB = kCombineThreads / ((D / 8) * SG);
-  hipLaunchKernelGGL((combine_kernel<D, SG>), dim3((unsigned)((n_rows + RPB - 1) / RPB)), dim3(kCombineThreads), 0,
-                     stream, p, n_rows);
+void launch_combine_t(const AttnParams &p, hipStream_t stream) {
+  constexpr int BPU = (D / 16) / (kCombineThreads / (64 * SG));  // workgroups per unit
+  hipLaunchKernelGGL((combine_kernel<D, SG>), dim3((unsigned)(p.part_units * BPU)), dim3(kCombineThreads), 0, stream, p);
 }
 
-hipError_t launch_combine(const AttnParams &p, int64_t n_tokens, hipStream_t stream) {
-  const int64_t n_rows = n_tokens * p.n_q_heads;
-  if (n_rows == 0) return hipSuccess;
+hipError_t launch_combine(const AttnParams &p, hipStream_t stream) {
+  if (p.part_units == 0) return hipSuccess;
+  if (p.part_units * (p.head_dim / 16) > 0x7fffffff) return hipErrorInvalidValue;
   const bool many = p.n_splits > 8;  // more splits than one thread keeps in flight: four groups of threads per row
   if (p.head_dim == 128) {
-    if (many) launch_combine_t<128, 4>(p, n_rows, stream); else launch_combine_t<128, 1>(p, n_rows, stream);
+    if (many) launch_combine_t<128, 4>(p, stream); else launch_combine_t<128, 1>(p, stream);
   } else if (p.head_dim == 64) {
-    if (many) launch_combine_t<64, 4>(p, n_rows, stream); else launch_combine_t<64, 1>(p, n_rows, stream);
+    if (many) launch_combine_t<64, 4>(p, stream); else launch_combine_t<64, 1>(p, stream);
   } else {
     return hipErrorInvalidValue;
   }

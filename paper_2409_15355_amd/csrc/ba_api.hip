@@ -243,6 +243,48 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
   return BA_OK;
 }
 
+
+// ---- fewer than four query heads per KV head in the whole-prompt calls: run as groups of four --------
+constexpr int kPadGroup = 4;
+
+// A packed [T][n_kv_heads * 4][D] bf16 tensor in the workspace.
+ba_tensor padded_tensor(void *ptr, const ba_heads *h) {
+  ba_tensor t;
+  t.ptr = ptr;
+  t.stride_head = h->head_dim;
+  t.stride_tok = (int64_t)h->n_kv_heads * kPadGroup * h->head_dim;
+  t.dtype = BA_DTYPE_BF16;
+  return t;
+}
+size_t padded_rows_bytes(const ba_heads *h, size_t T) { return align256(T * h->n_kv_heads * kPadGroup * h->head_dim * 2); }
+size_t padded_lse_bytes(const ba_heads *h, size_t T) { return align256(T * h->n_kv_heads * kPadGroup * 4); }
+ba_heads padded_heads(const ba_heads *h) {
+  ba_heads p = *h;
+  p.n_q_heads = h->n_kv_heads * kPadGroup;
+  p.q_to_kv = nullptr;  // (the caller's map, if any, has been checked to be the default one)
+  return p;
+}
+int32_t move_heads(const ba_heads *h, const ba_tensor *real, void *padded, int64_t T, bool to_padded, hipStream_t stream,
+                   const char *what) {
+  ba::HeadPadParams pp;
+  memset(&pp, 0, sizeof(pp));
+  pp.real = real->ptr;
+  pp.real_st = real->stride_tok;
+  pp.real_sh = real->stride_head;
+  pp.padded = padded;
+  pp.padded_sh = h->head_dim;
+  pp.padded_st = (int64_t)h->n_kv_heads * kPadGroup * h->head_dim;
+  pp.tokens = T;
+  pp.n_kv_heads = h->n_kv_heads;
+  pp.group = h->n_q_heads / h->n_kv_heads;
+  pp.group_padded = kPadGroup;
+  pp.chunks = h->head_dim * 2 / 16;
+  pp.elt = 2;
+  hipError_t e = ba::launch_pad_heads(pp, to_padded, stream);
+  if (e != hipSuccess) return device_fail(e, what);
+  return BA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -428,10 +470,13 @@ size_t ba_block_attention_prompts_workspace_bytes(const ba_heads *heads, int32_t
                                                   const int32_t *block_offsets, int32_t rope_mode,
                                                   int32_t have_k_rot_out) {
   if (check_heads(heads, true) != BA_OK || check_prompt_blocks(n_prompts, cu_blk, block_offsets) != BA_OK) return 0;
-  if (rope_mode != BA_ROPE_APPLY) return 0;
   const size_t T = (size_t)block_offsets[cu_blk[n_prompts]];
+  size_t pad_bytes = 0;
+  if (heads->n_q_heads / heads->n_kv_heads < kPadGroup)  // padded q and o, padded log-sum-exps (see head_pad.hip)
+    pad_bytes = 2 * padded_rows_bytes(heads, T) + padded_lse_bytes(heads, T);
+  if (rope_mode != BA_ROPE_APPLY) return pad_bytes;
   const size_t k_bytes = have_k_rot_out ? 0 : align256(T * heads->n_kv_heads * heads->head_dim * 2);
-  return k_bytes + align256(T * heads->head_dim * 4);  // rotated K; scale * (cos, sin) per token and pair
+  return pad_bytes + k_bytes + align256(T * heads->head_dim * 4);  // rotated K; scale * (cos, sin) per token and pair
 }
 
 int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k, const ba_tensor *v,
@@ -464,7 +509,32 @@ int32_t ba_block_attention_prompts(const ba_heads *heads, const ba_tensor *q, co
   for (int b = 0; b < n_blocks; ++b) max_len = std::max<int64_t>(max_len, (int64_t)block_offsets[b + 1] - block_offsets[b]);
   const int64_t widest = std::max(std::max(q->stride_tok, o_out->stride_tok),
                                   (int64_t)G * std::max(q->stride_head, o_out->stride_head));
-  if (G < 4) return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention needs at least 4 query heads per KV head");
+  if (G < kPadGroup) {
+    // run as groups of four: padded q in, padded o and log-sum-exps out, through the workspace
+    const size_t need =
+        ba_block_attention_prompts_workspace_bytes(heads, n_prompts, cu_blk, block_offsets, rope_mode, k_rot_out != nullptr);
+    if (!ws || ws_bytes < need || ((uintptr_t)ws & 255))
+      return fail(BA_ERR_WORKSPACE, "whole prompts: 256-byte aligned workspace of %zu bytes needed, %zu given", need,
+                  ws_bytes);
+    const ba_heads h4 = padded_heads(heads);
+    char *wsp = (char *)ws;
+    const ba_tensor q4 = padded_tensor(wsp, heads);
+    wsp += padded_rows_bytes(heads, (size_t)T);
+    const ba_tensor o4 = padded_tensor(wsp, heads);
+    wsp += padded_rows_bytes(heads, (size_t)T);
+    float *lse4 = (float *)wsp;
+    wsp += padded_lse_bytes(heads, (size_t)T);
+    if ((rc = move_heads(heads, q, q4.ptr, T, true, stream, "whole prompts: head padding launch"))) return rc;
+    if ((rc = ba_block_attention_prompts(&h4, &q4, k, v, &o4, k_rot_out, lse_out ? lse4 : nullptr, n_prompts, cu_blk,
+                                         block_offsets, rope_mode, wsp, ws_bytes - (size_t)(wsp - (char *)ws), stream_)))
+      return rc;
+    if ((rc = move_heads(heads, o_out, o4.ptr, T, false, stream, "whole prompts: head un-padding launch"))) return rc;
+    if (lse_out) {
+      hipError_t e = ba::launch_pad_lse(lse_out, lse4, T, heads->n_kv_heads, G, kPadGroup, false, stream);
+      if (e != hipSuccess) return device_fail(e, "whole prompts: log-sum-exp un-padding launch");
+    }
+    return BA_OK;
+  }
   if ((max_len + 1) * widest >= 0x40000000 || max_len * G > 0x3fffffff)
     return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention: a block of %lld tokens at these strides is too long",
                 (long long)max_len);
@@ -561,9 +631,14 @@ size_t ba_block_attention_prompts_backward_workspace_bytes(const ba_heads *heads
                                                            const int32_t *cu_blk, const int32_t *block_offsets) {
   if (check_heads(heads, true) != BA_OK || check_prompt_blocks(n_prompts, cu_blk, block_offsets) != BA_OK) return 0;
   const size_t T = (size_t)block_offsets[cu_blk[n_prompts]];
-  const size_t D = heads->head_dim, hq = heads->n_q_heads, hkv = heads->n_kv_heads;
+  const size_t D = heads->head_dim, hkv = heads->n_kv_heads;
+  size_t hq = heads->n_q_heads, pad_bytes = 0;
+  if (hq / hkv < (size_t)kPadGroup) {  // padded q, o, d_out and dq, padded log-sum-exps; the rest for groups of four
+    pad_bytes = 4 * padded_rows_bytes(heads, T) + padded_lse_bytes(heads, T);
+    hq = hkv * kPadGroup;
+  }
   // rotated scaled q, rotated k, the table of rotation factors, (log-sum-exp, delta) per row (+ padding)
-  return align256(T * hq * D * 2) + align256(T * hkv * D * 2) + align256(T * D * 4) + align256(T * hq * 8 + 16);
+  return pad_bytes + align256(T * hq * D * 2) + align256(T * hkv * D * 2) + align256(T * D * 4) + align256(T * hq * 8 + 16);
 }
 
 int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tensor *q, const ba_tensor *k,
@@ -595,14 +670,38 @@ int32_t ba_block_attention_prompts_backward(const ba_heads *heads, const ba_tens
   const int64_t widest =
       std::max(std::max((int64_t)hq * D, std::max(std::max(d_out->stride_tok, o->stride_tok), dq_out->stride_tok)),
                (int64_t)G * std::max((int64_t)D, std::max(std::max(d_out->stride_head, o->stride_head), dq_out->stride_head)));
-  if (G < 4) return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention needs at least 4 query heads per KV head");
-  if ((max_len + 1) * widest >= 0x40000000 || max_len * G > 0x3fffffff)
-    return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention: a block of %lld tokens at these strides is too long",
-                (long long)max_len);
   const size_t need = ba_block_attention_prompts_backward_workspace_bytes(heads, n_prompts, cu_blk, block_offsets);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 255))
     return fail(BA_ERR_WORKSPACE, "whole prompts, backward: 256-byte aligned workspace of %zu bytes needed, %zu given",
                 need, ws_bytes);
+  if (G < kPadGroup) {
+    // run as groups of four (see head_pad.hip): the phantom heads' output gradient is zero, so they add
+    // nothing to dk and dv, which the padded call writes straight to the caller's tensors
+    const ba_heads h4 = padded_heads(heads);
+    char *wp = (char *)ws;
+    const ba_tensor q4 = padded_tensor(wp, heads);
+    wp += padded_rows_bytes(heads, (size_t)T);
+    const ba_tensor o4 = padded_tensor(wp, heads);
+    wp += padded_rows_bytes(heads, (size_t)T);
+    const ba_tensor do4 = padded_tensor(wp, heads);
+    wp += padded_rows_bytes(heads, (size_t)T);
+    const ba_tensor dq4 = padded_tensor(wp, heads);
+    wp += padded_rows_bytes(heads, (size_t)T);
+    float *lse4 = (float *)wp;
+    wp += padded_lse_bytes(heads, (size_t)T);
+    if ((rc = move_heads(heads, q, q4.ptr, T, true, stream, "backward: head padding launch"))) return rc;
+    if ((rc = move_heads(heads, o, o4.ptr, T, true, stream, "backward: head padding launch"))) return rc;
+    if ((rc = move_heads(heads, d_out, do4.ptr, T, true, stream, "backward: head padding launch"))) return rc;
+    hipError_t pe = ba::launch_pad_lse(const_cast<float *>(lse), lse4, T, hkv, G, kPadGroup, true, stream);
+    if (pe != hipSuccess) return device_fail(pe, "backward: log-sum-exp padding launch");
+    if ((rc = ba_block_attention_prompts_backward(&h4, &q4, k, v, &o4, lse4, &do4, &dq4, dk_out, dv_out, n_prompts, cu_blk,
+                                                  block_offsets, wp, ws_bytes - (size_t)(wp - (char *)ws), stream_)))
+      return rc;
+    return move_heads(heads, dq_out, dq4.ptr, T, false, stream, "backward: head un-padding launch");
+  }
+  if ((max_len + 1) * widest >= 0x40000000 || max_len * G > 0x3fffffff)
+    return fail(BA_ERR_UNSUPPORTED, "whole-prompt attention: a block of %lld tokens at these strides is too long",
+                (long long)max_len);
   char *wsp = (char *)ws;
   uint16_t *q_rot = (uint16_t *)wsp;
   wsp += align256((size_t)T * hq * D * 2);
@@ -856,6 +955,7 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   uint16_t *q_ws = (uint16_t *)(wsp + align256(pl.kf_bytes));
   uint16_t *part_o = (uint16_t *)(wsp + align256(pl.kf_bytes) + align256(pl.q_bytes));
   float *part_ml = (float *)(wsp + align256(pl.kf_bytes) + align256(pl.q_bytes) + align256(pl.part_o_bytes));
+  int32_t *part_idx = (int32_t *)((char *)part_ml + align256(pl.part_ml_bytes));
 
   ba::RopeTable rt;
   build_rope_table(heads, &rt);
@@ -916,7 +1016,8 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   ap.o_sh = o_out->stride_head;
   ap.part_o = part_o;
   ap.part_ml = part_ml;
-  ap.part_rows = pl.lq_total * heads->n_q_heads;
+  ap.part_idx = part_idx;
+  ap.part_units = pl.total_tiles * heads->n_kv_heads * (ba::kTileRows / 32);
   ap.n_q_heads = heads->n_q_heads;
   ap.n_kv_heads = heads->n_kv_heads;
   ap.group = G;
@@ -927,10 +1028,13 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   ap.rope_layout = heads->rope_layout;
   ap.n_splits = pl.n_splits;
 
+  int64_t tile_base = 0;  // row tiles of the launches so far: the split partials are indexed by row tile
   for (int n0 = 0; n0 < n_prompts; n0 += ba::kFinMaxPrompts) {
     const int n = std::min(ba::kFinMaxPrompts, n_prompts - n0);
     ba::FinalMeta meta;
     const int64_t tiles = ba::build_final_meta(cu_q, cu_ctx, n0, n, G, &meta);
+    ap.tile_base = (int32_t)tile_base;
+    tile_base += tiles;
     ap.total_tiles = (int32_t)tiles;
     if (rope_mode == BA_ROPE_APPLY) {  // absolute positions of the final block's tokens
       if ((rc = run_rope_prepass(heads, rt, q_f, q_ws, k_f, &kf_use, n, meta.cu_q, pos0.data() + n0, stream)))
@@ -947,7 +1051,7 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
     hipError_t e;
     {
       ProfileScope ps(BA_PROFILE_COMBINE, stream);
-      e = ba::launch_combine(ap, pl.lq_total, stream);
+      e = ba::launch_combine(ap, stream);
     }
     if (e != hipSuccess) return device_fail(e, "split combine launch");
   }
@@ -1032,7 +1136,7 @@ int32_t run_final_blocks(const BlocksCall &c, ba::AttnParams ap) {
   std::vector<MetaT> metas(1);
   std::vector<RotsT> rots(1);
   int n0 = 0;
-  int64_t rot_base = 0;
+  int64_t rot_base = 0, tile_base = 0;
   while (n0 < c.n_prompts) {
     MetaT &meta = metas[0];
     RotsT &rr = rots[0];
@@ -1074,6 +1178,8 @@ int32_t run_final_blocks(const BlocksCall &c, ba::AttnParams ap) {
     meta.tile_start[np] = (int32_t)tiles;
     meta.rot_base = (int32_t)rot_base;
     ap.total_tiles = (int32_t)tiles;
+    ap.tile_base = (int32_t)tile_base;
+    tile_base += tiles;
     const ba::RopeRots *big = nullptr;
     const ba::RopeRotsSmall *small = nullptr;
     if constexpr (std::is_same<RotsT, ba::RopeRots>::value) big = &rr; else small = &rr;
@@ -1212,6 +1318,8 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
   uint16_t *part_o = (uint16_t *)wsp;
   wsp += align256(pl.part_o_bytes);
   float *part_ml = (float *)wsp;
+  wsp += align256(pl.part_ml_bytes);
+  int32_t *part_idx = (int32_t *)wsp;
 
   ba::RopeTable rt;
   build_rope_table(heads, &rt);
@@ -1257,7 +1365,8 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
   ap.o_sh = o_out->stride_head;
   ap.part_o = part_o;
   ap.part_ml = part_ml;
-  ap.part_rows = pl.lq_total * heads->n_q_heads;
+  ap.part_idx = part_idx;
+  ap.part_units = pl.total_tiles * heads->n_kv_heads * (ba::kTileRows / 32);
   ap.n_q_heads = heads->n_q_heads;
   ap.n_kv_heads = heads->n_kv_heads;
   ap.group = G;
@@ -1280,7 +1389,7 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
     hipError_t e;
     {
       ProfileScope ps(BA_PROFILE_COMBINE, stream);
-      e = ba::launch_combine(ap, pl.lq_total, stream);
+      e = ba::launch_combine(ap, stream);
     }
     if (e != hipSuccess) return device_fail(e, "split combine launch");
   }

@@ -134,9 +134,15 @@ struct AttnParams {
   int64_t vf_st, vf_sh;
   uint16_t *o;
   int64_t o_st, o_sh;
-  uint16_t *part_o;  // [n_splits][part_rows][D]   fp16: each split's own normalised output
-  float *part_ml;    // [n_splits][part_rows][2]   (reference in log2 units, sum of exponentials)
-  int64_t part_rows;
+  // Split partials, per "unit" = the 32 packed rows one wave owns: unit = ((tile_base + row tile) *
+  // n_kv_heads + KV head) * 8 + wave.  A split's normalised output stays in the layout the MFMA
+  // accumulators have (no transposition on the way out; every wave instruction stores 1 KB of
+  // consecutive memory); the merge kernel reads that layout back and writes the rows where they belong.
+  uint16_t *part_o;   // [n_splits][part_units][D / 16][64 lanes][8] fp16
+  float *part_ml;     // [n_splits][part_units][32][2]  (reference in log2 units, sum of exponentials)
+  int32_t *part_idx;  // [part_units][32]  output row (token * n_q_heads + head) of each packed row, -1: none
+  int64_t part_units;
+  int32_t tile_base;  // row tiles of the call's earlier launches
   int32_t n_q_heads, n_kv_heads, group, head_dim;
   FastDiv group_div;  // division by `group`
   float scale_log2e;  // softmax scale * log2(e)
@@ -222,6 +228,24 @@ struct FinalBlocksMetaT {
 using FinalBlocksMeta = FinalBlocksMetaT<kBlkMaxPrompts, kBlkMaxBlocks>;
 using FinalBlocksMetaSmall = FinalBlocksMetaT<kBlkSmallPrompts, kBlkSmallBlocks>;
 
+// Rows of [tokens][heads][chunks * 16 bytes] tensors moved between a caller's tensor with `group`
+// query heads per KV head and a packed one with `group_padded` (phantom heads are zero).
+struct HeadPadParams {
+  void *real;          // [tokens][n_kv_heads * group] rows, strides in elements of `elt` bytes
+  int64_t real_st, real_sh;
+  void *padded;        // [tokens][n_kv_heads * group_padded] rows
+  int64_t padded_st, padded_sh;
+  int64_t tokens;
+  int32_t n_kv_heads, group, group_padded;
+  int32_t chunks;      // 16-byte pieces per row
+  int32_t elt;         // bytes per element (strides are in elements)
+};
+// to_padded: real -> padded (phantoms zeroed); else padded -> real (real heads only)
+hipError_t launch_pad_heads(const HeadPadParams &p, bool to_padded, hipStream_t stream);
+// the same for [tokens][heads] floats (real: packed [tokens][n_kv_heads * group])
+hipError_t launch_pad_lse(float *real, float *padded, int64_t tokens, int n_kv_heads, int group, int group_padded,
+                          bool to_padded, hipStream_t stream);
+
 hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
 // the same for short blocks: meta.tile_start counts row tiles of kShortTileRows rows
 hipError_t launch_attn_encode_short(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
@@ -229,7 +253,7 @@ hipError_t launch_attn_prompt_short(const AttnParams &p, const PromptMeta &meta,
 hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMeta &meta, hipStream_t stream);
 hipError_t launch_attn_final_blocks(const AttnParams &p, const FinalBlocksMetaSmall &meta, hipStream_t stream);
 hipError_t launch_attn_final(const AttnParams &p, const FinalMeta &meta, hipStream_t stream);
-// Merge split-KV partials into the bf16 output.  rows = tokens * n_q_heads.
-hipError_t launch_combine(const AttnParams &p, int64_t n_tokens, hipStream_t stream);
+// Merge the split-KV partials of all p.part_units units into the bf16 output.
+hipError_t launch_combine(const AttnParams &p, hipStream_t stream);
 
 }  // namespace ba

@@ -106,9 +106,10 @@ int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, co
     pl.q_bytes = (size_t)pl.lq_total * h->n_q_heads * h->head_dim * 2;  // rotated, pre-scaled queries
   }
   if (pl.n_splits > 1) {
-    const size_t rows = (size_t)pl.lq_total * h->n_q_heads;
+    const size_t rows = partial_rows(pl.total_tiles, h->n_kv_heads);
     pl.part_o_bytes = (size_t)pl.n_splits * rows * h->head_dim * 2;  // fp16
     pl.part_ml_bytes = (size_t)pl.n_splits * rows * 2 * 4;
+    pl.part_idx_bytes = rows * 4;
   }
   *plan = pl;
   return BA_OK;
@@ -190,9 +191,10 @@ int32_t plan_final_blocks(const ba_heads *h, int32_t n_prompts, const int32_t *c
   pl.q_bytes = (size_t)pl.lq_total * h->n_q_heads * h->head_dim * 2;
   pl.rot_bytes = (size_t)pl.n_blocks * h->head_dim * 4;  // D/2 (cos, sin) pairs per block
   if (pl.n_splits > 1) {
-    const size_t rows = (size_t)pl.lq_total * h->n_q_heads;
+    const size_t rows = partial_rows(pl.total_tiles, h->n_kv_heads);
     pl.part_o_bytes = (size_t)pl.n_splits * rows * h->head_dim * 2;
     pl.part_ml_bytes = (size_t)pl.n_splits * rows * 2 * 4;
+    pl.part_idx_bytes = rows * 4;
   }
   *plan = pl;
   return BA_OK;

@@ -21,6 +21,10 @@ const char *last_error();
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Split partials are kept per row tile (whole tiles, also where a problem's last tile is ragged):
+// packed rows they cover, over all KV heads.
+inline size_t partial_rows(int64_t total_tiles, int n_kv_heads) { return (size_t)total_tiles * n_kv_heads * kTileRows; }
+
 int32_t check_heads(const ba_heads *h, bool attention);
 // block_offsets of n_blocks blocks: starts at 0, never decreases
 int32_t check_offsets(int32_t n_blocks, const int32_t *offs);
@@ -36,9 +40,10 @@ struct FinalPlan {
   int64_t total_tiles = 0;  // row tiles over all prompts
   int max_nt = 0;           // longest walk, key tiles
   int n_splits = 1;
-  size_t kf_bytes = 0, q_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0;
+  size_t kf_bytes = 0, q_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0, part_idx_bytes = 0;
   size_t total() const {
-    return align256(kf_bytes) + align256(q_bytes) + align256(part_o_bytes) + align256(part_ml_bytes);
+    return align256(kf_bytes) + align256(q_bytes) + align256(part_o_bytes) + align256(part_ml_bytes) +
+           align256(part_idx_bytes);
   }
 };
 int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_ctx,
@@ -52,7 +57,7 @@ struct BlocksPlan {
   int64_t n_blocks = 0;  // non-empty blocks over all prompts
   int max_nt = 0;
   int n_splits = 1;
-  size_t kf_bytes = 0, q_bytes = 0, rot_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0;
+  size_t kf_bytes = 0, q_bytes = 0, rot_bytes = 0, part_o_bytes = 0, part_ml_bytes = 0, part_idx_bytes = 0;
   // Small blocks: the context is first gathered (K re-encoded, V copied) into the workspace and the
   // call continues as ba_final_block_attention.
   bool gather = false;
@@ -62,7 +67,7 @@ struct BlocksPlan {
   size_t total() const {
     if (gather) return 2 * align256(gather_kv_bytes) + gather_final_bytes;
     return align256(kf_bytes) + align256(q_bytes) + align256(rot_bytes) + align256(part_o_bytes) +
-           align256(part_ml_bytes);
+           align256(part_ml_bytes) + align256(part_idx_bytes);
   }
 };
 // gather_below: mean length (tokens) of a call's cached blocks below which the call gathers

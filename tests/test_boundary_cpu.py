@@ -107,7 +107,7 @@ def test_final_rejects_bad_arguments_and_sizes_workspace(lib):
     assert call([0, 256], [0, 31744]) == -4   # workspace missing
     need = ba.ba_final_block_attention_workspace_bytes(h, [0, 256], [0, 31744])
     # config 5: 8 KV splits x 8192 packed rows x (128 fp16 + 2 fp32) + rotated final-block keys and queries
-    assert need == 8 * 8192 * 128 * 2 + 8 * 8192 * 2 * 4 + 256 * 8 * 128 * 2 + 256 * 32 * 128 * 2
+    assert need == 8 * 8192 * 128 * 2 + 8 * 8192 * 2 * 4 + 8192 * 4 + 256 * 8 * 128 * 2 + 256 * 32 * 128 * 2
     assert call([0, 256], [0, 31744], ws=ctypes.c_void_p(0x10000), wsb=need - 1) == -4
     # zero prompts: legal no-op
     cq = i32([0])
@@ -157,7 +157,7 @@ def test_final_cached_rejects_bad_arguments_and_sizes_workspace(lib):
     assert call([0, 256], [0, 31], [1024 * b for b in range(31)], [1024] * 31) == -4  # workspace missing
     need = ba.ba_final_block_attention_cached_workspace_bytes(h, [0, 256], [0, 31], [1024] * 31)
     # config 5 as 31 cached blocks: split partials + rotated final-block keys and queries + 31 rows of rotations
-    assert need == 8 * 8192 * 128 * 2 + 8 * 8192 * 2 * 4 + 256 * 8 * 128 * 2 + 256 * 32 * 128 * 2 + 31 * 128 * 4
+    assert need == 8 * 8192 * 128 * 2 + 8 * 8192 * 2 * 4 + 8192 * 4 + 256 * 8 * 128 * 2 + 256 * 32 * 128 * 2 + 31 * 128 * 4
     # zero prompts: legal no-op
     z = i32([0])
     assert lib.ba_final_block_attention_cached(ctypes.byref(h.c), None, None, None, None, None, None, None, 0, p(z),
@@ -179,7 +179,7 @@ def test_whole_prompts_rejects_bad_arguments_and_sizes_workspace(lib):
     assert call(h, [0, 2, 2], [0, 5, 9]) == -1              # a prompt without a block
     assert call(h, [0, 2], [0, 9, 5]) == -1                 # offsets decrease
     assert call(h, [0, 2], [0, 5, 9], rope=7) == -1         # unknown rope mode
-    assert call(ba.Heads(4, 4, 64), [0, 2], [0, 5, 9]) == -2   # fewer than four query heads per KV head
+    assert call(ba.Heads(4, 4, 64), [0, 2], [0, 5, 9]) == -4   # (fewer than four query heads per KV head: run padded) workspace missing
     assert call(h, [0, 2], [0, 5, 9]) == -4                 # workspace missing
     assert b"workspace" in lib.ba_last_error()
     # rotated keys + the table of factors (one (cos, sin) pair per token and dimension pair)
@@ -188,6 +188,13 @@ def test_whole_prompts_rejects_bad_arguments_and_sizes_workspace(lib):
     assert ba.ba_block_attention_prompts_workspace_bytes(h, [0, 2], [0, 100, 164], have_k_rot_out=True) == \
         (164 * 128 * 4 + 255) // 256 * 256
     assert ba.ba_block_attention_prompts_workspace_bytes(h, [0, 2], [0, 100, 164], ba.ROPE_NONE) == 0
+    # two query heads per KV head run as groups of four: padded q and o (4 heads per KV head), padded log-sum-exps
+    a256 = lambda n: (n + 255) // 256 * 256
+    h2 = ba.Heads(16, 8, 128, 500000.0)
+    assert ba.ba_block_attention_prompts_workspace_bytes(h2, [0, 2], [0, 100, 164], ba.ROPE_NONE) == \
+        2 * a256(164 * 32 * 128 * 2) + a256(164 * 32 * 4)
+    assert ba.ba_block_attention_prompts_workspace_bytes(h2, [0, 2], [0, 100, 164]) == \
+        2 * a256(164 * 32 * 128 * 2) + a256(164 * 32 * 4) + 164 * 8 * 128 * 2 + a256(164 * 128 * 4)
     assert call(h, [0, 2], [0, 0, 0]) == 0                  # no tokens: legal no-op
     # a block whose row offsets would not fit the kernel's 32-bit arithmetic: 3,000 tokens at a token
     # stride of 2^19 elements
@@ -215,7 +222,7 @@ def test_whole_prompts_backward_rejects_bad_arguments_and_sizes_workspace(lib):
     assert call(h, [1, 2], [0, 5, 9]) == -1                   # cu_blk[0] != 0
     assert call(h, [0, 2], [0, 9, 5]) == -1                   # offsets decrease
     assert call(h, [0, 2], [0, 5, 9], lse_p=None) == -1       # no log-sum-exps
-    assert call(ba.Heads(4, 4, 64), [0, 2], [0, 5, 9]) == -2  # fewer than four query heads per KV head
+    assert call(ba.Heads(4, 4, 64), [0, 2], [0, 5, 9]) == -4  # (fewer than four query heads per KV head: run padded) workspace missing
     assert call(h, [0, 2], [0, 5, 9]) == -4                   # workspace missing
     # rotated q, rotated k, the table of rotation factors, (log-sum-exp, delta) per row + padding
     T = 164

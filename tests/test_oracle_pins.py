@@ -519,3 +519,32 @@ def test_backward_equals_finite_differences_and_respects_the_mask():
     M = oracle.block_mask(offs)
     S = (qr[:, 1] @ kr[:, 0].T) / math.sqrt(d)
     assert np.allclose(np.exp(lse[:, 1]), (np.exp(S) * M).sum(axis=1), rtol=1e-12)
+
+
+def test_backward_term_sums_bound_the_gradients_and_are_tight_for_one_sign():
+    """masked_attention_backward_term_sums is the scale the GPU gradient tolerance is stated against:
+    by the triangle inequality it bounds the gradient's magnitude element by element (for dq and dk,
+    pair norm by pair norm: the rotation back is orthogonal), and where every product has one sign
+    (dV with a non-negative output gradient) it equals the gradient itself."""
+    rng = np.random.default_rng(77)
+    T, hq, hkv, d = 37, 4, 2, 16
+    offs = [0, 9, 9, 21, 37]
+    th = oracle.theta(10000.0, d)
+    q, k, v = (rng.standard_normal((T, h, d)) for h in (hq, hkv, hkv))
+    for layout in (oracle.LAYOUT_INTERLEAVED, oracle.LAYOUT_HALF):
+        do = rng.standard_normal((T, hq, d))
+        dq, dk, dv, _ = oracle.masked_attention_backward_bruteforce(q, k, v, do, offs, th, layout=layout)
+        aq, ak, av = oracle.masked_attention_backward_term_sums(q, k, v, do, offs, th, layout=layout)
+
+        def pair_norm(x):
+            if layout == oracle.LAYOUT_HALF:
+                n = np.sqrt(x[..., :d // 2] ** 2 + x[..., d // 2:] ** 2)
+                return np.concatenate([n, n], axis=-1)
+            return np.repeat(np.sqrt(x[..., 0::2] ** 2 + x[..., 1::2] ** 2), 2, axis=-1)
+
+        assert (np.abs(dv) <= av + 1e-12).all() and (pair_norm(dq) <= aq + 1e-12).all() and (pair_norm(dk) <= ak + 1e-12).all()
+        assert (av > 0).all()
+        do_pos = np.abs(do)
+        _, _, dv_pos, _ = oracle.masked_attention_backward_bruteforce(q, k, v, do_pos, offs, th, layout=layout)
+        _, _, av_pos = oracle.masked_attention_backward_term_sums(q, k, v, do_pos, offs, th, layout=layout)
+        assert np.allclose(dv_pos, av_pos, rtol=1e-12, atol=1e-12)
