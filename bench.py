@@ -37,8 +37,39 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
 
+NOMINAL_CLOCK_GHZ = 2.4         # the clock the published peaks are quoted at
+
+
 def visible_pairs_final(t_ctx: int, l_q: int) -> int:
     return l_q * t_ctx + l_q * (l_q + 1) // 2
+
+
+def kernel_sources_sha16() -> str:
+    """Fingerprint of the HIP sources the library is built from: counter readings stored under
+    profiles/ are only quoted while it matches the sources they were collected with."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2409_15355_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        h.update(name.encode())
+        h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def stored_counters():
+    """profiles/counters.json (rocprofv3 --pmc readings of this benchmark's kernels), or None when it
+    is missing or was collected with other kernel sources."""
+    path = os.path.join(ROOT, "profiles", "counters.json")
+    try:
+        c = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    return c if c.get("csrc_sha16") == kernel_sources_sha16() else None
+
+
+def parity_figures(got: np.ndarray, ref: np.ndarray) -> dict:
+    err = np.abs(got - ref)
+    return {"max_abs": float(err.max()), "mean_abs": float(err.mean())}
 
 
 def main() -> int:
@@ -166,17 +197,28 @@ def main() -> int:
     prof_ms, prof_n = ba.ba_profile_end()
     attn_us = prof_ms[ba.PROFILE_ATTENTION] / max(prof_n[ba.PROFILE_ATTENTION], 1) * 1e3
     achieved = flops_layer / (attn_us * 1e-6) / 1e12
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):  # HBM bytes per launch from the committed rocprofv3 --pmc summaries
-        try:
-            traffic = json.load(open(tpath)).get("attn_kernel_final_cfg5_bytes_per_launch")
-        except (OSError, ValueError):
-            traffic = None
+    # HBM bytes per launch and the sustained shader clock come from committed rocprofv3 --pmc readings
+    # (FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy; GRBM_GUI_ACTIVE cycles over the kernel's
+    # duration); they are quoted only while the kernel sources are the ones they were collected with
+    counters = stored_counters()
+    head_c = (counters or {}).get("attn_kernel_final_cfg5") or {}
+    traffic = head_c.get("bytes_per_launch")
+    clock_ghz = head_c.get("clock_ghz")
     roofline = {"bound": "mfma", "kernel": "attn_kernel<128, FinalMeta>", "achieved": round(achieved, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": traffic, "avg_launch_us": round(attn_us, 2),
                 "launches_timed": prof_n[ba.PROFILE_ATTENTION],
+                "avg_launch_us_kernel_trace": head_c.get("kernel_trace_avg_us"),
+                # the same achieved rate against the peak at the clock the part sustains under this load
+                "clock_measured": None if not clock_ghz else {
+                    "sustained_clock_GHz": clock_ghz,
+                    "peak_at_that_clock": round(MFMA_BF16_PEAK_TFLOPS * clock_ghz / NOMINAL_CLOCK_GHZ, 1),
+                    "frac": round(achieved / (MFMA_BF16_PEAK_TFLOPS * clock_ghz / NOMINAL_CLOCK_GHZ), 4),
+                    "source": "profiles/counters.json"},
+                "counters_current": counters is not None,
+                "note": "avg_launch_us is bracketed by HIP events on the launch stream, which keep neighbouring "
+                        "kernels from overlapping and read about 2 to 5 % above the kernel trace's duration of the "
+                        "same kernel: frac is conservative by that much",
                 "other_kernels_us_per_layer": {
                     "rope_final_block_keys": round(prof_ms[ba.PROFILE_REENCODE] / max(prof_n[ba.PROFILE_REENCODE], 1) * 1e3, 2),
                     "split_combine": round(prof_ms[ba.PROFILE_COMBINE] / max(prof_n[ba.PROFILE_COMBINE], 1) * 1e3, 2)}}
@@ -256,6 +298,11 @@ def main() -> int:
             w4 = wl.config4()
             P, L = 32, 1000
             cache = randn_bf16(wl.tensor_seed(4, 0), (w4.n_layers, P * L, hkv, d))
+            host4 = None
+            if not args.no_cpu_baseline and args.only == "":
+                # layer 0 comes from the host generator, so that the oracle sees the same array
+                host4 = wl.normal_bf16_bits(wl.tensor_seed(4, 1), (P * L, hkv, d))
+                cache[0].copy_(dev_bf16(host4))
             dst = torch.empty_like(cache)
             src_off = (np.arange(P) * L).astype(np.int32)
             lens = np.full(P, L, dtype=np.int32)
@@ -271,6 +318,25 @@ def main() -> int:
                 ba.ba_reencode_positions(h4, cache, cache, src_off, src_off, lens, None, new_pos0, ba.REENC_SHIFT)
 
             ms_g, _ = timed(gather, reps, 3)
+            oracle4 = None
+            if host4 is not None:
+                import oracle
+                th4 = oracle.theta(w4.rope_base, d)
+                got_bits = dst[0].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+                k64 = oracle.bf16_bits_to_f64(host4)[None]
+                t0 = time.perf_counter()
+                ref4 = oracle.reencode(k64, src_off, new_pos0, lens, th4, new_pos0=new_pos0)[0]
+                cpu4 = time.perf_counter() - t0
+                got4 = oracle.bf16_bits_to_f64(got_bits)
+                nrm = np.repeat(np.sqrt(ref4[..., 0::2] ** 2 + ref4[..., 1::2] ** 2), 2, axis=-1)
+                exact = wl.f32_to_bf16_bits(ref4.astype(np.float32))
+                oracle4 = {"seconds_one_layer": round(cpu4, 2), "cores": oracle.num_threads(),
+                           "GBps": round(2.0 * host4.size * 2 / cpu4 / 1e9, 3),
+                           "sample": "layer 0 of 32 (1/32 of the elements); the other layers hold device-drawn values",
+                           "parity_on_sample": {
+                               "max_err_over_pair_norm": float((np.abs(got4 - ref4) / np.maximum(nrm, 1e-30)).max()),
+                               "fraction_equal_to_rounded_oracle": float((exact == got_bits).mean())}}
+                del k64, ref4, got4, nrm, exact
             ms_i, _ = timed(inplace, reps, 3)
             rows_out["reencode_cfg4"] = {"bytes": nbytes, "gather_ms": round(ms_g, 4),
                                          "gather_GBps": round(nbytes / ms_g / 1e6, 1),
@@ -301,7 +367,8 @@ def main() -> int:
             ms_f32, _ = timed(f32_keys, reps_o, 2)
             rows_out["reencode_cfg4"].update({"absolute_mode_GBps": round(nbytes / ms_abs / 1e6, 1),
                                               "half_layout_GBps": round(nbytes / ms_half / 1e6, 1),
-                                              "fp32_GBps": round(2 * nbytes / ms_f32 / 1e6, 1)})
+                                              "fp32_GBps": round(2 * nbytes / ms_f32 / 1e6, 1),
+                                              "oracle": oracle4})
             del cache32, dst32
             torch.cuda.empty_cache()
         # a-1, full-attention mode: the same 32,000 tokens as ONE block
@@ -330,9 +397,14 @@ def main() -> int:
             w3 = wl.config3()
             offs3 = w3.passage_block_offsets()
             T3 = int(offs3[-1])
-            q = randn_bf16(wl.tensor_seed(3, 0), (T3, hq, d))
-            k = randn_bf16(wl.tensor_seed(3, 1), (T3, hkv, d))
-            v = randn_bf16(wl.tensor_seed(3, 2), (T3, hkv, d))
+            with_oracle = not args.no_cpu_baseline and args.only == ""
+            if with_oracle:  # host-drawn arrays, the same for the oracle
+                hb3 = [wl.normal_bf16_bits(wl.tensor_seed(3, i), (T3, h_, d)) for i, h_ in enumerate((hq, hkv, hkv))]
+                q, k, v = (dev_bf16(b) for b in hb3)
+            else:
+                q = randn_bf16(wl.tensor_seed(3, 0), (T3, hq, d))
+                k = randn_bf16(wl.tensor_seed(3, 1), (T3, hkv, d))
+                v = randn_bf16(wl.tensor_seed(3, 2), (T3, hkv, d))
             o = torch.empty_like(q)
             kl = torch.empty_like(k)
             h3 = ba.Heads(hq, hkv, d, w3.rope_base)
@@ -345,7 +417,7 @@ def main() -> int:
             ms_e, _ = timed(enc3, 20 if args.only == "" else 200, 3)
             lens3 = np.diff(offs3).astype(np.int64)
             fl = 4.0 * d * hq * float((lens3 * (lens3 + 1) // 2).sum())
-            byts = 2.0 * T3 * d * (2 * hq + 4 * hkv)  # q, o, k, k_local(w), k_local(r), v
+            byts = 2.0 * T3 * d * (2 * hq + 3 * hkv)  # q, o, k, v read or written once, and one write of k_local
             # issued work: every (128-row tile, 32-key tile) pair the short-block schedule walks is computed
             # in full, masked or not (rows = tokens x query heads of a KV group)
             G3 = hq // hkv
@@ -356,20 +428,37 @@ def main() -> int:
                     last_tok = (min(n_rows, (rt + 1) * 128) - 1) // G3
                     issued += 128 * 32 * (last_tok // 32 + 1)
             fl_issued = 4.0 * d * hkv * issued
+            oracle3 = None
+            if with_oracle:
+                import oracle
+                f = oracle.bf16_bits_to_f64
+                th3 = oracle.theta(w3.rope_base, d)
+                t0 = time.perf_counter()
+                ref_o, _ = oracle.encode_blocks(f(hb3[0]), f(hb3[1]), f(hb3[2]), offs3, th3)
+                cpu3 = time.perf_counter() - t0
+                oracle3 = {"seconds": round(cpu3, 2), "cores": oracle.num_threads(), "TFLOPs": round(fl / cpu3 / 1e12, 5),
+                           "sample": "all 160 blocks, every row",
+                           "parity_on_sample": parity_figures(o.float().cpu().numpy().astype(np.float64), ref_o)}
+                del ref_o, hb3
             rows_out["encode_cfg3_ragged"] = {"ms": round(ms_e, 4), "algorithmic_TFLOPs": round(fl / ms_e / 1e9, 1),
                                               "issued_TFLOPs": round(fl_issued / ms_e / 1e9, 1),
-                                              "GBps": round(byts / ms_e / 1e6, 1), "tokens": T3}
+                                              "GBps": round(byts / ms_e / 1e6, 1),
+                                              "frac_of_hbm_peak": round(byts / ms_e / 1e6 / HBM_PEAK_GBS, 4),
+                                              "bound": "hbm (20.5 KB per token against about 100 keys of work each)",
+                                              "tokens": T3, "oracle": oracle3}
             del q, k, v, o, kl, ws_3
         # a-3 batched: config 3's eight final blocks (32..128 query tokens over about 4,000 context tokens each)
         if args.only in ("", "final3"):
             w3 = wl.config3()
             cu_q3, cu_ctx3 = w3.cu_q(), w3.cu_ctx()
             Tq, Tc = int(cu_q3[-1]), int(cu_ctx3[-1])
-            qf3 = randn_bf16(wl.tensor_seed(3, 40), (Tq, hq, d))
-            kc3 = randn_bf16(wl.tensor_seed(3, 41), (Tc, hkv, d))
-            vc3 = randn_bf16(wl.tensor_seed(3, 42), (Tc, hkv, d))
-            kf3 = randn_bf16(wl.tensor_seed(3, 43), (Tq, hkv, d))
-            vf3 = randn_bf16(wl.tensor_seed(3, 44), (Tq, hkv, d))
+            with_oracle = not args.no_cpu_baseline and args.only == ""
+            shapes3 = [(Tq, hq), (Tc, hkv), (Tc, hkv), (Tq, hkv), (Tq, hkv)]
+            if with_oracle:
+                hf3 = [wl.normal_bf16_bits(wl.tensor_seed(3, 40 + i), (n_, h_, d)) for i, (n_, h_) in enumerate(shapes3)]
+                qf3, kc3, vc3, kf3, vf3 = (dev_bf16(b) for b in hf3)
+            else:
+                qf3, kc3, vc3, kf3, vf3 = (randn_bf16(wl.tensor_seed(3, 40 + i), (n_, h_, d)) for i, (n_, h_) in enumerate(shapes3))
             o3 = torch.empty_like(qf3)
             h3 = ba.Heads(hq, hkv, d, w3.rope_base)
             ws_f3 = torch.empty(max(ba.ba_final_block_attention_workspace_bytes(h3, cu_q3, cu_ctx3, ba.ROPE_APPLY, False), 256),
@@ -382,8 +471,26 @@ def main() -> int:
             pairs3 = sum(visible_pairs_final(int(cu_ctx3[n + 1] - cu_ctx3[n]), int(cu_q3[n + 1] - cu_q3[n]))
                          for n in range(len(cu_q3) - 1))
             byts3 = 2.0 * d * (2 * Tc * hkv + 2 * Tq * hkv + 2 * Tq * hq)
-            rows_out["final_cfg3_batched"] = {"ms": round(ms_f3, 4), "TFLOPs": round(4.0 * d * hq * pairs3 / ms_f3 / 1e9, 1),
-                                              "GBps": round(byts3 / ms_f3 / 1e6, 1), "query_tokens": Tq, "context_tokens": Tc}
+            fl3 = 4.0 * d * hq * pairs3
+            oracle3f = None
+            if with_oracle:
+                import oracle
+                f = oracle.bf16_bits_to_f64
+                t0 = time.perf_counter()
+                ref3 = oracle.final_block(f(hf3[0]), f(hf3[1]), f(hf3[2]), f(hf3[3]), f(hf3[4]), cu_q3, cu_ctx3,
+                                          oracle.theta(w3.rope_base, d))
+                cpu3f = time.perf_counter() - t0
+                oracle3f = {"seconds": round(cpu3f, 2), "cores": oracle.num_threads(), "TFLOPs": round(fl3 / cpu3f / 1e12, 5),
+                            "sample": "all 8 prompts, every row",
+                            "parity_on_sample": parity_figures(o3.float().cpu().numpy().astype(np.float64), ref3)}
+                del ref3, hf3
+            rows_out["final_cfg3_batched"] = {"ms": round(ms_f3, 4), "TFLOPs": round(fl3 / ms_f3 / 1e9, 1),
+                                              "GBps": round(byts3 / ms_f3 / 1e6, 1),
+                                              "frac_of_mfma_peak": round(fl3 / ms_f3 / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                              "frac_of_hbm_peak": round(byts3 / ms_f3 / 1e6 / HBM_PEAK_GBS, 4),
+                                              "bound": "at the ridge: %.1f us of MFMA at peak, %.1f us of HBM at peak"
+                                                       % (fl3 / MFMA_BF16_PEAK_TFLOPS / 1e6, byts3 / HBM_PEAK_GBS / 1e3),
+                                              "query_tokens": Tq, "context_tokens": Tc, "oracle": oracle3f}
             del qf3, kc3, vc3, kf3, vf3, o3, ws_f3
         # the paper's own efficiency shape (Section 3.4): a 50-token query block behind a 32K-token prompt
         if args.only in ("", "query50"):
@@ -405,6 +512,8 @@ def main() -> int:
             fl5 = 4.0 * d * hq * visible_pairs_final(Tc5, Lq5)
             rows_out["final_50_query_tokens_32k"] = {"ms_per_layer": round(ms_5, 4), "TFLOPs": round(fl5 / ms_5 / 1e9, 1),
                                                      "GBps": round(2.0 * d * 2 * Tc5 * hkv / ms_5 / 1e6, 1),
+                                                     "frac_of_hbm_peak": round(2.0 * d * 2 * Tc5 * hkv / ms_5 / 1e6 / HBM_PEAK_GBS, 4),
+                                                     "frac_of_mfma_peak": round(fl5 / ms_5 / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
                                                      "note": "50 query tokens over 31,950 context tokens, one layer's K/V (131 MB) read once"}
             del qf5, kc5, vc5, kf5, vf5, o5, ws_5
         # config 2 end to end (10 passages of 200 tokens + 64 query tokens): the three steps one after
@@ -415,13 +524,11 @@ def main() -> int:
             cu_q2, cu_ctx2 = w2.cu_q(), w2.cu_ctx()
             T2, Lq2 = int(offs2[-1]), int(cu_q2[-1])
             h2 = ba.Heads(hq, hkv, d, w2.rope_base)
-            q2 = randn_bf16(wl.tensor_seed(2, 0), (T2, hq, d))
-            k2 = randn_bf16(wl.tensor_seed(2, 1), (T2, hkv, d))
-            v2 = randn_bf16(wl.tensor_seed(2, 2), (T2, hkv, d))
+            # (small enough to draw on the host always: the oracle then sees the same arrays)
+            hb2 = [wl.normal_bf16_bits(wl.tensor_seed(2, i), (n_, h_, d))
+                   for i, (n_, h_) in enumerate([(T2, hq), (T2, hkv), (T2, hkv), (Lq2, hq), (Lq2, hkv), (Lq2, hkv)])]
+            q2, k2, v2, qf2, kf2, vf2 = (dev_bf16(b) for b in hb2)
             o2, kl2, kre2 = torch.empty_like(q2), torch.empty_like(k2), torch.empty_like(k2)
-            qf2 = randn_bf16(wl.tensor_seed(2, 3), (Lq2, hq, d))
-            kf2 = randn_bf16(wl.tensor_seed(2, 4), (Lq2, hkv, d))
-            vf2 = randn_bf16(wl.tensor_seed(2, 5), (Lq2, hkv, d))
             of2 = torch.empty_like(qf2)
             ws_e2 = torch.empty(max(ba.ba_encode_blocks_workspace_bytes(h2, offs2, ba.ROPE_APPLY, True), 256),
                                 dtype=torch.uint8, device="cuda")
@@ -447,8 +554,33 @@ def main() -> int:
             ms_r2, _ = timed(re2, n2, 5)
             ms_f2, _ = timed(fin2, n2, 5)
             ms_a2, _ = timed(all2, n2, 5)
+            oracle2 = None
+            if not args.no_cpu_baseline and args.only == "":
+                import oracle
+                f = oracle.bf16_bits_to_f64
+                th2 = oracle.theta(w2.rope_base, d)
+                to64 = lambda t_: t_.float().cpu().numpy().astype(np.float64)
+                all2()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ref_o2, ref_kl2 = oracle.encode_blocks(f(hb2[0]), f(hb2[1]), f(hb2[2]), offs2, th2)
+                t1 = time.perf_counter()
+                # (each step's oracle starts from the bf16 values the device handed on, as the next call does)
+                kl_bits = kl2.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+                ref_kre2 = oracle.reencode(f(kl_bits)[None], src2, src2, len2, th2, new_pos0=src2)[0]
+                t2 = time.perf_counter()
+                kre_bits = kre2.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+                ref_of2 = oracle.final_block(f(hb2[3]), f(kre_bits), f(hb2[2]), f(hb2[4]), f(hb2[5]), cu_q2, cu_ctx2, th2)
+                t3 = time.perf_counter()
+                nrm2 = np.repeat(np.sqrt(ref_kre2[..., 0::2] ** 2 + ref_kre2[..., 1::2] ** 2), 2, axis=-1)
+                oracle2 = {"encode_s": round(t1 - t0, 3), "reencode_s": round(t2 - t1 - 0.0, 3), "final_s": round(t3 - t2, 3),
+                           "cores": oracle.num_threads(), "sample": "every row of all three steps",
+                           "parity": {"encode": parity_figures(to64(o2), ref_o2),
+                                      "reencode_max_err_over_pair_norm": float((np.abs(f(kre_bits) - ref_kre2) / np.maximum(nrm2, 1e-30)).max()),
+                                      "final": parity_figures(to64(of2), ref_of2)}}
             rows_out["cfg2_three_steps"] = {"encode_us": round(ms_e2 * 1e3, 1), "reencode_us": round(ms_r2 * 1e3, 1),
                                             "final_us": round(ms_f2 * 1e3, 1), "all_three_us": round(ms_a2 * 1e3, 1),
+                                            "oracle": oracle2,
                                             "note": "calls issued back to back from Python; latency-bound, no roofline claim"}
             del q2, k2, v2, o2, kl2, kre2, qf2, kf2, vf2, of2, ws_e2, ws_f2
         # whole prompts in one call: config 3's eight prompts with their query blocks appended

@@ -1046,7 +1046,6 @@ def test_whole_prompts_config_3_sampled(ba):
 # oracle's masked_attention_backward_term_sums) instead of the tensor's largest entry.
 GRAD_MAX_TOL = 2e-2
 GRAD_MEAN_TOL = 2e-3
-_grad_ratios = []
 
 
 def assert_grad_close(got, ref, mag, what):
@@ -1054,7 +1053,6 @@ def assert_grad_close(got, ref, mag, what):
     err = np.abs(got - ref) / scale
     assert np.isfinite(got).all(), f"{what}: non-finite gradient"
     i = int(np.argmax(err))
-    _grad_ratios.append((float(err.max()), float(err.mean()), what))
     assert float(err.max()) <= GRAD_MAX_TOL, (f"{what}: err {np.abs(got - ref).flat[i]:.4g} on an entry of {ref.flat[i]:.4g} "
                                               f"whose terms add up to {mag.flat[i]:.4g} in absolute value")
     assert float(err.mean()) <= GRAD_MEAN_TOL, f"{what}: mean scaled err {err.mean():.4g}"
@@ -1064,15 +1062,6 @@ def oracle_grads(q, k, v, do, offs, th, layout=0):
     """(dq, dk, dv) and the per-element sums of absolute terms they are compared against."""
     rq, rk, rv, _ = oracle.masked_attention_backward_bruteforce(q, k, v, do, offs, th, layout=layout)
     return (rq, rk, rv), oracle.masked_attention_backward_term_sums(q, k, v, do, offs, th, layout=layout)
-
-
-def test_zz_report_gradient_error_ratios():
-    """(not a check: prints the largest scaled gradient errors the tests above saw, next to the bounds)"""
-    if _grad_ratios:
-        mx = max(_grad_ratios)
-        mn = max(_grad_ratios, key=lambda r: r[1])
-        print(f"\nlargest scaled gradient error {mx[0]:.3e} ({mx[2]}), bound {GRAD_MAX_TOL}; "
-              f"largest mean {mn[1]:.3e} ({mn[2]}), bound {GRAD_MEAN_TOL}")
 
 
 @pytest.mark.parametrize("case", PROMPT_CASES, ids=[c[0] for c in PROMPT_CASES])
