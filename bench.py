@@ -80,6 +80,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows (config 3/4, single block)")
+    ap.add_argument("--equal-splits", action="store_true",
+                    help="skip the XCD speed calibration: KV splits of equal size")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for HBM byte counters")
     ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3|final3|query50|cfg2|prompts|smallblocks|cached")
@@ -147,7 +149,15 @@ def main() -> int:
     hq, hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
     t_ctx, l_q = w.prompts[0].t_ctx, w.prompts[0].final_len
     cu_q, cu_ctx = w.cu_q(), w.cu_ctx()
-    heads = ba.Heads(hq, hkv, d, w.rope_base)
+    # one-time calibration, as a serving process would do at start-up: the relative speed of the eight
+    # XCDs under the attention core's load; the final-block planner sizes its KV splits by it
+    xcd_speed = None
+    if not args.equal_splits:
+        ws_probe = torch.empty(ba.ba_measure_xcd_speed_workspace_bytes(), dtype=torch.uint8, device=dev)
+        xcd_speed = ba.ba_measure_xcd_speed(ws_probe)
+        del ws_probe
+        torch.cuda.empty_cache()
+    heads = ba.Heads(hq, hkv, d, w.rope_base, xcd_speed=xcd_speed)
     layers = []
     host0 = None
     for layer in range(w.n_layers):
@@ -678,7 +688,9 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "layers": w.n_layers, "context_blocks": 31, "block_len": 1024,
                    "final_len": l_q, "total_tokens": t_ctx + l_q, "n_q_heads": hq, "n_kv_heads": hkv, "head_dim": d,
-                   "rope": "applied to q_f/k_f inside the call", "flops_per_layer": flops_layer},
+                   "rope": "applied to q_f/k_f inside the call", "flops_per_layer": flops_layer,
+                   "kv_splits": "sized by measured XCD speed" if xcd_speed else "equal",
+                   "xcd_speed": None if not xcd_speed else [round(x, 4) for x in xcd_speed]},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "rows": rows_out,

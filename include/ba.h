@@ -74,6 +74,13 @@ typedef struct ba_heads {
   double rope_base;       /* theta_j = rope_base^(-2j/head_dim) (Eq. 1's theta_j)       */
   const double *inv_freq; /* host, nullable: head_dim/2 overrides of theta_j            */
   int32_t rope_layout;    /* BA_ROPE_INTERLEAVED or BA_ROPE_HALF                        */
+  const float *xcd_speed; /* host, nullable: relative speed of the device's 8 XCDs under the
+                             attention core's load, from ba_measure_xcd_speed().  The final-block
+                             calls then size their KV splits by the speed of the XCD each one
+                             runs on (the XCDs of one MI355X sustain clocks several per cent
+                             apart, and a launch ends with its slowest workgroup).  Changes which
+                             keys a split covers, hence low-order bits of the result, never the
+                             workspace size.  null = equal splits.                             */
 } ba_heads;
 
 /* Library version (major * 10000 + minor * 100 + patch). */
@@ -82,6 +89,19 @@ int32_t ba_version(void);
 const char *ba_status_string(int32_t status);
 /* Thread-local text describing the last non-OK status returned on this thread. */
 const char *ba_last_error(void);
+
+/*
+ * Relative speed of the eight XCDs of the current device under the attention core's load, for
+ * ba_heads.xcd_speed (Section 2.5's step is the one whose launch ends with its slowest workgroup).
+ * Runs the final-block attention core a few times on synthetic keys in the workspace (one workgroup
+ * per compute unit, each timing its walk with the shader-clock and real-time counters), waits for
+ * the stream, and writes eight numbers with mean 1 (each XCD's sustained clock over the mean).  If
+ * the device does not deal workgroups to XCDs round-robin as the planner assumes, all eight are 1.
+ * ws: 256-byte aligned, at least ba_measure_xcd_speed_workspace_bytes() bytes (about 150 MB).
+ * Synchronises the stream; a one-time calibration, not a hot-path call.
+ */
+int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_bytes, void *stream);
+size_t ba_measure_xcd_speed_workspace_bytes(void);
 
 /*
  * Per-kernel timing for benchmarks.  Between ba_profile_begin() and ba_profile_end() every

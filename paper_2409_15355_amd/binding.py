@@ -30,7 +30,8 @@ EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin"
            "ba_final_block_attention_cached", "ba_final_block_attention_cached_workspace_bytes",
            "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes",
            "ba_block_attention_prompts_backward", "ba_block_attention_prompts_backward_workspace_bytes",
-           "ba_schedule_final_block", "ba_schedule_encode_blocks", "ba_schedule_prompts"]
+           "ba_schedule_final_block", "ba_schedule_encode_blocks", "ba_schedule_prompts",
+           "ba_measure_xcd_speed", "ba_measure_xcd_speed_workspace_bytes"]
 
 
 class BaTensor(ctypes.Structure):
@@ -42,7 +43,8 @@ class BaHeads(ctypes.Structure):
     _fields_ = [("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("q_to_kv", ctypes.POINTER(ctypes.c_int32)),
                 ("softmax_scale", ctypes.c_float), ("rope_base", ctypes.c_double),
-                ("inv_freq", ctypes.POINTER(ctypes.c_double)), ("rope_layout", ctypes.c_int32)]
+                ("inv_freq", ctypes.POINTER(ctypes.c_double)), ("rope_layout", ctypes.c_int32),
+                ("xcd_speed", ctypes.POINTER(ctypes.c_float))]
 
 
 class BaWorkItem(ctypes.Structure):
@@ -128,6 +130,10 @@ def load():
     lib.ba_schedule_encode_blocks.argtypes = [_HP, ctypes.c_int32, _I32P, _WP, ctypes.c_int64]
     lib.ba_schedule_prompts.restype = ctypes.c_int64
     lib.ba_schedule_prompts.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, _WP, ctypes.c_int64]
+    lib.ba_measure_xcd_speed.restype = ctypes.c_int32
+    lib.ba_measure_xcd_speed.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.ba_measure_xcd_speed_workspace_bytes.restype = ctypes.c_size_t
+    lib.ba_measure_xcd_speed_workspace_bytes.argtypes = []
     _lib = lib
     return lib
 
@@ -143,14 +149,19 @@ class Heads:
 
     def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, rope_base: float = 10000.0,
                  rope_layout: int = ROPE_INTERLEAVED, softmax_scale: float = 0.0,
-                 q_to_kv: Optional[Sequence[int]] = None, inv_freq: Optional[Sequence[float]] = None):
+                 q_to_kv: Optional[Sequence[int]] = None, inv_freq: Optional[Sequence[float]] = None,
+                 xcd_speed: Optional[Sequence[float]] = None):
         self._q_to_kv = None if q_to_kv is None else np.ascontiguousarray(q_to_kv, dtype=np.int32)
         self._inv_freq = None if inv_freq is None else np.ascontiguousarray(inv_freq, dtype=np.float64)
+        self._xcd_speed = None if xcd_speed is None else np.ascontiguousarray(xcd_speed, dtype=np.float32)
+        if self._xcd_speed is not None and self._xcd_speed.shape != (8,):
+            raise ValueError("xcd_speed: eight numbers, one per XCD")
         self.c = BaHeads(n_q_heads, n_kv_heads, head_dim,
                          None if self._q_to_kv is None else self._q_to_kv.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
                          float(softmax_scale), float(rope_base),
                          None if self._inv_freq is None else self._inv_freq.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
-                         rope_layout)
+                         rope_layout,
+                         None if self._xcd_speed is None else self._xcd_speed.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
         self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
 
 
@@ -463,3 +474,15 @@ def ba_schedule_encode_blocks(heads: Heads, block_offsets):
 def ba_schedule_prompts(heads: Heads, cu_blk, block_offsets):
     cb, offs = _ints(cu_blk), _ints(block_offsets)
     return _schedule(load().ba_schedule_prompts, ctypes.byref(heads.c), len(cb) - 1, _ip(cb), _ip(offs))
+
+
+def ba_measure_xcd_speed_workspace_bytes() -> int:
+    return int(load().ba_measure_xcd_speed_workspace_bytes())
+
+
+def ba_measure_xcd_speed(ws, stream=None):
+    """Eight relative XCD speeds (mean 1) for Heads(xcd_speed=...); synchronises the stream."""
+    out = (ctypes.c_float * 8)()
+    wp, wb = _ws(ws)
+    _check(load().ba_measure_xcd_speed(out, wp, wb, _stream_handle(stream)))
+    return [float(x) for x in out]

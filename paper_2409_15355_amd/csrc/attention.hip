@@ -130,8 +130,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     // Consecutive work items share K/V tiles (same KV head and split, different row tile);
     // the dispatcher deals workgroup ids round-robin to the XCDs, so regroup ids such that
     // each XCD (and its L2) gets a contiguous run of work items.
-    const uint32_t n_wg = gridDim.x, q = n_wg / kXcds, r = n_wg % kXcds, x = id % kXcds;
-    id = x * q + min(x, r) + id / kXcds;
+    id = work_item_of_workgroup(id, gridDim.x);
   }
   const uint32_t n_rowtiles = (uint32_t)p.total_tiles;
   const uint32_t id_hi = id / n_rowtiles, id_lo = id - id_hi * n_rowtiles;
@@ -147,6 +146,15 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const int Gq = p.group;
   const int n_rows = pr.lq * Gq;
   const int row0 = pr.jt * kTileRows;
+  // Speed probe (ba_measure_xcd_speed): which XCD this workgroup runs on, and its shader-clock and
+  // real-time (100 MHz) counters here and behind the walk; their ratio is the XCD's clock under this load.
+  constexpr bool kProbe = std::is_same<Meta, FinalMeta>::value;
+  if (kProbe && p.wg_clock && threadIdx.x == 0) {
+    unsigned long long *rec = p.wg_clock + (size_t)blockIdx.x * 8;
+    rec[0] = (unsigned long long)(__builtin_amdgcn_s_getreg(6164) & 15);  // HW_REG_XCC_ID, bits 3:0
+    rec[1] = (unsigned long long)clock64();
+    rec[2] = (unsigned long long)wall_clock64();
+  }
 
   // ---- key tiles this work item walks ---------------------------------------------------
   // The key range is a list of segments: fully visible context segments first (one for a
@@ -158,7 +166,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const int last_tok = (int)fast_div((uint32_t)last_row, p.group_div);
   const int n_causal_tiles = causal_key_tiles(last_tok, kTileKeys);
   // this split's share of the walk (the arithmetic is the host planner's: one definition)
-  const TileRange tr = split_tile_range(n_ctx_tiles, n_causal_tiles, p.n_splits, split);
+  const TileRange tr = split_tile_range(n_ctx_tiles, n_causal_tiles, p.n_splits, split, p.use_cuts ? p.split_cut : nullptr);
   const int t_begin = tr.begin, t_end = tr.end;
   const int n_t = t_end - t_begin;
 
@@ -709,6 +717,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     for (; i < n_t; ++i) iteration(std::false_type{}, i);
   }
   static_assert(kNumKBuf == 4 && kNumVBuf == 4, "the copy distances above assume four buffers of each kind");
+  if (kProbe && p.wg_clock && threadIdx.x == 0) {
+    unsigned long long *rec = p.wg_clock + (size_t)blockIdx.x * 8;
+    rec[4] = (unsigned long long)clock64();
+    rec[5] = (unsigned long long)wall_clock64();
+  }
 
   // ---- epilogue -----------------------------------------------------------------------------------
   KParams kp = kBlocks ? args_again() : nullptr;

@@ -244,6 +244,9 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
 }
 
 
+// set by ba_measure_xcd_speed around its own final-block calls: where the workgroups leave their clock readings
+thread_local unsigned long long *g_probe_clock = nullptr;
+
 // ---- fewer than four query heads per KV head in the whole-prompt calls: run as groups of four --------
 constexpr int kPadGroup = 4;
 
@@ -1027,6 +1030,7 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
   ap.q_ready = rope_mode == BA_ROPE_APPLY;
   ap.rope_layout = heads->rope_layout;
   ap.n_splits = pl.n_splits;
+  ap.wg_clock = g_probe_clock;  // (null unless ba_measure_xcd_speed is the caller)
 
   int64_t tile_base = 0;  // row tiles of the launches so far: the split partials are indexed by row tile
   for (int n0 = 0; n0 < n_prompts; n0 += ba::kFinMaxPrompts) {
@@ -1036,6 +1040,8 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
     ap.tile_base = (int32_t)tile_base;
     tile_base += tiles;
     ap.total_tiles = (int32_t)tiles;
+    if ((rc = ba::plan_split_cuts(heads->xcd_speed, tiles, heads->n_kv_heads, pl.n_splits, ap.split_cut, &ap.use_cuts)))
+      return rc;
     if (rope_mode == BA_ROPE_APPLY) {  // absolute positions of the final block's tokens
       if ((rc = run_rope_prepass(heads, rt, q_f, q_ws, k_f, &kf_use, n, meta.cu_q, pos0.data() + n0, stream)))
         return rc;
@@ -1180,6 +1186,10 @@ int32_t run_final_blocks(const BlocksCall &c, ba::AttnParams ap) {
     ap.total_tiles = (int32_t)tiles;
     ap.tile_base = (int32_t)tile_base;
     tile_base += tiles;
+    {
+      int32_t rc_cuts = ba::plan_split_cuts(c.heads->xcd_speed, tiles, c.heads->n_kv_heads, ap.n_splits, ap.split_cut, &ap.use_cuts);
+      if (rc_cuts) return rc_cuts;
+    }
     const ba::RopeRots *big = nullptr;
     const ba::RopeRotsSmall *small = nullptr;
     if constexpr (std::is_same<RotsT, ba::RopeRots>::value) big = &rr; else small = &rr;
@@ -1397,3 +1407,108 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
 }
 
 }  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+// Calibration: relative XCD speeds under the attention core's load (ba_heads.xcd_speed).
+namespace {
+constexpr int kProbeCtx = 31744, kProbeLq = 256, kProbeHq = 32, kProbeHkv = 8, kProbeD = 128, kProbeRuns = 4;
+constexpr int kProbeMaxWg = 4096;
+ba_heads probe_heads() {
+  ba_heads h;
+  memset(&h, 0, sizeof(h));
+  h.n_q_heads = kProbeHq;
+  h.n_kv_heads = kProbeHkv;
+  h.head_dim = kProbeD;
+  h.rope_base = 500000.0;
+  h.rope_layout = BA_ROPE_INTERLEAVED;
+  return h;
+}
+struct ProbeLayout {
+  size_t kv_bytes, q_bytes, kvf_bytes, clock_bytes, final_bytes;
+  size_t total() const { return 2 * kv_bytes + 2 * q_bytes + 2 * kvf_bytes + clock_bytes + final_bytes; }
+};
+ProbeLayout probe_layout() {
+  ProbeLayout l;
+  l.kv_bytes = align256((size_t)kProbeCtx * kProbeHkv * kProbeD * 2);
+  l.q_bytes = align256((size_t)kProbeLq * kProbeHq * kProbeD * 2);
+  l.kvf_bytes = align256((size_t)kProbeLq * kProbeHkv * kProbeD * 2);
+  l.clock_bytes = align256((size_t)kProbeMaxWg * 8 * sizeof(unsigned long long));
+  const ba_heads h = probe_heads();
+  const int32_t cu_q[2] = {0, kProbeLq}, cu_ctx[2] = {0, kProbeCtx};
+  l.final_bytes = align256(ba_final_block_attention_workspace_bytes(&h, 1, cu_q, cu_ctx, BA_ROPE_NONE, 0));
+  return l;
+}
+}  // namespace
+
+extern "C" size_t ba_measure_xcd_speed_workspace_bytes(void) { return probe_layout().total(); }
+
+extern "C" int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_bytes, void *stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (!speed_out) return fail(BA_ERR_INVALID_ARG, "speed_out: null");
+  for (int x = 0; x < ba::kNumXcds; ++x) speed_out[x] = 1.0f;
+  const ProbeLayout l = probe_layout();
+  if (!ws || ws_bytes < l.total() || ((uintptr_t)ws & 255))
+    return fail(BA_ERR_WORKSPACE, "XCD speed probe: 256-byte aligned workspace of %zu bytes needed, %zu given", l.total(),
+                ws_bytes);
+  char *wp = (char *)ws;
+  const ba_heads h = probe_heads();
+  auto tensor = [&](size_t bytes, int heads_n) {
+    ba_tensor t;
+    t.ptr = wp;
+    t.stride_head = kProbeD;
+    t.stride_tok = (int64_t)heads_n * kProbeD;
+    t.dtype = BA_DTYPE_BF16;
+    wp += bytes;
+    return t;
+  };
+  const ba_tensor kc = tensor(l.kv_bytes, kProbeHkv), vc = tensor(l.kv_bytes, kProbeHkv);
+  const ba_tensor q = tensor(l.q_bytes, kProbeHq), o = tensor(l.q_bytes, kProbeHq);
+  const ba_tensor kf = tensor(l.kvf_bytes, kProbeHkv), vf = tensor(l.kvf_bytes, kProbeHkv);
+  unsigned long long *clk = (unsigned long long *)wp;
+  wp += l.clock_bytes;
+  // keys, values and queries with the bit activity of real data (the clock a part sustains depends on it)
+  hipError_t e = ba::launch_fill_random_bf16((uint16_t *)kc.ptr, (2 * l.kv_bytes + l.q_bytes) / 2, 0x9e3779b9u, stream);
+  if (e == hipSuccess)
+    e = ba::launch_fill_random_bf16((uint16_t *)kf.ptr, 2 * l.kvf_bytes / 2, 0x85ebca6bu, stream);
+  if (e == hipSuccess) e = hipMemsetAsync(clk, 0, l.clock_bytes, stream);
+  if (e != hipSuccess) return device_fail(e, "XCD speed probe: fill");
+  const int32_t cu_q[2] = {0, kProbeLq}, cu_ctx[2] = {0, kProbeCtx};
+  int32_t rc = BA_OK;
+  g_probe_clock = clk;
+  for (int run = 0; run < kProbeRuns && rc == BA_OK; ++run)  // (the later runs are at the steady clock; the last one's readings stay)
+    rc = ba_final_block_attention(&h, &q, &kc, &vc, &kf, &vf, &o, nullptr, 1, cu_q, cu_ctx, nullptr, BA_ROPE_NONE, wp,
+                                  l.final_bytes, stream_);
+  g_probe_clock = nullptr;
+  if (rc) return rc;
+  ba::FinalPlan pl;
+  if ((rc = ba::plan_final(&h, 1, cu_q, cu_ctx, BA_ROPE_NONE, false, num_cus(), &pl))) return rc;
+  const int64_t n_wg = pl.total_tiles * kProbeHkv * pl.n_splits;
+  if (n_wg < ba::kNumXcds || n_wg > kProbeMaxWg) return BA_OK;  // nothing to learn from such a launch: equal speeds
+  std::vector<unsigned long long> rec((size_t)n_wg * 8);
+  if ((e = hipStreamSynchronize(stream)) != hipSuccess) return device_fail(e, "XCD speed probe: synchronize");
+  if ((e = hipMemcpy(rec.data(), clk, rec.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost)) != hipSuccess)
+    return device_fail(e, "XCD speed probe: read-back");
+  double sum[ba::kNumXcds] = {0}, total = 0.0;
+  int cnt[ba::kNumXcds] = {0};
+  for (int64_t wg = 0; wg < n_wg; ++wg) {
+    const unsigned long long *r = &rec[(size_t)wg * 8];
+    const int x = ba::xcd_of_workgroup((unsigned)wg);
+    if ((int)r[0] != x || r[5] <= r[2] || r[4] <= r[1]) return BA_OK;  // not the mapping the planner assumes: equal speeds
+    sum[x] += (double)(r[4] - r[1]) / (double)(r[5] - r[2]);  // shader cycles per 10 ns
+    ++cnt[x];
+  }
+  for (int x = 0; x < ba::kNumXcds; ++x) {
+    if (!cnt[x]) return BA_OK;
+    sum[x] /= cnt[x];
+    total += sum[x];
+  }
+  for (int x = 0; x < ba::kNumXcds; ++x) {
+    const double s = sum[x] * ba::kNumXcds / total;
+    if (!(s >= 0.5 && s <= 2.0)) {
+      for (int y = 0; y < ba::kNumXcds; ++y) speed_out[y] = 1.0f;
+      return BA_OK;
+    }
+    speed_out[x] = (float)s;
+  }
+  return BA_OK;
+}

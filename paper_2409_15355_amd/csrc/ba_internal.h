@@ -152,6 +152,9 @@ struct AttnParams {
   int32_t rope_layout;
   const float *blk_rot;  // block table only: [blocks][D/2][2] (cos, sin) of minus each block's shift
   int32_t n_splits;
+  int32_t use_cuts;            // split_cut holds unequal shares (see split_tile_range)
+  uint32_t split_cut[33];      // cumulative shares of the splits, 1 / 65536 units
+  unsigned long long *wg_clock;  // speed probe only, else null: per workgroup (XCC id, shader cycles, 100 MHz ticks, 0)
   int32_t total_tiles;  // row tiles over all problems of this launch
   FastDiv tiles_div;    // division by total_tiles (short-block schedule)
   float *lse;           // short-block schedule: [tokens][n_q_heads] log-sum-exp of the scaled scores, or null
@@ -245,6 +248,9 @@ hipError_t launch_pad_heads(const HeadPadParams &p, bool to_padded, hipStream_t 
 // the same for [tokens][heads] floats (real: packed [tokens][n_kv_heads * group])
 hipError_t launch_pad_lse(float *real, float *padded, int64_t tokens, int n_kv_heads, int group, int group_padded,
                           bool to_padded, hipStream_t stream);
+
+// n pseudo-random bf16 values (synthetic operands of the XCD speed probe)
+hipError_t launch_fill_random_bf16(uint16_t *dst, int64_t n, uint32_t seed, hipStream_t stream);
 
 hipError_t launch_attn_encode(const AttnParams &p, const EncodeMeta &meta, hipStream_t stream);
 // the same for short blocks: meta.tile_start counts row tiles of kShortTileRows rows

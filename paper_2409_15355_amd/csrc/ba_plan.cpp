@@ -115,6 +115,40 @@ int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, co
   return BA_OK;
 }
 
+int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, uint32_t cuts[33],
+                        int32_t *use) {
+  *use = 0;
+  for (int s = 0; s <= kMaxSplits; ++s) cuts[s] = 0;
+  if (!xcd_speed || n_splits <= 1 || tiles <= 0) return BA_OK;
+  if (n_splits > kMaxSplits) return fail(BA_ERR_INVALID_ARG, "more than %d splits", kMaxSplits);
+  for (int x = 0; x < kNumXcds; ++x)
+    if (!(xcd_speed[x] >= 0.5f && xcd_speed[x] <= 2.0f))
+      return fail(BA_ERR_INVALID_ARG, "xcd_speed[%d] = %g: relative speeds lie between 0.5 and 2", x, (double)xcd_speed[x]);
+  // XCD x runs the work items [lo_x, hi_x) (see work_item_of_workgroup); split s is the items
+  // [s m, (s + 1) m), m = tiles * n_kv_heads.  A split's speed = the mean speed over its items.
+  const int64_t m = tiles * n_kv_heads, n_wg = m * n_splits;
+  const int64_t q = n_wg / kNumXcds, r = n_wg % kNumXcds;
+  double w[kMaxSplits], total = 0.0;
+  for (int s = 0; s < n_splits; ++s) {
+    double sum = 0.0;
+    for (int x = 0; x < kNumXcds; ++x) {
+      const int64_t lo = x * q + std::min<int64_t>(x, r), hi = (x + 1) * q + std::min<int64_t>(x + 1, r);
+      const int64_t a = std::max<int64_t>(lo, s * m), b = std::min<int64_t>(hi, (s + 1) * m);
+      if (b > a) sum += (double)(b - a) * xcd_speed[x];
+    }
+    w[s] = sum / (double)m;
+    total += w[s];
+  }
+  double acc = 0.0;
+  for (int s = 0; s < n_splits; ++s) {
+    cuts[s] = (uint32_t)(acc / total * 65536.0 + 0.5);
+    acc += w[s];
+  }
+  for (int s = n_splits; s <= kMaxSplits; ++s) cuts[s] = 65536;
+  *use = 1;
+  return BA_OK;
+}
+
 int64_t build_final_meta(const int32_t *cu_q, const int32_t *cu_ctx, int n0, int n, int G, FinalMeta *meta) {
   memset(meta, 0, sizeof(*meta));
   meta->n = n;
@@ -314,6 +348,9 @@ int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const 
     const int n = std::min(ba::kFinMaxPrompts, n_prompts - n0);
     ba::FinalMeta meta;
     const int64_t tiles = ba::build_final_meta(cu_q, cu_ctx, n0, n, G, &meta);
+    uint32_t cuts[33];
+    int32_t use_cuts = 0;
+    if ((rc = ba::plan_split_cuts(heads->xcd_speed, tiles, heads->n_kv_heads, pl.n_splits, cuts, &use_cuts))) return rc;
     // the kernel's own walk: every (split, row tile) of the launch, once per KV head
     for (int split = 0; split < pl.n_splits; ++split)
       for (int64_t tile = 0; tile < tiles; ++tile) {
@@ -324,7 +361,7 @@ int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const 
         const int last_row = std::min(n_rows, row0 + ba::kTileRows) - 1;
         const int n_ctx_tiles = (tctx + ba::kTileKeys - 1) / ba::kTileKeys;
         const int n_causal = ba::causal_key_tiles(last_row / G, ba::kTileKeys);
-        const ba::TileRange tr = ba::split_tile_range(n_ctx_tiles, n_causal, pl.n_splits, split);
+        const ba::TileRange tr = ba::split_tile_range(n_ctx_tiles, n_causal, pl.n_splits, split, use_cuts ? cuts : nullptr);
         ba_work_item w;
         memset(&w, 0, sizeof(w));
         w.launch = launch;

@@ -64,6 +64,21 @@ __global__ __launch_bounds__(kPadThreads) void pad_lse_kernel(float *real, float
   }
 }
 
+// Pseudo-random bf16 values of magnitude 1/8 .. 2 with random signs and mantissas (a hash of the
+// element index): synthetic operands for the speed probe.
+__global__ __launch_bounds__(kPadThreads) void fill_random_bf16_kernel(uint16_t *dst, int64_t n, uint32_t seed) {
+  for (int64_t i = (int64_t)blockIdx.x * kPadThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kPadThreads) {
+    uint32_t h = (uint32_t)i * 0x9e3779b1u + seed;
+    h ^= h >> 16;
+    h *= 0x7feb352du;
+    h ^= h >> 15;
+    h *= 0x846ca68bu;
+    h ^= h >> 16;
+    const uint32_t sign = (h >> 31) << 15, expo = (124u + ((h >> 8) & 3u)) << 7, mant = h & 0x7fu;
+    dst[i] = (uint16_t)(sign | expo | mant);
+  }
+}
+
 unsigned grid_for(int64_t n) {
   const int64_t wg = (n + kPadThreads - 1) / kPadThreads;
   return (unsigned)(wg < 1 ? 1 : (wg > 8192 ? 8192 : wg));
@@ -78,6 +93,12 @@ hipError_t launch_pad_heads(const HeadPadParams &p, bool to_padded, hipStream_t 
     hipLaunchKernelGGL(pad_heads_kernel, dim3(grid_for(n)), dim3(kPadThreads), 0, stream, p);
   else
     hipLaunchKernelGGL(unpad_heads_kernel, dim3(grid_for(n)), dim3(kPadThreads), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_random_bf16(uint16_t *dst, int64_t n, uint32_t seed, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_random_bf16_kernel, dim3(grid_for(n)), dim3(kPadThreads), 0, stream, dst, n, seed);
   return hipGetLastError();
 }
 

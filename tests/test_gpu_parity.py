@@ -1496,3 +1496,30 @@ def test_drawn_reencode_cases_match_the_oracle(ba, seed):
             ba.ba_reencode_positions(heads, src, dst, src_off, dst_off, lens, old, new, mode)
             torch.cuda.synchronize()
             assert_reencode_bf16(host_bits(dst), ref, layout, tag)
+
+
+def test_final_block_with_splits_sized_by_xcd_speed(ba):
+    """ba_heads.xcd_speed: unequal KV splits (here with strongly skewed speeds, so that every split
+    boundary moves) give the oracle's result like the equal ones; and the probe that measures the
+    speeds returns eight numbers with mean 1 that lie within what XCD clocks differ by."""
+    torch = torch_mod()
+    hq, hkv, d, lq, tc = 8, 2, 128, 70, 9000
+    qb, kfb, vfb = gen_qkv(8100, lq, hq, hkv, d)
+    kcb, vcb = wl.normal_bf16_bits(8103, (tc, hkv, d)), wl.normal_bf16_bits(8104, (tc, hkv, d))
+    cu_q, cu_ctx = np.array([0, lq], dtype=np.int32), np.array([0, tc], dtype=np.int32)
+    f = oracle.bf16_bits_to_f64
+    ref = oracle.final_block(f(qb), f(kcb), f(vcb), f(kfb), f(vfb), cu_q, cu_ctx, oracle.theta(500000.0, d))
+    outs = []
+    for speeds in (None, [0.6, 1.9, 0.8, 1.2, 0.5, 2.0, 1.0, 1.0], [1.03, 0.97, 1.0, 1.0, 1.02, 0.98, 1.01, 0.99]):
+        heads = ba.Heads(hq, hkv, d, 500000.0, xcd_speed=speeds)
+        o = gpu_final(ba, heads, dev_bf16(qb), dev_bf16(kcb), dev_bf16(vcb), dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
+        assert_attention_close(host_f64(o), ref, f"speeds {speeds}")
+        outs.append(host_bits(o))
+    assert len(ba.ba_schedule_final_block(ba.Heads(hq, hkv, d), cu_q, cu_ctx)) > 2  # (several splits, or the test is idle)
+    ws = torch.empty(ba.ba_measure_xcd_speed_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    sp = ba.ba_measure_xcd_speed(ws)
+    assert len(sp) == 8 and abs(sum(sp) / 8 - 1.0) < 1e-3 and all(0.8 < x < 1.25 for x in sp), sp
+    # measured speeds are accepted as they come
+    heads = ba.Heads(hq, hkv, d, 500000.0, xcd_speed=sp)
+    o = gpu_final(ba, heads, dev_bf16(qb), dev_bf16(kcb), dev_bf16(vcb), dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
+    assert_attention_close(host_f64(o), ref, "measured speeds")

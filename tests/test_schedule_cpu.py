@@ -185,3 +185,44 @@ def test_split_range_arithmetic_partitions_every_walk():
                             at_self = w.self_end
                     assert at_ctx == tc and at_self == min(lq, ((ws[0].row_end - 1) // 64 + 1) * 64)  # (one head per group: row = token)
     assert len(seen_splits) >= 6 and max(seen_splits) >= 16
+
+
+@pytest.mark.parametrize("speeds", [[1.0] * 8, [0.92, 1.0, 1.08, 1.0, 0.95, 1.05, 1.0, 1.0], [0.5, 2.0, 0.5, 2.0, 1.0, 1.0, 1.0, 1.0]])
+def test_splits_sized_by_xcd_speed_still_cover_the_mask_exactly(speeds):
+    """ba_heads.xcd_speed moves the boundaries between KV splits (faster XCDs get more key tiles); the
+    work items must still cover every visible pair exactly once."""
+    rng = np.random.default_rng(5)
+    h = ba.Heads(32, 8, 128, 500000.0, xcd_speed=speeds)
+    for case in range(6):
+        n_prompts = int(rng.integers(1, 4))
+        lqs = [int(rng.choice([1, 64, 130, 256])) for _ in range(n_prompts)]
+        tcs = [int(rng.choice([0, 700, 3001, 9000, 31744])) for _ in range(n_prompts)]
+        if case == 0:
+            n_prompts, lqs, tcs = 1, [256], [31744]
+        cu_q, cu_ctx = np.concatenate([[0], np.cumsum(lqs)]), np.concatenate([[0], np.cumsum(tcs)])
+        items = ba.ba_schedule_final_block(h, cu_q, cu_ctx, 256)
+        cov = coverage_of(items, 4, {p: (tcs[p], lqs[p]) for p in range(n_prompts)})
+        for p in range(n_prompts):
+            assert np.array_equal(cov[p], expected_final(tcs[p], lqs[p], 4)), (case, p, lqs, tcs)
+        if case == 0:
+            # config 5: split s runs on XCD s; its share of the key tiles follows that XCD's speed
+            tiles = [sum(w.ctx_end - w.ctx_begin + w.self_end - w.self_begin for w in items if w.split == s and w.row_begin == 0) // 64
+                     for s in range(8)]
+            if len(set(speeds)) == 1:
+                assert max(tiles[:7]) - min(tiles[:7]) <= 1
+            else:
+                order = np.argsort(speeds[:7])
+                assert tiles[order[0]] < tiles[order[-1]]
+                share = np.array(tiles[:7], dtype=float) / np.array(speeds[:7])
+                assert share.max() / share.min() < 1.06   # equal time per split, to a tile
+
+
+def test_bad_xcd_speeds_are_rejected():
+    h = ba.Heads(32, 8, 128, 500000.0, xcd_speed=[1, 1, 1, 0.1, 1, 1, 1, 1])
+    with pytest.raises(ba.BaError):
+        ba.ba_schedule_final_block(h, [0, 256], [0, 31744], 256)
+    h = ba.Heads(32, 8, 128, 500000.0, xcd_speed=[1, 1, 1, float("nan"), 1, 1, 1, 1])
+    with pytest.raises(ba.BaError):
+        ba.ba_schedule_final_block(h, [0, 256], [0, 31744], 256)
+    with pytest.raises(ValueError):
+        ba.Heads(32, 8, 128, xcd_speed=[1.0] * 7)
