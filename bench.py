@@ -233,6 +233,21 @@ def main() -> int:
                     "rope_final_block_keys": round(prof_ms[ba.PROFILE_REENCODE] / max(prof_n[ba.PROFILE_REENCODE], 1) * 1e3, 2),
                     "split_combine": round(prof_ms[ba.PROFILE_COMBINE] / max(prof_n[ba.PROFILE_COMBINE], 1) * 1e3, 2)}}
 
+    # ------------------------------------------------------------------ what an MFMA loop sustains here
+    # (the library's diagnostic: random bf16 operands, 8 waves per compute unit, with and without an
+    # operand fragment from LDS per MFMA; the attention core reads one per MFMA)
+    mfma_ceiling = None
+    if args.only == "":
+        mfma_ceiling = {}
+        for name, reads in (("registers_only", 0), ("one_lds_fragment_per_two_mfma", 1), ("one_lds_fragment_per_mfma", 2)):
+            r = ba.ba_diag_mfma_ceiling(reads)
+            mfma_ceiling[name] = {"TFLOPs": round(r["TFLOPs"], 1), "clock_GHz": round(r["clock_GHz"], 3),
+                                  "pipe_busy": round(r["pipe_busy"], 3),
+                                  "frac_of_nominal_peak": round(r["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)}
+        roofline["sustained_mfma_loop"] = mfma_ceiling
+        roofline["frac_of_sustained_loop_with_lds_operands"] = round(
+            achieved / max(mfma_ceiling["one_lds_fragment_per_mfma"]["TFLOPs"], 1e-9), 4)
+
     # ------------------------------------------------------------------ cpu baseline (oracle)
     cpu_baseline = None
     if host0 is not None and args.only == "":

@@ -104,6 +104,19 @@ int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_bytes, void
 size_t ba_measure_xcd_speed_workspace_bytes(void);
 
 /*
+ * Diagnostic for benchmarks: the rate of v_mfma_f32_32x32x16_bf16 this device sustains on operands
+ * with the bit activity of real data, 8 waves per compute unit, with 0, 1 or 2 one-KB operand
+ * fragments re-read from LDS per two MFMAs (the attention core reads one per MFMA): the ceiling an
+ * MFMA loop of that shape runs under when the part is power-limited, to set beside the nominal peak.
+ * Runs for a few milliseconds and synchronises the stream.  Writes (each nullable) the TFLOP/s, the
+ * shader clock sustained (GHz) and the fraction of cycles the matrix pipes were busy.
+ * ws: 256-byte aligned, at least ba_diag_mfma_ceiling_workspace_bytes() bytes.
+ */
+int32_t ba_diag_mfma_ceiling(int32_t lds_reads_per_two_mfma, double *tflops, double *clock_ghz,
+                             double *pipe_busy, void *ws, size_t ws_bytes, void *stream);
+size_t ba_diag_mfma_ceiling_workspace_bytes(void);
+
+/*
  * Per-kernel timing for benchmarks.  Between ba_profile_begin() and ba_profile_end() every
  * kernel launch the library makes is bracketed by two HIP events recorded on the launch
  * stream (at most max_records launches per class; later ones go untimed).

@@ -31,7 +31,8 @@ EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin"
            "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes",
            "ba_block_attention_prompts_backward", "ba_block_attention_prompts_backward_workspace_bytes",
            "ba_schedule_final_block", "ba_schedule_encode_blocks", "ba_schedule_prompts",
-           "ba_measure_xcd_speed", "ba_measure_xcd_speed_workspace_bytes"]
+           "ba_measure_xcd_speed", "ba_measure_xcd_speed_workspace_bytes",
+           "ba_diag_mfma_ceiling", "ba_diag_mfma_ceiling_workspace_bytes"]
 
 
 class BaTensor(ctypes.Structure):
@@ -130,6 +131,11 @@ def load():
     lib.ba_schedule_encode_blocks.argtypes = [_HP, ctypes.c_int32, _I32P, _WP, ctypes.c_int64]
     lib.ba_schedule_prompts.restype = ctypes.c_int64
     lib.ba_schedule_prompts.argtypes = [_HP, ctypes.c_int32, _I32P, _I32P, _WP, ctypes.c_int64]
+    lib.ba_diag_mfma_ceiling.restype = ctypes.c_int32
+    lib.ba_diag_mfma_ceiling.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                         ctypes.POINTER(ctypes.c_double), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.ba_diag_mfma_ceiling_workspace_bytes.restype = ctypes.c_size_t
+    lib.ba_diag_mfma_ceiling_workspace_bytes.argtypes = []
     lib.ba_measure_xcd_speed.restype = ctypes.c_int32
     lib.ba_measure_xcd_speed.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.ba_measure_xcd_speed_workspace_bytes.restype = ctypes.c_size_t
@@ -486,3 +492,14 @@ def ba_measure_xcd_speed(ws, stream=None):
     wp, wb = _ws(ws)
     _check(load().ba_measure_xcd_speed(out, wp, wb, _stream_handle(stream)))
     return [float(x) for x in out]
+
+
+def ba_diag_mfma_ceiling(lds_reads_per_two_mfma: int, stream=None) -> dict:
+    """Sustained MFMA rate on data-like operands (see include/ba.h); synchronises the stream."""
+    import torch
+    ws = torch.empty(int(load().ba_diag_mfma_ceiling_workspace_bytes()), dtype=torch.uint8, device="cuda")
+    t, c, b = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    wp, wb = _ws(ws)
+    _check(load().ba_diag_mfma_ceiling(int(lds_reads_per_two_mfma), ctypes.byref(t), ctypes.byref(c), ctypes.byref(b), wp, wb,
+                                       _stream_handle(stream)))
+    return {"TFLOPs": t.value, "clock_GHz": c.value, "pipe_busy": b.value}

@@ -1512,3 +1512,57 @@ extern "C" int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_
   }
   return BA_OK;
 }
+
+// ------------------------------------------------------------------------------------------
+// Diagnostic: the MFMA rate the device sustains on data-like operands (see diag.hip).
+extern "C" size_t ba_diag_mfma_ceiling_workspace_bytes(void) { return align256(ba::diag_mfma_workspace_bytes(num_cus())); }
+
+extern "C" int32_t ba_diag_mfma_ceiling(int32_t lds_reads_per_two_mfma, double *tflops, double *clock_ghz,
+                                        double *pipe_busy, void *ws, size_t ws_bytes, void *stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  if (lds_reads_per_two_mfma < 0 || lds_reads_per_two_mfma > 2)
+    return fail(BA_ERR_INVALID_ARG, "lds_reads_per_two_mfma: 0, 1 or 2");
+  const int n_wg = num_cus(), iters = 6000, runs = 5;
+  const size_t need = ba_diag_mfma_ceiling_workspace_bytes();
+  if (!ws || ws_bytes < need || ((uintptr_t)ws & 255))
+    return fail(BA_ERR_WORKSPACE, "MFMA diagnostic: 256-byte aligned workspace of %zu bytes needed, %zu given", need, ws_bytes);
+  hipEvent_t e0, e1;
+  hipError_t e = hipEventCreate(&e0);
+  if (e != hipSuccess) return device_fail(e, "MFMA diagnostic: event");
+  if ((e = hipEventCreate(&e1)) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    return device_fail(e, "MFMA diagnostic: event");
+  }
+  e = ba::launch_mfma_ceiling(lds_reads_per_two_mfma, n_wg, iters, ws, 1u, stream);  // warm-up
+  if (e == hipSuccess) e = hipEventRecord(e0, stream);
+  for (int r = 0; r < runs && e == hipSuccess; ++r) e = ba::launch_mfma_ceiling(lds_reads_per_two_mfma, n_wg, iters, ws, 7u + r, stream);
+  if (e == hipSuccess) e = hipEventRecord(e1, stream);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  std::vector<unsigned long long> clk((size_t)n_wg * 8 * 2);
+  if (e == hipSuccess) e = hipMemcpy(clk.data(), ws, clk.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return device_fail(e, "MFMA diagnostic");
+  // Per workgroup, the wave that ran longest: the two waves of a SIMD do not share its matrix pipe
+  // evenly (one may issue most of its loop before the other), so a single wave's time understates
+  // how long the pipe was in use.
+  double cyc = 0.0, ticks = 0.0, cyc_longest = 0.0;
+  for (int wg = 0; wg < n_wg; ++wg) {
+    unsigned long long longest = 0;
+    for (int w = 0; w < 8; ++w) {
+      const unsigned long long c = clk[((size_t)wg * 8 + w) * 2];
+      cyc += (double)c;
+      ticks += (double)clk[((size_t)wg * 8 + w) * 2 + 1];
+      longest = std::max(longest, c);
+    }
+    cyc_longest += (double)longest;
+  }
+  const double waves = (double)n_wg * 8, mfma_per_wave = (double)iters * 16;
+  if (tflops) *tflops = runs * waves * mfma_per_wave * 32768.0 / (ms * 1e-3) / 1e12;
+  if (clock_ghz) *clock_ghz = ticks > 0 ? cyc / (10.0 * ticks) : 0.0;
+  // two waves share a SIMD's matrix pipe, an MFMA of this shape occupies it for 32 cycles
+  if (pipe_busy) *pipe_busy = cyc_longest > 0 ? mfma_per_wave * 32.0 * 2.0 / (cyc_longest / n_wg) : 0.0;
+  return BA_OK;
+}

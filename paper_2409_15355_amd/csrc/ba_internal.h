@@ -249,6 +249,11 @@ hipError_t launch_pad_heads(const HeadPadParams &p, bool to_padded, hipStream_t 
 hipError_t launch_pad_lse(float *real, float *padded, int64_t tokens, int n_kv_heads, int group, int group_padded,
                           bool to_padded, hipStream_t stream);
 
+// MFMA rate diagnostic (diag.hip): n_wg workgroups of 8 waves, `iters` x 16 MFMAs each, with
+// reads_per_two (0, 1, 2) LDS fragment reads per two MFMAs; per wave (shader cycles, 100 MHz ticks) into ws
+size_t diag_mfma_workspace_bytes(int n_wg);
+hipError_t launch_mfma_ceiling(int reads_per_two, int n_wg, int iters, void *ws, uint32_t seed, hipStream_t stream);
+
 // n pseudo-random bf16 values (synthetic operands of the XCD speed probe)
 hipError_t launch_fill_random_bf16(uint16_t *dst, int64_t n, uint32_t seed, hipStream_t stream);
 
