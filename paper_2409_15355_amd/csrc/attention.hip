@@ -311,6 +311,20 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
 #pragma unroll
     for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
   float mb = 0.f;      // the row's reference, log2 units
+  // minus the reference in all sixteen registers of an accumulator tuple: what the score accumulators
+  // start from.  Kept (not rebuilt from mb by sixteen moves inside every MFMA block, where each vector
+  // instruction of this wave delays the next MFMA) and rebuilt only when the reference moves.
+  // (not with a block table: that kernel has no sixteen registers to spare and would spill them)
+  constexpr bool kKeepNegmb = !kBlocks;
+  f32x16_t negmb;
+  auto set_negmb = [&]() __attribute__((always_inline)) {
+    if constexpr (kKeepNegmb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) negmb[v] = -mb;
+      asm volatile("" : "+v"(negmb));  // (opaque: or the compiler re-derives the tuple from mb at every use)
+    }
+  };
+  set_negmb();
   float l_run = 0.f;   // this lane's share of the running sum of exponentials
   const int first_tok_wave = (int)fast_div((uint32_t)(row0 + wave * 32), p.group_div);
 
@@ -341,9 +355,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   constexpr int NPV = 4 * G::DT;
   constexpr int NQK = 2 * G::KCH;
   constexpr int NS = NPV + NQK;
-  constexpr int W = 8;
+#ifndef BA_WIN128
+#define BA_WIN128 5
+#endif
+  constexpr int W = D == 128 ? BA_WIN128 : 8;
   static_assert(W - 1 <= NPV, "the window is primed with V fragments only");
-  static_assert(2 * G::IPW <= NPV, "one copy instruction behind every second PV step");
   auto frag_read = [&](int st, uint32_t vofs, uint32_t kofs) __attribute__((always_inline)) {
     return st < NPV ? read_v(vofs, st / G::DT, st % G::DT) : read_k(kofs, st - NPV);
   };
@@ -353,12 +369,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   };
   // (the K fragments are requested whether or not a next tile exists: the buffer is inside LDS
   // either way and without a next tile nothing consumes them)
-  // The wave has issue slots to spare while its MFMAs execute, so the block also carries this
-  // wave's share of a tile copy (prepared by the caller, in the softmax half), one LDS-direct load
-  // behind every second MFMA, and builds the tuple the score accumulators start from.
-  // (copy: whether there is a tile to copy; cp_off: this lane's source offsets for it)
-  auto mfma_block = [&](uint32_t vofs, uint32_t kofs, bool more, bool copy, const CopyJob &cj,
-                        const uint32_t (&cp_off)[G::IPW], const bf16x8_t (&pf)[4], f32x16_t (&sacc)[2],
+  // The block holds nothing but the MFMAs, their fragment reads and the waits between them: a wave
+  // issues an instruction every few cycles at best, an MFMA of this shape leaves room for about three
+  // others before the next one is due, and every instruction beyond that (tile copies, address
+  // arithmetic, the moves that build an accumulator's start value) leaves the matrix pipe idle.
+  auto mfma_block = [&](uint32_t vofs, uint32_t kofs, bool more, const bf16x8_t (&pf)[4], f32x16_t (&sacc)[2],
                         bf16x8_t (&fr)[W]) __attribute__((always_inline)) {
     // the wave in its MFMA block goes first at the issue arbiter; the other wave of the SIMD, in its
     // exponentials, fills the slots between
@@ -368,10 +383,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       if (st + W - 1 < NS) fr[(st + W - 1) % W] = frag_read(st + W - 1, vofs, kofs);
       const int kc = st / G::DT, dt = st % G::DT;
       oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % W], pf[kc], oacc[dt], 0, 0, 0);
-      if ((st & 1) && st / 2 < G::IPW) {
-        const int i = st / 2;
-        if (__builtin_expect(copy, 1)) lds_dma16(cj.ptr, cp_off[i], cj.dst + i * 1024);
-      }
       __builtin_amdgcn_sched_barrier(0);
     }
     if (more) {
@@ -381,10 +392,14 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
         const int q = st - NPV, a = q & 1, kk = q >> 1;
         if (kk == 0) {
           // the accumulator starts at minus the row's reference: the MFMA result is the exponent
-          f32x16_t negmb;
+          f32x16_t start;
+          if constexpr (kKeepNegmb) {
+            start = negmb;
+          } else {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) negmb[v] = -mb;
-          sacc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % W], qf[kk], negmb, 0, 0, 0);
+            for (int v = 0; v < 16; ++v) start[v] = -mb;
+          }
+          sacc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % W], qf[kk], start, 0, 0, 0);
         } else {
           sacc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[st % W], qf[kk], sacc[a], 0, 0, 0);
         }
@@ -423,6 +438,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   auto rebase = [&](f32x16_t (&sacc)[2], float shift) __attribute__((always_inline)) {
     const float alpha = __builtin_amdgcn_exp2f(-shift);
     mb += shift;
+    set_negmb();
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -482,6 +498,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       const float mx = row_max(sacc);
       const float shift = mx == -INFINITY ? 0.f : mx;
       mb = shift;
+      set_negmb();
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -648,9 +665,6 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     auto iteration = [&](auto steady_c, int i) __attribute__((always_inline)) {
       constexpr bool steady = decltype(steady_c)::value;
       softmax(cm, i == 0, sacc, pf);
-      // tile i+1 of this wave's kind must have landed before the barrier; the only copy that
-      // may be younger is tile i+2's (tile i+3's starts inside the MFMA block below)
-      if (steady || i + 2 < n_t) dma_wait<G::IPW>(); else dma_wait<0>();
       // Tile i+1 opens a segment of a block table: new query fragments.  Waves 0..3 turn theirs here;
       // waves 4..7 have done so right behind their previous MFMA block (see below), in the same
       // half-period, so that the workgroup stalls once per boundary, not twice.
@@ -659,17 +673,21 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
         load_q(rot_of(cm.seg + 1));
         __builtin_amdgcn_s_setprio(0);
       }
+      // This wave's share of the copy of tile i+3 goes out here, in the softmax half, where the wave
+      // has issue slots to spare (its buffer's last readers finished before the barrier that opened
+      // this half-period: K(i-1) was last read by QK(i-1), V(i-1) by PV(i-1), both in MFMA blocks
+      // that ended at or before that barrier for every wave).
       const bool copy = steady || i + 3 < n_t;
-      CopyJob cj;
-      cj.ptr = cp_ptr;
-      cj.dst = lds_copy + (uint32_t)((i + 3) & (kNumKBuf - 1)) * TB;
-      cj.rb = prim_rb;
-      cj.valid = kTileKeys;
-      cj.full = true;
-      uint32_t cp_off[G::IPW];
-#pragma unroll
-      for (int u = 0; u < G::IPW; ++u) cp_off[u] = g_src[u];
       if (copy) {
+        CopyJob cj;
+        cj.ptr = cp_ptr;
+        cj.dst = lds_copy + (uint32_t)((i + 3) & (kNumKBuf - 1)) * TB;
+        cj.rb = prim_rb;
+        cj.valid = kTileKeys;
+        cj.full = true;
+        uint32_t cp_off[G::IPW];
+#pragma unroll
+        for (int u = 0; u < G::IPW; ++u) cp_off[u] = g_src[u];
         const uint32_t rb = cp.seg >= n_ctx_segs ? f_rb : c_rb;
         if (steady || (cp.ts > 0 && rb == prim_rb && (cp.ts + 1) * kTileKeys <= cp.len)) {
           cp_ptr += tile_bytes;
@@ -684,11 +702,18 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
           cp_ptr = cj.ptr + (uint64_t)(cj.rb * (uint32_t)kTileKeys);
         }
         advance(cp);
+#pragma unroll
+        for (int u = 0; u < G::IPW; ++u) lds_dma16(cj.ptr, cp_off[u], cj.dst + u * 1024);
       }
+      // tile i+1 of this wave's kind must have landed before the barrier; the copies that may be
+      // younger are tile i+2's and the one just started
+      if (steady || copy) dma_wait<2 * G::IPW>();
+      else if (i + 2 < n_t) dma_wait<G::IPW>();
+      else dma_wait<0>();
       const uint32_t vofs = VBASE + (i & (kNumVBuf - 1)) * TB;
       preload(vofs, fr);
       wg_barrier();
-      mfma_block(vofs, ((i + 1) & (kNumKBuf - 1)) * TB, steady || i + 1 < n_t, copy, cj, cp_off, pf, sacc, fr);
+      mfma_block(vofs, ((i + 1) & (kNumKBuf - 1)) * TB, steady || i + 1 < n_t, pf, sacc, fr);
       if constexpr (kBlocks && !steady) {
         advance(cm);
         if (role_b && i + 2 < n_t && cm.rem == 1) {  // (QK of tile i+1 is done: the fragments are free)
@@ -754,8 +779,14 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       float2 ml = {l_tot > 0.f ? mb : -INFINITY, l_tot};  // reference in log2 units; -inf: nothing visible
       *reinterpret_cast<float2 *>(BA_ARG(part_ml) + (slot * 32 + col) * 2) = ml;
       if (split == 0) {
-        const int g = my_row - my_tok * Gq;
-        BA_ARG(part_idx)[unit * 32 + col] = row_ok ? (pr.q_tok0 + my_tok) * BA_ARG(n_q_heads) + kvh * Gq + g : -1;
+        // (the row's token is worked out again, from a copy of the row number the compiler cannot
+        // see through: kept from before the walk it would be spilled)
+        int row_e = my_row;
+        asm volatile("" : "+v"(row_e));
+        const FastDiv gd = {BA_ARG(group_div.mul), BA_ARG(group_div.sh1), BA_ARG(group_div.sh2)};
+        const int tok_e = (int)fast_div((uint32_t)row_e, gd);
+        const int g = row_e - tok_e * Gq;
+        BA_ARG(part_idx)[unit * 32 + col] = row_e < n_rows ? (pr.q_tok0 + tok_e) * BA_ARG(n_q_heads) + kvh * Gq + g : -1;
       }
     }
     return;
@@ -770,6 +801,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   constexpr int PITCH = HD * 4;           // bytes per staged row piece (256 or 128)
   constexpr int HLPR = 256 / PITCH;       // pieces per 256-byte LDS line
   lds_char *stage = smem + wave * (32 * PITCH);
+  // (the swizzled chunk offsets below are the same expressions as the K fragment offsets of the loop:
+  // computed from an opaque copy of the lane's column, or the compiler keeps them alive across the
+  // whole walk, where there is no register for them, and spills them)
+  int col_e = col;
+  asm volatile("" : "+v"(col_e));
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     // write: lane (col, hf) owns query row `col`; chunk index XOR row keeps banks apart
@@ -782,7 +818,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
         f32x4_t w = {oacc[dt][q4 * 4 + 0] * inv, oacc[dt][q4 * 4 + 1] * inv, oacc[dt][q4 * 4 + 2] * inv,
                      oacc[dt][q4 * 4 + 3] * inv};
         *reinterpret_cast<__attribute__((address_space(3))) f32x4_t *>(
-            stage + col * PITCH + ((chunk ^ ((col / HLPR) & (HCH - 1))) << 4)) = w;
+            stage + col_e * PITCH + ((chunk ^ ((col_e / HLPR) & (HCH - 1))) << 4)) = w;
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
