@@ -874,32 +874,57 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(AttnParams p) 
   const int k = (int)(blockIdx.x % BPU) * KPB + kl;
   // all loads are unconditional and independent, so they go out together
   constexpr int MAXS = 32;  // the host never asks for more splits
-  float wgt[MAXS];
-  float m = -INFINITY;
   const int n_mine = (p.n_splits - g + SG - 1) / SG;  // splits g, g + SG, ...
   const float2 *ml = reinterpret_cast<const float2 *>(p.part_ml) + unit * 32 + col;
   const char *po = (const char *)p.part_o + unit * (int64_t)(32 * D * 2) + k * 1024 + lane * 16;
   const int64_t ml_stride = p.part_units * 32, o_stride = p.part_units * (int64_t)(32 * D * 2);
-#pragma unroll 8
-  for (int j = 0; j < n_mine; ++j) {
-    const int s = g + j * SG;
-    wgt[j & (MAXS - 1)] = ml[s * ml_stride].x;
-    m = fmaxf(m, wgt[j & (MAXS - 1)]);
-  }
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  float l = 0.f;
-#pragma unroll 8
-  for (int j = 0; j < n_mine; ++j) {
-    const int s = g + j * SG;
-    const float ms = wgt[j & (MAXS - 1)];
-    const float ls = ml[s * ml_stride].y;
-    const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m) * ls;
-    const u32x4_t o = *reinterpret_cast<const u32x4_t *>(po + s * o_stride);
-    l += w;
+  float l = 0.f, m = -INFINITY;
+  if (n_mine <= 8) {
+    // the common case (up to eight splits per thread): every load of the thread is requested before
+    // anything is used, a split beyond the thread's last reads its last one again with weight zero
+    float2 mls[8];
+    u32x4_t os[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc[2 * i] += w * f16_lo(o[i]);
-      acc[2 * i + 1] += w * f16_hi(o[i]);
+    for (int j = 0; j < 8; ++j) {
+      const int s = g + min(j, n_mine - 1) * SG;
+      mls[j] = ml[s * ml_stride];
+      os[j] = *reinterpret_cast<const u32x4_t *>(po + s * o_stride);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < n_mine) m = fmaxf(m, mls[j].x);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float w = (j >= n_mine || mls[j].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mls[j].x - m) * mls[j].y;
+      l += w;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += w * f16_lo(os[j][i]);
+        acc[2 * i + 1] += w * f16_hi(os[j][i]);
+      }
+    }
+  } else {
+    float wgt[MAXS];
+#pragma unroll 8
+    for (int j = 0; j < n_mine; ++j) {
+      const int s = g + j * SG;
+      wgt[j & (MAXS - 1)] = ml[s * ml_stride].x;
+      m = fmaxf(m, wgt[j & (MAXS - 1)]);
+    }
+#pragma unroll 8
+    for (int j = 0; j < n_mine; ++j) {
+      const int s = g + j * SG;
+      const float ms = wgt[j & (MAXS - 1)];
+      const float ls = ml[s * ml_stride].y;
+      const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m) * ls;
+      const u32x4_t o = *reinterpret_cast<const u32x4_t *>(po + s * o_stride);
+      l += w;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[2 * i] += w * f16_lo(o[i]);
+        acc[2 * i + 1] += w * f16_hi(o[i]);
+      }
     }
   }
   const int idx = p.part_idx[unit * 32 + col];
