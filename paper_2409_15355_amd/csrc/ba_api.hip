@@ -197,14 +197,6 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
                          const int32_t *pos0, hipStream_t stream, const ba::RopeRots *rots = nullptr,
                          const ba::RopeRotsSmall *rots_small = nullptr, float *rot_dst = nullptr, int n_rot = 0,
                          float *q_table = nullptr, bool rows_too = false) {
-  ba::RopeSegs segs;
-  memset(&segs, 0, sizeof(segs));
-  segs.n = n;
-  for (int i = 0; i < n; ++i) {
-    segs.start[i] = start[i];
-    segs.pos0[i] = pos0 ? pos0[i] : 0;
-  }
-  segs.start[n] = start[n];
   const int64_t tokens = (int64_t)start[n] - start[0];
   if (tokens <= 0) return BA_OK;
   ba::RopePrepassParams p;
@@ -234,10 +226,24 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
   p.do_k = 1;
   p.rot_dst = rot_dst;
   p.n_rot = n_rot;
-  hipError_t e;
-  {
+  auto fill_and_launch = [&](auto &segs) {
+    memset(&segs, 0, sizeof(segs));
+    segs.n = n;
+    for (int i = 0; i < n; ++i) {
+      segs.start[i] = start[i];
+      segs.pos0[i] = pos0 ? pos0[i] : 0;
+    }
+    segs.start[n] = start[n];
     ProfileScope ps(BA_PROFILE_REENCODE, stream);
-    e = ba::launch_rope_prepass(p, segs, rots, rots_small, rt, stream);
+    return ba::launch_rope_prepass(p, segs, rots, rots_small, rt, stream);
+  };
+  hipError_t e;
+  if (n <= ba::kRopeSmallSegs) {
+    ba::RopeSegsSmall segs;
+    e = fill_and_launch(segs);
+  } else {
+    ba::RopeSegs segs;
+    e = fill_and_launch(segs);
   }
   if (e != hipSuccess) return device_fail(e, "RoPE pre-pass launch");
   return BA_OK;

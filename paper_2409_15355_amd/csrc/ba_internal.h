@@ -63,11 +63,18 @@ constexpr int kBlkSmallPrompts = 16, kBlkSmallBlocks = 64;
 // [start[s], start[s+1]) and its first token has position pos0[s].
 constexpr int kRopeMaxSegs = 320;
 
-struct RopeSegs {
+// (two capacities: the table travels by value in the kernel arguments, and a final-block call of a
+// few prompts should not carry 2.5 KB of it through every launch)
+template <int N>
+struct RopeSegsT {
+  static constexpr int kSegs = N;
   int32_t n;
-  int32_t start[kRopeMaxSegs + 1];
-  int32_t pos0[kRopeMaxSegs];
+  int32_t start[N + 1];
+  int32_t pos0[N];
 };
+using RopeSegs = RopeSegsT<kRopeMaxSegs>;
+constexpr int kRopeSmallSegs = 8;
+using RopeSegsSmall = RopeSegsT<kRopeSmallSegs>;
 
 struct RopePrepassParams {
   const uint16_t *q_src;
@@ -96,6 +103,8 @@ using RopeRotsSmall = RopeRotsT<kBlkSmallBlocks>;
 
 // rots / rots_small: at most one non-null, and only with p.rot_dst
 hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeRots *rots,
+                               const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream);
+hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegsSmall &segs, const RopeRots *rots,
                                const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention ----------

@@ -37,8 +37,8 @@ __host__ __device__ inline int q_groups(const RopePrepassParams &p) {
   return (p.do_q == 1 || p.do_q == 3) ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : (p.do_q == 2 ? 1 : 0);
 }
 
-template <int D, int LAYOUT>
-__global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParams p, RopeSegs segs, RopeTable rt,
+template <int D, int LAYOUT, typename Segs>
+__global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParams p, Segs segs, RopeTable rt,
                                                                 RopeRotsSmall rots) {
   constexpr int VEC = 8;
   constexpr int CH = D / VEC;
@@ -135,8 +135,8 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
 }
 
 // rots: a small table of rotations to fill in the same launch, or null
-template <int D>
-hipError_t launch_d(RopePrepassParams p, const RopeSegs &segs, const RopeTable &rt, const RopeRotsSmall *rots,
+template <int D, typename Segs>
+hipError_t launch_d(RopePrepassParams p, const Segs &segs, const RopeTable &rt, const RopeRotsSmall *rots,
                     hipStream_t stream) {
   constexpr int TPP = kThreads / (D / 8 / 2);
   const int64_t tokens = (int64_t)segs.start[segs.n] - segs.start[0];
@@ -154,16 +154,15 @@ hipError_t launch_d(RopePrepassParams p, const RopeSegs &segs, const RopeTable &
   }
   dim3 grid(gx, (unsigned)groups + rot_rows, 1);
   if (p.layout == 0)
-    hipLaunchKernelGGL((rope_prepass_kernel<D, 0>), grid, dim3(kThreads), 0, stream, p, segs, rt, rots ? *rots : none);
+    hipLaunchKernelGGL((rope_prepass_kernel<D, 0, Segs>), grid, dim3(kThreads), 0, stream, p, segs, rt, rots ? *rots : none);
   else
-    hipLaunchKernelGGL((rope_prepass_kernel<D, 1>), grid, dim3(kThreads), 0, stream, p, segs, rt, rots ? *rots : none);
+    hipLaunchKernelGGL((rope_prepass_kernel<D, 1, Segs>), grid, dim3(kThreads), 0, stream, p, segs, rt, rots ? *rots : none);
   return hipGetLastError();
 }
 
-}  // namespace
-
-hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeRots *rots,
-                               const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream) {
+template <typename Segs>
+hipError_t launch_rope_prepass_t(const RopePrepassParams &p, const Segs &segs, const RopeRots *rots,
+                                 const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream) {
   // a large table of rotations gets a launch of its own; a small one rides along with the rows
   const bool want_rot = p.rot_dst && p.n_rot > 0;
   if (want_rot && rots) {
@@ -177,6 +176,17 @@ hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs,
   if (p.head_dim == 128) return launch_d<128>(p, segs, rt, ride, stream);
   if (p.head_dim == 64) return launch_d<64>(p, segs, rt, ride, stream);
   return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs, const RopeRots *rots,
+                               const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream) {
+  return launch_rope_prepass_t(p, segs, rots, rots_small, rt, stream);
+}
+hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegsSmall &segs, const RopeRots *rots,
+                               const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream) {
+  return launch_rope_prepass_t(p, segs, rots, rots_small, rt, stream);
 }
 
 }  // namespace ba
