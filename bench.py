@@ -72,6 +72,68 @@ def parity_figures(got: np.ndarray, ref: np.ndarray) -> dict:
     return {"max_abs": float(err.max()), "mean_abs": float(err.mean())}
 
 
+def phase_budget(args, torch, ba, dev, randn_bf16) -> int:
+    """Per-phase budget of the headline kernel by differences: the same geometry (256 query tokens,
+    32/8 heads of 128, one workgroup per compute unit) over contexts of 8K to 62K tokens.  The kernel's
+    time is linear in the key tiles a workgroup walks: the slope is the steady-state tile period, the
+    intercept everything else a launch pays (dispatch, prologue up to the first MFMA, pipeline fill and
+    drain, the causal segment's extra cost, epilogue, end of kernel).  Prints one JSON line."""
+    hq, hkv, d, lq = 32, 8, 128, 256
+    heads = ba.Heads(hq, hkv, d, 500000.0)
+    n_layers = 8
+    points = []
+    for t_ctx in (7936, 15872, 31744, 47616, 63488):
+        cu_q, cu_ctx = np.array([0, lq], dtype=np.int32), np.array([0, t_ctx], dtype=np.int32)
+        items = ba.ba_schedule_final_block(heads, cu_q, cu_ctx, 256)
+        n_splits = items[0].n_splits
+        tiles = max((w.ctx_end - w.ctx_begin + w.self_end - w.self_begin + 63) // 64 for w in items)
+        L = [dict(kc=randn_bf16(100 + 10 * i, (t_ctx, hkv, d)), vc=randn_bf16(101 + 10 * i, (t_ctx, hkv, d)),
+                  q=randn_bf16(102 + 10 * i, (lq, hq, d)), kf=randn_bf16(103 + 10 * i, (lq, hkv, d)),
+                  vf=randn_bf16(104 + 10 * i, (lq, hkv, d))) for i in range(n_layers)]
+        o = torch.empty((lq, hq, d), dtype=torch.bfloat16, device=dev)
+        ws = torch.empty(ba.ba_final_block_attention_workspace_bytes(heads, cu_q, cu_ctx), dtype=torch.uint8, device=dev)
+
+        def step():
+            for t in L:
+                ba.ba_final_block_attention(heads, t["q"], t["kc"], t["vc"], t["kf"], t["vf"], o, None, cu_q, cu_ctx,
+                                            None, ba.ROPE_APPLY, ws)
+        for _ in range(60):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        call_us = e0.elapsed_time(e1) / (20 * n_layers) * 1e3
+        ba.ba_profile_begin(1 << 12)
+        for _ in range(10):
+            step()
+        torch.cuda.synchronize()
+        ms, n = ba.ba_profile_end()
+        points.append({"context_tokens": t_ctx, "kv_splits": n_splits, "key_tiles_per_workgroup": int(tiles),
+                       "attention_kernel_us": round(ms[0] / n[0] * 1e3, 2), "rope_prepass_us": round(ms[1] / n[1] * 1e3, 2),
+                       "merge_us": round(ms[2] / max(n[2], 1) * 1e3, 2), "call_us": round(call_us, 2)})
+        del L, o, ws
+        torch.cuda.empty_cache()
+    x = np.array([p["key_tiles_per_workgroup"] for p in points], dtype=np.float64)
+    out = {"geometry": "256 query tokens x 32/8 heads x 128, 256 workgroups", "points": points}
+    for key in ("attention_kernel_us", "call_us"):
+        y = np.array([p[key] for p in points])
+        slope, icpt = np.polyfit(x, y, 1)
+        out[key + "_fit"] = {"us_per_key_tile": round(float(slope), 4), "fixed_us": round(float(icpt), 2),
+                             "largest_residual_us": round(float(np.abs(y - (slope * x + icpt)).max()), 2)}
+    c = ((stored_counters() or {}).get("attn_kernel_final_cfg5") or {}).get("clock_ghz")
+    if c:
+        out["at_sustained_clock_GHz"] = c
+        out["cycles_per_key_tile"] = round(out["attention_kernel_us_fit"]["us_per_key_tile"] * c * 1e3)
+        out["fixed_cycles"] = round(out["attention_kernel_us_fit"]["fixed_us"] * c * 1e3)
+        out["mfma_cycles_per_key_tile_at_full_pipe"] = 2048
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,6 +144,9 @@ def main() -> int:
     ap.add_argument("--no-rows", action="store_true", help="skip the secondary rows (config 3/4, single block)")
     ap.add_argument("--equal-splits", action="store_true",
                     help="skip the XCD speed calibration: KV splits of equal size")
+    ap.add_argument("--phase-budget", action="store_true",
+                    help="instead of the benchmark: the attention core's time at the headline geometry over several "
+                         "context lengths, and from their differences the time per key tile and the fixed part of a launch")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for HBM byte counters")
     ap.add_argument("--only", default="", help="run only one secondary row in a loop (for profiling): reencode|single|encode3|final3|query50|cfg2|prompts|smallblocks|cached")
@@ -143,6 +208,9 @@ def main() -> int:
             each = sorted(max(marks[i].elapsed_time(marks[i + 1]), 0.0) for i in range(steps))
             timed.last_median_min = (each[len(each) // 2], each[0], each[-1]) if each else (0.0, 0.0, 0.0)
         return max(marks[0].elapsed_time(marks[-1]), 0.0) / steps, wall_ms / steps
+
+    if args.phase_budget:
+        return phase_budget(args, torch, ba, dev, randn_bf16)
 
     # ------------------------------------------------------------------ headline: config 5
     w = wl.config5(n_layers=args.layers)

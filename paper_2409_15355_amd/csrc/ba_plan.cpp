@@ -72,7 +72,7 @@ int choose_splits(int64_t base_wgs, int max_tiles, int n_cu) {
   double best_cost = 0;
   for (int s = 1; s <= s_max; ++s) {
     const double rounds = (double)((base_wgs * s + n_cu - 1) / n_cu);
-    const double cost = rounds * (4.0 + (max_tiles + s - 1) / s) + 0.5 * s;
+    const double cost = rounds * (4.0 + (max_tiles + s - 1) / s) + 0.25 * s;
     if (s == 1 || cost < best_cost) {
       best = s;
       best_cost = cost;
