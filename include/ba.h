@@ -95,13 +95,37 @@ const char *ba_last_error(void);
  * ba_heads.xcd_speed (Section 2.5's step is the one whose launch ends with its slowest workgroup).
  * Runs the final-block attention core a few times on synthetic keys in the workspace (one workgroup
  * per compute unit, each timing its walk with the shader-clock and real-time counters), waits for
- * the stream, and writes eight numbers with mean 1 (each XCD's sustained clock over the mean).  If
- * the device does not deal workgroups to XCDs round-robin as the planner assumes, all eight are 1.
+ * the stream, and writes eight numbers with mean 1: the share of the keys each XCD's split should get
+ * for all of them to end together (a second pass with splits sized by the first pass's figures
+ * corrects them).  If the device does not deal workgroups to XCDs round-robin as the planner
+ * assumes, all eight are 1.
  * ws: 256-byte aligned, at least ba_measure_xcd_speed_workspace_bytes() bytes (about 150 MB).
  * Synchronises the stream; a one-time calibration, not a hot-path call.
  */
 int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_bytes, void *stream);
 size_t ba_measure_xcd_speed_workspace_bytes(void);
+
+/*
+ * Diagnostic for benchmarks: where the time of one launch of the final-block attention core goes
+ * (Section 2.5's step at 256 query tokens over 31,744 context tokens, 32 / 8 heads of 128: one
+ * workgroup per compute unit, 8 KV splits of 62 or 63 key tiles).  The same synthetic run as
+ * ba_measure_xcd_speed, same workspace; wave 0 of every workgroup reads the 100 MHz real-time counter
+ * at its phase boundaries.  xcd_speed: host, nullable: eight figures as in ba_heads.xcd_speed, the
+ * splits of the timed launch are sized by them (null: equal splits).
+ * phases_us, microseconds, means over the workgroups unless noted:
+ *   [0] kernel entry (first arguments loaded) -> first three tile copies issued
+ *   [1] -> those tiles and the query fragments have landed
+ *   [2] -> first scores done, the loop is entered (pipeline fill)
+ *   [3] the walk over the key tiles
+ *   [4] walk's end -> the split partial's stores complete
+ *   [5] workgroup lifetime ([0] to [4] together)
+ *   [6] first workgroup's entry -> last workgroup's stores complete (one number: the launch)
+ *   [7] the longest walk of any workgroup (one number; [7] - [3] = what imbalance costs)
+ * Synchronises the stream.  BA_ERR_UNSUPPORTED if the device does not give the probe's launch shape.
+ */
+#define BA_DIAG_PHASES 8
+int32_t ba_diag_final_block_phases(double phases_us[BA_DIAG_PHASES], const float *xcd_speed, void *ws, size_t ws_bytes,
+                                   void *stream);
 
 /*
  * Diagnostic for benchmarks: the rate of v_mfma_f32_32x32x16_bf16 this device sustains on operands

@@ -31,7 +31,7 @@ EXPORTS = ["ba_version", "ba_status_string", "ba_last_error", "ba_profile_begin"
            "ba_block_attention_prompts", "ba_block_attention_prompts_workspace_bytes",
            "ba_block_attention_prompts_backward", "ba_block_attention_prompts_backward_workspace_bytes",
            "ba_schedule_final_block", "ba_schedule_encode_blocks", "ba_schedule_prompts",
-           "ba_measure_xcd_speed", "ba_measure_xcd_speed_workspace_bytes",
+           "ba_measure_xcd_speed", "ba_measure_xcd_speed_workspace_bytes", "ba_diag_final_block_phases",
            "ba_diag_mfma_ceiling", "ba_diag_mfma_ceiling_workspace_bytes"]
 
 
@@ -138,6 +138,9 @@ def load():
     lib.ba_diag_mfma_ceiling_workspace_bytes.argtypes = []
     lib.ba_measure_xcd_speed.restype = ctypes.c_int32
     lib.ba_measure_xcd_speed.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.ba_diag_final_block_phases.restype = ctypes.c_int32
+    lib.ba_diag_final_block_phases.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                               ctypes.c_size_t, ctypes.c_void_p]
     lib.ba_measure_xcd_speed_workspace_bytes.restype = ctypes.c_size_t
     lib.ba_measure_xcd_speed_workspace_bytes.argtypes = []
     _lib = lib
@@ -492,6 +495,23 @@ def ba_measure_xcd_speed(ws, stream=None):
     wp, wb = _ws(ws)
     _check(load().ba_measure_xcd_speed(out, wp, wb, _stream_handle(stream)))
     return [float(x) for x in out]
+
+
+DIAG_PHASES = ("entry_to_first_copies_issued", "to_first_tiles_and_queries_landed", "to_loop_entered", "walk",
+               "walk_end_to_partials_stored", "workgroup_lifetime", "launch_first_entry_to_last_store", "longest_walk")
+
+
+def ba_diag_final_block_phases(ws, xcd_speed=None, stream=None) -> dict:
+    """Microseconds per phase of one final-block launch (see include/ba.h); ws as for ba_measure_xcd_speed."""
+    out = (ctypes.c_double * len(DIAG_PHASES))()
+    wp, wb = _ws(ws)
+    sp = None
+    if xcd_speed is not None:
+        if len(xcd_speed) != 8:
+            raise ValueError("xcd_speed: eight numbers")
+        sp = (ctypes.c_float * 8)(*[float(x) for x in xcd_speed])
+    _check(load().ba_diag_final_block_phases(out, sp, wp, wb, _stream_handle(stream)))
+    return {k: float(v) for k, v in zip(DIAG_PHASES, out)}
 
 
 def ba_diag_mfma_ceiling(lds_reads_per_two_mfma: int, stream=None) -> dict:

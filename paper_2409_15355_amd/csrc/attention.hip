@@ -146,11 +146,16 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const int Gq = p.group;
   const int n_rows = pr.lq * Gq;
   const int row0 = pr.jt * kTileRows;
-  // Speed probe (ba_measure_xcd_speed): which XCD this workgroup runs on, and its shader-clock and
-  // real-time (100 MHz) counters here and behind the walk; their ratio is the XCD's clock under this load.
+  // Probe (ba_measure_xcd_speed, ba_diag_final_block_phases): which XCD this workgroup runs on, its
+  // shader-clock and real-time (100 MHz) counters here and behind the walk (their ratio is the XCD's
+  // clock under this load), and the real-time counter at the phase boundaries in between.
   constexpr bool kProbe = std::is_same<Meta, FinalMeta>::value;
+  auto probe_mark = [&](int slot) __attribute__((always_inline)) {
+    if (kProbe && p.wg_clock && threadIdx.x == 0)
+      p.wg_clock[(size_t)blockIdx.x * kProbeRecord + slot] = (unsigned long long)wall_clock64();
+  };
   if (kProbe && p.wg_clock && threadIdx.x == 0) {
-    unsigned long long *rec = p.wg_clock + (size_t)blockIdx.x * 8;
+    unsigned long long *rec = p.wg_clock + (size_t)blockIdx.x * kProbeRecord;
     rec[0] = (unsigned long long)(__builtin_amdgcn_s_getreg(6164) & 15);  // HW_REG_XCC_ID, bits 3:0
     rec[1] = (unsigned long long)clock64();
     rec[2] = (unsigned long long)wall_clock64();
@@ -540,6 +545,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     }
   }
 
+  probe_mark(3);  // the first tile copies are on their way
   // ---- Q fragments (B operand of S^T = K Q^T).  With rotary embedding the rows come from the
   //      RoPE pre-pass, already rotated and multiplied by scale * log2(e); otherwise they are the
   //      caller's and are scaled here, before one rounding back to bf16.  With a block table the
@@ -641,6 +647,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   };
   load_q(rot_of(cm.seg));
   dma_wait<0>();  // unconditional: first tiles and Q fragments are complete from here on
+  probe_mark(6);
   f32x16_t sacc[2];
   bf16x8_t pf[4];
   bf16x8_t fr[W];
@@ -661,6 +668,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     // tile, other stride) is worked out from the cursor.  `steady` (compile time) promises the
     // common case: tiles i+1 and i+3 exist, tile i+1 lies in the same segment as tile i, and the
     // copy is such a following full tile.
+    probe_mark(7);  // (wave 0:) the first scores are done, the loop begins
     const uint64_t tile_bytes = (uint64_t)(prim_rb * (uint32_t)kTileKeys);
     auto iteration = [&](auto steady_c, int i) __attribute__((always_inline)) {
       constexpr bool steady = decltype(steady_c)::value;
@@ -743,7 +751,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   }
   static_assert(kNumKBuf == 4 && kNumVBuf == 4, "the copy distances above assume four buffers of each kind");
   if (kProbe && p.wg_clock && threadIdx.x == 0) {
-    unsigned long long *rec = p.wg_clock + (size_t)blockIdx.x * 8;
+    unsigned long long *rec = p.wg_clock + (size_t)blockIdx.x * kProbeRecord;
     rec[4] = (unsigned long long)clock64();
     rec[5] = (unsigned long long)wall_clock64();
   }
@@ -788,6 +796,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
         const int g = row_e - tok_e * Gq;
         BA_ARG(part_idx)[unit * 32 + col] = row_e < n_rows ? (pr.q_tok0 + tok_e) * BA_ARG(n_q_heads) + kvh * Gq + g : -1;
       }
+    }
+    if (kProbe && p.wg_clock && threadIdx.x == 0) {
+      probe_mark(8);                    // the partial's stores are issued
+      __builtin_amdgcn_s_waitcnt(0);
+      probe_mark(9);                    // and complete
     }
     return;
   }

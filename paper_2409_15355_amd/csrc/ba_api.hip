@@ -1438,7 +1438,7 @@ ProbeLayout probe_layout() {
   l.kv_bytes = align256((size_t)kProbeCtx * kProbeHkv * kProbeD * 2);
   l.q_bytes = align256((size_t)kProbeLq * kProbeHq * kProbeD * 2);
   l.kvf_bytes = align256((size_t)kProbeLq * kProbeHkv * kProbeD * 2);
-  l.clock_bytes = align256((size_t)kProbeMaxWg * 8 * sizeof(unsigned long long));
+  l.clock_bytes = align256((size_t)kProbeMaxWg * ba::kProbeRecord * sizeof(unsigned long long));
   const ba_heads h = probe_heads();
   const int32_t cu_q[2] = {0, kProbeLq}, cu_ctx[2] = {0, kProbeCtx};
   l.final_bytes = align256(ba_final_block_attention_workspace_bytes(&h, 1, cu_q, cu_ctx, BA_ROPE_NONE, 0));
@@ -1448,16 +1448,21 @@ ProbeLayout probe_layout() {
 
 extern "C" size_t ba_measure_xcd_speed_workspace_bytes(void) { return probe_layout().total(); }
 
-extern "C" int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_bytes, void *stream_) {
+namespace {
+// Runs the probe launches and reads the workgroups' records back (empty: the launch has a shape
+// there is nothing to learn from).  Synchronises the stream.
+int32_t run_probe(void *ws, size_t ws_bytes, void *stream_, const float *xcd_speed, std::vector<unsigned long long> *rec,
+                  int64_t *n_wg_out) {
   hipStream_t stream = (hipStream_t)stream_;
-  if (!speed_out) return fail(BA_ERR_INVALID_ARG, "speed_out: null");
-  for (int x = 0; x < ba::kNumXcds; ++x) speed_out[x] = 1.0f;
+  rec->clear();
+  *n_wg_out = 0;
   const ProbeLayout l = probe_layout();
   if (!ws || ws_bytes < l.total() || ((uintptr_t)ws & 255))
-    return fail(BA_ERR_WORKSPACE, "XCD speed probe: 256-byte aligned workspace of %zu bytes needed, %zu given", l.total(),
+    return fail(BA_ERR_WORKSPACE, "final-block probe: 256-byte aligned workspace of %zu bytes needed, %zu given", l.total(),
                 ws_bytes);
   char *wp = (char *)ws;
-  const ba_heads h = probe_heads();
+  ba_heads h = probe_heads();
+  h.xcd_speed = xcd_speed;
   auto tensor = [&](size_t bytes, int heads_n) {
     ba_tensor t;
     t.ptr = wp;
@@ -1477,7 +1482,7 @@ extern "C" int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_
   if (e == hipSuccess)
     e = ba::launch_fill_random_bf16((uint16_t *)kf.ptr, 2 * l.kvf_bytes / 2, 0x85ebca6bu, stream);
   if (e == hipSuccess) e = hipMemsetAsync(clk, 0, l.clock_bytes, stream);
-  if (e != hipSuccess) return device_fail(e, "XCD speed probe: fill");
+  if (e != hipSuccess) return device_fail(e, "final-block probe: fill");
   const int32_t cu_q[2] = {0, kProbeLq}, cu_ctx[2] = {0, kProbeCtx};
   int32_t rc = BA_OK;
   g_probe_clock = clk;
@@ -1489,33 +1494,90 @@ extern "C" int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_
   ba::FinalPlan pl;
   if ((rc = ba::plan_final(&h, 1, cu_q, cu_ctx, BA_ROPE_NONE, false, num_cus(), &pl))) return rc;
   const int64_t n_wg = pl.total_tiles * kProbeHkv * pl.n_splits;
-  if (n_wg < ba::kNumXcds || n_wg > kProbeMaxWg) return BA_OK;  // nothing to learn from such a launch: equal speeds
-  std::vector<unsigned long long> rec((size_t)n_wg * 8);
-  if ((e = hipStreamSynchronize(stream)) != hipSuccess) return device_fail(e, "XCD speed probe: synchronize");
-  if ((e = hipMemcpy(rec.data(), clk, rec.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost)) != hipSuccess)
-    return device_fail(e, "XCD speed probe: read-back");
-  double sum[ba::kNumXcds] = {0}, total = 0.0;
-  int cnt[ba::kNumXcds] = {0};
-  for (int64_t wg = 0; wg < n_wg; ++wg) {
-    const unsigned long long *r = &rec[(size_t)wg * 8];
-    const int x = ba::xcd_of_workgroup((unsigned)wg);
-    if ((int)r[0] != x || r[5] <= r[2] || r[4] <= r[1]) return BA_OK;  // not the mapping the planner assumes: equal speeds
-    sum[x] += (double)(r[4] - r[1]) / (double)(r[5] - r[2]);  // shader cycles per 10 ns
-    ++cnt[x];
-  }
-  for (int x = 0; x < ba::kNumXcds; ++x) {
-    if (!cnt[x]) return BA_OK;
-    sum[x] /= cnt[x];
-    total += sum[x];
-  }
-  for (int x = 0; x < ba::kNumXcds; ++x) {
-    const double s = sum[x] * ba::kNumXcds / total;
-    if (!(s >= 0.5 && s <= 2.0)) {
-      for (int y = 0; y < ba::kNumXcds; ++y) speed_out[y] = 1.0f;
-      return BA_OK;
+  if ((e = hipStreamSynchronize(stream)) != hipSuccess) return device_fail(e, "final-block probe: synchronize");
+  if (n_wg < ba::kNumXcds || n_wg > kProbeMaxWg) return BA_OK;
+  rec->resize((size_t)n_wg * ba::kProbeRecord);
+  if ((e = hipMemcpy(rec->data(), clk, rec->size() * sizeof(unsigned long long), hipMemcpyDeviceToHost)) != hipSuccess)
+    return device_fail(e, "final-block probe: read-back");
+  *n_wg_out = n_wg;
+  return BA_OK;
+}
+}  // namespace
+
+extern "C" int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_bytes, void *stream_) {
+  if (!speed_out) return fail(BA_ERR_INVALID_ARG, "speed_out: null");
+  float speed[ba::kNumXcds];
+  for (int x = 0; x < ba::kNumXcds; ++x) speed_out[x] = speed[x] = 1.0f;
+  // Two passes: equal splits first, then splits sized by the first pass's figures, whose residual
+  // corrects them.  What is measured is how long an XCD's workgroups take from entry to the end of
+  // their walk (not its clock alone: cycles per tile differ between XCDs too, with the place of their
+  // keys in memory and with the causal tiles of the last split); a split's share is scaled by
+  // mean / own, which equalises those times where time is proportional to tiles.
+  for (int pass = 0; pass < 2; ++pass) {
+    std::vector<unsigned long long> rec;
+    int64_t n_wg = 0;
+    if (int32_t rc = run_probe(ws, ws_bytes, stream_, pass ? speed : nullptr, &rec, &n_wg)) return rc;
+    if (n_wg == 0) return BA_OK;  // nothing to learn from such a launch: equal speeds
+    double sum[ba::kNumXcds] = {0}, total = 0.0;
+    int cnt[ba::kNumXcds] = {0};
+    for (int64_t wg = 0; wg < n_wg; ++wg) {
+      const unsigned long long *r = &rec[(size_t)wg * ba::kProbeRecord];
+      const int x = ba::xcd_of_workgroup((unsigned)wg);
+      if ((int)r[0] != x || r[5] <= r[2]) return BA_OK;  // not the mapping the planner assumes: equal speeds
+      sum[x] += (double)(r[5] - r[2]);
+      ++cnt[x];
     }
-    speed_out[x] = (float)s;
+    for (int x = 0; x < ba::kNumXcds; ++x) {
+      if (!cnt[x]) return BA_OK;
+      sum[x] /= cnt[x];
+      total += sum[x];
+    }
+    double next[ba::kNumXcds], norm = 0.0;
+    for (int x = 0; x < ba::kNumXcds; ++x) {
+      next[x] = (double)speed[x] * (total / ba::kNumXcds) / sum[x];
+      norm += next[x];
+    }
+    for (int x = 0; x < ba::kNumXcds; ++x) {
+      const double v = next[x] * ba::kNumXcds / norm;
+      if (!(v >= 0.5 && v <= 2.0)) return BA_OK;  // implausible: keep equal speeds
+      speed[x] = (float)v;
+    }
   }
+  for (int x = 0; x < ba::kNumXcds; ++x) speed_out[x] = speed[x];
+  return BA_OK;
+}
+
+extern "C" int32_t ba_diag_final_block_phases(double phases_us[BA_DIAG_PHASES], const float *xcd_speed, void *ws,
+                                              size_t ws_bytes, void *stream_) {
+  if (!phases_us) return fail(BA_ERR_INVALID_ARG, "phases_us: null");
+  for (int i = 0; i < BA_DIAG_PHASES; ++i) phases_us[i] = 0.0;
+  std::vector<unsigned long long> rec;
+  int64_t n_wg = 0;
+  if (int32_t rc = run_probe(ws, ws_bytes, stream_, xcd_speed, &rec, &n_wg)) return rc;
+  if (n_wg == 0) return fail(BA_ERR_UNSUPPORTED, "final-block phases: this device's launch is not the shape the probe times");
+  unsigned long long first = ~0ull, last = 0;
+  for (int64_t wg = 0; wg < n_wg; ++wg) {
+    const unsigned long long *r = &rec[(size_t)wg * ba::kProbeRecord];
+    if (!(r[2] <= r[3] && r[3] <= r[6] && r[6] <= r[7] && r[7] <= r[5] && r[5] <= r[8] && r[8] <= r[9]))
+      return fail(BA_ERR_DEVICE, "final-block phases: workgroup %lld left marks out of order", (long long)wg);
+    first = std::min(first, r[2]);
+    last = std::max(last, r[9]);
+  }
+  const double tick_us = 0.01;  // the real-time counter runs at 100 MHz
+  double longest_walk = 0.0;
+  for (int64_t wg = 0; wg < n_wg; ++wg) {
+    const unsigned long long *r = &rec[(size_t)wg * ba::kProbeRecord];
+    phases_us[0] += (double)(r[3] - r[2]);
+    phases_us[1] += (double)(r[6] - r[3]);
+    phases_us[2] += (double)(r[7] - r[6]);
+    phases_us[3] += (double)(r[5] - r[7]);
+    phases_us[4] += (double)(r[9] - r[5]);
+    phases_us[5] += (double)(r[9] - r[2]);
+    longest_walk = std::max(longest_walk, (double)(r[5] - r[7]));
+  }
+  for (int i = 0; i <= 5; ++i) phases_us[i] *= tick_us / (double)n_wg;
+  phases_us[6] = (double)(last - first) * tick_us;
+  phases_us[7] = longest_walk * tick_us;
   return BA_OK;
 }
 

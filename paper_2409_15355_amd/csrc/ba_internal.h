@@ -123,6 +123,7 @@ inline FastDiv make_fast_div(uint32_t d) {
   return f;
 }
 
+constexpr int kProbeRecord = 16;
 constexpr int kTileRows = 256;  // packed (token, head-in-group) query rows per workgroup
 constexpr int kTileKeys = 64;   // keys per K/V tile
 constexpr int kShortTileRows = 128;  // packed query rows per workgroup of the short-block schedule
@@ -163,7 +164,10 @@ struct AttnParams {
   int32_t n_splits;
   int32_t use_cuts;            // split_cut holds unequal shares (see split_tile_range)
   uint32_t split_cut[33];      // cumulative shares of the splits, 1 / 65536 units
-  unsigned long long *wg_clock;  // speed probe only, else null: per workgroup (XCC id, shader cycles, 100 MHz ticks, 0)
+  unsigned long long *wg_clock;  // probe only, else null: kProbeRecord numbers per workgroup:
+                                 // [0] XCC id, [1] shader cycles and [2] 100 MHz ticks at entry, [4] and [5] the same
+                                 // behind the walk, ticks [3] first tile copies issued, [6] first tiles and query
+                                 // fragments landed, [7] loop entered, [8] partials' stores issued, [9] complete
   int32_t total_tiles;  // row tiles over all problems of this launch
   FastDiv tiles_div;    // division by total_tiles (short-block schedule)
   float *lse;           // short-block schedule: [tokens][n_q_heads] log-sum-exp of the scaled scores, or null

@@ -382,3 +382,21 @@ def test_python_face_rejects_tensors_the_boundary_cannot_check(lib):
                                                t164q, t164k, t164k, [0, 2], [0, 100, 164])
     with pytest.raises(ValueError, match="block_offsets"):
         ba.ba_block_attention_prompts(h, t164q, t164k, t164k, t164q, None, None, [0, 3], [0, 100, 164])
+
+
+def test_probes_and_diagnostics_reject_bad_arguments_before_any_device_work(lib):
+    speeds = (ctypes.c_float * 8)()
+    phases = (ctypes.c_double * 8)()
+    need = lib.ba_measure_xcd_speed_workspace_bytes()
+    assert need > 2 * 31744 * 8 * 128 * 2  # (the probe's synthetic keys and values live in the workspace)
+    assert lib.ba_measure_xcd_speed(None, None, 0, None) == -1
+    assert lib.ba_measure_xcd_speed(speeds, None, 0, None) == -4
+    assert lib.ba_measure_xcd_speed(speeds, ctypes.c_void_p(0x1000), need - 1, None) == -4
+    assert lib.ba_measure_xcd_speed(speeds, ctypes.c_void_p(0x1010), need, None) == -4  # not 256-byte aligned
+    assert [float(x) for x in speeds] == [1.0] * 8  # (equal speeds whenever nothing was measured)
+    assert lib.ba_diag_final_block_phases(None, None, None, 0, None) == -1
+    assert lib.ba_diag_final_block_phases(phases, None, None, 0, None) == -4
+    assert lib.ba_diag_final_block_phases(phases, None, ctypes.c_void_p(0x1000), need - 1, None) == -4
+    assert b"workspace" in lib.ba_last_error()
+    t = ctypes.c_double()
+    assert lib.ba_diag_mfma_ceiling(3, ctypes.byref(t), ctypes.byref(t), ctypes.byref(t), None, 0, None) == -1

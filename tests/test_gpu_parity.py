@@ -1523,3 +1523,18 @@ def test_final_block_with_splits_sized_by_xcd_speed(ba):
     heads = ba.Heads(hq, hkv, d, 500000.0, xcd_speed=sp)
     o = gpu_final(ba, heads, dev_bf16(qb), dev_bf16(kcb), dev_bf16(vcb), dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
     assert_attention_close(host_f64(o), ref, "measured speeds")
+
+
+@pytest.mark.gpu
+def test_phase_marks_of_a_final_block_launch_are_consistent(ba):
+    """The diagnostic's phases are positive, add up to the workgroup lifetime, and fit inside the launch."""
+    torch = torch_mod()
+    ws = torch.empty(ba.ba_measure_xcd_speed_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    ph = ba.ba_diag_final_block_phases(ws, xcd_speed=[1.02, 0.98, 1.0, 1.0, 1.01, 0.99, 1.0, 1.0])
+    parts = [ph[k] for k in ba.DIAG_PHASES[:5]]
+    assert all(x > 0.0 for x in parts), ph
+    assert abs(sum(parts) - ph["workgroup_lifetime"]) < 0.05, ph
+    assert ph["walk"] <= ph["longest_walk"] <= ph["launch_first_entry_to_last_store"], ph
+    assert ph["workgroup_lifetime"] <= ph["launch_first_entry_to_last_store"] < 1000.0, ph
+    # the walk is most of a workgroup's life at this shape (62 or 63 key tiles)
+    assert ph["walk"] > 0.8 * ph["workgroup_lifetime"], ph
