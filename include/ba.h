@@ -363,7 +363,8 @@ size_t ba_block_attention_prompts_backward_workspace_bytes(const ba_heads *heads
  * kernels, computed by the code the calls themselves use.  Host only: no device is touched, so
  * these run on a machine without a GPU.
  *
- * A work item is one workgroup's job at one KV head (every item runs once per KV head): packed query
+ * A work item is one workgroup's job at one KV head (an item with kv_head = -1 runs once per KV
+ * head; with splits sized by XCD speed the final-block query lists every KV head's items): packed query
  * rows [row_begin, row_end) of a "problem" (row = token_in_problem * group + head_in_group, group =
  * n_q_heads / n_kv_heads) against two key ranges -- context keys [ctx_begin, ctx_end), counted from
  * the problem's first visible context key and all visible to every row, and the problem's own
@@ -383,6 +384,8 @@ typedef struct ba_work_item {
   int32_t split, n_splits;
   int32_t ctx_begin, ctx_end;
   int32_t self_begin, self_end;
+  int32_t kv_head;     /* the KV head, or -1: the same item at every KV head                    */
+  int32_t xcd;         /* with kv_head >= 0: the XCD (of eight) whose compute units run it, else -1 */
 } ba_work_item;
 /* ba_final_block_attention on a device of n_compute_units compute units (256 on MI355X). */
 int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const int32_t *cu_q,

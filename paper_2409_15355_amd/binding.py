@@ -51,7 +51,7 @@ class BaHeads(ctypes.Structure):
 class BaWorkItem(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("launch", "problem", "first_token", "tile_rows", "tile_keys", "row_begin",
                                                "row_end", "split", "n_splits", "ctx_begin", "ctx_end", "self_begin",
-                                               "self_end")]
+                                               "self_end", "kv_head", "xcd")]
 
 
 class BaError(RuntimeError):

@@ -132,11 +132,12 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     // each XCD (and its L2) gets a contiguous run of work items.
     id = work_item_of_workgroup(id, gridDim.x);
   }
-  const uint32_t n_rowtiles = (uint32_t)p.total_tiles;
-  const uint32_t id_hi = id / n_rowtiles, id_lo = id - id_hi * n_rowtiles;
-  const int rowtile = kFinal ? (int)id_lo : (int)(n_rowtiles - 1 - id_lo);
-  const int split = (int)(id_hi / (uint32_t)p.n_kv_heads);
-  const int kvh = (int)(id_hi - (uint32_t)split * (uint32_t)p.n_kv_heads);
+  // (divisions by launch constants: multipliers from the host instead of hardware divisions, each of
+  // which is some thirty instructions on the one scalar unit that the eight waves of a workgroup share)
+  const ItemOrder order = {p.total_tiles, p.n_kv_heads, p.n_splits, p.kv_group};
+  const ItemCoords item = item_coords(id, order, &p.item_divs);
+  const int rowtile = kFinal ? item.rowtile : p.total_tiles - 1 - item.rowtile;
+  const int split = item.split, kvh = item.kvh;
   const Problem pr = locate(meta, rowtile);
 
   const int lane = threadIdx.x & 63;
@@ -171,7 +172,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   const int last_tok = (int)fast_div((uint32_t)last_row, p.group_div);
   const int n_causal_tiles = causal_key_tiles(last_tok, kTileKeys);
   // this split's share of the walk (the arithmetic is the host planner's: one definition)
-  const TileRange tr = split_tile_range(n_ctx_tiles, n_causal_tiles, p.n_splits, split, p.use_cuts ? p.split_cut : nullptr);
+  const TileRange tr = split_tile_range(n_ctx_tiles, n_causal_tiles, p.n_splits, split, p.use_cuts ? p.split_cut[kvh] : nullptr,
+                                        &p.split_divs);
   const int t_begin = tr.begin, t_end = tr.end;
   const int n_t = t_end - t_begin;
 
@@ -201,18 +203,16 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   // One wave instruction fills 1024 contiguous LDS bytes, lane i writing [16 i, 16 i + 16); the
   // swizzle is applied on the GLOBAL side.  Rows at or beyond a tile's valid count re-read its
   // last valid row: their scores are masked, and a finite duplicate keeps 0 * v equal to 0.
-  const char *kc_base = (const char *)(p.kc + (int64_t)pr.ctx0 * p.kc_st + (int64_t)kvh * p.kc_sh);
-  const char *vc_base = (const char *)(p.vc + (int64_t)pr.ctx0 * p.vc_st + (int64_t)kvh * p.vc_sh);
-  const char *kf_base = (const char *)(p.kf + (int64_t)pr.q_tok0 * p.kf_st + (int64_t)kvh * p.kf_sh);
-  const char *vf_base = (const char *)(p.vf + (int64_t)pr.q_tok0 * p.vf_st + (int64_t)kvh * p.vf_sh);
-  const uint32_t kc_rb = (uint32_t)p.kc_st * 2u, vc_rb = (uint32_t)p.vc_st * 2u;  // row strides, bytes
-  const uint32_t kf_rb = (uint32_t)p.kf_st * 2u, vf_rb = (uint32_t)p.vf_st * 2u;
   // Waves 0..3 fetch the K tiles and waves 4..7 the V tiles (see the walk below), so each wave
-  // keeps the addressing of one kind only.
+  // works out the addressing of one kind only (tensor and strides are picked first, the 64-bit
+  // products come after: half as many of them).
   const bool role_b = wave >= kWaves / 2;
-  const char *c_base = role_b ? vc_base : kc_base;  // context segment of this wave's kind
-  const char *f_base = role_b ? vf_base : kf_base;  // causal segment
-  const uint32_t c_rb = role_b ? vc_rb : kc_rb, f_rb = role_b ? vf_rb : kf_rb;
+  const uint16_t *c_ptr = role_b ? p.vc : p.kc, *f_ptr = role_b ? p.vf : p.kf;
+  const int64_t c_st = role_b ? p.vc_st : p.kc_st, c_sh = role_b ? p.vc_sh : p.kc_sh;
+  const int64_t f_st = role_b ? p.vf_st : p.kf_st, f_sh = role_b ? p.vf_sh : p.kf_sh;
+  const char *c_base = (const char *)(c_ptr + (int64_t)pr.ctx0 * c_st + (int64_t)kvh * c_sh);    // context segment
+  const char *f_base = (const char *)(f_ptr + (int64_t)pr.q_tok0 * f_st + (int64_t)kvh * f_sh);  // causal segment
+  const uint32_t c_rb = (uint32_t)c_st * 2u, f_rb = (uint32_t)f_st * 2u;  // row strides, bytes
   // Full tiles of segments with the "primary" row stride (the context's if there is one, else the
   // causal segment's) take a short path with cached lane offsets.
   const uint32_t prim_rb = n_ctx_segs > 0 ? c_rb : f_rb;
@@ -532,20 +532,33 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   // buffer is refilled only after the barrier that follows its last reader.
   Cursor cp = cursor_at(t_begin);  // the next tile to copy
   const char *cp_ptr = nullptr;    // where the tile after the last copied one starts (same segment)
-  if (n_t > 0) {
+  auto first_copy = [&](int j) __attribute__((always_inline)) {  // tile j = 0, 1, 2 of the walk, before the loop
+    if (j < n_t) {
+      // (as in the loop: a full tile that follows the last copied one in memory needs the pointer only)
+      const uint32_t rb = cp.seg >= n_ctx_segs ? f_rb : c_rb;
+      if (j > 0 && cp.ts > 0 && rb == prim_rb && (cp.ts + 1) * kTileKeys <= cp.len) {
+        const uint32_t dst = lds_copy + (uint32_t)j * TB;
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
-      if (j < n_t) {
+        for (int i = 0; i < G::IPW; ++i) lds_dma16(cp_ptr, g_src[i], dst + i * 1024);
+        cp_ptr += (uint64_t)(prim_rb * (uint32_t)kTileKeys);
+      } else {
         const CopyJob c = copy_prepare(cp, j);
 #pragma unroll
         for (int i = 0; i < G::IPW; ++i) copy_part(c, i);
         cp_ptr = c.ptr + (uint64_t)(c.rb * (uint32_t)kTileKeys);
-        advance(cp);
       }
+      advance(cp);
     }
-  }
+  };
+  // Start-up order.  Every workgroup of a launch starts at the same moment and would ask for its
+  // first three tiles of either kind and its query rows at once: 160 KB per compute unit, which its
+  // vector-memory path takes some 2,500 cycles to move, and the first MFMA waited for all of it.  The
+  // first scores need tile 0 and the query rows only: those are asked for first and waited for; tiles
+  // 1 and 2 are asked for behind the barrier that publishes tile 0 and arrive while the first scores
+  // and the first exponentials are worked out (the loop's own waits cover them, as every later tile).
+  first_copy(0);
+  probe_mark(3);  // tile 0 is on its way
 
-  probe_mark(3);  // the first tile copies are on their way
   // ---- Q fragments (B operand of S^T = K Q^T).  With rotary embedding the rows come from the
   //      RoPE pre-pass, already rotated and multiplied by scale * log2(e); otherwise they are the
   //      caller's and are scaled here, before one rounding back to bf16.  With a block table the
@@ -564,23 +577,28 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     return kp;
   };
 #define BA_ARG(field) (kBlocks ? kp->field : p.field)
-  auto load_q = [&](int rot) __attribute__((always_inline)) {
+  // this lane's query row: where its fragments start, and its token inside the problem
+  struct QRow {
+    const uint16_t *ptr;
+    int tok;
+  };
+  auto q_row = [&]() __attribute__((always_inline)) {
     KParams kp = kBlocks ? args_again() : nullptr;
     const FastDiv gdiv = {BA_ARG(group_div.mul), BA_ARG(group_div.sh1), BA_ARG(group_div.sh2)};
     // (addresses are rebuilt from the row number each time: with a block table this runs inside the
     // loop, and hoisted address registers would not fit next to the accumulators)
     int row_v = my_row;
     asm volatile("" : "+v"(row_v));
-    const int tok_v = (int)fast_div((uint32_t)row_v, gdiv);
-    const int g = row_v - tok_v * Gq;
+    QRow r;
+    r.tok = (int)fast_div((uint32_t)row_v, gdiv);
+    const int g = row_v - r.tok * Gq;
     const int head = kvh * Gq + g;
-    const uint16_t *qp = BA_ARG(q) + (int64_t)(pr.q_tok0 + tok_v) * BA_ARG(q_st) + (int64_t)head * BA_ARG(q_sh) + hf * 8;
-    u32x4_t raw[G::KCH];
-#pragma unroll
-    for (int kk = 0; kk < G::KCH; ++kk) {
-      u32x4_t z = {0u, 0u, 0u, 0u};
-      raw[kk] = row_ok ? *reinterpret_cast<const u32x4_t *>(qp + kk * 16) : z;
-    }
+    r.ptr = BA_ARG(q) + (int64_t)(pr.q_tok0 + r.tok) * BA_ARG(q_st) + (int64_t)head * BA_ARG(q_sh) + hf * 8;
+    return r;
+  };
+  // fragments as loaded -> rotated / scaled as the call asks -> qf
+  auto q_finish = [&](u32x4_t (&raw)[G::KCH], int tok_v, int rot) __attribute__((always_inline)) {
+    KParams kp = kBlocks ? args_again() : nullptr;
     // rotate the fragments by the angles of a table row: entry j = (cos, sin) (times a scale, if any)
     auto rotate_by = [&](const f32x4_t *tab) __attribute__((always_inline)) {
       if (BA_ARG(rope_layout) == 0) {
@@ -640,24 +658,77 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       qf[kk] = __builtin_bit_cast(bf16x8_t, raw[kk]);
     }
   };
+  auto load_q = [&](int rot) __attribute__((always_inline)) {
+    const QRow r = q_row();
+    u32x4_t raw[G::KCH];
+#pragma unroll
+    for (int kk = 0; kk < G::KCH; ++kk) {
+      u32x4_t z = {0u, 0u, 0u, 0u};
+      raw[kk] = row_ok ? *reinterpret_cast<const u32x4_t *>(r.ptr + kk * 16) : z;
+    }
+    q_finish(raw, r.tok, rot);
+  };
+  // The first load of the query rows, before the loop.  A lane fetching the sixteen-byte pieces of its
+  // own row touches a cache line per lane and instruction (thirty-two lines for one kilobyte), and a
+  // workgroup's 64 KB of query rows then take some 2.5 microseconds to arrive, five times as long as
+  // its first tiles.  Here the rows are fetched whole instead (LDS-direct, four 256-byte rows per
+  // wave instruction) into a slice of tile buffers 1 and 2 of the wave's kind, which are idle until
+  // the first barrier, laid out as a K tile of 32 rows; the fragments are then read from the slice
+  // at the offsets of a K fragment.  Each wave reads only what it fetched itself: no barrier.
+  auto load_q_first = [&](int rot) __attribute__((always_inline)) {
+    KParams kp = kBlocks ? args_again() : nullptr;
+    const FastDiv gdiv = {BA_ARG(group_div.mul), BA_ARG(group_div.sh1), BA_ARG(group_div.sh2)};
+    const uint32_t slice = (role_b ? VBASE : 0u) + TB + (uint32_t)(wave & (kWaves / 2 - 1)) * (32 * G::ROWB);
+    static_assert((kWaves / 2) * 32 * G::ROWB == 2 * TB, "the slices of a kind's four waves fill its tile buffers 1 and 2");
+    const int wave_row0 = row0 + wave * 32;
+    const int tok_first = (int)fast_div((uint32_t)min(wave_row0, n_rows - 1), gdiv);  // wave-uniform
+    const char *qbase = (const char *)(BA_ARG(q) + (int64_t)(pr.q_tok0 + tok_first) * BA_ARG(q_st) +
+                                       (int64_t)(kvh * Gq) * BA_ARG(q_sh));
+    const uint32_t st_b = (uint32_t)BA_ARG(q_st) * 2u, sh_b = (uint32_t)BA_ARG(q_sh) * 2u;  // (the host checked that they fit)
+#pragma unroll
+    for (int j = 0; j < 32 / G::RPI; ++j) {
+      const int r_in = j * G::RPI + lane / G::CPR, pos = lane % G::CPR;
+      const int r = min(wave_row0 + r_in, n_rows - 1);  // rows beyond the problem: its last row, zeroed below
+      const int tok = (int)fast_div((uint32_t)r, gdiv);
+      const uint32_t off = (uint32_t)(tok - tok_first) * st_b + (uint32_t)(r - tok * Gq) * sh_b +
+                           ((uint32_t)(pos ^ ((r_in / G::LPR) & (G::CPR - 1))) << 4);
+      lds_dma16(qbase, off, (uint32_t)(uintptr_t)smem + slice + j * 1024);
+    }
+    dma_wait<0>();  // tile 0 (this wave's share) and the query rows are complete from here on
+    u32x4_t raw[G::KCH];
+#pragma unroll
+    for (int kk = 0; kk < G::KCH; ++kk) {
+      raw[kk] = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t *>(smem + slice + k_rd[kk]);
+      if (!row_ok) raw[kk] = u32x4_t{0u, 0u, 0u, 0u};
+    }
+    q_finish(raw, my_tok, rot);
+  };
   Cursor cm = cursor_at(t_begin);  // the tile whose softmax comes next
   auto rot_of = [&](int sg) __attribute__((always_inline)) {
     if constexpr (kBlocks) return sg < n_ctx_segs ? meta.rot_base + pr.blk0 + sg : -1;
     return -1;
   };
-  load_q(rot_of(cm.seg));
-  dma_wait<0>();  // unconditional: first tiles and Q fragments are complete from here on
+  if (p.q_rows_fit32) {
+    load_q_first(rot_of(cm.seg));
+  } else {
+    load_q(rot_of(cm.seg));
+    dma_wait<0>();
+  }
   probe_mark(6);
   f32x16_t sacc[2];
   bf16x8_t pf[4];
   bf16x8_t fr[W];
   if (n_t > 0) {
     if (!role_b) {
-      wg_barrier();  // tiles 0..2 of both kinds are visible
+      wg_barrier();  // tile 0 of both kinds is visible
+      first_copy(1);
+      first_copy(2);
       qk_first(0, sacc);
       wg_barrier();
     } else {
       wg_barrier();
+      first_copy(1);
+      first_copy(2);
       wg_barrier();
       qk_first(0, sacc);
       wg_barrier();
@@ -999,7 +1070,13 @@ hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, hipStream_t stre
     if (e != hipSuccess) return e;
     raised.store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL((attn_kernel<D, Meta>), dim3((unsigned)n_wg), dim3(kThreads), lds, stream, p, meta);
+  AttnParams pl = p;  // with the launch's divisors
+  pl.tiles_div = make_fast_div((uint32_t)p.total_tiles);
+  pl.kv_group = kv_group_of(p.n_kv_heads);
+  pl.item_divs = make_item_divs(ItemOrder{p.total_tiles, p.n_kv_heads, p.n_splits, pl.kv_group});
+  pl.split_divs = make_split_divs(p.n_splits);
+  pl.q_rows_fit32 = p.q_st > 0 && p.q_sh > 0 && 32 * p.q_st * 2 + (int64_t)p.group * p.q_sh * 2 < (int64_t)1 << 32;
+  hipLaunchKernelGGL((attn_kernel<D, Meta>), dim3((unsigned)n_wg), dim3(kThreads), lds, stream, pl, meta);
   return hipGetLastError();
 }
 

@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ba_schedule.h"
+
 namespace ba {
 
 constexpr int kMaxFreq = 64;  // head_dim / 2 <= 64
@@ -108,20 +110,6 @@ hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegsSmall &
                                const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream);
 
 // ---------------------------------------------------------------- attention ----------
-// Division of a 32-bit unsigned number by a divisor fixed on the host (round-up multiplier of
-// Granlund and Montgomery): n / d = (t + ((n - t) >> sh1)) >> sh2 with t = mulhi(n, mul).
-struct FastDiv {
-  uint32_t mul, sh1, sh2;
-};
-inline FastDiv make_fast_div(uint32_t d) {
-  FastDiv f;
-  uint32_t l = 0;
-  while ((1ull << l) < d) ++l;  // ceil(log2 d)
-  f.mul = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
-  f.sh1 = l < 1 ? l : 1;
-  f.sh2 = l > 0 ? l - 1 : 0;
-  return f;
-}
 
 constexpr int kProbeRecord = 16;
 constexpr int kTileRows = 256;  // packed (token, head-in-group) query rows per workgroup
@@ -157,19 +145,23 @@ struct AttnParams {
   FastDiv group_div;  // division by `group`
   float scale_log2e;  // softmax scale * log2(e)
   int32_t q_ready;    // q is already rotated and multiplied by scale_log2e (the RoPE pre-pass ran)
+  int32_t q_rows_fit32;  // main core, filled at the launch: 32 tokens and a group of heads of q span less than 2^32 bytes
   const float *q_table;  // else, if non-null: [tokens][D/2][2] = scale_log2e * (cos, sin) of each
                          // token's position times theta_j; the kernel rotates q with it
   int32_t rope_layout;
   const float *blk_rot;  // block table only: [blocks][D/2][2] (cos, sin) of minus each block's shift
   int32_t n_splits;
   int32_t use_cuts;            // split_cut holds unequal shares (see split_tile_range)
-  uint32_t split_cut[33];      // cumulative shares of the splits, 1 / 65536 units
+  uint32_t split_cut[kMaxCutHeads][33];  // per KV head: cumulative shares of its splits, 1 / 65536 units
   unsigned long long *wg_clock;  // probe only, else null: kProbeRecord numbers per workgroup:
                                  // [0] XCC id, [1] shader cycles and [2] 100 MHz ticks at entry, [4] and [5] the same
                                  // behind the walk, ticks [3] first tile copies issued, [6] first tiles and query
                                  // fragments landed, [7] loop entered, [8] partials' stores issued, [9] complete
   int32_t total_tiles;  // row tiles over all problems of this launch
-  FastDiv tiles_div;    // division by total_tiles (short-block schedule)
+  FastDiv tiles_div;    // division by total_tiles
+  int32_t kv_group;     // main core, filled at the launch: KV heads per group in the order of the work items
+  ItemDivs item_divs;   // ... and the divisors of item_coords
+  SplitDivs split_divs; // divisions by n_splits and 2 n_splits (main core; filled at the launch)
   float *lse;           // short-block schedule: [tokens][n_q_heads] log-sum-exp of the scaled scores, or null
 };
 

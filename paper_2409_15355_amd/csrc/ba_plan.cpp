@@ -115,36 +115,36 @@ int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, co
   return BA_OK;
 }
 
-int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, uint32_t cuts[33],
+int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, uint32_t cuts[kMaxCutHeads][33],
                         int32_t *use) {
   *use = 0;
-  for (int s = 0; s <= kMaxSplits; ++s) cuts[s] = 0;
+  for (int h = 0; h < kMaxCutHeads; ++h)
+    for (int s = 0; s <= kMaxSplits; ++s) cuts[h][s] = 0;
   if (!xcd_speed || n_splits <= 1 || tiles <= 0) return BA_OK;
   if (n_splits > kMaxSplits) return fail(BA_ERR_INVALID_ARG, "more than %d splits", kMaxSplits);
   for (int x = 0; x < kNumXcds; ++x)
     if (!(xcd_speed[x] >= 0.5f && xcd_speed[x] <= 2.0f))
       return fail(BA_ERR_INVALID_ARG, "xcd_speed[%d] = %g: relative speeds lie between 0.5 and 2", x, (double)xcd_speed[x]);
-  // XCD x runs the work items [lo_x, hi_x) (see work_item_of_workgroup); split s is the items
-  // [s m, (s + 1) m), m = tiles * n_kv_heads.  A split's speed = the mean speed over its items.
-  const int64_t m = tiles * n_kv_heads, n_wg = m * n_splits;
-  const int64_t q = n_wg / kNumXcds, r = n_wg % kNumXcds;
-  double w[kMaxSplits], total = 0.0;
-  for (int s = 0; s < n_splits; ++s) {
-    double sum = 0.0;
-    for (int x = 0; x < kNumXcds; ++x) {
-      const int64_t lo = x * q + std::min<int64_t>(x, r), hi = (x + 1) * q + std::min<int64_t>(x + 1, r);
-      const int64_t a = std::max<int64_t>(lo, s * m), b = std::min<int64_t>(hi, (s + 1) * m);
-      if (b > a) sum += (double)(b - a) * xcd_speed[x];
+  if (n_kv_heads > kMaxCutHeads || tiles * n_kv_heads * n_splits > 0x7fffffff) return BA_OK;  // equal splits
+  // The speed of (KV head, split) = the mean speed of the XCDs that run its row tiles (see item_id,
+  // xcd_of_work_item); a KV head's key range is shared out in proportion to its splits' speeds.
+  const ItemOrder order = {(int)tiles, n_kv_heads, n_splits, kv_group_of(n_kv_heads)};
+  const unsigned n_wg = (unsigned)(tiles * n_kv_heads * n_splits);
+  for (int h = 0; h < n_kv_heads; ++h) {
+    double w[kMaxSplits], total = 0.0;
+    for (int s = 0; s < n_splits; ++s) {
+      double sum = 0.0;
+      for (int64_t t = 0; t < tiles; ++t) sum += xcd_speed[xcd_of_work_item(item_id((int)t, h, s, order), n_wg)];
+      w[s] = sum / (double)tiles;
+      total += w[s];
     }
-    w[s] = sum / (double)m;
-    total += w[s];
+    double acc = 0.0;
+    for (int s = 0; s < n_splits; ++s) {
+      cuts[h][s] = (uint32_t)(acc / total * 65536.0 + 0.5);
+      acc += w[s];
+    }
+    for (int s = n_splits; s <= kMaxSplits; ++s) cuts[h][s] = 65536;
   }
-  double acc = 0.0;
-  for (int s = 0; s < n_splits; ++s) {
-    cuts[s] = (uint32_t)(acc / total * 65536.0 + 0.5);
-    acc += w[s];
-  }
-  for (int s = n_splits; s <= kMaxSplits; ++s) cuts[s] = 65536;
   *use = 1;
   return BA_OK;
 }
@@ -348,10 +348,14 @@ int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const 
     const int n = std::min(ba::kFinMaxPrompts, n_prompts - n0);
     ba::FinalMeta meta;
     const int64_t tiles = ba::build_final_meta(cu_q, cu_ctx, n0, n, G, &meta);
-    uint32_t cuts[33];
+    uint32_t cuts[ba::kMaxCutHeads][33];
     int32_t use_cuts = 0;
     if ((rc = ba::plan_split_cuts(heads->xcd_speed, tiles, heads->n_kv_heads, pl.n_splits, cuts, &use_cuts))) return rc;
-    // the kernel's own walk: every (split, row tile) of the launch, once per KV head
+    // the kernel's own walk: every (split, row tile) of the launch; the same at every KV head unless
+    // the splits are sized by XCD speed, when every KV head has shares of its own
+    const ba::ItemOrder order = {(int)tiles, heads->n_kv_heads, pl.n_splits, ba::kv_group_of(heads->n_kv_heads)};
+    const int64_t n_wg = tiles * heads->n_kv_heads * pl.n_splits;
+    for (int kvh = use_cuts ? 0 : -1; kvh < (use_cuts ? heads->n_kv_heads : 0); ++kvh)
     for (int split = 0; split < pl.n_splits; ++split)
       for (int64_t tile = 0; tile < tiles; ++tile) {
         const int i = ba::segment_of(meta.tile_start, meta.n, (int)tile);
@@ -361,7 +365,7 @@ int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const 
         const int last_row = std::min(n_rows, row0 + ba::kTileRows) - 1;
         const int n_ctx_tiles = (tctx + ba::kTileKeys - 1) / ba::kTileKeys;
         const int n_causal = ba::causal_key_tiles(last_row / G, ba::kTileKeys);
-        const ba::TileRange tr = ba::split_tile_range(n_ctx_tiles, n_causal, pl.n_splits, split, use_cuts ? cuts : nullptr);
+        const ba::TileRange tr = ba::split_tile_range(n_ctx_tiles, n_causal, pl.n_splits, split, use_cuts ? cuts[kvh] : nullptr);
         ba_work_item w;
         memset(&w, 0, sizeof(w));
         w.launch = launch;
@@ -373,6 +377,9 @@ int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const 
         w.row_end = last_row + 1;
         w.split = split;
         w.n_splits = pl.n_splits;
+        w.kv_head = kvh;
+        w.xcd = kvh >= 0 && n_wg <= 0x7fffffff
+                    ? ba::xcd_of_work_item(ba::item_id((int)tile, kvh, split, order), (unsigned)n_wg) : -1;
         w.ctx_begin = std::min(tctx, std::min(tr.begin, n_ctx_tiles) * ba::kTileKeys);
         w.ctx_end = std::min(tctx, std::min(tr.end, n_ctx_tiles) * ba::kTileKeys);
         w.self_begin = std::min(lq, std::max(0, tr.begin - n_ctx_tiles) * ba::kTileKeys);
@@ -408,6 +415,7 @@ int64_t ba_schedule_encode_blocks(const ba_heads *heads, int32_t n_blocks, const
         const int last_row = std::min(n_rows, row0 + tile_rows) - 1;
         ba_work_item w;
         memset(&w, 0, sizeof(w));
+        w.kv_head = w.xcd = -1;
         w.launch = launch;
         w.problem = b0 + i;
         w.first_token = meta[m].offs[i];
@@ -450,6 +458,7 @@ int64_t ba_schedule_prompts(const ba_heads *heads, int32_t n_prompts, const int3
       const int keys_walked = ((dq + last_row / G) / 32 + 1) * 32;
       ba_work_item w;
       memset(&w, 0, sizeof(w));
+      w.kv_head = w.xcd = -1;
       w.launch = launch;
       w.problem = blks[b0 + i].prompt;
       w.first_token = meta.start[i];

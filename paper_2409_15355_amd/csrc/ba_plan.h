@@ -52,7 +52,7 @@ int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, co
 // splits, one workgroup each) by the speed of the XCDs its workgroups run on: cuts[s] = where split s
 // begins, 1 / 65536 units (see split_tile_range).  xcd_speed: eight positive numbers or null.
 // *use = 0 when the splits stay equal (no speeds, one split).  BA_ERR_INVALID_ARG on bad speeds.
-int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, uint32_t cuts[33],
+int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, uint32_t cuts[kMaxCutHeads][33],
                         int32_t *use);
 // The table of one final-block launch: prompts [n0, n0 + n).  Returns its row tiles.
 int64_t build_final_meta(const int32_t *cu_q, const int32_t *cu_ctx, int n0, int n, int G, FinalMeta *meta);

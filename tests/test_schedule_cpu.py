@@ -20,7 +20,20 @@ def lib():
 
 def coverage_of(items, G, problem_rows):
     """count[problem][token, key] over the items; keys = (context keys..., own tokens...).
-    problem_rows: {problem: (n_ctx_keys, n_tokens)}.  Also checks the per-item invariants."""
+    problem_rows: {problem: (n_ctx_keys, n_tokens)}.  Also checks the per-item invariants.
+    Items that name their KV head (splits sized by XCD speed) are checked head by head: every head's
+    items must give the same, complete coverage."""
+    heads_named = sorted({w.kv_head for w in items})
+    if heads_named and heads_named != [-1]:
+        assert -1 not in heads_named
+        covs = [_coverage_of([w for w in items if w.kv_head == h], G, problem_rows) for h in heads_named]
+        for c in covs[1:]:
+            assert all(np.array_equal(c[p], covs[0][p]) for p in c)
+        return covs[0]
+    return _coverage_of(items, G, problem_rows)
+
+
+def _coverage_of(items, G, problem_rows):
     cov = {p: np.zeros((lq, tc + lq), dtype=np.int32) for p, (tc, lq) in problem_rows.items()}
     seen_rows = {p: np.zeros(lq * G, dtype=np.int32) for p, (tc, lq) in problem_rows.items()}
     for w in items:
@@ -205,16 +218,27 @@ def test_splits_sized_by_xcd_speed_still_cover_the_mask_exactly(speeds):
         for p in range(n_prompts):
             assert np.array_equal(cov[p], expected_final(tcs[p], lqs[p], 4)), (case, p, lqs, tcs)
         if case == 0:
-            # config 5: split s runs on XCD s; its share of the key tiles follows that XCD's speed
-            tiles = [sum(w.ctx_end - w.ctx_begin + w.self_end - w.self_begin for w in items if w.split == s and w.row_begin == 0) // 64
-                     for s in range(8)]
-            if len(set(speeds)) == 1:
-                assert max(tiles[:7]) - min(tiles[:7]) <= 1
-            else:
-                order = np.argsort(speeds[:7])
-                assert tiles[order[0]] < tiles[order[-1]]
-                share = np.array(tiles[:7], dtype=float) / np.array(speeds[:7])
-                assert share.max() / share.min() < 1.06   # equal time per split, to a tile
+            # config 5: 256 workgroups; the splits of a KV head lie on the two XCDs of its pair of heads,
+            # four on each, and a split's share of the key tiles follows the speed of the XCD that runs it
+            assert sorted({w.kv_head for w in items}) == list(range(8))
+            for kvh in range(8):
+                mine = [w for w in items if w.kv_head == kvh and w.row_begin == 0]
+                assert [w.split for w in sorted(mine, key=lambda w: w.split)] == list(range(8))
+                assert {w.xcd for w in mine} == {2 * (kvh // 2), 2 * (kvh // 2) + 1}
+                assert all(w.xcd == 2 * (kvh // 2) + (w.split >= 4) for w in mine)
+                tiles = {w.split: (w.ctx_end - w.ctx_begin + w.self_end - w.self_begin) // 64 for w in mine}
+                sp = {w.split: speeds[w.xcd] for w in mine}
+                if len(set(speeds)) == 1:
+                    assert max(tiles[s] for s in range(7)) - min(tiles[s] for s in range(7)) <= 1
+                else:
+                    share = np.array([tiles[s] / sp[s] for s in range(7)])
+                    assert share.max() / share.min() < 1.06   # equal time per split, to a tile
+                    if sp[0] != sp[4]:
+                        assert (tiles[0] < tiles[4]) == (sp[0] < sp[4])
+            # every row tile of a (KV head, split) runs on the same XCD: they share its K/V tiles
+            for kvh in range(8):
+                for s_ in range(8):
+                    assert len({w.xcd for w in items if w.kv_head == kvh and w.split == s_}) == 1
 
 
 def test_bad_xcd_speeds_are_rejected():
