@@ -1046,7 +1046,8 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
     ap.tile_base = (int32_t)tile_base;
     tile_base += tiles;
     ap.total_tiles = (int32_t)tiles;
-    if ((rc = ba::plan_split_cuts(heads->xcd_speed, tiles, heads->n_kv_heads, pl.n_splits, ap.split_cut, &ap.use_cuts)))
+    if ((rc = ba::plan_split_cuts(heads->xcd_speed, tiles, heads->n_kv_heads, pl.n_splits, pl.max_nt, num_cus(),
+                                  ba::final_q_bytes_per_kv_head(heads, pl.lq_total), ap.split_cut, &ap.use_cuts, &ap.kv_group)))
       return rc;
     if (rope_mode == BA_ROPE_APPLY) {  // absolute positions of the final block's tokens
       if ((rc = run_rope_prepass(heads, rt, q_f, q_ws, k_f, &kf_use, n, meta.cu_q, pos0.data() + n0, stream)))
@@ -1138,6 +1139,7 @@ struct BlocksCall {
   int32_t n_prompts;
   const int32_t *cu_q, *cu_blk, *blk_tok_off, *blk_len, *blk_old_pos0, *blk_new_pos0, *q_pos0;
   hipStream_t stream;
+  int max_nt;  // longest walk of the call, key tiles
 };
 
 // Launches of at most MetaT::kPrompts prompts and MetaT::kBlocks non-empty blocks each: the RoPE
@@ -1193,7 +1195,9 @@ int32_t run_final_blocks(const BlocksCall &c, ba::AttnParams ap) {
     ap.tile_base = (int32_t)tile_base;
     tile_base += tiles;
     {
-      int32_t rc_cuts = ba::plan_split_cuts(c.heads->xcd_speed, tiles, c.heads->n_kv_heads, ap.n_splits, ap.split_cut, &ap.use_cuts);
+      int32_t rc_cuts = ba::plan_split_cuts(c.heads->xcd_speed, tiles, c.heads->n_kv_heads, ap.n_splits, c.max_nt, num_cus(),
+                                            ba::final_q_bytes_per_kv_head(c.heads, c.cu_q[c.n_prompts]), ap.split_cut,
+                                            &ap.use_cuts, &ap.kv_group);
       if (rc_cuts) return rc_cuts;
     }
     const ba::RopeRots *big = nullptr;
@@ -1395,7 +1399,7 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
   ap.n_splits = pl.n_splits;
 
   BlocksCall call{heads, &rt, q_f, q_ws, k_f, &kf_use, rot_ws, n_prompts, cu_q, cu_blk, blk_tok_off, blk_len,
-                  blk_old_pos0, blk_new_pos0, q_pos0, stream};
+                  blk_old_pos0, blk_new_pos0, q_pos0, stream, pl.max_nt};
   if (n_prompts <= ba::kBlkSmallPrompts && pl.n_blocks <= ba::kBlkSmallBlocks)
     rc = run_final_blocks<ba::FinalBlocksMetaSmall, ba::RopeRotsSmall>(call, ap);
   else

@@ -115,27 +115,23 @@ int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, co
   return BA_OK;
 }
 
-int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, uint32_t cuts[kMaxCutHeads][33],
-                        int32_t *use) {
-  *use = 0;
-  for (int h = 0; h < kMaxCutHeads; ++h)
-    for (int s = 0; s <= kMaxSplits; ++s) cuts[h][s] = 0;
-  if (!xcd_speed || n_splits <= 1 || tiles <= 0) return BA_OK;
-  if (n_splits > kMaxSplits) return fail(BA_ERR_INVALID_ARG, "more than %d splits", kMaxSplits);
-  for (int x = 0; x < kNumXcds; ++x)
-    if (!(xcd_speed[x] >= 0.5f && xcd_speed[x] <= 2.0f))
-      return fail(BA_ERR_INVALID_ARG, "xcd_speed[%d] = %g: relative speeds lie between 0.5 and 2", x, (double)xcd_speed[x]);
-  if (n_kv_heads > kMaxCutHeads || tiles * n_kv_heads * n_splits > 0x7fffffff) return BA_OK;  // equal splits
-  // The speed of (KV head, split) = the mean speed of the XCDs that run its row tiles (see item_id,
-  // xcd_of_work_item); a KV head's key range is shared out in proportion to its splits' speeds.
-  const ItemOrder order = {(int)tiles, n_kv_heads, n_splits, kv_group_of(n_kv_heads)};
+namespace {
+// Cut lists of one candidate order of the work items, and how long its launch is expected to take,
+// in tile periods of a workgroup: an XCD is done when its longest item is, or when its compute
+// units have worked through all its items, whichever is later; before that it fetches the query
+// rows of the KV heads it hosts (about a megabyte per microsecond and XCD, a tile period being 1.6).
+double try_kv_group(const float *speed, int64_t tiles, int n_kv_heads, int n_splits, int kv_group, int max_nt, int n_cu,
+                    double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33]) {
+  const ItemOrder order = {(int)tiles, n_kv_heads, n_splits, kv_group};
   const unsigned n_wg = (unsigned)(tiles * n_kv_heads * n_splits);
+  double longest[kNumXcds] = {0}, sum[kNumXcds] = {0};
+  bool hosts[kNumXcds][kMaxCutHeads] = {};
   for (int h = 0; h < n_kv_heads; ++h) {
     double w[kMaxSplits], total = 0.0;
     for (int s = 0; s < n_splits; ++s) {
-      double sum = 0.0;
-      for (int64_t t = 0; t < tiles; ++t) sum += xcd_speed[xcd_of_work_item(item_id((int)t, h, s, order), n_wg)];
-      w[s] = sum / (double)tiles;
+      double acc = 0.0;
+      for (int64_t t = 0; t < tiles; ++t) acc += speed[xcd_of_work_item(item_id((int)t, h, s, order), n_wg)];
+      w[s] = acc / (double)tiles;
       total += w[s];
     }
     double acc = 0.0;
@@ -144,7 +140,59 @@ int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, i
       acc += w[s];
     }
     for (int s = n_splits; s <= kMaxSplits; ++s) cuts[h][s] = 65536;
+    for (int s = 0; s < n_splits; ++s) {
+      const double item_tiles = (double)max_nt * (double)(cuts[h][s + 1] - cuts[h][s]) / 65536.0;
+      for (int64_t t = 0; t < tiles; ++t) {
+        const int x = xcd_of_work_item(item_id((int)t, h, s, order), n_wg);
+        longest[x] = std::max(longest[x], item_tiles);
+        sum[x] += item_tiles;
+        hosts[x][h] = true;
+      }
+    }
   }
+  const double cu_per_xcd = std::max(1.0, (double)n_cu / kNumXcds);
+  double worst = 0.0;
+  for (int x = 0; x < kNumXcds; ++x) {
+    int hosted = 0;
+    for (int h = 0; h < n_kv_heads; ++h) hosted += hosts[x][h];
+    const double fetch = hosted * q_bytes_per_kv_head / 1.0e6 / 1.6;
+    worst = std::max(worst, std::max(longest[x], sum[x] / cu_per_xcd) / (double)speed[x] + fetch);
+  }
+  return worst;
+}
+}  // namespace
+
+int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, int max_nt, int n_cu,
+                        double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33], int32_t *use, int32_t *kv_group) {
+  *use = 0;
+  *kv_group = kv_group_of(n_kv_heads);
+  for (int h = 0; h < kMaxCutHeads; ++h)
+    for (int s = 0; s <= kMaxSplits; ++s) cuts[h][s] = 0;
+  if (!xcd_speed || n_splits <= 1 || tiles <= 0) return BA_OK;
+  if (n_splits > kMaxSplits) return fail(BA_ERR_INVALID_ARG, "more than %d splits", kMaxSplits);
+  for (int x = 0; x < kNumXcds; ++x)
+    if (!(xcd_speed[x] >= 0.5f && xcd_speed[x] <= 2.0f))
+      return fail(BA_ERR_INVALID_ARG, "xcd_speed[%d] = %g: relative speeds lie between 0.5 and 2", x, (double)xcd_speed[x]);
+  if (n_kv_heads > kMaxCutHeads || tiles * n_kv_heads * n_splits > 0x7fffffff) return BA_OK;  // equal splits
+  // The speed of (KV head, split) = the mean speed of the XCDs that run its row tiles (item_id,
+  // xcd_of_work_item), and a KV head's key range is shared out in proportion to its splits' speeds.
+  // How far that can even out the XCDs depends on the order of the work items: with small groups of
+  // KV heads an XCD fetches few query rows but shares a KV head with few other XCDs; with one group
+  // of all KV heads every XCD fetches every query row and all of them can be balanced against each
+  // other.  Every group size (a power of two that divides the KV heads, or all of them) is tried.
+  double best = 0.0;
+  int best_group = 0;
+  for (int g = 1; g <= n_kv_heads; g = (2 * g <= n_kv_heads || g == n_kv_heads) ? 2 * g : n_kv_heads) {
+    if (n_kv_heads % g) continue;
+    uint32_t trial[kMaxCutHeads][33];
+    const double t = try_kv_group(xcd_speed, tiles, n_kv_heads, n_splits, g, std::max(1, max_nt), n_cu, q_bytes_per_kv_head, trial);
+    if (!best_group || t < best - 1e-9) {
+      best = t;
+      best_group = g;
+      memcpy(cuts, trial, sizeof(trial));
+    }
+  }
+  *kv_group = best_group;
   *use = 1;
   return BA_OK;
 }
@@ -350,10 +398,13 @@ int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const 
     const int64_t tiles = ba::build_final_meta(cu_q, cu_ctx, n0, n, G, &meta);
     uint32_t cuts[ba::kMaxCutHeads][33];
     int32_t use_cuts = 0;
-    if ((rc = ba::plan_split_cuts(heads->xcd_speed, tiles, heads->n_kv_heads, pl.n_splits, cuts, &use_cuts))) return rc;
+    int32_t kv_group = 0;
+    if ((rc = ba::plan_split_cuts(heads->xcd_speed, tiles, heads->n_kv_heads, pl.n_splits, pl.max_nt, n_compute_units,
+                                  ba::final_q_bytes_per_kv_head(heads, pl.lq_total), cuts, &use_cuts, &kv_group)))
+      return rc;
     // the kernel's own walk: every (split, row tile) of the launch; the same at every KV head unless
     // the splits are sized by XCD speed, when every KV head has shares of its own
-    const ba::ItemOrder order = {(int)tiles, heads->n_kv_heads, pl.n_splits, ba::kv_group_of(heads->n_kv_heads)};
+    const ba::ItemOrder order = {(int)tiles, heads->n_kv_heads, pl.n_splits, kv_group};
     const int64_t n_wg = tiles * heads->n_kv_heads * pl.n_splits;
     for (int kvh = use_cuts ? 0 : -1; kvh < (use_cuts ? heads->n_kv_heads : 0); ++kvh)
     for (int split = 0; split < pl.n_splits; ++split)

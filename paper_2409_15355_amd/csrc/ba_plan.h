@@ -48,12 +48,19 @@ struct FinalPlan {
 };
 int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, const int32_t *cu_ctx,
                    int32_t rope_mode, bool have_rot_out, int n_cu, FinalPlan *plan);
-// Shares of the KV splits of one final-block launch (tiles row tiles x n_kv_heads KV heads x n_splits
-// splits, one workgroup each) by the speed of the XCDs its workgroups run on: cuts[s] = where split s
-// begins, 1 / 65536 units (see split_tile_range).  xcd_speed: eight positive numbers or null.
-// *use = 0 when the splits stay equal (no speeds, one split).  BA_ERR_INVALID_ARG on bad speeds.
-int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, uint32_t cuts[kMaxCutHeads][33],
-                        int32_t *use);
+// Order of the work items and shares of the KV splits of one final-block launch (tiles row tiles x
+// n_kv_heads KV heads x n_splits splits, one workgroup each; the longest walk is max_nt key tiles) on
+// a device of n_cu compute units.  xcd_speed: eight positive numbers or null.  With speeds the
+// splits of every KV head are sized by the speed of the XCDs that run them: cuts[h][s] = where split s
+// of KV head h begins, 1 / 65536 units (see split_tile_range), and *kv_group (see ItemOrder) is the
+// group size under which the launch is expected to end soonest.  *use = 0 when the splits stay equal
+// (no speeds, one split, too many KV heads): then *kv_group is the default.  BA_ERR_INVALID_ARG on
+// bad speeds.  q_bytes_per_kv_head: the query rows a workgroup's XCD fetches per KV head it hosts.
+int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, int max_nt, int n_cu,
+                        double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33], int32_t *use, int32_t *kv_group);
+inline double final_q_bytes_per_kv_head(const ba_heads *h, int64_t lq_total) {
+  return (double)lq_total * (h->n_q_heads / h->n_kv_heads) * h->head_dim * 2.0;
+}
 // The table of one final-block launch: prompts [n0, n0 + n).  Returns its row tiles.
 int64_t build_final_meta(const int32_t *cu_q, const int32_t *cu_ctx, int n0, int n, int G, FinalMeta *meta);
 

@@ -93,9 +93,9 @@ BA_HD TileRange split_tile_range(int n_ctx_tiles, int n_causal_tiles, int n_spli
 // split) pairs are ordered by group of kv_group KV heads, then split, then head inside the group.
 // With XCD-aware numbering of the workgroups (below) an XCD then runs a contiguous range of splits
 // of ONE group of KV heads, so it fetches the query rows of that group only (at config 5, with
-// groups of two: 512 KB instead of the whole 2 MB, which every XCD fetching at once at the start of
-// a launch cost two microseconds), while the splits of a KV head still lie on more than one XCD, so
-// that their sizes can follow those XCDs' speeds.
+// groups of one: 256 KB instead of the whole 2 MB, which every XCD fetching at once at the start of
+// a launch cost two microseconds); with larger groups the splits of a KV head lie on more than one
+// XCD, so that their sizes can follow those XCDs' speeds (the planner weighs the two).
 struct ItemOrder {
   int n_rowtiles, n_kv_heads, n_splits, kv_group;  // kv_group divides n_kv_heads
 };
@@ -105,7 +105,8 @@ struct ItemDivs {
 struct ItemCoords {
   int rowtile, kvh, split;
 };
-BA_HD int kv_group_of(int n_kv_heads) { return n_kv_heads % 2 == 0 ? 2 : 1; }
+// (the default, when nothing is known of the XCDs' speeds: an XCD fetches as few query rows as the order allows)
+BA_HD int kv_group_of(int n_kv_heads) { return n_kv_heads > 0 ? 1 : 1; }
 inline ItemDivs make_item_divs(const ItemOrder &o) {
   ItemDivs d;
   d.by_rowtiles = make_fast_div((unsigned)(o.n_rowtiles > 0 ? o.n_rowtiles : 1));

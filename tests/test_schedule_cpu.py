@@ -218,14 +218,16 @@ def test_splits_sized_by_xcd_speed_still_cover_the_mask_exactly(speeds):
         for p in range(n_prompts):
             assert np.array_equal(cov[p], expected_final(tcs[p], lqs[p], 4)), (case, p, lqs, tcs)
         if case == 0:
-            # config 5: 256 workgroups; the splits of a KV head lie on the two XCDs of its pair of heads,
-            # four on each, and a split's share of the key tiles follows the speed of the XCD that runs it
+            # config 5: 256 workgroups; a split's share of its KV head's key tiles follows the speed of the XCD
+            # that runs it (which XCDs a KV head's splits lie on is the planner's choice)
             assert sorted({w.kv_head for w in items}) == list(range(8))
             for kvh in range(8):
                 mine = [w for w in items if w.kv_head == kvh and w.row_begin == 0]
                 assert [w.split for w in sorted(mine, key=lambda w: w.split)] == list(range(8))
-                assert {w.xcd for w in mine} == {2 * (kvh // 2), 2 * (kvh // 2) + 1}
-                assert all(w.xcd == 2 * (kvh // 2) + (w.split >= 4) for w in mine)
+                if len(set(speeds)) == 1:
+                    assert {w.xcd for w in mine} == {kvh}   # nothing to balance: an XCD fetches one KV head's query rows
+                else:
+                    assert len({w.xcd for w in mine}) >= 2  # a KV head's splits lie on XCDs that can be balanced against each other
                 tiles = {w.split: (w.ctx_end - w.ctx_begin + w.self_end - w.self_begin) // 64 for w in mine}
                 sp = {w.split: speeds[w.xcd] for w in mine}
                 if len(set(speeds)) == 1:
