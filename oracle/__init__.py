@@ -310,11 +310,15 @@ def masked_attention_backward_bruteforce(q, k, v, d_out, offs, th, *, scale=None
 
 def masked_attention_backward_term_sums(q, k, v, d_out, offs, th, *, scale=None, layout=LAYOUT_INTERLEAVED):
     """For every element of the gradients that masked_attention_backward_bruteforce returns, the sum
-    of the ABSOLUTE values of the products it is the sum of (dV = sum_i P_ij dO_i, dq^ = scale sum_j
-    dS_ij k^_j, dk^ = scale sum_i dS_ij q^_i).  Not a gradient: the scale a rounding-error bound is
-    stated against (|fl(sum a_i b_i) - sum a_i b_i| <= eps sum |a_i b_i|).  dq and dk are turned back
-    by an orthogonal map of each dimension pair, so both members of a pair get the pair's Euclidean
-    norm of the rotated-frame sums.  Returns (aq, ak, av).  Tiny inputs only."""
+    of the ABSOLUTE values of the products it is the sum of: dV = sum_i P_ij dO_i; dq^ = scale sum_j
+    dS_ij k^_j and dk^ = scale sum_i dS_ij q^_i, where dS_ij = P_ij (sum_d dO_id v_jd - sum_d dO_id
+    O_id) is itself a sum of products, so that its share is P_ij (sum_d |dO_id v_jd| + sum_d |dO_id
+    O_id|): what does not cancel when the two inner sums nearly do (a row that sees one key has
+    dS = 0 exactly, and an error in either inner sum still reaches dq in full).  Not a gradient: the
+    scale a rounding-error bound is stated against (|fl(sum a_i b_i) - sum a_i b_i| <= eps sum
+    |a_i b_i|).  dq and dk are turned back by an orthogonal map of each dimension pair, so both
+    members of a pair get the pair's Euclidean norm of the rotated-frame sums.  Returns (aq, ak, av).
+    Tiny inputs only."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
@@ -336,10 +340,11 @@ def masked_attention_backward_term_sums(q, k, v, d_out, offs, th, *, scale=None,
         E = np.exp(S - S.max(axis=1, keepdims=True))
         P = E / E.sum(axis=1, keepdims=True)
         dO = d_out[:, h, :]
-        dS = P * (dO @ v[:, g, :].T - (dO * (P @ v[:, g, :])).sum(axis=1, keepdims=True))
+        O = P @ v[:, g, :]
+        abs_dS = P * (np.abs(dO) @ np.abs(v[:, g, :]).T + (np.abs(dO) * np.abs(O)).sum(axis=1, keepdims=True))
         av[:, g, :] += P.T @ np.abs(dO)
-        aq[:, h, :] = sc * (np.abs(dS) @ np.abs(kr[:, g, :]))
-        ak[:, g, :] += sc * (np.abs(dS).T @ np.abs(qr[:, h, :]))
+        aq[:, h, :] = sc * (abs_dS @ np.abs(kr[:, g, :]))
+        ak[:, g, :] += sc * (abs_dS.T @ np.abs(qr[:, h, :]))
 
     def pair_norm(a):
         if layout == LAYOUT_HALF:

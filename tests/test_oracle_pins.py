@@ -548,3 +548,28 @@ def test_backward_term_sums_bound_the_gradients_and_are_tight_for_one_sign():
         _, _, dv_pos, _ = oracle.masked_attention_backward_bruteforce(q, k, v, do_pos, offs, th, layout=layout)
         _, _, av_pos = oracle.masked_attention_backward_term_sums(q, k, v, do_pos, offs, th, layout=layout)
         assert np.allclose(dv_pos, av_pos, rtol=1e-12, atol=1e-12)
+    # dq and dk: every product written out in loops, on a case small enough for that (one KV head,
+    # two query heads; softmax and output recomputed here from the rotated rows)
+    T, hq, d = 5, 2, 4
+    offs = [0, 2, 5]
+    th = oracle.theta(10000.0, d)
+    q, k, v, do = rng.standard_normal((T, hq, d)), rng.standard_normal((T, 1, d)), rng.standard_normal((T, 1, d)), rng.standard_normal((T, hq, d))
+    aq, ak, _ = oracle.masked_attention_backward_term_sums(q, k, v, do, offs, th)
+    qr, kr = oracle.rope_dense(q, np.arange(T), th, oracle.LAYOUT_INTERLEAVED), oracle.rope_dense(k, np.arange(T), th, oracle.LAYOUT_INTERLEAVED)
+    mask, sc = oracle.block_mask(offs), 1.0 / np.sqrt(d)
+    want_q, want_k = np.zeros((T, hq, d)), np.zeros((T, 1, d))
+    for h in range(hq):
+        for i in range(T):
+            vis = [j for j in range(T) if mask[i, j]]
+            e = np.array([np.exp(sc * float(qr[i, h] @ kr[j, 0])) for j in vis])
+            prob = e / e.sum()
+            out = sum(pj * v[j, 0] for pj, j in zip(prob, vis))
+            for pj, j in zip(prob, vis):
+                share = pj * sum(abs(do[i, h, c] * v[j, 0, c]) + abs(do[i, h, c] * out[c]) for c in range(d))
+                for c in range(d):
+                    want_q[i, h, c] += sc * share * abs(kr[j, 0, c])
+                    want_k[j, 0, c] += sc * share * abs(qr[i, h, c])
+    pn = lambda x: np.repeat(np.sqrt(x[..., 0::2] ** 2 + x[..., 1::2] ** 2), 2, axis=-1)
+    assert np.allclose(aq, pn(want_q), rtol=1e-10) and np.allclose(ak, pn(want_k), rtol=1e-10)
+    # a row that sees a single key: its dS is zero, its share of the term sums is not
+    assert (aq[0] > 0).all() and (aq[2] > 0).all()
