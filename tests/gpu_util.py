@@ -73,5 +73,8 @@ def assert_reencode_bf16(got_bits: np.ndarray, ref_f64: np.ndarray, layout: int,
     if roundings > 1:
         return
     exact = wl.f32_to_bf16_bits(ref_f64.astype(np.float32))
-    frac = float((exact == got_bits).mean())
-    assert frac > 0.995, f"{what}: only {frac:.4f} of elements equal the rounded oracle value"
+    # (a fraction of few elements is coarse: one element in 128 is already 0.8 %, so small tensors may
+    # have two elements on the other side of a rounding boundary)
+    wrong = int((exact != got_bits).sum())
+    frac = 1.0 - wrong / exact.size
+    assert frac > 0.995 or wrong <= 2, f"{what}: only {frac:.4f} of elements equal the rounded oracle value"
