@@ -526,8 +526,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
   //     half-period   -1      0        1            2            3         ...
   //     waves 0..3   QK(0)  SM(0)  PV(0) QK(1)    SM(1)      PV(1) QK(2)
   //     waves 4..7     -    QK(0)    SM(0)     PV(0) QK(1)     SM(1)
-  // Waves 0..3 fetch K(i+3) and waves 4..7 V(i+3) from inside their MFMA block of iteration i; at
-  // the end of its softmax half a wave waits until the tile it started two iterations earlier
+  // Waves 0..3 fetch K(i+3) and waves 4..7 V(i+3) in the softmax half of iteration i; at
+  // the end of that half a wave waits until the tile it started two iterations earlier
   // (K(i+1) resp. V(i+1)) has landed, and the barrier that ends the half-period publishes it.  A
   // buffer is refilled only after the barrier that follows its last reader.
   Cursor cp = cursor_at(t_begin);  // the next tile to copy
