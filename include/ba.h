@@ -110,7 +110,8 @@ size_t ba_measure_xcd_speed_workspace_bytes(void);
  * (Section 2.5's step at 256 query tokens over 31,744 context tokens, 32 / 8 heads of 128: one
  * workgroup per compute unit, 8 KV splits of 62 or 63 key tiles).  The same synthetic run as
  * ba_measure_xcd_speed, same workspace; wave 0 of every workgroup reads the 100 MHz real-time counter
- * at its phase boundaries.  xcd_speed: host, nullable: eight figures as in ba_heads.xcd_speed, the
+ * at its phase boundaries (means over four launches, after three that bring the clocks to their
+ * steady state).  xcd_speed: host, nullable: eight figures as in ba_heads.xcd_speed, the
  * splits of the timed launch are sized by them (null: equal splits).
  * phases_us, microseconds, means over the workgroups unless noted:
  *   [0] kernel entry (first arguments loaded) -> first three tile copies issued

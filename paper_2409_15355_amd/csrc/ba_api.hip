@@ -1421,7 +1421,8 @@ int32_t ba_final_block_attention_cached(const ba_heads *heads, const ba_tensor *
 // ------------------------------------------------------------------------------------------
 // Calibration: relative XCD speeds under the attention core's load (ba_heads.xcd_speed).
 namespace {
-constexpr int kProbeCtx = 31744, kProbeLq = 256, kProbeHq = 32, kProbeHkv = 8, kProbeD = 128, kProbeRuns = 4;
+constexpr int kProbeCtx = 31744, kProbeLq = 256, kProbeHq = 32, kProbeHkv = 8, kProbeD = 128;
+constexpr int kProbeWarmRuns = 3, kProbeRuns = 4;  // launches to reach the steady clock, then launches that are read
 constexpr int kProbeMaxWg = 4096;
 ba_heads probe_heads() {
   ba_heads h;
@@ -1442,7 +1443,7 @@ ProbeLayout probe_layout() {
   l.kv_bytes = align256((size_t)kProbeCtx * kProbeHkv * kProbeD * 2);
   l.q_bytes = align256((size_t)kProbeLq * kProbeHq * kProbeD * 2);
   l.kvf_bytes = align256((size_t)kProbeLq * kProbeHkv * kProbeD * 2);
-  l.clock_bytes = align256((size_t)kProbeMaxWg * ba::kProbeRecord * sizeof(unsigned long long));
+  l.clock_bytes = align256((size_t)kProbeMaxWg * ba::kProbeRecord * sizeof(unsigned long long) * kProbeRuns);
   const ba_heads h = probe_heads();
   const int32_t cu_q[2] = {0, kProbeLq}, cu_ctx[2] = {0, kProbeCtx};
   l.final_bytes = align256(ba_final_block_attention_workspace_bytes(&h, 1, cu_q, cu_ctx, BA_ROPE_NONE, 0));
@@ -1453,8 +1454,10 @@ ProbeLayout probe_layout() {
 extern "C" size_t ba_measure_xcd_speed_workspace_bytes(void) { return probe_layout().total(); }
 
 namespace {
-// Runs the probe launches and reads the workgroups' records back (empty: the launch has a shape
-// there is nothing to learn from).  Synchronises the stream.
+// Runs the probe launches and reads the workgroups' records back: kProbeRuns launches' worth, one
+// after the other in *rec (the clocks of the XCDs drift by a few per cent from launch to launch, so
+// one launch alone is a noisy sample).  Empty: the launch has a shape there is nothing to learn from.
+// Synchronises the stream.
 int32_t run_probe(void *ws, size_t ws_bytes, void *stream_, const float *xcd_speed, std::vector<unsigned long long> *rec,
                   int64_t *n_wg_out) {
   hipStream_t stream = (hipStream_t)stream_;
@@ -1489,18 +1492,23 @@ int32_t run_probe(void *ws, size_t ws_bytes, void *stream_, const float *xcd_spe
   if (e != hipSuccess) return device_fail(e, "final-block probe: fill");
   const int32_t cu_q[2] = {0, kProbeLq}, cu_ctx[2] = {0, kProbeCtx};
   int32_t rc = BA_OK;
-  g_probe_clock = clk;
-  for (int run = 0; run < kProbeRuns && rc == BA_OK; ++run)  // (the later runs are at the steady clock; the last one's readings stay)
-    rc = ba_final_block_attention(&h, &q, &kc, &vc, &kf, &vf, &o, nullptr, 1, cu_q, cu_ctx, nullptr, BA_ROPE_NONE, wp,
-                                  l.final_bytes, stream_);
-  g_probe_clock = nullptr;
-  if (rc) return rc;
   ba::FinalPlan pl;
   if ((rc = ba::plan_final(&h, 1, cu_q, cu_ctx, BA_ROPE_NONE, false, num_cus(), &pl))) return rc;
   const int64_t n_wg = pl.total_tiles * kProbeHkv * pl.n_splits;
+  const bool readable = n_wg >= ba::kNumXcds && n_wg <= kProbeMaxWg;
+  const size_t per_run = (size_t)n_wg * ba::kProbeRecord;
+  if (readable) rec->resize(per_run * kProbeRuns);
+  // (back to back, as a caller's layers run: a pause between launches lets the clocks recover and
+  // shows a faster part than the one that does the work; every measured launch has records of its own)
+  for (int run = 0; run < kProbeWarmRuns + kProbeRuns && rc == BA_OK; ++run) {
+    g_probe_clock = run >= kProbeWarmRuns && readable ? clk + per_run * (run - kProbeWarmRuns) : nullptr;
+    rc = ba_final_block_attention(&h, &q, &kc, &vc, &kf, &vf, &o, nullptr, 1, cu_q, cu_ctx, nullptr, BA_ROPE_NONE, wp,
+                                  l.final_bytes, stream_);
+    g_probe_clock = nullptr;
+  }
+  if (rc) return rc;
   if ((e = hipStreamSynchronize(stream)) != hipSuccess) return device_fail(e, "final-block probe: synchronize");
-  if (n_wg < ba::kNumXcds || n_wg > kProbeMaxWg) return BA_OK;
-  rec->resize((size_t)n_wg * ba::kProbeRecord);
+  if (!readable) return BA_OK;
   if ((e = hipMemcpy(rec->data(), clk, rec->size() * sizeof(unsigned long long), hipMemcpyDeviceToHost)) != hipSuccess)
     return device_fail(e, "final-block probe: read-back");
   *n_wg_out = n_wg;
@@ -1524,9 +1532,9 @@ extern "C" int32_t ba_measure_xcd_speed(float speed_out[8], void *ws, size_t ws_
     if (n_wg == 0) return BA_OK;  // nothing to learn from such a launch: equal speeds
     double sum[ba::kNumXcds] = {0}, total = 0.0;
     int cnt[ba::kNumXcds] = {0};
-    for (int64_t wg = 0; wg < n_wg; ++wg) {
-      const unsigned long long *r = &rec[(size_t)wg * ba::kProbeRecord];
-      const int x = ba::xcd_of_workgroup((unsigned)wg);
+    for (int64_t i = 0; i < n_wg * kProbeRuns; ++i) {
+      const unsigned long long *r = &rec[(size_t)i * ba::kProbeRecord];
+      const int x = ba::xcd_of_workgroup((unsigned)(i % n_wg));
       if ((int)r[0] != x || r[5] <= r[2]) return BA_OK;  // not the mapping the planner assumes: equal speeds
       sum[x] += (double)(r[5] - r[2]);
       ++cnt[x];
@@ -1559,29 +1567,30 @@ extern "C" int32_t ba_diag_final_block_phases(double phases_us[BA_DIAG_PHASES], 
   int64_t n_wg = 0;
   if (int32_t rc = run_probe(ws, ws_bytes, stream_, xcd_speed, &rec, &n_wg)) return rc;
   if (n_wg == 0) return fail(BA_ERR_UNSUPPORTED, "final-block phases: this device's launch is not the shape the probe times");
-  unsigned long long first = ~0ull, last = 0;
-  for (int64_t wg = 0; wg < n_wg; ++wg) {
-    const unsigned long long *r = &rec[(size_t)wg * ba::kProbeRecord];
-    if (!(r[2] <= r[3] && r[3] <= r[6] && r[6] <= r[7] && r[7] <= r[5] && r[5] <= r[8] && r[8] <= r[9]))
-      return fail(BA_ERR_DEVICE, "final-block phases: workgroup %lld left marks out of order", (long long)wg);
-    first = std::min(first, r[2]);
-    last = std::max(last, r[9]);
-  }
+  // means over the launches that were read; per launch: its own first entry and last store
   const double tick_us = 0.01;  // the real-time counter runs at 100 MHz
-  double longest_walk = 0.0;
-  for (int64_t wg = 0; wg < n_wg; ++wg) {
-    const unsigned long long *r = &rec[(size_t)wg * ba::kProbeRecord];
-    phases_us[0] += (double)(r[3] - r[2]);
-    phases_us[1] += (double)(r[6] - r[3]);
-    phases_us[2] += (double)(r[7] - r[6]);
-    phases_us[3] += (double)(r[5] - r[7]);
-    phases_us[4] += (double)(r[9] - r[5]);
-    phases_us[5] += (double)(r[9] - r[2]);
-    longest_walk = std::max(longest_walk, (double)(r[5] - r[7]));
+  for (int run = 0; run < kProbeRuns; ++run) {
+    const unsigned long long *base = &rec[(size_t)run * n_wg * ba::kProbeRecord];
+    unsigned long long first = ~0ull, last = 0;
+    double longest_walk = 0.0;
+    for (int64_t wg = 0; wg < n_wg; ++wg) {
+      const unsigned long long *r = base + (size_t)wg * ba::kProbeRecord;
+      if (!(r[2] <= r[3] && r[3] <= r[6] && r[6] <= r[7] && r[7] <= r[5] && r[5] <= r[8] && r[8] <= r[9]))
+        return fail(BA_ERR_DEVICE, "final-block phases: workgroup %lld left marks out of order", (long long)wg);
+      first = std::min(first, r[2]);
+      last = std::max(last, r[9]);
+      phases_us[0] += (double)(r[3] - r[2]);
+      phases_us[1] += (double)(r[6] - r[3]);
+      phases_us[2] += (double)(r[7] - r[6]);
+      phases_us[3] += (double)(r[5] - r[7]);
+      phases_us[4] += (double)(r[9] - r[5]);
+      phases_us[5] += (double)(r[9] - r[2]);
+      longest_walk = std::max(longest_walk, (double)(r[5] - r[7]));
+    }
+    phases_us[6] += (double)(last - first) * (double)n_wg;  // (scaled like the sums above)
+    phases_us[7] += longest_walk * (double)n_wg;
   }
-  for (int i = 0; i <= 5; ++i) phases_us[i] *= tick_us / (double)n_wg;
-  phases_us[6] = (double)(last - first) * tick_us;
-  phases_us[7] = longest_walk * tick_us;
+  for (int i = 0; i < BA_DIAG_PHASES; ++i) phases_us[i] *= tick_us / ((double)n_wg * kProbeRuns);
   return BA_OK;
 }
 
