@@ -130,16 +130,23 @@ def phase_budget(args, torch, ba, dev, randn_bf16) -> int:
         out["cycles_per_key_tile"] = round(out["attention_kernel_us_fit"]["us_per_key_tile"] * c * 1e3)
         out["fixed_cycles"] = round(out["attention_kernel_us_fit"]["fixed_us"] * c * 1e3)
         out["mfma_cycles_per_key_tile_at_full_pipe"] = 2048
-    # the same launch from the inside: wave 0 of every workgroup reads the real-time counter at its phase boundaries
+    # the same launch from the inside: wave 0 of every workgroup reads the real-time counter at its phase
+    # boundaries.  Equal splits and splits sized by the calibration's figures take turns (the clocks settle
+    # over the first milliseconds of a busy spell: a column measured behind a pause reads faster than one
+    # measured in the middle of the work), and the first turn is left out.
     wsp = torch.empty(ba.ba_measure_xcd_speed_workspace_bytes(), dtype=torch.uint8, device=dev)
-    marks = [ba.ba_diag_final_block_phases(wsp) for _ in range(3)][-1]
-    out["marks_inside_one_launch_us"] = {k: round(v, 2) for k, v in marks.items()}
     speeds = ba.ba_measure_xcd_speed(wsp)
-    marks = [ba.ba_diag_final_block_phases(wsp, xcd_speed=speeds) for _ in range(3)][-1]
-    out["marks_with_splits_sized_by_xcd_speed_us"] = {k: round(v, 2) for k, v in marks.items()}
+    turns = {"equal": [], "sized": []}
+    for turn in range(5):
+        turns["equal"].append(ba.ba_diag_final_block_phases(wsp))
+        turns["sized"].append(ba.ba_diag_final_block_phases(wsp, xcd_speed=speeds))
+    mean = lambda rows: {k: round(float(np.mean([r[k] for r in rows[1:]])), 2) for k in rows[0]}
+    out["marks_inside_one_launch_us"] = mean(turns["equal"])
+    out["marks_with_splits_sized_by_xcd_speed_us"] = mean(turns["sized"])
     out["xcd_speed"] = [round(x, 4) for x in speeds]
-    out["marks_note"] = ("means over the 256 workgroups of the probe's launch (31,744 context tokens, equal splits, "
-                         "queries scaled in the kernel); the last two are single numbers: the launch, and the longest walk")
+    out["marks_note"] = ("means over the 256 workgroups of the probe's launches (31,744 context tokens, queries scaled in "
+                         "the kernel; four launches per reading, four readings per column, the two columns taking turns); "
+                         "the last two are single numbers: the launch, and the longest walk")
     print(json.dumps(out))
     return 0
 
