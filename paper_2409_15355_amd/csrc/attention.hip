@@ -179,6 +179,11 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
 
   const int my_row = row0 + wave * 32 + col;
   const bool row_ok = my_row < n_rows;
+  // A wave none of whose 32 rows exists (the last row tile of a problem, a final block of few tokens)
+  // still copies its share of the tiles and meets every barrier, but skips its exponentials and MFMAs:
+  // they would run on zeros at full power, and this part's clock is set by the power it draws.
+  // (not with a block table: that kernel has no scalar register left for the flag and would spill)
+  const bool wave_has_rows = kBlocks || row0 + wave * 32 < n_rows;
   const int my_tok = (int)fast_div((uint32_t)my_row, p.group_div);  // query token (inside the problem) of this lane's column
   bf16x8_t qf[G::KCH];  // Q fragments, filled below once the first tile copies are on their way
 
@@ -723,14 +728,14 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       wg_barrier();  // tile 0 of both kinds is visible
       first_copy(1);
       first_copy(2);
-      qk_first(0, sacc);
+      if (wave_has_rows) qk_first(0, sacc);
       wg_barrier();
     } else {
       wg_barrier();
       first_copy(1);
       first_copy(2);
       wg_barrier();
-      qk_first(0, sacc);
+      if (wave_has_rows) qk_first(0, sacc);
       wg_barrier();
     }
     // One iteration.  The copy of tile i+3 is prepared here, in the softmax half, where scalar
@@ -743,7 +748,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     const uint64_t tile_bytes = (uint64_t)(prim_rb * (uint32_t)kTileKeys);
     auto iteration = [&](auto steady_c, int i) __attribute__((always_inline)) {
       constexpr bool steady = decltype(steady_c)::value;
-      softmax(cm, i == 0, sacc, pf);
+      if (wave_has_rows) softmax(cm, i == 0, sacc, pf);
       // Tile i+1 opens a segment of a block table: new query fragments.  Waves 0..3 turn theirs here;
       // waves 4..7 have done so right behind their previous MFMA block (see below), in the same
       // half-period, so that the workgroup stalls once per boundary, not twice.
@@ -790,9 +795,9 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
       else if (i + 2 < n_t) dma_wait<G::IPW>();
       else dma_wait<0>();
       const uint32_t vofs = VBASE + (i & (kNumVBuf - 1)) * TB;
-      preload(vofs, fr);
+      if (wave_has_rows) preload(vofs, fr);
       wg_barrier();
-      mfma_block(vofs, ((i + 1) & (kNumKBuf - 1)) * TB, steady || i + 1 < n_t, pf, sacc, fr);
+      if (wave_has_rows) mfma_block(vofs, ((i + 1) & (kNumKBuf - 1)) * TB, steady || i + 1 < n_t, pf, sacc, fr);
       if constexpr (kBlocks && !steady) {
         advance(cm);
         if (role_b && i + 2 < n_t && cm.rem == 1) {  // (QK of tile i+1 is done: the fragments are free)
