@@ -340,6 +340,31 @@ def test_final_block_matches_oracle(ba, case, layout):
     assert_attention_close(host_f64(o), ref, name)
 
 
+def test_final_block_query_heads_a_gigabyte_apart(ba):
+    """Queries laid out head-major in a 4 GB buffer (head stride 2^29 elements), used as given
+    (no rotary embedding): a group's rows then span 2^32 bytes, which the attention core's whole-row
+    fetch of the query rows (32-bit offsets from the wave's first row) cannot address, so it takes its
+    other way of loading them; same result either way."""
+    torch = torch_mod()
+    hq, hkv, d, lq, tc = 4, 1, 128, 70, 900
+    qb, kfb, vfb = gen_qkv(960, lq, hq, hkv, d)
+    kcb, vcb = wl.normal_bf16_bits(963, (tc, hkv, d)), wl.normal_bf16_bits(964, (tc, hkv, d))
+    cu_q, cu_ctx = np.array([0, lq], dtype=np.int32), np.array([0, tc], dtype=np.int32)
+    f = oracle.bf16_bits_to_f64
+    th = oracle.theta(10000.0, d)
+    ref = oracle.final_block(f(qb), f(kcb), f(vcb), f(kfb), f(vfb), cu_q, cu_ctx, th, rope_mode=oracle.ROPE_NONE)
+    heads = ba.Heads(hq, hkv, d, 10000.0)
+    big = torch.empty(hq << 29, dtype=torch.bfloat16, device="cuda")
+    q_far = big.as_strided((lq, hq, d), (d, 1 << 29, 1))
+    q_far.copy_(dev_bf16(qb))
+    assert q_far.stride(1) * 2 * hq >= 1 << 32
+    o_far = gpu_final(ba, heads, q_far, dev_bf16(kcb), dev_bf16(vcb), dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx, rope_mode=0)
+    assert_attention_close(host_f64(o_far), ref, "head-major queries, heads 1 GB apart")
+    o_near = gpu_final(ba, heads, dev_bf16(qb), dev_bf16(kcb), dev_bf16(vcb), dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx, rope_mode=0)
+    assert np.array_equal(host_bits(o_far.contiguous()), host_bits(o_near)), "the two ways of loading the query rows differ"
+    del big
+
+
 @pytest.mark.parametrize("route", ["contiguous", "block-table"])
 def test_final_block_context_rows_beyond_four_gigabytes(ba, route):
     """The context's rows lie 16 MB apart (views with a token stride of 2^23 elements into 5 GB
