@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libba_hip.so")
-SOURCES = ["ba_api.hip", "ba_plan.cpp", "reencode.hip", "rope_prepass.hip", "attention.hip", "attention_short.hip", "attention_bwd.hip", "head_pad.hip", "diag.hip"]
+SOURCES = ["ba_api.hip", "ba_api_prompts.hip", "ba_api_cached.hip", "ba_probe.hip", "ba_plan.cpp", "reencode.hip", "rope_prepass.hip", "attention.hip", "attention_short.hip", "attention_bwd.hip", "head_pad.hip", "diag.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # MFMA results the softmax reads go to ordinary VGPRs; the allocator moves the

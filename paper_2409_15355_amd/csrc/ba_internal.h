@@ -109,6 +109,11 @@ hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegs &segs,
 hipError_t launch_rope_prepass(const RopePrepassParams &p, const RopeSegsSmall &segs, const RopeRots *rots,
                                const RopeRotsSmall *rots_small, const RopeTable &rt, hipStream_t stream);
 
+// ---------------------------------------------------------------- shared by the files of the boundary ----
+int32_t device_fail(hipError_t e, const char *what);  // BA_ERR_DEVICE with the runtime's text
+int num_cus();                                        // compute units of the current device
+unsigned long long *&probe_clock();                   // this thread's AttnParams::wg_clock for the next final-block launches
+
 // ---------------------------------------------------------------- attention ----------
 
 constexpr int kProbeRecord = 16;
