@@ -1077,7 +1077,7 @@ hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, hipStream_t stre
   }
   AttnParams pl = p;  // with the launch's divisors
   pl.tiles_div = make_fast_div((uint32_t)p.total_tiles);
-  pl.kv_group = p.kv_group > 0 ? p.kv_group : kv_group_of(p.n_kv_heads);  // (the planner's choice, or the default)
+  pl.kv_group = p.kv_group > 0 ? p.kv_group : kDefaultKvGroup;  // (the planner's choice, or the default)
   pl.item_divs = make_item_divs(ItemOrder{p.total_tiles, p.n_kv_heads, p.n_splits, pl.kv_group});
   pl.split_divs = make_split_divs(p.n_splits);
   pl.q_rows_fit32 = p.q_st > 0 && p.q_sh > 0 && 32 * p.q_st * 2 + (int64_t)p.group * p.q_sh * 2 < (int64_t)1 << 32;

@@ -165,7 +165,7 @@ double try_kv_group(const float *speed, int64_t tiles, int n_kv_heads, int n_spl
 int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, int max_nt, int n_cu,
                         double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33], int32_t *use, int32_t *kv_group) {
   *use = 0;
-  *kv_group = kv_group_of(n_kv_heads);
+  *kv_group = kDefaultKvGroup;
   for (int h = 0; h < kMaxCutHeads; ++h)
     for (int s = 0; s <= kMaxSplits; ++s) cuts[h][s] = 0;
   if (!xcd_speed || n_splits <= 1 || tiles <= 0) return BA_OK;

@@ -106,7 +106,7 @@ struct ItemCoords {
   int rowtile, kvh, split;
 };
 // (the default, when nothing is known of the XCDs' speeds: an XCD fetches as few query rows as the order allows)
-BA_HD int kv_group_of(int n_kv_heads) { return n_kv_heads > 0 ? 1 : 1; }
+constexpr int kDefaultKvGroup = 1;
 inline ItemDivs make_item_divs(const ItemOrder &o) {
   ItemDivs d;
   d.by_rowtiles = make_fast_div((unsigned)(o.n_rowtiles > 0 ? o.n_rowtiles : 1));
