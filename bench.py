@@ -312,8 +312,8 @@ def main() -> int:
                     "source": "profiles/counters.json"},
                 "counters_current": counters is not None,
                 "note": "avg_launch_us is bracketed by HIP events on the launch stream, which keep neighbouring "
-                        "kernels from overlapping and read about 2 to 5 % above the kernel trace's duration of the "
-                        "same kernel: frac is conservative by that much",
+                        "kernels from overlapping and read up to 5 % above the kernel trace's duration of the "
+                        "same kernel (the small kernels about 2 us above): frac is conservative by that much at most",
                 "other_kernels_us_per_layer": {
                     "rope_final_block_keys": round(prof_ms[ba.PROFILE_REENCODE] / max(prof_n[ba.PROFILE_REENCODE], 1) * 1e3, 2),
                     "split_combine": round(prof_ms[ba.PROFILE_COMBINE] / max(prof_n[ba.PROFILE_COMBINE], 1) * 1e3, 2)}}
