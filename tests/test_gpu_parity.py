@@ -640,6 +640,13 @@ def test_config_5_final_block_full_size_sampled(ba):
     f = oracle.bf16_bits_to_f64
     ref = oracle.final_block(f(qb), f(kcb), f(vcb), f(kfb), f(vfb), cu_q, cu_ctx, oracle.theta(w.rope_base, d), rows=rows)
     assert_attention_close(host_f64(o)[rows], ref, "cfg5 final (sampled rows)")
+    # ... and as bench.py launches it: KV splits sized by the XCD speeds measured on this device (another
+    # order of the work items, unequal splits), then by a skewed set that moves every cut
+    wsp = torch.empty(ba.ba_measure_xcd_speed_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    for speeds in (ba.ba_measure_xcd_speed(wsp), [1.06, 0.97, 1.03, 0.99, 1.02, 0.98, 1.03, 0.92]):
+        sized = ba.Heads(hq, hkv, d, w.rope_base, xcd_speed=speeds)
+        o2 = gpu_final(ba, sized, dev_bf16(qb), dev_bf16(kcb), dev_bf16(vcb), dev_bf16(kfb), dev_bf16(vfb), cu_q, cu_ctx)
+        assert_attention_close(host_f64(o2)[rows], ref, f"cfg5 final, splits sized by {speeds} (sampled rows)")
 
 
 def test_config_5_final_block_from_block_cache_full_size_sampled(ba):
@@ -674,6 +681,15 @@ def test_config_5_final_block_from_block_cache_full_size_sampled(ba):
     rows = sorted(set([0, 1, 63, 64, 128, 255] + np.random.default_rng(6).integers(0, Lq, 8).tolist()))
     ref = oracle.final_block(f(qb), k_ctx, v_ctx, f(kfb), f(vfb), cu_q, [0, Tc], th, rows=rows)
     assert_attention_close(host_f64(o)[rows], ref, "cfg5 final from block cache (sampled rows)")
+    # ... and with the KV splits sized by a skewed set of XCD speeds (as bench.py passes measured ones)
+    sized = ba.Heads(hq, hkv, d, w.rope_base, xcd_speed=[1.06, 0.97, 1.03, 0.99, 1.02, 0.98, 1.03, 0.92])
+    o2 = torch.full((Lq, hq, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws2 = torch.empty(ba.ba_final_block_attention_cached_workspace_bytes(sized, cu_q, cu_blk, b_len), dtype=torch.uint8,
+                      device="cuda")
+    ba.ba_final_block_attention_cached(sized, dev_bf16(qb), dev_bf16(kcache_b), dev_bf16(vcache_b), dev_bf16(kfb),
+                                       dev_bf16(vfb), o2, None, cu_q, cu_blk, b_off, b_len, None, None, None, ws2)
+    torch.cuda.synchronize()
+    assert_attention_close(host_f64(o2)[rows], ref, "cfg5 final from block cache, sized splits (sampled rows)")
 
 
 def test_config_5_single_block_full_attention_sampled(ba):
