@@ -77,8 +77,9 @@ typedef struct ba_heads {
   const float *xcd_speed; /* host, nullable: relative speed of the device's 8 XCDs under the
                              attention core's load, from ba_measure_xcd_speed().  The final-block
                              calls then size their KV splits by the speed of the XCD each one
-                             runs on (the XCDs of one MI355X sustain clocks several per cent
-                             apart, and a launch ends with its slowest workgroup).  Changes which
+                             runs on, and choose which XCDs share KV heads (the XCDs of one
+                             MI355X sustain clocks several per cent apart, and a launch ends with
+                             its slowest workgroup).  Changes which
                              keys a split covers, hence low-order bits of the result, never the
                              workspace size.  null = equal splits.                             */
 } ba_heads;

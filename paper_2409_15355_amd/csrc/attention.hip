@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
     // Consecutive work items share K/V tiles (same KV head and split, different row tile);
     // the dispatcher deals workgroup ids round-robin to the XCDs, so regroup ids such that
     // each XCD (and its L2) gets a contiguous run of work items.
-    id = work_item_of_workgroup(id, gridDim.x);
+    id = work_item_of_workgroup(id, gridDim.x, p.xcd_runs);
   }
   // (divisions by launch constants: multipliers from the host instead of hardware divisions, each of
   // which is some thirty instructions on the one scalar unit that the eight waves of a workgroup share)
@@ -1078,6 +1078,8 @@ hipError_t launch_attn_t(const AttnParams &p, const Meta &meta, hipStream_t stre
   AttnParams pl = p;  // with the launch's divisors
   pl.tiles_div = make_fast_div((uint32_t)p.total_tiles);
   pl.kv_group = p.kv_group > 0 ? p.kv_group : kDefaultKvGroup;  // (the planner's choice, or the default)
+  // (likewise the XCDs' runs; anything that is not a permutation fit for this launch reads as "in order")
+  pl.xcd_runs = p.xcd_runs != 0 && xcd_runs_valid(p.xcd_runs, (unsigned)n_wg) ? p.xcd_runs : kIdentityXcdRuns;
   pl.item_divs = make_item_divs(ItemOrder{p.total_tiles, p.n_kv_heads, p.n_splits, pl.kv_group});
   pl.split_divs = make_split_divs(p.n_splits);
   pl.q_rows_fit32 = p.q_st > 0 && p.q_sh > 0 && 32 * p.q_st * 2 + (int64_t)p.group * p.q_sh * 2 < (int64_t)1 << 32;

@@ -628,7 +628,8 @@ int32_t ba_final_block_attention(const ba_heads *heads, const ba_tensor *q_f, co
     tile_base += tiles;
     ap.total_tiles = (int32_t)tiles;
     if ((rc = ba::plan_split_cuts(heads->xcd_speed, tiles, heads->n_kv_heads, pl.n_splits, pl.max_nt, num_cus(),
-                                  ba::final_q_bytes_per_kv_head(heads, pl.lq_total), ap.split_cut, &ap.use_cuts, &ap.kv_group)))
+                                  ba::final_q_bytes_per_kv_head(heads, pl.lq_total), ap.split_cut, &ap.use_cuts, &ap.kv_group,
+                                  &ap.xcd_runs)))
       return rc;
     if (rope_mode == BA_ROPE_APPLY) {  // absolute positions of the final block's tokens
       if ((rc = run_rope_prepass(heads, rt, q_f, q_ws, k_f, &kf_use, n, meta.cu_q, pos0.data() + n0, stream)))

@@ -93,7 +93,7 @@ int32_t run_final_blocks(const BlocksCall &c, ba::AttnParams ap) {
     {
       int32_t rc_cuts = ba::plan_split_cuts(c.heads->xcd_speed, tiles, c.heads->n_kv_heads, ap.n_splits, c.max_nt, num_cus(),
                                             ba::final_q_bytes_per_kv_head(c.heads, c.cu_q[c.n_prompts]), ap.split_cut,
-                                            &ap.use_cuts, &ap.kv_group);
+                                            &ap.use_cuts, &ap.kv_group, &ap.xcd_runs);
       if (rc_cuts) return rc_cuts;
     }
     const ba::RopeRots *big = nullptr;

@@ -165,6 +165,7 @@ struct AttnParams {
   int32_t total_tiles;  // row tiles over all problems of this launch
   FastDiv tiles_div;    // division by total_tiles
   int32_t kv_group;     // main core, filled at the launch: KV heads per group in the order of the work items
+  uint32_t xcd_runs;    // main core: which run of work items each XCD takes (work_item_of_workgroup); 0 = in order
   ItemDivs item_divs;   // ... and the divisors of item_coords
   SplitDivs split_divs; // divisions by n_splits and 2 n_splits (main core; filled at the launch)
   float *lse;           // short-block schedule: [tokens][n_q_heads] log-sum-exp of the scaled scores, or null

@@ -120,8 +120,8 @@ namespace {
 // in tile periods of a workgroup: an XCD is done when its longest item is, or when its compute
 // units have worked through all its items, whichever is later; before that it fetches the query
 // rows of the KV heads it hosts (about a megabyte per microsecond and XCD, a tile period being 1.6).
-double try_kv_group(const float *speed, int64_t tiles, int n_kv_heads, int n_splits, int kv_group, int max_nt, int n_cu,
-                    double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33]) {
+double try_kv_group(const float *speed, int64_t tiles, int n_kv_heads, int n_splits, int kv_group, unsigned runs, int max_nt,
+                    int n_cu, double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33]) {
   const ItemOrder order = {(int)tiles, n_kv_heads, n_splits, kv_group};
   const unsigned n_wg = (unsigned)(tiles * n_kv_heads * n_splits);
   double longest[kNumXcds] = {0}, sum[kNumXcds] = {0};
@@ -130,7 +130,7 @@ double try_kv_group(const float *speed, int64_t tiles, int n_kv_heads, int n_spl
     double w[kMaxSplits], total = 0.0;
     for (int s = 0; s < n_splits; ++s) {
       double acc = 0.0;
-      for (int64_t t = 0; t < tiles; ++t) acc += speed[xcd_of_work_item(item_id((int)t, h, s, order), n_wg)];
+      for (int64_t t = 0; t < tiles; ++t) acc += speed[xcd_of_work_item(item_id((int)t, h, s, order), n_wg, runs)];
       w[s] = acc / (double)tiles;
       total += w[s];
     }
@@ -143,7 +143,7 @@ double try_kv_group(const float *speed, int64_t tiles, int n_kv_heads, int n_spl
     for (int s = 0; s < n_splits; ++s) {
       const double item_tiles = (double)max_nt * (double)(cuts[h][s + 1] - cuts[h][s]) / 65536.0;
       for (int64_t t = 0; t < tiles; ++t) {
-        const int x = xcd_of_work_item(item_id((int)t, h, s, order), n_wg);
+        const int x = xcd_of_work_item(item_id((int)t, h, s, order), n_wg, runs);
         longest[x] = std::max(longest[x], item_tiles);
         sum[x] += item_tiles;
         hosts[x][h] = true;
@@ -160,12 +160,38 @@ double try_kv_group(const float *speed, int64_t tiles, int n_kv_heads, int n_spl
   }
   return worst;
 }
+
+// Which run of work items each XCD takes (work_item_of_workgroup) under groups of kv_group KV heads:
+// the runs of one group of KV heads are neighbours, and only their XCDs can be balanced against each
+// other, so the XCDs are dealt to the groups in order of speed, to and fro (fastest and slowest end
+// up together), which brings the groups' mean speeds as close as a greedy deal gets them.  Identity
+// when the runs do not line up with the groups.
+unsigned deal_xcd_runs(const float *speed, int64_t tiles, int n_kv_heads, int n_splits, int kv_group) {
+  const int64_t n_wg = tiles * n_kv_heads * n_splits;
+  if (n_wg % kNumXcds || (kNumXcds * kv_group) % n_kv_heads) return kIdentityXcdRuns;
+  const int per_group = kNumXcds * kv_group / n_kv_heads;  // runs (= XCDs) that share one group of KV heads
+  if (per_group < 2 || per_group >= kNumXcds || kNumXcds % per_group) return kIdentityXcdRuns;
+  const int n_groups = kNumXcds / per_group;
+  int by_speed[kNumXcds];
+  for (int x = 0; x < kNumXcds; ++x) by_speed[x] = x;
+  std::stable_sort(by_speed, by_speed + kNumXcds, [&](int a, int b) { return speed[a] > speed[b]; });
+  int taken[kNumXcds] = {0};
+  unsigned runs = 0;
+  for (int i = 0; i < kNumXcds; ++i) {
+    const int pass = i / n_groups, pos = i % n_groups;
+    const int group = (pass & 1) ? n_groups - 1 - pos : pos;
+    runs |= (unsigned)(group * per_group + taken[group]++) << (4 * by_speed[i]);
+  }
+  return runs;
+}
 }  // namespace
 
 int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, int max_nt, int n_cu,
-                        double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33], int32_t *use, int32_t *kv_group) {
+                        double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33], int32_t *use, int32_t *kv_group,
+                        uint32_t *xcd_runs) {
   *use = 0;
   *kv_group = kDefaultKvGroup;
+  *xcd_runs = kIdentityXcdRuns;
   for (int h = 0; h < kMaxCutHeads; ++h)
     for (int s = 0; s <= kMaxSplits; ++s) cuts[h][s] = 0;
   if (!xcd_speed || n_splits <= 1 || tiles <= 0) return BA_OK;
@@ -179,17 +205,24 @@ int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, i
   // How far that can even out the XCDs depends on the order of the work items: with small groups of
   // KV heads an XCD fetches few query rows but shares a KV head with few other XCDs; with one group
   // of all KV heads every XCD fetches every query row and all of them can be balanced against each
-  // other.  Every group size (a power of two that divides the KV heads, or all of them) is tried.
+  // other.  Every group size (a power of two that divides the KV heads, or all of them) is tried, with
+  // the XCDs in their own order and dealt to the groups by speed (deal_xcd_runs).
   double best = 0.0;
   int best_group = 0;
   for (int g = 1; g <= n_kv_heads; g = (2 * g <= n_kv_heads || g == n_kv_heads) ? 2 * g : n_kv_heads) {
     if (n_kv_heads % g) continue;
-    uint32_t trial[kMaxCutHeads][33];
-    const double t = try_kv_group(xcd_speed, tiles, n_kv_heads, n_splits, g, std::max(1, max_nt), n_cu, q_bytes_per_kv_head, trial);
-    if (!best_group || t < best - 1e-9) {
-      best = t;
-      best_group = g;
-      memcpy(cuts, trial, sizeof(trial));
+    const unsigned dealt = deal_xcd_runs(xcd_speed, tiles, n_kv_heads, n_splits, g);
+    for (int k = 0; k < (dealt == kIdentityXcdRuns ? 1 : 2); ++k) {
+      const unsigned runs = k ? dealt : kIdentityXcdRuns;
+      uint32_t trial[kMaxCutHeads][33];
+      const double t = try_kv_group(xcd_speed, tiles, n_kv_heads, n_splits, g, runs, std::max(1, max_nt), n_cu,
+                                    q_bytes_per_kv_head, trial);
+      if (!best_group || t < best - 1e-9) {
+        best = t;
+        best_group = g;
+        *xcd_runs = runs;
+        memcpy(cuts, trial, sizeof(trial));
+      }
     }
   }
   *kv_group = best_group;
@@ -399,8 +432,9 @@ int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const 
     uint32_t cuts[ba::kMaxCutHeads][33];
     int32_t use_cuts = 0;
     int32_t kv_group = 0;
+    uint32_t xcd_runs = ba::kIdentityXcdRuns;
     if ((rc = ba::plan_split_cuts(heads->xcd_speed, tiles, heads->n_kv_heads, pl.n_splits, pl.max_nt, n_compute_units,
-                                  ba::final_q_bytes_per_kv_head(heads, pl.lq_total), cuts, &use_cuts, &kv_group)))
+                                  ba::final_q_bytes_per_kv_head(heads, pl.lq_total), cuts, &use_cuts, &kv_group, &xcd_runs)))
       return rc;
     // the kernel's own walk: every (split, row tile) of the launch; the same at every KV head unless
     // the splits are sized by XCD speed, when every KV head has shares of its own
@@ -430,7 +464,7 @@ int64_t ba_schedule_final_block(const ba_heads *heads, int32_t n_prompts, const 
         w.n_splits = pl.n_splits;
         w.kv_head = kvh;
         w.xcd = kvh >= 0 && n_wg <= 0x7fffffff
-                    ? ba::xcd_of_work_item(ba::item_id((int)tile, kvh, split, order), (unsigned)n_wg) : -1;
+                    ? ba::xcd_of_work_item(ba::item_id((int)tile, kvh, split, order), (unsigned)n_wg, xcd_runs) : -1;
         w.ctx_begin = std::min(tctx, std::min(tr.begin, n_ctx_tiles) * ba::kTileKeys);
         w.ctx_end = std::min(tctx, std::min(tr.end, n_ctx_tiles) * ba::kTileKeys);
         w.self_begin = std::min(lq, std::max(0, tr.begin - n_ctx_tiles) * ba::kTileKeys);

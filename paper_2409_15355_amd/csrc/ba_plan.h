@@ -54,10 +54,13 @@ int32_t plan_final(const ba_heads *h, int32_t n_prompts, const int32_t *cu_q, co
 // splits of every KV head are sized by the speed of the XCDs that run them: cuts[h][s] = where split s
 // of KV head h begins, 1 / 65536 units (see split_tile_range), and *kv_group (see ItemOrder) is the
 // group size under which the launch is expected to end soonest.  *use = 0 when the splits stay equal
-// (no speeds, one split, too many KV heads): then *kv_group is the default.  BA_ERR_INVALID_ARG on
-// bad speeds.  q_bytes_per_kv_head: the query rows a workgroup's XCD fetches per KV head it hosts.
+// (no speeds, one split, too many KV heads): then *kv_group is the default.  *xcd_runs: which run of
+// work items each XCD takes (work_item_of_workgroup; the identity unless a deal by speed is expected to
+// end sooner).  BA_ERR_INVALID_ARG on bad speeds.  q_bytes_per_kv_head: the query rows a workgroup's
+// XCD fetches per KV head it hosts.
 int32_t plan_split_cuts(const float *xcd_speed, int64_t tiles, int n_kv_heads, int n_splits, int max_nt, int n_cu,
-                        double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33], int32_t *use, int32_t *kv_group);
+                        double q_bytes_per_kv_head, uint32_t cuts[kMaxCutHeads][33], int32_t *use, int32_t *kv_group,
+                        uint32_t *xcd_runs);
 inline double final_q_bytes_per_kv_head(const ba_heads *h, int64_t lq_total) {
   return (double)lq_total * (h->n_q_heads / h->n_kv_heads) * h->head_dim * 2.0;
 }

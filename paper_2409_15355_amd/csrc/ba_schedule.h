@@ -136,16 +136,29 @@ constexpr int kNumXcds = 8;
 BA_HD int xcd_of_workgroup(unsigned wg) { return (int)(wg % kNumXcds); }
 // The work item that workgroup `wg` of an n_wg-workgroup final-block launch takes: ids are regrouped
 // so that each XCD (and its L2) gets a contiguous run of work items, which then share K/V tiles.
-BA_HD unsigned work_item_of_workgroup(unsigned wg, unsigned n_wg) {
-  const unsigned q = n_wg / kNumXcds, r = n_wg % kNumXcds, x = wg % kNumXcds;
+// runs: which run each XCD takes, four bits per XCD (XCD x takes run (runs >> 4x) & 7).  Neighbouring
+// runs hold splits of the same KV heads (see ItemOrder), and only XCDs that share KV heads can be
+// balanced against each other through the sizes of their splits, so the planner may put a slow XCD
+// next to a fast one.  Anything but the identity needs runs of equal length (n_wg a multiple of 8).
+constexpr unsigned kIdentityXcdRuns = 0x76543210u;
+BA_HD bool xcd_runs_valid(unsigned runs, unsigned n_wg) {
+  unsigned seen = 0;
+  for (int x = 0; x < kNumXcds; ++x) seen |= 1u << ((runs >> (4 * x)) & 15u);
+  return seen == 0xffu && (runs == kIdentityXcdRuns || n_wg % kNumXcds == 0);
+}
+BA_HD unsigned work_item_of_workgroup(unsigned wg, unsigned n_wg, unsigned runs = kIdentityXcdRuns) {
+  const unsigned q = n_wg / kNumXcds, r = n_wg % kNumXcds, x = (runs >> (4 * (wg % kNumXcds))) & 7u;
   return x * q + (x < r ? x : r) + wg / kNumXcds;
 }
 // ... and the XCD that runs work item `item` of such a launch (the inverse, for the planner)
-BA_HD int xcd_of_work_item(unsigned item, unsigned n_wg) {
+BA_HD int xcd_of_work_item(unsigned item, unsigned n_wg, unsigned runs = kIdentityXcdRuns) {
   const unsigned q = n_wg / kNumXcds, r = n_wg % kNumXcds;
-  // XCD x runs items [x q + min(x, r), (x + 1) q + min(x + 1, r))
-  const unsigned big = r * (q + 1);  // items on the r XCDs that run q + 1 of them
-  return item < big ? (int)(item / (q + 1)) : (int)(r + (q ? (item - big) / q : 0));
+  // run x holds items [x q + min(x, r), (x + 1) q + min(x + 1, r))
+  const unsigned big = r * (q + 1);  // items in the r runs that hold q + 1 of them
+  const unsigned run = item < big ? item / (q + 1) : r + (q ? (item - big) / q : 0);
+  for (int x = 0; x < kNumXcds; ++x)
+    if (((runs >> (4 * x)) & 7u) == run) return x;
+  return (int)run;
 }
 // KV heads that get a cut list of their own when the splits are sized by XCD speed
 constexpr int kMaxCutHeads = 8;

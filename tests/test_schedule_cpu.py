@@ -243,6 +243,34 @@ def test_splits_sized_by_xcd_speed_still_cover_the_mask_exactly(speeds):
                     assert len({w.xcd for w in items if w.kv_head == kvh and w.split == s_}) == 1
 
 
+@pytest.mark.parametrize("speeds", [[1.0608, 0.9721, 1.0293, 0.9882, 1.0236, 0.9837, 1.0255, 0.9167],
+                                    [1.0393, 0.9966, 0.9955, 0.9547, 1.0547, 0.9905, 1.0048, 0.9638],
+                                    [0.93, 0.94, 0.95, 0.96, 1.04, 1.05, 1.06, 1.07]])
+def test_xcds_are_dealt_to_kv_head_groups_by_speed(speeds):
+    """With measured speeds the planner also chooses which XCD runs which stretch of the work items: XCDs
+    that share KV heads can be balanced against each other, so slow ones are put with fast ones.  Every
+    XCD still runs an eighth of the launch, and the launch is expected to end within 3 % of the time a
+    perfect balance would give (speeds as measured on two devices, and a set sorted the worst way)."""
+    h = ba.Heads(32, 8, 128, 500000.0, xcd_speed=speeds)
+    items = ba.ba_schedule_final_block(h, [0, 256], [0, 31744], 256)
+    assert len(items) == 256
+    tiles = lambda w: -(-(w.ctx_end - w.ctx_begin) // 64) - (-(w.self_end - w.self_begin) // 64)
+    per_xcd = {x: [w for w in items if w.xcd == x] for x in range(8)}
+    assert all(len(v) == 32 for v in per_xcd.values())
+    ends = [max(tiles(w) for w in per_xcd[x]) / speeds[x] for x in range(8)]
+    ideal = sum(tiles(w) for w in items) / 32.0 / sum(speeds)
+    assert max(ends) <= 1.03 * ideal, (ends, ideal)
+    hosted = {x: frozenset(w.kv_head for w in per_xcd[x]) for x in range(8)}
+    if 1 < len(hosted[0]) < 8:
+        # groups of XCDs share KV heads; the slowest XCD sits in a group with the fastest
+        assert hosted[int(np.argmin(speeds))] == hosted[int(np.argmax(speeds))]
+        groups = {}
+        for x in range(8):
+            groups.setdefault(hosted[x], []).append(speeds[x])
+        means = [np.mean(v) for v in groups.values()]
+        assert max(means) - min(means) < 0.02, groups
+
+
 def test_bad_xcd_speeds_are_rejected():
     h = ba.Heads(32, 8, 128, 500000.0, xcd_speed=[1, 1, 1, 0.1, 1, 1, 1, 1])
     with pytest.raises(ba.BaError):
