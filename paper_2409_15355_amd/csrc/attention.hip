@@ -641,7 +641,8 @@ __global__ __launch_bounds__(kThreads) void attn_kernel(AttnParams p, Meta meta)
         // un-rotated rows and the pre-pass's table of scale * (cos, sin) per token: rotate here, so that
         // the rotated queries never make a round trip through memory
         // (lanes beyond the problem's rows hold zeros: any row of the table will do, take an existing one)
-        rotate_by(reinterpret_cast<const f32x4_t *>(BA_ARG(q_table) + (int64_t)(pr.q_tok0 + (row_ok ? tok_v : 0)) * D));
+        rotate_by(reinterpret_cast<const f32x4_t *>(
+            BA_ARG(q_table) + (int64_t)((BA_ARG(q_table_by_pos) ? 0 : pr.q_tok0) + (row_ok ? tok_v : 0)) * D));
       } else {
 #pragma unroll
         for (int kk = 0; kk < G::KCH; ++kk)

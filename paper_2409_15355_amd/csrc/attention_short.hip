@@ -190,7 +190,8 @@ __global__ __launch_bounds__(kSThreads, 3) void encode_short_kernel(AttnParams p
       // The rows of a wave span at most 8 tokens (the host sends only groups of 4 or more query
       // heads here).  Chunk c of token row t sits at chunk c ^ (t & 7), which keeps the reads of
       // different tokens off each other's banks.
-      const char *tbase = (const char *)(p.q_table + (int64_t)q_tok0 * D);
+      // (a row per token of the call, or, for per-block encoding, a row per position inside the block)
+      const char *tbase = (const char *)(p.q_table + (p.q_table_by_pos ? (int64_t)0 : (int64_t)q_tok0 * D));
 #pragma unroll
       for (int u = 0; u < kTabOps; ++u) {
         const int t = u * (1024 / TROW) + lane / TCH, pc = lane % TCH;

@@ -164,7 +164,8 @@ int32_t run_reencode(ba::ReencParams p, const ba::RopeTable &rt, int n_blocks, c
 int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_tensor *q, uint16_t *q_rot,
                          const ba_tensor *k, const ba_tensor *k_rot, int n, const int32_t *start,
                          const int32_t *pos0, hipStream_t stream, const ba::RopeRots *rots,
-                         const ba::RopeRotsSmall *rots_small, float *rot_dst, int n_rot, float *q_table, bool rows_too) {
+                         const ba::RopeRotsSmall *rots_small, float *rot_dst, int n_rot, float *q_table, bool rows_too,
+                         int table_rows) {
   const int64_t tokens = (int64_t)start[n] - start[0];
   if (tokens <= 0) return BA_OK;
   ba::RopePrepassParams p;
@@ -191,6 +192,12 @@ int32_t run_rope_prepass(const ba_heads *h, const ba::RopeTable &rt, const ba_te
   p.heads_per_thread = tokens >= 16384 ? 8 : (tokens >= 2048 ? 2 : 1);
   p.do_q = q_table ? (rows_too ? 3 : 2) : 1;  // a table of factors for the attention core, rotated rows, or both
   p.q_table = q_table;
+  if (table_rows > 0) {  // the table by position (every segment starts at position 0), no rotated rows
+    p.do_q = 4;
+    p.table_rows = table_rows;
+  } else if (table_rows < 0) {  // keys only: the table of this call is already written
+    p.do_q = 0;
+  }
   p.do_k = 1;
   p.rot_dst = rot_dst;
   p.n_rot = n_rot;
@@ -357,6 +364,7 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
   ap.q_st = q->stride_tok;
   ap.q_sh = q->stride_head;
   ap.q_table = q_table;
+  ap.q_table_by_pos = 1;
   ap.kf = (const uint16_t *)k_use.ptr;
   ap.kf_st = k_use.stride_tok;
   ap.kf_sh = k_use.stride_head;
@@ -387,16 +395,22 @@ int32_t ba_encode_blocks(const ba_heads *heads, const ba_tensor *q, const ba_ten
                                   (int64_t)G * std::max(q->stride_head, o_out->stride_head));
   const int64_t short_max = ba::encode_short_max(G, widest);
 
+  int64_t longest_block = 1;
+  for (int b = 0; b < n_blocks; ++b) longest_block = std::max<int64_t>(longest_block, block_offsets[b + 1] - block_offsets[b]);
+  bool table_written = false;
   for (int b0 = 0; b0 < n_blocks; b0 += ba::kEncMaxBlocks) {
     const int n = std::min(ba::kEncMaxBlocks, n_blocks - b0);
     ba::EncodeMeta meta[2];  // [0] main core, [1] short blocks
     int64_t tiles[2];
     if ((rc = ba::build_encode_metas(block_offsets, b0, n, G, short_max, meta, tiles))) return rc;
     if (tiles[0] + tiles[1] == 0) continue;
-    if (rope_mode == BA_ROPE_APPLY) {  // local positions: every block starts at 0
+    if (rope_mode == BA_ROPE_APPLY) {
+      // local positions: every block starts at 0, so one table of factors by position serves all blocks
+      // (as many rows as the longest block has tokens; written by the first launch)
       if ((rc = run_rope_prepass(heads, rt, q, nullptr, k, &k_use, n, meta[0].offs, nullptr, stream, nullptr, nullptr,
-                                 nullptr, 0, q_table)))
+                                 nullptr, 0, q_table, false, table_written ? -1 : (int)longest_block)))
         return rc;
+      table_written = true;
     }
     for (int m = 1; m >= 0; --m) {
       if (tiles[m] == 0) continue;

@@ -66,7 +66,8 @@ int32_t run_reencode(ReencParams p, const RopeTable &rt, int n_blocks, const int
 int32_t run_rope_prepass(const ba_heads *h, const RopeTable &rt, const ba_tensor *q, uint16_t *q_rot, const ba_tensor *k,
                          const ba_tensor *k_rot, int n, const int32_t *start, const int32_t *pos0, hipStream_t stream,
                          const RopeRots *rots = nullptr, const RopeRotsSmall *rots_small = nullptr, float *rot_dst = nullptr,
-                         int n_rot = 0, float *q_table = nullptr, bool rows_too = false);
+                         int n_rot = 0, float *q_table = nullptr, bool rows_too = false,
+                         int table_rows = 0);
 
 }  // namespace api
 }  // namespace ba

@@ -92,7 +92,10 @@ struct RopePrepassParams {
   float *rot_dst;    // [n_rot][D/2][2]: (cos, sin) of rot_angle[b] * theta_j, or null
   int32_t n_rot;
   float *q_table;    // do_q == 2: instead of rotating Q rows, write q_scale * (cos, sin) per token: [tokens][D/2][2];
-                     // do_q == 3: both the rotated rows and the table
+                     // do_q == 3: both the rotated rows and the table;
+                     // do_q == 4: the table only, by position: row r = q_scale * (cos, sin) of position r,
+                     //            r < table_rows (for calls all of whose segments start at position 0)
+  int32_t table_rows;
 };
 
 // positions (in tokens) by which the rows of the rotation table turn
@@ -153,6 +156,8 @@ struct AttnParams {
   int32_t q_rows_fit32;  // main core, filled at the launch: 32 tokens and a group of heads of q span less than 2^32 bytes
   const float *q_table;  // else, if non-null: [tokens][D/2][2] = scale_log2e * (cos, sin) of each
                          // token's position times theta_j; the kernel rotates q with it
+  int32_t q_table_by_pos;  // ... or, if set, [positions][D/2][2]: a row per position inside the block (per-block
+                           // encoding, where every block starts at position 0 and the blocks share one table)
   int32_t rope_layout;
   const float *blk_rot;  // block table only: [blocks][D/2][2] (cos, sin) of minus each block's shift
   int32_t n_splits;

@@ -12,6 +12,8 @@
 // per thread (many short threads); many tokens: several heads per thread.
 #include <string.h>
 
+#include <algorithm>
+
 #include "ba_device.h"
 
 namespace ba {
@@ -34,7 +36,8 @@ __global__ __launch_bounds__(kThreads) void rope_rot_table_kernel(float *dst, in
 
 // workgroup rows of the Q job: head groups, or one row when only the table of factors is written
 __host__ __device__ inline int q_groups(const RopePrepassParams &p) {
-  return (p.do_q == 1 || p.do_q == 3) ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread : (p.do_q == 2 ? 1 : 0);
+  return (p.do_q == 1 || p.do_q == 3) ? (p.n_q_heads + p.heads_per_thread - 1) / p.heads_per_thread
+                                      : ((p.do_q == 2 || p.do_q == 4) ? 1 : 0);
 }
 
 template <int D, int LAYOUT, typename Segs>
@@ -59,18 +62,25 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
     }
   }
   const int c = threadIdx.x % TPV;
-  const int t = segs.start[0] + blockIdx.x * TPP + threadIdx.x / TPV;
-  if (t >= segs.start[segs.n]) return;
-  int lo = 0, hi = segs.n;  // largest s with start[s] <= t
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (segs.start[mid] <= t) lo = mid; else hi = mid;
-  }
-  const int pos = segs.pos0[lo] + (t - segs.start[lo]);
-
   // which tensor and which heads this workgroup handles: Q head groups first, then K
   const int groups_q = q_groups(p);
   const bool is_q = (int)blockIdx.y < groups_q;
+  int t = segs.start[0] + blockIdx.x * TPP + threadIdx.x / TPV;
+  int pos;
+  if (is_q && p.do_q == 4) {
+    // the table by position: this thread's row is a position, not a token
+    t = blockIdx.x * TPP + threadIdx.x / TPV;
+    if (t >= p.table_rows) return;
+    pos = t;
+  } else {
+    if (t >= segs.start[segs.n]) return;
+    int lo = 0, hi = segs.n;  // largest s with start[s] <= t
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (segs.start[mid] <= t) lo = mid; else hi = mid;
+    }
+    pos = segs.pos0[lo] + (t - segs.start[lo]);
+  }
   const int grp = is_q ? blockIdx.y : blockIdx.y - groups_q;
   const int n_heads = is_q ? p.n_q_heads : p.n_kv_heads;
   const int h_begin = grp * p.heads_per_thread;
@@ -94,7 +104,7 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
       sn[e] *= scale;
     }
   }
-  if (is_q && (p.do_q == 2 || (p.do_q == 3 && grp == 0))) {
+  if (is_q && (p.do_q == 2 || p.do_q == 4 || (p.do_q == 3 && grp == 0))) {
     // the factors themselves, for the attention core to rotate q with: entry j at [t][j] = (cos, sin)
     float2 *row = reinterpret_cast<float2 *>(p.q_table) + (int64_t)t * (D / 2);
 #pragma unroll
@@ -106,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void rope_prepass_kernel(RopePrepassParam
         j = c * VEC + e;
       row[j] = make_float2(cs[e], sn[e]);
     }
-    if (p.do_q == 2) return;
+    if (p.do_q == 2 || p.do_q == 4) return;
   }
 #pragma unroll 4
   for (int h = h_begin; h < h_end; ++h) {
@@ -142,7 +152,9 @@ hipError_t launch_d(RopePrepassParams p, const Segs &segs, const RopeTable &rt, 
   const int64_t tokens = (int64_t)segs.start[segs.n] - segs.start[0];
   const int groups = q_groups(p) + (p.do_k ? (p.n_kv_heads + p.heads_per_thread - 1) / p.heads_per_thread : 0);
   if (tokens <= 0 || groups == 0) return hipSuccess;
-  const unsigned gx = (unsigned)((tokens + TPP - 1) / TPP);
+  // (a table by position has rows of its own to cover; it never has more of them than the call has tokens)
+  const int64_t span = std::max<int64_t>(tokens, p.do_q == 4 ? p.table_rows : 0);
+  const unsigned gx = (unsigned)((span + TPP - 1) / TPP);
   RopeRotsSmall none;
   unsigned rot_rows = 0;
   if (rots) {
