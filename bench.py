@@ -554,7 +554,7 @@ def main() -> int:
                                               "issued_TFLOPs": round(fl_issued / ms_e / 1e9, 1),
                                               "GBps": round(byts / ms_e / 1e6, 1),
                                               "frac_of_hbm_peak": round(byts / ms_e / 1e6 / HBM_PEAK_GBS, 4),
-                                              "bound": "hbm (20.5 KB per token against about 100 keys of work each)",
+                                              "bound": "hbm (22 KB per token: q, o, k, v and one write of k_local, against about 100 keys of work each)",
                                               "tokens": T3, "oracle": oracle3}
             del q, k, v, o, kl, ws_3
         # a-3 batched: config 3's eight final blocks (32..128 query tokens over about 4,000 context tokens each)
