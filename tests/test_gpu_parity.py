@@ -174,6 +174,9 @@ ENC_CASES = [
     # more blocks than one launch's table holds, on either schedule
     ("700-blocks-gqa4", 4, 1, 64, 10000.0, [1 + (7 * i) % 23 for i in range(700)]),
     ("700-blocks-mha", 2, 2, 64, 10000.0, [1 + (5 * i) % 17 for i in range(700)]),
+    # the longest block lies in the second launch, and is longer than the whole first launch: the table of
+    # rotation factors (a row per position inside a block) is written by the first launch for all of them
+    ("long-block-in-second-launch", 4, 1, 64, 10000.0, [1 + i % 2 for i in range(320)] + [700, 3, 64]),
 ]
 
 
