@@ -271,6 +271,25 @@ def test_xcds_are_dealt_to_kv_head_groups_by_speed(speeds):
         assert max(means) - min(means) < 0.02, groups
 
 
+def test_every_xcd_runs_its_share_whatever_the_speeds():
+    """Drawn speeds and shapes: the work items of a launch are dealt to the XCDs in equal numbers (to
+    within one), each (KV head, split, row tile) exactly once, whichever XCD runs which stretch."""
+    rng = np.random.default_rng(77)
+    for case in range(40):
+        hkv = int(rng.choice([1, 2, 4, 8]))
+        g = int(rng.choice([1, 4, 8]))
+        speeds = [float(x) for x in rng.uniform(0.8, 1.25, 8)]
+        h = ba.Heads(hkv * g, hkv, 128, 500000.0, xcd_speed=speeds)
+        lq, tc = int(rng.choice([1, 50, 64, 256, 700])), int(rng.choice([0, 900, 8000, 31744, 100000]))
+        items = ba.ba_schedule_final_block(h, [0, lq], [0, tc], 256)
+        if not items or items[0].xcd < 0:
+            continue  # equal splits (one split, or nothing to size): no XCDs in the answer
+        seen = {(w.kv_head, w.split, w.row_begin) for w in items}
+        assert len(seen) == len(items), (case, hkv, g, lq, tc)
+        counts = np.bincount([w.xcd for w in items], minlength=8)
+        assert counts.max() - counts.min() <= 1, (case, counts)
+
+
 def test_bad_xcd_speeds_are_rejected():
     h = ba.Heads(32, 8, 128, 500000.0, xcd_speed=[1, 1, 1, 0.1, 1, 1, 1, 1])
     with pytest.raises(ba.BaError):
